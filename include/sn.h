@@ -1,0 +1,189 @@
+/*
+ * sn.h -- C ABI of the MI355X (gfx950) kernels for the memory-budgeted CNN
+ * training step of SuperNeurons (arXiv 1801.04380).
+ *
+ * The paper's runtime owns all GPU memory; each CONV step is handed whatever
+ * bytes are free at that step as "convolution workspace", tries only the
+ * algorithms whose workspace fits, and takes the fastest of them (Sec. 3.5).
+ * The workspace never changes the result (Sec. 3.5).  The cheap layers (ACT,
+ * BN, POOL) are the ones its cost-aware recomputation replays (Sec. 3.4).
+ * This library is that layer level: CONV forward / backward-data /
+ * backward-filter with an explicit workspace budget, the planner, and the cheap
+ * layers, forward and backward.
+ *
+ * Conventions for every entry point
+ *  - All tensor pointers are DEVICE pointers owned by the caller, 16-byte
+ *    aligned (workspace: 256-byte aligned).  Shape structs and the size_t /
+ *    enum outputs of the query and planner calls are HOST memory.
+ *  - The library never allocates, frees or keeps device memory and holds no
+ *    pointer after a call returns.
+ *  - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
+ *    default stream).  No call synchronises the device.  Outputs are valid once
+ *    the stream reaches that point; workspace contents are undefined afterwards.
+ *  - Outputs are overwritten, never accumulated into.
+ *  - Layouts: activations NCHW, filters KCRS, both dense row-major.
+ *    P = floor((H + 2*pad_h - R)/stride_h) + 1, Q likewise.  groups = 1,
+ *    dilation = 1, no bias.  The filter is applied as cross-correlation.
+ *  - Errors are return codes; on any error nothing has been launched.
+ *  - bf16 values are the upper 16 bits of an IEEE fp32, stored as uint16;
+ *    fp32 results are rounded to bf16 to nearest, ties to even.
+ */
+#ifndef SN_H
+#define SN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SN_OK = 0,
+    SN_ERR_BAD_ARG = 1,             /* null pointer, misaligned pointer, bad dimension */
+    SN_ERR_UNSUPPORTED = 2,         /* valid request this build has no kernel for */
+    SN_ERR_WORKSPACE_TOO_SMALL = 3, /* named algorithm needs more workspace than given */
+    SN_ERR_LAUNCH = 4               /* the HIP runtime refused a launch */
+} sn_status;
+
+typedef enum { SN_F32 = 0, SN_BF16 = 1 } sn_dtype;
+
+typedef enum { SN_CONV_FWD = 0, SN_CONV_BWD_DATA = 1, SN_CONV_BWD_FILTER = 2 } sn_conv_dir;
+
+/* The algorithm menu the planner chooses from (Sec. 3.5: several algorithms,
+ * some of which need workspace to reach their speed).
+ *  DIRECT       implicit GEMM straight from the NCHW/KCRS tensors; 0 bytes.
+ *  IM2COL_GEMM  explicit: unfold patches into a column buffer in the workspace
+ *               (as many images per pass as fit), then a GEMM over it; the
+ *               backward-data form folds the column gradient back (col2im).
+ *  STAGED       implicit GEMM that stages a re-laid-out operand in the
+ *               workspace: the filter packed tap-major for forward and
+ *               backward-data; per-slice partial sums of dw (reduced in a fixed
+ *               order, so the result is run-to-run identical) for
+ *               backward-filter.
+ *  AUTO         let the planner pick the fastest algorithm that fits. */
+typedef enum {
+    SN_ALGO_AUTO = -1,
+    SN_ALGO_DIRECT = 0,
+    SN_ALGO_IM2COL_GEMM = 1,
+    SN_ALGO_STAGED = 2,
+    SN_ALGO_COUNT = 3
+} sn_conv_algo;
+
+typedef struct {
+    int32_t N, C, H, W;        /* input x[N][C][H][W] */
+    int32_t K, R, S;           /* filter w[K][C][R][S] */
+    int32_t stride_h, stride_w;
+    int32_t pad_h, pad_w;
+    int32_t in_dtype;          /* sn_dtype of x, w, dy */
+    int32_t out_dtype;         /* sn_dtype of y, dx; dw is always fp32.  fp32 in => fp32 out */
+} sn_conv_shape;
+
+typedef void *sn_stream;
+
+/* Library version, for the binding's sanity check. */
+int sn_version(void);
+
+/* Output size rule used by every CONV and POOL entry point (floor rule; it
+ * reproduces the AlexNet tensor sizes of Sec. 4.1).  Returns 0 if the window
+ * does not fit. */
+int sn_out_dim(int in, int pad, int window, int stride);
+
+/* Workspace needs of one algorithm for one CONV step (Sec. 3.5: an algorithm is
+ * memory-feasible iff its workspace fits the free bytes).
+ *  min_bytes        least workspace with which the algorithm runs at all
+ *  preferred_bytes  workspace beyond which it gets no faster
+ * Returns SN_ERR_UNSUPPORTED if the algorithm cannot run this shape. */
+sn_status sn_conv_workspace_query(const sn_conv_shape *shape, sn_conv_dir dir, sn_conv_algo algo,
+                                  size_t *min_bytes, size_t *preferred_bytes);
+
+/* Planner (Sec. 3.5): among the algorithms whose min_bytes <= budget_bytes pick
+ * the fastest.  "Fastest" comes from times recorded for this exact shape by
+ * sn_planner_record / sn_conv_autotune (the paper benchmarks the feasible
+ * algorithms at run time); a recorded time applies to budgets >= the workspace
+ * it was measured with.  With no feasible record the choice falls back to a
+ * built-in ranking.  Ties go to the smaller workspace.  DIRECT needs 0 bytes,
+ * so a plan always exists.  bytes_used = the workspace the choice will use
+ * (<= budget_bytes).  predicted_ms may be NULL; it receives the recorded time
+ * or a negative value if the choice came from the built-in ranking. */
+sn_status sn_conv_plan(const sn_conv_shape *shape, sn_conv_dir dir, size_t budget_bytes,
+                       sn_conv_algo *algo, size_t *bytes_used, float *predicted_ms);
+
+/* Record / forget measured times (host-side table, process-wide, thread-safe). */
+sn_status sn_planner_record(const sn_conv_shape *shape, sn_conv_dir dir, sn_conv_algo algo,
+                            size_t workspace_bytes, float ms);
+void sn_planner_clear(void);
+
+/* Benchmark every algorithm that fits workspace_bytes on the caller's own
+ * buffers (same arguments as the matching sn_conv2d_* call: a, b are its two
+ * inputs, out its output) and record the times.  Synchronises the stream. */
+sn_status sn_conv_autotune(sn_conv_dir dir, const void *a, const void *b, void *out,
+                           const sn_conv_shape *shape, void *workspace, size_t workspace_bytes,
+                           int iters, sn_stream stream);
+
+/* CONV forward:  y[n,k,p,q] = sum_{c,r,s} x[n,c,p*sh+r-ph,q*sw+s-pw] * w[k,c,r,s]
+ * (out-of-image taps contribute 0).  x, w of in_dtype; y of out_dtype.
+ * algo = AUTO plans with workspace_bytes as the budget.  A named algorithm whose
+ * min_bytes exceeds workspace_bytes returns SN_ERR_WORKSPACE_TOO_SMALL.
+ * workspace may be NULL iff workspace_bytes == 0. */
+sn_status sn_conv2d_fwd(const void *x, const void *w, void *y, const sn_conv_shape *shape,
+                        sn_conv_algo algo, void *workspace, size_t workspace_bytes, sn_stream stream);
+
+/* CONV backward-data: dx[n,c,h,v] = sum over (k,p,q,r,s) with p*sh+r-ph = h and
+ * q*sw+s-pw = v of dy[n,k,p,q] * w[k,c,r,s].  dy, w of in_dtype; dx of out_dtype. */
+sn_status sn_conv2d_bwd_data(const void *dy, const void *w, void *dx, const sn_conv_shape *shape,
+                             sn_conv_algo algo, void *workspace, size_t workspace_bytes, sn_stream stream);
+
+/* CONV backward-filter: dw[k,c,r,s] = sum_{n,p,q} dy[n,k,p,q] * x[n,c,p*sh+r-ph,q*sw+s-pw].
+ * x, dy of in_dtype; dw always fp32.  DIRECT may split the (n,p,q) sum across
+ * workgroups and combine with floating-point atomics (sum order not fixed);
+ * STAGED and IM2COL_GEMM sum in a fixed order. */
+sn_status sn_conv2d_bwd_filter(const void *x, const void *dy, void *dw, const sn_conv_shape *shape,
+                               sn_conv_algo algo, void *workspace, size_t workspace_bytes, sn_stream stream);
+
+/* ACT (ReLU), one of the cheap layers recomputation replays (Sec. 3.4):
+ * y = x > 0 ? x : 0.  n elements of `dtype`.  y may alias x. */
+sn_status sn_relu_fwd(const void *x, void *y, size_t n, sn_dtype dtype, sn_stream stream);
+
+/* dx = x > 0 ? dy : 0.  x may be the layer's input or its output (same gate).
+ * dx may alias dy. */
+sn_status sn_relu_bwd(const void *x, const void *dy, void *dx, size_t n, sn_dtype dtype, sn_stream stream);
+
+/* BN forward, training mode (Sec. 3.4 cheap layer): per channel c over M = N*H*W,
+ *   mean = sum(x)/M, var = sum((x-mean)^2)/M, invstd = 1/sqrt(var+eps),
+ *   y = gamma*(x-mean)*invstd + beta.
+ * x, y of `dtype` [N][C][H][W]; gamma, beta, save_mean, save_invstd fp32 [C];
+ * arithmetic in fp32.  Running statistics are NOT touched, so a replay of this
+ * call is side-effect free and gives bit-identical outputs.  y must not alias x
+ * (y doubles as scratch for the per-slice partial statistics). */
+sn_status sn_bn_fwd(const void *x, const float *gamma, const float *beta, void *y,
+                    float *save_mean, float *save_invstd,
+                    int N, int C, int H, int W, float eps, sn_dtype dtype, sn_stream stream);
+
+/* BN backward from the saved statistics, xhat = (x-mean)*invstd:
+ *   dbeta = sum(dy), dgamma = sum(dy*xhat),
+ *   dx = gamma*invstd/M * (M*dy - dbeta - xhat*dgamma).
+ * dx must alias neither x nor dy. */
+sn_status sn_bn_bwd(const void *x, const void *dy, const float *gamma,
+                    const float *save_mean, const float *save_invstd,
+                    void *dx, float *dgamma, float *dbeta,
+                    int N, int C, int H, int W, sn_dtype dtype, sn_stream stream);
+
+/* POOL (max) forward, the paper's example of a cheap-to-recompute layer
+ * (Sec. 3.4).  Window kh x kw, stride, padding (pad < window; padded positions
+ * never win).  Of equal maxima the first in row-major window order wins.
+ * idx[n,c,p,q] = h*W + v of the winner inside its input plane (int32). */
+sn_status sn_maxpool_fwd(const void *x, void *y, int32_t *idx, int N, int C, int H, int W,
+                         int kh, int kw, int sh, int sw, int ph, int pw,
+                         sn_dtype dtype, sn_stream stream);
+
+/* POOL backward: dx[n,c,i] = sum of dy[n,c,p,q] over the windows whose idx is i
+ * (overlapping windows add; fp32 accumulation in window order). */
+sn_status sn_maxpool_bwd(const void *dy, const int32_t *idx, void *dx, int N, int C, int H, int W,
+                         int kh, int kw, int sh, int sw, int ph, int pw,
+                         sn_dtype dtype, sn_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SN_H */

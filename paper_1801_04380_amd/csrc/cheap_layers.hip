@@ -1,0 +1,614 @@
+// The cheap layers that cost-aware recomputation replays (Sec. 3.4 of the
+// paper): ACT (ReLU), BN (training mode) and POOL (max), forward and backward.
+// All of them stream an N*C*H*W tensor once or twice and are bound by HBM
+// bandwidth, so the kernels are about 16-byte coalesced accesses, enough
+// workgroups for 256 compute units, and fixed-order wavefront reductions for
+// the BN statistics.  Storage is fp32 or bf16; arithmetic is fp32.
+#include "sn_internal.h"
+#include <type_traits>
+
+namespace sn {
+namespace {
+
+constexpr int WAVE = 64;
+
+template <typename T> __device__ inline float ld(const T *p);
+template <> __device__ inline float ld<float>(const float *p) { return *p; }
+template <> __device__ inline float ld<bf16_t>(const bf16_t *p) { return bf16_to_f32(*p); }
+__device__ inline void st(float *p, float v) { *p = v; }
+__device__ inline void st(bf16_t *p, float v) { *p = f32_to_bf16(v); }
+
+// 16-byte vector of T, unpacked to / packed from floats.
+template <typename T> struct Vec;
+template <> struct Vec<float> {
+    static constexpr int N = 4;
+    __device__ static void load(const float *p, float (&f)[4])
+    {
+        float4 v = *reinterpret_cast<const float4 *>(p);
+        f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+    }
+    __device__ static void store(float *p, const float (&f)[4])
+    {
+        *reinterpret_cast<float4 *>(p) = make_float4(f[0], f[1], f[2], f[3]);
+    }
+};
+template <> struct Vec<bf16_t> {
+    static constexpr int N = 8;
+    __device__ static void load(const bf16_t *p, float (&f)[8])
+    {
+        uint4 v = *reinterpret_cast<const uint4 *>(p);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            f[2 * i] = __uint_as_float(w[i] << 16);
+            f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+    __device__ static void store(bf16_t *p, const float (&f)[8])
+    {
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            w[i] = (uint32_t)f32_to_bf16(f[2 * i]) | ((uint32_t)f32_to_bf16(f[2 * i + 1]) << 16);
+        *reinterpret_cast<uint4 *>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+};
+
+// ------------------------------------------------------------------ ReLU
+// Flat streaming kernels: each thread moves UNROLL 16-byte vectors, a workgroup
+// covers one contiguous run; the ragged end (< one vector) is done by scalars.
+constexpr int RELU_UNROLL = 4;
+
+template <typename T>
+__global__ void __launch_bounds__(256) relu_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, size_t n)
+{
+    constexpr int V = Vec<T>::N;
+    const size_t nvec = n / V;
+    const size_t base = (size_t)blockIdx.x * (256 * RELU_UNROLL) + threadIdx.x;
+#pragma unroll
+    for (int u = 0; u < RELU_UNROLL; ++u) {
+        const size_t i = base + (size_t)u * 256;
+        if (i < nvec) {
+            uint4 v = reinterpret_cast<const uint4 *>(x)[i];
+            if (sizeof(T) == 2) {
+                // a bf16 is positive iff its sign bit is clear: clear every half whose sign is set
+                uint32_t *w = reinterpret_cast<uint32_t *>(&v);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    uint32_t neg = (w[k] >> 15) & 0x00010001u;
+                    w[k] &= ~(neg * 0xffffu);
+                }
+            } else {
+                float *f = reinterpret_cast<float *>(&v);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) f[k] = f[k] > 0.f ? f[k] : 0.f;
+            }
+            reinterpret_cast<uint4 *>(y)[i] = v;
+        }
+    }
+    if (blockIdx.x == 0) {
+        const size_t i = nvec * V + threadIdx.x;
+        if (threadIdx.x < V && i < n) {
+            float f = ld<T>(x + i);
+            st(y + i, f > 0.f ? f : 0.f);
+        }
+    }
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256)
+relu_bwd_kernel(const T *__restrict__ x, const T *__restrict__ dy, T *__restrict__ dx, size_t n)
+{
+    constexpr int V = Vec<T>::N;
+    const size_t nvec = n / V;
+    const size_t base = (size_t)blockIdx.x * (256 * RELU_UNROLL) + threadIdx.x;
+#pragma unroll
+    for (int u = 0; u < RELU_UNROLL; ++u) {
+        const size_t i = base + (size_t)u * 256;
+        if (i < nvec) {
+            uint4 xv = reinterpret_cast<const uint4 *>(x)[i];
+            uint4 gv = reinterpret_cast<const uint4 *>(dy)[i];
+            if (sizeof(T) == 2) {
+                const uint32_t *xw = reinterpret_cast<const uint32_t *>(&xv);
+                uint32_t *gw = reinterpret_cast<uint32_t *>(&gv);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    // x > 0 iff the 16 bits are in 0x0001 .. 0x7fff
+                    uint32_t lo = xw[k] & 0xffffu, hi = xw[k] >> 16;
+                    uint32_t keep = ((lo - 1u) < 0x7fffu ? 0x0000ffffu : 0u) | ((hi - 1u) < 0x7fffu ? 0xffff0000u : 0u);
+                    gw[k] &= keep;
+                }
+            } else {
+                const float *xf = reinterpret_cast<const float *>(&xv);
+                float *gf = reinterpret_cast<float *>(&gv);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) gf[k] = xf[k] > 0.f ? gf[k] : 0.f;
+            }
+            reinterpret_cast<uint4 *>(dx)[i] = gv;
+        }
+    }
+    if (blockIdx.x == 0) {
+        const size_t i = nvec * V + threadIdx.x;
+        if (threadIdx.x < V && i < n) {
+            float f = ld<T>(x + i), gr = ld<T>(dy + i);
+            st(dx + i, f > 0.f ? gr : 0.f);
+        }
+    }
+}
+
+// ------------------------------------------------------------------ BN
+// One channel's data is N planes of HW contiguous elements.  The planes are cut
+// into segments of at most SEG elements; a wavefront takes one segment at a
+// time and walks it with 16-byte accesses (scalar head and tail when the segment
+// does not start or end on a 16-byte boundary -- planes with odd H*W do not).
+// Workgroup (c, slice) takes the segments slice*4 + wave, stepping by 4*nslice,
+// so which wave adds which element, and in what order, depends on the shape
+// only: the statistics are bit-identical from run to run.
+constexpr int SEG = 4096;
+
+struct Slices {
+    int nseg_plane;  // segments per plane
+    int nseg;        // segments per channel = N * nseg_plane
+    int nslice;      // workgroups per channel
+};
+
+template <typename T, typename FVec, typename FOne>
+__device__ inline void walk_segment(const T *p, int len, int lane, FVec fvec, FOne fone)
+{
+    constexpr int V = Vec<T>::N;
+    const int mis = (int)((reinterpret_cast<uintptr_t>(p) & 15u) / sizeof(T));
+    int head = (V - mis) % V;
+    if (head > len) head = len;
+    if (lane < head) fone(lane);
+    const int nvec = (len - head) / V;
+    for (int i = lane; i < nvec; i += WAVE) fvec(head + i * V);
+    const int done = head + nvec * V;
+    if (lane < len - done) fone(done + lane);
+}
+
+__device__ inline float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+    return v;
+}
+
+// Pass 1 (forward): per (channel, slice) partial sums of (x - shift) and
+// (x - shift)^2, shift = the channel's first element, which keeps the variance
+// free of cancellation whatever the channel's mean is.
+template <typename T>
+__global__ void __launch_bounds__(256)
+bn_stats_kernel(const T *__restrict__ x, float *__restrict__ part, int N, int C, int HW, Slices sl)
+{
+    constexpr int V = Vec<T>::N;
+    const int c = blockIdx.x, slice = blockIdx.y;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const float shift = ld<T>(x + (size_t)c * HW);
+    float s1 = 0.f, s2 = 0.f;
+    for (int seg = slice * 4 + wave; seg < sl.nseg; seg += 4 * sl.nslice) {
+        const int n = seg / sl.nseg_plane, k = seg - n * sl.nseg_plane;
+        const int e0 = k * SEG, len = min(SEG, HW - e0);
+        const T *p = x + ((size_t)n * C + c) * HW + e0;
+        walk_segment<T>(
+            p, len, lane,
+            [&](int off) {
+                float f[V];
+                Vec<T>::load(p + off, f);
+#pragma unroll
+                for (int i = 0; i < V; ++i) {
+                    float d = f[i] - shift;
+                    s1 += d;
+                    s2 += d * d;
+                }
+            },
+            [&](int off) {
+                float d = ld<T>(p + off) - shift;
+                s1 += d;
+                s2 += d * d;
+            });
+    }
+    s1 = wave_sum(s1);
+    s2 = wave_sum(s2);
+    __shared__ float red[2][4];
+    if (lane == 0) { red[0][wave] = s1; red[1][wave] = s2; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float *o = part + ((size_t)c * sl.nslice + slice) * 2;
+        o[0] = (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]);
+        o[1] = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
+    }
+}
+
+// Pass 2 (forward): one wavefront per channel folds the slices in fixed order.
+template <typename T>
+__global__ void __launch_bounds__(64)
+bn_stats_final_kernel(const T *__restrict__ x, const float *__restrict__ part, float *__restrict__ mean,
+                      float *__restrict__ invstd, int N, int HW, int nslice, float eps)
+{
+    const int c = blockIdx.x, lane = threadIdx.x;
+    double s1 = 0.0, s2 = 0.0;
+    for (int i = lane; i < nslice; i += WAVE) {
+        s1 += part[((size_t)c * nslice + i) * 2];
+        s2 += part[((size_t)c * nslice + i) * 2 + 1];
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        s1 += __shfl_xor(s1, o, WAVE);
+        s2 += __shfl_xor(s2, o, WAVE);
+    }
+    if (lane == 0) {
+        const double M = (double)N * (double)HW;
+        const double shift = (double)ld<T>(x + (size_t)c * HW);
+        const double d = s1 / M;
+        double var = s2 / M - d * d;
+        if (var < 0.0) var = 0.0;
+        mean[c] = (float)(shift + d);
+        invstd[c] = (float)(1.0 / sqrt(var + (double)eps));
+    }
+}
+
+// Pass 3 (forward): y = gamma*invstd*(x - mean) + beta.
+template <typename T>
+__global__ void __launch_bounds__(256)
+bn_apply_kernel(const T *__restrict__ x, T *__restrict__ y, const float *__restrict__ gamma,
+                const float *__restrict__ beta, const float *__restrict__ mean,
+                const float *__restrict__ invstd, int N, int C, int HW, Slices sl)
+{
+    constexpr int V = Vec<T>::N;
+    const int c = blockIdx.x, slice = blockIdx.y;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const float mu = mean[c], a = gamma[c] * invstd[c], b = beta[c];
+    for (int seg = slice * 4 + wave; seg < sl.nseg; seg += 4 * sl.nslice) {
+        const int n = seg / sl.nseg_plane, k = seg - n * sl.nseg_plane;
+        const int e0 = k * SEG, len = min(SEG, HW - e0);
+        const size_t base = ((size_t)n * C + c) * HW + e0;
+        const T *p = x + base;
+        T *o = y + base;
+        walk_segment<T>(
+            p, len, lane,
+            [&](int off) {
+                float f[V];
+                Vec<T>::load(p + off, f);
+#pragma unroll
+                for (int i = 0; i < V; ++i) f[i] = (f[i] - mu) * a + b;
+                Vec<T>::store(o + off, f);
+            },
+            [&](int off) { st(o + off, (ld<T>(p + off) - mu) * a + b); });
+    }
+}
+
+// Backward pass 1: per (channel, slice) partial sums of dy and dy*(x - mean).
+template <typename T>
+__global__ void __launch_bounds__(256)
+bn_bwd_reduce_kernel(const T *__restrict__ x, const T *__restrict__ dy, const float *__restrict__ mean,
+                     float *__restrict__ part, int N, int C, int HW, Slices sl)
+{
+    constexpr int V = Vec<T>::N;
+    const int c = blockIdx.x, slice = blockIdx.y;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const float mu = mean[c];
+    float s1 = 0.f, s2 = 0.f;
+    for (int seg = slice * 4 + wave; seg < sl.nseg; seg += 4 * sl.nslice) {
+        const int n = seg / sl.nseg_plane, k = seg - n * sl.nseg_plane;
+        const int e0 = k * SEG, len = min(SEG, HW - e0);
+        const size_t base = ((size_t)n * C + c) * HW + e0;
+        const T *p = x + base, *gp = dy + base;
+        walk_segment<T>(
+            p, len, lane,
+            [&](int off) {
+                float f[V], gr[V];
+                Vec<T>::load(p + off, f);
+                Vec<T>::load(gp + off, gr);
+#pragma unroll
+                for (int i = 0; i < V; ++i) {
+                    s1 += gr[i];
+                    s2 += gr[i] * (f[i] - mu);
+                }
+            },
+            [&](int off) {
+                float gr = ld<T>(gp + off);
+                s1 += gr;
+                s2 += gr * (ld<T>(p + off) - mu);
+            });
+    }
+    s1 = wave_sum(s1);
+    s2 = wave_sum(s2);
+    __shared__ float red[2][4];
+    if (lane == 0) { red[0][wave] = s1; red[1][wave] = s2; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float *o = part + ((size_t)c * sl.nslice + slice) * 2;
+        o[0] = (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]);
+        o[1] = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
+    }
+}
+
+__global__ void __launch_bounds__(64)
+bn_bwd_final_kernel(const float *__restrict__ part, const float *__restrict__ invstd,
+                    float *__restrict__ dgamma, float *__restrict__ dbeta, int nslice)
+{
+    const int c = blockIdx.x, lane = threadIdx.x;
+    double s1 = 0.0, s2 = 0.0;
+    for (int i = lane; i < nslice; i += WAVE) {
+        s1 += part[((size_t)c * nslice + i) * 2];
+        s2 += part[((size_t)c * nslice + i) * 2 + 1];
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        s1 += __shfl_xor(s1, o, WAVE);
+        s2 += __shfl_xor(s2, o, WAVE);
+    }
+    if (lane == 0) {
+        dbeta[c] = (float)s1;
+        dgamma[c] = (float)(s2 * (double)invstd[c]);
+    }
+}
+
+// Backward pass 3: dx = gamma*invstd * (dy - dbeta/M - xhat*dgamma/M).
+template <typename T>
+__global__ void __launch_bounds__(256)
+bn_bwd_apply_kernel(const T *__restrict__ x, const T *__restrict__ dy, T *__restrict__ dx,
+                    const float *__restrict__ gamma, const float *__restrict__ mean,
+                    const float *__restrict__ invstd, const float *__restrict__ dgamma,
+                    const float *__restrict__ dbeta, int N, int C, int HW, Slices sl)
+{
+    constexpr int V = Vec<T>::N;
+    const int c = blockIdx.x, slice = blockIdx.y;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const float invM = 1.f / ((float)N * (float)HW);
+    const float mu = mean[c], is = invstd[c], k1 = gamma[c] * is;
+    const float kb = dbeta[c] * invM, kg = dgamma[c] * invM * is;  // xhat*dgamma/M = (x-mu)*kg
+    for (int seg = slice * 4 + wave; seg < sl.nseg; seg += 4 * sl.nslice) {
+        const int n = seg / sl.nseg_plane, k = seg - n * sl.nseg_plane;
+        const int e0 = k * SEG, len = min(SEG, HW - e0);
+        const size_t base = ((size_t)n * C + c) * HW + e0;
+        const T *p = x + base, *gp = dy + base;
+        T *o = dx + base;
+        walk_segment<T>(
+            p, len, lane,
+            [&](int off) {
+                float f[V], gr[V];
+                Vec<T>::load(p + off, f);
+                Vec<T>::load(gp + off, gr);
+#pragma unroll
+                for (int i = 0; i < V; ++i) f[i] = k1 * (gr[i] - kb - (f[i] - mu) * kg);
+                Vec<T>::store(o + off, f);
+            },
+            [&](int off) { st(o + off, k1 * (ld<T>(gp + off) - kb - (ld<T>(p + off) - mu) * kg)); });
+    }
+}
+
+// Tensors too small to hold the partial sums (fewer than 8 bytes per channel):
+// one thread per channel does the whole layer.
+template <typename T>
+__global__ void bn_fwd_tiny_kernel(const T *__restrict__ x, T *__restrict__ y, const float *__restrict__ gamma,
+                                   const float *__restrict__ beta, float *__restrict__ mean,
+                                   float *__restrict__ invstd, int N, int C, int HW, float eps)
+{
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= C) return;
+    const float M = (float)N * (float)HW;
+    float s = 0.f;
+    for (int n = 0; n < N; ++n)
+        for (int i = 0; i < HW; ++i) s += ld<T>(x + ((size_t)n * C + c) * HW + i);
+    const float mu = s / M;
+    float ss = 0.f;
+    for (int n = 0; n < N; ++n)
+        for (int i = 0; i < HW; ++i) {
+            float d = ld<T>(x + ((size_t)n * C + c) * HW + i) - mu;
+            ss += d * d;
+        }
+    const float is = 1.f / sqrtf(ss / M + eps);
+    mean[c] = mu;
+    invstd[c] = is;
+    const float a = gamma[c] * is, b = beta[c];
+    for (int n = 0; n < N; ++n)
+        for (int i = 0; i < HW; ++i) {
+            const size_t j = ((size_t)n * C + c) * HW + i;
+            st(y + j, (ld<T>(x + j) - mu) * a + b);
+        }
+}
+
+template <typename T>
+__global__ void bn_bwd_tiny_kernel(const T *__restrict__ x, const T *__restrict__ dy, T *__restrict__ dx,
+                                   const float *__restrict__ gamma, const float *__restrict__ mean,
+                                   const float *__restrict__ invstd, float *__restrict__ dgamma,
+                                   float *__restrict__ dbeta, int N, int C, int HW)
+{
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= C) return;
+    const float invM = 1.f / ((float)N * (float)HW);
+    const float mu = mean[c], is = invstd[c];
+    float db = 0.f, dg = 0.f;
+    for (int n = 0; n < N; ++n)
+        for (int i = 0; i < HW; ++i) {
+            const size_t j = ((size_t)n * C + c) * HW + i;
+            const float gr = ld<T>(dy + j);
+            db += gr;
+            dg += gr * (ld<T>(x + j) - mu);
+        }
+    dg *= is;
+    dbeta[c] = db;
+    dgamma[c] = dg;
+    const float k1 = gamma[c] * is, kb = db * invM, kg = dg * invM * is;
+    for (int n = 0; n < N; ++n)
+        for (int i = 0; i < HW; ++i) {
+            const size_t j = ((size_t)n * C + c) * HW + i;
+            st(dx + j, k1 * (ld<T>(dy + j) - kb - (ld<T>(x + j) - mu) * kg));
+        }
+}
+
+Slices make_slices(int N, int C, int HW, size_t scratch_bytes)
+{
+    Slices s;
+    s.nseg_plane = (HW + SEG - 1) / SEG;
+    s.nseg = N * s.nseg_plane;
+    long long want = (4096 + C - 1) / C;            // about 4096 workgroups in all
+    long long most = (s.nseg + 3) / 4;              // at least one segment per wave
+    long long fit = (long long)(scratch_bytes / (2 * sizeof(float)) / (size_t)C);
+    if (want > most) want = most;
+    if (want > fit) want = fit;
+    if (want > 65535) want = 65535;
+    if (want < 1) want = 1;
+    s.nslice = (int)want;
+    return s;
+}
+
+// ------------------------------------------------------------------ max-pool
+template <typename T>
+__global__ void __launch_bounds__(256)
+maxpool_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, int32_t *__restrict__ idx, size_t total,
+                   int H, int W, int P, int Q, int kh, int kw, int sh, int sw, int ph, int pw)
+{
+    const size_t o = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (o >= total) return;
+    const int PQ = P * Q;
+    const size_t nc = o / PQ;
+    const int pq = (int)(o - nc * PQ), p = pq / Q, q = pq - p * Q;
+    const T *xp = x + nc * (size_t)H * W;
+    const int h0 = p * sh - ph, v0 = q * sw - pw;
+    const int hb = max(h0, 0), he = min(h0 + kh, H), vb = max(v0, 0), ve = min(v0 + kw, W);
+    // row-major scan, a later element wins only if strictly greater
+    int best = hb * W + vb;
+    T bestraw = xp[best];
+    float bv = ld<T>(&bestraw);
+    for (int h = hb; h < he; ++h)
+        for (int v = vb; v < ve; ++v) {
+            T raw = xp[h * W + v];
+            float f = ld<T>(&raw);
+            if (f > bv) { bv = f; best = h * W + v; bestraw = raw; }
+        }
+    y[o] = bestraw;
+    idx[o] = best;
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256)
+maxpool_bwd_kernel(const T *__restrict__ dy, const int32_t *__restrict__ idx, T *__restrict__ dx, size_t total,
+                   int H, int W, int P, int Q, int kh, int kw, int sh, int sw, int ph, int pw)
+{
+    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= total) return;
+    const int HW = H * W;
+    const size_t nc = e / HW;
+    const int hw = (int)(e - nc * HW), h = hw / W, v = hw - h * W;
+    // windows p with p*sh - ph <= h < p*sh - ph + kh
+    const int pnum = h + ph - kh + 1, qnum = v + pw - kw + 1;
+    const int p0 = pnum > 0 ? (pnum + sh - 1) / sh : 0, p1 = min((h + ph) / sh, P - 1);
+    const int q0 = qnum > 0 ? (qnum + sw - 1) / sw : 0, q1 = min((v + pw) / sw, Q - 1);
+    const T *gp = dy + nc * (size_t)P * Q;
+    const int32_t *ip = idx + nc * (size_t)P * Q;
+    float acc = 0.f;
+    for (int p = p0; p <= p1; ++p)
+        for (int q = q0; q <= q1; ++q)
+            if (ip[p * Q + q] == hw) acc += ld<T>(gp + p * Q + q);
+    st(dx + e, acc);
+}
+
+template <typename F> hipError_t by_dtype(int bf16, F f)
+{
+    if (bf16) f((bf16_t *)nullptr);
+    else f((float *)nullptr);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_relu_fwd(const void *x, void *y, size_t n, int bf16, hipStream_t s)
+{
+    if (n == 0) return hipSuccess;
+    return by_dtype(bf16, [&](auto *tag) {
+        typedef typename std::remove_pointer<decltype(tag)>::type T;
+        const size_t nvec = n / Vec<T>::N;
+        const size_t per = 256 * RELU_UNROLL;
+        dim3 grid((unsigned)((nvec + per - 1) / per + (nvec == 0 ? 1 : 0))), block(256);
+        hipLaunchKernelGGL(relu_fwd_kernel<T>, grid, block, 0, s, (const T *)x, (T *)y, n);
+    });
+}
+
+hipError_t launch_relu_bwd(const void *x, const void *dy, void *dx, size_t n, int bf16, hipStream_t s)
+{
+    if (n == 0) return hipSuccess;
+    return by_dtype(bf16, [&](auto *tag) {
+        typedef typename std::remove_pointer<decltype(tag)>::type T;
+        const size_t nvec = n / Vec<T>::N;
+        const size_t per = 256 * RELU_UNROLL;
+        dim3 grid((unsigned)((nvec + per - 1) / per + (nvec == 0 ? 1 : 0))), block(256);
+        hipLaunchKernelGGL(relu_bwd_kernel<T>, grid, block, 0, s, (const T *)x, (const T *)dy, (T *)dx, n);
+    });
+}
+
+hipError_t launch_bn_fwd(const void *x, const float *gamma, const float *beta, void *y, float *mean,
+                         float *invstd, int N, int C, int HW, float eps, int bf16, hipStream_t s)
+{
+    const size_t esz = bf16 ? 2 : 4;
+    if ((size_t)N * HW * esz < 2 * sizeof(float))
+        return by_dtype(bf16, [&](auto *tag) {
+            typedef typename std::remove_pointer<decltype(tag)>::type T;
+            hipLaunchKernelGGL(bn_fwd_tiny_kernel<T>, dim3((C + 63) / 64), dim3(64), 0, s, (const T *)x, (T *)y,
+                               gamma, beta, mean, invstd, N, C, HW, eps);
+        });
+    // y is dead until pass 3, so it holds the per-slice partial sums meanwhile
+    const Slices sl = make_slices(N, C, HW, (size_t)N * C * HW * esz);
+    float *part = reinterpret_cast<float *>(y);
+    return by_dtype(bf16, [&](auto *tag) {
+        typedef typename std::remove_pointer<decltype(tag)>::type T;
+        dim3 grid(C, sl.nslice), block(256);
+        hipLaunchKernelGGL(bn_stats_kernel<T>, grid, block, 0, s, (const T *)x, part, N, C, HW, sl);
+        hipLaunchKernelGGL(bn_stats_final_kernel<T>, dim3(C), dim3(64), 0, s, (const T *)x, part, mean, invstd,
+                           N, HW, sl.nslice, eps);
+        hipLaunchKernelGGL(bn_apply_kernel<T>, grid, block, 0, s, (const T *)x, (T *)y, gamma, beta, mean,
+                           invstd, N, C, HW, sl);
+    });
+}
+
+hipError_t launch_bn_bwd(const void *x, const void *dy, const float *gamma, const float *mean,
+                         const float *invstd, void *dx, float *dgamma, float *dbeta, int N, int C, int HW,
+                         int bf16, hipStream_t s)
+{
+    const size_t esz = bf16 ? 2 : 4;
+    if ((size_t)N * HW * esz < 2 * sizeof(float))
+        return by_dtype(bf16, [&](auto *tag) {
+            typedef typename std::remove_pointer<decltype(tag)>::type T;
+            hipLaunchKernelGGL(bn_bwd_tiny_kernel<T>, dim3((C + 63) / 64), dim3(64), 0, s, (const T *)x,
+                               (const T *)dy, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);
+        });
+    const Slices sl = make_slices(N, C, HW, (size_t)N * C * HW * esz);
+    float *part = reinterpret_cast<float *>(dx);  // dx is dead until pass 3
+    return by_dtype(bf16, [&](auto *tag) {
+        typedef typename std::remove_pointer<decltype(tag)>::type T;
+        dim3 grid(C, sl.nslice), block(256);
+        hipLaunchKernelGGL(bn_bwd_reduce_kernel<T>, grid, block, 0, s, (const T *)x, (const T *)dy, mean, part,
+                           N, C, HW, sl);
+        hipLaunchKernelGGL(bn_bwd_final_kernel, dim3(C), dim3(64), 0, s, part, invstd, dgamma, dbeta,
+                           sl.nslice);
+        hipLaunchKernelGGL(bn_bwd_apply_kernel<T>, grid, block, 0, s, (const T *)x, (const T *)dy, (T *)dx,
+                           gamma, mean, invstd, dgamma, dbeta, N, C, HW, sl);
+    });
+}
+
+hipError_t launch_maxpool_fwd(const void *x, void *y, int32_t *idx, int NC, int H, int W, int P, int Q, int kh,
+                              int kw, int sh, int sw, int ph, int pw, int bf16, hipStream_t s)
+{
+    const size_t total = (size_t)NC * P * Q;
+    return by_dtype(bf16, [&](auto *tag) {
+        typedef typename std::remove_pointer<decltype(tag)>::type T;
+        dim3 grid((unsigned)((total + 255) / 256)), block(256);
+        hipLaunchKernelGGL(maxpool_fwd_kernel<T>, grid, block, 0, s, (const T *)x, (T *)y, idx, total, H, W, P,
+                           Q, kh, kw, sh, sw, ph, pw);
+    });
+}
+
+hipError_t launch_maxpool_bwd(const void *dy, const int32_t *idx, void *dx, int NC, int H, int W, int P, int Q,
+                              int kh, int kw, int sh, int sw, int ph, int pw, int bf16, hipStream_t s)
+{
+    const size_t total = (size_t)NC * H * W;
+    return by_dtype(bf16, [&](auto *tag) {
+        typedef typename std::remove_pointer<decltype(tag)>::type T;
+        dim3 grid((unsigned)((total + 255) / 256)), block(256);
+        hipLaunchKernelGGL(maxpool_bwd_kernel<T>, grid, block, 0, s, (const T *)dy, idx, (T *)dx, total, H, W, P,
+                           Q, kh, kw, sh, sw, ph, pw);
+    });
+}
+
+}  // namespace sn

@@ -1,0 +1,518 @@
+// Host side of the C ABI: argument checks, the workspace queries, the planner of
+// Sec. 3.5 (fastest algorithm whose workspace fits the budget) and the dispatch
+// of each call to the HIP kernels.  No device memory is allocated here.
+#include <algorithm>
+#include <cstring>
+#include <mutex>
+#include <vector>
+
+#include "sn_internal.h"
+
+using namespace sn;
+
+namespace {
+
+constexpr size_t WS_ALIGN = 256;
+
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+bool valid_dtype(int d) { return d == SN_F32 || d == SN_BF16; }
+
+// Shape check shared by every CONV entry point.  On success fills g.
+sn_status make_geom(const sn_conv_shape *s, ConvGeom *g)
+{
+    if (!s) return SN_ERR_BAD_ARG;
+    if (s->N < 1 || s->C < 1 || s->H < 1 || s->W < 1 || s->K < 1 || s->R < 1 || s->S < 1) return SN_ERR_BAD_ARG;
+    if (s->stride_h < 1 || s->stride_w < 1 || s->pad_h < 0 || s->pad_w < 0) return SN_ERR_BAD_ARG;
+    if (!valid_dtype(s->in_dtype) || !valid_dtype(s->out_dtype)) return SN_ERR_BAD_ARG;
+    if (s->in_dtype == SN_F32 && s->out_dtype != SN_F32) return SN_ERR_BAD_ARG;
+    const int P = sn_out_dim(s->H, s->pad_h, s->R, s->stride_h);
+    const int Q = sn_out_dim(s->W, s->pad_w, s->S, s->stride_w);
+    if (P < 1 || Q < 1) return SN_ERR_BAD_ARG;
+    // index ranges the kernels rely on: every GEMM dimension and every plane fits in int32
+    const long long lim = 0x7fffffffLL;
+    const long long CRS = (long long)s->C * s->R * s->S, KRS = (long long)s->K * s->R * s->S;
+    if ((long long)s->N * P * Q > lim || (long long)s->N * s->H * s->W > lim || CRS > lim || KRS > lim)
+        return SN_ERR_UNSUPPORTED;
+    if ((long long)s->C * s->H * s->W > lim || (long long)s->K * P * Q > lim || (long long)s->K * CRS > lim)
+        return SN_ERR_UNSUPPORTED;
+    if (s->pad_h >= 32768 || s->pad_w >= 32768 || s->R >= 32768 || s->S >= 32768) return SN_ERR_UNSUPPORTED;
+    g->N = s->N; g->C = s->C; g->H = s->H; g->W = s->W; g->K = s->K; g->R = s->R; g->S = s->S;
+    g->sh = s->stride_h; g->sw = s->stride_w; g->ph = s->pad_h; g->pw = s->pad_w;
+    g->P = P; g->Q = Q;
+    g->in_bf16 = s->in_dtype == SN_BF16;
+    g->out_bf16 = s->out_dtype == SN_BF16;
+    return SN_OK;
+}
+
+size_t in_elem(const ConvGeom &g) { return g.in_bf16 ? 2 : 4; }
+
+// ---- workspace layouts ------------------------------------------------------
+// IM2COL_GEMM, per image of a pass:
+//   forward          col                         C*R*S*P*Q * in_elem
+//   backward-filter  col, plus one block of fp32 partial dw slices per call
+//   backward-data    dcol (fp32)                 C*R*S*P*Q * 4
+struct Im2colPlan {
+    size_t per_image;  // bytes per image of a pass (256-aligned)
+    size_t fixed;      // bytes needed once per call (256-aligned)
+    int splits;        // backward-filter slices per pass
+};
+
+ConvGeom gemm_geom_1x1(const ConvGeom &g, int nimg);
+
+bool im2col_supported(const ConvGeom &g)
+{
+    return (long long)g.C * g.R * g.S <= 65535;  // grid.y of the unfold kernel
+}
+
+Im2colPlan im2col_plan(const ConvGeom &g, sn_conv_dir dir)
+{
+    Im2colPlan p;
+    const size_t cells = (size_t)g.C * g.R * g.S * g.P * g.Q;
+    p.per_image = align_up(cells * (dir == SN_CONV_BWD_DATA ? 4 : in_elem(g)), WS_ALIGN);
+    p.fixed = 0;
+    p.splits = 1;
+    if (dir == SN_CONV_BWD_FILTER) {
+        // sized for a full-batch pass, the most slices any pass can want
+        p.splits = generic_bwd_filter_splits(gemm_geom_1x1(g, g.N));
+        p.fixed = align_up((size_t)p.splits * g.K * g.C * g.R * g.S * sizeof(float), WS_ALIGN);
+    }
+    return p;
+}
+
+// The GEMM of the explicit algorithm, seen as a 1x1 stride-1 convolution over
+// the unfolded tensor [nimg][C*R*S][P][Q].
+ConvGeom gemm_geom_1x1(const ConvGeom &g, int nimg)
+{
+    ConvGeom u = g;
+    u.N = nimg;
+    u.C = g.C * g.R * g.S;
+    u.H = g.P; u.W = g.Q;
+    u.R = u.S = 1;
+    u.sh = u.sw = 1;
+    u.ph = u.pw = 0;
+    return u;
+}
+
+// STAGED backward-filter: fp32 partial dw per slice of the (n,p,q) sum.
+size_t staged_bwd_filter_bytes(const ConvGeom &g, int *splits_out)
+{
+    int splits = generic_bwd_filter_splits(g);
+    if (splits_out) *splits_out = splits;
+    return align_up((size_t)splits * g.K * g.C * g.R * g.S * sizeof(float), WS_ALIGN);
+}
+
+sn_status query(const ConvGeom &g, sn_conv_dir dir, sn_conv_algo algo, size_t *min_b, size_t *pref_b)
+{
+    switch (algo) {
+    case SN_ALGO_DIRECT:
+        *min_b = *pref_b = 0;
+        return SN_OK;
+    case SN_ALGO_IM2COL_GEMM: {
+        if (!im2col_supported(g)) return SN_ERR_UNSUPPORTED;
+        Im2colPlan p = im2col_plan(g, dir);
+        *min_b = p.fixed + p.per_image;
+        *pref_b = p.fixed + p.per_image * (size_t)g.N;
+        return SN_OK;
+    }
+    case SN_ALGO_STAGED:
+        if (dir == SN_CONV_BWD_FILTER) {
+            *min_b = *pref_b = staged_bwd_filter_bytes(g, nullptr);
+            return SN_OK;
+        }
+        return SN_ERR_UNSUPPORTED;
+    default:
+        return SN_ERR_BAD_ARG;
+    }
+}
+
+// ---- planner table ------------------------------------------------------------
+struct Record {
+    sn_conv_shape shape;
+    int dir, algo;
+    size_t ws;
+    float ms;
+};
+std::mutex g_mu;
+std::vector<Record> g_table;
+
+bool same_shape(const sn_conv_shape &a, const sn_conv_shape &b) { return std::memcmp(&a, &b, sizeof(a)) == 0; }
+
+// Built-in ranking used when nothing has been measured for the shape: lower is
+// tried first.  The workspace-staged implicit GEMM, then the direct one; the
+// explicit unfold pays a write and a read of a buffer R*S times the input, so it
+// is only ever picked on measurement.
+const sn_conv_algo kRanking[] = {SN_ALGO_STAGED, SN_ALGO_DIRECT, SN_ALGO_IM2COL_GEMM};
+
+sn_status plan(const sn_conv_shape *shape, const ConvGeom &g, sn_conv_dir dir, size_t budget,
+               sn_conv_algo *algo, size_t *bytes, float *ms_out)
+{
+    bool found = false;
+    Record best = {};
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        for (const Record &r : g_table) {
+            if (r.dir != (int)dir || !same_shape(r.shape, *shape) || r.ws > budget) continue;
+            if (!found || r.ms < best.ms || (r.ms == best.ms && r.ws < best.ws)) {
+                best = r;
+                found = true;
+            }
+        }
+    }
+    if (found) {
+        *algo = (sn_conv_algo)best.algo;
+        *bytes = best.ws;
+        if (ms_out) *ms_out = best.ms;
+        return SN_OK;
+    }
+    for (sn_conv_algo a : kRanking) {
+        size_t mn = 0, pf = 0;
+        if (a == SN_ALGO_IM2COL_GEMM) continue;
+        if (query(g, dir, a, &mn, &pf) != SN_OK || mn > budget) continue;
+        *algo = a;
+        *bytes = std::min(pf, budget);
+        if (ms_out) *ms_out = -1.f;
+        return SN_OK;
+    }
+    return SN_ERR_UNSUPPORTED;  // unreachable: DIRECT needs 0 bytes
+}
+
+sn_status check_ws(const void *ws, size_t bytes)
+{
+    if (bytes > 0 && !ws) return SN_ERR_BAD_ARG;
+    if (ws && !aligned(ws, WS_ALIGN)) return SN_ERR_BAD_ARG;
+    return SN_OK;
+}
+
+sn_status launch_status(hipError_t e) { return e == hipSuccess ? SN_OK : SN_ERR_LAUNCH; }
+
+// Resolve AUTO and check the budget for a named algorithm.
+sn_status resolve(const sn_conv_shape *shape, const ConvGeom &g, sn_conv_dir dir, sn_conv_algo *algo,
+                  size_t ws_bytes)
+{
+    if (*algo == SN_ALGO_AUTO) {
+        size_t used;
+        return plan(shape, g, dir, ws_bytes, algo, &used, nullptr);
+    }
+    size_t mn = 0, pf = 0;
+    sn_status s = query(g, dir, *algo, &mn, &pf);
+    if (s != SN_OK) return s;
+    if (mn > ws_bytes) return SN_ERR_WORKSPACE_TOO_SMALL;
+    return SN_OK;
+}
+
+// Images per pass of the explicit algorithm under this budget.
+int im2col_chunk(const ConvGeom &g, const Im2colPlan &p, size_t ws_bytes)
+{
+    size_t fit = (ws_bytes - p.fixed) / p.per_image;
+    return (int)std::min<size_t>(fit, (size_t)g.N);
+}
+
+size_t out_elem(const ConvGeom &g) { return g.out_bf16 ? 2 : 4; }
+
+sn_status run_fwd(const void *x, const void *w, void *y, const ConvGeom &g, sn_conv_algo algo, void *ws,
+                  size_t ws_bytes, hipStream_t st)
+{
+    if (algo == SN_ALGO_DIRECT) return launch_status(launch_generic_fwd(x, w, y, g, st));
+    if (algo == SN_ALGO_IM2COL_GEMM) {
+        const Im2colPlan p = im2col_plan(g, SN_CONV_FWD);
+        const int chunk = im2col_chunk(g, p, ws_bytes);
+        for (int n0 = 0; n0 < g.N; n0 += chunk) {
+            const int nimg = std::min(chunk, g.N - n0);
+            hipError_t e = launch_im2col(x, ws, g, n0, nimg, st);
+            if (e != hipSuccess) return SN_ERR_LAUNCH;
+            char *yo = static_cast<char *>(y) + (size_t)n0 * g.K * g.P * g.Q * out_elem(g);
+            e = launch_generic_fwd(ws, w, yo, gemm_geom_1x1(g, nimg), st);
+            if (e != hipSuccess) return SN_ERR_LAUNCH;
+        }
+        return SN_OK;
+    }
+    return SN_ERR_UNSUPPORTED;
+}
+
+sn_status run_bwd_data(const void *dy, const void *w, void *dx, const ConvGeom &g, sn_conv_algo algo, void *ws,
+                       size_t ws_bytes, hipStream_t st)
+{
+    if (algo == SN_ALGO_DIRECT) return launch_status(launch_generic_bwd_data(dy, w, dx, g, st));
+    if (algo == SN_ALGO_IM2COL_GEMM) {
+        const Im2colPlan p = im2col_plan(g, SN_CONV_BWD_DATA);
+        const int chunk = im2col_chunk(g, p, ws_bytes);
+        for (int n0 = 0; n0 < g.N; n0 += chunk) {
+            const int nimg = std::min(chunk, g.N - n0);
+            ConvGeom u = gemm_geom_1x1(g, nimg);
+            u.out_bf16 = 0;  // the column gradient stays fp32 until it is folded
+            const char *dyo = static_cast<const char *>(dy) + (size_t)n0 * g.K * g.P * g.Q * in_elem(g);
+            hipError_t e = launch_generic_bwd_data(dyo, w, ws, u, st);
+            if (e != hipSuccess) return SN_ERR_LAUNCH;
+            e = launch_col2im(static_cast<const float *>(ws), dx, g, n0, nimg, st);
+            if (e != hipSuccess) return SN_ERR_LAUNCH;
+        }
+        return SN_OK;
+    }
+    return SN_ERR_UNSUPPORTED;
+}
+
+sn_status run_bwd_filter(const void *x, const void *dy, void *dw, const ConvGeom &g, sn_conv_algo algo,
+                         void *ws, size_t ws_bytes, hipStream_t st)
+{
+    float *dwf = static_cast<float *>(dw);
+    if (algo == SN_ALGO_DIRECT)
+        return launch_status(launch_generic_bwd_filter(x, dy, dwf, g, generic_bwd_filter_splits(g), nullptr, false, st));
+    if (algo == SN_ALGO_STAGED) {
+        int splits;
+        staged_bwd_filter_bytes(g, &splits);
+        return launch_status(launch_generic_bwd_filter(x, dy, dwf, g, splits, static_cast<float *>(ws), false, st));
+    }
+    if (algo == SN_ALGO_IM2COL_GEMM) {
+        const Im2colPlan p = im2col_plan(g, SN_CONV_BWD_FILTER);
+        const int chunk = im2col_chunk(g, p, ws_bytes);
+        float *partial = static_cast<float *>(ws);
+        char *col = static_cast<char *>(ws) + p.fixed;
+        // each pass reduces its slices in fixed order; passes after the first add to dw
+        for (int n0 = 0, pass = 0; n0 < g.N; n0 += chunk, ++pass) {
+            const int nimg = std::min(chunk, g.N - n0);
+            hipError_t e = launch_im2col(x, col, g, n0, nimg, st);
+            if (e != hipSuccess) return SN_ERR_LAUNCH;
+            const ConvGeom u = gemm_geom_1x1(g, nimg);
+            const char *dyo = static_cast<const char *>(dy) + (size_t)n0 * g.K * g.P * g.Q * in_elem(g);
+            int splits = std::min(p.splits, generic_bwd_filter_splits(u));
+            e = launch_generic_bwd_filter(col, dyo, dwf, u, splits, partial, pass > 0, st);
+            if (e != hipSuccess) return SN_ERR_LAUNCH;
+        }
+        return SN_OK;
+    }
+    return SN_ERR_UNSUPPORTED;
+}
+
+}  // namespace
+
+extern "C" {
+
+int sn_version(void) { return 1; }
+
+int sn_out_dim(int in, int pad, int window, int stride)
+{
+    if (in < 1 || pad < 0 || window < 1 || stride < 1) return 0;
+    const long long span = (long long)in + 2LL * pad - window;
+    if (span < 0) return 0;
+    return (int)(span / stride) + 1;
+}
+
+sn_status sn_conv_workspace_query(const sn_conv_shape *shape, sn_conv_dir dir, sn_conv_algo algo,
+                                  size_t *min_bytes, size_t *preferred_bytes)
+{
+    ConvGeom g;
+    sn_status s = make_geom(shape, &g);
+    if (s != SN_OK) return s;
+    if (!min_bytes || !preferred_bytes || dir < SN_CONV_FWD || dir > SN_CONV_BWD_FILTER) return SN_ERR_BAD_ARG;
+    return query(g, dir, algo, min_bytes, preferred_bytes);
+}
+
+sn_status sn_conv_plan(const sn_conv_shape *shape, sn_conv_dir dir, size_t budget_bytes, sn_conv_algo *algo,
+                       size_t *bytes_used, float *predicted_ms)
+{
+    ConvGeom g;
+    sn_status s = make_geom(shape, &g);
+    if (s != SN_OK) return s;
+    if (!algo || !bytes_used || dir < SN_CONV_FWD || dir > SN_CONV_BWD_FILTER) return SN_ERR_BAD_ARG;
+    return plan(shape, g, dir, budget_bytes, algo, bytes_used, predicted_ms);
+}
+
+sn_status sn_planner_record(const sn_conv_shape *shape, sn_conv_dir dir, sn_conv_algo algo,
+                            size_t workspace_bytes, float ms)
+{
+    ConvGeom g;
+    sn_status s = make_geom(shape, &g);
+    if (s != SN_OK) return s;
+    if (dir < SN_CONV_FWD || dir > SN_CONV_BWD_FILTER || !(ms >= 0.f)) return SN_ERR_BAD_ARG;
+    size_t mn = 0, pf = 0;
+    s = query(g, dir, algo, &mn, &pf);
+    if (s != SN_OK) return s;
+    if (workspace_bytes < mn) return SN_ERR_WORKSPACE_TOO_SMALL;
+    std::lock_guard<std::mutex> lk(g_mu);
+    for (Record &r : g_table)
+        if (r.dir == (int)dir && r.algo == (int)algo && r.ws == workspace_bytes && same_shape(r.shape, *shape)) {
+            r.ms = ms;
+            return SN_OK;
+        }
+    Record r;
+    r.shape = *shape;
+    r.dir = dir;
+    r.algo = algo;
+    r.ws = workspace_bytes;
+    r.ms = ms;
+    g_table.push_back(r);
+    return SN_OK;
+}
+
+void sn_planner_clear(void)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_table.clear();
+}
+
+static sn_status conv_call(sn_conv_dir dir, const void *a, const void *b, void *out, const sn_conv_shape *shape,
+                           sn_conv_algo algo, void *ws, size_t ws_bytes, sn_stream stream)
+{
+    ConvGeom g;
+    sn_status s = make_geom(shape, &g);
+    if (s != SN_OK) return s;
+    if (!a || !b || !out || !aligned(a, 16) || !aligned(b, 16) || !aligned(out, 16)) return SN_ERR_BAD_ARG;
+    if (algo < SN_ALGO_AUTO || algo >= SN_ALGO_COUNT) return SN_ERR_BAD_ARG;
+    s = check_ws(ws, ws_bytes);
+    if (s != SN_OK) return s;
+    s = resolve(shape, g, dir, &algo, ws_bytes);
+    if (s != SN_OK) return s;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    switch (dir) {
+    case SN_CONV_FWD: return run_fwd(a, b, out, g, algo, ws, ws_bytes, st);
+    case SN_CONV_BWD_DATA: return run_bwd_data(a, b, out, g, algo, ws, ws_bytes, st);
+    default: return run_bwd_filter(a, b, out, g, algo, ws, ws_bytes, st);
+    }
+}
+
+sn_status sn_conv2d_fwd(const void *x, const void *w, void *y, const sn_conv_shape *shape, sn_conv_algo algo,
+                        void *workspace, size_t workspace_bytes, sn_stream stream)
+{
+    return conv_call(SN_CONV_FWD, x, w, y, shape, algo, workspace, workspace_bytes, stream);
+}
+
+sn_status sn_conv2d_bwd_data(const void *dy, const void *w, void *dx, const sn_conv_shape *shape,
+                             sn_conv_algo algo, void *workspace, size_t workspace_bytes, sn_stream stream)
+{
+    return conv_call(SN_CONV_BWD_DATA, dy, w, dx, shape, algo, workspace, workspace_bytes, stream);
+}
+
+sn_status sn_conv2d_bwd_filter(const void *x, const void *dy, void *dw, const sn_conv_shape *shape,
+                               sn_conv_algo algo, void *workspace, size_t workspace_bytes, sn_stream stream)
+{
+    return conv_call(SN_CONV_BWD_FILTER, x, dy, dw, shape, algo, workspace, workspace_bytes, stream);
+}
+
+sn_status sn_conv_autotune(sn_conv_dir dir, const void *a, const void *b, void *out, const sn_conv_shape *shape,
+                           void *workspace, size_t workspace_bytes, int iters, sn_stream stream)
+{
+    ConvGeom g;
+    sn_status s = make_geom(shape, &g);
+    if (s != SN_OK) return s;
+    if (dir < SN_CONV_FWD || dir > SN_CONV_BWD_FILTER || iters < 1) return SN_ERR_BAD_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return SN_ERR_LAUNCH;
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return SN_ERR_LAUNCH; }
+    sn_status result = SN_OK;
+    for (int algo = 0; algo < SN_ALGO_COUNT && result == SN_OK; ++algo) {
+        size_t mn = 0, pf = 0;
+        if (query(g, dir, (sn_conv_algo)algo, &mn, &pf) != SN_OK || mn > workspace_bytes) continue;
+        const size_t used = std::min(pf, workspace_bytes);
+        // one untimed run, then `iters` timed ones
+        s = conv_call(dir, a, b, out, shape, (sn_conv_algo)algo, workspace, used, stream);
+        if (s != SN_OK) { result = s; break; }
+        if (hipEventRecord(e0, st) != hipSuccess) { result = SN_ERR_LAUNCH; break; }
+        for (int i = 0; i < iters && s == SN_OK; ++i)
+            s = conv_call(dir, a, b, out, shape, (sn_conv_algo)algo, workspace, used, stream);
+        if (s != SN_OK) { result = s; break; }
+        float ms = 0.f;
+        if (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+            hipEventElapsedTime(&ms, e0, e1) != hipSuccess) {
+            result = SN_ERR_LAUNCH;
+            break;
+        }
+        result = sn_planner_record(shape, dir, (sn_conv_algo)algo, used, ms / (float)iters);
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return result;
+}
+
+static sn_status check_cheap(int N, int C, int H, int W, int dtype)
+{
+    if (N < 1 || C < 1 || H < 1 || W < 1 || !valid_dtype(dtype)) return SN_ERR_BAD_ARG;
+    if ((long long)H * W > 0x7fffffffLL || (long long)N * H * W > 0x7fffffffLL) return SN_ERR_UNSUPPORTED;
+    if ((long long)N * C > 0x7fffffffLL) return SN_ERR_UNSUPPORTED;
+    return SN_OK;
+}
+
+sn_status sn_relu_fwd(const void *x, void *y, size_t n, sn_dtype dtype, sn_stream stream)
+{
+    if (!valid_dtype(dtype)) return SN_ERR_BAD_ARG;
+    if (n == 0) return SN_OK;
+    if (!x || !y || !aligned(x, 16) || !aligned(y, 16)) return SN_ERR_BAD_ARG;
+    if (n / (dtype == SN_BF16 ? 8 : 4) / 1024 > 0x7fffffffULL) return SN_ERR_UNSUPPORTED;
+    return launch_status(launch_relu_fwd(x, y, n, dtype == SN_BF16, static_cast<hipStream_t>(stream)));
+}
+
+sn_status sn_relu_bwd(const void *x, const void *dy, void *dx, size_t n, sn_dtype dtype, sn_stream stream)
+{
+    if (!valid_dtype(dtype)) return SN_ERR_BAD_ARG;
+    if (n == 0) return SN_OK;
+    if (!x || !dy || !dx || !aligned(x, 16) || !aligned(dy, 16) || !aligned(dx, 16)) return SN_ERR_BAD_ARG;
+    if (n / (dtype == SN_BF16 ? 8 : 4) / 1024 > 0x7fffffffULL) return SN_ERR_UNSUPPORTED;
+    return launch_status(launch_relu_bwd(x, dy, dx, n, dtype == SN_BF16, static_cast<hipStream_t>(stream)));
+}
+
+sn_status sn_bn_fwd(const void *x, const float *gamma, const float *beta, void *y, float *save_mean,
+                    float *save_invstd, int N, int C, int H, int W, float eps, sn_dtype dtype, sn_stream stream)
+{
+    sn_status s = check_cheap(N, C, H, W, dtype);
+    if (s != SN_OK) return s;
+    if (!x || !gamma || !beta || !y || !save_mean || !save_invstd || x == y) return SN_ERR_BAD_ARG;
+    if (!aligned(x, 16) || !aligned(y, 16) || !aligned(gamma, 4) || !aligned(beta, 4) || !aligned(save_mean, 4) ||
+        !aligned(save_invstd, 4) || !(eps >= 0.f))
+        return SN_ERR_BAD_ARG;
+    if (C > 65535 * 32) return SN_ERR_UNSUPPORTED;
+    return launch_status(launch_bn_fwd(x, gamma, beta, y, save_mean, save_invstd, N, C, H * W, eps,
+                                       dtype == SN_BF16, static_cast<hipStream_t>(stream)));
+}
+
+sn_status sn_bn_bwd(const void *x, const void *dy, const float *gamma, const float *save_mean,
+                    const float *save_invstd, void *dx, float *dgamma, float *dbeta, int N, int C, int H, int W,
+                    sn_dtype dtype, sn_stream stream)
+{
+    sn_status s = check_cheap(N, C, H, W, dtype);
+    if (s != SN_OK) return s;
+    if (!x || !dy || !gamma || !save_mean || !save_invstd || !dx || !dgamma || !dbeta || dx == x || dx == dy)
+        return SN_ERR_BAD_ARG;
+    if (!aligned(x, 16) || !aligned(dy, 16) || !aligned(dx, 16) || !aligned(gamma, 4) || !aligned(save_mean, 4) ||
+        !aligned(save_invstd, 4) || !aligned(dgamma, 4) || !aligned(dbeta, 4))
+        return SN_ERR_BAD_ARG;
+    if (C > 65535 * 32) return SN_ERR_UNSUPPORTED;
+    return launch_status(launch_bn_bwd(x, dy, gamma, save_mean, save_invstd, dx, dgamma, dbeta, N, C, H * W,
+                                       dtype == SN_BF16, static_cast<hipStream_t>(stream)));
+}
+
+static sn_status check_pool(int N, int C, int H, int W, int kh, int kw, int sh, int sw, int ph, int pw, int dtype,
+                            int *P, int *Q)
+{
+    sn_status s = check_cheap(N, C, H, W, dtype);
+    if (s != SN_OK) return s;
+    if (kh < 1 || kw < 1 || sh < 1 || sw < 1 || ph < 0 || pw < 0 || ph >= kh || pw >= kw) return SN_ERR_BAD_ARG;
+    *P = sn_out_dim(H, ph, kh, sh);
+    *Q = sn_out_dim(W, pw, kw, sw);
+    if (*P < 1 || *Q < 1) return SN_ERR_BAD_ARG;
+    return SN_OK;
+}
+
+sn_status sn_maxpool_fwd(const void *x, void *y, int32_t *idx, int N, int C, int H, int W, int kh, int kw, int sh,
+                         int sw, int ph, int pw, sn_dtype dtype, sn_stream stream)
+{
+    int P, Q;
+    sn_status s = check_pool(N, C, H, W, kh, kw, sh, sw, ph, pw, dtype, &P, &Q);
+    if (s != SN_OK) return s;
+    if (!x || !y || !idx || !aligned(x, 16) || !aligned(y, 16) || !aligned(idx, 16)) return SN_ERR_BAD_ARG;
+    return launch_status(launch_maxpool_fwd(x, y, idx, N * C, H, W, P, Q, kh, kw, sh, sw, ph, pw,
+                                            dtype == SN_BF16, static_cast<hipStream_t>(stream)));
+}
+
+sn_status sn_maxpool_bwd(const void *dy, const int32_t *idx, void *dx, int N, int C, int H, int W, int kh, int kw,
+                         int sh, int sw, int ph, int pw, sn_dtype dtype, sn_stream stream)
+{
+    int P, Q;
+    sn_status s = check_pool(N, C, H, W, kh, kw, sh, sw, ph, pw, dtype, &P, &Q);
+    if (s != SN_OK) return s;
+    if (!dy || !idx || !dx || !aligned(dy, 16) || !aligned(dx, 16) || !aligned(idx, 16)) return SN_ERR_BAD_ARG;
+    return launch_status(launch_maxpool_bwd(dy, idx, dx, N * C, H, W, P, Q, kh, kw, sh, sw, ph, pw,
+                                            dtype == SN_BF16, static_cast<hipStream_t>(stream)));
+}
+
+}  // extern "C"

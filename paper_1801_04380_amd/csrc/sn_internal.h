@@ -1,0 +1,76 @@
+// Internal declarations shared by the host dispatcher and the HIP kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "sn.h"
+
+namespace sn {
+
+// Geometry of one CONV step, derived once on the host.
+struct ConvGeom {
+    int N, C, H, W, K, R, S, sh, sw, ph, pw, P, Q;
+    int in_bf16;   // 1: x, w, dy are bf16; 0: fp32
+    int out_bf16;  // 1: y / dx stored as bf16; 0: fp32
+};
+
+typedef unsigned short bf16_t;
+
+__host__ __device__ inline float bf16_to_f32(bf16_t v)
+{
+    union { uint32_t u; float f; } c;
+    c.u = (uint32_t)v << 16;
+    return c.f;
+}
+
+// fp32 -> bf16, round to nearest, ties to even; NaN stays NaN.
+__host__ __device__ inline bf16_t f32_to_bf16(float f)
+{
+    union { uint32_t u; float f; } c;
+    c.f = f;
+    if ((c.u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((c.u >> 16) | 0x40u);
+    c.u += 0x7fffu + ((c.u >> 16) & 1u);
+    return (bf16_t)(c.u >> 16);
+}
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ---- launchers implemented in the .hip files (all enqueue on `st`, return hipError_t) ----
+
+// Fallback implicit GEMM for any geometry and either dtype.  For backward-filter
+// `splits` > 1 spreads the (n,p,q) sum over that many workgroup slices: with
+// partial == nullptr the slices combine into dw with atomics (dw must be zeroed
+// first, which the launcher does); otherwise slice z writes its own
+// partial[z][K*C*R*S] and a reduction in slice order follows, which adds to the
+// existing dw when `accumulate` is set.
+hipError_t launch_generic_fwd(const void *x, const void *w, void *y, const ConvGeom &g, hipStream_t st);
+hipError_t launch_generic_bwd_data(const void *dy, const void *w, void *dx, const ConvGeom &g, hipStream_t st);
+hipError_t launch_generic_bwd_filter(const void *x, const void *dy, float *dw, const ConvGeom &g,
+                                     int splits, float *partial, bool accumulate, hipStream_t st);
+int generic_bwd_filter_splits(const ConvGeom &g);
+
+hipError_t launch_fill_zero(float *p, size_t n, hipStream_t st);
+// dw[i] = (accumulate ? dw[i] : 0) + sum_z partial[z][i], z ascending.
+hipError_t launch_reduce_partials(const float *partial, float *dw, size_t n, int splits, bool accumulate,
+                                  hipStream_t st);
+
+// im2col: col[i][C*R*S][P*Q] for images n0 .. n0+nimg-1 (i = n - n0), zero where
+// the tap falls outside the image.  Element type as the input.
+hipError_t launch_im2col(const void *x, void *col, const ConvGeom &g, int n0, int nimg, hipStream_t st);
+// col2im: dx[n][c][h][v] = sum over taps of dcol[i][(c,r,s)][p][q]; dcol is fp32.
+hipError_t launch_col2im(const float *dcol, void *dx, const ConvGeom &g, int n0, int nimg, hipStream_t st);
+
+// Cheap layers.
+hipError_t launch_relu_fwd(const void *x, void *y, size_t n, int bf16, hipStream_t st);
+hipError_t launch_relu_bwd(const void *x, const void *dy, void *dx, size_t n, int bf16, hipStream_t st);
+hipError_t launch_bn_fwd(const void *x, const float *gamma, const float *beta, void *y, float *mean,
+                         float *invstd, int N, int C, int HW, float eps, int bf16, hipStream_t st);
+hipError_t launch_bn_bwd(const void *x, const void *dy, const float *gamma, const float *mean,
+                         const float *invstd, void *dx, float *dgamma, float *dbeta, int N, int C,
+                         int HW, int bf16, hipStream_t st);
+hipError_t launch_maxpool_fwd(const void *x, void *y, int32_t *idx, int NC, int H, int W, int P, int Q,
+                              int kh, int kw, int sh, int sw, int ph, int pw, int bf16, hipStream_t st);
+hipError_t launch_maxpool_bwd(const void *dy, const int32_t *idx, void *dx, int NC, int H, int W, int P,
+                              int Q, int kh, int kw, int sh, int sw, int ph, int pw, int bf16,
+                              hipStream_t st);
+
+}  // namespace sn

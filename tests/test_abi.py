@@ -1,0 +1,82 @@
+"""CPU-only checks of the C ABI: the library loads, exports every symbol the
+header declares, and its host-side logic (shape rule, argument checks, workspace
+queries, planner) behaves as documented.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_1801_04380_amd as sn
+from paper_1801_04380_amd import _lib
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "sn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sn_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = _lib.load()
+    names = _declared_symbols()
+    assert len(names) >= 16
+    for name in names:
+        assert hasattr(lib, name), name
+        assert name in _lib.SIGNATURES, "binding lacks " + name
+    assert lib.sn_version() == 1
+
+
+def test_out_dim_floor_rule():
+    assert sn.sn_out_dim(227, 0, 11, 4) == 55
+    assert sn.sn_out_dim(55, 0, 3, 2) == 27
+    assert sn.sn_out_dim(27, 0, 3, 2) == 13
+    assert sn.sn_out_dim(56, 0, 1, 2) == 28      # floor, not ceil
+    assert sn.sn_out_dim(56, 1, 3, 2) == 28
+    assert sn.sn_out_dim(35, 0, 3, 2) == 17
+    assert sn.sn_out_dim(2, 0, 3, 1) == 0        # window does not fit
+
+
+def test_bad_arguments_are_refused_before_any_launch():
+    lib = _lib.load()
+    s = sn.conv_shape(2, 16, 16, 16, 16, 3, 3, (1, 1), (1, 1))
+    one = ctypes.c_void_p(256)
+    # null tensors
+    assert lib.sn_conv2d_fwd(None, None, None, ctypes.byref(s), 0, None, 0, None) == 1
+    # misaligned tensor pointer
+    assert lib.sn_conv2d_fwd(ctypes.c_void_p(260), one, one, ctypes.byref(s), 0, None, 0, None) == 1
+    # workspace bytes without a workspace, misaligned workspace
+    assert lib.sn_conv2d_fwd(one, one, one, ctypes.byref(s), 0, None, 1024, None) == 1
+    assert lib.sn_conv2d_fwd(one, one, one, ctypes.byref(s), 0, ctypes.c_void_p(128), 1024, None) == 1
+    # named algorithm with too little workspace
+    assert lib.sn_conv2d_fwd(one, one, one, ctypes.byref(s), sn.SN_ALGO_IM2COL_GEMM, one, 256, None) == 3
+    # bad shapes
+    for field, val in (("N", 0), ("stride_h", 0), ("pad_w", -1), ("in_dtype", 5), ("R", 40)):
+        b = sn.conv_shape(2, 16, 16, 16, 16, 3, 3, (1, 1), (1, 1))
+        setattr(b, field, val)
+        assert lib.sn_conv2d_fwd(one, one, one, ctypes.byref(b), 0, None, 0, None) == 1, field
+    # fp32 inputs cannot produce bf16 outputs
+    b = sn.conv_shape(2, 16, 16, 16, 16, 3, 3, in_dtype=sn.SN_F32, out_dtype=sn.SN_BF16)
+    assert lib.sn_conv2d_fwd(one, one, one, ctypes.byref(b), 0, None, 0, None) == 1
+    # cheap layers
+    assert lib.sn_relu_fwd(None, None, 10, 0, None) == 1
+    assert lib.sn_relu_fwd(None, None, 0, 0, None) == 0          # empty tensor: nothing to do
+    assert lib.sn_bn_fwd(one, one, one, one, one, one, 1, 1, 1, 1, 1e-5, 0, None) == 1   # y aliases x
+    assert lib.sn_maxpool_fwd(one, one, one, 1, 1, 4, 4, 2, 2, 2, 2, 2, 0, 0, None) == 1  # pad >= window
+
+
+def test_workspace_query():
+    s = sn.conv_shape(2, 16, 16, 16, 16, 3, 3, (1, 1), (1, 1))
+    assert sn.sn_conv_workspace_query(s, sn.SN_CONV_FWD, sn.SN_ALGO_DIRECT) == (0, 0)
+    mn, pf = sn.sn_conv_workspace_query(s, sn.SN_CONV_FWD, sn.SN_ALGO_IM2COL_GEMM)
+    # one image / the whole batch of the unfolded input: C*R*S*P*Q fp32 (288 KiB for the batch of 2)
+    assert mn == 16 * 9 * 256 * 4 and pf == 2 * mn == 288 * 1024
+    mn, pf = sn.sn_conv_workspace_query(s, sn.SN_CONV_BWD_FILTER, sn.SN_ALGO_STAGED)
+    assert mn == pf and mn % 256 == 0 and mn >= 16 * 16 * 9 * 4
+    b = sn.conv_shape(2, 16, 16, 16, 16, 3, 3, (1, 1), (1, 1), sn.SN_BF16, sn.SN_BF16)
+    mnb, _ = sn.sn_conv_workspace_query(b, sn.SN_CONV_FWD, sn.SN_ALGO_IM2COL_GEMM)
+    assert mnb == 16 * 9 * 256 * 2
+    mnd, _ = sn.sn_conv_workspace_query(b, sn.SN_CONV_BWD_DATA, sn.SN_ALGO_IM2COL_GEMM)
+    assert mnd == 16 * 9 * 256 * 4                # the column gradient is fp32

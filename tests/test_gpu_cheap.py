@@ -1,0 +1,129 @@
+"""GPU parity of the cheap layers (ReLU, BN, max-pool) against the fp64 oracle.
+
+Bars: pool indices bit-exact; values relative L2 <= 1e-5 (fp32 storage) or
+<= 5e-3 (bf16 storage, oracle fed the bf16-rounded inputs).  ReLU and pool
+forward only move values, so they must match exactly in either storage type.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_1801_04380_amd as sn
+from paper_1801_04380_amd import workloads as wl
+from _parity import DT, TOL, f64, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+# sizes: a ragged tail below one vector, several workgroups, odd plane sizes
+FLAT_SIZES = [0, 1, 7, 8, 9, 1023, 4096, 100003, 5 * 1024 * 1024 + 13]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("n", FLAT_SIZES)
+def test_relu(n, dtype):
+    x = wl.activation((n,), dtype, seed=n + 1)
+    dy = wl.activation((n,), dtype, seed=n + 2)
+    if n >= 9:
+        x[3] = 0.0
+        x[5] = -0.0
+    xd, dyd = x.cuda(), dy.cuda()
+    y = torch.full_like(xd, float("nan"))
+    dx = torch.full_like(xd, float("nan"))
+    sn.sn_relu_fwd(xd, y)
+    sn.sn_relu_bwd(xd, dyd, dx)
+    dx2 = torch.full_like(xd, float("nan"))
+    sn.sn_relu_bwd(y, dyd, dx2)              # gating on the output is the same gate
+    torch.cuda.synchronize()
+    assert np.array_equal(f64(y), oracle.relu_fwd(f64(x)))
+    want = oracle.relu_bwd(f64(x), f64(dy))
+    assert np.array_equal(f64(dx), want)
+    assert np.array_equal(f64(dx2), want)
+    if n:
+        z = xd.clone()
+        sn.sn_relu_fwd(z, z)                 # in place
+        torch.cuda.synchronize()
+        assert torch.equal(z, y)
+
+
+BN_SHAPES = [(2, 3, 5, 7), (4, 16, 14, 14), (3, 8, 7, 7), (2, 5, 35, 35), (8, 64, 56, 56), (2, 4, 224, 224),
+             (1, 1, 1, 1), (1, 3, 1, 1), (2, 2, 1, 1), (1, 2, 1, 3), (64, 32, 7, 7), (2, 130, 9, 9)]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", BN_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_bn(shape, dtype):
+    N, C, H, W = shape
+    seed = N * 1000 + C * 10 + H
+    # a mean well away from 0 and a different scale per channel
+    x = wl.activation(shape, "f32", seed, scale=1.0)
+    x = (x * torch.linspace(0.5, 3.0, C).view(1, C, 1, 1) + torch.linspace(-2.0, 5.0, C).view(1, C, 1, 1))
+    x = x.to(DT[dtype])
+    dy = wl.activation(shape, dtype, seed + 1)
+    gamma, beta = wl.bn_params(C, seed)
+    eps = 1e-5
+    xd, dyd, gd, bd = x.cuda(), dy.cuda(), gamma.cuda(), beta.cuda()
+    y = torch.full_like(xd, float("nan"))
+    mean = torch.empty(C, device="cuda")
+    invstd = torch.empty(C, device="cuda")
+    sn.sn_bn_fwd(xd, gd, bd, y, mean, invstd, eps)
+    dx = torch.full_like(xd, float("nan"))
+    dgamma = torch.empty(C, device="cuda")
+    dbeta = torch.empty(C, device="cuda")
+    sn.sn_bn_bwd(xd, dyd, gd, mean, invstd, dx, dgamma, dbeta)
+    # a replay must reproduce the first run bit for bit
+    y2 = torch.empty_like(y)
+    mean2, invstd2 = torch.empty_like(mean), torch.empty_like(invstd)
+    sn.sn_bn_fwd(xd, gd, bd, y2, mean2, invstd2, eps)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2) and torch.equal(mean, mean2) and torch.equal(invstd, invstd2)
+
+    yo, mo, io = oracle.bn_fwd(f64(x), f64(gamma), f64(beta), eps)
+    tol = TOL[dtype]
+    assert rel_l2(f64(mean), mo) <= 1e-5
+    assert rel_l2(f64(invstd), io) <= 1e-5
+    assert rel_l2(f64(y), yo) <= tol
+    # backward from the statistics the GPU saved (what the API consumes)
+    dxo, dgo, dbo = oracle.bn_bwd(f64(x), f64(dy), f64(gamma), f64(mean), f64(invstd))
+    assert rel_l2(f64(dgamma), dgo) <= 1e-5
+    assert rel_l2(f64(dbeta), dbo) <= 1e-5
+    # dx is a difference of nearly equal terms when M is tiny (it is exactly 0 for M = 1)
+    if N * H * W > 1:
+        assert rel_l2(f64(dx), dxo) <= tol
+    else:
+        assert float(dx.float().abs().max()) <= 1e-5
+
+
+POOL_CASES = [((2, 16, 16, 16), (2, 2), (2, 2), (0, 0)), ((2, 8, 55, 55), (3, 3), (2, 2), (0, 0)),
+              ((3, 5, 13, 13), (3, 3), (2, 2), (0, 0)), ((2, 6, 35, 35), (3, 3), (2, 2), (0, 0)),
+              ((2, 4, 17, 17), (3, 3), (2, 2), (0, 0)), ((1, 3, 9, 12), (3, 3), (2, 2), (1, 1)),
+              ((2, 3, 7, 10), (3, 2), (1, 2), (1, 0)), ((1, 1, 1, 1), (1, 1), (1, 1), (0, 0)),
+              ((2, 4, 224, 224), (2, 2), (2, 2), (0, 0)), ((2, 3, 15, 15), (2, 2), (2, 2), (0, 0)),
+              ((1, 2, 8, 8), (3, 3), (1, 1), (1, 1))]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", POOL_CASES, ids=lambda c: "x".join(map(str, c[0])) + "_k%d%d_s%d%d_p%d%d" % (c[1] + c[2] + c[3]))
+def test_maxpool(case, dtype):
+    shape, kernel, stride, pad = case
+    N, C, H, W = shape
+    # after a ReLU, coarsely quantised: all-zero windows and equal maxima are common
+    x = wl.activation(shape, "f32", seed=H * 31 + W, relu=True)
+    x = (torch.round(x * 4.0) / 4.0).to(DT[dtype])
+    yo, io = oracle.maxpool_fwd(f64(x), kernel, stride, pad)
+    P, Q = yo.shape[2:]
+    dy = wl.activation((N, C, P, Q), dtype, seed=H * 31 + W + 1)
+    xd, dyd = x.cuda(), dy.cuda()
+    y = torch.full((N, C, P, Q), float("nan"), dtype=DT[dtype], device="cuda")
+    idx = torch.full((N, C, P, Q), -7, dtype=torch.int32, device="cuda")
+    sn.sn_maxpool_fwd(xd, y, idx, kernel, stride, pad)
+    dx = torch.full_like(xd, float("nan"))
+    sn.sn_maxpool_bwd(dyd, idx, dx, kernel, stride, pad)
+    torch.cuda.synchronize()
+    assert np.array_equal(idx.cpu().numpy(), io)           # bit-exact, ties included
+    assert np.array_equal(f64(y), yo)
+    dxo = oracle.maxpool_bwd(f64(dy), io, shape)
+    if kernel[0] <= stride[0] and kernel[1] <= stride[1]:
+        assert np.array_equal(f64(dx), dxo)                # no overlap: pure routing
+    else:
+        assert rel_l2(f64(dx), dxo) <= TOL[dtype]
