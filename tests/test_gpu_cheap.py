@@ -87,11 +87,13 @@ def test_bn(shape, dtype):
     dxo, dgo, dbo = oracle.bn_bwd(f64(x), f64(dy), f64(gamma), f64(mean), f64(invstd))
     assert rel_l2(f64(dgamma), dgo) <= 1e-5
     assert rel_l2(f64(dbeta), dbo) <= 1e-5
-    # dx is a difference of nearly equal terms when M is tiny (it is exactly 0 for M = 1)
-    if N * H * W > 1:
+    if N * H * W > 4:
         assert rel_l2(f64(dx), dxo) <= tol
     else:
-        assert float(dx.float().abs().max()) <= 1e-5
+        # with a handful of elements per channel dx is a difference of nearly equal terms
+        # (exactly 0 for M = 1), so the error is measured against the size of those terms
+        terms = f64(gamma).reshape(1, C, 1, 1) * f64(invstd).reshape(1, C, 1, 1) * f64(dy)
+        assert np.linalg.norm(f64(dx) - dxo) <= tol * np.linalg.norm(terms)
 
 
 POOL_CASES = [((2, 16, 16, 16), (2, 2), (2, 2), (0, 0)), ((2, 8, 55, 55), (3, 3), (2, 2), (0, 0)),
