@@ -1,0 +1,304 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X.
+
+One step = one pass of the whole hot path over one batch of a synthetic,
+network-shaped workload (default: the VGG-16-shaped configuration, N = 32, bf16
+in / fp32 accumulate): for every conv layer, CONV forward, BN forward, ReLU
+forward and max-pool forward (the layers recomputation replays), then their
+backward passes, CONV backward-data and CONV backward-filter, each CONV planned
+under the given workspace budget.  Inputs are resident in HBM before the timed
+region; autotuning happens before it too.
+
+Prints ONE JSON line: conv fwd+bwd TFLOP/s over the whole step time, the roofline
+of the dominant kernel class (timed with events on the launch stream inside the
+timed region), and the CPU oracle timed on a bounded sample as a baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK = {"bf16_mfma_tflops": 2500.0, "f32_mfma_tflops": 157.3, "hbm_gbs": 8000.0}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", type=int, default=3, help="configuration number 1..5 (3 = VGG-16 N=32)")
+    ap.add_argument("--budget-mib", type=float, default=None, help="workspace budget; default: the largest listed")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-autotune", action="store_true")
+    ap.add_argument("--detail", default=None, help="write the per-layer table to this JSON file")
+    return ap.parse_args()
+
+
+class Op:
+    """One call of the step with its algorithmic work, timed with a pair of events."""
+
+    def __init__(self, key, layer, fn, flops=0.0, nbytes=0.0, nominal=0.0):
+        self.key, self.layer, self.fn = key, layer, fn
+        self.flops, self.nbytes, self.nominal = flops, nbytes, nominal
+        self.ms = []
+        self.ev = None
+
+
+def build_ops(cfg_no, budget, autotune):
+    import torch
+
+    import paper_1801_04380_amd as sn
+    from paper_1801_04380_amd import workloads as wl
+
+    cfg = wl.CONFIGS[cfg_no]
+    N, dtype = cfg["N"], cfg["dtype"]
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    code = sn.SN_BF16 if dtype == "bf16" else sn.SN_F32
+    b = 2 if dtype == "bf16" else 4
+    dev = "cuda"
+    ws = torch.empty(max(budget, 256), dtype=torch.uint8, device=dev) if budget else None
+    fwd_ops, bwd_ops, plans = [], [], {}
+    tune_ms = 0.0
+    for li, layer in enumerate(cfg["layers"]):
+        x, w, _ = wl.conv_inputs(layer, N, dtype, wl.layer_seed(cfg_no, li))
+        P, Q = wl.out_hw(layer)
+        K, C = layer.K, layer.C
+        shape = sn.conv_shape(N, C, layer.H, layer.W, K, layer.R, layer.S, layer.stride, layer.pad, code, code)
+        xd, wd = x.to(dev), w.to(dev)
+        del x, w
+        y = torch.empty((N, K, P, Q), dtype=tdt, device=dev)
+        dy = torch.empty_like(y)
+        dx = torch.empty_like(xd)
+        dw = torch.empty((K, C, layer.R, layer.S), dtype=torch.float32, device=dev)
+        nominal, algo_flops = wl.conv_flops(layer, N)
+        ex, ew, ey = xd.numel(), wd.numel(), y.numel()
+
+        def conv_call(direction, a, bb, out, shape=shape):
+            fn = {0: sn.sn_conv2d_fwd, 1: sn.sn_conv2d_bwd_data, 2: sn.sn_conv2d_bwd_filter}[direction]
+            return lambda: fn(a, bb, out, shape, sn.SN_ALGO_AUTO, ws)
+
+        # the gradient that reaches the conv comes from the cheap layers' backward below;
+        # fill it once so the autotune runs on real values
+        dy.copy_(wl.activation((N, K, P, Q), dtype, wl.layer_seed(cfg_no, li) + 7).to(dev))
+        if autotune:
+            t0 = time.time()
+            for d, (a, bb, out) in {0: (xd, wd, y), 1: (dy, wd, dx), 2: (xd, dy, dw)}.items():
+                sn.sn_conv_autotune(d, a, bb, out, shape, ws, iters=2)
+            torch.cuda.synchronize()
+            tune_ms += (time.time() - t0) * 1e3
+        for d in (0, 1, 2):
+            algo, used, ms = sn.sn_conv_plan(shape, d, budget)
+            plans[(layer.name, d)] = (sn.ALGO_NAMES[algo], used, ms)
+        names = {0: "conv_fwd", 1: "conv_bwd_data", 2: "conv_bwd_filter"}
+        byts = {0: (ex + ew) * b + ey * b, 1: (ey + ew) * b + ex * b, 2: (ex + ey) * b + ew * 4}
+        for _ in range(layer.mult):
+            fwd_ops.append(Op(names[0], layer.name, conv_call(0, xd, wd, y), algo_flops, byts[0], nominal))
+        cheap_f, cheap_b = [], []
+        act_in = y
+        E = y.numel()
+        if cfg["bn"]:
+            gamma, beta = (t.to(dev) for t in wl.bn_params(K, wl.layer_seed(cfg_no, li)))
+            ybn = torch.empty_like(y)
+            mean, invstd = torch.empty(K, device=dev), torch.empty(K, device=dev)
+            dgamma, dbeta = torch.empty(K, device=dev), torch.empty(K, device=dev)
+            g_bn = torch.empty_like(y)
+            cheap_f.append(Op("bn_fwd", layer.name,
+                              lambda y=y, ga=gamma, be=beta, o=ybn, m=mean, i=invstd: sn.sn_bn_fwd(y, ga, be, o, m, i),
+                              nbytes=2 * E * b))
+            act_in = ybn
+        a = torch.empty_like(y)
+        cheap_f.append(Op("relu_fwd", layer.name, lambda s=act_in, o=a: sn.sn_relu_fwd(s, o), nbytes=2 * E * b))
+        g_a = torch.empty_like(y)
+        if layer.pool:
+            kernel, stride = layer.pool
+            PP, QQ = sn.sn_out_dim(P, 0, kernel[0], stride[0]), sn.sn_out_dim(Q, 0, kernel[1], stride[1])
+            pooled = torch.empty((N, K, PP, QQ), dtype=tdt, device=dev)
+            idx = torch.empty((N, K, PP, QQ), dtype=torch.int32, device=dev)
+            g_pool = wl.activation((N, K, PP, QQ), dtype, wl.layer_seed(cfg_no, li) + 9).to(dev)
+            Eo = pooled.numel()
+            cheap_f.append(Op("maxpool_fwd", layer.name,
+                              lambda s=a, o=pooled, i=idx, k=kernel, st=stride: sn.sn_maxpool_fwd(s, o, i, k, st),
+                              nbytes=E * b + Eo * (b + 4)))
+            cheap_b.append(Op("maxpool_bwd", layer.name,
+                              lambda g=g_pool, i=idx, o=g_a, k=kernel, st=stride: sn.sn_maxpool_bwd(g, i, o, k, st),
+                              nbytes=Eo * (b + 4) + E * b))
+        else:
+            g_a.copy_(dy)
+        relu_grad_out = g_bn if cfg["bn"] else dy
+        cheap_b.append(Op("relu_bwd", layer.name, lambda s=a, g=g_a, o=relu_grad_out: sn.sn_relu_bwd(s, g, o),
+                          nbytes=3 * E * b))
+        if cfg["bn"]:
+            cheap_b.append(Op("bn_bwd", layer.name,
+                              lambda y=y, g=g_bn, ga=gamma, m=mean, i=invstd, o=dy, dg=dgamma, db=dbeta:
+                              sn.sn_bn_bwd(y, g, ga, m, i, o, dg, db), nbytes=3 * E * b))
+        for _ in range(layer.mult):
+            fwd_ops.extend(cheap_f)
+        layer_bwd = []
+        for _ in range(layer.mult):
+            layer_bwd.extend(cheap_b)
+            if not layer.first:  # the gradient of the image is not needed in training
+                layer_bwd.append(Op(names[1], layer.name, conv_call(1, dy, wd, dx), algo_flops, byts[1], nominal))
+            layer_bwd.append(Op(names[2], layer.name, conv_call(2, xd, dy, dw), algo_flops, byts[2], nominal))
+        bwd_ops = layer_bwd + bwd_ops  # backward visits the layers in reverse
+    return cfg, fwd_ops + bwd_ops, plans, tune_ms
+
+
+def cpu_baseline(cfg_no):
+    """The fp64 oracle, as it stands, on a bounded sample: the most expensive layer of the
+    workload at a reduced batch (conv cost is linear in N), all three directions."""
+    import oracle
+    from paper_1801_04380_amd import workloads as wl
+
+    cfg = wl.CONFIGS[cfg_no]
+    layer = max(cfg["layers"], key=lambda l: wl.conv_flops(l, 1)[0])
+    per_img = wl.conv_flops(layer, 1)[0]
+    n = int(max(1, min(cfg["N"], round(200e9 / (3 * per_img)))))
+    x, w, dy = wl.conv_inputs(layer, n, cfg["dtype"], 1)
+    xo, wo, dyo = (t.double().numpy() for t in (x, w, dy))
+    oracle.conv2d_fwd(xo[:1, :, :8, :8].copy(), wo, layer.stride, layer.pad)  # load the library
+    t0 = time.time()
+    oracle.conv2d_fwd(xo, wo, layer.stride, layer.pad)
+    oracle.conv2d_bwd_data(dyo, wo, xo.shape, layer.stride, layer.pad)
+    oracle.conv2d_bwd_filter(xo, dyo, wo.shape, layer.stride, layer.pad)
+    dt = time.time() - t0
+    flops = 3 * wl.conv_flops(layer, n)[1]
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "%s %s (C=%d K=%d %dx%d, %dx%d filter) at N=%d of %d, fwd+bwd-data+bwd-filter, fp64, %.1f s"
+                      % (cfg["name"], layer.name, layer.C, layer.K, layer.H, layer.W, layer.R, layer.S, n,
+                         cfg["N"], dt)}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    import paper_1801_04380_amd as sn
+    from paper_1801_04380_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    cfg = wl.CONFIGS[args.workload]
+    budgets = [b for b in cfg["budgets"] if b]
+    if args.budget_mib is not None:
+        budget = int(args.budget_mib * (1 << 20))
+    else:
+        budget = max(budgets) if budgets else 64 << 20
+    cfg, ops, plans, tune_ms = build_ops(args.workload, budget, not args.no_autotune)
+    stream = torch.cuda.current_stream()
+
+    def step(timed):
+        for op in ops:
+            if timed:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                op.fn()
+                e1.record(stream)
+                op.ev = (op.ev or []) + [(e0, e1)]
+            else:
+                op.fn()
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # an Op object appears once per occurrence in the step; shared objects (mult > 1) hold all their events
+    seen, by_key = set(), {}
+    for op in ops:
+        if id(op) in seen:
+            continue
+        seen.add(id(op))
+        times = [a.elapsed_time(bb) for a, bb in op.ev]
+        k = by_key.setdefault(op.key, dict(ms=0.0, launches=0, flops=0.0, nbytes=0.0, nominal=0.0, layers={}))
+        k["ms"] += sum(times)
+        k["launches"] += len(times)
+        k["flops"] += op.flops * len(times)
+        k["nominal"] += op.nominal * len(times)
+        k["nbytes"] += op.nbytes * len(times)
+        lay = k["layers"].setdefault(op.layer, dict(ms=0.0, launches=0, flops=op.flops, nbytes=op.nbytes))
+        lay["ms"] += sum(times)
+        lay["launches"] += len(times)
+    conv_keys = [k for k in by_key if k.startswith("conv_")]
+    conv_flops_step = sum(by_key[k]["flops"] for k in conv_keys) / args.steps
+    conv_ms_step = sum(by_key[k]["ms"] for k in conv_keys) / args.steps
+    cheap_keys = [k for k in by_key if not k.startswith("conv_")]
+    cheap_bytes_step = sum(by_key[k]["nbytes"] for k in cheap_keys) / args.steps
+    cheap_ms_step = sum(by_key[k]["ms"] for k in cheap_keys) / args.steps
+    replay_keys = [k for k in cheap_keys if k.endswith("_fwd")]
+    replay_gbs = (sum(by_key[k]["nbytes"] for k in replay_keys) / max(sum(by_key[k]["ms"] for k in replay_keys), 1e-9)
+                  / 1e6)
+    value = conv_flops_step / (wall_ms * 1e-3) / 1e12
+
+    dom = max(by_key, key=lambda k: by_key[k]["ms"])
+    d = by_key[dom]
+    avg_ms = d["ms"] / d["launches"]
+    if dom.startswith("conv_"):
+        peak = PEAK["bf16_mfma_tflops"] if cfg["dtype"] == "bf16" else PEAK["f32_mfma_tflops"]
+        achieved = d["flops"] / d["launches"] / (avg_ms * 1e-3) / 1e12
+        roof = {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+                "traffic": None}
+    else:
+        achieved = d["nbytes"] / d["launches"] / (avg_ms * 1e-3) / 1e9
+        roof = {"bound": "hbm", "achieved": achieved, "peak": PEAK["hbm_gbs"], "unit": "GB/s",
+                "frac": achieved / PEAK["hbm_gbs"], "traffic": None}
+    roof.update({"kernel": dom, "launches_per_step": d["launches"] / args.steps, "avg_launch_ms": avg_ms})
+
+    breakdown = {}
+    for k, v in sorted(by_key.items()):
+        e = {"ms_per_step": v["ms"] / args.steps}
+        if v["flops"]:
+            e["tflops"] = v["flops"] / (v["ms"] * 1e-3) / 1e12
+            e["frac_mfma_peak"] = e["tflops"] / (PEAK["bf16_mfma_tflops"] if cfg["dtype"] == "bf16"
+                                                 else PEAK["f32_mfma_tflops"])
+        else:
+            e["gbs"] = v["nbytes"] / (v["ms"] * 1e-3) / 1e9
+            e["frac_hbm_peak"] = e["gbs"] / PEAK["hbm_gbs"]
+        breakdown[k] = e
+
+    out = {
+        "metric": "conv fwd+bwd TFLOP/s (% MFMA peak) per workspace budget; recompute GB/s",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg["dtype"], "data": "synthetic",
+        "config": {"workload": cfg["name"], "batch": cfg["N"], "workspace_budget_bytes": budget,
+                   "layers": len(cfg["layers"]), "ops_per_step": len(ops)},
+        "conv_only_tflops": conv_flops_step / (conv_ms_step * 1e-3) / 1e12,
+        "conv_frac_mfma_peak": conv_flops_step / (conv_ms_step * 1e-3) / 1e12
+        / (PEAK["bf16_mfma_tflops"] if cfg["dtype"] == "bf16" else PEAK["f32_mfma_tflops"]),
+        "recompute_gbs": replay_gbs, "cheap_layers_gbs": cheap_bytes_step / (cheap_ms_step * 1e-3) / 1e9,
+        "autotune_ms": tune_ms,
+        "roofline": roof, "breakdown": breakdown,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.workload)
+    if args.detail:
+        detail = {"plans": {"%s/%d" % k: v for k, v in plans.items()},
+                  "layers": {k: v["layers"] for k, v in by_key.items()}}
+        for k, v in detail["layers"].items():
+            for name, lay in v.items():
+                t = lay["ms"] / lay["launches"]
+                lay["avg_ms"] = t
+                if lay["flops"]:
+                    lay["tflops"] = lay["flops"] / (t * 1e-3) / 1e12
+                lay["gbs"] = lay["nbytes"] / (t * 1e-3) / 1e9
+        os.makedirs(os.path.dirname(os.path.abspath(args.detail)), exist_ok=True)
+        with open(args.detail, "w") as f:
+            json.dump(detail, f, indent=1)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
