@@ -120,7 +120,9 @@ sn_status query(const ConvGeom &g, sn_conv_dir dir, sn_conv_algo algo, size_t *m
             *min_b = *pref_b = staged_bwd_filter_bytes(g, nullptr);
             return SN_OK;
         }
-        return SN_ERR_UNSUPPORTED;
+        if (!tile_conv_supported(g, dir == SN_CONV_BWD_DATA)) return SN_ERR_UNSUPPORTED;
+        *min_b = *pref_b = tile_conv_packed_bytes(g, dir == SN_CONV_BWD_DATA);
+        return SN_OK;
     default:
         return SN_ERR_BAD_ARG;
     }
@@ -210,10 +212,25 @@ int im2col_chunk(const ConvGeom &g, const Im2colPlan &p, size_t ws_bytes)
 
 size_t out_elem(const ConvGeom &g) { return g.out_bf16 ? 2 : 4; }
 
+// Zero-workspace implicit GEMM: the stride-1 bf16 tile kernel where it applies,
+// the general kernel otherwise.
+hipError_t direct_fwd(const void *x, const void *w, void *y, const ConvGeom &g, hipStream_t st)
+{
+    if (tile_conv_supported(g, false)) return launch_tile_conv(x, w, y, g, false, nullptr, st);
+    return launch_generic_fwd(x, w, y, g, st);
+}
+
+hipError_t direct_bwd_data(const void *dy, const void *w, void *dx, const ConvGeom &g, hipStream_t st)
+{
+    if (tile_conv_supported(g, true)) return launch_tile_conv(dy, w, dx, g, true, nullptr, st);
+    return launch_generic_bwd_data(dy, w, dx, g, st);
+}
+
 sn_status run_fwd(const void *x, const void *w, void *y, const ConvGeom &g, sn_conv_algo algo, void *ws,
                   size_t ws_bytes, hipStream_t st)
 {
-    if (algo == SN_ALGO_DIRECT) return launch_status(launch_generic_fwd(x, w, y, g, st));
+    if (algo == SN_ALGO_DIRECT) return launch_status(direct_fwd(x, w, y, g, st));
+    if (algo == SN_ALGO_STAGED) return launch_status(launch_tile_conv(x, w, y, g, false, ws, st));
     if (algo == SN_ALGO_IM2COL_GEMM) {
         const Im2colPlan p = im2col_plan(g, SN_CONV_FWD);
         const int chunk = im2col_chunk(g, p, ws_bytes);
@@ -222,7 +239,7 @@ sn_status run_fwd(const void *x, const void *w, void *y, const ConvGeom &g, sn_c
             hipError_t e = launch_im2col(x, ws, g, n0, nimg, st);
             if (e != hipSuccess) return SN_ERR_LAUNCH;
             char *yo = static_cast<char *>(y) + (size_t)n0 * g.K * g.P * g.Q * out_elem(g);
-            e = launch_generic_fwd(ws, w, yo, gemm_geom_1x1(g, nimg), st);
+            e = direct_fwd(ws, w, yo, gemm_geom_1x1(g, nimg), st);
             if (e != hipSuccess) return SN_ERR_LAUNCH;
         }
         return SN_OK;
@@ -233,7 +250,8 @@ sn_status run_fwd(const void *x, const void *w, void *y, const ConvGeom &g, sn_c
 sn_status run_bwd_data(const void *dy, const void *w, void *dx, const ConvGeom &g, sn_conv_algo algo, void *ws,
                        size_t ws_bytes, hipStream_t st)
 {
-    if (algo == SN_ALGO_DIRECT) return launch_status(launch_generic_bwd_data(dy, w, dx, g, st));
+    if (algo == SN_ALGO_DIRECT) return launch_status(direct_bwd_data(dy, w, dx, g, st));
+    if (algo == SN_ALGO_STAGED) return launch_status(launch_tile_conv(dy, w, dx, g, true, ws, st));
     if (algo == SN_ALGO_IM2COL_GEMM) {
         const Im2colPlan p = im2col_plan(g, SN_CONV_BWD_DATA);
         const int chunk = im2col_chunk(g, p, ws_bytes);
@@ -242,7 +260,7 @@ sn_status run_bwd_data(const void *dy, const void *w, void *dx, const ConvGeom &
             ConvGeom u = gemm_geom_1x1(g, nimg);
             u.out_bf16 = 0;  // the column gradient stays fp32 until it is folded
             const char *dyo = static_cast<const char *>(dy) + (size_t)n0 * g.K * g.P * g.Q * in_elem(g);
-            hipError_t e = launch_generic_bwd_data(dyo, w, ws, u, st);
+            hipError_t e = direct_bwd_data(dyo, w, ws, u, st);
             if (e != hipSuccess) return SN_ERR_LAUNCH;
             e = launch_col2im(static_cast<const float *>(ws), dx, g, n0, nimg, st);
             if (e != hipSuccess) return SN_ERR_LAUNCH;

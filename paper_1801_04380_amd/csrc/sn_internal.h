@@ -48,6 +48,14 @@ hipError_t launch_generic_bwd_filter(const void *x, const void *dy, float *dw, c
                                      int splits, float *partial, bool accumulate, hipStream_t st);
 int generic_bwd_filter_splits(const ConvGeom &g);
 
+// Stride-1 bf16 fast path (forward, or backward-data when bwd_data is set).
+// `packed` = workspace for the re-laid-out filter (tile_conv_packed_bytes), or
+// nullptr to gather the filter from the KCRS tensor inside the kernel.
+bool tile_conv_supported(const ConvGeom &g, bool bwd_data);
+size_t tile_conv_packed_bytes(const ConvGeom &g, bool bwd_data);
+hipError_t launch_tile_conv(const void *in, const void *w, void *out, const ConvGeom &g, bool bwd_data,
+                            void *packed, hipStream_t st);
+
 hipError_t launch_fill_zero(float *p, size_t n, hipStream_t st);
 // dw[i] = (accumulate ? dw[i] : 0) + sum_z partial[z][i], z ascending.
 hipError_t launch_reduce_partials(const float *partial, float *dw, size_t n, int splits, bool accumulate,

@@ -36,6 +36,10 @@ CASES = [
     (L("big_pad", 4, 5, 5, 6, 3, 3, (1, 1), (2, 2)), 2),
     (L("stride_gt_filter", 8, 16, 16, 8, 2, 2, (3, 3), (0, 0)), 2),
     (L("deep_c", 512, 7, 7, 64, 3, 3, (1, 1), (1, 1)), 2),
+    (L("wide", 20, 19, 100, 72, 3, 3, (1, 1), (1, 1)), 2),            # column tiles, ragged last tile
+    (L("wide_k64", 16, 37, 70, 64, 3, 3, (1, 1), (1, 1)), 1),
+    (L("small_imgs", 32, 7, 7, 96, 3, 3, (1, 1), (1, 1)), 9),         # one tile spans several images
+    (L("1x1_small", 40, 7, 7, 48, 1, 1), 11),
 ]
 IDS = [c[0].name for c in CASES]
 
