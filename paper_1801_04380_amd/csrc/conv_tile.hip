@@ -47,6 +47,7 @@ struct TileProblem {
     int out_bf16;
     int TH, TW, LW;          // tile rows, tile columns, LDS patch width in pixels
     int ncoltiles;
+    int tiles_per_img;       // > 0: row tiles never cross an image (used for wide images); 0: they may
     int Hp;                  // padded rows per image = Pout + R - 1
     int nchunks;             // ceil(Cin / 16)
     // filter access: A(m, red, tap) = w[m*w_sm + red*w_sr + (tflip ? T-1-tap : tap)]
@@ -84,9 +85,16 @@ conv_tile_kernel(const bf16_t *__restrict__ in, const bf16_t *__restrict__ w, vo
     // ---- tile geometry
     const int rowtile = blockIdx.x / p.ncoltiles, coltile = blockIdx.x - rowtile * p.ncoltiles;
     const int k0 = blockIdx.y * KT;
-    const int o0 = rowtile * p.TH;               // first flattened (image, row)
     const int q0 = coltile * p.TW;
-    const int NP = p.N * p.Pout;
+    int o0, NP;                                  // first flattened (image, row) and the row limit
+    if (p.tiles_per_img > 0) {
+        const int img = rowtile / p.tiles_per_img;
+        o0 = img * p.Pout + (rowtile - img * p.tiles_per_img) * p.TH;
+        NP = (img + 1) * p.Pout;
+    } else {
+        o0 = rowtile * p.TH;
+        NP = p.N * p.Pout;
+    }
     const int n0 = o0 / p.Pout, u0 = n0 * p.Hp + (o0 - n0 * p.Pout);
     const int olast = min(o0 + p.TH, NP) - 1;
     const int nl = olast / p.Pout;
@@ -302,26 +310,33 @@ bool make_plan(const TileProblem &base, int R, int S, Plan *pl)
     TileProblem p = base;
     const int KT = p.Kout <= 64 ? 64 : 128;
     const int PIXT = KT == 128 ? 256 : 512;
+    const long long NP = (long long)p.N * p.Pout;
+    long long nrowtiles;
+    int lrows_max;
     if (p.Qout <= 64) {
         p.TW = p.Qout;
         p.TH = PIXT / p.Qout;
         p.ncoltiles = 1;
+        p.tiles_per_img = 0;
+        if (p.TH > NP) p.TH = (int)NP;
+        nrowtiles = (NP + p.TH - 1) / p.TH;
+        // most patch rows a tile can need: TH rows, one halo, and one more halo per image boundary inside it
+        const int crossings = p.N > 1 ? (p.TH - 1) / p.Pout + 1 : 0;
+        lrows_max = p.TH + (crossings + 1) * (R - 1);
     } else {
         p.TW = 32;
         p.TH = PIXT / 32;
         p.ncoltiles = (p.Qout + 31) / 32;
+        if (p.TH > p.Pout) p.TH = p.Pout;
+        p.tiles_per_img = (p.Pout + p.TH - 1) / p.TH;
+        nrowtiles = (long long)p.N * p.tiles_per_img;
+        lrows_max = p.TH + R - 1;
     }
-    const long long NP = (long long)p.N * p.Pout;
-    if (p.TH > NP) p.TH = (int)NP;
     p.LW = p.TW + S - 1;
     p.Hp = p.Pout + R - 1;
-    // most patch rows a tile can need: TH rows, one halo, and one more halo per image boundary inside it
-    const int crossings = p.N > 1 ? (p.TH - 1) / p.Pout + 1 : 0;
-    const int lrows_max = p.TH + (crossings + 1) * (R - 1);
     if ((long long)lrows_max * p.LW > XPIX_MAX) return false;
     p.nchunks = (p.Cin + 15) / 16;
     p.Mpad = (p.Kout + 63) / 64 * 64;
-    const long long nrowtiles = (NP + p.TH - 1) / p.TH;
     if (nrowtiles * p.ncoltiles > 0x7fffffffLL) return false;
     pl->p = p;
     pl->KT = KT;

@@ -97,7 +97,7 @@ ConvGeom gemm_geom_1x1(const ConvGeom &g, int nimg)
 // STAGED backward-filter: fp32 partial dw per slice of the (n,p,q) sum.
 size_t staged_bwd_filter_bytes(const ConvGeom &g, int *splits_out)
 {
-    int splits = generic_bwd_filter_splits(g);
+    int splits = tile_wgrad_supported(g) ? tile_wgrad_slices(g) : generic_bwd_filter_splits(g);
     if (splits_out) *splits_out = splits;
     return align_up((size_t)splits * g.K * g.C * g.R * g.S * sizeof(float), WS_ALIGN);
 }
@@ -274,9 +274,13 @@ sn_status run_bwd_filter(const void *x, const void *dy, void *dw, const ConvGeom
                          void *ws, size_t ws_bytes, hipStream_t st)
 {
     float *dwf = static_cast<float *>(dw);
-    if (algo == SN_ALGO_DIRECT)
+    const bool tile = tile_wgrad_supported(g);
+    if (algo == SN_ALGO_DIRECT) {
+        if (tile) return launch_status(launch_tile_wgrad(x, dy, dwf, g, nullptr, st));
         return launch_status(launch_generic_bwd_filter(x, dy, dwf, g, generic_bwd_filter_splits(g), nullptr, false, st));
+    }
     if (algo == SN_ALGO_STAGED) {
+        if (tile) return launch_status(launch_tile_wgrad(x, dy, dwf, g, static_cast<float *>(ws), st));
         int splits;
         staged_bwd_filter_bytes(g, &splits);
         return launch_status(launch_generic_bwd_filter(x, dy, dwf, g, splits, static_cast<float *>(ws), false, st));

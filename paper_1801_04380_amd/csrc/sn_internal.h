@@ -56,6 +56,14 @@ size_t tile_conv_packed_bytes(const ConvGeom &g, bool bwd_data);
 hipError_t launch_tile_conv(const void *in, const void *w, void *out, const ConvGeom &g, bool bwd_data,
                             void *packed, hipStream_t st);
 
+// Stride-1 bf16 backward-filter fast path.  partial == nullptr: the slices of the
+// (n,p,q) sum combine with atomics into a zero-filled dw; otherwise slice z writes
+// partial[z][K*C*R*S] (tile_wgrad_slices of them) and a fixed-order reduction follows.
+bool tile_wgrad_supported(const ConvGeom &g);
+int tile_wgrad_slices(const ConvGeom &g);
+hipError_t launch_tile_wgrad(const void *x, const void *dy, float *dw, const ConvGeom &g, float *partial,
+                             hipStream_t st);
+
 hipError_t launch_fill_zero(float *p, size_t n, hipStream_t st);
 // dw[i] = (accumulate ? dw[i] : 0) + sum_z partial[z][i], z ascending.
 hipError_t launch_reduce_partials(const float *partial, float *dw, size_t n, int splits, bool accumulate,
