@@ -147,42 +147,74 @@ conv_wgrad_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[a][b][t][v] = 0.f;
 
-    // staging items per thread: dy octets KTB*NSG, x octets CTB*xrows*NGX
+    // staging items per thread: dy octets KTB*NSG, x octets CTB*xrows*NGX.  What depends on the
+    // item only is worked out once (integer division by run-time values is slow): the LDS offset,
+    // the row and column octet inside the chunk (packed), and the global offset inside the image.
     constexpr int YIT = (KTB * (PIXC_MAX / 8) + 255) / 256;
     constexpr int XIT_MAX = 10;
     uint4 yreg[YIT], xreg[XIT_MAX];
     const int ny = KTB * NSG, nx = CTB * p.xrows * NGX;
     const int xper = p.xrows * NGX;
+    int ydesc[YIT], ygoff[YIT], xdesc[XIT_MAX], xgoff[XIT_MAX];   // desc = ldsoff | row << 16 | octet << 24 | zero-fill << 30; -1: no item
+#pragma unroll
+    for (int it = 0; it < YIT; ++it) {
+        const int e = it * 256 + tid;
+        ydesc[it] = -1;
+        ygoff[it] = 0;
+        if (e < ny) {
+            const int kl = e / NSG, sg = e - kl * NSG;
+            const int rl = sg / OPR, oc = sg - rl * OPR;
+            if (k0 + kl < p.K) {
+                ydesc[it] = (kl * p.AP + sg * 8) | (rl << 16) | (oc << 24);
+                ygoff[it] = (k0 + kl) * PQ + rl * p.Q;
+            } else {
+                ydesc[it] = (kl * p.AP + sg * 8) | (1 << 30);   // k beyond K: zero fill
+            }
+        }
+    }
+#pragma unroll
+    for (int it = 0; it < XIT_MAX; ++it) {
+        const int e = it * 256 + tid;
+        xdesc[it] = -1;
+        xgoff[it] = 0;
+        if (e < nx) {
+            const int cl = e / xper, r2 = e - cl * xper;
+            const int row = r2 / NGX, og = r2 - row * NGX;
+            if (c0 + cl < p.C) {
+                xdesc[it] = (cl * p.CP + r2 * 8) | (row << 16) | (og << 24);
+                xgoff[it] = (c0 + cl) * HW + row * p.W;
+            } else {
+                xdesc[it] = (cl * p.CP + r2 * 8) | (1 << 30);   // c beyond C: zero fill
+            }
+        }
+    }
 
     auto prefetch = [&](int chunk) {
         const int img = chunk / (p.rowchunks * p.ncoltiles);
         const int rem = chunk - img * (p.rowchunks * p.ncoltiles);
         const int rc = rem / p.ncoltiles, ct = rem - rc * p.ncoltiles;
         const int p0 = rc * p.TH, q0 = ct * p.TWP;
+        const bf16_t *ybase = dy + (size_t)img * p.K * PQ + (size_t)p0 * p.Q;
+        const int h0 = p0 + r0 - p.ph;
+        const bf16_t *xbase = x + (size_t)img * p.C * HW + (ptrdiff_t)h0 * p.W;
 #pragma unroll
         for (int it = 0; it < YIT; ++it) {
-            const int e = it * 256 + tid;
             uint4 v = make_uint4(0, 0, 0, 0);
-            if (e < ny) {
-                const int kl = e / NSG, sg = e - kl * NSG;
-                const int rl = sg / OPR, col = (sg - rl * OPR) * 8;
-                const int k = k0 + kl, pp = p0 + rl;
-                if (k < p.K && pp < p.P)
-                    v = load_row8(dy + ((size_t)(img * p.K + k) * p.P + pp) * p.Q, q0 + col, p.Q);
+            const int d = ydesc[it];
+            if (d >= 0 && !(d >> 30)) {
+                const int rl = (d >> 16) & 0xff, oc = d >> 24;
+                if (p0 + rl < p.P) v = load_row8(ybase + ygoff[it], q0 + oc * 8, p.Q);
             }
             yreg[it] = v;
         }
 #pragma unroll
         for (int it = 0; it < XIT_MAX; ++it) {
-            const int e = it * 256 + tid;
             if (it * 256 >= nx) break;
             uint4 v = make_uint4(0, 0, 0, 0);
-            if (e < nx) {
-                const int cl = e / xper, r2 = e - cl * xper;
-                const int row = r2 / NGX, og = r2 - row * NGX;
-                const int c = c0 + cl, h = p0 + row + r0 - p.ph;
-                if (c < p.C && (unsigned)h < (unsigned)p.H)
-                    v = load_row8(x + ((size_t)(img * p.C + c) * p.H + h) * p.W, q0 - p.apr + og * 8, p.W);
+            const int d = xdesc[it];
+            if (d >= 0 && !(d >> 30)) {
+                const int row = (d >> 16) & 0xff, og = d >> 24;
+                if ((unsigned)(h0 + row) < (unsigned)p.H) v = load_row8(xbase + xgoff[it], q0 - p.apr + og * 8, p.W);
             }
             xreg[it] = v;
         }
@@ -191,21 +223,12 @@ conv_wgrad_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
     auto stage_store = [&](int buf) {
         bf16_t *ys = smem + buf * bufstride, *xs = ys + YS_MAX;
 #pragma unroll
-        for (int it = 0; it < YIT; ++it) {
-            const int e = it * 256 + tid;
-            if (e < ny) {
-                const int kl = e / NSG, sg = e - kl * NSG;
-                *reinterpret_cast<uint4 *>(ys + kl * p.AP + sg * 8) = yreg[it];
-            }
-        }
+        for (int it = 0; it < YIT; ++it)
+            if (ydesc[it] >= 0) *reinterpret_cast<uint4 *>(ys + (ydesc[it] & 0xffff)) = yreg[it];
 #pragma unroll
         for (int it = 0; it < XIT_MAX; ++it) {
-            const int e = it * 256 + tid;
             if (it * 256 >= nx) break;
-            if (e < nx) {
-                const int cl = e / xper, r2 = e - cl * xper;
-                *reinterpret_cast<uint4 *>(xs + cl * p.CP + r2 * 8) = xreg[it];
-            }
+            if (xdesc[it] >= 0) *reinterpret_cast<uint4 *>(xs + (xdesc[it] & 0xffff)) = xreg[it];
         }
     };
 
