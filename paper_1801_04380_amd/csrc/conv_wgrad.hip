@@ -19,16 +19,20 @@
 //                    its aligned 8 pixels plus the neighbours it needs and builds
 //                    each shifted operand with funnel shifts (v_alignbit).
 // Row pitches are padded to an odd number of 16-byte units (conflict-free reads
-// for 16 consecutive k or c).  Global loads are 16 bytes wide wherever the 8
-// pixels lie inside the image row (whatever their alignment) and element-wise at
-// the row ends.  The (n,p,q) sum is split over gridDim.z slices; a slice either
+// for 16 consecutive k or c).  Global loads are 16 bytes wide whatever their
+// alignment.  The (n,p,q) sum is split over gridDim.z slices; a slice either
 // adds its result into a zeroed dw with fp32 atomics (no workspace) or writes
-// partial[slice], which is then reduced in slice order.
+// partial[slice], which is then reduced in slice order.  Either way the
+// accumulators go through LDS first so that global accesses are coalesced.
 //
 // One workgroup per CU (the 9 accumulator tiles plus the staging registers need
 // more than 256 registers per lane), so the overlap is inside the workgroup: LDS
 // is double buffered, the global loads of chunk i+1 fly during the MFMAs of chunk
-// i and are written to the other buffer half way through them; one barrier per chunk.
+// i and are written to the other buffer half way through them; one barrier per
+// chunk.  With a single wave per SIMD every non-MFMA instruction costs issue
+// time, so everything that depends only on the thread is worked out once.
+#include <cstdlib>
+
 #include "sn_internal.h"
 
 namespace sn {
@@ -47,8 +51,12 @@ struct WgradProblem {
     int nsteps;                  // TH*TWP/16
     int ncoltiles, rowchunks;    // per image
     int nchunks, cps;            // total chunks, chunks per slice
-    int nrg;                     // tap-row groups (R / RG), folded into blockIdx.y
     int ctiles;                  // c tiles
+    // how the valid columns of a staged octet are found:
+    //  0: a chunk spans the whole image width, the mask is fixed per thread
+    //  1: column tiles and W a multiple of 8: an octet is wholly inside or outside the row
+    //  2: column tiles and ragged W: recomputed per chunk
+    int colmode;
 };
 
 struct __attribute__((packed, aligned(2))) U16x8 { unsigned short e[8]; };
@@ -61,18 +69,34 @@ __device__ inline uint4 load8_any(const bf16_t *p)
     return o;
 }
 
-// 8 pixels starting at column v0 of a row of width W (row pointer `row`), zero outside [0,W).
-__device__ inline uint4 load_row8(const bf16_t *row, int v0, int W)
+// Bit mask of the columns v0 .. v0+7 that lie inside a row of width W.
+__device__ inline uint32_t col_mask(int v0, int W)
 {
-    if (v0 >= 0 && v0 + 8 <= W) return load8_any(row + v0);
+    const int lo = min(8, max(0, -v0)), hi = max(0, min(8, W - v0));
+    return hi > lo ? (((1u << hi) - 1u) & ~((1u << lo) - 1u)) : 0u;
+}
+
+// Reads 8 pixels element by element (only the columns in vm): for the rare window
+// that would run past the end of the tensor.
+__device__ __attribute__((noinline)) uint4 load8_tail(const bf16_t *base, unsigned off, uint32_t vm)
+{
     unsigned short e[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int v = v0 + i;
-        e[i] = (v >= 0 && v < W) ? row[v] : (unsigned short)0;
-    }
+    for (int i = 0; i < 8; ++i) e[i] = ((vm >> i) & 1u) ? base[off + i] : (unsigned short)0;
     return make_uint4(e[0] | ((uint32_t)e[1] << 16), e[2] | ((uint32_t)e[3] << 16), e[4] | ((uint32_t)e[5] << 16),
                       e[6] | ((uint32_t)e[7] << 16));
+}
+
+// Clears the columns of an octet that are not in vm.
+__device__ inline uint4 apply_mask(uint4 r, uint32_t vm)
+{
+    uint32_t *d = reinterpret_cast<uint32_t *>(&r);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t b0 = (vm >> (2 * j)) & 1u, b1 = (vm >> (2 * j + 1)) & 1u;
+        d[j] &= ((0u - b0) & 0xffffu) | ((0u - b1) & 0xffff0000u);
+    }
+    return r;
 }
 
 // Elements d .. d+7 of a window whose dwords D[0..7] hold elements -4 .. 11.
@@ -111,6 +135,11 @@ template <int S, int TC, int TM> struct TapLoop<S, TC, TM, S> {
     __device__ static inline void run(const uint32_t (&)[TC][8], const bf16x8 (&)[TM], Acc &, int) {}
 };
 
+// desc of a staged octet: LDS element offset (bits 0-15) | chunk row (16-20) | 8-bit field (21-28)
+__device__ inline int desc_lds(int d) { return d & 0xffff; }
+__device__ inline int desc_row(int d) { return (d >> 16) & 31; }
+__device__ inline int desc_f8(int d) { return (d >> 21) & 255; }
+
 template <int S, int RG, int TM, int TC>
 __global__ void __launch_bounds__(256, 1)
 conv_wgrad_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, float *__restrict__ out,
@@ -147,162 +176,247 @@ conv_wgrad_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[a][b][t][v] = 0.f;
 
-    // staging items per thread: dy octets KTB*NSG, x octets CTB*xrows*NGX.  What depends on the
-    // item only is worked out once (integer division by run-time values is slow): the LDS offset,
-    // the row and column octet inside the chunk (packed), and the global offset inside the image.
+    // ---- staging items of this thread: dy octets (KTB*NSG in all) and x octets (CTB*xrows*NGX).
+    // desc: see above; its 8-bit field is the fixed column mask (colmode 0) or the octet's column
+    // index (colmode 1, 2).  goff: element offset inside the chunk frame, -1 if the item's channel
+    // is out of range (the item then always stores zeros).
     constexpr int YIT = (KTB * (PIXC_MAX / 8) + 255) / 256;
     constexpr int XIT_MAX = 10;
     uint4 yreg[YIT], xreg[XIT_MAX];
+    uint32_t ymask[(YIT + 3) / 4], xmask[(XIT_MAX + 3) / 4];   // colmode 2: masks of the staged octets
+#pragma unroll
+    for (int i = 0; i < (YIT + 3) / 4; ++i) ymask[i] = 0;
+#pragma unroll
+    for (int i = 0; i < (XIT_MAX + 3) / 4; ++i) xmask[i] = 0;
     const int ny = KTB * NSG, nx = CTB * p.xrows * NGX;
     const int xper = p.xrows * NGX;
-    int ydesc[YIT], ygoff[YIT], xdesc[XIT_MAX], xgoff[XIT_MAX];   // desc = ldsoff | row << 16 | octet << 24 | zero-fill << 30; -1: no item
+    int ydesc[YIT], ygoff[YIT], xdesc[XIT_MAX], xgoff[XIT_MAX];
 #pragma unroll
     for (int it = 0; it < YIT; ++it) {
         const int e = it * 256 + tid;
         ydesc[it] = -1;
-        ygoff[it] = 0;
+        ygoff[it] = -1;
         if (e < ny) {
             const int kl = e / NSG, sg = e - kl * NSG;
             const int rl = sg / OPR, oc = sg - rl * OPR;
-            if (k0 + kl < p.K) {
-                ydesc[it] = (kl * p.AP + sg * 8) | (rl << 16) | (oc << 24);
-                ygoff[it] = (k0 + kl) * PQ + rl * p.Q;
-            } else {
-                ydesc[it] = (kl * p.AP + sg * 8) | (1 << 30);   // k beyond K: zero fill
-            }
+            const int f8 = p.colmode == 0 ? (int)col_mask(oc * 8, p.Q) : oc;
+            ydesc[it] = (kl * p.AP + sg * 8) | (rl << 16) | (f8 << 21);
+            if (k0 + kl < p.K) ygoff[it] = (k0 + kl) * PQ + rl * p.Q + oc * 8;
         }
     }
 #pragma unroll
     for (int it = 0; it < XIT_MAX; ++it) {
         const int e = it * 256 + tid;
         xdesc[it] = -1;
-        xgoff[it] = 0;
+        xgoff[it] = -1;
         if (e < nx) {
             const int cl = e / xper, r2 = e - cl * xper;
             const int row = r2 / NGX, og = r2 - row * NGX;
-            if (c0 + cl < p.C) {
-                xdesc[it] = (cl * p.CP + r2 * 8) | (row << 16) | (og << 24);
-                xgoff[it] = (c0 + cl) * HW + row * p.W;
-            } else {
-                xdesc[it] = (cl * p.CP + r2 * 8) | (1 << 30);   // c beyond C: zero fill
-            }
+            const int f8 = p.colmode == 0 ? (int)col_mask(og * 8 - p.apr, p.W) : og;
+            xdesc[it] = (cl * p.CP + r2 * 8) | (row << 16) | (f8 << 21);
+            if (c0 + cl < p.C) xgoff[it] = (c0 + cl) * HW + row * p.W + og * 8;
         }
     }
+    const unsigned ytotal = (unsigned)p.N * p.K * PQ, xtotal = (unsigned)p.N * p.C * HW;
 
-    auto prefetch = [&](int chunk) {
-        const int img = chunk / (p.rowchunks * p.ncoltiles);
-        const int rem = chunk - img * (p.rowchunks * p.ncoltiles);
-        const int rc = rem / p.ncoltiles, ct = rem - rc * p.ncoltiles;
-        const int p0 = rc * p.TH, q0 = ct * p.TWP;
-        const bf16_t *ybase = dy + (size_t)img * p.K * PQ + (size_t)p0 * p.Q;
+    // chunk coordinates, advanced incrementally
+    int c_img = 0, c_rc = 0, c_ct = 0;
+    auto set_chunk = [&](int chunk) {
+        c_img = chunk / (p.rowchunks * p.ncoltiles);
+        const int rem = chunk - c_img * (p.rowchunks * p.ncoltiles);
+        c_rc = rem / p.ncoltiles;
+        c_ct = rem - c_rc * p.ncoltiles;
+    };
+    auto next_chunk = [&]() {
+        if (++c_ct == p.ncoltiles) {
+            c_ct = 0;
+            if (++c_rc == p.rowchunks) { c_rc = 0; ++c_img; }
+        }
+    };
+
+    // Issues the loads of the current chunk coordinates into yreg / xreg.  Branch-free in the
+    // common case: an octet that is not wanted (row outside the image, columns all outside the
+    // row, channel out of range) is still loaded, from element 0 of the tensor, and its mask is
+    // 0; stage_store turns it into zeros.  The masks of the chunk's octets are kept in ymask /
+    // xmask, 8 bits each.
+    auto prefetch = [&]() {
+        const int p0 = c_rc * p.TH, q0 = c_ct * p.TWP;
         const int h0 = p0 + r0 - p.ph;
-        const bf16_t *xbase = x + (size_t)img * p.C * HW + (ptrdiff_t)h0 * p.W;
+        const int ychunk = c_img * p.K * PQ + p0 * p.Q + q0;
+        const int xchunk = c_img * p.C * HW + h0 * p.W + q0 - p.apr;
+        const int yrows = p.P - p0;            // chunk rows below this are inside the image
+#pragma unroll
+        for (int i = 0; i < (YIT + 3) / 4; ++i) ymask[i] = 0;
+#pragma unroll
+        for (int i = 0; i < (XIT_MAX + 3) / 4; ++i) xmask[i] = 0;
 #pragma unroll
         for (int it = 0; it < YIT; ++it) {
-            uint4 v = make_uint4(0, 0, 0, 0);
             const int d = ydesc[it];
-            if (d >= 0 && !(d >> 30)) {
-                const int rl = (d >> 16) & 0xff, oc = d >> 24;
-                if (p0 + rl < p.P) v = load_row8(ybase + ygoff[it], q0 + oc * 8, p.Q);
-            }
-            yreg[it] = v;
+            uint32_t vm = desc_f8(d);
+            if (p.colmode == 1) vm = (q0 + (int)vm * 8 < p.Q) ? 0xffu : 0u;
+            else if (p.colmode == 2) vm = col_mask(q0 + (int)vm * 8, p.Q);
+            if (ygoff[it] < 0 || desc_row(d) >= yrows) vm = 0;
+            unsigned off = vm ? (unsigned)(ychunk + ygoff[it]) : 0u;
+            ymask[it >> 2] |= vm << (8 * (it & 3));
+            if (p.colmode != 1 && off + 8u > ytotal) yreg[it] = load8_tail(dy, off, vm);
+            else yreg[it] = load8_any(dy + off);
         }
 #pragma unroll
         for (int it = 0; it < XIT_MAX; ++it) {
             if (it * 256 >= nx) break;
-            uint4 v = make_uint4(0, 0, 0, 0);
             const int d = xdesc[it];
-            if (d >= 0 && !(d >> 30)) {
-                const int row = (d >> 16) & 0xff, og = d >> 24;
-                if ((unsigned)(h0 + row) < (unsigned)p.H) v = load_row8(xbase + xgoff[it], q0 - p.apr + og * 8, p.W);
-            }
-            xreg[it] = v;
+            uint32_t vm = desc_f8(d);
+            if (p.colmode == 1) vm = ((unsigned)(q0 - p.apr + (int)vm * 8) < (unsigned)p.W) ? 0xffu : 0u;
+            else if (p.colmode == 2) vm = col_mask(q0 - p.apr + (int)vm * 8, p.W);
+            if (xgoff[it] < 0 || (unsigned)(h0 + desc_row(d)) >= (unsigned)p.H) vm = 0;
+            unsigned off = vm ? (unsigned)(xchunk + xgoff[it]) : 0u;
+            xmask[it >> 2] |= vm << (8 * (it & 3));
+            if (p.colmode != 1 && off + 8u > xtotal) xreg[it] = load8_tail(x, off, vm);
+            else xreg[it] = load8_any(x + off);
         }
     };
 
+    // Writes the staged octets to LDS, clearing the columns that are not wanted.
     auto stage_store = [&](int buf) {
         bf16_t *ys = smem + buf * bufstride, *xs = ys + YS_MAX;
 #pragma unroll
-        for (int it = 0; it < YIT; ++it)
-            if (ydesc[it] >= 0) *reinterpret_cast<uint4 *>(ys + (ydesc[it] & 0xffff)) = yreg[it];
+        for (int it = 0; it < YIT; ++it) {
+            const int d = ydesc[it];
+            if (d < 0) continue;
+            const uint32_t vm = (ymask[it >> 2] >> (8 * (it & 3))) & 0xffu;
+            uint4 v = yreg[it];
+            if (vm != 0xffu) v = apply_mask(v, vm);
+            *reinterpret_cast<uint4 *>(ys + desc_lds(d)) = v;
+        }
 #pragma unroll
         for (int it = 0; it < XIT_MAX; ++it) {
             if (it * 256 >= nx) break;
-            if (xdesc[it] >= 0) *reinterpret_cast<uint4 *>(xs + (xdesc[it] & 0xffff)) = xreg[it];
+            const int d = xdesc[it];
+            if (d < 0) continue;
+            const uint32_t vm = (xmask[it >> 2] >> (8 * (it & 3))) & 0xffu;
+            uint4 v = xreg[it];
+            if (vm != 0xffu) v = apply_mask(v, vm);
+            *reinterpret_cast<uint4 *>(xs + desc_lds(d)) = v;
         }
     };
 
-    auto compute = [&](int buf, int jbeg, int jend) {
-        const bf16_t *ys = smem + buf * bufstride, *xs = ys + YS_MAX;
-        for (int j = jbeg; j < jend; ++j) {
-            const int oct = 2 * j + g;
-            bf16x8 a[TM];
+    // One step = 16 pixel slots: the A operands and, per filter row, the aligned octet of x plus
+    // the neighbours the column shifts need.  The LDS reads of step j+1 are issued before the
+    // MFMAs of step j (two register sets, loop unrolled by two).
+    struct Frag {
+        bf16x8 a[TM];
+        uint4 m[RG][TC];
+        uint32_t lo[RG][TC][2], hi[RG][TC][2];
+    };
+    auto load_frag = [&](Frag &f, const bf16_t *ys, const bf16_t *xs, int j) {
+        const int oct = 2 * j + g;
 #pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
-                a[tm] = *reinterpret_cast<const bf16x8 *>(ys + ((wk * TM + tm) * 32 + l32) * p.AP + oct * 8);
-            const int xo = steptab[oct];
+        for (int tm = 0; tm < TM; ++tm)
+            f.a[tm] = *reinterpret_cast<const bf16x8 *>(ys + ((wk * TM + tm) * 32 + l32) * p.AP + oct * 8);
+        const int xo = steptab[oct];
 #pragma unroll
-            for (int rl = 0; rl < RG; ++rl) {
-                uint32_t D[TC][8];
+        for (int rl = 0; rl < RG; ++rl)
 #pragma unroll
-                for (int tc = 0; tc < TC; ++tc) {
-                    const bf16_t *src = xs + ((wc * TC + tc) * 32 + l32) * p.CP + xo + rl * p.LWX;
-                    const uint4 m = *reinterpret_cast<const uint4 *>(src);
-                    D[tc][2] = m.x; D[tc][3] = m.y; D[tc][4] = m.z; D[tc][5] = m.w;
-                    if (S == 1) {
-                        D[tc][0] = D[tc][1] = D[tc][6] = D[tc][7] = 0;
-                    } else if (S == 3) {
-                        D[tc][0] = 0;
-                        D[tc][1] = (uint32_t)src[-1] << 16;
-                        D[tc][6] = src[8];
-                        D[tc][7] = 0;
-                    } else {
-                        const uint2 lo = *reinterpret_cast<const uint2 *>(src - 4);
-                        const uint2 hi = *reinterpret_cast<const uint2 *>(src + 8);
-                        D[tc][0] = lo.x; D[tc][1] = lo.y; D[tc][6] = hi.x; D[tc][7] = hi.y;
-                    }
+            for (int tc = 0; tc < TC; ++tc) {
+                const bf16_t *src = xs + ((wc * TC + tc) * 32 + l32) * p.CP + xo + rl * p.LWX;
+                f.m[rl][tc] = *reinterpret_cast<const uint4 *>(src);
+                if (S == 3) {
+                    f.lo[rl][tc][0] = 0;
+                    f.lo[rl][tc][1] = (uint32_t)src[-1] << 16;
+                    f.hi[rl][tc][0] = src[8];
+                    f.hi[rl][tc][1] = 0;
+                } else if (S > 3) {
+                    const uint2 l2 = *reinterpret_cast<const uint2 *>(src - 4);
+                    const uint2 h2 = *reinterpret_cast<const uint2 *>(src + 8);
+                    f.lo[rl][tc][0] = l2.x; f.lo[rl][tc][1] = l2.y;
+                    f.hi[rl][tc][0] = h2.x; f.hi[rl][tc][1] = h2.y;
+                } else {
+                    f.lo[rl][tc][0] = f.lo[rl][tc][1] = f.hi[rl][tc][0] = f.hi[rl][tc][1] = 0;
                 }
-                TapLoop<S, TC, TM, 0>::run(D, a, acc, rl);
             }
+    };
+    auto mma_frag = [&](const Frag &f) {
+#pragma unroll
+        for (int rl = 0; rl < RG; ++rl) {
+            uint32_t D[TC][8];
+#pragma unroll
+            for (int tc = 0; tc < TC; ++tc) {
+                D[tc][0] = f.lo[rl][tc][0]; D[tc][1] = f.lo[rl][tc][1];
+                D[tc][2] = f.m[rl][tc].x; D[tc][3] = f.m[rl][tc].y; D[tc][4] = f.m[rl][tc].z; D[tc][5] = f.m[rl][tc].w;
+                D[tc][6] = f.hi[rl][tc][0]; D[tc][7] = f.hi[rl][tc][1];
+            }
+            TapLoop<S, TC, TM, 0>::run(D, f.a, acc, rl);
         }
+    };
+    auto compute = [&](int buf) {
+        const bf16_t *ys = smem + buf * bufstride, *xs = ys + YS_MAX;
+        Frag f0, f1;
+        load_frag(f0, ys, xs, 0);
+        int j = 0;
+        for (; j + 2 <= p.nsteps; j += 2) {
+            load_frag(f1, ys, xs, j + 1);
+            mma_frag(f0);
+            if (j + 2 < p.nsteps) load_frag(f0, ys, xs, j + 2);
+            mma_frag(f1);
+        }
+        if (j < p.nsteps) mma_frag(f0);
     };
 
     const int cbeg = blockIdx.z * p.cps, cend = min(p.nchunks, cbeg + p.cps);
     if (cbeg < cend) {
-        prefetch(cbeg);
+        set_chunk(cbeg);
+        prefetch();
         stage_store(0);
     }
     __syncthreads();
-    const int half = p.nsteps >> 1;
     for (int chunk = cbeg, buf = 0; chunk < cend; ++chunk, buf ^= 1) {
         const bool more = chunk + 1 < cend;
-        if (more) prefetch(chunk + 1);
-        compute(buf, 0, half);
+        if (more) {
+            next_chunk();
+            prefetch();
+        }
+        compute(buf);
         if (more) stage_store(buf ^ 1);
-        compute(buf, half, p.nsteps);
         __syncthreads();
     }
 
-    // ---- epilogue: tile rows are k (8*(v/4) + 4*(lane/32) + v%4), columns c (lane % 32)
+    // ---- epilogue.  An accumulator tile keeps column c = lane % 32 and rows k = 8*(v/4) +
+    // 4*(lane/32) + v%4 in register v.  Four passes (v/4 = 0..3) each move KTB/4 rows of the
+    // workgroup's dw block through LDS as [row][c*T + t], from where consecutive lanes write
+    // consecutive addresses of dw[k][c][r][s].
+    constexpr int ROWS = KTB / 4, ROWLEN = CTB * T, EP = ROWLEN + 1;
+    float *stage = reinterpret_cast<float *>(smem);
     const int Tall = p.R * S;
     float *dst = out + (use_atomics ? (size_t)0 : (size_t)blockIdx.z * p.K * p.C * Tall);
 #pragma unroll
-    for (int tm = 0; tm < TM; ++tm)
+    for (int ps = 0; ps < 4; ++ps) {
 #pragma unroll
-        for (int tc = 0; tc < TC; ++tc) {
-            const int c = c0 + (wc * TC + tc) * 32 + l32;
-            if (c >= p.C) continue;
+        for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
-            for (int t = 0; t < T; ++t)
+            for (int tc = 0; tc < TC; ++tc)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int k = k0 + (wk * TM + tm) * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-                    if (k >= p.K) continue;
-                    const size_t off = ((size_t)k * p.C + c) * Tall + r0 * S + t;
-                    if (use_atomics) unsafeAtomicAdd(dst + off, acc[tm][tc][t][v]);
-                    else dst[off] = acc[tm][tc][t][v];
-                }
+                for (int t = 0; t < T; ++t)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int rr = ((wk * TM + tm) * 2 + g) * 4 + i;
+                        stage[rr * EP + ((wc * TC + tc) * 32 + l32) * T + t] = acc[tm][tc][t][4 * ps + i];
+                    }
+        __syncthreads();
+        for (int e = tid; e < ROWS * ROWLEN; e += 256) {
+            const int rr = e / ROWLEN, j = e - rr * ROWLEN;
+            const int cl = j / T, t = j - cl * T;
+            // rr = ((wk*TM + tm)*2 + g)*4 + i  ->  k = k0 + (wk*TM + tm)*32 + 8*ps + 4*g + i
+            const int k = k0 + (rr >> 3) * 32 + 8 * ps + (rr & 7);
+            const int c = c0 + cl;
+            if (k < p.K && c < p.C) {
+                const size_t off = ((size_t)k * p.C + c) * Tall + r0 * S + t;
+                const float val = stage[rr * EP + j];
+                if (use_atomics) unsafeAtomicAdd(dst + off, val);
+                else dst[off] = val;
+            }
         }
+        __syncthreads();
+    }
 }
 
 struct WPlan {
@@ -319,7 +433,7 @@ int odd16(int elems)  // pitch in elements: a multiple of 8 whose count of 16-by
     return units * 8;
 }
 
-bool make_wplan(const ConvGeom &g, int want_slices, WPlan *pl)
+bool make_wplan(const ConvGeom &g, WPlan *pl)
 {
     if (!g.in_bf16 || g.sh != 1 || g.sw != 1) return false;
     if (g.S != 1 && g.S != 3 && g.S != 5 && g.S != 7) return false;
@@ -332,46 +446,50 @@ bool make_wplan(const ConvGeom &g, int want_slices, WPlan *pl)
     else if ((g.S == 5 && g.R == 5) || (g.S == 7 && g.R == 1)) RG = 1;
     else return false;
     const long long lim = 0x7fffffffLL;
-    if ((long long)g.N * g.C * g.H * g.W > lim || (long long)g.N * g.K * g.P * g.Q > lim) return false;
+    if ((long long)g.N * g.C * g.H * g.W + 64 > lim || (long long)g.N * g.K * g.P * g.Q + 64 > lim) return false;
     WgradProblem p;
     p.N = g.N; p.C = g.C; p.H = g.H; p.W = g.W; p.K = g.K; p.P = g.P; p.Q = g.Q; p.R = g.R; p.ph = g.ph;
-    if (g.Q <= 64) { p.TWP = (g.Q + 7) / 8 * 8; p.ncoltiles = 1; }
-    else { p.TWP = 32; p.ncoltiles = (g.Q + 31) / 32; }
+    if (g.Q <= 64) { p.TWP = (g.Q + 7) / 8 * 8; p.ncoltiles = 1; p.colmode = 0; }
+    else { p.TWP = 32; p.ncoltiles = (g.Q + 31) / 32; p.colmode = (g.W % 8 == 0) ? 1 : 2; }
     int th = PIXC_MAX / p.TWP;
     if (th > g.P) th = g.P;
     while (th > 1 && (th * p.TWP) % 16 != 0) --th;
-    if ((th * p.TWP) % 16 != 0) {      // a single row of 8, 24, 40 or 56 slots: pad the row pair
-        th = 2;
-    }
+    if ((th * p.TWP) % 16 != 0) th = 2;      // a single row of 8, 24, 40 or 56 slots: pad to a row pair
     p.TH = th;
     p.nsteps = p.TH * p.TWP / 16;
-    if (p.TH * p.TWP > PIXC_MAX) return false;
+    if (p.TH * p.TWP > PIXC_MAX || p.TH > 31) return false;
     p.apr = g.S > 1 ? 8 : 0;
     p.LWX = p.TWP + 2 * p.apr;
     p.xrows = p.TH + RG - 1;
+    if (p.xrows > 31) return false;
     p.AP = odd16(p.TH * p.TWP);
     p.CP = odd16(p.xrows * p.LWX);
     const int KTB = 2 * TM * 32, CTB = 2 * TC * 32;
     const long long nx = (long long)CTB * p.xrows * (p.LWX / 8);
     if (nx > 10 * 256) return false;
+    if ((long long)CTB * p.CP > 65535 || (long long)KTB * p.AP > 65535) return false;   // LDS offsets are 16 bits
     p.rowchunks = (g.P + p.TH - 1) / p.TH;
     const long long nch = (long long)g.N * p.rowchunks * p.ncoltiles;
     if (nch > lim) return false;
     p.nchunks = (int)nch;
-    p.nrg = g.R / RG;
+    const int nrg = g.R / RG;
     p.ctiles = (g.C + CTB - 1) / CTB;
     const int ktiles = (g.K + KTB - 1) / KTB;
     if (ktiles > 65535) return false;
-    const long long tiles = (long long)p.ctiles * p.nrg * ktiles;
-    long long slices = want_slices > 0 ? want_slices : (768 + tiles - 1) / tiles;
+    const long long tiles = (long long)p.ctiles * nrg * ktiles;
+    // slices: about two workgroups per CU in all; every slice costs a pass over dw in the epilogue
+    long long slices = (512 + tiles - 1) / tiles;
+    if (const char *dbg = getenv("SN_WGRAD_SLICES")) slices = atoi(dbg);
     if (slices > p.nchunks) slices = p.nchunks;
     if (slices > 65535) slices = 65535;
     if (slices < 1) slices = 1;
     p.cps = (int)((p.nchunks + slices - 1) / slices);
     slices = (p.nchunks + p.cps - 1) / p.cps;
     pl->p = p;
-    pl->grid = dim3(p.ctiles * p.nrg, ktiles, (unsigned)slices);
-    pl->smem = 2 * ((size_t)KTB * (PIXC_MAX + 8) + (size_t)CTB * p.CP) * sizeof(bf16_t);  // double buffered
+    pl->grid = dim3(p.ctiles * nrg, ktiles, (unsigned)slices);
+    const size_t stage_bytes = 2 * ((size_t)KTB * (PIXC_MAX + 8) + (size_t)CTB * p.CP) * sizeof(bf16_t);  // double buffered
+    const size_t epi_bytes = (size_t)(KTB / 4) * (CTB * RG * g.S + 1) * sizeof(float);
+    pl->smem = stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
     if (pl->smem > 156 * 1024) return false;
     pl->S = g.S; pl->RG = RG; pl->TM = TM; pl->TC = TC;
     return true;
@@ -393,13 +511,13 @@ hipError_t launch_cfg(const bf16_t *x, const bf16_t *dy, float *out, int atomics
 bool tile_wgrad_supported(const ConvGeom &g)
 {
     WPlan pl;
-    return make_wplan(g, 0, &pl);
+    return make_wplan(g, &pl);
 }
 
 int tile_wgrad_slices(const ConvGeom &g)
 {
     WPlan pl;
-    return make_wplan(g, 0, &pl) ? (int)pl.grid.z : 0;
+    return make_wplan(g, &pl) ? (int)pl.grid.z : 0;
 }
 
 // partial == nullptr: slices add into dw with atomics (dw is zero-filled first);
@@ -408,7 +526,7 @@ hipError_t launch_tile_wgrad(const void *x, const void *dy, float *dw, const Con
                              hipStream_t st)
 {
     WPlan pl;
-    if (!make_wplan(g, 0, &pl)) return hipErrorInvalidValue;
+    if (!make_wplan(g, &pl)) return hipErrorInvalidValue;
     const size_t nw = (size_t)g.K * g.C * g.R * g.S;
     const int slices = (int)pl.grid.z;
     const bool direct_store = !partial && slices == 1;
