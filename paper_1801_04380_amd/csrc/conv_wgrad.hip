@@ -76,15 +76,15 @@ __device__ inline uint32_t col_mask(int v0, int W)
     return hi > lo ? (((1u << hi) - 1u) & ~((1u << lo) - 1u)) : 0u;
 }
 
-// Reads 8 pixels element by element (only the columns in vm): for the rare window
-// that would run past the end of the tensor.
-__device__ __attribute__((noinline)) uint4 load8_tail(const bf16_t *base, unsigned off, uint32_t vm)
+// Moves the elements of an octet down by sh positions (element sh becomes element 0).
+__device__ inline uint4 shift_down(uint4 r, uint32_t sh)
 {
-    unsigned short e[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) e[i] = ((vm >> i) & 1u) ? base[off + i] : (unsigned short)0;
-    return make_uint4(e[0] | ((uint32_t)e[1] << 16), e[2] | ((uint32_t)e[3] << 16), e[4] | ((uint32_t)e[5] << 16),
-                      e[6] | ((uint32_t)e[7] << 16));
+    const unsigned long long lo = r.x | ((unsigned long long)r.y << 32), hi = r.z | ((unsigned long long)r.w << 32);
+    const uint32_t bits = sh * 16;
+    unsigned long long nlo, nhi;
+    if (bits >= 64) { nlo = hi >> (bits - 64); nhi = 0; }
+    else { nlo = (lo >> bits) | (bits ? hi << (64 - bits) : 0ull); nhi = hi >> bits; }
+    return make_uint4((uint32_t)nlo, (uint32_t)(nlo >> 32), (uint32_t)nhi, (uint32_t)(nhi >> 32));
 }
 
 // Clears the columns of an octet that are not in vm.
@@ -140,7 +140,7 @@ __device__ inline int desc_lds(int d) { return d & 0xffff; }
 __device__ inline int desc_row(int d) { return (d >> 16) & 31; }
 __device__ inline int desc_f8(int d) { return (d >> 21) & 255; }
 
-template <int S, int RG, int TM, int TC>
+template <int S, int RG, int TM, int TC, int COLMODE>
 __global__ void __launch_bounds__(256, 1)
 conv_wgrad_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, float *__restrict__ out,
                   int use_atomics, WgradProblem p)
@@ -183,11 +183,7 @@ conv_wgrad_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
     constexpr int YIT = (KTB * (PIXC_MAX / 8) + 255) / 256;
     constexpr int XIT_MAX = 10;
     uint4 yreg[YIT], xreg[XIT_MAX];
-    uint32_t ymask[(YIT + 3) / 4], xmask[(XIT_MAX + 3) / 4];   // colmode 2: masks of the staged octets
-#pragma unroll
-    for (int i = 0; i < (YIT + 3) / 4; ++i) ymask[i] = 0;
-#pragma unroll
-    for (int i = 0; i < (XIT_MAX + 3) / 4; ++i) xmask[i] = 0;
+    uint32_t yinfo[(YIT + 1) / 2], xinfo[(XIT_MAX + 1) / 2];   // per staged octet: column mask | shift << 8
     const int ny = KTB * NSG, nx = CTB * p.xrows * NGX;
     const int xper = p.xrows * NGX;
     int ydesc[YIT], ygoff[YIT], xdesc[XIT_MAX], xgoff[XIT_MAX];
@@ -199,7 +195,7 @@ conv_wgrad_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
         if (e < ny) {
             const int kl = e / NSG, sg = e - kl * NSG;
             const int rl = sg / OPR, oc = sg - rl * OPR;
-            const int f8 = p.colmode == 0 ? (int)col_mask(oc * 8, p.Q) : oc;
+            const int f8 = COLMODE == 0 ? (int)col_mask(oc * 8, p.Q) : oc;
             ydesc[it] = (kl * p.AP + sg * 8) | (rl << 16) | (f8 << 21);
             if (k0 + kl < p.K) ygoff[it] = (k0 + kl) * PQ + rl * p.Q + oc * 8;
         }
@@ -212,7 +208,7 @@ conv_wgrad_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
         if (e < nx) {
             const int cl = e / xper, r2 = e - cl * xper;
             const int row = r2 / NGX, og = r2 - row * NGX;
-            const int f8 = p.colmode == 0 ? (int)col_mask(og * 8 - p.apr, p.W) : og;
+            const int f8 = COLMODE == 0 ? (int)col_mask(og * 8 - p.apr, p.W) : og;
             xdesc[it] = (cl * p.CP + r2 * 8) | (row << 16) | (f8 << 21);
             if (c0 + cl < p.C) xgoff[it] = (c0 + cl) * HW + row * p.W + og * 8;
         }
@@ -234,11 +230,13 @@ conv_wgrad_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
         }
     };
 
-    // Issues the loads of the current chunk coordinates into yreg / xreg.  Branch-free in the
-    // common case: an octet that is not wanted (row outside the image, columns all outside the
-    // row, channel out of range) is still loaded, from element 0 of the tensor, and its mask is
-    // 0; stage_store turns it into zeros.  The masks of the chunk's octets are kept in ymask /
-    // xmask, 8 bits each.
+    // Issues the loads of the current chunk coordinates into yreg / xreg.  Straight-line code, so
+    // that the compiler keeps all of a chunk's loads in flight: an octet that is not wanted (row
+    // outside the image, columns all outside the row, channel out of range) is still loaded, from
+    // element 0 of the tensor, with mask 0, and stage_store turns it into zeros.  An octet that
+    // hangs over the end of its row is loaded whole and masked later; if it would run past the
+    // end of the tensor itself the load starts sh elements earlier and stage_store shifts it back.
+    // info keeps mask | sh << 8 per octet, two octets per register.
     auto prefetch = [&]() {
         const int p0 = c_rc * p.TH, q0 = c_ct * p.TWP;
         const int h0 = p0 + r0 - p.ph;
@@ -246,33 +244,41 @@ conv_wgrad_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
         const int xchunk = c_img * p.C * HW + h0 * p.W + q0 - p.apr;
         const int yrows = p.P - p0;            // chunk rows below this are inside the image
 #pragma unroll
-        for (int i = 0; i < (YIT + 3) / 4; ++i) ymask[i] = 0;
+        for (int i = 0; i < (YIT + 1) / 2; ++i) yinfo[i] = 0;
 #pragma unroll
-        for (int i = 0; i < (XIT_MAX + 3) / 4; ++i) xmask[i] = 0;
+        for (int i = 0; i < (XIT_MAX + 1) / 2; ++i) xinfo[i] = 0;
 #pragma unroll
         for (int it = 0; it < YIT; ++it) {
             const int d = ydesc[it];
             uint32_t vm = desc_f8(d);
-            if (p.colmode == 1) vm = (q0 + (int)vm * 8 < p.Q) ? 0xffu : 0u;
-            else if (p.colmode == 2) vm = col_mask(q0 + (int)vm * 8, p.Q);
+            if (COLMODE == 1) vm = (q0 + (int)vm * 8 < p.Q) ? 0xffu : 0u;
+            if (COLMODE == 2) vm = col_mask(q0 + (int)vm * 8, p.Q);
             if (ygoff[it] < 0 || desc_row(d) >= yrows) vm = 0;
             unsigned off = vm ? (unsigned)(ychunk + ygoff[it]) : 0u;
-            ymask[it >> 2] |= vm << (8 * (it & 3));
-            if (p.colmode != 1 && off + 8u > ytotal) yreg[it] = load8_tail(dy, off, vm);
-            else yreg[it] = load8_any(dy + off);
+            uint32_t sh = 0;
+            if (COLMODE != 1) {
+                sh = off + 8u > ytotal ? off + 8u - ytotal : 0u;
+                off -= sh;
+            }
+            yinfo[it >> 1] |= (vm | (sh << 8)) << (16 * (it & 1));
+            yreg[it] = load8_any(dy + off);
         }
 #pragma unroll
         for (int it = 0; it < XIT_MAX; ++it) {
             if (it * 256 >= nx) break;
             const int d = xdesc[it];
             uint32_t vm = desc_f8(d);
-            if (p.colmode == 1) vm = ((unsigned)(q0 - p.apr + (int)vm * 8) < (unsigned)p.W) ? 0xffu : 0u;
-            else if (p.colmode == 2) vm = col_mask(q0 - p.apr + (int)vm * 8, p.W);
+            if (COLMODE == 1) vm = ((unsigned)(q0 - p.apr + (int)vm * 8) < (unsigned)p.W) ? 0xffu : 0u;
+            if (COLMODE == 2) vm = col_mask(q0 - p.apr + (int)vm * 8, p.W);
             if (xgoff[it] < 0 || (unsigned)(h0 + desc_row(d)) >= (unsigned)p.H) vm = 0;
             unsigned off = vm ? (unsigned)(xchunk + xgoff[it]) : 0u;
-            xmask[it >> 2] |= vm << (8 * (it & 3));
-            if (p.colmode != 1 && off + 8u > xtotal) xreg[it] = load8_tail(x, off, vm);
-            else xreg[it] = load8_any(x + off);
+            uint32_t sh = 0;
+            if (COLMODE != 1) {
+                sh = off + 8u > xtotal ? off + 8u - xtotal : 0u;
+                off -= sh;
+            }
+            xinfo[it >> 1] |= (vm | (sh << 8)) << (16 * (it & 1));
+            xreg[it] = load8_any(x + off);
         }
     };
 
@@ -283,8 +289,9 @@ conv_wgrad_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
         for (int it = 0; it < YIT; ++it) {
             const int d = ydesc[it];
             if (d < 0) continue;
-            const uint32_t vm = (ymask[it >> 2] >> (8 * (it & 3))) & 0xffu;
+            const uint32_t info = (yinfo[it >> 1] >> (16 * (it & 1))) & 0xffffu, vm = info & 0xffu;
             uint4 v = yreg[it];
+            if (COLMODE != 1 && (info >> 8)) v = shift_down(v, info >> 8);
             if (vm != 0xffu) v = apply_mask(v, vm);
             *reinterpret_cast<uint4 *>(ys + desc_lds(d)) = v;
         }
@@ -293,8 +300,9 @@ conv_wgrad_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
             if (it * 256 >= nx) break;
             const int d = xdesc[it];
             if (d < 0) continue;
-            const uint32_t vm = (xmask[it >> 2] >> (8 * (it & 3))) & 0xffu;
+            const uint32_t info = (xinfo[it >> 1] >> (16 * (it & 1))) & 0xffffu, vm = info & 0xffu;
             uint4 v = xreg[it];
+            if (COLMODE != 1 && (info >> 8)) v = shift_down(v, info >> 8);
             if (vm != 0xffu) v = apply_mask(v, vm);
             *reinterpret_cast<uint4 *>(xs + desc_lds(d)) = v;
         }
@@ -447,6 +455,7 @@ bool make_wplan(const ConvGeom &g, WPlan *pl)
     else return false;
     const long long lim = 0x7fffffffLL;
     if ((long long)g.N * g.C * g.H * g.W + 64 > lim || (long long)g.N * g.K * g.P * g.Q + 64 > lim) return false;
+    if ((long long)g.N * g.C * g.H * g.W < 8 || (long long)g.N * g.K * g.P * g.Q < 8) return false;   // 16-byte loads
     WgradProblem p;
     p.N = g.N; p.C = g.C; p.H = g.H; p.W = g.W; p.K = g.K; p.P = g.P; p.Q = g.Q; p.R = g.R; p.ph = g.ph;
     if (g.Q <= 64) { p.TWP = (g.Q + 7) / 8 * 8; p.ncoltiles = 1; p.colmode = 0; }
@@ -495,15 +504,25 @@ bool make_wplan(const ConvGeom &g, WPlan *pl)
     return true;
 }
 
+template <int S, int RG, int TM, int TC, int COLMODE>
+hipError_t launch_mode(const bf16_t *x, const bf16_t *dy, float *out, int atomics, const WPlan &pl, hipStream_t st)
+{
+    // dynamic LDS beyond 64 KB has to be enabled once per kernel
+    static const hipError_t attr =
+        hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_wgrad_kernel<S, RG, TM, TC, COLMODE>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 156 * 1024);
+    if (attr != hipSuccess) return attr;
+    hipLaunchKernelGGL((conv_wgrad_kernel<S, RG, TM, TC, COLMODE>), pl.grid, dim3(256), pl.smem, st, x, dy, out,
+                       atomics, pl.p);
+    return hipGetLastError();
+}
+
 template <int S, int RG, int TM, int TC>
 hipError_t launch_cfg(const bf16_t *x, const bf16_t *dy, float *out, int atomics, const WPlan &pl, hipStream_t st)
 {
-    // dynamic LDS beyond 64 KB has to be enabled once per kernel
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_wgrad_kernel<S, RG, TM, TC>),
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, 156 * 1024);
-    if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL((conv_wgrad_kernel<S, RG, TM, TC>), pl.grid, dim3(256), pl.smem, st, x, dy, out, atomics, pl.p);
-    return hipGetLastError();
+    if (pl.p.colmode == 0) return launch_mode<S, RG, TM, TC, 0>(x, dy, out, atomics, pl, st);
+    if (pl.p.colmode == 1) return launch_mode<S, RG, TM, TC, 1>(x, dy, out, atomics, pl, st);
+    return launch_mode<S, RG, TM, TC, 2>(x, dy, out, atomics, pl, st);
 }
 
 }  // namespace
