@@ -10,27 +10,43 @@
 //
 // Work decomposition.  A 256-thread workgroup owns KT output channels x PIXT
 // output pixels (KT=128, PIXT=256 or KT=64, PIXT=512) and walks the input
-// channels 16 at a time.  The pixels of a tile are TH consecutive rows of the
-// flattened (image, output row) space times TW columns; TW = Qout for images up
-// to 64 wide (so small images fill the lanes: a tile may span several images),
-// otherwise 8x32 / 16x32 patches.  Per 16-channel chunk the workgroup keeps in
-// LDS
+// channels 16 at a time; each wave multiplies a 64-channel x 128-pixel block
+// with v_mfma_f32_32x32x16_bf16 (2 x 4 tiles, 128 accumulator registers).
+// Two pixel tilings:
+//   WIDE    8x32 / 16x32 patches of one image; an MFMA tile is one output row,
+//           and the four tiles of a wave are four consecutive rows;
+//   NARROW  (images up to 64 wide) TH consecutive rows of the flattened
+//           (image, output row) space times the whole width, so small images
+//           fill the lanes: a tile may span several images.
+// Per 16-channel chunk the workgroup keeps in LDS
 //   xs: the input patch with halo, transposed to [pixel][16 channels] (32 bytes
 //       per pixel, so one MFMA lane reads its 8 consecutive channels with a
-//       single 16-byte load); the transposition happens on the way in: each lane
-//       gathers 8 channels of one pixel with 2-byte loads that are coalesced
-//       across lanes along the image row, and writes 16 bytes;
-//   ws: the filter slab [tap][KT][16 channels].
+//       single 16-byte load).  The transposition happens on the way in: each
+//       thread gathers 8 channels of two neighbouring pixels with 4-byte loads
+//       that are coalesced across lanes along the image row, and writes two
+//       16-byte items.  The patch rows are padded to a multiple of 16 pixels;
+//   ws: the filter slab [tap][KT][16 channels] of one stage.
 // Both are XOR-swizzled on the 16-byte half index with bit 3 of the row index,
-// which makes the 16-byte reads of 16 consecutive rows hit distinct banks.
-// A tap (r,s) only shifts the pixel index by r*LW + s, so the nine taps of a 3x3
-// filter reuse one patch.  Each wave multiplies a 64-channel x 128-pixel block
-// with v_mfma_f32_32x32x16_bf16 (2 x 4 tiles, 128 accumulator registers).
-// Global loads of the next stage are issued before the MFMAs of the current one.
+// which makes the 16-byte reads of 16 consecutive rows hit distinct banks; with
+// the padded patch rows the swizzle of a pixel does not depend on the tap row.
+// A tap (r,s) only shifts the pixel index by r*LWp + s, so all taps reuse one
+// patch.  A chunk is worked off in stages of one filter column (all r for one
+// s; all taps for 1xS filters): in the WIDE tiling the operand of output row i,
+// tap row r is the operand of output row i+1, tap row r-1, so a wave reads
+// 4+R-1 patch rows per stage instead of 4*R.
+//
+// Both LDS arrays are double buffered.  The global loads of the next stage
+// (filter) and of the next chunk (patch) are issued before the MFMAs of the
+// current stage and written to the other buffer after them; one barrier per
+// stage.  The loads are branch free: addresses that fall outside the image or
+// the tensor are clamped to a valid one, and what they return is never stored
+// (the LDS buffers are zeroed once; the set of pixels outside the image is the
+// same for every chunk) or belongs to output channels that are not written.
 //
 // The filter slab comes either from a copy pre-packed into the caller's
-// workspace in exactly the LDS order (STAGED algorithm: wide, contiguous loads),
-// or is gathered from the KCRS tensor with 2-byte loads (DIRECT, no workspace).
+// workspace in exactly the LDS order, swizzle included (STAGED algorithm: a
+// stage is one contiguous run of 16-byte loads), or is gathered from the KCRS
+// tensor with 2-byte loads (DIRECT, no workspace).
 #include "sn_internal.h"
 
 namespace sn {
@@ -38,44 +54,75 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
 
-constexpr int XPIX_MAX = 640;  // input patch pixels held in LDS
-constexpr int XROUNDS_MAX = (XPIX_MAX * 2 + 255) / 256;
+constexpr int XPAIRS_MAX = 384;  // NARROW: pixel pairs gathered per chunk
+constexpr int WIDE_LWP = 48;    // WIDE: padded patch row (32 + S - 1 <= 48)
+constexpr int LDS_LIMIT = 160 * 1024;
+constexpr int EPI_PITCH = 272;  // bytes per channel row of the output staging: 128 pixels and a pad
 
 struct TileProblem {
     int N, Cin, Hin, Win, Kout, Pout, Qout, padh, padw;
     int out_bf16;
-    int TH, TW, LW;          // tile rows, tile columns, LDS patch width in pixels
+    int TH, TW, LW, LWp;     // tile rows, tile columns, patch width in pixels, padded patch width
     int ncoltiles;
-    int tiles_per_img;       // > 0: row tiles never cross an image (used for wide images); 0: they may
+    int tiles_per_img;       // WIDE: row tiles per image
     int Hp;                  // padded rows per image = Pout + R - 1
     int nchunks;             // ceil(Cin / 16)
+    int xslots;              // pixel slots of one patch buffer in LDS
     // filter access: A(m, red, tap) = w[m*w_sm + red*w_sr + (tflip ? T-1-tap : tap)]
     int w_sm, w_sr, tflip;
     int Mpad;                // rows per (chunk, tap) block of the packed filter
 };
 
-template <int R, int S, int KT> struct Cfg {
-    static constexpr int T = R * S;
-    // one filter row per stage: the filter slab staged through registers stays small
-    // enough (S 16-byte pieces per thread at KT=128) for two workgroups per CU
-    static constexpr int RG = 1;
-    static constexpr int TRES = RG * S;
-    static constexpr int NSUB = R / RG;  // stages per channel chunk
-    static constexpr int PIXT = (KT == 128) ? 256 : 512;
-    static constexpr int WITEMS = (TRES * KT * 2 + 255) / 256;
-};
+// Filter columns per stage: a 1xS filter has too little work per column.
+constexpr int sg_of(int R, int S) { return (R == 1 && S > 1) ? S : 1; }
 
-__device__ inline int swz(int row) { return (row >> 3) & 1; }
+__device__ __host__ inline int swz(int row) { return (row >> 3) & 1; }
 
-template <int R, int S, int KT, bool STAGED>
+// Two consecutive bf16 as one 4-byte load, whatever the alignment.
+struct __attribute__((packed, aligned(2))) U32u { uint32_t v; };
+__device__ inline uint32_t load2_any(const bf16_t *p) { return reinterpret_cast<const U32u *>(p)->v; }
+
+// Eight consecutive bf16 as one 16-byte store, whatever the alignment.
+struct __attribute__((packed, aligned(2))) U128u { uint4 v; };
+__device__ inline void store8_any(bf16_t *p, uint4 v) { reinterpret_cast<U128u *>(p)->v = v; }
+
+// Two fp32 to a pair of bf16 (round to nearest even), the first in the low half.
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ inline uint32_t pack2_bf16(float a, float b)
+{
+    f32x2 f = {a, b};
+    bf16x2 h = __builtin_convertvector(f, bf16x2);
+    uint32_t r;
+    __builtin_memcpy(&r, &h, 4);
+    return r;
+}
+
+// Keeps the first n (< 8) elements of an octet.
+__device__ inline uint4 keep_first(uint4 v, int n)
+{
+    uint32_t *d = reinterpret_cast<uint32_t *>(&v);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) d[j] &= n > 2 * j + 1 ? 0xffffffffu : (n > 2 * j ? 0xffffu : 0u);
+    return v;
+}
+
+template <int R, int S, int KT, bool STAGED, bool WIDE>
 __global__ void __launch_bounds__(256, 2)
 conv_tile_kernel(const bf16_t *__restrict__ in, const bf16_t *__restrict__ w, void *__restrict__ out, TileProblem p)
 {
-    typedef Cfg<R, S, KT> C;
-    constexpr int T = C::T, TRES = C::TRES, NSUB = C::NSUB, WITEMS = C::WITEMS;
-    __shared__ uint4 xs[XPIX_MAX * 2];
-    __shared__ uint4 ws[TRES * KT * 2];
+    constexpr int SG = sg_of(R, S), T = R * S, TRES = R * SG, NSUB = S / SG;
+    constexpr int PIXT = KT == 128 ? 256 : 512;
+    constexpr int WSZ = TRES * KT * 2;                 // 16-byte items of one filter slab
+    constexpr int WITEMS = (WSZ + 255) / 256;
+    // gather rounds: a thread takes one pixel pair x 8 channels per round
+    constexpr int XR = WIDE ? ((PIXT / 32 + R - 1) * ((32 + S) / 2) + 127) / 128 : XPAIRS_MAX / 128;
+    constexpr int NB = WIDE ? 4 + R - 1 : 4;
+    extern __shared__ __attribute__((aligned(16))) uint4 smem[];
+    const int XS = p.xslots * 2;                       // 16-byte items of one patch buffer
+    uint4 *const xs = smem, *const ws = smem + 2 * XS;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, g = lane >> 5;
@@ -86,56 +133,105 @@ conv_tile_kernel(const bf16_t *__restrict__ in, const bf16_t *__restrict__ w, vo
     const int rowtile = blockIdx.x / p.ncoltiles, coltile = blockIdx.x - rowtile * p.ncoltiles;
     const int k0 = blockIdx.y * KT;
     const int q0 = coltile * p.TW;
-    int o0, NP;                                  // first flattened (image, row) and the row limit
-    if (p.tiles_per_img > 0) {
-        const int img = rowtile / p.tiles_per_img;
-        o0 = img * p.Pout + (rowtile - img * p.tiles_per_img) * p.TH;
+    const int LWp = WIDE ? WIDE_LWP : p.LWp;
+    const int HWin = p.Hin * p.Win;
+    int o0, NP, u0, lrows, img = 0;   // first flattened (image, row), its limit, first patch row, patch rows
+    if (WIDE) {
+        img = rowtile / p.tiles_per_img;
+        const int pp0 = (rowtile - img * p.tiles_per_img) * p.TH;
+        o0 = img * p.Pout + pp0;
         NP = (img + 1) * p.Pout;
+        u0 = img * p.Hp + pp0;
+        lrows = p.TH + R - 1;
     } else {
         o0 = rowtile * p.TH;
         NP = p.N * p.Pout;
+        const int n0 = o0 / p.Pout;
+        u0 = n0 * p.Hp + (o0 - n0 * p.Pout);
+        const int olast = min(o0 + p.TH, NP) - 1, nl = olast / p.Pout;
+        lrows = nl * p.Hp + (olast - nl * p.Pout) - u0 + R;
     }
-    const int n0 = o0 / p.Pout, u0 = n0 * p.Hp + (o0 - n0 * p.Pout);
-    const int olast = min(o0 + p.TH, NP) - 1;
-    const int nl = olast / p.Pout;
-    const int lrows = nl * p.Hp + (olast - nl * p.Pout) - u0 + R;
-    const int xpix = lrows * p.LW;
-    const int HWin = p.Hin * p.Win;
 
-    // ---- per-thread constants of the input-patch gather
-    int xoff[XROUNDS_MAX];   // element offset of channel 0 of this thread's pixel, -1: zero fill
-    const int xo = tid >> 7;  // which 8-channel half this thread gathers
+    // ---- zero both patch buffers once: pixels outside the image are never written again
+    for (int i = tid; i < 2 * XS; i += 256) xs[i] = make_uint4(0, 0, 0, 0);
+
+    // ---- per-thread constants of the patch gather.  A thread takes two neighbouring
+    // pixels of a patch row x 8 channels: one 4-byte load per channel (2-byte aligned)
+    // brings both pixels, so that two 16-byte LDS items are built with 8 byte-permutes.
+    // If only one pixel of the pair is inside the image the load is placed so that it
+    // stays inside the row (rows have at least 2 pixels), and the half that holds the
+    // live pixel goes to that pixel's slot.
+    const int xo = tid >> 7, tp = tid & 127;
+    const uint32_t xo8 = (uint32_t)xo * 8u * (uint32_t)HWin;
+    uint32_t xoff[XR];       // element offset of the load for the thread's first channel of chunk 0
+    int xdlo[XR], xdhi[XR];  // 16-byte LDS index for the low / high halves, -1: not stored
+    const int LWh = (p.LW + 1) >> 1;
+    const int xpairs = lrows * LWh;
+    const int xrounds = WIDE ? XR : (xpairs + 127) >> 7;
 #pragma unroll
-    for (int rd = 0; rd < XROUNDS_MAX; ++rd) {
-        const int lp = rd * 128 + (tid & 127);
-        int off = -1;
-        if (lp < xpix) {
-            const int lrow = lp / p.LW, lcol = lp - lrow * p.LW;
-            const int u = u0 + lrow, n = u / p.Hp, h = u - n * p.Hp - p.padh;
+    for (int rd = 0; rd < XR; ++rd) {
+        const int lp = rd * 128 + tp;
+        int off = 0, dlo = -1, dhi = -1;
+        if (lp < xpairs) {
+            const int lrow = lp / LWh, lcol = (lp - lrow * LWh) * 2;
+            const int u = u0 + lrow, n = WIDE ? img : u / p.Hp, h = u - n * p.Hp - p.padh;
             const int v = q0 - p.padw + lcol;
-            if (n < p.N && (unsigned)h < (unsigned)p.Hin && (unsigned)v < (unsigned)p.Win)
-                off = (n * p.Cin * p.Hin + h) * p.Win + v;
+            if (n < p.N && (unsigned)h < (unsigned)p.Hin) {
+                const int rowoff = (n * p.Cin * p.Hin + h) * p.Win;
+                const bool va = (unsigned)v < (unsigned)p.Win;
+                const bool vb = lcol + 1 < p.LW && (unsigned)(v + 1) < (unsigned)p.Win;
+                const int slot = lrow * LWp + lcol;
+                const int da = slot * 2 + (xo ^ swz(slot)), db = (slot + 1) * 2 + (xo ^ swz(slot + 1));
+                if (va && vb) { off = rowoff + v; dlo = da; dhi = db; }
+                else if (va && v >= 1) { off = rowoff + v - 1; dhi = da; }
+                else if (va) { off = rowoff; dlo = da; }
+                else if (vb) { off = rowoff + v + 1; dlo = db; }
+            }
         }
-        xoff[rd] = off;
+        xoff[rd] = (uint32_t)off + xo8;
+        xdlo[rd] = dlo;
+        xdhi[rd] = dhi;
     }
-    const int xrounds = (xpix + 127) >> 7;
 
-    // ---- per-lane constants of the MFMA operand reads and of the output
-    int pixbase[4], outoff[4];
+    // ---- per-thread constants of the DIRECT filter gather: thread item = (tap, row, half)
+    uint32_t wsrc[STAGED ? 1 : WITEMS];
+    int wdst[STAGED ? 1 : WITEMS];
+    if (!STAGED) {
 #pragma unroll
-    for (int f = 0; f < 4; ++f) {
-        const int i = (wp * 4 + f) * 32 + l32;
-        const int rl = i / p.TW, cl = i - rl * p.TW;
-        const int o = o0 + rl;
-        int pb = 0, oo = -1;
-        if (rl < p.TH && o < NP && q0 + cl < p.Qout) {
-            const int n = o / p.Pout, pp = o - n * p.Pout;
-            pb = (n * p.Hp + pp - u0) * p.LW + cl;
-            oo = (n * p.Kout * p.Pout + pp) * p.Qout + q0 + cl;
+        for (int it = 0; it < WITEMS; ++it) {
+            const int e = min(it * 256 + tid, WSZ - 1);
+            int tl, row, o;
+            tl = e % TRES;
+            const int q = e / TRES;
+            if (p.tflip) { row = q % KT; o = q / KT; }   // backward-data: (m, tap) contiguous for one red
+            else { o = q & 1; row = q >> 1; }            // forward: (red, tap) contiguous for one m
+            const int r = tl / SG, sl = tl - r * SG, tap = r * S + sl;
+            wsrc[it] = (uint32_t)(min(k0 + row, p.Kout - 1) * p.w_sm + (p.tflip ? T - 1 - tap : tap) +
+                                  o * 8 * p.w_sr);
+            wdst[it] = (tl * KT + row) * 2 + (o ^ swz(row));
         }
-        pixbase[f] = pb;
-        outoff[f] = oo;
     }
+
+    // ---- per-lane constants of the MFMA operand reads
+    int pixbase[WIDE ? 1 : 4];
+    if (WIDE) {
+        pixbase[0] = (wp * 4) * WIDE_LWP + l32;
+    } else {
+#pragma unroll
+        for (int f = 0; f < 4; ++f) {
+            const int i = (wp * 4 + f) * 32 + l32;
+            const int rl = i / p.TW, cl = i - rl * p.TW;
+            const int o = o0 + rl;
+            int pb = 0;
+            if (rl < p.TH && o < NP) {
+                const int n = o / p.Pout, pp = o - n * p.Pout;
+                pb = (n * p.Hp + pp - u0) * LWp + cl;
+            }
+            pixbase[f] = pb;
+        }
+    }
+    const int arow = wk * 64 + l32;
+    const int aidx = arow * 2 + (g ^ swz(arow));
 
     f32x16 acc[2][4];
 #pragma unroll
@@ -145,154 +241,264 @@ conv_tile_kernel(const bf16_t *__restrict__ in, const bf16_t *__restrict__ w, vo
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][f][v] = 0.f;
 
-    uint4 xreg[XROUNDS_MAX], wreg[WITEMS];
+    uint32_t xraw[XR][8];
+    u16x8 wreg[WITEMS];
 
-    auto prefetch = [&](int stage) {
-        const int chunk = stage / NSUB, sub = stage - chunk * NSUB;
+    // Global loads of the patch of one chunk; nothing here looks at what a load returns.
+    auto load_x = [&](int chunk) {
         const int c0 = chunk * 16;
-        if (sub == 0) {
+        if (c0 + 16 <= p.Cin) {
+            const bf16_t *src = in + (size_t)c0 * HWin;
 #pragma unroll
-            for (int rd = 0; rd < XROUNDS_MAX; ++rd) {
-                if (rd >= xrounds) break;
-                unsigned short e[8];
+            for (int rd = 0; rd < XR; ++rd) {
+                if (!WIDE && rd >= xrounds) break;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) xraw[rd][i] = load2_any(src + (size_t)i * HWin + xoff[rd]);
+            }
+        } else {   // the last chunk has fewer than 16 channels: clamp, store_x clears them
+#pragma unroll
+            for (int rd = 0; rd < XR; ++rd) {
+                if (!WIDE && rd >= xrounds) break;
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
-                    const int c = c0 + xo * 8 + i;
-                    e[i] = (xoff[rd] >= 0 && c < p.Cin) ? in[xoff[rd] + c * HWin] : (unsigned short)0;
+                    const int c = min(c0 + xo * 8 + i, p.Cin - 1);
+                    xraw[rd][i] = load2_any(in + (size_t)c * HWin + (xoff[rd] - xo8));
                 }
-                xreg[rd] = make_uint4(e[0] | ((uint32_t)e[1] << 16), e[2] | ((uint32_t)e[3] << 16),
-                                      e[4] | ((uint32_t)e[5] << 16), e[6] | ((uint32_t)e[7] << 16));
             }
         }
+    };
+    auto store_x = [&](int chunk, uint4 *xb) {
+        const int nvalid = p.Cin - chunk * 16 - xo * 8;
 #pragma unroll
-        for (int it = 0; it < WITEMS; ++it) {
-            const int e = it * 256 + tid;
-            uint4 val = make_uint4(0, 0, 0, 0);
-            if (STAGED) {
-                // packed filter: [chunk][tap][Mpad][16] in exactly the order of ws
-                const int tl = e / (KT * 2), rem = e - tl * (KT * 2), row = rem >> 1, o = rem & 1;
-                if (tl < TRES && k0 + row < p.Mpad) {
-                    const size_t src = ((size_t)(chunk * T + sub * TRES + tl) * p.Mpad + k0 + row) * 2 + o;
-                    val = reinterpret_cast<const uint4 *>(w)[src];
-                }
+        for (int rd = 0; rd < XR; ++rd) {
+            if (!WIDE && rd >= xrounds) break;
+            uint4 lo, hi;
+            lo.x = __builtin_amdgcn_perm(xraw[rd][1], xraw[rd][0], 0x05040100u);
+            lo.y = __builtin_amdgcn_perm(xraw[rd][3], xraw[rd][2], 0x05040100u);
+            lo.z = __builtin_amdgcn_perm(xraw[rd][5], xraw[rd][4], 0x05040100u);
+            lo.w = __builtin_amdgcn_perm(xraw[rd][7], xraw[rd][6], 0x05040100u);
+            hi.x = __builtin_amdgcn_perm(xraw[rd][1], xraw[rd][0], 0x07060302u);
+            hi.y = __builtin_amdgcn_perm(xraw[rd][3], xraw[rd][2], 0x07060302u);
+            hi.z = __builtin_amdgcn_perm(xraw[rd][5], xraw[rd][4], 0x07060302u);
+            hi.w = __builtin_amdgcn_perm(xraw[rd][7], xraw[rd][6], 0x07060302u);
+            if (nvalid < 8) { lo = keep_first(lo, nvalid); hi = keep_first(hi, nvalid); }
+            if (xdlo[rd] >= 0) xb[xdlo[rd]] = lo;
+            if (xdhi[rd] >= 0) xb[xdhi[rd]] = hi;
+        }
+    };
+
+    // Global loads of the filter slab of stage (chunk, sg).
+    auto load_w = [&](int chunk, int sg) {
+        if (STAGED) {
+            const uint4 *src = reinterpret_cast<const uint4 *>(w) +
+                               ((size_t)(chunk * NSUB + sg) * TRES * p.Mpad + k0) * 2;
+#pragma unroll
+            for (int it = 0; it < WITEMS; ++it) {
+                const int e = min(it * 256 + tid, WSZ - 1);
+                const int tl = e / (KT * 2), rem = e - tl * (KT * 2);
+                const uint4 v = src[(size_t)tl * p.Mpad * 2 + rem];
+                __builtin_memcpy(&wreg[it], &v, 16);
+            }
+        } else {
+            const int c0 = chunk * 16;
+            const int tapoff = p.tflip ? -sg * SG : sg * SG;
+            if (c0 + 16 <= p.Cin) {
+                const bf16_t *src = w + (ptrdiff_t)c0 * p.w_sr + tapoff;
+#pragma unroll
+                for (int it = 0; it < WITEMS; ++it)
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) wreg[it][i] = src[(size_t)i * p.w_sr + wsrc[it]];
             } else {
-                // gather from KCRS: lanes run over taps fastest so that they follow memory
-                int tl, row, o;
-                if (p.tflip) {  // backward-data: (tap, m) contiguous for one red
-                    tl = e % TRES; const int q = e / TRES; row = q % KT; o = q / KT;
-                } else {        // forward: (red, tap) contiguous for one m
-                    tl = e % TRES; const int q = e / TRES; o = q & 1; row = q >> 1;
-                }
-                if (e < TRES * KT * 2 && k0 + row < p.Kout) {
-                    const int tap = sub * TRES + tl;
-                    const int base = (k0 + row) * p.w_sm + (p.tflip ? T - 1 - tap : tap);
-                    unsigned short el[8];
+#pragma unroll
+                for (int it = 0; it < WITEMS; ++it) {
+                    const int o = STAGED ? 0 : ((wdst[it] & 1) ^ swz(wdst[it] >> 1));
 #pragma unroll
                     for (int i = 0; i < 8; ++i) {
-                        const int red = c0 + o * 8 + i;
-                        el[i] = red < p.Cin ? w[base + red * p.w_sr] : (unsigned short)0;
+                        const int red = min(c0 + o * 8 + i, p.Cin - 1);
+                        wreg[it][i] = w[(ptrdiff_t)red * p.w_sr + tapoff + (wsrc[it] - (uint32_t)(o * 8 * p.w_sr))];
                     }
-                    val = make_uint4(el[0] | ((uint32_t)el[1] << 16), el[2] | ((uint32_t)el[3] << 16),
-                                     el[4] | ((uint32_t)el[5] << 16), el[6] | ((uint32_t)el[7] << 16));
                 }
             }
-            wreg[it] = val;
         }
     };
-
-    auto stage_store = [&](int stage) {
-        const int sub = stage % NSUB;
-        if (sub == 0) {
-#pragma unroll
-            for (int rd = 0; rd < XROUNDS_MAX; ++rd) {
-                if (rd >= xrounds) break;
-                const int lp = rd * 128 + (tid & 127);
-                if (lp < xpix) xs[lp * 2 + (xo ^ swz(lp))] = xreg[rd];
-            }
-        }
+    auto store_w = [&](uint4 *wb) {
 #pragma unroll
         for (int it = 0; it < WITEMS; ++it) {
             const int e = it * 256 + tid;
-            int tl, row, o;
-            if (STAGED) {
-                tl = e / (KT * 2); const int rem = e - tl * (KT * 2); row = rem >> 1; o = rem & 1;
-            } else if (p.tflip) {
-                tl = e % TRES; const int q = e / TRES; row = q % KT; o = q / KT;
-            } else {
-                tl = e % TRES; const int q = e / TRES; o = q & 1; row = q >> 1;
+            if ((it + 1) * 256 <= WSZ || e < WSZ) {
+                uint4 v;
+                __builtin_memcpy(&v, &wreg[it], 16);
+                wb[STAGED ? e : wdst[it]] = v;
             }
-            if (e < TRES * KT * 2) ws[(tl * KT + row) * 2 + (o ^ swz(row))] = wreg[it];
         }
     };
 
-    auto compute = [&](int stage) {
-        const int sub = stage % NSUB;
-#pragma unroll
-        for (int tl = 0; tl < TRES; ++tl) {
-            const int tap = sub * TRES + tl;
-            const int r = tap / S, s = tap - r * S;
-            const int tapoff = r * p.LW + s;
-            bf16x8 a[2], b[4];
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const int row = wk * 64 + i * 32 + l32;
-                a[i] = *reinterpret_cast<const bf16x8 *>(&ws[(tl * KT + row) * 2 + (g ^ swz(row))]);
-            }
-#pragma unroll
-            for (int f = 0; f < 4; ++f) {
-                const int pix = pixbase[f] + tapoff;
-                b[f] = *reinterpret_cast<const bf16x8 *>(&xs[pix * 2 + (g ^ swz(pix))]);
-            }
+    // The MFMAs of one stage.  The LDS reads of tap t+1 are issued before the MFMAs of
+    // tap t, so their latency is covered by eight MFMAs.
+    auto compute = [&](const uint4 *xb, const uint4 *wb, int sg) {
+        bf16x8 a[2][2], b[2][NB];
+        auto read_tap = [&](int t) {
+            const int sl = t / R, r = t - sl * R, s = sg * SG + sl;
 #pragma unroll
             for (int i = 0; i < 2; ++i)
+                a[t & 1][i] = *reinterpret_cast<const bf16x8 *>(wb + ((r * SG + sl) * KT + i * 32) * 2 + aidx);
+            if (WIDE) {
+                if (r == 0) {
+                    const int slot = pixbase[0] + s;
+                    const uint4 *bp = xb + slot * 2 + (g ^ swz(slot));
 #pragma unroll
-                for (int f = 0; f < 4; ++f)
-                    acc[i][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[f], acc[i][f], 0, 0, 0);
+                    for (int j = 0; j < NB; ++j)
+                        b[sl & 1][j] = *reinterpret_cast<const bf16x8 *>(bp + j * WIDE_LWP * 2);
+                }
+            } else {
+#pragma unroll
+                for (int f = 0; f < 4; ++f) {
+                    const int slot = pixbase[f] + s;
+                    b[t & 1][f] = *reinterpret_cast<const bf16x8 *>(xb + (slot + r * LWp) * 2 + (g ^ swz(slot)));
+                }
+            }
+        };
+        read_tap(0);
+#pragma unroll
+        for (int t = 0; t < TRES; ++t) {
+            const int sl = t / R, r = t - sl * R;
+            if (t + 1 < TRES) read_tap(t + 1);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int f = 0; f < 4; ++f)
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+                    acc[i][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        WIDE ? b[sl & 1][f + r] : b[t & 1][f], a[t & 1][i], acc[i][f], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
-    const int nstage = p.nchunks * NSUB;
-    prefetch(0);
-    for (int stage = 0; stage < nstage; ++stage) {
-        __syncthreads();
-        stage_store(stage);
-        __syncthreads();
-        if (stage + 1 < nstage) prefetch(stage + 1);
-        compute(stage);
+    load_x(0);
+    load_w(0, 0);
+    __syncthreads();   // the zero fill is complete
+    store_x(0, xs);
+    store_w(ws);
+    int wpar = 0;
+    // Every stage issues the same loads and stores, so that the wait counters are exact:
+    // past the end they fetch the last stage / chunk again, into a buffer nobody reads.
+    for (int chunk = 0; chunk < p.nchunks; ++chunk) {
+        const int cnext = min(chunk + 1, p.nchunks - 1);
+        uint4 *const xcur = xs + (chunk & 1) * XS, *const xnext = xs + ((chunk + 1) & 1) * XS;
+        if (!WIDE) {
+            // keeps the per-tap operand addresses from being hoisted out of the loop into registers
+#pragma unroll
+            for (int f = 0; f < (WIDE ? 1 : 4); ++f) asm volatile("" : "+v"(pixbase[f]));
+        }
+#pragma unroll
+        for (int sg = 0; sg < NSUB; ++sg) {
+            __syncthreads();
+            if (sg + 1 < NSUB) load_w(chunk, sg + 1);
+            else load_w(cnext, chunk + 1 < p.nchunks ? 0 : NSUB - 1);
+            if (sg == 0) load_x(cnext);
+            __builtin_amdgcn_sched_barrier(0);   // the loads stay ahead of the MFMAs
+            compute(xcur, ws + wpar * WSZ, sg);
+            __builtin_amdgcn_sched_barrier(0);
+            wpar ^= 1;
+            store_w(ws + wpar * WSZ);
+            if (sg == NSUB - 1) store_x(cnext, xnext);
+        }
     }
 
-    // ---- epilogue: a 32x32 tile keeps column (lane % 32), rows 8*(v/4) + 4*(lane/32) + v%4
+    // ---- epilogue.  The MFMAs take the pixels as rows, so a lane holds, for output
+    // channel lane % 32 of a tile, the pixels 8*(v/4) + 4*(lane/32) + v%4: four
+    // consecutive pixels per group of four registers.
     const int PQ = p.Pout * p.Qout;
+    auto pix_off = [&](int i) -> int {   // offset of pixel i of the tile in channel 0, -1: not an output
+        const int rl = i / p.TW, cl = i - rl * p.TW;
+        const int o = o0 + rl;
+        if (!(rl < p.TH && o < NP && q0 + cl < p.Qout)) return -1;
+        const int n = o / p.Pout, pp = o - n * p.Pout;
+        return (n * p.Kout * p.Pout + pp) * p.Qout + q0 + cl;
+    };
+    if (p.out_bf16) {
+        // bf16: through LDS, 32 channels x 128 pixels per wave and pass, so that a lane
+        // writes 8 consecutive pixels of one channel with one 16-byte store
+        constexpr int EP = EPI_PITCH;
+        __syncthreads();   // the last stage has been read
+        char *const stage = reinterpret_cast<char *>(smem) + wave * 32 * EP;
+        const int oct = lane & 15, krow = lane >> 4;
+        const int i0 = wp * 128 + oct * 8;
+        const int off0 = pix_off(i0), off7 = pix_off(i0 + 7);
+        const bool contig = off0 >= 0 && off7 == off0 + 7;
+        int eoff[8];
+        bool any = false;
+        if (!contig) {
 #pragma unroll
-    for (int f = 0; f < 4; ++f) {
-        if (outoff[f] < 0) continue;
+            for (int e = 0; e < 8; ++e) { eoff[e] = pix_off(i0 + e); any = any || eoff[e] >= 0; }
+        }
+        bf16_t *const o16 = reinterpret_cast<bf16_t *>(out);
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < 2; ++i) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int k = k0 + wk * 64 + i * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+            for (int f = 0; f < 4; ++f)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    uint2 v;
+                    v.x = pack2_bf16(acc[i][f][4 * j], acc[i][f][4 * j + 1]);
+                    v.y = pack2_bf16(acc[i][f][4 * j + 2], acc[i][f][4 * j + 3]);
+                    *reinterpret_cast<uint2 *>(stage + l32 * EP + (f * 32 + 8 * j + 4 * g) * 2) = v;
+                }
+            __syncthreads();
+#pragma unroll
+            for (int rd = 0; rd < 8; ++rd) {
+                const int kl = rd * 4 + krow, k = k0 + wk * 64 + i * 32 + kl;
+                const uint4 v = *reinterpret_cast<const uint4 *>(stage + kl * EP + oct * 16);
                 if (k >= p.Kout) continue;
-                const int off = outoff[f] + k * PQ;
-                if (p.out_bf16) reinterpret_cast<bf16_t *>(out)[off] = f32_to_bf16(acc[i][f][v]);
-                else reinterpret_cast<float *>(out)[off] = acc[i][f][v];
+                if (contig) {
+                    store8_any(o16 + (size_t)k * PQ + off0, v);
+                } else if (any) {
+                    const uint32_t d[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (eoff[e] >= 0) o16[(size_t)k * PQ + eoff[e]] = (bf16_t)(d[e >> 1] >> (16 * (e & 1)));
+                }
             }
+            if (i == 0) __syncthreads();
+        }
+    } else {
+        float *const o32 = reinterpret_cast<float *>(out);
+#pragma unroll
+        for (int f = 0; f < 4; ++f)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int off = pix_off((wp * 4 + f) * 32 + 8 * j + 4 * g + e);
+                    if (off < 0) continue;
+#pragma unroll
+                    for (int i = 0; i < 2; ++i) {
+                        const int k = k0 + wk * 64 + i * 32 + l32;
+                        if (k < p.Kout) o32[(size_t)k * PQ + off] = acc[i][f][4 * j + e];
+                    }
+                }
     }
 }
 
-// Packs A(m, red, tap) into [chunk = red/16][tap][Mpad][16], zero padded, which is
-// the order the kernel's filter slab has in LDS.
+// Packs A(m, red, tap) into [chunk = red/16][stage][tap of the stage][Mpad][16],
+// zero padded, the two 8-channel halves of a row swapped where the LDS swizzle
+// swaps them: a stage's slab is copied to LDS as it is.
 __global__ void __launch_bounds__(256)
-pack_filter_kernel(const bf16_t *__restrict__ w, bf16_t *__restrict__ wp, int M, int RED, int T, int w_sm,
-                   int w_sr, int tflip, int Mpad, size_t total)
+pack_filter_kernel(const bf16_t *__restrict__ w, bf16_t *__restrict__ wp, int M, int RED, int R, int S, int SG,
+                   int w_sm, int w_sr, int tflip, int Mpad, size_t total)
 {
     const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (e >= total) return;
-    const int j = (int)(e & 15);
+    const int j = (int)(e & 7), hs = (int)((e >> 3) & 1);
     size_t q = e >> 4;
     const int m = (int)(q % Mpad);
     q /= Mpad;
-    const int tap = (int)(q % T), chunk = (int)(q / T);
-    const int red = chunk * 16 + j;
+    const int TRES = R * SG, NSUB = S / SG;
+    const int tl = (int)(q % TRES);
+    q /= TRES;
+    const int sg = (int)(q % NSUB), chunk = (int)(q / NSUB);
+    const int r = tl / SG, s = sg * SG + tl % SG, tap = r * S + s, T = R * S;
+    const int red = chunk * 16 + (hs ^ swz(m)) * 8 + j;
     bf16_t v = 0;
     if (m < M && red < RED) v = w[(size_t)m * w_sm + (size_t)red * w_sr + (tflip ? T - 1 - tap : tap)];
     wp[e] = v;
@@ -301,45 +507,65 @@ pack_filter_kernel(const bf16_t *__restrict__ w, bf16_t *__restrict__ wp, int M,
 struct Plan {
     TileProblem p;
     int KT;
+    bool wide;
+    size_t lds;
     dim3 grid;
 };
 
-// Tiling for one problem; false if the patch would not fit the LDS budget.
+// Tiling for one problem; false if the patch would not fit in LDS.
 bool make_plan(const TileProblem &base, int R, int S, Plan *pl)
 {
     TileProblem p = base;
     const int KT = p.Kout <= 64 ? 64 : 128;
     const int PIXT = KT == 128 ? 256 : 512;
     const long long NP = (long long)p.N * p.Pout;
-    long long nrowtiles;
-    int lrows_max;
-    if (p.Qout <= 64) {
+    long long nrowtiles = 0;
+    bool wide = p.Qout > 64;
+    if (!wide) {
+        // pixels of the tile that are real outputs, per tiling
+        const int th = PIXT / p.Qout;
+        const double eff_narrow = (double)th * p.Qout / PIXT;
+        const int ct = (p.Qout + 31) / 32;
+        const double eff_wide = (double)p.Qout / (ct * 32);
+        wide = eff_wide >= eff_narrow && p.Pout >= PIXT / 32;
+    }
+    if (!wide) {
         p.TW = p.Qout;
         p.TH = PIXT / p.Qout;
         p.ncoltiles = 1;
         p.tiles_per_img = 0;
         if (p.TH > NP) p.TH = (int)NP;
         nrowtiles = (NP + p.TH - 1) / p.TH;
+        p.LW = p.TW + S - 1;
+        p.LWp = (p.LW + 15) / 16 * 16;
         // most patch rows a tile can need: TH rows, one halo, and one more halo per image boundary inside it
         const int crossings = p.N > 1 ? (p.TH - 1) / p.Pout + 1 : 0;
-        lrows_max = p.TH + (crossings + 1) * (R - 1);
+        const int lrows_max = p.TH + (crossings + 1) * (R - 1);
+        if ((long long)lrows_max * ((p.LW + 1) / 2) > XPAIRS_MAX) return false;
+        p.xslots = lrows_max * p.LWp;
     } else {
         p.TW = 32;
         p.TH = PIXT / 32;
         p.ncoltiles = (p.Qout + 31) / 32;
+        p.xslots = (p.TH + R - 1) * WIDE_LWP;
         if (p.TH > p.Pout) p.TH = p.Pout;
         p.tiles_per_img = (p.Pout + p.TH - 1) / p.TH;
         nrowtiles = (long long)p.N * p.tiles_per_img;
-        lrows_max = p.TH + R - 1;
+        p.LW = p.TW + S - 1;
+        p.LWp = WIDE_LWP;
+        if (p.LW > WIDE_LWP) return false;
     }
-    p.LW = p.TW + S - 1;
     p.Hp = p.Pout + R - 1;
-    if ((long long)lrows_max * p.LW > XPIX_MAX) return false;
     p.nchunks = (p.Cin + 15) / 16;
-    p.Mpad = (p.Kout + 63) / 64 * 64;
+    p.Mpad = (p.Kout + KT - 1) / KT * KT;
+    size_t lds = ((size_t)2 * p.xslots * 2 + (size_t)2 * R * sg_of(R, S) * KT * 2) * 16;
+    if (lds < (size_t)4 * 32 * EPI_PITCH) lds = (size_t)4 * 32 * EPI_PITCH;   // the epilogue's staging
+    if (lds > (size_t)LDS_LIMIT) return false;
     if (nrowtiles * p.ncoltiles > 0x7fffffffLL) return false;
     pl->p = p;
     pl->KT = KT;
+    pl->wide = wide;
+    pl->lds = lds;
     pl->grid = dim3((unsigned)(nrowtiles * p.ncoltiles), (p.Kout + KT - 1) / KT, 1);
     return true;
 }
@@ -347,6 +573,7 @@ bool make_plan(const TileProblem &base, int R, int S, Plan *pl)
 bool problem_of(const ConvGeom &g, bool bwd_data, TileProblem *p)
 {
     if (!g.in_bf16 || g.sh != 1 || g.sw != 1) return false;
+    if (g.W < 2 || g.Q < 2) return false;   // the patch gather loads pixel pairs inside a row
     const long long lim = 0x7fffffffLL;
     if ((long long)g.N * g.C * g.H * g.W > lim || (long long)g.N * g.K * g.P * g.Q > lim) return false;
     if ((long long)g.K * g.C * g.R * g.S > lim) return false;
@@ -365,18 +592,35 @@ bool problem_of(const ConvGeom &g, bool bwd_data, TileProblem *p)
     return true;
 }
 
+template <int R, int S, int KT, bool STAGED, bool WIDE>
+hipError_t launch_one(const bf16_t *in, const bf16_t *w, void *out, const Plan &pl, hipStream_t st)
+{
+    auto kern = conv_tile_kernel<R, S, KT, STAGED, WIDE>;
+    static bool attr_set = false;   // the limit of dynamic LDS is a property of the kernel, set once
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_LIMIT);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, pl.grid, dim3(256), pl.lds, st, in, w, out, pl.p);
+    return hipGetLastError();
+}
+
 template <int R, int S>
 hipError_t launch_rs(const bf16_t *in, const bf16_t *w, void *out, const Plan &pl, bool staged, hipStream_t st)
 {
-    dim3 block(256);
-    if (pl.KT == 128) {
-        if (staged) hipLaunchKernelGGL((conv_tile_kernel<R, S, 128, true>), pl.grid, block, 0, st, in, w, out, pl.p);
-        else hipLaunchKernelGGL((conv_tile_kernel<R, S, 128, false>), pl.grid, block, 0, st, in, w, out, pl.p);
-    } else {
-        if (staged) hipLaunchKernelGGL((conv_tile_kernel<R, S, 64, true>), pl.grid, block, 0, st, in, w, out, pl.p);
-        else hipLaunchKernelGGL((conv_tile_kernel<R, S, 64, false>), pl.grid, block, 0, st, in, w, out, pl.p);
+    const int sel = (pl.KT == 128 ? 4 : 0) | (staged ? 2 : 0) | (pl.wide ? 1 : 0);
+    switch (sel) {
+    case 0: return launch_one<R, S, 64, false, false>(in, w, out, pl, st);
+    case 1: return launch_one<R, S, 64, false, true>(in, w, out, pl, st);
+    case 2: return launch_one<R, S, 64, true, false>(in, w, out, pl, st);
+    case 3: return launch_one<R, S, 64, true, true>(in, w, out, pl, st);
+    case 4: return launch_one<R, S, 128, false, false>(in, w, out, pl, st);
+    case 5: return launch_one<R, S, 128, false, true>(in, w, out, pl, st);
+    case 6: return launch_one<R, S, 128, true, false>(in, w, out, pl, st);
+    default: return launch_one<R, S, 128, true, true>(in, w, out, pl, st);
     }
-    return hipGetLastError();
 }
 
 bool filter_supported(int R, int S)
@@ -411,11 +655,10 @@ hipError_t launch_tile_conv(const void *in, const void *w, void *out, const Conv
         return hipErrorInvalidValue;
     const bf16_t *wsrc = static_cast<const bf16_t *>(w);
     if (packed) {
-        const int T = g.R * g.S;
-        const size_t total = (size_t)pl.p.nchunks * T * pl.p.Mpad * 16;
+        const size_t total = (size_t)pl.p.nchunks * g.R * g.S * pl.p.Mpad * 16;
         hipLaunchKernelGGL(pack_filter_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, wsrc,
-                           static_cast<bf16_t *>(packed), pl.p.Kout, pl.p.Cin, T, pl.p.w_sm, pl.p.w_sr,
-                           pl.p.tflip, pl.p.Mpad, total);
+                           static_cast<bf16_t *>(packed), pl.p.Kout, pl.p.Cin, g.R, g.S, sg_of(g.R, g.S),
+                           pl.p.w_sm, pl.p.w_sr, pl.p.tflip, pl.p.Mpad, total);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         wsrc = static_cast<const bf16_t *>(packed);
