@@ -47,6 +47,9 @@
 // workspace in exactly the LDS order, swizzle included (STAGED algorithm: a
 // stage is one contiguous run of 16-byte loads), or is gathered from the KCRS
 // tensor with 2-byte loads (DIRECT, no workspace).
+#include <type_traits>
+#include <utility>
+
 #include "sn_internal.h"
 
 namespace sn {
@@ -55,6 +58,7 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int XPAIRS_MAX = 384;  // NARROW: pixel pairs gathered per chunk
 constexpr int WIDE_LWP = 48;    // WIDE: padded patch row (32 + S - 1 <= 48)
@@ -74,6 +78,16 @@ struct TileProblem {
     int w_sm, w_sr, tflip;
     int Mpad;                // rows per (chunk, tap) block of the packed filter
 };
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>)
+template <typename F, int... I> __device__ inline void static_for_impl(F &&f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F> __device__ inline void static_for(F &&f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
 
 // Filter columns per stage: a 1xS filter has too little work per column.
 constexpr int sg_of(int R, int S) { return (R == 1 && S > 1) ? S : 1; }
@@ -122,7 +136,7 @@ conv_tile_kernel(const bf16_t *__restrict__ in, const bf16_t *__restrict__ w, vo
     constexpr int NB = WIDE ? 4 + R - 1 : 4;
     extern __shared__ __attribute__((aligned(16))) uint4 smem[];
     const int XS = p.xslots * 2;                       // 16-byte items of one patch buffer
-    uint4 *const xs = smem, *const ws = smem + 2 * XS;
+    uint4 *const xs = smem;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, g = lane >> 5;
@@ -167,7 +181,6 @@ conv_tile_kernel(const bf16_t *__restrict__ in, const bf16_t *__restrict__ w, vo
     int xdlo[XR], xdhi[XR];  // 16-byte LDS index for the low / high halves, -1: not stored
     const int LWh = (p.LW + 1) >> 1;
     const int xpairs = lrows * LWh;
-    const int xrounds = WIDE ? XR : (xpairs + 127) >> 7;
 #pragma unroll
     for (int rd = 0; rd < XR; ++rd) {
         const int lp = rd * 128 + tp;
@@ -242,7 +255,7 @@ conv_tile_kernel(const bf16_t *__restrict__ in, const bf16_t *__restrict__ w, vo
             for (int v = 0; v < 16; ++v) acc[i][f][v] = 0.f;
 
     uint32_t xraw[XR][8];
-    u16x8 wreg[WITEMS];
+    u16x8 wreg[STAGED ? 1 : WITEMS];
 
     // Global loads of the patch of one chunk; nothing here looks at what a load returns.
     auto load_x = [&](int chunk) {
@@ -251,14 +264,12 @@ conv_tile_kernel(const bf16_t *__restrict__ in, const bf16_t *__restrict__ w, vo
             const bf16_t *src = in + (size_t)c0 * HWin;
 #pragma unroll
             for (int rd = 0; rd < XR; ++rd) {
-                if (!WIDE && rd >= xrounds) break;
 #pragma unroll
                 for (int i = 0; i < 8; ++i) xraw[rd][i] = load2_any(src + (size_t)i * HWin + xoff[rd]);
             }
         } else {   // the last chunk has fewer than 16 channels: clamp, store_x clears them
 #pragma unroll
             for (int rd = 0; rd < XR; ++rd) {
-                if (!WIDE && rd >= xrounds) break;
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
                     const int c = min(c0 + xo * 8 + i, p.Cin - 1);
@@ -271,7 +282,6 @@ conv_tile_kernel(const bf16_t *__restrict__ in, const bf16_t *__restrict__ w, vo
         const int nvalid = p.Cin - chunk * 16 - xo * 8;
 #pragma unroll
         for (int rd = 0; rd < XR; ++rd) {
-            if (!WIDE && rd >= xrounds) break;
             uint4 lo, hi;
             lo.x = __builtin_amdgcn_perm(xraw[rd][1], xraw[rd][0], 0x05040100u);
             lo.y = __builtin_amdgcn_perm(xraw[rd][3], xraw[rd][2], 0x05040100u);
@@ -333,47 +343,99 @@ conv_tile_kernel(const bf16_t *__restrict__ in, const bf16_t *__restrict__ w, vo
         }
     };
 
-    // The MFMAs of one stage.  The LDS reads of tap t+1 are issued before the MFMAs of
-    // tap t, so their latency is covered by eight MFMAs.
+    // The MFMAs of one stage.
     auto compute = [&](const uint4 *xb, const uint4 *wb, int sg) {
-        bf16x8 a[2][2], b[2][NB];
-        auto read_tap = [&](int t) {
-            const int sl = t / R, r = t - sl * R, s = sg * SG + sl;
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
-                a[t & 1][i] = *reinterpret_cast<const bf16x8 *>(wb + ((r * SG + sl) * KT + i * 32) * 2 + aidx);
+        for (int sl = 0; sl < SG; ++sl) {
+            const int s = sg * SG + sl;
+            bf16x8 b[NB];
             if (WIDE) {
-                if (r == 0) {
-                    const int slot = pixbase[0] + s;
-                    const uint4 *bp = xb + slot * 2 + (g ^ swz(slot));
+                const int slot = pixbase[0] + s;
+                const uint4 *bp = xb + slot * 2 + (g ^ swz(slot));
 #pragma unroll
-                    for (int j = 0; j < NB; ++j)
-                        b[sl & 1][j] = *reinterpret_cast<const bf16x8 *>(bp + j * WIDE_LWP * 2);
-                }
-            } else {
-#pragma unroll
-                for (int f = 0; f < 4; ++f) {
-                    const int slot = pixbase[f] + s;
-                    b[t & 1][f] = *reinterpret_cast<const bf16x8 *>(xb + (slot + r * LWp) * 2 + (g ^ swz(slot)));
-                }
+                for (int j = 0; j < NB; ++j) b[j] = *reinterpret_cast<const bf16x8 *>(bp + j * WIDE_LWP * 2);
             }
-        };
-        read_tap(0);
 #pragma unroll
-        for (int t = 0; t < TRES; ++t) {
-            const int sl = t / R, r = t - sl * R;
-            if (t + 1 < TRES) read_tap(t + 1);
-            __builtin_amdgcn_sched_barrier(0);
+            for (int r = 0; r < R; ++r) {
+                if (!WIDE) {
 #pragma unroll
-            for (int f = 0; f < 4; ++f)
+                    for (int f = 0; f < 4; ++f) {
+                        const int slot = pixbase[f] + s;
+                        b[f] = *reinterpret_cast<const bf16x8 *>(xb + (slot + r * LWp) * 2 + (g ^ swz(slot)));
+                    }
+                }
+                bf16x8 a[2];
 #pragma unroll
                 for (int i = 0; i < 2; ++i)
-                    acc[i][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        WIDE ? b[sl & 1][f + r] : b[t & 1][f], a[t & 1][i], acc[i][f], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
+                    a[i] = *reinterpret_cast<const bf16x8 *>(wb + ((r * SG + sl) * KT + i * 32) * 2 + aidx);
+#pragma unroll
+                for (int f = 0; f < 4; ++f)
+#pragma unroll
+                    for (int i = 0; i < 2; ++i)
+                        acc[i][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WIDE ? b[f + r] : b[f], a[i], acc[i][f], 0, 0, 0);
+            }
         }
     };
 
+    if constexpr (STAGED) {
+        // Packed filter: the slab of a stage is fetched two stages ahead into one of two
+        // register sets (the set of a stage is its parity; two chunks are unrolled so that
+        // the parity is known at compile time), and written to LDS one stage ahead.  The
+        // patch of the next chunk is fetched during the first stage of a chunk and written
+        // after its last.  Loads complete in order: a stage waits for the slab issued one
+        // stage ago while the loads issued since stay in flight.  Every stage issues the
+        // same loads, so the counts are exact; past the end they fetch the last slab / chunk
+        // again, and what they bring is written to a buffer nobody reads.
+        uint4 *const ws = smem + 2 * XS;
+        const int nstage = p.nchunks * NSUB;
+        u32x4 wr[2][WITEMS];
+        auto load_ws = [&](int stage, u32x4(&dst)[WITEMS]) {
+            const int st = min(stage, nstage - 1);
+            const u32x4 *src = reinterpret_cast<const u32x4 *>(w) + ((size_t)st * TRES * p.Mpad + k0) * 2;
+#pragma unroll
+            for (int it = 0; it < WITEMS; ++it) {
+                const int e = min(it * 256 + tid, WSZ - 1);
+                const int tl = e / (KT * 2), rem = e - tl * (KT * 2);
+                dst[it] = src[(size_t)tl * p.Mpad * 2 + rem];
+            }
+        };
+        auto store_ws = [&](uint4 *wb, const u32x4(&srcr)[WITEMS]) {
+#pragma unroll
+            for (int it = 0; it < WITEMS; ++it) {
+                const int e = it * 256 + tid;
+                if ((it + 1) * 256 <= WSZ || e < WSZ) reinterpret_cast<u32x4 *>(wb)[e] = srcr[it];
+            }
+        };
+        load_ws(0, wr[0]);
+        load_ws(1, wr[1]);
+        load_x(0);
+        __syncthreads();   // the zero fill is complete
+        store_x(0, xs);
+        store_ws(ws, wr[0]);
+        for (int chunk0 = 0; chunk0 < p.nchunks; chunk0 += 2) {
+            static_for<2 * NSUB>([&](auto idx) {
+                constexpr int c = decltype(idx)::value / NSUB, sg = decltype(idx)::value % NSUB;
+                constexpr int par = decltype(idx)::value & 1;   // parity of the stage
+                const int chunk = chunk0 + c;
+                const int cnext = min(chunk + 1, p.nchunks - 1);
+                uint4 *const xcur = xs + c * XS, *const xnext = xs + (c ^ 1) * XS;
+                __syncthreads();
+                if (!WIDE) {
+                    // keeps the operand addresses of later stages from being worked out early
+#pragma unroll
+                    for (int f = 0; f < (WIDE ? 1 : 4); ++f) asm volatile("" : "+v"(pixbase[f]));
+                }
+                load_ws(chunk * NSUB + sg + 2, wr[par]);
+                if (sg == 0) load_x(cnext);
+                __builtin_amdgcn_sched_barrier(0);   // the loads stay ahead of the MFMAs
+                if (chunk < p.nchunks) compute(xcur, ws + par * WSZ, sg);
+                __builtin_amdgcn_sched_barrier(0);
+                store_ws(ws + (par ^ 1) * WSZ, wr[par ^ 1]);
+                if (sg == NSUB - 1) store_x(cnext, xnext);
+            });
+        }
+    } else {
+    uint4 *const ws = smem + 2 * XS;
     load_x(0);
     load_w(0, 0);
     __syncthreads();   // the zero fill is complete
@@ -403,6 +465,7 @@ conv_tile_kernel(const bf16_t *__restrict__ in, const bf16_t *__restrict__ w, vo
             store_w(ws + wpar * WSZ);
             if (sg == NSUB - 1) store_x(cnext, xnext);
         }
+    }
     }
 
     // ---- epilogue.  The MFMAs take the pixels as rows, so a lane holds, for output
@@ -513,7 +576,7 @@ struct Plan {
 };
 
 // Tiling for one problem; false if the patch would not fit in LDS.
-bool make_plan(const TileProblem &base, int R, int S, Plan *pl)
+bool make_plan(const TileProblem &base, int R, int S, bool staged, Plan *pl)
 {
     TileProblem p = base;
     const int KT = p.Kout <= 64 ? 64 : 128;
@@ -635,14 +698,15 @@ bool tile_conv_supported(const ConvGeom &g, bool bwd_data)
 {
     TileProblem p;
     Plan pl;
-    return filter_supported(g.R, g.S) && problem_of(g, bwd_data, &p) && make_plan(p, g.R, g.S, &pl);
+    return filter_supported(g.R, g.S) && problem_of(g, bwd_data, &p) && make_plan(p, g.R, g.S, false, &pl) &&
+           make_plan(p, g.R, g.S, true, &pl);
 }
 
 size_t tile_conv_packed_bytes(const ConvGeom &g, bool bwd_data)
 {
     TileProblem p;
     Plan pl;
-    if (!filter_supported(g.R, g.S) || !problem_of(g, bwd_data, &p) || !make_plan(p, g.R, g.S, &pl)) return 0;
+    if (!tile_conv_supported(g, bwd_data) || !problem_of(g, bwd_data, &p) || !make_plan(p, g.R, g.S, true, &pl)) return 0;
     return align_up((size_t)pl.p.nchunks * g.R * g.S * pl.p.Mpad * 16 * sizeof(bf16_t), 256);
 }
 
@@ -651,7 +715,8 @@ hipError_t launch_tile_conv(const void *in, const void *w, void *out, const Conv
 {
     TileProblem p;
     Plan pl;
-    if (!filter_supported(g.R, g.S) || !problem_of(g, bwd_data, &p) || !make_plan(p, g.R, g.S, &pl))
+    if (!tile_conv_supported(g, bwd_data) || !problem_of(g, bwd_data, &p) ||
+        !make_plan(p, g.R, g.S, packed != nullptr, &pl))
         return hipErrorInvalidValue;
     const bf16_t *wsrc = static_cast<const bf16_t *>(w);
     if (packed) {
