@@ -31,8 +31,6 @@
 // i and are written to the other buffer half way through them; one barrier per
 // chunk.  With a single wave per SIMD every non-MFMA instruction costs issue
 // time, so everything that depends only on the thread is worked out once.
-#include <cstdlib>
-
 #include "sn_internal.h"
 
 namespace sn {
@@ -488,7 +486,6 @@ bool make_wplan(const ConvGeom &g, WPlan *pl)
     const long long tiles = (long long)p.ctiles * nrg * ktiles;
     // slices: about two workgroups per CU in all; every slice costs a pass over dw in the epilogue
     long long slices = (512 + tiles - 1) / tiles;
-    if (const char *dbg = getenv("SN_WGRAD_SLICES")) slices = atoi(dbg);
     if (slices > p.nchunks) slices = p.nchunks;
     if (slices > 65535) slices = 65535;
     if (slices < 1) slices = 1;
@@ -530,11 +527,12 @@ hipError_t launch_cfg(const bf16_t *x, const bf16_t *dy, float *out, int atomics
 bool tile_wgrad_supported(const ConvGeom &g)
 {
     WPlan pl;
-    return make_wplan(g, &pl);
+    return rows_wgrad_supported(g) || make_wplan(g, &pl);
 }
 
 int tile_wgrad_slices(const ConvGeom &g)
 {
+    if (rows_wgrad_supported(g)) return rows_wgrad_slices(g);
     WPlan pl;
     return make_wplan(g, &pl) ? (int)pl.grid.z : 0;
 }
@@ -544,6 +542,7 @@ int tile_wgrad_slices(const ConvGeom &g)
 hipError_t launch_tile_wgrad(const void *x, const void *dy, float *dw, const ConvGeom &g, float *partial,
                              hipStream_t st)
 {
+    if (rows_wgrad_supported(g)) return launch_rows_wgrad(x, dy, dw, g, partial, st);
     WPlan pl;
     if (!make_wplan(g, &pl)) return hipErrorInvalidValue;
     const size_t nw = (size_t)g.K * g.C * g.R * g.S;

@@ -64,6 +64,12 @@ int tile_wgrad_slices(const ConvGeom &g);
 hipError_t launch_tile_wgrad(const void *x, const void *dy, float *dw, const ConvGeom &g, float *partial,
                              hipStream_t st);
 
+// The row-stationary variant for 3x3 / 1x1 filters (same contract); launch_tile_wgrad prefers it.
+bool rows_wgrad_supported(const ConvGeom &g);
+int rows_wgrad_slices(const ConvGeom &g);
+hipError_t launch_rows_wgrad(const void *x, const void *dy, float *dw, const ConvGeom &g, float *partial,
+                             hipStream_t st);
+
 hipError_t launch_fill_zero(float *p, size_t n, hipStream_t st);
 // dw[i] = (accumulate ? dw[i] : 0) + sum_z partial[z][i], z ascending.
 hipError_t launch_reduce_partials(const float *partial, float *dw, size_t n, int splits, bool accumulate,
