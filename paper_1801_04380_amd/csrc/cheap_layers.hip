@@ -505,11 +505,118 @@ maxpool_bwd_kernel(const T *__restrict__ dy, const int32_t *__restrict__ idx, T 
     st(dx + e, acc);
 }
 
+// 2x2 windows, stride 2, no padding (the pool of the VGG-style workloads): windows do not
+// overlap, so a thread owns 8 neighbouring windows of one output row and moves whole
+// vectors: forward it reads 16 columns of the two input rows, backward it writes 8 columns
+// of the two rows under its 4 windows (and the uncovered last row of an odd-height image).
+// Threads of a workgroup are (output row, group of windows), the groups padded to a power
+// of two, so that no thread needs a 64-bit division.
+template <typename T, int NEL> struct __attribute__((packed, aligned(sizeof(T)))) Pack { T e[NEL]; };
+
+template <typename T>
+__global__ void __launch_bounds__(256)
+maxpool2_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, int32_t *__restrict__ idx, unsigned rows, int H,
+                    int W, int P, int Q, int lg)
+{
+    const unsigned row = blockIdx.x * (256u >> lg) + (threadIdx.x >> lg);
+    const int g = threadIdx.x & ((1 << lg) - 1);
+    if (row >= rows || g * 8 >= Q) return;
+    const unsigned nc = row / (unsigned)P;
+    const int p = (int)(row - nc * (unsigned)P);
+    const T *r0 = x + ((size_t)nc * H + 2 * p) * W + 16 * g, *r1 = r0 + W;
+    T *yo = y + (size_t)row * Q + 8 * g;
+    int32_t *io = idx + (size_t)row * Q + 8 * g;
+    const int base = 2 * p * W + 16 * g;
+    const int nout = min(8, Q - 8 * g);
+    Pack<T, 16> a, b;
+    if (nout == 8) {
+        a = *reinterpret_cast<const Pack<T, 16> *>(r0);
+        b = *reinterpret_cast<const Pack<T, 16> *>(r1);
+    } else {
+        for (int j = 0; j < 2 * nout; ++j) { a.e[j] = r0[j]; b.e[j] = r1[j]; }
+    }
+    Pack<T, 8> out;
+    Pack<int32_t, 8> oi;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        // row-major scan of the window, a later element wins only if strictly greater
+        T raw = a.e[2 * j];
+        float bv = ld<T>(&raw);
+        int best = base + 2 * j;
+        float f = ld<T>(&a.e[2 * j + 1]);
+        if (f > bv) { bv = f; best = base + 2 * j + 1; raw = a.e[2 * j + 1]; }
+        f = ld<T>(&b.e[2 * j]);
+        if (f > bv) { bv = f; best = base + W + 2 * j; raw = b.e[2 * j]; }
+        f = ld<T>(&b.e[2 * j + 1]);
+        if (f > bv) { bv = f; best = base + W + 2 * j + 1; raw = b.e[2 * j + 1]; }
+        out.e[j] = raw;
+        oi.e[j] = best;
+    }
+    if (nout == 8) {
+        *reinterpret_cast<Pack<T, 8> *>(yo) = out;
+        *reinterpret_cast<Pack<int32_t, 8> *>(io) = oi;
+    } else {
+        for (int j = 0; j < nout; ++j) { yo[j] = out.e[j]; io[j] = oi.e[j]; }
+    }
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256)
+maxpool2_bwd_kernel(const T *__restrict__ dy, const int32_t *__restrict__ idx, T *__restrict__ dx, unsigned rows,
+                    int H, int W, int P, int Q, int lg)
+{
+    const unsigned row = blockIdx.x * (256u >> lg) + (threadIdx.x >> lg);
+    const int g = threadIdx.x & ((1 << lg) - 1);
+    if (row >= rows || g * 8 >= W) return;
+    const unsigned nc = row / (unsigned)P;
+    const int p = (int)(row - nc * (unsigned)P);
+    const size_t wrow = (size_t)row * Q + 4 * g;
+    const int nwin = max(0, min(4, Q - 4 * g));
+    Pack<T, 4> d;
+    Pack<int32_t, 4> wi;
+    if (nwin == 4) {
+        d = *reinterpret_cast<const Pack<T, 4> *>(dy + wrow);
+        wi = *reinterpret_cast<const Pack<int32_t, 4> *>(idx + wrow);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            wi.e[j] = -1;
+            d.e[j] = T(0);
+            if (j < nwin) { wi.e[j] = idx[wrow + j]; d.e[j] = dy[wrow + j]; }
+        }
+    }
+    const int ncol = min(8, W - 8 * g);
+    const int hlast = (p == P - 1) ? H - 1 : 2 * p + 1;   // an odd height leaves one row without a window
+    for (int h = 2 * p; h <= hlast; ++h) {
+        Pack<T, 8> out;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) out.e[c] = wi.e[c >> 1] == h * W + 8 * g + c ? d.e[c >> 1] : T(0);
+        T *o = dx + ((size_t)nc * H + h) * W + 8 * g;
+        if (ncol == 8) *reinterpret_cast<Pack<T, 8> *>(o) = out;
+        else
+            for (int c = 0; c < ncol; ++c) o[c] = out.e[c];
+    }
+}
+
 template <typename F> hipError_t by_dtype(int bf16, F f)
 {
     if (bf16) f((bf16_t *)nullptr);
     else f((float *)nullptr);
     return hipGetLastError();
+}
+
+// The 2x2 / stride 2 / unpadded kernels apply, and their row count and group count fit.
+bool pool2_fast(int NC, int P, int kh, int kw, int sh, int sw, int ph, int pw)
+{
+    return kh == 2 && kw == 2 && sh == 2 && sw == 2 && ph == 0 && pw == 0 && (long long)NC * P < (1LL << 31);
+}
+
+// Smallest lg with 2^lg >= groups, or -1 if a row has more than 256 groups.
+int log2_groups(int groups)
+{
+    for (int lg = 0; lg <= 8; ++lg)
+        if ((1 << lg) >= groups) return lg;
+    return -1;
 }
 
 }  // namespace
@@ -591,6 +698,16 @@ hipError_t launch_maxpool_fwd(const void *x, void *y, int32_t *idx, int NC, int 
                               int kw, int sh, int sw, int ph, int pw, int bf16, hipStream_t s)
 {
     const size_t total = (size_t)NC * P * Q;
+    if (total == 0) return hipSuccess;
+    if (pool2_fast(NC, P, kh, kw, sh, sw, ph, pw) && log2_groups((Q + 7) / 8) >= 0) {
+        const int lg = log2_groups((Q + 7) / 8);
+        const unsigned rows = (unsigned)NC * P, rpb = 256u >> lg;
+        return by_dtype(bf16, [&](auto *tag) {
+            typedef typename std::remove_pointer<decltype(tag)>::type T;
+            hipLaunchKernelGGL(maxpool2_fwd_kernel<T>, dim3((rows + rpb - 1) / rpb), dim3(256), 0, s, (const T *)x,
+                               (T *)y, idx, rows, H, W, P, Q, lg);
+        });
+    }
     return by_dtype(bf16, [&](auto *tag) {
         typedef typename std::remove_pointer<decltype(tag)>::type T;
         dim3 grid((unsigned)((total + 255) / 256)), block(256);
@@ -603,6 +720,16 @@ hipError_t launch_maxpool_bwd(const void *dy, const int32_t *idx, void *dx, int 
                               int kh, int kw, int sh, int sw, int ph, int pw, int bf16, hipStream_t s)
 {
     const size_t total = (size_t)NC * H * W;
+    if (total == 0) return hipSuccess;
+    if (pool2_fast(NC, P, kh, kw, sh, sw, ph, pw) && P > 0 && Q > 0 && log2_groups((W + 7) / 8) >= 0) {
+        const int lg = log2_groups((W + 7) / 8);
+        const unsigned rows = (unsigned)NC * P, rpb = 256u >> lg;
+        return by_dtype(bf16, [&](auto *tag) {
+            typedef typename std::remove_pointer<decltype(tag)>::type T;
+            hipLaunchKernelGGL(maxpool2_bwd_kernel<T>, dim3((rows + rpb - 1) / rpb), dim3(256), 0, s, (const T *)dy,
+                               idx, (T *)dx, rows, H, W, P, Q, lg);
+        });
+    }
     return by_dtype(bf16, [&](auto *tag) {
         typedef typename std::remove_pointer<decltype(tag)>::type T;
         dim3 grid((unsigned)((total + 255) / 256)), block(256);

@@ -101,7 +101,9 @@ POOL_CASES = [((2, 16, 16, 16), (2, 2), (2, 2), (0, 0)), ((2, 8, 55, 55), (3, 3)
               ((2, 4, 17, 17), (3, 3), (2, 2), (0, 0)), ((1, 3, 9, 12), (3, 3), (2, 2), (1, 1)),
               ((2, 3, 7, 10), (3, 2), (1, 2), (1, 0)), ((1, 1, 1, 1), (1, 1), (1, 1), (0, 0)),
               ((2, 4, 224, 224), (2, 2), (2, 2), (0, 0)), ((2, 3, 15, 15), (2, 2), (2, 2), (0, 0)),
-              ((1, 2, 8, 8), (3, 3), (1, 1), (1, 1))]
+              ((1, 2, 8, 8), (3, 3), (1, 1), (1, 1)), ((3, 5, 14, 14), (2, 2), (2, 2), (0, 0)),
+              ((1, 2, 2, 2), (2, 2), (2, 2), (0, 0)), ((2, 3, 33, 20), (2, 2), (2, 2), (0, 0)),
+              ((1, 2, 6, 300), (2, 2), (2, 2), (0, 0))]
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
