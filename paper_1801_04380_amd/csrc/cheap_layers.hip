@@ -516,7 +516,7 @@ template <typename T, int NEL> struct __attribute__((packed, aligned(sizeof(T)))
 template <typename T>
 __global__ void __launch_bounds__(256)
 maxpool2_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, int32_t *__restrict__ idx, unsigned rows, int H,
-                    int W, int P, int Q, int lg)
+                    int W, int P, int Q, int lg, const T *__restrict__ xend)
 {
     const unsigned row = blockIdx.x * (256u >> lg) + (threadIdx.x >> lg);
     const int g = threadIdx.x & ((1 << lg) - 1);
@@ -528,12 +528,18 @@ maxpool2_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, int32_t *__restr
     int32_t *io = idx + (size_t)row * Q + 8 * g;
     const int base = 2 * p * W + 16 * g;
     const int nout = min(8, Q - 8 * g);
+    // the 16 columns may run past the row end; they are read anyway as long as they are inside
+    // the tensor, and the windows they would feed are not stored
     Pack<T, 16> a, b;
-    if (nout == 8) {
+    if (r1 + 16 <= xend) {
         a = *reinterpret_cast<const Pack<T, 16> *>(r0);
         b = *reinterpret_cast<const Pack<T, 16> *>(r1);
     } else {
-        for (int j = 0; j < 2 * nout; ++j) { a.e[j] = r0[j]; b.e[j] = r1[j]; }
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            a.e[j] = b.e[j] = T(0);
+            if (j < 2 * nout) { a.e[j] = r0[j]; b.e[j] = r1[j]; }
+        }
     }
     Pack<T, 8> out;
     Pack<int32_t, 8> oi;
@@ -556,7 +562,9 @@ maxpool2_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, int32_t *__restr
         *reinterpret_cast<Pack<T, 8> *>(yo) = out;
         *reinterpret_cast<Pack<int32_t, 8> *>(io) = oi;
     } else {
-        for (int j = 0; j < nout; ++j) { yo[j] = out.e[j]; io[j] = oi.e[j]; }
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            if (j < nout) { yo[j] = out.e[j]; io[j] = oi.e[j]; }
     }
 }
 
@@ -592,9 +600,13 @@ maxpool2_bwd_kernel(const T *__restrict__ dy, const int32_t *__restrict__ idx, T
 #pragma unroll
         for (int c = 0; c < 8; ++c) out.e[c] = wi.e[c >> 1] == h * W + 8 * g + c ? d.e[c >> 1] : T(0);
         T *o = dx + ((size_t)nc * H + h) * W + 8 * g;
-        if (ncol == 8) *reinterpret_cast<Pack<T, 8> *>(o) = out;
-        else
-            for (int c = 0; c < ncol; ++c) o[c] = out.e[c];
+        if (ncol == 8) {
+            *reinterpret_cast<Pack<T, 8> *>(o) = out;
+        } else {
+#pragma unroll
+            for (int c = 0; c < 8; ++c)
+                if (c < ncol) o[c] = out.e[c];
+        }
     }
 }
 
@@ -705,7 +717,7 @@ hipError_t launch_maxpool_fwd(const void *x, void *y, int32_t *idx, int NC, int 
         return by_dtype(bf16, [&](auto *tag) {
             typedef typename std::remove_pointer<decltype(tag)>::type T;
             hipLaunchKernelGGL(maxpool2_fwd_kernel<T>, dim3((rows + rpb - 1) / rpb), dim3(256), 0, s, (const T *)x,
-                               (T *)y, idx, rows, H, W, P, Q, lg);
+                               (T *)y, idx, rows, H, W, P, Q, lg, (const T *)x + (size_t)NC * H * W);
         });
     }
     return by_dtype(bf16, [&](auto *tag) {

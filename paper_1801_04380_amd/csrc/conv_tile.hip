@@ -1,547 +1,9 @@
-// Stride-1 implicit-GEMM convolution for bf16 on gfx950 MFMA: the fast path of
-// CONV forward and CONV backward-data (Sec. 3.5 of the paper; definitions in sn.h).
-//
-// Backward-data of a stride-1 convolution is itself a stride-1 forward
-// convolution of dy with the filter transposed in (k,c) and flipped in (r,s)
-// and padding R-1-pad, so both directions run the same kernel on a "problem":
-// input in[N][Cin][Hin][Win], output out[N][Kout][Pout][Qout], taps (r,s),
-// padding (padh,padw), filter element A(m, red, tap) with m an output channel
-// and red an input channel.
-//
-// Work decomposition.  A 256-thread workgroup owns KT output channels x PIXT
-// output pixels (KT=128, PIXT=256 or KT=64, PIXT=512) and walks the input
-// channels 16 at a time; each wave multiplies a 64-channel x 128-pixel block
-// with v_mfma_f32_32x32x16_bf16 (2 x 4 tiles, 128 accumulator registers).
-// Two pixel tilings:
-//   WIDE    8x32 / 16x32 patches of one image; an MFMA tile is one output row,
-//           and the four tiles of a wave are four consecutive rows;
-//   NARROW  (images up to 64 wide) TH consecutive rows of the flattened
-//           (image, output row) space times the whole width, so small images
-//           fill the lanes: a tile may span several images.
-// Per 16-channel chunk the workgroup keeps in LDS
-//   xs: the input patch with halo, transposed to [pixel][16 channels] (32 bytes
-//       per pixel, so one MFMA lane reads its 8 consecutive channels with a
-//       single 16-byte load).  The transposition happens on the way in: each
-//       thread gathers 8 channels of two neighbouring pixels with 4-byte loads
-//       that are coalesced across lanes along the image row, and writes two
-//       16-byte items.  The patch rows are padded to a multiple of 16 pixels;
-//   ws: the filter slab [tap][KT][16 channels] of one stage.
-// Both are XOR-swizzled on the 16-byte half index with bit 3 of the row index,
-// which makes the 16-byte reads of 16 consecutive rows hit distinct banks; with
-// the padded patch rows the swizzle of a pixel does not depend on the tap row.
-// A tap (r,s) only shifts the pixel index by r*LWp + s, so all taps reuse one
-// patch.  A chunk is worked off in stages of one filter column (all r for one
-// s; all taps for 1xS filters): in the WIDE tiling the operand of output row i,
-// tap row r is the operand of output row i+1, tap row r-1, so a wave reads
-// 4+R-1 patch rows per stage instead of 4*R.
-//
-// Both LDS arrays are double buffered.  The global loads of the next stage
-// (filter) and of the next chunk (patch) are issued before the MFMAs of the
-// current stage and written to the other buffer after them; one barrier per
-// stage.  The loads are branch free: addresses that fall outside the image or
-// the tensor are clamped to a valid one, and what they return is never stored
-// (the LDS buffers are zeroed once; the set of pixels outside the image is the
-// same for every chunk) or belongs to output channels that are not written.
-//
-// The filter slab comes either from a copy pre-packed into the caller's
-// workspace in exactly the LDS order, swizzle included (STAGED algorithm: a
-// stage is one contiguous run of 16-byte loads), or is gathered from the KCRS
-// tensor with 2-byte loads (DIRECT, no workspace).
-#include <type_traits>
-#include <utility>
-
-#include "sn_internal.h"
+// Host side of the stride-1 bf16 tile convolution (the kernel is in conv_tile.h): the
+// filter packing kernel, the choice of the tiling, and the entry points.
+#include "conv_tile.h"
 
 namespace sn {
 namespace {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-constexpr int XPAIRS_MAX = 384;  // NARROW: pixel pairs gathered per chunk
-constexpr int WIDE_LWP = 48;    // WIDE: padded patch row (32 + S - 1 <= 48)
-constexpr int LDS_LIMIT = 160 * 1024;
-constexpr int EPI_PITCH = 272;  // bytes per channel row of the output staging: 128 pixels and a pad
-
-struct TileProblem {
-    int N, Cin, Hin, Win, Kout, Pout, Qout, padh, padw;
-    int out_bf16;
-    int TH, TW, LW, LWp;     // tile rows, tile columns, patch width in pixels, padded patch width
-    int ncoltiles;
-    int tiles_per_img;       // WIDE: row tiles per image
-    int Hp;                  // padded rows per image = Pout + R - 1
-    int nchunks;             // ceil(Cin / 16)
-    int xslots;              // pixel slots of one patch buffer in LDS
-    // filter access: A(m, red, tap) = w[m*w_sm + red*w_sr + (tflip ? T-1-tap : tap)]
-    int w_sm, w_sr, tflip;
-    int Mpad;                // rows per (chunk, tap) block of the packed filter
-};
-
-// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>)
-template <typename F, int... I> __device__ inline void static_for_impl(F &&f, std::integer_sequence<int, I...>)
-{
-    (f(std::integral_constant<int, I>{}), ...);
-}
-template <int N, typename F> __device__ inline void static_for(F &&f)
-{
-    static_for_impl(f, std::make_integer_sequence<int, N>{});
-}
-
-// Filter columns per stage: a 1xS filter has too little work per column.
-constexpr int sg_of(int R, int S) { return (R == 1 && S > 1) ? S : 1; }
-
-__device__ __host__ inline int swz(int row) { return (row >> 3) & 1; }
-
-// Two consecutive bf16 as one 4-byte load, whatever the alignment.
-struct __attribute__((packed, aligned(2))) U32u { uint32_t v; };
-__device__ inline uint32_t load2_any(const bf16_t *p) { return reinterpret_cast<const U32u *>(p)->v; }
-
-// Eight consecutive bf16 as one 16-byte store, whatever the alignment.
-struct __attribute__((packed, aligned(2))) U128u { uint4 v; };
-__device__ inline void store8_any(bf16_t *p, uint4 v) { reinterpret_cast<U128u *>(p)->v = v; }
-
-// Two fp32 to a pair of bf16 (round to nearest even), the first in the low half.
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-__device__ inline uint32_t pack2_bf16(float a, float b)
-{
-    f32x2 f = {a, b};
-    bf16x2 h = __builtin_convertvector(f, bf16x2);
-    uint32_t r;
-    __builtin_memcpy(&r, &h, 4);
-    return r;
-}
-
-// Keeps the first n (< 8) elements of an octet.
-__device__ inline uint4 keep_first(uint4 v, int n)
-{
-    uint32_t *d = reinterpret_cast<uint32_t *>(&v);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) d[j] &= n > 2 * j + 1 ? 0xffffffffu : (n > 2 * j ? 0xffffu : 0u);
-    return v;
-}
-
-template <int R, int S, int KT, bool STAGED, bool WIDE>
-__global__ void __launch_bounds__(256, 2)
-conv_tile_kernel(const bf16_t *__restrict__ in, const bf16_t *__restrict__ w, void *__restrict__ out, TileProblem p)
-{
-    constexpr int SG = sg_of(R, S), T = R * S, TRES = R * SG, NSUB = S / SG;
-    constexpr int PIXT = KT == 128 ? 256 : 512;
-    constexpr int WSZ = TRES * KT * 2;                 // 16-byte items of one filter slab
-    constexpr int WITEMS = (WSZ + 255) / 256;
-    // gather rounds: a thread takes one pixel pair x 8 channels per round
-    constexpr int XR = WIDE ? ((PIXT / 32 + R - 1) * ((32 + S) / 2) + 127) / 128 : XPAIRS_MAX / 128;
-    constexpr int NB = WIDE ? 4 + R - 1 : 4;
-    extern __shared__ __attribute__((aligned(16))) uint4 smem[];
-    const int XS = p.xslots * 2;                       // 16-byte items of one patch buffer
-    uint4 *const xs = smem;
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int l32 = lane & 31, g = lane >> 5;
-    const int wk = (KT == 128) ? (wave >> 1) : 0;
-    const int wp = (KT == 128) ? (wave & 1) : wave;
-
-    // ---- tile geometry
-    const int rowtile = blockIdx.x / p.ncoltiles, coltile = blockIdx.x - rowtile * p.ncoltiles;
-    const int k0 = blockIdx.y * KT;
-    const int q0 = coltile * p.TW;
-    const int LWp = WIDE ? WIDE_LWP : p.LWp;
-    const int HWin = p.Hin * p.Win;
-    int o0, NP, u0, lrows, img = 0;   // first flattened (image, row), its limit, first patch row, patch rows
-    if (WIDE) {
-        img = rowtile / p.tiles_per_img;
-        const int pp0 = (rowtile - img * p.tiles_per_img) * p.TH;
-        o0 = img * p.Pout + pp0;
-        NP = (img + 1) * p.Pout;
-        u0 = img * p.Hp + pp0;
-        lrows = p.TH + R - 1;
-    } else {
-        o0 = rowtile * p.TH;
-        NP = p.N * p.Pout;
-        const int n0 = o0 / p.Pout;
-        u0 = n0 * p.Hp + (o0 - n0 * p.Pout);
-        const int olast = min(o0 + p.TH, NP) - 1, nl = olast / p.Pout;
-        lrows = nl * p.Hp + (olast - nl * p.Pout) - u0 + R;
-    }
-
-    // ---- zero both patch buffers once: pixels outside the image are never written again
-    for (int i = tid; i < 2 * XS; i += 256) xs[i] = make_uint4(0, 0, 0, 0);
-
-    // ---- per-thread constants of the patch gather.  A thread takes two neighbouring
-    // pixels of a patch row x 8 channels: one 4-byte load per channel (2-byte aligned)
-    // brings both pixels, so that two 16-byte LDS items are built with 8 byte-permutes.
-    // If only one pixel of the pair is inside the image the load is placed so that it
-    // stays inside the row (rows have at least 2 pixels), and the half that holds the
-    // live pixel goes to that pixel's slot.
-    const int xo = tid >> 7, tp = tid & 127;
-    const uint32_t xo8 = (uint32_t)xo * 8u * (uint32_t)HWin;
-    uint32_t xoff[XR];       // element offset of the load for the thread's first channel of chunk 0
-    int xdlo[XR], xdhi[XR];  // 16-byte LDS index for the low / high halves, -1: not stored
-    const int LWh = (p.LW + 1) >> 1;
-    const int xpairs = lrows * LWh;
-#pragma unroll
-    for (int rd = 0; rd < XR; ++rd) {
-        const int lp = rd * 128 + tp;
-        int off = 0, dlo = -1, dhi = -1;
-        if (lp < xpairs) {
-            const int lrow = lp / LWh, lcol = (lp - lrow * LWh) * 2;
-            const int u = u0 + lrow, n = WIDE ? img : u / p.Hp, h = u - n * p.Hp - p.padh;
-            const int v = q0 - p.padw + lcol;
-            if (n < p.N && (unsigned)h < (unsigned)p.Hin) {
-                const int rowoff = (n * p.Cin * p.Hin + h) * p.Win;
-                const bool va = (unsigned)v < (unsigned)p.Win;
-                const bool vb = lcol + 1 < p.LW && (unsigned)(v + 1) < (unsigned)p.Win;
-                const int slot = lrow * LWp + lcol;
-                const int da = slot * 2 + (xo ^ swz(slot)), db = (slot + 1) * 2 + (xo ^ swz(slot + 1));
-                if (va && vb) { off = rowoff + v; dlo = da; dhi = db; }
-                else if (va && v >= 1) { off = rowoff + v - 1; dhi = da; }
-                else if (va) { off = rowoff; dlo = da; }
-                else if (vb) { off = rowoff + v + 1; dlo = db; }
-            }
-        }
-        xoff[rd] = (uint32_t)off + xo8;
-        xdlo[rd] = dlo;
-        xdhi[rd] = dhi;
-    }
-
-    // ---- per-thread constants of the DIRECT filter gather: thread item = (tap, row, half)
-    uint32_t wsrc[STAGED ? 1 : WITEMS];
-    int wdst[STAGED ? 1 : WITEMS];
-    if (!STAGED) {
-#pragma unroll
-        for (int it = 0; it < WITEMS; ++it) {
-            const int e = min(it * 256 + tid, WSZ - 1);
-            int tl, row, o;
-            tl = e % TRES;
-            const int q = e / TRES;
-            if (p.tflip) { row = q % KT; o = q / KT; }   // backward-data: (m, tap) contiguous for one red
-            else { o = q & 1; row = q >> 1; }            // forward: (red, tap) contiguous for one m
-            const int r = tl / SG, sl = tl - r * SG, tap = r * S + sl;
-            wsrc[it] = (uint32_t)(min(k0 + row, p.Kout - 1) * p.w_sm + (p.tflip ? T - 1 - tap : tap) +
-                                  o * 8 * p.w_sr);
-            wdst[it] = (tl * KT + row) * 2 + (o ^ swz(row));
-        }
-    }
-
-    // ---- per-lane constants of the MFMA operand reads
-    int pixbase[WIDE ? 1 : 4];
-    if (WIDE) {
-        pixbase[0] = (wp * 4) * WIDE_LWP + l32;
-    } else {
-#pragma unroll
-        for (int f = 0; f < 4; ++f) {
-            const int i = (wp * 4 + f) * 32 + l32;
-            const int rl = i / p.TW, cl = i - rl * p.TW;
-            const int o = o0 + rl;
-            int pb = 0;
-            if (rl < p.TH && o < NP) {
-                const int n = o / p.Pout, pp = o - n * p.Pout;
-                pb = (n * p.Hp + pp - u0) * LWp + cl;
-            }
-            pixbase[f] = pb;
-        }
-    }
-    const int arow = wk * 64 + l32;
-    const int aidx = arow * 2 + (g ^ swz(arow));
-
-    f32x16 acc[2][4];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int f = 0; f < 4; ++f)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][f][v] = 0.f;
-
-    uint32_t xraw[XR][8];
-    u16x8 wreg[STAGED ? 1 : WITEMS];
-
-    // Global loads of the patch of one chunk; nothing here looks at what a load returns.
-    auto load_x = [&](int chunk) {
-        const int c0 = chunk * 16;
-        if (c0 + 16 <= p.Cin) {
-            const bf16_t *src = in + (size_t)c0 * HWin;
-#pragma unroll
-            for (int rd = 0; rd < XR; ++rd) {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) xraw[rd][i] = load2_any(src + (size_t)i * HWin + xoff[rd]);
-            }
-        } else {   // the last chunk has fewer than 16 channels: clamp, store_x clears them
-#pragma unroll
-            for (int rd = 0; rd < XR; ++rd) {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const int c = min(c0 + xo * 8 + i, p.Cin - 1);
-                    xraw[rd][i] = load2_any(in + (size_t)c * HWin + (xoff[rd] - xo8));
-                }
-            }
-        }
-    };
-    auto store_x = [&](int chunk, uint4 *xb) {
-        const int nvalid = p.Cin - chunk * 16 - xo * 8;
-#pragma unroll
-        for (int rd = 0; rd < XR; ++rd) {
-            uint4 lo, hi;
-            lo.x = __builtin_amdgcn_perm(xraw[rd][1], xraw[rd][0], 0x05040100u);
-            lo.y = __builtin_amdgcn_perm(xraw[rd][3], xraw[rd][2], 0x05040100u);
-            lo.z = __builtin_amdgcn_perm(xraw[rd][5], xraw[rd][4], 0x05040100u);
-            lo.w = __builtin_amdgcn_perm(xraw[rd][7], xraw[rd][6], 0x05040100u);
-            hi.x = __builtin_amdgcn_perm(xraw[rd][1], xraw[rd][0], 0x07060302u);
-            hi.y = __builtin_amdgcn_perm(xraw[rd][3], xraw[rd][2], 0x07060302u);
-            hi.z = __builtin_amdgcn_perm(xraw[rd][5], xraw[rd][4], 0x07060302u);
-            hi.w = __builtin_amdgcn_perm(xraw[rd][7], xraw[rd][6], 0x07060302u);
-            if (nvalid < 8) { lo = keep_first(lo, nvalid); hi = keep_first(hi, nvalid); }
-            if (xdlo[rd] >= 0) xb[xdlo[rd]] = lo;
-            if (xdhi[rd] >= 0) xb[xdhi[rd]] = hi;
-        }
-    };
-
-    // Global loads of the filter slab of stage (chunk, sg).
-    auto load_w = [&](int chunk, int sg) {
-        if (STAGED) {
-            const uint4 *src = reinterpret_cast<const uint4 *>(w) +
-                               ((size_t)(chunk * NSUB + sg) * TRES * p.Mpad + k0) * 2;
-#pragma unroll
-            for (int it = 0; it < WITEMS; ++it) {
-                const int e = min(it * 256 + tid, WSZ - 1);
-                const int tl = e / (KT * 2), rem = e - tl * (KT * 2);
-                const uint4 v = src[(size_t)tl * p.Mpad * 2 + rem];
-                __builtin_memcpy(&wreg[it], &v, 16);
-            }
-        } else {
-            const int c0 = chunk * 16;
-            const int tapoff = p.tflip ? -sg * SG : sg * SG;
-            if (c0 + 16 <= p.Cin) {
-                const bf16_t *src = w + (ptrdiff_t)c0 * p.w_sr + tapoff;
-#pragma unroll
-                for (int it = 0; it < WITEMS; ++it)
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) wreg[it][i] = src[(size_t)i * p.w_sr + wsrc[it]];
-            } else {
-#pragma unroll
-                for (int it = 0; it < WITEMS; ++it) {
-                    const int o = STAGED ? 0 : ((wdst[it] & 1) ^ swz(wdst[it] >> 1));
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        const int red = min(c0 + o * 8 + i, p.Cin - 1);
-                        wreg[it][i] = w[(ptrdiff_t)red * p.w_sr + tapoff + (wsrc[it] - (uint32_t)(o * 8 * p.w_sr))];
-                    }
-                }
-            }
-        }
-    };
-    auto store_w = [&](uint4 *wb) {
-#pragma unroll
-        for (int it = 0; it < WITEMS; ++it) {
-            const int e = it * 256 + tid;
-            if ((it + 1) * 256 <= WSZ || e < WSZ) {
-                uint4 v;
-                __builtin_memcpy(&v, &wreg[it], 16);
-                wb[STAGED ? e : wdst[it]] = v;
-            }
-        }
-    };
-
-    // The MFMAs of one stage.
-    auto compute = [&](const uint4 *xb, const uint4 *wb, int sg) {
-#pragma unroll
-        for (int sl = 0; sl < SG; ++sl) {
-            const int s = sg * SG + sl;
-            bf16x8 b[NB];
-            if (WIDE) {
-                const int slot = pixbase[0] + s;
-                const uint4 *bp = xb + slot * 2 + (g ^ swz(slot));
-#pragma unroll
-                for (int j = 0; j < NB; ++j) b[j] = *reinterpret_cast<const bf16x8 *>(bp + j * WIDE_LWP * 2);
-            }
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-                if (!WIDE) {
-#pragma unroll
-                    for (int f = 0; f < 4; ++f) {
-                        const int slot = pixbase[f] + s;
-                        b[f] = *reinterpret_cast<const bf16x8 *>(xb + (slot + r * LWp) * 2 + (g ^ swz(slot)));
-                    }
-                }
-                bf16x8 a[2];
-#pragma unroll
-                for (int i = 0; i < 2; ++i)
-                    a[i] = *reinterpret_cast<const bf16x8 *>(wb + ((r * SG + sl) * KT + i * 32) * 2 + aidx);
-#pragma unroll
-                for (int f = 0; f < 4; ++f)
-#pragma unroll
-                    for (int i = 0; i < 2; ++i)
-                        acc[i][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WIDE ? b[f + r] : b[f], a[i], acc[i][f], 0, 0, 0);
-            }
-        }
-    };
-
-    if constexpr (STAGED) {
-        // Packed filter: the slab of a stage is fetched two stages ahead into one of two
-        // register sets (the set of a stage is its parity; two chunks are unrolled so that
-        // the parity is known at compile time), and written to LDS one stage ahead.  The
-        // patch of the next chunk is fetched during the first stage of a chunk and written
-        // after its last.  Loads complete in order: a stage waits for the slab issued one
-        // stage ago while the loads issued since stay in flight.  Every stage issues the
-        // same loads, so the counts are exact; past the end they fetch the last slab / chunk
-        // again, and what they bring is written to a buffer nobody reads.
-        uint4 *const ws = smem + 2 * XS;
-        const int nstage = p.nchunks * NSUB;
-        u32x4 wr[2][WITEMS];
-        auto load_ws = [&](int stage, u32x4(&dst)[WITEMS]) {
-            const int st = min(stage, nstage - 1);
-            const u32x4 *src = reinterpret_cast<const u32x4 *>(w) + ((size_t)st * TRES * p.Mpad + k0) * 2;
-#pragma unroll
-            for (int it = 0; it < WITEMS; ++it) {
-                const int e = min(it * 256 + tid, WSZ - 1);
-                const int tl = e / (KT * 2), rem = e - tl * (KT * 2);
-                dst[it] = src[(size_t)tl * p.Mpad * 2 + rem];
-            }
-        };
-        auto store_ws = [&](uint4 *wb, const u32x4(&srcr)[WITEMS]) {
-#pragma unroll
-            for (int it = 0; it < WITEMS; ++it) {
-                const int e = it * 256 + tid;
-                if ((it + 1) * 256 <= WSZ || e < WSZ) reinterpret_cast<u32x4 *>(wb)[e] = srcr[it];
-            }
-        };
-        load_ws(0, wr[0]);
-        load_ws(1, wr[1]);
-        load_x(0);
-        __syncthreads();   // the zero fill is complete
-        store_x(0, xs);
-        store_ws(ws, wr[0]);
-        for (int chunk0 = 0; chunk0 < p.nchunks; chunk0 += 2) {
-            static_for<2 * NSUB>([&](auto idx) {
-                constexpr int c = decltype(idx)::value / NSUB, sg = decltype(idx)::value % NSUB;
-                constexpr int par = decltype(idx)::value & 1;   // parity of the stage
-                const int chunk = chunk0 + c;
-                const int cnext = min(chunk + 1, p.nchunks - 1);
-                uint4 *const xcur = xs + c * XS, *const xnext = xs + (c ^ 1) * XS;
-                __syncthreads();
-                if (!WIDE) {
-                    // keeps the operand addresses of later stages from being worked out early
-#pragma unroll
-                    for (int f = 0; f < (WIDE ? 1 : 4); ++f) asm volatile("" : "+v"(pixbase[f]));
-                }
-                load_ws(chunk * NSUB + sg + 2, wr[par]);
-                if (sg == 0) load_x(cnext);
-                __builtin_amdgcn_sched_barrier(0);   // the loads stay ahead of the MFMAs
-                if (chunk < p.nchunks) compute(xcur, ws + par * WSZ, sg);
-                __builtin_amdgcn_sched_barrier(0);
-                store_ws(ws + (par ^ 1) * WSZ, wr[par ^ 1]);
-                if (sg == NSUB - 1) store_x(cnext, xnext);
-            });
-        }
-    } else {
-    uint4 *const ws = smem + 2 * XS;
-    load_x(0);
-    load_w(0, 0);
-    __syncthreads();   // the zero fill is complete
-    store_x(0, xs);
-    store_w(ws);
-    int wpar = 0;
-    // Every stage issues the same loads and stores, so that the wait counters are exact:
-    // past the end they fetch the last stage / chunk again, into a buffer nobody reads.
-    for (int chunk = 0; chunk < p.nchunks; ++chunk) {
-        const int cnext = min(chunk + 1, p.nchunks - 1);
-        uint4 *const xcur = xs + (chunk & 1) * XS, *const xnext = xs + ((chunk + 1) & 1) * XS;
-        if (!WIDE) {
-            // keeps the per-tap operand addresses from being hoisted out of the loop into registers
-#pragma unroll
-            for (int f = 0; f < (WIDE ? 1 : 4); ++f) asm volatile("" : "+v"(pixbase[f]));
-        }
-#pragma unroll
-        for (int sg = 0; sg < NSUB; ++sg) {
-            __syncthreads();
-            if (sg + 1 < NSUB) load_w(chunk, sg + 1);
-            else load_w(cnext, chunk + 1 < p.nchunks ? 0 : NSUB - 1);
-            if (sg == 0) load_x(cnext);
-            __builtin_amdgcn_sched_barrier(0);   // the loads stay ahead of the MFMAs
-            compute(xcur, ws + wpar * WSZ, sg);
-            __builtin_amdgcn_sched_barrier(0);
-            wpar ^= 1;
-            store_w(ws + wpar * WSZ);
-            if (sg == NSUB - 1) store_x(cnext, xnext);
-        }
-    }
-    }
-
-    // ---- epilogue.  The MFMAs take the pixels as rows, so a lane holds, for output
-    // channel lane % 32 of a tile, the pixels 8*(v/4) + 4*(lane/32) + v%4: four
-    // consecutive pixels per group of four registers.
-    const int PQ = p.Pout * p.Qout;
-    auto pix_off = [&](int i) -> int {   // offset of pixel i of the tile in channel 0, -1: not an output
-        const int rl = i / p.TW, cl = i - rl * p.TW;
-        const int o = o0 + rl;
-        if (!(rl < p.TH && o < NP && q0 + cl < p.Qout)) return -1;
-        const int n = o / p.Pout, pp = o - n * p.Pout;
-        return (n * p.Kout * p.Pout + pp) * p.Qout + q0 + cl;
-    };
-    if (p.out_bf16) {
-        // bf16: through LDS, 32 channels x 128 pixels per wave and pass, so that a lane
-        // writes 8 consecutive pixels of one channel with one 16-byte store
-        constexpr int EP = EPI_PITCH;
-        __syncthreads();   // the last stage has been read
-        char *const stage = reinterpret_cast<char *>(smem) + wave * 32 * EP;
-        const int oct = lane & 15, krow = lane >> 4;
-        const int i0 = wp * 128 + oct * 8;
-        const int off0 = pix_off(i0), off7 = pix_off(i0 + 7);
-        const bool contig = off0 >= 0 && off7 == off0 + 7;
-        int eoff[8];
-        bool any = false;
-        if (!contig) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) { eoff[e] = pix_off(i0 + e); any = any || eoff[e] >= 0; }
-        }
-        bf16_t *const o16 = reinterpret_cast<bf16_t *>(out);
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-#pragma unroll
-            for (int f = 0; f < 4; ++f)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    uint2 v;
-                    v.x = pack2_bf16(acc[i][f][4 * j], acc[i][f][4 * j + 1]);
-                    v.y = pack2_bf16(acc[i][f][4 * j + 2], acc[i][f][4 * j + 3]);
-                    *reinterpret_cast<uint2 *>(stage + l32 * EP + (f * 32 + 8 * j + 4 * g) * 2) = v;
-                }
-            __syncthreads();
-#pragma unroll
-            for (int rd = 0; rd < 8; ++rd) {
-                const int kl = rd * 4 + krow, k = k0 + wk * 64 + i * 32 + kl;
-                const uint4 v = *reinterpret_cast<const uint4 *>(stage + kl * EP + oct * 16);
-                if (k >= p.Kout) continue;
-                if (contig) {
-                    store8_any(o16 + (size_t)k * PQ + off0, v);
-                } else if (any) {
-                    const uint32_t d[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        if (eoff[e] >= 0) o16[(size_t)k * PQ + eoff[e]] = (bf16_t)(d[e >> 1] >> (16 * (e & 1)));
-                }
-            }
-            if (i == 0) __syncthreads();
-        }
-    } else {
-        float *const o32 = reinterpret_cast<float *>(out);
-#pragma unroll
-        for (int f = 0; f < 4; ++f)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int off = pix_off((wp * 4 + f) * 32 + 8 * j + 4 * g + e);
-                    if (off < 0) continue;
-#pragma unroll
-                    for (int i = 0; i < 2; ++i) {
-                        const int k = k0 + wk * 64 + i * 32 + l32;
-                        if (k < p.Kout) o32[(size_t)k * PQ + off] = acc[i][f][4 * j + e];
-                    }
-                }
-    }
-}
 
 // Packs A(m, red, tap) into [chunk = red/16][stage][tap of the stage][Mpad][16],
 // zero padded, the two 8-channel halves of a row swapped where the LDS swizzle
@@ -567,21 +29,15 @@ pack_filter_kernel(const bf16_t *__restrict__ w, bf16_t *__restrict__ wp, int M,
     wp[e] = v;
 }
 
-struct Plan {
-    TileProblem p;
-    int KT;
-    bool wide;
-    size_t lds;
-    dim3 grid;
-};
-
-// Tiling for one problem; false if the patch would not fit in LDS.
-bool make_plan(const TileProblem &base, int R, int S, bool staged, Plan *pl)
+// Tiling for one problem with NF 32-pixel tiles per wave; false if the patch would not fit in LDS.
+bool plan_for(const TileProblem &base, int R, int S, int NF, Plan *pl)
 {
     TileProblem p = base;
     const int KT = p.Kout <= 64 ? 64 : 128;
-    const int PIXT = KT == 128 ? 256 : 512;
+    const int PIXT = (KT == 128 ? 2 : 4) * NF * 32;
     const long long NP = (long long)p.N * p.Pout;
+    const bool xt3 = S / sg_of(R, S) >= 3;   // WIDE tiling: the patch is parked in LDS before it is transposed
+    p.ragged = p.Win % 8 != 0;
     long long nrowtiles = 0;
     bool wide = p.Qout > 64;
     if (!wide) {
@@ -606,11 +62,15 @@ bool make_plan(const TileProblem &base, int R, int S, bool staged, Plan *pl)
         const int lrows_max = p.TH + (crossings + 1) * (R - 1);
         if ((long long)lrows_max * ((p.LW + 1) / 2) > XPAIRS_MAX) return false;
         p.xslots = lrows_max * p.LWp;
+        p.xt_rows = lrows_max;
+        p.xt_cols = (p.Win + 7) / 8 * 8;
     } else {
         p.TW = 32;
         p.TH = PIXT / 32;
         p.ncoltiles = (p.Qout + 31) / 32;
         p.xslots = (p.TH + R - 1) * WIDE_LWP;
+        p.xt_rows = p.TH + R - 1;
+        p.xt_cols = WIDE_LWP;
         if (p.TH > p.Pout) p.TH = p.Pout;
         p.tiles_per_img = (p.Pout + p.TH - 1) / p.TH;
         nrowtiles = (long long)p.N * p.tiles_per_img;
@@ -622,14 +82,37 @@ bool make_plan(const TileProblem &base, int R, int S, bool staged, Plan *pl)
     p.nchunks = (p.Cin + 15) / 16;
     p.Mpad = (p.Kout + KT - 1) / KT * KT;
     size_t lds = ((size_t)2 * p.xslots * 2 + (size_t)2 * R * sg_of(R, S) * KT * 2) * 16;
+    if (xt3 && wide) lds += (size_t)16 * p.xt_rows * p.xt_cols * sizeof(bf16_t);
     if (lds < (size_t)4 * 32 * EPI_PITCH) lds = (size_t)4 * 32 * EPI_PITCH;   // the epilogue's staging
     if (lds > (size_t)LDS_LIMIT) return false;
     if (nrowtiles * p.ncoltiles > 0x7fffffffLL) return false;
     pl->p = p;
     pl->KT = KT;
+    pl->NF = NF;
     pl->wide = wide;
     pl->lds = lds;
     pl->grid = dim3((unsigned)(nrowtiles * p.ncoltiles), (p.Kout + KT - 1) / KT, 1);
+    return true;
+}
+
+// The tiling for one problem: the largest tile, unless (3x3 and 1x1 filters, which have the
+// kernels) that leaves compute units without work and a smaller one does not.
+bool make_plan(const TileProblem &base, int R, int S, bool staged, Plan *pl)
+{
+    (void)staged;
+    if (!plan_for(base, R, S, 4, pl)) return false;
+    const bool multi = (R == 3 && S == 3) || (R == 1 && S == 1);
+    if (!multi) return true;
+    // 64 output channels in the WIDE tiling: half the pixels per workgroup, so that two fit on a CU
+    if (pl->KT == 64 && pl->wide) {
+        Plan alt;
+        if (plan_for(base, R, S, 2, &alt) && alt.wide) *pl = alt;
+    }
+    // fewer workgroups than compute units: halve the pixels per workgroup
+    if ((long long)pl->grid.x * pl->grid.y < 256) {
+        Plan alt;
+        if (plan_for(base, R, S, 2, &alt)) *pl = alt;
+    }
     return true;
 }
 
@@ -653,37 +136,6 @@ bool problem_of(const ConvGeom &g, bool bwd_data, TileProblem *p)
     }
     p->out_bf16 = g.out_bf16;
     return true;
-}
-
-template <int R, int S, int KT, bool STAGED, bool WIDE>
-hipError_t launch_one(const bf16_t *in, const bf16_t *w, void *out, const Plan &pl, hipStream_t st)
-{
-    auto kern = conv_tile_kernel<R, S, KT, STAGED, WIDE>;
-    static bool attr_set = false;   // the limit of dynamic LDS is a property of the kernel, set once
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_LIMIT);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
-    hipLaunchKernelGGL(kern, pl.grid, dim3(256), pl.lds, st, in, w, out, pl.p);
-    return hipGetLastError();
-}
-
-template <int R, int S>
-hipError_t launch_rs(const bf16_t *in, const bf16_t *w, void *out, const Plan &pl, bool staged, hipStream_t st)
-{
-    const int sel = (pl.KT == 128 ? 4 : 0) | (staged ? 2 : 0) | (pl.wide ? 1 : 0);
-    switch (sel) {
-    case 0: return launch_one<R, S, 64, false, false>(in, w, out, pl, st);
-    case 1: return launch_one<R, S, 64, false, true>(in, w, out, pl, st);
-    case 2: return launch_one<R, S, 64, true, false>(in, w, out, pl, st);
-    case 3: return launch_one<R, S, 64, true, true>(in, w, out, pl, st);
-    case 4: return launch_one<R, S, 128, false, false>(in, w, out, pl, st);
-    case 5: return launch_one<R, S, 128, false, true>(in, w, out, pl, st);
-    case 6: return launch_one<R, S, 128, true, false>(in, w, out, pl, st);
-    default: return launch_one<R, S, 128, true, true>(in, w, out, pl, st);
-    }
 }
 
 bool filter_supported(int R, int S)
@@ -730,11 +182,9 @@ hipError_t launch_tile_conv(const void *in, const void *w, void *out, const Conv
     }
     const bf16_t *src = static_cast<const bf16_t *>(in);
     const bool staged = packed != nullptr;
-    if (g.R == 1 && g.S == 1) return launch_rs<1, 1>(src, wsrc, out, pl, staged, st);
-    if (g.R == 3 && g.S == 3) return launch_rs<3, 3>(src, wsrc, out, pl, staged, st);
-    if (g.R == 5 && g.S == 5) return launch_rs<5, 5>(src, wsrc, out, pl, staged, st);
-    if (g.R == 1 && g.S == 7) return launch_rs<1, 7>(src, wsrc, out, pl, staged, st);
-    return launch_rs<7, 1>(src, wsrc, out, pl, staged, st);
+    if (g.R == 1 && g.S == 1) return launch_tile_1x1(src, wsrc, out, pl, staged, st);
+    if (g.R == 3 && g.S == 3) return launch_tile_3x3(src, wsrc, out, pl, staged, st);
+    return launch_tile_other(g.R, g.S, src, wsrc, out, pl, staged, st);
 }
 
 }  // namespace sn
