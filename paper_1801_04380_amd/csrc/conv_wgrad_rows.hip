@@ -92,12 +92,12 @@ template <int d> __device__ inline bf16x8 shifted(const uint32_t (&D)[8])
 // WIDE: 32-column tiles of an image whose width is a multiple of 8 (otherwise the chunk spans the
 // whole width, which may be ragged).
 template <int S, int RG, int TM, int TH, int TWP, bool WIDE>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+__global__ void __launch_bounds__(TM * 256) __attribute__((amdgpu_waves_per_eu(TM, TM)))
 wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, float *__restrict__ out,
                   int use_atomics, RowsProblem p)
 {
-    constexpr int T = RG * S, KTB = 2 * TM * 32;
-    constexpr int OPR = TWP / 8, TPR = 256 / OPR;      // octets per row; threads per octet column
+    constexpr int T = RG * S, KTB = 2 * TM * 32, NT = TM * 256;   // 4*TM waves: 2*TM along k, 2 along c
+    constexpr int OPR = TWP / 8, TPR = NT / OPR;      // octets per row; threads per octet column
     constexpr int XROWS = TH + RG - 1, APR = S > 1 ? 8 : 0, LWX = TWP + 2 * APR, PW = (S - 1) / 2;
     constexpr int AP = odd16c(TH * TWP), CP = odd16c(XROWS * LWX);
     constexpr int YS = KTB * AP, XS = CTB * CP, BUF = YS + XS;   // elements
@@ -106,12 +106,11 @@ wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
     constexpr int YKREP = KTB >= TPR ? KTB / TPR : 1, YRPT = KTB >= TPR ? 1 : TPR / KTB;
     constexpr int YIT = KTB >= TPR ? TH * YKREP : TH / YRPT;
     constexpr int XCREP = CTB >= TPR ? CTB / TPR : 1, XRPT = CTB >= TPR ? 1 : TPR / CTB;
-    constexpr int XIT = CTB >= TPR ? XROWS * XCREP : XROWS / XRPT;
+    constexpr int XIT = CTB >= TPR ? XROWS * XCREP : (XROWS + XRPT - 1) / XRPT;
     constexpr bool APRON = WIDE && S > 1;   // a whole-width chunk has nothing beside it
-    constexpr int AIT = APRON ? CTB * XROWS * 2 / 256 : 0;
+    constexpr int AIT = APRON ? (CTB * XROWS * 2 + NT - 1) / NT : 0;
     constexpr bool RAGGED = !WIDE;
-    static_assert(TH % YRPT == 0 && XROWS % XRPT == 0, "rows do not split over the threads");
-    static_assert(!APRON || (CTB * XROWS * 2) % 256 == 0, "apron items do not split over the threads");
+    static_assert(TH % YRPT == 0, "rows do not split over the threads");
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -125,7 +124,7 @@ wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
 
     // the aprons of a whole-width chunk are never written: zero for good
     if (!WIDE && S > 1) {
-        for (int i = tid; i < 2 * CTB * XROWS * 2; i += 256) {
+        for (int i = tid; i < 2 * CTB * XROWS * 2; i += NT) {
             const int buf = i / (CTB * XROWS * 2), rem = i - buf * (CTB * XROWS * 2);
             const int c = rem / (XROWS * 2), r2 = rem - c * (XROWS * 2);
             bf16_t *dst = smem + buf * BUF + YS + c * CP + (r2 >> 1) * LWX + ((r2 & 1) ? APR + TWP : 0);
@@ -133,9 +132,10 @@ wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
         }
     }
 
-    f32x16 acc[TM][T];
+    constexpr int WTM = 1;   // k tiles per wave
+    f32x16 acc[WTM][T];
 #pragma unroll
-    for (int a = 0; a < TM; ++a)
+    for (int a = 0; a < WTM; ++a)
 #pragma unroll
         for (int t = 0; t < T; ++t)
 #pragma unroll
@@ -156,12 +156,13 @@ wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
         ygoff[it] = (k0 + y_k(it) < p.K && col_in) ? (k0 + y_k(it)) * PQ + y_row(it) * p.Q + oc * 8 : -1;
 #pragma unroll
     for (int it = 0; it < XIT; ++it)
-        xgoff[it] = (c0 + x_c(it) < p.C && col_in) ? (c0 + x_c(it)) * HW + x_row(it) * p.W + oc * 8 : -1;
-    const int aside = tid & 1, ac = (tid >> 1) & (CTB - 1), ahalf = tid >> 7;   // apron item: side, c, row parity
+        xgoff[it] = (c0 + x_c(it) < p.C && col_in && x_row(it) < XROWS) ? (c0 + x_c(it)) * HW + x_row(it) * p.W + oc * 8 : -1;
+    const int aside = tid & 1, ac = (tid >> 1) & (CTB - 1);   // apron item it: side, c, row (it * NT + tid) / 128
+    auto a_row = [&](int it) { return (it * NT + tid) >> 7; };
     if (APRON) {
 #pragma unroll
         for (int it = 0; it < AIT; ++it)
-            agoff[it] = c0 + ac < p.C ? (c0 + ac) * HW + (it * 2 + ahalf) * p.W + (aside ? TWP : -8) : NEVER;
+            agoff[it] = (c0 + ac < p.C && a_row(it) < XROWS) ? (c0 + ac) * HW + a_row(it) * p.W + (aside ? TWP : -8) : NEVER;
     }
     // the valid columns of this thread's octet as dword masks (whole-width chunks only)
     u32x4 cmask = {~0u, ~0u, ~0u, ~0u};
@@ -188,85 +189,83 @@ wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
         }
     };
 
-    u32x4 yreg[YIT], xreg[XIT], areg[APRON ? AIT : 1];
-
-    // Issues the loads of the chunk at the current coordinates.  Straight-line code: nothing
-    // here looks at what a load returns.  A ragged last octet of the tensor is read from 8
-    // elements before the end (stage_store moves it back into place).
-    auto prefetch = [&]() {
-        const int p0 = c_rc * TH, q0 = WIDE ? c_ct * TWP : 0;
-        const int h0 = p0 - p.ph;
-        const int ybase = c_img * p.K * PQ + p0 * p.Q + q0;
-        const int xbase = c_img * p.C * HW + h0 * p.W + q0;
-        const bool colok = !WIDE || q0 + oc * 8 < p.Q;
-#pragma unroll
-        for (int it = 0; it < YIT; ++it) {
-            const bool ok = ygoff[it] >= 0 && p0 + y_row(it) < p.P && colok;
-            int off = ybase + ygoff[it];
+    // ---- staging, one item (a 16-byte octet) at a time.  The items of the next chunk are
+    // loaded and written to the other LDS buffer in between the MFMAs of the current chunk (see
+    // compute), a few at a time: a burst of all of them would wait for the L1 cache to take them
+    // while the MFMA pipe runs dry.  Items 0 .. YIT-1 are dy octets, then XIT x octets, then the
+    // aprons.  Nothing looks at what a load returns before it is written to LDS.  A ragged last
+    // octet of the tensor is read from 8 elements before the end and moved back into place.
+    constexpr int NITEMS = YIT + XIT + AIT;
+    u32x4 sreg[NITEMS];
+    int k_p0 = 0, k_q0 = 0, k_h0 = 0, k_ybase = 0, k_xbase = 0;   // of the chunk being staged
+    bool k_colok = true;
+    auto begin_chunk = [&]() {
+        k_p0 = c_rc * TH;
+        k_q0 = WIDE ? c_ct * TWP : 0;
+        k_h0 = k_p0 - p.ph;
+        k_ybase = c_img * p.K * PQ + k_p0 * p.Q + k_q0;
+        k_xbase = c_img * p.C * HW + k_h0 * p.W + k_q0;
+        k_colok = !WIDE || k_q0 + oc * 8 < p.Q;
+    };
+    auto item_load = [&](int i) {
+        if (i < YIT) {
+            const int it = i;
+            const bool ok = ygoff[it] >= 0 && k_p0 + y_row(it) < p.P && k_colok;
+            int off = k_ybase + ygoff[it];
             if (RAGGED) off = min(off, ytotal - 8);
-            yreg[it] = load8_any(ok ? dy + off : zp);
-        }
-#pragma unroll
-        for (int it = 0; it < XIT; ++it) {
-            const bool ok = xgoff[it] >= 0 && (unsigned)(h0 + x_row(it)) < (unsigned)p.H && colok;
-            int off = xbase + xgoff[it];
+            sreg[i] = load8_any(ok ? dy + off : zp);
+        } else if (i < YIT + XIT) {
+            const int it = i - YIT;
+            const bool ok = xgoff[it] >= 0 && (unsigned)(k_h0 + x_row(it)) < (unsigned)p.H && k_colok;
+            int off = k_xbase + xgoff[it];
             if (RAGGED) off = min(off, xtotal - 8);
-            xreg[it] = load8_any(ok ? x + off : zp);
-        }
-        if (APRON) {
-#pragma unroll
-            for (int it = 0; it < AIT; ++it) {
-                const bool ok = agoff[it] != NEVER && (unsigned)(h0 + it * 2 + ahalf) < (unsigned)p.H &&
-                                (aside ? q0 + TWP < p.W : q0 > 0);
-                areg[it] = load8_any(ok ? x + (xbase + agoff[it]) : zp);
-            }
+            sreg[i] = load8_any(ok ? x + off : zp);
+        } else {
+            const int it = i - YIT - XIT;
+            const bool ok = agoff[it] != NEVER && (unsigned)(k_h0 + a_row(it)) < (unsigned)p.H &&
+                            (aside ? k_q0 + TWP < p.W : k_q0 > 0);
+            sreg[i] = load8_any(ok ? x + (k_xbase + agoff[it]) : zp);
         }
     };
-
-    // Writes the staged octets of the chunk at the current coordinates to LDS.
     const int ylds0 = (KTB >= TPR ? tq : tq % KTB) * AP + (KTB >= TPR ? 0 : (tq / KTB) * TWP) + oc * 8;
     const int xlds0 = (CTB >= TPR ? tq : tq % CTB) * CP + (CTB >= TPR ? 0 : (tq / CTB) * LWX) + APR + oc * 8;
-    const int alds0 = ac * CP + ahalf * LWX + (aside ? APR + TWP : 0);
-    auto stage_store = [&](int buf) {
+    const int alds0 = ac * CP + (aside ? APR + TWP : 0);
+    auto item_store = [&](int i, int buf) {
         bf16_t *ys = smem + buf * BUF, *xs = ys + YS;
-        const int p0 = c_rc * TH, h0 = p0 - p.ph;
-        const int ybase = c_img * p.K * PQ + p0 * p.Q;
-        const int xbase = c_img * p.C * HW + h0 * p.W;
-#pragma unroll
-        for (int it = 0; it < YIT; ++it) {
-            u32x4 v = yreg[it];
+        u32x4 v = sreg[i];
+        if (i < YIT) {
+            const int it = i;
             if (RAGGED) {
-                const int over = ybase + ygoff[it] + 8 - ytotal;
-                if (ygoff[it] >= 0 && p0 + y_row(it) < p.P && over > 0) v = shift_down(v, over);
+                const int over = k_ybase + ygoff[it] + 8 - ytotal;
+                if (ygoff[it] >= 0 && k_p0 + y_row(it) < p.P && over > 0) v = shift_down(v, over);
                 v &= cmask;
             }
             const int o = KTB >= TPR ? (it % YKREP) * TPR * AP + (it / YKREP) * TWP : it * YRPT * TWP;
             *reinterpret_cast<u32x4 *>(ys + ylds0 + o) = v;
-        }
-#pragma unroll
-        for (int it = 0; it < XIT; ++it) {
-            u32x4 v = xreg[it];
+        } else if (i < YIT + XIT) {
+            const int it = i - YIT;
             if (RAGGED) {
-                const int over = xbase + xgoff[it] + 8 - xtotal;
-                if (xgoff[it] >= 0 && (unsigned)(h0 + x_row(it)) < (unsigned)p.H && over > 0) v = shift_down(v, over);
+                const int over = k_xbase + xgoff[it] + 8 - xtotal;
+                if (xgoff[it] >= 0 && (unsigned)(k_h0 + x_row(it)) < (unsigned)p.H && over > 0) v = shift_down(v, over);
                 v &= cmask;
             }
             const int o = CTB >= TPR ? (it % XCREP) * TPR * CP + (it / XCREP) * LWX : it * XRPT * LWX;
-            *reinterpret_cast<u32x4 *>(xs + xlds0 + o) = v;
-        }
-        if (APRON) {
-#pragma unroll
-            for (int it = 0; it < AIT; ++it) *reinterpret_cast<u32x4 *>(xs + alds0 + it * 2 * LWX) = areg[it];
+            if (x_row(it) < XROWS) *reinterpret_cast<u32x4 *>(xs + xlds0 + o) = v;
+        } else {
+            const int it = i - YIT - XIT;
+            if (a_row(it) < XROWS) *reinterpret_cast<u32x4 *>(xs + alds0 + a_row(it) * LWX) = v;
         }
     };
 
     // ---- the MFMAs of one chunk
-    const int ylane = (wk * TM * 32 + l32) * AP + 8 * g;
+    const int ylane = (wk * WTM * 32 + l32) * AP + 8 * g;
     const int xlane = (wc * 32 + l32) * CP + APR + 8 * g;
     struct Raw {
         u32x4 m;
         uint32_t lo, hi;
     };
+    constexpr int NSTEP = NCG * XROWS;   // (column group, x row) steps of a chunk
+    constexpr int LAG = 4;               // an item is written to LDS this many items after its load
     auto compute = [&](int buf) {
         const bf16_t *ys = smem + buf * BUF + ylane, *xs = smem + buf * BUF + YS + xlane;
         auto load_raw = [&](Raw &r, int cg, int xr) {
@@ -277,14 +276,14 @@ wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
                 r.hi = src[8];
             }
         };
-        auto load_a = [&](bf16x8 (&a)[TM], int cg, int row) {
+        auto load_a = [&](bf16x8 (&a)[WTM], int cg, int row) {
 #pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
+            for (int tm = 0; tm < WTM; ++tm)
                 a[tm] = *reinterpret_cast<const bf16x8 *>(ys + tm * 32 * AP + row * TWP + cg * 16);
         };
 #pragma unroll
         for (int cg = 0; cg < NCG; ++cg) {
-            bf16x8 aw[RG + 1][TM];   // dy rows in flight, by row % (RG + 1)
+            bf16x8 aw[RG + 1][WTM];   // dy rows in flight, by row % (RG + 1)
             Raw raw[2];
             load_raw(raw[0], cg, 0);
             load_a(aw[0], cg, 0);
@@ -311,31 +310,43 @@ wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
 #pragma unroll
                     for (int s = 0; s < S; ++s)
 #pragma unroll
-                        for (int tm = 0; tm < TM; ++tm)
+                        for (int tm = 0; tm < WTM; ++tm)
                             acc[tm][fr * S + s] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                                 aw[pl % (RG + 1)][tm], b[s], acc[tm][fr * S + s], 0, 0, 0);
                 }
                 __builtin_amdgcn_sched_barrier(0);
+                // this step's share of the next chunk's staging
+                const int st = cg * XROWS + xr;
+                const int lo = st * NITEMS / NSTEP, hi = (st + 1) * NITEMS / NSTEP;
+#pragma unroll
+                for (int i = 0; i < NITEMS; ++i)
+                    if (i >= lo && i < hi) item_load(i);
+#pragma unroll
+                for (int i = 0; i < NITEMS; ++i)
+                    if (i + LAG >= lo && i + LAG < hi) item_store(i, buf ^ 1);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
+#pragma unroll
+        for (int i = NITEMS - LAG; i < NITEMS; ++i) item_store(i, buf ^ 1);
     };
 
     const int cbeg = blockIdx.z * p.cps, cend = min(p.nchunks, cbeg + p.cps);
     __syncthreads();   // the zero fill is complete
     if (cbeg < cend) {
         set_chunk(cbeg);
-        prefetch();
-        stage_store(0);
+        begin_chunk();
+#pragma unroll
+        for (int i = 0; i < NITEMS; ++i) item_load(i);
+#pragma unroll
+        for (int i = 0; i < NITEMS; ++i) item_store(i, 0);
     }
     __syncthreads();
     for (int chunk = cbeg, buf = 0; chunk < cend; ++chunk, buf ^= 1) {
-        // every round issues the same loads; past the end they fetch the last chunk again
+        // every round stages a chunk; past the end it is the last chunk again
         if (chunk + 1 < cend) next_chunk();
-        prefetch();
-        __builtin_amdgcn_sched_barrier(0);
+        begin_chunk();
         compute(buf);
-        __builtin_amdgcn_sched_barrier(0);
-        stage_store(buf ^ 1);
         __syncthreads();
     }
 
@@ -349,16 +360,16 @@ wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
 #pragma unroll
     for (int ps = 0; ps < 4; ++ps) {
 #pragma unroll
-        for (int tm = 0; tm < TM; ++tm)
+        for (int tm = 0; tm < WTM; ++tm)
 #pragma unroll
             for (int t = 0; t < T; ++t)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const int rr = ((wk * TM + tm) * 2 + g) * 4 + i;
+                    const int rr = ((wk * WTM + tm) * 2 + g) * 4 + i;
                     stage[rr * EP + (wc * 32 + l32) * T + t] = acc[tm][t][4 * ps + i];
                 }
         __syncthreads();
-        for (int e = tid; e < ROWS * ROWLEN; e += 256) {
+        for (int e = tid; e < ROWS * ROWLEN; e += NT) {
             const int rr = e / ROWLEN, j = e - rr * ROWLEN;
             // rr = ((wk*TM + tm)*2 + g)*4 + i  ->  k = k0 + (wk*TM + tm)*32 + 8*ps + 4*g + i
             const int k = k0 + (rr >> 3) * 32 + 8 * ps + (rr & 7);
@@ -413,8 +424,9 @@ bool make_rplan(const ConvGeom &g, RPlan *pl)
     const long long nch = (long long)g.N * p.rowchunks * p.ncoltiles;
     if (nch > lim) return false;
     p.nchunks = (int)nch;
-    // one k tile per wave: two (288 accumulator registers) leave too few registers for the staging
-    const int TM = 1, KTB = 2 * TM * 32;
+    // 64 k per workgroup of 256 threads; 128 k per 512 threads (two waves per SIMD, half the L1
+    // traffic per MFMA, but twice the bytes the slices add into dw) where there is enough work
+    const int TM = (g.K >= 256 && (long long)g.N * g.P * g.Q >= 20000) ? 2 : 1, KTB = 2 * TM * 32;
     p.ctiles = (g.C + CTB - 1) / CTB;
     const int ktiles = (g.K + KTB - 1) / KTB;
     if (ktiles > 65535) return false;
@@ -442,7 +454,7 @@ hipError_t launch_shape(const bf16_t *x, const bf16_t *dy, float *out, int atomi
     static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL(kern, pl.grid, dim3(256), smem, st, x, dy, out, atomics, pl.p);
+    hipLaunchKernelGGL(kern, pl.grid, dim3(TM * 256), smem, st, x, dy, out, atomics, pl.p);
     return hipGetLastError();
 }
 
@@ -487,8 +499,8 @@ hipError_t launch_rows_wgrad(const void *x, const void *dy, float *dw, const Con
     const int atomics = (!partial && !direct_store) ? 1 : 0;
     const bf16_t *xs = static_cast<const bf16_t *>(x), *ds = static_cast<const bf16_t *>(dy);
     hipError_t e;
-    if (pl.S == 3) e = launch_tm<3, 3, 1>(xs, ds, out, atomics, pl, st);
-    else e = launch_tm<1, 1, 1>(xs, ds, out, atomics, pl, st);
+    if (pl.S == 3) e = pl.TM == 2 ? launch_tm<3, 3, 2>(xs, ds, out, atomics, pl, st) : launch_tm<3, 3, 1>(xs, ds, out, atomics, pl, st);
+    else e = pl.TM == 2 ? launch_tm<1, 1, 2>(xs, ds, out, atomics, pl, st) : launch_tm<1, 1, 1>(xs, ds, out, atomics, pl, st);
     if (e != hipSuccess) return e;
     if (partial) return launch_reduce_partials(partial, dw, nw, slices, false, st);
     return hipSuccess;
