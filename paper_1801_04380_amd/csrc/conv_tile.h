@@ -174,9 +174,9 @@ conv_tile_kernel(const bf16_t *__restrict__ in, const bf16_t *__restrict__ w, vo
     // gather rounds: a thread takes one pixel pair x 8 channels per round
     constexpr int XR = WIDE ? ((PIXT / 32 + R - 1) * ((32 + S) / 2) + 127) / 128 : XPAIRS_MAX / 128;
     constexpr int NB = WIDE ? NF + R - 1 : NF;
-    // WIDE tiling with three or more stages per chunk: the patch comes in as whole 16-byte octets
+    // WIDE tiling, KT = 128, three or more stages per chunk: the patch comes in as whole 16-byte octets
     // of image rows, is parked in LDS as it is, and is transposed from there (see x_issue below).
-    constexpr bool XT = WIDE && NSUB >= 3;
+    constexpr bool XT = WIDE && NSUB >= 3 && KT == 128;
     constexpr int XG = WIDE ? (16 * (PIXT / 32 + R - 1) * (WIDE_LWP / 8) + 255) / 256 : XG_MAX;   // load rounds
     constexpr int XTR = WIDE ? ((PIXT / 32 + R - 1) * (31 + S) + 127) / 128 : 2 * XPAIRS_MAX / 128;  // transposition rounds
     extern __shared__ __attribute__((aligned(16))) uint4 smem[];

@@ -82,7 +82,7 @@ bool plan_for(const TileProblem &base, int R, int S, int NF, Plan *pl)
     p.nchunks = (p.Cin + 15) / 16;
     p.Mpad = (p.Kout + KT - 1) / KT * KT;
     size_t lds = ((size_t)2 * p.xslots * 2 + (size_t)2 * R * sg_of(R, S) * KT * 2) * 16;
-    if (xt3 && wide) lds += (size_t)16 * p.xt_rows * p.xt_cols * sizeof(bf16_t);
+    if (xt3 && wide && KT == 128) lds += (size_t)16 * p.xt_rows * p.xt_cols * sizeof(bf16_t);
     if (lds < (size_t)4 * 32 * EPI_PITCH) lds = (size_t)4 * 32 * EPI_PITCH;   // the epilogue's staging
     if (lds > (size_t)LDS_LIMIT) return false;
     if (nrowtiles * p.ncoltiles > 0x7fffffffLL) return false;
@@ -103,11 +103,6 @@ bool make_plan(const TileProblem &base, int R, int S, bool staged, Plan *pl)
     if (!plan_for(base, R, S, 4, pl)) return false;
     const bool multi = (R == 3 && S == 3) || (R == 1 && S == 1);
     if (!multi) return true;
-    // 64 output channels in the WIDE tiling: half the pixels per workgroup, so that two fit on a CU
-    if (pl->KT == 64 && pl->wide) {
-        Plan alt;
-        if (plan_for(base, R, S, 2, &alt) && alt.wide) *pl = alt;
-    }
     // fewer workgroups than compute units: halve the pixels per workgroup
     if ((long long)pl->grid.x * pl->grid.y < 256) {
         Plan alt;
