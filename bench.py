@@ -24,6 +24,13 @@ sys.path.insert(0, ROOT)
 
 PEAK = {"bf16_mfma_tflops": 2500.0, "f32_mfma_tflops": 157.3, "hbm_gbs": 8000.0}
 
+# HBM bytes per launch of an op class, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this
+# command (profiles/bench_vgg16_n32_hbm_traffic.txt gives the runs, the calibration and the sums).
+# Only for the workload and budget the counters were collected on; anything else reports null.
+MEASURED_TRAFFIC = {("cfg3_vgg16_n32", 2 << 30, "conv_bwd_filter"): 397e6}
+KERNELS = {"conv_fwd": "conv_tile_kernel (+ pack_filter_kernel)", "conv_bwd_data": "conv_tile_kernel (+ pack_filter_kernel)",
+           "conv_bwd_filter": "wgrad_rows_kernel (+ fill_zero_kernel or reduce_partials_kernel)"}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -254,7 +261,9 @@ def main():
         achieved = d["nbytes"] / d["launches"] / (avg_ms * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": achieved, "peak": PEAK["hbm_gbs"], "unit": "GB/s",
                 "frac": achieved / PEAK["hbm_gbs"], "traffic": None}
-    roof.update({"kernel": dom, "launches_per_step": d["launches"] / args.steps, "avg_launch_ms": avg_ms})
+    roof["traffic"] = MEASURED_TRAFFIC.get((cfg["name"], budget, dom))
+    roof.update({"kernel": dom, "hip_kernels": KERNELS.get(dom, dom), "launches_per_step": d["launches"] / args.steps,
+                 "avg_launch_ms": avg_ms, "algorithmic_bytes_per_launch": d["nbytes"] / d["launches"]})
 
     breakdown = {}
     for k, v in sorted(by_key.items()):
