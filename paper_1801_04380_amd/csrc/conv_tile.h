@@ -69,12 +69,17 @@ struct TileProblem {
     // filter access: A(m, red, tap) = w[m*w_sm + red*w_sr + (tflip ? T-1-tap : tap)]
     int w_sm, w_sr, tflip;
     int Mpad;                // rows per (chunk, tap) block of the packed filter
+    // conv_tile2.h only: load rounds and transposition rounds per chunk, bytes of one parked buffer
+    int xg_rounds, xtr_rounds, pk_bytes;
+    int xt_upc;              // units of the load size a parked channel has room for (64, 128 or 256)
+    uint32_t in_bytes, w_bytes;   // sizes of the input tensor and of the packed filter
 };
 
 struct Plan {
     TileProblem p;
     int KT, NF;
     bool wide;
+    int dw;                  // conv_tile2.h only: bytes per load item (16 or 4)
     size_t lds;
     dim3 grid;
 };

@@ -1,6 +1,6 @@
 // Host side of the stride-1 bf16 tile convolution (the kernel is in conv_tile.h): the
 // filter packing kernel, the choice of the tiling, and the entry points.
-#include "conv_tile.h"
+#include "conv_tile2.h"
 
 namespace sn {
 namespace {
@@ -111,6 +111,47 @@ bool make_plan(const TileProblem &base, int R, int S, bool staged, Plan *pl)
     return true;
 }
 
+// The tiling for the second-generation kernel (conv_tile2.h), or false where it does not apply:
+// 3x3 filters, more than 64 output channels, an even image width (a multiple of 8 for the
+// WIDE tiling), an input tensor of at most 2 GiB.
+bool make_plan2(const TileProblem &base, int R, int S, Plan *pl)
+{
+    if (!(R == 3 && S == 3) || base.Kout <= 64 || base.Win % 2 != 0) return false;
+    if (!make_plan(base, R, S, true, pl) || pl->KT != 128 || (pl->NF != 4 && pl->NF != 2)) return false;
+    TileProblem &p = pl->p;
+    const int dw = p.Win % 8 == 0 ? 16 : 4;
+    if (pl->wide && dw != 16) return false;
+    const int pixt = 2 * pl->NF * 32;
+    if (pl->wide) {
+        p.xt_rows = pixt / 32 + R - 1;
+        p.xt_cols = WIDE_LWP;
+    } else {
+        // xt_rows = the most patch rows of a tile (set by plan_for); a parked row holds the image row
+        p.xt_cols = dw == 16 ? p.Win : (p.Win + 3) / 4 * 4;
+    }
+    const int units = p.xt_rows * (p.xt_cols * 2 / dw);   // units of dw bytes per parked channel
+    p.xt_upc = units <= 64 ? 64 : units <= 128 ? 128 : 256;
+    if (units > 256 || (dw == 16 && p.xt_upc != 64)) return false;
+    p.xg_rounds = 16 * p.xt_upc / 256;
+    p.xtr_rounds = (2 * p.xt_rows * ((p.xt_cols + 15) / 16) + 15) / 16;
+    if (!pl->wide && p.xtr_rounds > V2_XTR_MAX_NARROW) return false;
+    const int chstride = p.xt_upc * dw + V2_CH_PAD;
+    p.pk_bytes = (16 * chstride + V2_PK_SLACK + 15) / 16 * 16;
+    if (p.pk_bytes > 0xffff) return false;   // transposition offsets are 16 bits
+    if ((p.xslots * 2 + V2_TRASH) > 0xffff) return false;
+    const unsigned long long in_bytes = 2ull * p.N * p.Cin * p.Hin * p.Win;
+    const unsigned long long w_bytes = 32ull * p.nchunks * R * S * p.Mpad;
+    if (in_bytes > 0x80000000ull || w_bytes >= 0xfffffff0ull) return false;
+    p.in_bytes = (uint32_t)in_bytes;
+    p.w_bytes = (uint32_t)w_bytes;
+    size_t lds = (size_t)2 * (p.xslots * 2 + V2_TRASH) * 16 + (size_t)2 * p.pk_bytes;
+    if (lds < (size_t)4 * 32 * EPI_PITCH) lds = (size_t)4 * 32 * EPI_PITCH;
+    if (lds > (size_t)LDS_LIMIT) return false;
+    pl->lds = lds;
+    pl->dw = dw;
+    return true;
+}
+
 bool problem_of(const ConvGeom &g, bool bwd_data, TileProblem *p)
 {
     if (!g.in_bf16 || g.sh != 1 || g.sw != 1) return false;
@@ -177,6 +218,9 @@ hipError_t launch_tile_conv(const void *in, const void *w, void *out, const Conv
     }
     const bf16_t *src = static_cast<const bf16_t *>(in);
     const bool staged = packed != nullptr;
+    Plan pl2;
+    if (staged && reinterpret_cast<uintptr_t>(in) % 16 == 0 && make_plan2(p, g.R, g.S, &pl2))
+        return launch_tile2_3x3(src, wsrc, out, pl2, st);
     if (g.R == 1 && g.S == 1) return launch_tile_1x1(src, wsrc, out, pl, staged, st);
     if (g.R == 3 && g.S == 3) return launch_tile_3x3(src, wsrc, out, pl, staged, st);
     return launch_tile_other(g.R, g.S, src, wsrc, out, pl, staged, st);

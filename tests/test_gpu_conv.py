@@ -40,6 +40,18 @@ CASES = [
     (L("wide_k64", 16, 37, 70, 64, 3, 3, (1, 1), (1, 1)), 1),
     (L("small_imgs", 32, 7, 7, 96, 3, 3, (1, 1), (1, 1)), 9),         # one tile spans several images
     (L("1x1_small", 40, 7, 7, 48, 1, 1), 11),
+    # 3x3 with more than 64 output channels (forward) or input channels (backward-data) and an even
+    # width: the tilings of the packed-filter kernel that loads its patch straight into LDS
+    (L("cols72", 40, 21, 72, 136, 3, 3, (1, 1), (1, 1)), 2),          # column tiles, 16-byte items, ragged rows
+    (L("cols64_big", 24, 64, 64, 160, 3, 3, (1, 1), (1, 1)), 8),      # enough tiles for the largest tile size
+    (L("w8", 48, 8, 8, 96, 3, 3, (1, 1), (1, 1)), 20),                # rows of several images in one tile
+    (L("w24", 17, 11, 24, 80, 3, 3, (1, 1), (1, 1)), 3),
+    (L("w28", 64, 28, 28, 128, 3, 3, (1, 1), (1, 1)), 3),             # 4-byte items
+    (L("w14", 35, 14, 14, 96, 3, 3, (1, 1), (1, 1)), 7),
+    (L("w6_pad0", 20, 9, 6, 70, 3, 3, (1, 1), (0, 0)), 5),
+    (L("w28_big", 16, 28, 28, 256, 3, 3, (1, 1), (1, 1)), 48),
+    (L("c96_bwd", 96, 16, 16, 48, 3, 3, (1, 1), (1, 1)), 3),          # backward-data into 96 channels
+    (L("c130_pad2", 130, 10, 12, 130, 3, 3, (1, 1), (2, 2)), 2),
 ]
 IDS = [c[0].name for c in CASES]
 
