@@ -126,7 +126,7 @@ __device__ __forceinline__ void conv_tile2_body(const bf16_t *__restrict__ in, c
         const bool full = c0 + 16 <= p.Cin;
 #pragma unroll
         for (int rd = 0; rd < XG; ++rd) {
-            if (rd >= p.xg_rounds) break;
+            if (DW == 4 && rd >= p.xg_rounds) break;   // 16-byte items: always 4 rounds
             const int cr = c0 + rd * gch;   // first channel of the round
             const bool ok = xg_off != OUTSIDE && (full || cr + xg_sub < p.Cin);
             const uint32_t off = ok ? xg_off : OUTSIDE;
@@ -229,24 +229,41 @@ __device__ __forceinline__ void conv_tile2_body(const bf16_t *__restrict__ in, c
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][f][v] = 0.f;
 
-    auto compute = [&](const uint4 *__restrict__ xb, const u32x4(&a)[TRES * 2], int sg) {
+    // The MFMAs of one stage.  WIDE: the operand of output row i, tap row r is the operand of
+    // output row i+1, tap row r-1, so a stage reads NF+R-1 patch rows; the first R-1 of them are
+    // not needed by the last tap row, during which the next stage's first R-1 rows are fetched.
+    bf16x8 bw[NB];
+    auto compute = [&](const uint4 *__restrict__ xb, const u32x4(&a)[TRES * 2], auto sgc) {
+        constexpr int sg = decltype(sgc)::value;
+        static_assert(SG == 1 || !WIDE, "the row window is written for one filter column per stage");
 #pragma unroll
         for (int sl = 0; sl < SG; ++sl) {
             const int s = sg * SG + sl;
-            bf16x8 b[NB];
+            const int wslot = pixbase[0] + s;
+            const uint4 *bp = xb + wslot * 2 + (g ^ swz(wslot));        // WIDE: this stage's rows
+            const uint4 *bn = xb + (wslot + 1) * 2 + (g ^ swz(wslot + 1));   // and the next stage's
             if (WIDE) {
-                const int slot = pixbase[0] + s;
-                const uint4 *bp = xb + slot * 2 + (g ^ swz(slot));
 #pragma unroll
-                for (int j = 0; j < NB; ++j) b[j] = *reinterpret_cast<const bf16x8 *>(bp + j * WIDE_LWP * 2);
+                for (int j = (sg == 0 ? 0 : R - 1); j < NB; ++j)
+                    bw[j] = *reinterpret_cast<const bf16x8 *>(bp + j * WIDE_LWP * 2);
             }
 #pragma unroll
             for (int r = 0; r < R; ++r) {
+                bf16x8 b[NF];
                 if (!WIDE) {
 #pragma unroll
                     for (int f = 0; f < NF; ++f) {
                         const int slot = pixbase[f] + s;
                         b[f] = *reinterpret_cast<const bf16x8 *>(xb + (slot + r * LWp) * 2 + (g ^ swz(slot)));
+                    }
+                } else {
+#pragma unroll
+                    for (int f = 0; f < NF; ++f) b[f] = bw[f + r];
+                    if (r == R - 1 && sg + 1 < NSUB) {
+#pragma unroll
+                        for (int j = 0; j < R - 1; ++j)
+                            bw[j] = *reinterpret_cast<const bf16x8 *>(bn + j * WIDE_LWP * 2);
+                        __builtin_amdgcn_sched_barrier(0);   // issued before the last tap row's MFMAs, not after
                     }
                 }
 #pragma unroll
@@ -255,7 +272,7 @@ __device__ __forceinline__ void conv_tile2_body(const bf16_t *__restrict__ in, c
                     for (int i = 0; i < 2; ++i) {
                         bf16x8 av;
                         __builtin_memcpy(&av, &a[(r * SG + sl) * 2 + i], 16);
-                        acc[i][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WIDE ? b[f + r] : b[f], av, acc[i][f], 0, 0, 0);
+                        acc[i][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[f], av, acc[i][f], 0, 0, 0);
                     }
             }
         }
@@ -286,7 +303,7 @@ __device__ __forceinline__ void conv_tile2_body(const bf16_t *__restrict__ in, c
         if (!tail && sg == 0) dma_issue(min(chunk + 2, p.nchunks - 1), pcur);
         __builtin_amdgcn_sched_barrier(0);   // the loads are issued a whole stage before their use
         if (!tail && sg == NSUB - 1) x_transpose(pnext, xnext);
-        compute(xcur, areg[par], sg);
+        compute(xcur, areg[par], sgc);
         if (!tail && sg == NSUB - 1) __syncthreads();
     };
     int chunk0 = 0;

@@ -369,16 +369,30 @@ wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
                     stage[rr * EP + (wc * 32 + l32) * T + t] = acc[tm][t][4 * ps + i];
                 }
         __syncthreads();
-        for (int e = tid; e < ROWS * ROWLEN; e += NT) {
-            const int rr = e / ROWLEN, j = e - rr * ROWLEN;
-            // rr = ((wk*TM + tm)*2 + g)*4 + i  ->  k = k0 + (wk*TM + tm)*32 + 8*ps + 4*g + i
-            const int k = k0 + (rr >> 3) * 32 + 8 * ps + (rr & 7);
-            const int c = c0 + j / T;
-            if (k < p.K && c < p.C) {
-                const size_t off = (size_t)k * p.C * T + (size_t)c0 * T + j;
-                const float val = stage[rr * EP + j];
-                if (use_atomics) unsafeAtomicAdd(dst + off, val);
-                else dst[off] = val;
+        if (!use_atomics && p.C % CTB == 0 && (reinterpret_cast<uintptr_t>(dst) & 15) == 0) {
+            // whole rows of 64 c x T taps are contiguous and 16-byte aligned in dw: float4 stores
+            constexpr int R4 = ROWLEN / 4;
+            for (int e = tid; e < ROWS * R4; e += NT) {
+                const int rr = e / R4, j = (e - rr * R4) * 4;
+                const int k = k0 + (rr >> 3) * 32 + 8 * ps + (rr & 7);
+                if (k < p.K) {
+                    const float *sp = stage + rr * EP + j;
+                    const float4 v = make_float4(sp[0], sp[1], sp[2], sp[3]);
+                    *reinterpret_cast<float4 *>(dst + (size_t)k * p.C * T + (size_t)c0 * T + j) = v;
+                }
+            }
+        } else {
+            for (int e = tid; e < ROWS * ROWLEN; e += NT) {
+                const int rr = e / ROWLEN, j = e - rr * ROWLEN;
+                // rr = ((wk*TM + tm)*2 + g)*4 + i  ->  k = k0 + (wk*TM + tm)*32 + 8*ps + 4*g + i
+                const int k = k0 + (rr >> 3) * 32 + 8 * ps + (rr & 7);
+                const int c = c0 + j / T;
+                if (k < p.K && c < p.C) {
+                    const size_t off = (size_t)k * p.C * T + (size_t)c0 * T + j;
+                    const float val = stage[rr * EP + j];
+                    if (use_atomics) unsafeAtomicAdd(dst + off, val);
+                    else dst[off] = val;
+                }
             }
         }
         __syncthreads();
