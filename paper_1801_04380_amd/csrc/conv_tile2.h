@@ -8,8 +8,9 @@
 //  * The filter operand never touches LDS.  In the packed layout the 16 bytes a
 //    lane needs for one (tap, 32 output channels) tile are one aligned item and the
 //    64 items of a wave are one contiguous 1 KB run, so each wave fetches its own
-//    operands from L2 straight into registers, one stage (filter column) ahead,
-//    into one of two register sets.
+//    operands from L2 straight into registers, one stage (filter column) ahead
+//    into one of two register sets (five stages ahead into one of six for the
+//    smaller tiles, whose stages are short).
 //  * The input patch of a 16-channel chunk travels global memory -> LDS without
 //    passing through registers (global_load_lds): items of DW bytes (16, or 4 when
 //    the image width is not a multiple of 8) land in a "parked" buffer laid out
@@ -168,21 +169,26 @@ __device__ __forceinline__ void conv_tile2_body(const bf16_t *__restrict__ in, c
     const int chs4 = 4 * chstride;   // bytes between channel c and c + 4 of the parked patch
     // xb0 is the start of LDS: the indices count from there for either patch buffer
     auto x_transpose = [&](const char *__restrict__ pk, uint4 *__restrict__ xb) {
-        s16x4 lo[XTR], hi[XTR];
+        constexpr int GRP = (NF >= 4) ? XTR : 2;   // rounds whose reads are in flight together
 #pragma unroll
-        for (int rd = 0; rd < XTR; ++rd) {
-            if (!WIDE && rd >= p.xtr_rounds) break;
-            const uint32_t src = xs_sd[rd] & 0xffffu;
-            lo[rd] = lds_read_tr16(pk + src);
-            hi[rd] = lds_read_tr16(pk + src + chs4);
-        }
+        for (int r0 = 0; r0 < XTR; r0 += GRP) {
+            if (!WIDE && r0 >= p.xtr_rounds) break;
+            s16x4 lo[GRP], hi[GRP];
 #pragma unroll
-        for (int rd = 0; rd < XTR; ++rd) {
-            if (!WIDE && rd >= p.xtr_rounds) break;
-            u32x4 v;
-            __builtin_memcpy(&v, &lo[rd], 8);
-            __builtin_memcpy(reinterpret_cast<char *>(&v) + 8, &hi[rd], 8);
-            reinterpret_cast<u32x4 *>(xb)[xs_sd[rd] >> 16] = v;
+            for (int i = 0; i < GRP; ++i) {
+                if (r0 + i >= XTR) continue;
+                const uint32_t src = xs_sd[r0 + i] & 0xffffu;
+                lo[i] = lds_read_tr16(pk + src);
+                hi[i] = lds_read_tr16(pk + src + chs4);
+            }
+#pragma unroll
+            for (int i = 0; i < GRP; ++i) {
+                if (r0 + i >= XTR) continue;
+                u32x4 v;
+                __builtin_memcpy(&v, &lo[i], 8);
+                __builtin_memcpy(reinterpret_cast<char *>(&v) + 8, &hi[i], 8);
+                reinterpret_cast<u32x4 *>(xb)[xs_sd[r0 + i] >> 16] = v;
+            }
         }
     };
 
@@ -192,7 +198,11 @@ __device__ __forceinline__ void conv_tile2_body(const bf16_t *__restrict__ in, c
     const __amdgpu_buffer_rsrc_t w_rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(w), 0, p.w_bytes, 0x00020000);
     const uint32_t wlane = (uint32_t)(((k0 + wk * 64 + l32) * 2 + (g ^ swz(l32))) * 16);
     const uint32_t wtap = (uint32_t)p.Mpad * 32u;   // bytes per tap
-    u32x4 areg[2][TRES * 2];
+    // Register sets of filter operands: a stage's set is loaded AD - 1 stages ahead.  Small tiles
+    // have short stages and few registers in accumulators: they look further ahead.
+    constexpr int AD = (NF >= 4) ? 2 : 2 * NSUB;
+    static_assert((2 * NSUB) % AD == 0, "a trip of the main loop must use every set equally often");
+    u32x4 areg[AD][TRES * 2];
     auto load_a = [&](int stage, u32x4(&dst)[TRES * 2]) {
         const uint32_t sbase = (uint32_t)min(stage, nstage - 1) * (uint32_t)TRES * wtap;
 #pragma unroll
@@ -279,7 +289,8 @@ __device__ __forceinline__ void conv_tile2_body(const bf16_t *__restrict__ in, c
     };
 
     // ---- prologue: chunks 0 and 1 on their way, chunk 0 transposed
-    load_a(0, areg[0]);
+#pragma unroll
+    for (int i = 0; i < AD - 1; ++i) load_a(i, areg[i]);
     dma_issue(0, pk0);
     dma_issue(min(1, p.nchunks - 1), pk1);
     __syncthreads();   // zero fill done, both parked patches have landed
@@ -299,24 +310,34 @@ __device__ __forceinline__ void conv_tile2_body(const bf16_t *__restrict__ in, c
 #pragma unroll
             for (int f = 0; f < (WIDE ? 1 : NF); ++f) asm volatile("" : "+v"(pixbase[f]));
         }
-        if (!tail || sg + 1 < NSUB) load_a(chunk * NSUB + sg + 1, areg[par ^ 1]);
+        load_a(chunk * NSUB + sg + AD - 1, areg[(par + AD - 1) % AD]);   // past the end: the last stage again
         if (!tail && sg == 0) dma_issue(min(chunk + 2, p.nchunks - 1), pcur);
         __builtin_amdgcn_sched_barrier(0);   // the loads are issued a whole stage before their use
         if (!tail && sg == NSUB - 1) x_transpose(pnext, xnext);
         compute(xcur, areg[par], sgc);
-        if (!tail && sg == NSUB - 1) __syncthreads();
+        if (!tail && sg == NSUB - 1) {
+            // End of a chunk: the next patch buffer has been written, and the parked patch after
+            // it, whose loads were issued a chunk ago, has to have landed; the loads issued since
+            // (KEEP of them, at least) stay in flight, which a fence would not allow.
+            constexpr int KEEP = (2 * NSUB - 1) * TRES * 2 + (DW == 16 ? 4 : 8);
+            static_assert(KEEP < 64, "the counter has 6 bits");
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_waitcnt((KEEP & 15) | ((KEEP >> 4) << 14) | (7 << 4));   // vmcnt(KEEP) lgkmcnt(0)
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+        }
     };
     int chunk0 = 0;
     for (; chunk0 + 1 < p.nchunks; chunk0 += 2) {
         static_for<2 * NSUB>([&](auto idx) {
             constexpr int c = decltype(idx)::value / NSUB, sg = decltype(idx)::value % NSUB;
             stage(std::integral_constant<int, c>{}, std::integral_constant<int, sg>{},
-                  std::integral_constant<int, decltype(idx)::value & 1>{}, std::false_type{}, chunk0 + c);
+                  std::integral_constant<int, decltype(idx)::value % AD>{}, std::false_type{}, chunk0 + c);
         });
     }
     if (p.nchunks & 1) {
         static_for<NSUB>([&](auto idx) {
-            stage(std::integral_constant<int, 0>{}, idx, std::integral_constant<int, decltype(idx)::value & 1>{},
+            stage(std::integral_constant<int, 0>{}, idx, std::integral_constant<int, decltype(idx)::value % AD>{},
                   std::true_type{}, chunk0);
         });
     }
