@@ -9,9 +9,15 @@ backward passes, CONV backward-data and CONV backward-filter, each CONV planned
 under the given workspace budget.  Inputs are resident in HBM before the timed
 region; autotuning happens before it too.
 
+After the warm-up steps a few steps run with a pair of events around every call:
+that gives the per-class breakdown and names the dominant class, and is not part
+of the timed region (two hundred event records per step cost time of their own).
+The timed region is exactly --steps steps with events only around the launches of
+the dominant class, on the stream they are launched on.
+
 Prints ONE JSON line: conv fwd+bwd TFLOP/s over the whole step time, the roofline
-of the dominant kernel class (timed with events on the launch stream inside the
-timed region), and the CPU oracle timed on a bounded sample as a baseline.
+of the dominant kernel class from the events of the timed region, and the CPU
+oracle timed on a bounded sample as a baseline.
 """
 import argparse
 import json
@@ -35,8 +41,8 @@ KERNELS = {"conv_fwd": "conv_tile_kernel (+ pack_filter_kernel)", "conv_bwd_data
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", type=int, default=3, help="configuration number 1..5 (3 = VGG-16 N=32)")
     ap.add_argument("--budget-mib", type=float, default=None, help="workspace budget; default: the largest listed")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -202,9 +208,10 @@ def main():
     cfg, ops, plans, tune_ms = build_ops(args.workload, budget, not args.no_autotune)
     stream = torch.cuda.current_stream()
 
-    def step(timed):
+    def step(timed_keys):
+        """One pass of the hot path; ops whose class is in timed_keys get a pair of events."""
         for op in ops:
-            if timed:
+            if timed_keys is None or op.key in timed_keys:
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record(stream)
                 op.fn()
@@ -213,44 +220,57 @@ def main():
             else:
                 op.fn()
 
+    def collect():
+        # an Op object appears once per occurrence in the step; shared objects (mult > 1) hold all their events
+        seen, table = set(), {}
+        for op in ops:
+            if id(op) in seen or not op.ev:
+                continue
+            seen.add(id(op))
+            times = [a.elapsed_time(bb) for a, bb in op.ev]
+            k = table.setdefault(op.key, dict(ms=0.0, launches=0, flops=0.0, nbytes=0.0, nominal=0.0, layers={}))
+            k["ms"] += sum(times)
+            k["launches"] += len(times)
+            k["flops"] += op.flops * len(times)
+            k["nominal"] += op.nominal * len(times)
+            k["nbytes"] += op.nbytes * len(times)
+            lay = k["layers"].setdefault(op.layer, dict(ms=0.0, launches=0, flops=op.flops, nbytes=op.nbytes))
+            lay["ms"] += sum(times)
+            lay["launches"] += len(times)
+            op.ev = None
+        return table
+
     for _ in range(args.warmup):
-        step(False)
+        step(set())
+    # per-class breakdown: a pass of its own with events around every op (the events cost time, so
+    # it is not the timed region); it also says which class is the dominant one
+    BREAKDOWN_STEPS = 3
+    torch.cuda.synchronize()
+    for _ in range(BREAKDOWN_STEPS):
+        step(None)
+    torch.cuda.synchronize()
+    by_key = collect()
+    dom = max(by_key, key=lambda k: by_key[k]["ms"])
+    # the timed region: exactly args.steps steps, events only around the launches of the dominant class
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step(True)
+        step({dom})
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    d = collect()[dom]
 
-    # an Op object appears once per occurrence in the step; shared objects (mult > 1) hold all their events
-    seen, by_key = set(), {}
-    for op in ops:
-        if id(op) in seen:
-            continue
-        seen.add(id(op))
-        times = [a.elapsed_time(bb) for a, bb in op.ev]
-        k = by_key.setdefault(op.key, dict(ms=0.0, launches=0, flops=0.0, nbytes=0.0, nominal=0.0, layers={}))
-        k["ms"] += sum(times)
-        k["launches"] += len(times)
-        k["flops"] += op.flops * len(times)
-        k["nominal"] += op.nominal * len(times)
-        k["nbytes"] += op.nbytes * len(times)
-        lay = k["layers"].setdefault(op.layer, dict(ms=0.0, launches=0, flops=op.flops, nbytes=op.nbytes))
-        lay["ms"] += sum(times)
-        lay["launches"] += len(times)
     conv_keys = [k for k in by_key if k.startswith("conv_")]
-    conv_flops_step = sum(by_key[k]["flops"] for k in conv_keys) / args.steps
-    conv_ms_step = sum(by_key[k]["ms"] for k in conv_keys) / args.steps
+    conv_flops_step = sum(by_key[k]["flops"] for k in conv_keys) / BREAKDOWN_STEPS
+    conv_ms_step = sum(by_key[k]["ms"] for k in conv_keys) / BREAKDOWN_STEPS
     cheap_keys = [k for k in by_key if not k.startswith("conv_")]
-    cheap_bytes_step = sum(by_key[k]["nbytes"] for k in cheap_keys) / args.steps
-    cheap_ms_step = sum(by_key[k]["ms"] for k in cheap_keys) / args.steps
+    cheap_bytes_step = sum(by_key[k]["nbytes"] for k in cheap_keys) / BREAKDOWN_STEPS
+    cheap_ms_step = sum(by_key[k]["ms"] for k in cheap_keys) / BREAKDOWN_STEPS
     replay_keys = [k for k in cheap_keys if k.endswith("_fwd")]
     replay_gbs = (sum(by_key[k]["nbytes"] for k in replay_keys) / max(sum(by_key[k]["ms"] for k in replay_keys), 1e-9)
                   / 1e6)
     value = conv_flops_step / (wall_ms * 1e-3) / 1e12
 
-    dom = max(by_key, key=lambda k: by_key[k]["ms"])
-    d = by_key[dom]
     avg_ms = d["ms"] / d["launches"]
     if dom.startswith("conv_"):
         peak = PEAK["bf16_mfma_tflops"] if cfg["dtype"] == "bf16" else PEAK["f32_mfma_tflops"]
@@ -267,7 +287,7 @@ def main():
 
     breakdown = {}
     for k, v in sorted(by_key.items()):
-        e = {"ms_per_step": v["ms"] / args.steps}
+        e = {"ms_per_step": v["ms"] / BREAKDOWN_STEPS}
         if v["flops"]:
             e["tflops"] = v["flops"] / (v["ms"] * 1e-3) / 1e12
             e["frac_mfma_peak"] = e["tflops"] / (PEAK["bf16_mfma_tflops"] if cfg["dtype"] == "bf16"
