@@ -4,9 +4,10 @@
 One step = one pass of the whole hot path over one batch of a synthetic,
 network-shaped workload (default: the VGG-16-shaped configuration, N = 32, bf16
 in / fp32 accumulate): for every conv layer, CONV forward, BN forward, ReLU
-forward and max-pool forward (the layers recomputation replays), then their
-backward passes, CONV backward-data and CONV backward-filter, each CONV planned
-under the given workspace budget.  Inputs are resident in HBM before the timed
+forward and max-pool forward (the layers recomputation replays; BN and the ReLU
+after it are one call, sn_bn_relu_fwd, unless --no-fuse), then their backward
+passes, CONV backward-data and CONV backward-filter, each CONV planned under the
+given workspace budget.  Inputs are resident in HBM before the timed
 region; autotuning happens before it too.
 
 After the warm-up steps a few steps run with a pair of events around every call:
@@ -47,6 +48,7 @@ def parse():
     ap.add_argument("--budget-mib", type=float, default=None, help="workspace budget; default: the largest listed")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-autotune", action="store_true")
+    ap.add_argument("--no-fuse", action="store_true", help="BN forward and ReLU forward as two calls instead of one")
     ap.add_argument("--detail", default=None, help="write the per-layer table to this JSON file")
     return ap.parse_args()
 
@@ -61,7 +63,7 @@ class Op:
         self.ev = None
 
 
-def build_ops(cfg_no, budget, autotune):
+def build_ops(cfg_no, budget, autotune, fuse):
     import torch
 
     import paper_1801_04380_amd as sn
@@ -119,12 +121,19 @@ def build_ops(cfg_no, budget, autotune):
             mean, invstd = torch.empty(K, device=dev), torch.empty(K, device=dev)
             dgamma, dbeta = torch.empty(K, device=dev), torch.empty(K, device=dev)
             g_bn = torch.empty_like(y)
-            cheap_f.append(Op("bn_fwd", layer.name,
-                              lambda y=y, ga=gamma, be=beta, o=ybn, m=mean, i=invstd: sn.sn_bn_fwd(y, ga, be, o, m, i),
-                              nbytes=2 * E * b))
-            act_in = ybn
         a = torch.empty_like(y)
-        cheap_f.append(Op("relu_fwd", layer.name, lambda s=act_in, o=a: sn.sn_relu_fwd(s, o), nbytes=2 * E * b))
+        if cfg["bn"] and fuse:
+            # BN and the ReLU after it in one pass: 1 read + 1 write of E elements is all the pair needs
+            cheap_f.append(Op("bn_relu_fwd", layer.name,
+                              lambda y=y, ga=gamma, be=beta, o=a, m=mean, i=invstd: sn.sn_bn_relu_fwd(y, ga, be, o, m, i),
+                              nbytes=2 * E * b))
+        else:
+            if cfg["bn"]:
+                cheap_f.append(Op("bn_fwd", layer.name,
+                                  lambda y=y, ga=gamma, be=beta, o=ybn, m=mean, i=invstd: sn.sn_bn_fwd(y, ga, be, o, m, i),
+                                  nbytes=2 * E * b))
+                act_in = ybn
+            cheap_f.append(Op("relu_fwd", layer.name, lambda s=act_in, o=a: sn.sn_relu_fwd(s, o), nbytes=2 * E * b))
         g_a = torch.empty_like(y)
         if layer.pool:
             kernel, stride = layer.pool
@@ -205,7 +214,7 @@ def main():
         budget = int(args.budget_mib * (1 << 20))
     else:
         budget = max(budgets) if budgets else 64 << 20
-    cfg, ops, plans, tune_ms = build_ops(args.workload, budget, not args.no_autotune)
+    cfg, ops, plans, tune_ms = build_ops(args.workload, budget, not args.no_autotune, not args.no_fuse)
     stream = torch.cuda.current_stream()
 
     def step(timed_keys):
@@ -307,7 +316,8 @@ def main():
         "conv_only_tflops": conv_flops_step / (conv_ms_step * 1e-3) / 1e12,
         "conv_frac_mfma_peak": conv_flops_step / (conv_ms_step * 1e-3) / 1e12
         / (PEAK["bf16_mfma_tflops"] if cfg["dtype"] == "bf16" else PEAK["f32_mfma_tflops"]),
-        "recompute_gbs": replay_gbs, "cheap_layers_gbs": cheap_bytes_step / (cheap_ms_step * 1e-3) / 1e9,
+        "recompute_gbs": replay_gbs,
+        "recompute_ms_per_step": sum(by_key[k]["ms"] for k in replay_keys) / BREAKDOWN_STEPS, "cheap_layers_gbs": cheap_bytes_step / (cheap_ms_step * 1e-3) / 1e9,
         "autotune_ms": tune_ms,
         "roofline": roof, "breakdown": breakdown,
     }

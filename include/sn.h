@@ -160,6 +160,15 @@ sn_status sn_bn_fwd(const void *x, const float *gamma, const float *beta, void *
                     float *save_mean, float *save_invstd,
                     int N, int C, int H, int W, float eps, sn_dtype dtype, sn_stream stream);
 
+/* BN forward followed by ReLU in one pass, the segment that recomputation replays after a
+ * CONV (Sec. 3.4: the cheap layers between two checkpoints are recomputed together):
+ *   y = max(gamma*(x-mean)*invstd + beta, 0)   (0 unless the BN output is > 0),
+ * everything else as sn_bn_fwd.  The BN output itself is not stored: sn_relu_bwd gates on y,
+ * and sn_bn_bwd needs x and the saved statistics only. */
+sn_status sn_bn_relu_fwd(const void *x, const float *gamma, const float *beta, void *y,
+                         float *save_mean, float *save_invstd,
+                         int N, int C, int H, int W, float eps, sn_dtype dtype, sn_stream stream);
+
 /* BN backward from the saved statistics, xhat = (x-mean)*invstd:
  *   dbeta = sum(dy), dgamma = sum(dy*xhat),
  *   dx = gamma*invstd/M * (M*dy - dbeta - xhat*dgamma).

@@ -15,7 +15,7 @@ __all__ = [
     "SnError", "conv_shape", "sn_out_dim", "sn_conv_workspace_query", "sn_conv_plan",
     "sn_planner_record", "sn_planner_clear", "sn_conv_autotune",
     "sn_conv2d_fwd", "sn_conv2d_bwd_data", "sn_conv2d_bwd_filter",
-    "sn_relu_fwd", "sn_relu_bwd", "sn_bn_fwd", "sn_bn_bwd", "sn_maxpool_fwd", "sn_maxpool_bwd",
+    "sn_relu_fwd", "sn_relu_bwd", "sn_bn_fwd", "sn_bn_relu_fwd", "sn_bn_bwd", "sn_maxpool_fwd", "sn_maxpool_bwd",
 ]
 
 SN_F32, SN_BF16 = 0, 1
@@ -133,6 +133,12 @@ def sn_bn_fwd(x, gamma, beta, y, save_mean, save_invstd, eps=1e-5):
     N, C, H, W = x.shape
     _check("sn_bn_fwd", load().sn_bn_fwd(_ptr(x), _ptr(gamma), _ptr(beta), _ptr(y), _ptr(save_mean),
                                          _ptr(save_invstd), N, C, H, W, eps, _dtype_code(x), _stream()))
+
+
+def sn_bn_relu_fwd(x, gamma, beta, y, save_mean, save_invstd, eps=1e-5):
+    N, C, H, W = x.shape
+    _check("sn_bn_relu_fwd", load().sn_bn_relu_fwd(_ptr(x), _ptr(gamma), _ptr(beta), _ptr(y), _ptr(save_mean),
+                                                   _ptr(save_invstd), N, C, H, W, eps, _dtype_code(x), _stream()))
 
 
 def sn_bn_bwd(x, dy, gamma, save_mean, save_invstd, dx, dgamma, dbeta):

@@ -173,6 +173,9 @@ __device__ inline float wave_sum(float v)
     return v;
 }
 
+// The activation that may follow BN in the same pass: ReLU as in relu_fwd_kernel (0 unless v > 0).
+__device__ inline float act(float v, int relu) { return (!relu || v > 0.f) ? v : 0.f; }
+
 // Pass 1 (forward): per (channel, slice) partial sums of (x - shift) and
 // (x - shift)^2, shift = the channel's first element, which keeps the variance
 // free of cancellation whatever the channel's mean is.
@@ -252,13 +255,16 @@ template <typename T>
 __global__ void __launch_bounds__(256)
 bn_apply_kernel(const T *__restrict__ x, T *__restrict__ y, const float *__restrict__ gamma,
                 const float *__restrict__ beta, const float *__restrict__ mean,
-                const float *__restrict__ invstd, int N, int C, int HW, Slices sl)
+                const float *__restrict__ invstd, int N, int C, int HW, Slices sl, int relu)
 {
     constexpr int V = Vec<T>::N;
-    const int c = blockIdx.x, slice = blockIdx.y;
+    // the statistics pass has just read x front to back: walking it back to front finds the
+    // part that was read last still in the memory-side cache
+    const int c = gridDim.x - 1 - blockIdx.x, slice = gridDim.y - 1 - blockIdx.y;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const float mu = mean[c], a = gamma[c] * invstd[c], b = beta[c];
-    for (int seg = slice * 4 + wave; seg < sl.nseg; seg += 4 * sl.nslice) {
+    const int seg0 = slice * 4 + wave, step = 4 * sl.nslice;
+    for (int seg = seg0 + (seg0 < sl.nseg ? (sl.nseg - 1 - seg0) / step * step : 0); seg >= seg0 && seg < sl.nseg; seg -= step) {
         const int n = seg / sl.nseg_plane, k = seg - n * sl.nseg_plane;
         const int e0 = k * SEG, len = min(SEG, HW - e0);
         const size_t base = ((size_t)n * C + c) * HW + e0;
@@ -270,10 +276,10 @@ bn_apply_kernel(const T *__restrict__ x, T *__restrict__ y, const float *__restr
                 float f[V];
                 Vec<T>::load(p + off, f);
 #pragma unroll
-                for (int i = 0; i < V; ++i) f[i] = (f[i] - mu) * a + b;
+                for (int i = 0; i < V; ++i) f[i] = act((f[i] - mu) * a + b, relu);
                 Vec<T>::store(o + off, f);
             },
-            [&](int off) { st(o + off, (ld<T>(p + off) - mu) * a + b); });
+            [&](int off) { st(o + off, act((ld<T>(p + off) - mu) * a + b, relu)); });
     }
 }
 
@@ -353,12 +359,14 @@ bn_bwd_apply_kernel(const T *__restrict__ x, const T *__restrict__ dy, T *__rest
                     const float *__restrict__ dbeta, int N, int C, int HW, Slices sl)
 {
     constexpr int V = Vec<T>::N;
-    const int c = blockIdx.x, slice = blockIdx.y;
+    // back to front, as in bn_apply_kernel: the sums pass has just read x and dy front to back
+    const int c = gridDim.x - 1 - blockIdx.x, slice = gridDim.y - 1 - blockIdx.y;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const float invM = 1.f / ((float)N * (float)HW);
     const float mu = mean[c], is = invstd[c], k1 = gamma[c] * is;
     const float kb = dbeta[c] * invM, kg = dgamma[c] * invM * is;  // xhat*dgamma/M = (x-mu)*kg
-    for (int seg = slice * 4 + wave; seg < sl.nseg; seg += 4 * sl.nslice) {
+    const int seg0 = slice * 4 + wave, step = 4 * sl.nslice;
+    for (int seg = seg0 + (seg0 < sl.nseg ? (sl.nseg - 1 - seg0) / step * step : 0); seg >= seg0 && seg < sl.nseg; seg -= step) {
         const int n = seg / sl.nseg_plane, k = seg - n * sl.nseg_plane;
         const int e0 = k * SEG, len = min(SEG, HW - e0);
         const size_t base = ((size_t)n * C + c) * HW + e0;
@@ -378,12 +386,189 @@ bn_bwd_apply_kernel(const T *__restrict__ x, const T *__restrict__ dy, T *__rest
     }
 }
 
+// ---- BN in one pass over HBM, for channels that fit in the registers of one workgroup.
+// A workgroup of 1024 threads takes one channel: thread t holds vectors t, t + 1024, ...
+// (16 or 8 bytes each) of the channel's N*HW elements from the load until the store, so x
+// (and dy) are read once and y (dx) written once.  The statistics are two-pass sums over
+// the registers, reduced in a fixed order (wavefront butterflies, then the 16 wavefront
+// sums in index order), so they are the same from run to run.
+template <int VB> struct RawVec;
+template <> struct RawVec<16> { typedef uint4 type; };
+template <> struct RawVec<8> { typedef uint2 type; };
+
+template <typename T, int VB> __device__ inline void unpack(const typename RawVec<VB>::type &v, float (&f)[VB / sizeof(T)])
+{
+    const uint32_t *w = reinterpret_cast<const uint32_t *>(&v);
+    if (sizeof(T) == 2) {
+#pragma unroll
+        for (int i = 0; i < VB / 4; ++i) {
+            f[2 * i] = __uint_as_float(w[i] << 16);
+            f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < VB / 4; ++i) f[i] = __uint_as_float(w[i]);
+    }
+}
+
+template <typename T, int VB> __device__ inline typename RawVec<VB>::type pack(const float (&f)[VB / sizeof(T)])
+{
+    typename RawVec<VB>::type v;
+    uint32_t *w = reinterpret_cast<uint32_t *>(&v);
+    if (sizeof(T) == 2) {
+#pragma unroll
+        for (int i = 0; i < VB / 4; ++i)
+            w[i] = (uint32_t)f32_to_bf16(f[2 * i]) | ((uint32_t)f32_to_bf16(f[2 * i + 1]) << 16);
+    } else {
+#pragma unroll
+        for (int i = 0; i < VB / 4; ++i) w[i] = __float_as_uint(f[i]);
+    }
+    return v;
+}
+
+// Sum over the 1024 threads of a workgroup, the same value in every thread.
+__device__ inline float block_sum_1024(float v, float *red)
+{
+    v = wave_sum(v);
+    __syncthreads();   // red may still be read from the previous sum
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += red[i];
+    return s;
+}
+
+template <typename T, int VB, int NVMAX>
+__global__ void __launch_bounds__(1024)
+bn_fwd_fused_kernel(const T *__restrict__ x, T *__restrict__ y, const float *__restrict__ gamma,
+                    const float *__restrict__ beta, float *__restrict__ mean, float *__restrict__ invstd,
+                    int N, int C, int HW, float eps, int relu)
+{
+    constexpr int VE = VB / sizeof(T);
+    typedef typename RawVec<VB>::type VT;
+    __shared__ float red[16];
+    const int c = blockIdx.x, tid = threadIdx.x;
+    const int vpp = HW / VE, nvec = N * vpp;
+    VT v[NVMAX];
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < NVMAX; ++j) {
+        const int i = tid + j * 1024;
+        if (i < nvec) {
+            const int n = i / vpp, e = i - n * vpp;
+            v[j] = *reinterpret_cast<const VT *>(x + ((size_t)n * C + c) * HW + (size_t)e * VE);
+            float f[VE];
+            unpack<T, VB>(v[j], f);
+#pragma unroll
+            for (int k = 0; k < VE; ++k) s += f[k];
+        }
+    }
+    const float M = (float)N * (float)HW;
+    const float mu = block_sum_1024(s, red) / M;
+    float q = 0.f;
+#pragma unroll
+    for (int j = 0; j < NVMAX; ++j) {
+        if (tid + j * 1024 < nvec) {
+            float f[VE];
+            unpack<T, VB>(v[j], f);
+#pragma unroll
+            for (int k = 0; k < VE; ++k) q += (f[k] - mu) * (f[k] - mu);
+        }
+    }
+    const float var = block_sum_1024(q, red) / M;
+    const float is = 1.f / sqrtf(var + eps);
+    if (tid == 0) { mean[c] = mu; invstd[c] = is; }
+    const float a = gamma[c] * is, b = beta[c];
+#pragma unroll
+    for (int j = 0; j < NVMAX; ++j) {
+        const int i = tid + j * 1024;
+        if (i < nvec) {
+            const int n = i / vpp, e = i - n * vpp;
+            float f[VE];
+            unpack<T, VB>(v[j], f);
+#pragma unroll
+            for (int k = 0; k < VE; ++k) f[k] = act((f[k] - mu) * a + b, relu);
+            *reinterpret_cast<VT *>(y + ((size_t)n * C + c) * HW + (size_t)e * VE) = pack<T, VB>(f);
+        }
+    }
+}
+
+template <typename T, int VB, int NVMAX>
+__global__ void __launch_bounds__(1024)
+bn_bwd_fused_kernel(const T *__restrict__ x, const T *__restrict__ dy, T *__restrict__ dx,
+                    const float *__restrict__ gamma, const float *__restrict__ mean,
+                    const float *__restrict__ invstd, float *__restrict__ dgamma, float *__restrict__ dbeta,
+                    int N, int C, int HW)
+{
+    constexpr int VE = VB / sizeof(T);
+    typedef typename RawVec<VB>::type VT;
+    __shared__ float red[16];
+    const int c = blockIdx.x, tid = threadIdx.x;
+    const int vpp = HW / VE, nvec = N * vpp;
+    const float mu = mean[c], is = invstd[c];
+    VT xv[NVMAX], gv[NVMAX];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int j = 0; j < NVMAX; ++j) {
+        const int i = tid + j * 1024;
+        if (i < nvec) {
+            const int n = i / vpp, e = i - n * vpp;
+            const size_t off = ((size_t)n * C + c) * HW + (size_t)e * VE;
+            xv[j] = *reinterpret_cast<const VT *>(x + off);
+            gv[j] = *reinterpret_cast<const VT *>(dy + off);
+            float f[VE], gr[VE];
+            unpack<T, VB>(xv[j], f);
+            unpack<T, VB>(gv[j], gr);
+#pragma unroll
+            for (int k = 0; k < VE; ++k) {
+                s1 += gr[k];
+                s2 += gr[k] * (f[k] - mu);
+            }
+        }
+    }
+    const float db = block_sum_1024(s1, red);
+    const float dg = block_sum_1024(s2, red) * is;
+    if (tid == 0) { dbeta[c] = db; dgamma[c] = dg; }
+    const float invM = 1.f / ((float)N * (float)HW);
+    const float k1 = gamma[c] * is, kb = db * invM, kg = dg * invM * is;
+#pragma unroll
+    for (int j = 0; j < NVMAX; ++j) {
+        const int i = tid + j * 1024;
+        if (i < nvec) {
+            const int n = i / vpp, e = i - n * vpp;
+            const size_t off = ((size_t)n * C + c) * HW + (size_t)e * VE;
+            float f[VE], gr[VE];
+            unpack<T, VB>(xv[j], f);
+            unpack<T, VB>(gv[j], gr);
+#pragma unroll
+            for (int k = 0; k < VE; ++k) f[k] = k1 * (gr[k] - kb - (f[k] - mu) * kg);
+            *reinterpret_cast<VT *>(dx + off) = pack<T, VB>(f);
+        }
+    }
+}
+
+constexpr int BN_FUSED_NV = 13;   // vectors a thread can hold (13 * 1024 * 8 bf16 = 106496 elements per channel)
+
+// Vector size in bytes for the one-pass kernels, 0 if they do not apply.
+template <typename T> int bn_fused_vb(const void *a, const void *b, const void *c3, int N, int HW)
+{
+    const uintptr_t bits = reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b) | reinterpret_cast<uintptr_t>(c3);
+    for (int vb = 16; vb >= 8; vb /= 2) {
+        const int ve = vb / (int)sizeof(T);
+        if (HW % ve != 0 || bits % vb != 0) continue;
+        const long long nvec = (long long)N * (HW / ve);
+        if (nvec <= 1024LL * BN_FUSED_NV) return vb;
+    }
+    return 0;
+}
+
 // Tensors too small to hold the partial sums (fewer than 8 bytes per channel):
 // one thread per channel does the whole layer.
 template <typename T>
 __global__ void bn_fwd_tiny_kernel(const T *__restrict__ x, T *__restrict__ y, const float *__restrict__ gamma,
                                    const float *__restrict__ beta, float *__restrict__ mean,
-                                   float *__restrict__ invstd, int N, int C, int HW, float eps)
+                                   float *__restrict__ invstd, int N, int C, int HW, float eps, int relu)
 {
     const int c = blockIdx.x * blockDim.x + threadIdx.x;
     if (c >= C) return;
@@ -405,7 +590,7 @@ __global__ void bn_fwd_tiny_kernel(const T *__restrict__ x, T *__restrict__ y, c
     for (int n = 0; n < N; ++n)
         for (int i = 0; i < HW; ++i) {
             const size_t j = ((size_t)n * C + c) * HW + i;
-            st(y + j, (ld<T>(x + j) - mu) * a + b);
+            st(y + j, act((ld<T>(x + j) - mu) * a + b, relu));
         }
 }
 
@@ -658,15 +843,28 @@ hipError_t launch_relu_bwd(const void *x, const void *dy, void *dx, size_t n, in
 }
 
 hipError_t launch_bn_fwd(const void *x, const float *gamma, const float *beta, void *y, float *mean,
-                         float *invstd, int N, int C, int HW, float eps, int bf16, hipStream_t s)
+                         float *invstd, int N, int C, int HW, float eps, int bf16, int relu, hipStream_t s)
 {
     const size_t esz = bf16 ? 2 : 4;
     if ((size_t)N * HW * esz < 2 * sizeof(float))
         return by_dtype(bf16, [&](auto *tag) {
             typedef typename std::remove_pointer<decltype(tag)>::type T;
             hipLaunchKernelGGL(bn_fwd_tiny_kernel<T>, dim3((C + 63) / 64), dim3(64), 0, s, (const T *)x, (T *)y,
-                               gamma, beta, mean, invstd, N, C, HW, eps);
+                               gamma, beta, mean, invstd, N, C, HW, eps, relu);
         });
+    {
+        const int vb = bf16 ? bn_fused_vb<bf16_t>(x, y, nullptr, N, HW) : bn_fused_vb<float>(x, y, nullptr, N, HW);
+        if (vb)
+            return by_dtype(bf16, [&](auto *tag) {
+                typedef typename std::remove_pointer<decltype(tag)>::type T;
+                if (vb == 16)
+                    hipLaunchKernelGGL((bn_fwd_fused_kernel<T, 16, BN_FUSED_NV>), dim3(C), dim3(1024), 0, s, (const T *)x,
+                                       (T *)y, gamma, beta, mean, invstd, N, C, HW, eps, relu);
+                else
+                    hipLaunchKernelGGL((bn_fwd_fused_kernel<T, 8, BN_FUSED_NV>), dim3(C), dim3(1024), 0, s, (const T *)x,
+                                       (T *)y, gamma, beta, mean, invstd, N, C, HW, eps, relu);
+            });
+    }
     // y is dead until pass 3, so it holds the per-slice partial sums meanwhile
     const Slices sl = make_slices(N, C, HW, (size_t)N * C * HW * esz);
     float *part = reinterpret_cast<float *>(y);
@@ -677,7 +875,7 @@ hipError_t launch_bn_fwd(const void *x, const float *gamma, const float *beta, v
         hipLaunchKernelGGL(bn_stats_final_kernel<T>, dim3(C), dim3(64), 0, s, (const T *)x, part, mean, invstd,
                            N, HW, sl.nslice, eps);
         hipLaunchKernelGGL(bn_apply_kernel<T>, grid, block, 0, s, (const T *)x, (T *)y, gamma, beta, mean,
-                           invstd, N, C, HW, sl);
+                           invstd, N, C, HW, sl, relu);
     });
 }
 
@@ -692,6 +890,19 @@ hipError_t launch_bn_bwd(const void *x, const void *dy, const float *gamma, cons
             hipLaunchKernelGGL(bn_bwd_tiny_kernel<T>, dim3((C + 63) / 64), dim3(64), 0, s, (const T *)x,
                                (const T *)dy, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);
         });
+    {
+        const int vb = bf16 ? bn_fused_vb<bf16_t>(x, dy, dx, N, HW) : bn_fused_vb<float>(x, dy, dx, N, HW);
+        if (vb)
+            return by_dtype(bf16, [&](auto *tag) {
+                typedef typename std::remove_pointer<decltype(tag)>::type T;
+                if (vb == 16)
+                    hipLaunchKernelGGL((bn_bwd_fused_kernel<T, 16, BN_FUSED_NV>), dim3(C), dim3(1024), 0, s, (const T *)x,
+                                       (const T *)dy, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);
+                else
+                    hipLaunchKernelGGL((bn_bwd_fused_kernel<T, 8, BN_FUSED_NV>), dim3(C), dim3(1024), 0, s, (const T *)x,
+                                       (const T *)dy, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);
+            });
+    }
     const Slices sl = make_slices(N, C, HW, (size_t)N * C * HW * esz);
     float *part = reinterpret_cast<float *>(dx);  // dx is dead until pass 3
     return by_dtype(bf16, [&](auto *tag) {

@@ -473,8 +473,9 @@ sn_status sn_relu_bwd(const void *x, const void *dy, void *dx, size_t n, sn_dtyp
     return launch_status(launch_relu_bwd(x, dy, dx, n, dtype == SN_BF16, static_cast<hipStream_t>(stream)));
 }
 
-sn_status sn_bn_fwd(const void *x, const float *gamma, const float *beta, void *y, float *save_mean,
-                    float *save_invstd, int N, int C, int H, int W, float eps, sn_dtype dtype, sn_stream stream)
+static sn_status bn_fwd_common(const void *x, const float *gamma, const float *beta, void *y, float *save_mean,
+                               float *save_invstd, int N, int C, int H, int W, float eps, sn_dtype dtype, int relu,
+                               sn_stream stream)
 {
     sn_status s = check_cheap(N, C, H, W, dtype);
     if (s != SN_OK) return s;
@@ -484,7 +485,20 @@ sn_status sn_bn_fwd(const void *x, const float *gamma, const float *beta, void *
         return SN_ERR_BAD_ARG;
     if (C > 65535 * 32) return SN_ERR_UNSUPPORTED;
     return launch_status(launch_bn_fwd(x, gamma, beta, y, save_mean, save_invstd, N, C, H * W, eps,
-                                       dtype == SN_BF16, static_cast<hipStream_t>(stream)));
+                                       dtype == SN_BF16, relu, static_cast<hipStream_t>(stream)));
+}
+
+sn_status sn_bn_fwd(const void *x, const float *gamma, const float *beta, void *y, float *save_mean,
+                    float *save_invstd, int N, int C, int H, int W, float eps, sn_dtype dtype, sn_stream stream)
+{
+    return bn_fwd_common(x, gamma, beta, y, save_mean, save_invstd, N, C, H, W, eps, dtype, 0, stream);
+}
+
+sn_status sn_bn_relu_fwd(const void *x, const float *gamma, const float *beta, void *y, float *save_mean,
+                         float *save_invstd, int N, int C, int H, int W, float eps, sn_dtype dtype,
+                         sn_stream stream)
+{
+    return bn_fwd_common(x, gamma, beta, y, save_mean, save_invstd, N, C, H, W, eps, dtype, 1, stream);
 }
 
 sn_status sn_bn_bwd(const void *x, const void *dy, const float *gamma, const float *save_mean,

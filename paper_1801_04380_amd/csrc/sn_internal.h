@@ -84,8 +84,9 @@ hipError_t launch_col2im(const float *dcol, void *dx, const ConvGeom &g, int n0,
 // Cheap layers.
 hipError_t launch_relu_fwd(const void *x, void *y, size_t n, int bf16, hipStream_t st);
 hipError_t launch_relu_bwd(const void *x, const void *dy, void *dx, size_t n, int bf16, hipStream_t st);
+// relu != 0: the ReLU that follows BN is applied in the same pass (y = max(BN(x), 0)).
 hipError_t launch_bn_fwd(const void *x, const float *gamma, const float *beta, void *y, float *mean,
-                         float *invstd, int N, int C, int HW, float eps, int bf16, hipStream_t st);
+                         float *invstd, int N, int C, int HW, float eps, int bf16, int relu, hipStream_t st);
 hipError_t launch_bn_bwd(const void *x, const void *dy, const float *gamma, const float *mean,
                          const float *invstd, void *dx, float *dgamma, float *dbeta, int N, int C,
                          int HW, int bf16, hipStream_t st);

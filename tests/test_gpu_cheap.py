@@ -47,7 +47,9 @@ def test_relu(n, dtype):
 
 
 BN_SHAPES = [(2, 3, 5, 7), (4, 16, 14, 14), (3, 8, 7, 7), (2, 5, 35, 35), (8, 64, 56, 56), (2, 4, 224, 224),
-             (1, 1, 1, 1), (1, 3, 1, 1), (2, 2, 1, 1), (1, 2, 1, 3), (64, 32, 7, 7), (2, 130, 9, 9)]
+             (1, 1, 1, 1), (1, 3, 1, 1), (2, 2, 1, 1), (1, 2, 1, 3), (64, 32, 7, 7), (2, 130, 9, 9),
+             # a channel that just fits the one-pass kernels' registers, one just past that, 8-byte vectors
+             (32, 6, 56, 56), (34, 3, 56, 56), (32, 8, 14, 14)]
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -78,8 +80,19 @@ def test_bn(shape, dtype):
     torch.cuda.synchronize()
     assert torch.equal(y, y2) and torch.equal(mean, mean2) and torch.equal(invstd, invstd2)
 
+    # BN + ReLU in one pass: the same statistics, and exactly the ReLU of the BN output
+    a = torch.full_like(xd, float("nan"))
+    mean3, invstd3 = torch.empty_like(mean), torch.empty_like(invstd)
+    sn.sn_bn_relu_fwd(xd, gd, bd, a, mean3, invstd3, eps)
+    a_ref = torch.empty_like(y)
+    sn.sn_relu_fwd(y, a_ref)
+    torch.cuda.synchronize()
+    assert torch.equal(mean, mean3) and torch.equal(invstd, invstd3)
+    assert torch.equal(a, a_ref)
+
     yo, mo, io = oracle.bn_fwd(f64(x), f64(gamma), f64(beta), eps)
     tol = TOL[dtype]
+    assert rel_l2(f64(a), oracle.relu_fwd(yo)) <= tol
     assert rel_l2(f64(mean), mo) <= 1e-5
     assert rel_l2(f64(invstd), io) <= 1e-5
     assert rel_l2(f64(y), yo) <= tol
