@@ -34,9 +34,10 @@ PEAK = {"bf16_mfma_tflops": 2500.0, "f32_mfma_tflops": 157.3, "hbm_gbs": 8000.0}
 # HBM bytes per launch of an op class, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this
 # command (profiles/bench_vgg16_n32_hbm_traffic.txt gives the runs, the calibration and the sums).
 # Only for the workload and budget the counters were collected on; anything else reports null.
-MEASURED_TRAFFIC = {("cfg3_vgg16_n32", 2 << 30, "conv_bwd_filter"): 397e6}
-KERNELS = {"conv_fwd": "conv_tile_kernel (+ pack_filter_kernel)", "conv_bwd_data": "conv_tile_kernel (+ pack_filter_kernel)",
-           "conv_bwd_filter": "wgrad_rows_kernel (+ fill_zero_kernel or reduce_partials_kernel)"}
+MEASURED_TRAFFIC = {("cfg3_vgg16_n32", 2 << 30, "conv_bwd_filter"): 423e6}
+KERNELS = {"conv_fwd": "conv_tile2_kernel / conv_tile_kernel (+ pack_filter_kernel)",
+           "conv_bwd_data": "conv_tile2_kernel / conv_tile_kernel (+ pack_filter_kernel)",
+           "conv_bwd_filter": "wgrad_rows_kernel + reduce_partials4_kernel (STAGED) or fill_zero_kernel (DIRECT)"}
 
 
 def parse():
