@@ -73,6 +73,7 @@ struct TileProblem {
     int xg_rounds, xtr_rounds, pk_bytes;
     int xt_upc;              // units of the load size a parked channel has room for (64, 128 or 256)
     uint32_t in_bytes, w_bytes;   // sizes of the input tensor and of the packed filter
+    int nptiles, nktiles, pt_per_xcd;   // pixel tiles, channel tiles, pixel tiles per XCD (the grid is 8 * pt_per_xcd * nktiles)
 };
 
 struct Plan {
@@ -193,9 +194,15 @@ conv_tile_kernel(const bf16_t *__restrict__ in, const bf16_t *__restrict__ w, vo
     const int wk = (KT == 128) ? (wave >> 1) : 0;
     const int wp = (KT == 128) ? (wave & 1) : wave;
 
+    // ---- which tile.  Workgroup L runs on XCD L % 8 (round-robin dispatch), and every XCD has an
+    // L2 of its own: each XCD gets a contiguous range of pixel tiles, and the channel tiles of
+    // one pixel tile, which read the same patch, follow each other on the same XCD.
+    const int xcd_j = blockIdx.x >> 3;
+    const int ktile = xcd_j % p.nktiles, ptile = (blockIdx.x & 7) * p.pt_per_xcd + xcd_j / p.nktiles;
+    if (ptile >= p.nptiles) return;   // uniform for the workgroup, before any barrier
     // ---- tile geometry
-    const int rowtile = blockIdx.x / p.ncoltiles, coltile = blockIdx.x - rowtile * p.ncoltiles;
-    const int k0 = blockIdx.y * KT;
+    const int rowtile = ptile / p.ncoltiles, coltile = ptile - rowtile * p.ncoltiles;
+    const int k0 = ktile * KT;
     const int q0 = coltile * p.TW;
     const int LWp = WIDE ? WIDE_LWP : p.LWp;
     const int HWin = p.Hin * p.Win;

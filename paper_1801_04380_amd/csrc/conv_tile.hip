@@ -91,7 +91,14 @@ bool plan_for(const TileProblem &base, int R, int S, int NF, Plan *pl)
     pl->NF = NF;
     pl->wide = wide;
     pl->lds = lds;
-    pl->grid = dim3((unsigned)(nrowtiles * p.ncoltiles), (p.Kout + KT - 1) / KT, 1);
+    // one-dimensional grid, mapped to (pixel tile, channel tile) inside the kernel (see there)
+    p.nptiles = (int)(nrowtiles * p.ncoltiles);
+    p.nktiles = (p.Kout + KT - 1) / KT;
+    p.pt_per_xcd = (p.nptiles + 7) / 8;
+    const long long nwg = 8LL * p.pt_per_xcd * p.nktiles;
+    if (nwg > 0x7fffffffLL) return false;
+    pl->p = p;
+    pl->grid = dim3((unsigned)nwg, 1, 1);
     return true;
 }
 
@@ -104,7 +111,7 @@ bool make_plan(const TileProblem &base, int R, int S, bool staged, Plan *pl)
     const bool multi = (R == 3 && S == 3) || (R == 1 && S == 1);
     if (!multi) return true;
     // fewer workgroups than compute units: halve the pixels per workgroup
-    if ((long long)pl->grid.x * pl->grid.y < 256) {
+    if ((long long)pl->p.nptiles * pl->p.nktiles < 256) {
         Plan alt;
         if (plan_for(base, R, S, 2, &alt)) *pl = alt;
     }

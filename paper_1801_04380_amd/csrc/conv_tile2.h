@@ -66,9 +66,15 @@ __device__ __forceinline__ void conv_tile2_body(const bf16_t *__restrict__ in, c
     const int wk = wave >> 1, wp = wave & 1;
     const int XS = p.xslots * 2 + V2_TRASH;
 
+    // ---- which tile.  Workgroup L runs on XCD L % 8 (round-robin dispatch), and every XCD has an
+    // L2 of its own: each XCD gets a contiguous range of pixel tiles, and the channel tiles of
+    // one pixel tile, which read the same patch, follow each other on the same XCD.
+    const int xcd = blockIdx.x & 7, jx = blockIdx.x >> 3;
+    const int ktile = jx % p.nktiles, ptile = xcd * p.pt_per_xcd + jx / p.nktiles;
+    if (ptile >= p.nptiles) return;   // uniform for the workgroup, before any barrier
     // ---- tile geometry (as in conv_tile.h)
-    const int rowtile = blockIdx.x / p.ncoltiles, coltile = blockIdx.x - rowtile * p.ncoltiles;
-    const int k0 = blockIdx.y * KT;
+    const int rowtile = ptile / p.ncoltiles, coltile = ptile - rowtile * p.ncoltiles;
+    const int k0 = ktile * KT;
     const int q0 = coltile * p.TW;
     const int LWp = WIDE ? WIDE_LWP : p.LWp;
     const int HWin = p.Hin * p.Win;

@@ -55,7 +55,8 @@ struct RowsProblem {
     int N, C, H, W, K, P, Q, R, ph;
     int rowchunks, ncoltiles;   // chunks per image
     int nchunks, cps;           // total chunks, chunks per slice
-    int ctiles;
+    int ctiles, ktiles;
+    int xcd_slices;             // > 0: one-dimensional grid, this many slices per XCD
 };
 
 struct __attribute__((packed, aligned(2))) U128u { u32x4 v; };
@@ -116,8 +117,20 @@ wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, g = lane >> 5;
     const int wk = wave >> 1, wc = wave & 1;
-    const int ctile = blockIdx.x;
-    const int c0 = ctile * CTB, k0 = blockIdx.y * KTB;
+    // Which tile and slice.  With a one-dimensional grid (p.xcd_slices > 0) workgroup L runs on XCD
+    // L % 8 (round-robin dispatch), and every XCD has an L2 of its own: each XCD gets a contiguous
+    // range of slices, and the tiles of one slice, which read the same x and dy rows, follow each
+    // other on the same XCD.
+    int ctile, ktile, zslice;
+    if (p.xcd_slices > 0) {
+        const int tiles = p.ctiles * p.ktiles, jx = blockIdx.x >> 3, t = jx % tiles;
+        zslice = (blockIdx.x & 7) * p.xcd_slices + jx / tiles;
+        ctile = t % p.ctiles;
+        ktile = t / p.ctiles;
+    } else {
+        ctile = blockIdx.x; ktile = blockIdx.y; zslice = blockIdx.z;
+    }
+    const int c0 = ctile * CTB, k0 = ktile * KTB;
     const int PQ = p.P * p.Q, HW = p.H * p.W;
     const int ytotal = p.N * p.K * PQ, xtotal = p.N * p.C * HW;
     const bf16_t *const zp = reinterpret_cast<const bf16_t *>(zero_page);
@@ -331,7 +344,7 @@ wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
         for (int i = NITEMS - LAG; i < NITEMS; ++i) item_store(i, buf ^ 1);
     };
 
-    const int cbeg = blockIdx.z * p.cps, cend = min(p.nchunks, cbeg + p.cps);
+    const int cbeg = zslice * p.cps, cend = min(p.nchunks, cbeg + p.cps);
     __syncthreads();   // the zero fill is complete
     if (cbeg < cend) {
         set_chunk(cbeg);
@@ -356,7 +369,7 @@ wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
     // consecutive addresses of dw[k][c][r][s].
     constexpr int ROWS = KTB / 4, ROWLEN = CTB * T, EP = ROWLEN + 1;
     float *stage = reinterpret_cast<float *>(smem);
-    float *dst = out + (use_atomics ? (size_t)0 : (size_t)blockIdx.z * p.K * p.C * T);
+    float *dst = out + (use_atomics ? (size_t)0 : (size_t)zslice * p.K * p.C * T);
 #pragma unroll
     for (int ps = 0; ps < 4; ++ps) {
 #pragma unroll
@@ -402,6 +415,7 @@ wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
 struct RPlan {
     RowsProblem p;
     dim3 grid;
+    int nslices;
     int S, TM, TH, TWP;
     bool wide;
 };
@@ -452,8 +466,15 @@ bool make_rplan(const ConvGeom &g, RPlan *pl)
     if (slices < 1) slices = 1;
     p.cps = (int)((p.nchunks + slices - 1) / slices);
     slices = (p.nchunks + p.cps - 1) / p.cps;
-    pl->p = p;
+    p.ktiles = ktiles;
+    p.xcd_slices = 0;
+    pl->nslices = (int)slices;
     pl->grid = dim3(p.ctiles, ktiles, (unsigned)slices);
+    if (slices % 8 == 0 && tiles * slices <= 0x7fffffffLL) {
+        p.xcd_slices = (int)(slices / 8);
+        pl->grid = dim3((unsigned)(tiles * slices), 1, 1);
+    }
+    pl->p = p;
     pl->S = g.S; pl->TM = TM; pl->TH = TH; pl->TWP = TWP; pl->wide = wide;
     return true;
 }
@@ -492,7 +513,7 @@ bool rows_wgrad_supported(const ConvGeom &g)
 int rows_wgrad_slices(const ConvGeom &g)
 {
     RPlan pl;
-    return make_rplan(g, &pl) ? (int)pl.grid.z : 0;
+    return make_rplan(g, &pl) ? pl.nslices : 0;
 }
 
 // partial == nullptr: slices add into dw with atomics (dw is zero-filled first);
@@ -503,7 +524,7 @@ hipError_t launch_rows_wgrad(const void *x, const void *dy, float *dw, const Con
     RPlan pl;
     if (!make_rplan(g, &pl)) return hipErrorInvalidValue;
     const size_t nw = (size_t)g.K * g.C * g.R * g.S;
-    const int slices = (int)pl.grid.z;
+    const int slices = pl.nslices;
     const bool direct_store = !partial && slices == 1;
     float *out = partial ? partial : dw;
     if (!partial && !direct_store) {
