@@ -7,26 +7,34 @@ namespace {
 
 // Packs A(m, red, tap) into [chunk = red/16][stage][tap of the stage][Mpad][16],
 // zero padded, the two 8-channel halves of a row swapped where the LDS swizzle
-// swaps them: a stage's slab is copied to LDS as it is.
+// swaps them: a stage's slab is copied to LDS (or read by the MFMA lanes) as it is.
+// One thread per 16-byte item (8 channels of one row and tap).
 __global__ void __launch_bounds__(256)
-pack_filter_kernel(const bf16_t *__restrict__ w, bf16_t *__restrict__ wp, int M, int RED, int R, int S, int SG,
-                   int w_sm, int w_sr, int tflip, int Mpad, size_t total)
+pack_filter_kernel(const bf16_t *__restrict__ w, uint4 *__restrict__ wp, int M, int RED, int R, int S, int SG,
+                   int w_sm, int w_sr, int tflip, int Mpad, size_t items)
 {
-    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (e >= total) return;
-    const int j = (int)(e & 7), hs = (int)((e >> 3) & 1);
-    size_t q = e >> 4;
-    const int m = (int)(q % Mpad);
-    q /= Mpad;
-    const int TRES = R * SG, NSUB = S / SG;
-    const int tl = (int)(q % TRES);
-    q /= TRES;
-    const int sg = (int)(q % NSUB), chunk = (int)(q / NSUB);
-    const int r = tl / SG, s = sg * SG + tl % SG, tap = r * S + s, T = R * S;
-    const int red = chunk * 16 + (hs ^ swz(m)) * 8 + j;
-    bf16_t v = 0;
-    if (m < M && red < RED) v = w[(size_t)m * w_sm + (size_t)red * w_sr + (tflip ? T - 1 - tap : tap)];
-    wp[e] = v;
+    // Threads are numbered so that neighbours read neighbouring source elements: the tap runs
+    // fastest, then (forward) the half and the row, or (backward-data) the row and the half.
+    size_t q = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (q >= items) return;
+    const int T = R * S, TRES = R * SG, NSUB = S / SG;
+    const int tap = (int)(q % T);
+    q /= T;
+    int hs, m;
+    if (tflip) { m = (int)(q % Mpad); q /= Mpad; hs = (int)(q & 1); q >>= 1; }
+    else { hs = (int)(q & 1); q >>= 1; m = (int)(q % Mpad); q /= Mpad; }
+    const int chunk = (int)q;
+    const int r = tap / S, s = tap - r * S, sg = s / SG, tl = r * SG + (s - sg * SG);
+    const size_t it = ((((size_t)chunk * NSUB + sg) * TRES + tl) * Mpad + m) * 2 + hs;
+    const int red0 = chunk * 16 + (hs ^ swz(m)) * 8;
+    uint32_t d[4] = {0, 0, 0, 0};
+    if (m < M) {
+        const bf16_t *src = w + (size_t)m * w_sm + (size_t)red0 * w_sr + (tflip ? T - 1 - tap : tap);
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            if (red0 + j < RED) d[j >> 1] |= (uint32_t)src[(size_t)j * w_sr] << (16 * (j & 1));
+    }
+    wp[it] = make_uint4(d[0], d[1], d[2], d[3]);
 }
 
 // Tiling for one problem with NF 32-pixel tiles per wave; false if the patch would not fit in LDS.
@@ -215,10 +223,10 @@ hipError_t launch_tile_conv(const void *in, const void *w, void *out, const Conv
         return hipErrorInvalidValue;
     const bf16_t *wsrc = static_cast<const bf16_t *>(w);
     if (packed) {
-        const size_t total = (size_t)pl.p.nchunks * g.R * g.S * pl.p.Mpad * 16;
-        hipLaunchKernelGGL(pack_filter_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, wsrc,
-                           static_cast<bf16_t *>(packed), pl.p.Kout, pl.p.Cin, g.R, g.S, sg_of(g.R, g.S),
-                           pl.p.w_sm, pl.p.w_sr, pl.p.tflip, pl.p.Mpad, total);
+        const size_t items = (size_t)pl.p.nchunks * g.R * g.S * pl.p.Mpad * 2;
+        hipLaunchKernelGGL(pack_filter_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, st, wsrc,
+                           static_cast<uint4 *>(packed), pl.p.Kout, pl.p.Cin, g.R, g.S, sg_of(g.R, g.S),
+                           pl.p.w_sm, pl.p.w_sr, pl.p.tflip, pl.p.Mpad, items);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         wsrc = static_cast<const bf16_t *>(packed);
