@@ -5,7 +5,8 @@ One step = one pass of the whole hot path over one batch of a synthetic,
 network-shaped workload (default: the VGG-16-shaped configuration, N = 32, bf16
 in / fp32 accumulate): for every conv layer, CONV forward, BN forward, ReLU
 forward and max-pool forward (the layers recomputation replays; BN and the ReLU
-after it are one call, sn_bn_relu_fwd, unless --no-fuse), then their backward
+after it are one call, sn_bn_relu_fwd, and so are their backward passes,
+sn_bn_relu_bwd, unless --no-fuse), then their backward
 passes, CONV backward-data and CONV backward-filter, each CONV planned under the
 given workspace budget.  Inputs are resident in HBM before the timed
 region; autotuning happens before it too.
@@ -49,7 +50,7 @@ def parse():
     ap.add_argument("--budget-mib", type=float, default=None, help="workspace budget; default: the largest listed")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-autotune", action="store_true")
-    ap.add_argument("--no-fuse", action="store_true", help="BN forward and ReLU forward as two calls instead of one")
+    ap.add_argument("--no-fuse", action="store_true", help="BN and ReLU as separate calls, forward and backward")
     ap.add_argument("--detail", default=None, help="write the per-layer table to this JSON file")
     return ap.parse_args()
 
@@ -151,13 +152,19 @@ def build_ops(cfg_no, budget, autotune, fuse):
                               nbytes=Eo * (b + 4) + E * b))
         else:
             g_a.copy_(dy)
-        relu_grad_out = g_bn if cfg["bn"] else dy
-        cheap_b.append(Op("relu_bwd", layer.name, lambda s=a, g=g_a, o=relu_grad_out: sn.sn_relu_bwd(s, g, o),
-                          nbytes=3 * E * b))
-        if cfg["bn"]:
-            cheap_b.append(Op("bn_bwd", layer.name,
-                              lambda y=y, g=g_bn, ga=gamma, m=mean, i=invstd, o=dy, dg=dgamma, db=dbeta:
-                              sn.sn_bn_bwd(y, g, ga, m, i, o, dg, db), nbytes=3 * E * b))
+        if cfg["bn"] and fuse:
+            # ReLU backward and BN backward in one call: reads x, the gate and the gradient, writes dx
+            cheap_b.append(Op("bn_relu_bwd", layer.name,
+                              lambda y=y, s=a, g=g_a, ga=gamma, m=mean, i=invstd, o=dy, dg=dgamma, db=dbeta:
+                              sn.sn_bn_relu_bwd(y, s, g, ga, m, i, o, dg, db), nbytes=4 * E * b))
+        else:
+            relu_grad_out = g_bn if cfg["bn"] else dy
+            cheap_b.append(Op("relu_bwd", layer.name, lambda s=a, g=g_a, o=relu_grad_out: sn.sn_relu_bwd(s, g, o),
+                              nbytes=3 * E * b))
+            if cfg["bn"]:
+                cheap_b.append(Op("bn_bwd", layer.name,
+                                  lambda y=y, g=g_bn, ga=gamma, m=mean, i=invstd, o=dy, dg=dgamma, db=dbeta:
+                                  sn.sn_bn_bwd(y, g, ga, m, i, o, dg, db), nbytes=3 * E * b))
         for _ in range(layer.mult):
             fwd_ops.extend(cheap_f)
         layer_bwd = []

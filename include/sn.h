@@ -178,6 +178,15 @@ sn_status sn_bn_bwd(const void *x, const void *dy, const float *gamma,
                     void *dx, float *dgamma, float *dbeta,
                     int N, int C, int H, int W, sn_dtype dtype, sn_stream stream);
 
+/* Backward of the BN + ReLU pair (sn_bn_relu_fwd) in one call: sn_bn_bwd applied to
+ *   g = y > 0 ? dy : 0,
+ * where y is the pair's output (the ReLU gate of sn_relu_bwd) and dy the gradient that
+ * reaches it; g is never stored.  x is the BN input.  dx must alias none of x, y, dy. */
+sn_status sn_bn_relu_bwd(const void *x, const void *y, const void *dy, const float *gamma,
+                         const float *save_mean, const float *save_invstd,
+                         void *dx, float *dgamma, float *dbeta,
+                         int N, int C, int H, int W, sn_dtype dtype, sn_stream stream);
+
 /* POOL (max) forward, the paper's example of a cheap-to-recompute layer
  * (Sec. 3.4).  Window kh x kw, stride, padding (pad < window; padded positions
  * never win).  Of equal maxima the first in row-major window order wins.

@@ -15,7 +15,7 @@ __all__ = [
     "SnError", "conv_shape", "sn_out_dim", "sn_conv_workspace_query", "sn_conv_plan",
     "sn_planner_record", "sn_planner_clear", "sn_conv_autotune",
     "sn_conv2d_fwd", "sn_conv2d_bwd_data", "sn_conv2d_bwd_filter",
-    "sn_relu_fwd", "sn_relu_bwd", "sn_bn_fwd", "sn_bn_relu_fwd", "sn_bn_bwd", "sn_maxpool_fwd", "sn_maxpool_bwd",
+    "sn_relu_fwd", "sn_relu_bwd", "sn_bn_fwd", "sn_bn_relu_fwd", "sn_bn_bwd", "sn_bn_relu_bwd", "sn_maxpool_fwd", "sn_maxpool_bwd",
 ]
 
 SN_F32, SN_BF16 = 0, 1
@@ -146,6 +146,13 @@ def sn_bn_bwd(x, dy, gamma, save_mean, save_invstd, dx, dgamma, dbeta):
     _check("sn_bn_bwd", load().sn_bn_bwd(_ptr(x), _ptr(dy), _ptr(gamma), _ptr(save_mean), _ptr(save_invstd),
                                          _ptr(dx), _ptr(dgamma), _ptr(dbeta), N, C, H, W, _dtype_code(x),
                                          _stream()))
+
+
+def sn_bn_relu_bwd(x, y, dy, gamma, save_mean, save_invstd, dx, dgamma, dbeta):
+    N, C, H, W = x.shape
+    _check("sn_bn_relu_bwd", load().sn_bn_relu_bwd(_ptr(x), _ptr(y), _ptr(dy), _ptr(gamma), _ptr(save_mean),
+                                                   _ptr(save_invstd), _ptr(dx), _ptr(dgamma), _ptr(dbeta), N, C, H,
+                                                   W, _dtype_code(x), _stream()))
 
 
 def sn_maxpool_fwd(x, y, idx, kernel, stride, pad=(0, 0)):

@@ -286,8 +286,8 @@ bn_apply_kernel(const T *__restrict__ x, T *__restrict__ y, const float *__restr
 // Backward pass 1: per (channel, slice) partial sums of dy and dy*(x - mean).
 template <typename T>
 __global__ void __launch_bounds__(256)
-bn_bwd_reduce_kernel(const T *__restrict__ x, const T *__restrict__ dy, const float *__restrict__ mean,
-                     float *__restrict__ part, int N, int C, int HW, Slices sl)
+bn_bwd_reduce_kernel(const T *__restrict__ x, const T *__restrict__ dy, const T *__restrict__ gate,
+                     const float *__restrict__ mean, float *__restrict__ part, int N, int C, int HW, Slices sl)
 {
     constexpr int V = Vec<T>::N;
     const int c = blockIdx.x, slice = blockIdx.y;
@@ -298,13 +298,19 @@ bn_bwd_reduce_kernel(const T *__restrict__ x, const T *__restrict__ dy, const fl
         const int n = seg / sl.nseg_plane, k = seg - n * sl.nseg_plane;
         const int e0 = k * SEG, len = min(SEG, HW - e0);
         const size_t base = ((size_t)n * C + c) * HW + e0;
-        const T *p = x + base, *gp = dy + base;
+        const T *p = x + base, *gp = dy + base, *ap = gate ? gate + base : nullptr;
         walk_segment<T>(
             p, len, lane,
             [&](int off) {
                 float f[V], gr[V];
                 Vec<T>::load(p + off, f);
                 Vec<T>::load(gp + off, gr);
+                if (ap) {
+                    float a[V];
+                    Vec<T>::load(ap + off, a);
+#pragma unroll
+                    for (int i = 0; i < V; ++i) gr[i] = a[i] > 0.f ? gr[i] : 0.f;
+                }
 #pragma unroll
                 for (int i = 0; i < V; ++i) {
                     s1 += gr[i];
@@ -313,6 +319,7 @@ bn_bwd_reduce_kernel(const T *__restrict__ x, const T *__restrict__ dy, const fl
             },
             [&](int off) {
                 float gr = ld<T>(gp + off);
+                if (ap && !(ld<T>(ap + off) > 0.f)) gr = 0.f;
                 s1 += gr;
                 s2 += gr * (ld<T>(p + off) - mu);
             });
@@ -353,8 +360,8 @@ bn_bwd_final_kernel(const float *__restrict__ part, const float *__restrict__ in
 // Backward pass 3: dx = gamma*invstd * (dy - dbeta/M - xhat*dgamma/M).
 template <typename T>
 __global__ void __launch_bounds__(256)
-bn_bwd_apply_kernel(const T *__restrict__ x, const T *__restrict__ dy, T *__restrict__ dx,
-                    const float *__restrict__ gamma, const float *__restrict__ mean,
+bn_bwd_apply_kernel(const T *__restrict__ x, const T *__restrict__ dy, const T *__restrict__ gate,
+                    T *__restrict__ dx, const float *__restrict__ gamma, const float *__restrict__ mean,
                     const float *__restrict__ invstd, const float *__restrict__ dgamma,
                     const float *__restrict__ dbeta, int N, int C, int HW, Slices sl)
 {
@@ -370,7 +377,7 @@ bn_bwd_apply_kernel(const T *__restrict__ x, const T *__restrict__ dy, T *__rest
         const int n = seg / sl.nseg_plane, k = seg - n * sl.nseg_plane;
         const int e0 = k * SEG, len = min(SEG, HW - e0);
         const size_t base = ((size_t)n * C + c) * HW + e0;
-        const T *p = x + base, *gp = dy + base;
+        const T *p = x + base, *gp = dy + base, *ap = gate ? gate + base : nullptr;
         T *o = dx + base;
         walk_segment<T>(
             p, len, lane,
@@ -378,11 +385,21 @@ bn_bwd_apply_kernel(const T *__restrict__ x, const T *__restrict__ dy, T *__rest
                 float f[V], gr[V];
                 Vec<T>::load(p + off, f);
                 Vec<T>::load(gp + off, gr);
+                if (ap) {
+                    float a[V];
+                    Vec<T>::load(ap + off, a);
+#pragma unroll
+                    for (int i = 0; i < V; ++i) gr[i] = a[i] > 0.f ? gr[i] : 0.f;
+                }
 #pragma unroll
                 for (int i = 0; i < V; ++i) f[i] = k1 * (gr[i] - kb - (f[i] - mu) * kg);
                 Vec<T>::store(o + off, f);
             },
-            [&](int off) { st(o + off, k1 * (ld<T>(gp + off) - kb - (ld<T>(p + off) - mu) * kg)); });
+            [&](int off) {
+                float gr = ld<T>(gp + off);
+                if (ap && !(ld<T>(ap + off) > 0.f)) gr = 0.f;
+                st(o + off, k1 * (gr - kb - (ld<T>(p + off) - mu) * kg));
+            });
     }
 }
 
@@ -496,8 +513,8 @@ bn_fwd_fused_kernel(const T *__restrict__ x, T *__restrict__ y, const float *__r
 
 template <typename T, int VB, int NVMAX>
 __global__ void __launch_bounds__(1024)
-bn_bwd_fused_kernel(const T *__restrict__ x, const T *__restrict__ dy, T *__restrict__ dx,
-                    const float *__restrict__ gamma, const float *__restrict__ mean,
+bn_bwd_fused_kernel(const T *__restrict__ x, const T *__restrict__ dy, const T *__restrict__ gate,
+                    T *__restrict__ dx, const float *__restrict__ gamma, const float *__restrict__ mean,
                     const float *__restrict__ invstd, float *__restrict__ dgamma, float *__restrict__ dbeta,
                     int N, int C, int HW)
 {
@@ -520,6 +537,14 @@ bn_bwd_fused_kernel(const T *__restrict__ x, const T *__restrict__ dy, T *__rest
             float f[VE], gr[VE];
             unpack<T, VB>(xv[j], f);
             unpack<T, VB>(gv[j], gr);
+            if (gate) {   // the gradient that passes the ReLU is what is kept in registers
+                const VT av = *reinterpret_cast<const VT *>(gate + off);
+                float a[VE];
+                unpack<T, VB>(av, a);
+#pragma unroll
+                for (int k = 0; k < VE; ++k) gr[k] = a[k] > 0.f ? gr[k] : 0.f;
+                gv[j] = pack<T, VB>(gr);
+            }
 #pragma unroll
             for (int k = 0; k < VE; ++k) {
                 s1 += gr[k];
@@ -595,7 +620,8 @@ __global__ void bn_fwd_tiny_kernel(const T *__restrict__ x, T *__restrict__ y, c
 }
 
 template <typename T>
-__global__ void bn_bwd_tiny_kernel(const T *__restrict__ x, const T *__restrict__ dy, T *__restrict__ dx,
+__global__ void bn_bwd_tiny_kernel(const T *__restrict__ x, const T *__restrict__ dy, const T *__restrict__ gate,
+                                   T *__restrict__ dx,
                                    const float *__restrict__ gamma, const float *__restrict__ mean,
                                    const float *__restrict__ invstd, float *__restrict__ dgamma,
                                    float *__restrict__ dbeta, int N, int C, int HW)
@@ -608,7 +634,7 @@ __global__ void bn_bwd_tiny_kernel(const T *__restrict__ x, const T *__restrict_
     for (int n = 0; n < N; ++n)
         for (int i = 0; i < HW; ++i) {
             const size_t j = ((size_t)n * C + c) * HW + i;
-            const float gr = ld<T>(dy + j);
+            const float gr = (gate && !(ld<T>(gate + j) > 0.f)) ? 0.f : ld<T>(dy + j);
             db += gr;
             dg += gr * (ld<T>(x + j) - mu);
         }
@@ -619,7 +645,8 @@ __global__ void bn_bwd_tiny_kernel(const T *__restrict__ x, const T *__restrict_
     for (int n = 0; n < N; ++n)
         for (int i = 0; i < HW; ++i) {
             const size_t j = ((size_t)n * C + c) * HW + i;
-            st(dx + j, k1 * (ld<T>(dy + j) - kb - (ld<T>(x + j) - mu) * kg));
+            const float gr = (gate && !(ld<T>(gate + j) > 0.f)) ? 0.f : ld<T>(dy + j);
+            st(dx + j, k1 * (gr - kb - (ld<T>(x + j) - mu) * kg));
         }
 }
 
@@ -879,7 +906,7 @@ hipError_t launch_bn_fwd(const void *x, const float *gamma, const float *beta, v
     });
 }
 
-hipError_t launch_bn_bwd(const void *x, const void *dy, const float *gamma, const float *mean,
+hipError_t launch_bn_bwd(const void *x, const void *dy, const void *gate, const float *gamma, const float *mean,
                          const float *invstd, void *dx, float *dgamma, float *dbeta, int N, int C, int HW,
                          int bf16, hipStream_t s)
 {
@@ -888,19 +915,20 @@ hipError_t launch_bn_bwd(const void *x, const void *dy, const float *gamma, cons
         return by_dtype(bf16, [&](auto *tag) {
             typedef typename std::remove_pointer<decltype(tag)>::type T;
             hipLaunchKernelGGL(bn_bwd_tiny_kernel<T>, dim3((C + 63) / 64), dim3(64), 0, s, (const T *)x,
-                               (const T *)dy, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);
+                               (const T *)dy, (const T *)gate, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);
         });
     {
-        const int vb = bf16 ? bn_fused_vb<bf16_t>(x, dy, dx, N, HW) : bn_fused_vb<float>(x, dy, dx, N, HW);
+        int vb = bf16 ? bn_fused_vb<bf16_t>(x, dy, dx, N, HW) : bn_fused_vb<float>(x, dy, dx, N, HW);
+        if (vb && gate && reinterpret_cast<uintptr_t>(gate) % vb != 0) vb = 0;
         if (vb)
             return by_dtype(bf16, [&](auto *tag) {
                 typedef typename std::remove_pointer<decltype(tag)>::type T;
                 if (vb == 16)
                     hipLaunchKernelGGL((bn_bwd_fused_kernel<T, 16, BN_FUSED_NV>), dim3(C), dim3(1024), 0, s, (const T *)x,
-                                       (const T *)dy, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);
+                                       (const T *)dy, (const T *)gate, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);
                 else
                     hipLaunchKernelGGL((bn_bwd_fused_kernel<T, 8, BN_FUSED_NV>), dim3(C), dim3(1024), 0, s, (const T *)x,
-                                       (const T *)dy, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);
+                                       (const T *)dy, (const T *)gate, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);
             });
     }
     const Slices sl = make_slices(N, C, HW, (size_t)N * C * HW * esz);
@@ -908,12 +936,12 @@ hipError_t launch_bn_bwd(const void *x, const void *dy, const float *gamma, cons
     return by_dtype(bf16, [&](auto *tag) {
         typedef typename std::remove_pointer<decltype(tag)>::type T;
         dim3 grid(C, sl.nslice), block(256);
-        hipLaunchKernelGGL(bn_bwd_reduce_kernel<T>, grid, block, 0, s, (const T *)x, (const T *)dy, mean, part,
-                           N, C, HW, sl);
+        hipLaunchKernelGGL(bn_bwd_reduce_kernel<T>, grid, block, 0, s, (const T *)x, (const T *)dy, (const T *)gate,
+                           mean, part, N, C, HW, sl);
         hipLaunchKernelGGL(bn_bwd_final_kernel, dim3(C), dim3(64), 0, s, part, invstd, dgamma, dbeta,
                            sl.nslice);
-        hipLaunchKernelGGL(bn_bwd_apply_kernel<T>, grid, block, 0, s, (const T *)x, (const T *)dy, (T *)dx,
-                           gamma, mean, invstd, dgamma, dbeta, N, C, HW, sl);
+        hipLaunchKernelGGL(bn_bwd_apply_kernel<T>, grid, block, 0, s, (const T *)x, (const T *)dy, (const T *)gate,
+                           (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW, sl);
     });
 }
 

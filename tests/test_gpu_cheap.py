@@ -96,6 +96,23 @@ def test_bn(shape, dtype):
     assert rel_l2(f64(mean), mo) <= 1e-5
     assert rel_l2(f64(invstd), io) <= 1e-5
     assert rel_l2(f64(y), yo) <= tol
+    # ReLU backward + BN backward in one call: exactly the two calls in a row
+    g = torch.empty_like(dyd)
+    sn.sn_relu_bwd(a, dyd, g)
+    dx_ref = torch.full_like(xd, float("nan"))
+    dg_ref, db_ref = torch.empty(C, device="cuda"), torch.empty(C, device="cuda")
+    sn.sn_bn_bwd(xd, g, gd, mean, invstd, dx_ref, dg_ref, db_ref)
+    dx_f = torch.full_like(xd, float("nan"))
+    dg_f, db_f = torch.empty(C, device="cuda"), torch.empty(C, device="cuda")
+    sn.sn_bn_relu_bwd(xd, a, dyd, gd, mean, invstd, dx_f, dg_f, db_f)
+    torch.cuda.synchronize()
+    assert torch.equal(dx_f, dx_ref) and torch.equal(dg_f, dg_ref) and torch.equal(db_f, db_ref)
+    go = oracle.relu_bwd(f64(a), f64(dy))
+    dxo2, dgo2, dbo2 = oracle.bn_bwd(f64(x), go, f64(gamma), f64(mean), f64(invstd))
+    assert rel_l2(f64(dg_f), dgo2) <= 1e-5 and rel_l2(f64(db_f), dbo2) <= 1e-5
+    if N * H * W > 4:
+        assert rel_l2(f64(dx_f), dxo2) <= tol
+
     # backward from the statistics the GPU saved (what the API consumes)
     dxo, dgo, dbo = oracle.bn_bwd(f64(x), f64(dy), f64(gamma), f64(mean), f64(invstd))
     assert rel_l2(f64(dgamma), dgo) <= 1e-5
