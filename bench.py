@@ -78,6 +78,7 @@ def build_ops(cfg_no, budget, autotune, fuse):
     b = 2 if dtype == "bf16" else 4
     dev = "cuda"
     ws = torch.empty(max(budget, 256), dtype=torch.uint8, device=dev) if budget else None
+    wsbox = [ws]   # the workspace the conv calls are handed; main() swaps in smaller budgets
     fwd_ops, bwd_ops, plans = [], [], {}
     tune_ms = 0.0
     for li, layer in enumerate(cfg["layers"]):
@@ -96,7 +97,7 @@ def build_ops(cfg_no, budget, autotune, fuse):
 
         def conv_call(direction, a, bb, out, shape=shape):
             fn = {0: sn.sn_conv2d_fwd, 1: sn.sn_conv2d_bwd_data, 2: sn.sn_conv2d_bwd_filter}[direction]
-            return lambda: fn(a, bb, out, shape, sn.SN_ALGO_AUTO, ws)
+            return lambda: fn(a, bb, out, shape, sn.SN_ALGO_AUTO, wsbox[0])
 
         # the gradient that reaches the conv comes from the cheap layers' backward below;
         # fill it once so the autotune runs on real values
@@ -174,7 +175,7 @@ def build_ops(cfg_no, budget, autotune, fuse):
                 layer_bwd.append(Op(names[1], layer.name, conv_call(1, dy, wd, dx), algo_flops, byts[1], nominal))
             layer_bwd.append(Op(names[2], layer.name, conv_call(2, xd, dy, dw), algo_flops, byts[2], nominal))
         bwd_ops = layer_bwd + bwd_ops  # backward visits the layers in reverse
-    return cfg, fwd_ops + bwd_ops, plans, tune_ms
+    return cfg, fwd_ops + bwd_ops, plans, tune_ms, wsbox
 
 
 def cpu_baseline(cfg_no):
@@ -222,7 +223,7 @@ def main():
         budget = int(args.budget_mib * (1 << 20))
     else:
         budget = max(budgets) if budgets else 64 << 20
-    cfg, ops, plans, tune_ms = build_ops(args.workload, budget, not args.no_autotune, not args.no_fuse)
+    cfg, ops, plans, tune_ms, wsbox = build_ops(args.workload, budget, not args.no_autotune, not args.no_fuse)
     stream = torch.cuda.current_stream()
 
     def step(timed_keys):
@@ -277,6 +278,32 @@ def main():
     wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
     d = collect()[dom]
 
+    # the other budgets of the workload (Sec. 3.5: less free memory, slower algorithms): the conv calls
+    # alone, handed a smaller slice of the same workspace; the planner falls back by itself
+    per_budget = {}
+    full_ws = wsbox[0]
+    for bb in sorted(set(cfg["budgets"]) | {budget}):
+        if bb > budget:
+            continue
+        wsbox[0] = None if bb == 0 else full_ws[:bb]
+        conv_ops = [op for op in ops if op.key.startswith("conv_")]
+        for op in conv_ops:
+            op.fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record(stream)
+        for _ in range(3):
+            for op in conv_ops:
+                op.fn()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 3
+        fl = sum(op.flops for op in conv_ops)
+        peak = PEAK["bf16_mfma_tflops"] if cfg["dtype"] == "bf16" else PEAK["f32_mfma_tflops"]
+        per_budget[str(bb)] = {"conv_ms_per_step": ms, "conv_tflops": fl / (ms * 1e-3) / 1e12,
+                               "frac_mfma_peak": fl / (ms * 1e-3) / 1e12 / peak}
+    wsbox[0] = full_ws
+
     conv_keys = [k for k in by_key if k.startswith("conv_")]
     conv_flops_step = sum(by_key[k]["flops"] for k in conv_keys) / BREAKDOWN_STEPS
     conv_ms_step = sum(by_key[k]["ms"] for k in conv_keys) / BREAKDOWN_STEPS
@@ -326,7 +353,7 @@ def main():
         / (PEAK["bf16_mfma_tflops"] if cfg["dtype"] == "bf16" else PEAK["f32_mfma_tflops"]),
         "recompute_gbs": replay_gbs,
         "recompute_ms_per_step": sum(by_key[k]["ms"] for k in replay_keys) / BREAKDOWN_STEPS, "cheap_layers_gbs": cheap_bytes_step / (cheap_ms_step * 1e-3) / 1e9,
-        "autotune_ms": tune_ms,
+        "autotune_ms": tune_ms, "conv_per_budget": per_budget,
         "roofline": roof, "breakdown": breakdown,
     }
     if not args.no_cpu_baseline:
