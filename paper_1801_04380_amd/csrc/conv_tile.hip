@@ -38,7 +38,7 @@ pack_filter_kernel(const bf16_t *__restrict__ w, uint4 *__restrict__ wp, int M, 
 }
 
 // Tiling for one problem with NF 32-pixel tiles per wave; false if the patch would not fit in LDS.
-bool plan_for(const TileProblem &base, int R, int S, int NF, Plan *pl)
+bool plan_for(const TileProblem &base, int R, int S, int NF, Plan *pl, bool prefer_narrow = false)
 {
     TileProblem p = base;
     const int KT = p.Kout <= 64 ? 64 : 128;
@@ -54,7 +54,7 @@ bool plan_for(const TileProblem &base, int R, int S, int NF, Plan *pl)
         const double eff_narrow = (double)th * p.Qout / PIXT;
         const int ct = (p.Qout + 31) / 32;
         const double eff_wide = (double)p.Qout / (ct * 32);
-        wide = eff_wide >= eff_narrow && p.Pout >= PIXT / 32;
+        wide = (prefer_narrow ? eff_wide > eff_narrow : eff_wide >= eff_narrow) && p.Pout >= PIXT / 32;
     }
     if (!wide) {
         p.TW = p.Qout;
@@ -112,16 +112,16 @@ bool plan_for(const TileProblem &base, int R, int S, int NF, Plan *pl)
 
 // The tiling for one problem: the largest tile, unless (3x3 and 1x1 filters, which have the
 // kernels) that leaves compute units without work and a smaller one does not.
-bool make_plan(const TileProblem &base, int R, int S, bool staged, Plan *pl)
+bool make_plan(const TileProblem &base, int R, int S, bool staged, Plan *pl, bool prefer_narrow = false)
 {
     (void)staged;
-    if (!plan_for(base, R, S, 4, pl)) return false;
+    if (!plan_for(base, R, S, 4, pl, prefer_narrow)) return false;
     const bool multi = (R == 3 && S == 3) || (R == 1 && S == 1);
     if (!multi) return true;
     // fewer workgroups than compute units: halve the pixels per workgroup
     if ((long long)pl->p.nptiles * pl->p.nktiles < 256) {
         Plan alt;
-        if (plan_for(base, R, S, 2, &alt)) *pl = alt;
+        if (plan_for(base, R, S, 2, &alt, prefer_narrow)) *pl = alt;
     }
     return true;
 }
@@ -132,7 +132,9 @@ bool make_plan(const TileProblem &base, int R, int S, bool staged, Plan *pl)
 bool make_plan2(const TileProblem &base, int R, int S, Plan *pl)
 {
     if (!(R == 3 && S == 3) || base.Kout <= 64 || base.Win % 2 != 0) return false;
-    if (!make_plan(base, R, S, true, pl) || pl->KT != 128 || (pl->NF != 4 && pl->NF != 2)) return false;
+    // a width that rules out the WIDE tiling here (not a multiple of 8): whole rows where they fill the tile as well
+    if (!make_plan(base, R, S, true, pl, base.Win % 8 != 0) || pl->KT != 128 || (pl->NF != 4 && pl->NF != 2))
+        return false;
     TileProblem &p = pl->p;
     const int dw = p.Win % 8 == 0 ? 16 : 4;
     if (pl->wide && dw != 16) return false;
