@@ -35,7 +35,7 @@ PEAK = {"bf16_mfma_tflops": 2500.0, "f32_mfma_tflops": 157.3, "hbm_gbs": 8000.0}
 # HBM bytes per launch of an op class, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this
 # command (profiles/bench_vgg16_n32_hbm_traffic.txt gives the runs, the calibration and the sums).
 # Only for the workload and budget the counters were collected on; anything else reports null.
-MEASURED_TRAFFIC = {("cfg3_vgg16_n32", 2 << 30, "conv_bwd_filter"): 423e6}
+MEASURED_TRAFFIC = {("cfg3_vgg16_n32", 2 << 30, "conv_bwd_filter"): 272e6}
 KERNELS = {"conv_fwd": "conv_tile2_kernel / conv_tile_kernel (+ pack_filter_kernel)",
            "conv_bwd_data": "conv_tile2_kernel / conv_tile_kernel (+ pack_filter_kernel)",
            "conv_bwd_filter": "wgrad_rows_kernel + reduce_partials4_kernel (STAGED) or fill_zero_kernel (DIRECT)"}
@@ -50,6 +50,7 @@ def parse():
     ap.add_argument("--budget-mib", type=float, default=None, help="workspace budget; default: the largest listed")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-autotune", action="store_true")
+    ap.add_argument("--no-budget-sweep", action="store_true", help="skip the conv timing at the smaller budgets")
     ap.add_argument("--no-fuse", action="store_true", help="BN and ReLU as separate calls, forward and backward")
     ap.add_argument("--detail", default=None, help="write the per-layer table to this JSON file")
     return ap.parse_args()
@@ -283,7 +284,7 @@ def main():
     per_budget = {}
     full_ws = wsbox[0]
     for bb in sorted(set(cfg["budgets"]) | {budget}):
-        if bb > budget:
+        if bb > budget or args.no_budget_sweep:
             continue
         wsbox[0] = None if bb == 0 else full_ws[:bb]
         conv_ops = [op for op in ops if op.key.startswith("conv_")]
