@@ -188,7 +188,7 @@ def cpu_baseline(cfg_no):
     cfg = wl.CONFIGS[cfg_no]
     layer = max(cfg["layers"], key=lambda l: wl.conv_flops(l, 1)[0])
     per_img = wl.conv_flops(layer, 1)[0]
-    n = int(max(1, min(cfg["N"], round(200e9 / (3 * per_img)))))
+    n = int(max(1, min(cfg["N"], round(600e9 / (3 * per_img)))))   # about 10-20 s of the fp64 loops
     x, w, dy = wl.conv_inputs(layer, n, cfg["dtype"], 1)
     xo, wo, dyo = (t.double().numpy() for t in (x, w, dy))
     oracle.conv2d_fwd(xo[:1, :, :8, :8].copy(), wo, layer.stride, layer.pad)  # load the library
