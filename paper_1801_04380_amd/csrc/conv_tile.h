@@ -119,8 +119,12 @@ struct __attribute__((packed, aligned(2))) U32u { uint32_t v; };
 __device__ inline uint32_t load2_any(const bf16_t *p) { return reinterpret_cast<const U32u *>(p)->v; }
 
 // Eight consecutive bf16 as one 16-byte store, whatever the alignment.
-struct __attribute__((packed, aligned(2))) U128u { uint4 v; };
-__device__ inline void store8_any(bf16_t *p, uint4 v) { reinterpret_cast<U128u *>(p)->v = v; }
+struct __attribute__((packed, aligned(2))) U128u { uint32_t v[4]; };
+__device__ inline void store8_any(bf16_t *p, uint4 v)
+{
+    U128u u = {{v.x, v.y, v.z, v.w}};
+    *reinterpret_cast<U128u *>(p) = u;
+}
 
 // Two fp32 to a pair of bf16 (round to nearest even), the first in the low half.
 typedef float f32x2 __attribute__((ext_vector_type(2)));

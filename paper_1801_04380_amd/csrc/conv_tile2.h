@@ -59,7 +59,6 @@ __device__ __forceinline__ void conv_tile2_body(const bf16_t *__restrict__ in, c
     constexpr int WROWS = PIXT / 32 + R - 1;   // WIDE: patch rows
     constexpr int XG = DW == 16 ? 4 : 16;   // most load rounds per chunk: 16 / (channels per round)
     constexpr int XTR = WIDE ? (2 * WROWS * (WIDE_LWP / 16) + 15) / 16 : V2_XTR_MAX_NARROW;
-    constexpr int NEVER = -(1 << 30);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, g = lane >> 5;

@@ -99,7 +99,7 @@ wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
 {
     constexpr int T = RG * S, KTB = 2 * TM * 32, NT = TM * 256;   // 4*TM waves: 2*TM along k, 2 along c
     constexpr int OPR = TWP / 8, TPR = NT / OPR;      // octets per row; threads per octet column
-    constexpr int XROWS = TH + RG - 1, APR = S > 1 ? 8 : 0, LWX = TWP + 2 * APR, PW = (S - 1) / 2;
+    constexpr int XROWS = TH + RG - 1, APR = S > 1 ? 8 : 0, LWX = TWP + 2 * APR;
     constexpr int AP = odd16c(TH * TWP), CP = odd16c(XROWS * LWX);
     constexpr int YS = KTB * AP, XS = CTB * CP, BUF = YS + XS;   // elements
     constexpr int NCG = TWP / 16;
