@@ -89,20 +89,23 @@ template <int d> __device__ inline bf16x8 shifted(const uint32_t (&D)[8])
     return r;
 }
 
-// S: filter width (1 or 3), RG: filter rows (= R), TM: 32-row k tiles per wave, TH x TWP: chunk,
+// S: filter width (1 or 3), RG: filter rows (= R), TM: the workgroup owns 2*TM*32 k, TH x TWP: chunk,
 // WIDE: 32-column tiles of an image whose width is a multiple of 8 (otherwise the chunk spans the
-// whole width, which may be ragged).
-template <int S, int RG, int TM, int TH, int TWP, bool WIDE>
-__global__ void __launch_bounds__(TM * 256) __attribute__((amdgpu_waves_per_eu(TM, TM)))
+// whole width, which may be ragged), TP: 2 = two sets of waves share the k x c tile and split the
+// chunk's 16-column groups between them (their accumulators are added in the epilogue): a second
+// wave per SIMD where K is too small for TM = 2.
+template <int S, int RG, int TM, int TH, int TWP, bool WIDE, int TP>
+__global__ void __launch_bounds__(TM * TP * 256) __attribute__((amdgpu_waves_per_eu(TM * TP, TM * TP)))
 wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, float *__restrict__ out,
                   int use_atomics, RowsProblem p)
 {
-    constexpr int T = RG * S, KTB = 2 * TM * 32, NT = TM * 256;   // 4*TM waves: 2*TM along k, 2 along c
+    constexpr int T = RG * S, KTB = 2 * TM * 32, NT = TM * TP * 256;   // 4*TM*TP waves: TP sets of 2*TM along k x 2 along c
     constexpr int OPR = TWP / 8, TPR = NT / OPR;      // octets per row; threads per octet column
     constexpr int XROWS = TH + RG - 1, APR = S > 1 ? 8 : 0, LWX = TWP + 2 * APR;
     constexpr int AP = odd16c(TH * TWP), CP = odd16c(XROWS * LWX);
     constexpr int YS = KTB * AP, XS = CTB * CP, BUF = YS + XS;   // elements
     constexpr int NCG = TWP / 16;
+    static_assert(NCG % TP == 0, "the column groups do not split over the wave sets");
     // staging items of a thread: dy (k, row), x (c, row), apron (c, row, side)
     constexpr int YKREP = KTB >= TPR ? KTB / TPR : 1, YRPT = KTB >= TPR ? 1 : TPR / KTB;
     constexpr int YIT = KTB >= TPR ? TH * YKREP : TH / YRPT;
@@ -116,7 +119,7 @@ wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, g = lane >> 5;
-    const int wk = wave >> 1, wc = wave & 1;
+    const int wk = (wave >> 1) % (2 * TM), wc = wave & 1, ph = wave / (4 * TM);   // ph: which set of waves
     // Which tile and slice.  With a one-dimensional grid (p.xcd_slices > 0) workgroup L runs on XCD
     // L % 8 (round-robin dispatch), and every XCD has an L2 of its own: each XCD gets a contiguous
     // range of slices, and the tiles of one slice, which read the same x and dy rows, follow each
@@ -277,7 +280,8 @@ wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
         u32x4 m;
         uint32_t lo, hi;
     };
-    constexpr int NSTEP = NCG * XROWS;   // (column group, x row) steps of a chunk
+    constexpr int NCGW = NCG / TP;       // column groups per wave
+    constexpr int NSTEP = NCGW * XROWS;  // (column group, x row) steps of a chunk, per wave
     constexpr int LAG = 4;               // an item is written to LDS this many items after its load
     auto compute = [&](int buf) {
         const bf16_t *ys = smem + buf * BUF + ylane, *xs = smem + buf * BUF + YS + xlane;
@@ -295,7 +299,8 @@ wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
                 a[tm] = *reinterpret_cast<const bf16x8 *>(ys + tm * 32 * AP + row * TWP + cg * 16);
         };
 #pragma unroll
-        for (int cg = 0; cg < NCG; ++cg) {
+        for (int cgi = 0; cgi < NCGW; ++cgi) {
+            const int cg = cgi * TP + ph;
             bf16x8 aw[RG + 1][WTM];   // dy rows in flight, by row % (RG + 1)
             Raw raw[2];
             load_raw(raw[0], cg, 0);
@@ -329,7 +334,7 @@ wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 // this step's share of the next chunk's staging
-                const int st = cg * XROWS + xr;
+                const int st = cgi * XROWS + xr;
                 const int lo = st * NITEMS / NSTEP, hi = (st + 1) * NITEMS / NSTEP;
 #pragma unroll
                 for (int i = 0; i < NITEMS; ++i)
@@ -379,9 +384,23 @@ wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const int rr = ((wk * WTM + tm) * 2 + g) * 4 + i;
-                    stage[rr * EP + (wc * 32 + l32) * T + t] = acc[tm][t][4 * ps + i];
+                    if (ph == 0) stage[rr * EP + (wc * 32 + l32) * T + t] = acc[tm][t][4 * ps + i];
                 }
         __syncthreads();
+        if (TP == 2) {   // the second set of waves adds its share
+            if (ph == 1) {
+#pragma unroll
+                for (int tm = 0; tm < WTM; ++tm)
+#pragma unroll
+                    for (int t = 0; t < T; ++t)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const int rr = ((wk * WTM + tm) * 2 + g) * 4 + i;
+                            stage[rr * EP + (wc * 32 + l32) * T + t] += acc[tm][t][4 * ps + i];
+                        }
+            }
+            __syncthreads();
+        }
         if (!use_atomics && p.C % CTB == 0 && (reinterpret_cast<uintptr_t>(dst) & 15) == 0) {
             // whole rows of 64 c x T taps are contiguous and 16-byte aligned in dw: float4 stores
             constexpr int R4 = ROWLEN / 4;
@@ -416,7 +435,7 @@ struct RPlan {
     RowsProblem p;
     dim3 grid;
     int nslices;
-    int S, TM, TH, TWP;
+    int S, TM, TH, TWP, TP;
     bool wide;
 };
 
@@ -476,20 +495,22 @@ bool make_rplan(const ConvGeom &g, RPlan *pl)
     }
     pl->p = p;
     pl->S = g.S; pl->TM = TM; pl->TH = TH; pl->TWP = TWP; pl->wide = wide;
+    // a second set of waves on the same tile where the tile has one wave per SIMD and the chunk two column groups
+    pl->TP = (TM == 1 && TWP == 32 && (long long)g.N * g.P * g.Q >= 20000) ? 2 : 1;
     return true;
 }
 
-template <int S, int RG, int TM, int TH, int TWP, bool WIDE>
+template <int S, int RG, int TM, int TH, int TWP, bool WIDE, int TP = 1>
 hipError_t launch_shape(const bf16_t *x, const bf16_t *dy, float *out, int atomics, const RPlan &pl, hipStream_t st)
 {
     constexpr size_t smem = rows_smem<S, RG, TM, TH, TWP>();
     static_assert(smem <= 160 * 1024, "chunk does not fit in LDS");
-    auto kern = wgrad_rows_kernel<S, RG, TM, TH, TWP, WIDE>;
+    auto kern = wgrad_rows_kernel<S, RG, TM, TH, TWP, WIDE, TP>;
     // dynamic LDS beyond 64 KB has to be enabled once per kernel
     static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL(kern, pl.grid, dim3(TM * 256), smem, st, x, dy, out, atomics, pl.p);
+    hipLaunchKernelGGL(kern, pl.grid, dim3(TM * TP * 256), smem, st, x, dy, out, atomics, pl.p);
     return hipGetLastError();
 }
 
@@ -498,6 +519,10 @@ hipError_t launch_tm(const bf16_t *x, const bf16_t *dy, float *out, int atomics,
 {
     if (pl.TWP == 16) return launch_shape<S, RG, TM, 8, 16, false>(x, dy, out, atomics, pl, st);
     if (pl.TWP == 64) return launch_shape<S, RG, TM, 2, 64, false>(x, dy, out, atomics, pl, st);
+    if (TM == 1 && pl.TP == 2) {
+        if (pl.wide) return launch_shape<S, RG, 1, 4, 32, true, 2>(x, dy, out, atomics, pl, st);
+        return launch_shape<S, RG, 1, 4, 32, false, 2>(x, dy, out, atomics, pl, st);
+    }
     if (pl.wide) return launch_shape<S, RG, TM, 4, 32, true>(x, dy, out, atomics, pl, st);
     return launch_shape<S, RG, TM, 4, 32, false>(x, dy, out, atomics, pl, st);
 }

@@ -50,6 +50,7 @@ CASES = [
     (L("w14", 35, 14, 14, 96, 3, 3, (1, 1), (1, 1)), 7),
     (L("w6_pad0", 20, 9, 6, 70, 3, 3, (1, 1), (0, 0)), 5),
     (L("w28_big", 16, 28, 28, 256, 3, 3, (1, 1), (1, 1)), 48),
+    (L("w28_k96", 32, 28, 28, 96, 3, 3, (1, 1), (1, 1)), 32),         # backward-filter with two wave sets per tile
     (L("c96_bwd", 96, 16, 16, 48, 3, 3, (1, 1), (1, 1)), 3),          # backward-data into 96 channels
     (L("c130_pad2", 130, 10, 12, 130, 3, 3, (1, 1), (2, 2)), 2),
 ]
