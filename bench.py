@@ -155,10 +155,11 @@ def build_ops(cfg_no, budget, autotune, fuse):
         else:
             g_a.copy_(dy)
         if cfg["bn"] and fuse:
-            # ReLU backward and BN backward in one call: reads x, the gate and the gradient, writes dx
+            # ReLU backward and BN backward in one call: reads x and the gradient, writes dx (the
+            # ReLU gate is re-derived from x)
             cheap_b.append(Op("bn_relu_bwd", layer.name,
-                              lambda y=y, s=a, g=g_a, ga=gamma, m=mean, i=invstd, o=dy, dg=dgamma, db=dbeta:
-                              sn.sn_bn_relu_bwd(y, s, g, ga, m, i, o, dg, db), nbytes=4 * E * b))
+                              lambda y=y, g=g_a, ga=gamma, be=beta, m=mean, i=invstd, o=dy, dg=dgamma, db=dbeta:
+                              sn.sn_bn_relu_bwd(y, g, ga, be, m, i, o, dg, db), nbytes=3 * E * b))
         else:
             relu_grad_out = g_bn if cfg["bn"] else dy
             cheap_b.append(Op("relu_bwd", layer.name, lambda s=a, g=g_a, o=relu_grad_out: sn.sn_relu_bwd(s, g, o),

@@ -164,7 +164,7 @@ sn_status sn_bn_fwd(const void *x, const float *gamma, const float *beta, void *
  * CONV (Sec. 3.4: the cheap layers between two checkpoints are recomputed together):
  *   y = max(gamma*(x-mean)*invstd + beta, 0)   (0 unless the BN output is > 0),
  * everything else as sn_bn_fwd.  The BN output itself is not stored: sn_relu_bwd gates on y,
- * and sn_bn_bwd needs x and the saved statistics only. */
+ * sn_bn_bwd needs x and the saved statistics only, and sn_bn_relu_bwd does both from x. */
 sn_status sn_bn_relu_fwd(const void *x, const float *gamma, const float *beta, void *y,
                          float *save_mean, float *save_invstd,
                          int N, int C, int H, int W, float eps, sn_dtype dtype, sn_stream stream);
@@ -180,9 +180,14 @@ sn_status sn_bn_bwd(const void *x, const void *dy, const float *gamma,
 
 /* Backward of the BN + ReLU pair (sn_bn_relu_fwd) in one call: sn_bn_bwd applied to
  *   g = y > 0 ? dy : 0,
- * where y is the pair's output (the ReLU gate of sn_relu_bwd) and dy the gradient that
- * reaches it; g is never stored.  x is the BN input.  dx must alias none of x, y, dy. */
-sn_status sn_bn_relu_bwd(const void *x, const void *y, const void *dy, const float *gamma,
+ * where y is the pair's output as sn_bn_relu_fwd stored it (the ReLU gate of sn_relu_bwd) and
+ * dy the gradient that reaches it; g is never stored.  y is not an argument: whether it is
+ * > 0 is re-derived from x, gamma, beta and the saved statistics with the forward pass's own
+ * arithmetic (including the rounding of the stored value to `dtype`), so the result is
+ * bit-identical to gating on the stored y while the pair's output need not be alive, or
+ * recomputed (Sec. 3.4), for this call.  gamma, beta, save_mean, save_invstd must be the
+ * values the forward call used and wrote.  x is the BN input.  dx must alias neither x nor dy. */
+sn_status sn_bn_relu_bwd(const void *x, const void *dy, const float *gamma, const float *beta,
                          const float *save_mean, const float *save_invstd,
                          void *dx, float *dgamma, float *dbeta,
                          int N, int C, int H, int W, sn_dtype dtype, sn_stream stream);

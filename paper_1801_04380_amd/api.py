@@ -148,9 +148,9 @@ def sn_bn_bwd(x, dy, gamma, save_mean, save_invstd, dx, dgamma, dbeta):
                                          _stream()))
 
 
-def sn_bn_relu_bwd(x, y, dy, gamma, save_mean, save_invstd, dx, dgamma, dbeta):
+def sn_bn_relu_bwd(x, dy, gamma, beta, save_mean, save_invstd, dx, dgamma, dbeta):
     N, C, H, W = x.shape
-    _check("sn_bn_relu_bwd", load().sn_bn_relu_bwd(_ptr(x), _ptr(y), _ptr(dy), _ptr(gamma), _ptr(save_mean),
+    _check("sn_bn_relu_bwd", load().sn_bn_relu_bwd(_ptr(x), _ptr(dy), _ptr(gamma), _ptr(beta), _ptr(save_mean),
                                                    _ptr(save_invstd), _ptr(dx), _ptr(dgamma), _ptr(dbeta), N, C, H,
                                                    W, _dtype_code(x), _stream()))
 

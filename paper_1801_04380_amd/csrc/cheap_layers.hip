@@ -176,6 +176,20 @@ __device__ inline float wave_sum(float v)
 // The activation that may follow BN in the same pass: ReLU as in relu_fwd_kernel (0 unless v > 0).
 __device__ inline float act(float v, int relu) { return (!relu || v > 0.f) ? v : 0.f; }
 
+// The BN output before the activation.  Forward and backward both go through this one
+// expression (a single fused multiply-add), so the backward pass can re-derive from x,
+// bit for bit, what the forward pass stored.
+__device__ inline float bn_affine(float x, float mu, float a, float b) { return __builtin_fmaf(x - mu, a, b); }
+
+// Whether the stored output of BN + ReLU is > 0 for the BN output v: v > 0, and for bf16
+// storage v does not round to zero (every positive float above 0x8000 rounds to a
+// nonzero bf16).  This is the gate of the ReLU backward, taken without reading the output.
+template <typename T> __device__ inline bool relu_passes(float v)
+{
+    if (sizeof(T) == 2) return v > 0.f && __float_as_uint(v) > 0x8000u;
+    return v > 0.f;
+}
+
 // Pass 1 (forward): per (channel, slice) partial sums of (x - shift) and
 // (x - shift)^2, shift = the channel's first element, which keeps the variance
 // free of cancellation whatever the channel's mean is.
@@ -276,40 +290,41 @@ bn_apply_kernel(const T *__restrict__ x, T *__restrict__ y, const float *__restr
                 float f[V];
                 Vec<T>::load(p + off, f);
 #pragma unroll
-                for (int i = 0; i < V; ++i) f[i] = act((f[i] - mu) * a + b, relu);
+                for (int i = 0; i < V; ++i) f[i] = act(bn_affine(f[i], mu, a, b), relu);
                 Vec<T>::store(o + off, f);
             },
-            [&](int off) { st(o + off, act((ld<T>(p + off) - mu) * a + b, relu)); });
+            [&](int off) { st(o + off, act(bn_affine(ld<T>(p + off), mu, a, b), relu)); });
     }
 }
 
 // Backward pass 1: per (channel, slice) partial sums of dy and dy*(x - mean).
 template <typename T>
 __global__ void __launch_bounds__(256)
-bn_bwd_reduce_kernel(const T *__restrict__ x, const T *__restrict__ dy, const T *__restrict__ gate,
-                     const float *__restrict__ mean, float *__restrict__ part, int N, int C, int HW, Slices sl)
+bn_bwd_reduce_kernel(const T *__restrict__ x, const T *__restrict__ dy, const float *__restrict__ gamma,
+                     const float *__restrict__ beta, const float *__restrict__ mean,
+                     const float *__restrict__ invstd, float *__restrict__ part, int N, int C, int HW, Slices sl)
 {
     constexpr int V = Vec<T>::N;
     const int c = blockIdx.x, slice = blockIdx.y;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const float mu = mean[c];
+    const bool relu = beta != nullptr;
+    const float ga = gamma[c] * invstd[c], gb = relu ? beta[c] : 0.f;
     float s1 = 0.f, s2 = 0.f;
     for (int seg = slice * 4 + wave; seg < sl.nseg; seg += 4 * sl.nslice) {
         const int n = seg / sl.nseg_plane, k = seg - n * sl.nseg_plane;
         const int e0 = k * SEG, len = min(SEG, HW - e0);
         const size_t base = ((size_t)n * C + c) * HW + e0;
-        const T *p = x + base, *gp = dy + base, *ap = gate ? gate + base : nullptr;
+        const T *p = x + base, *gp = dy + base;
         walk_segment<T>(
             p, len, lane,
             [&](int off) {
                 float f[V], gr[V];
                 Vec<T>::load(p + off, f);
                 Vec<T>::load(gp + off, gr);
-                if (ap) {
-                    float a[V];
-                    Vec<T>::load(ap + off, a);
+                if (relu) {
 #pragma unroll
-                    for (int i = 0; i < V; ++i) gr[i] = a[i] > 0.f ? gr[i] : 0.f;
+                    for (int i = 0; i < V; ++i) gr[i] = relu_passes<T>(bn_affine(f[i], mu, ga, gb)) ? gr[i] : 0.f;
                 }
 #pragma unroll
                 for (int i = 0; i < V; ++i) {
@@ -318,10 +333,11 @@ bn_bwd_reduce_kernel(const T *__restrict__ x, const T *__restrict__ dy, const T 
                 }
             },
             [&](int off) {
+                const float f = ld<T>(p + off);
                 float gr = ld<T>(gp + off);
-                if (ap && !(ld<T>(ap + off) > 0.f)) gr = 0.f;
+                if (relu && !relu_passes<T>(bn_affine(f, mu, ga, gb))) gr = 0.f;
                 s1 += gr;
-                s2 += gr * (ld<T>(p + off) - mu);
+                s2 += gr * (f - mu);
             });
     }
     s1 = wave_sum(s1);
@@ -360,7 +376,7 @@ bn_bwd_final_kernel(const float *__restrict__ part, const float *__restrict__ in
 // Backward pass 3: dx = gamma*invstd * (dy - dbeta/M - xhat*dgamma/M).
 template <typename T>
 __global__ void __launch_bounds__(256)
-bn_bwd_apply_kernel(const T *__restrict__ x, const T *__restrict__ dy, const T *__restrict__ gate,
+bn_bwd_apply_kernel(const T *__restrict__ x, const T *__restrict__ dy, const float *__restrict__ beta,
                     T *__restrict__ dx, const float *__restrict__ gamma, const float *__restrict__ mean,
                     const float *__restrict__ invstd, const float *__restrict__ dgamma,
                     const float *__restrict__ dbeta, int N, int C, int HW, Slices sl)
@@ -372,12 +388,14 @@ bn_bwd_apply_kernel(const T *__restrict__ x, const T *__restrict__ dy, const T *
     const float invM = 1.f / ((float)N * (float)HW);
     const float mu = mean[c], is = invstd[c], k1 = gamma[c] * is;
     const float kb = dbeta[c] * invM, kg = dgamma[c] * invM * is;  // xhat*dgamma/M = (x-mu)*kg
+    const bool relu = beta != nullptr;
+    const float gb = relu ? beta[c] : 0.f;
     const int seg0 = slice * 4 + wave, step = 4 * sl.nslice;
     for (int seg = seg0 + (seg0 < sl.nseg ? (sl.nseg - 1 - seg0) / step * step : 0); seg >= seg0 && seg < sl.nseg; seg -= step) {
         const int n = seg / sl.nseg_plane, k = seg - n * sl.nseg_plane;
         const int e0 = k * SEG, len = min(SEG, HW - e0);
         const size_t base = ((size_t)n * C + c) * HW + e0;
-        const T *p = x + base, *gp = dy + base, *ap = gate ? gate + base : nullptr;
+        const T *p = x + base, *gp = dy + base;
         T *o = dx + base;
         walk_segment<T>(
             p, len, lane,
@@ -385,20 +403,19 @@ bn_bwd_apply_kernel(const T *__restrict__ x, const T *__restrict__ dy, const T *
                 float f[V], gr[V];
                 Vec<T>::load(p + off, f);
                 Vec<T>::load(gp + off, gr);
-                if (ap) {
-                    float a[V];
-                    Vec<T>::load(ap + off, a);
+                if (relu) {
 #pragma unroll
-                    for (int i = 0; i < V; ++i) gr[i] = a[i] > 0.f ? gr[i] : 0.f;
+                    for (int i = 0; i < V; ++i) gr[i] = relu_passes<T>(bn_affine(f[i], mu, k1, gb)) ? gr[i] : 0.f;
                 }
 #pragma unroll
                 for (int i = 0; i < V; ++i) f[i] = k1 * (gr[i] - kb - (f[i] - mu) * kg);
                 Vec<T>::store(o + off, f);
             },
             [&](int off) {
+                const float f = ld<T>(p + off);
                 float gr = ld<T>(gp + off);
-                if (ap && !(ld<T>(ap + off) > 0.f)) gr = 0.f;
-                st(o + off, k1 * (gr - kb - (ld<T>(p + off) - mu) * kg));
+                if (relu && !relu_passes<T>(bn_affine(f, mu, k1, gb))) gr = 0.f;
+                st(o + off, k1 * (gr - kb - (f - mu) * kg));
             });
     }
 }
@@ -505,7 +522,7 @@ bn_fwd_fused_kernel(const T *__restrict__ x, T *__restrict__ y, const float *__r
             float f[VE];
             unpack<T, VB>(v[j], f);
 #pragma unroll
-            for (int k = 0; k < VE; ++k) f[k] = act((f[k] - mu) * a + b, relu);
+            for (int k = 0; k < VE; ++k) f[k] = act(bn_affine(f[k], mu, a, b), relu);
             *reinterpret_cast<VT *>(y + ((size_t)n * C + c) * HW + (size_t)e * VE) = pack<T, VB>(f);
         }
     }
@@ -513,7 +530,7 @@ bn_fwd_fused_kernel(const T *__restrict__ x, T *__restrict__ y, const float *__r
 
 template <typename T, int VB, int NVMAX>
 __global__ void __launch_bounds__(1024)
-bn_bwd_fused_kernel(const T *__restrict__ x, const T *__restrict__ dy, const T *__restrict__ gate,
+bn_bwd_fused_kernel(const T *__restrict__ x, const T *__restrict__ dy, const float *__restrict__ beta,
                     T *__restrict__ dx, const float *__restrict__ gamma, const float *__restrict__ mean,
                     const float *__restrict__ invstd, float *__restrict__ dgamma, float *__restrict__ dbeta,
                     int N, int C, int HW)
@@ -524,6 +541,8 @@ bn_bwd_fused_kernel(const T *__restrict__ x, const T *__restrict__ dy, const T *
     const int c = blockIdx.x, tid = threadIdx.x;
     const int vpp = HW / VE, nvec = N * vpp;
     const float mu = mean[c], is = invstd[c];
+    const bool relu = beta != nullptr;
+    const float ga = gamma[c] * is, gb = relu ? beta[c] : 0.f;
     VT xv[NVMAX], gv[NVMAX];
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
@@ -537,12 +556,9 @@ bn_bwd_fused_kernel(const T *__restrict__ x, const T *__restrict__ dy, const T *
             float f[VE], gr[VE];
             unpack<T, VB>(xv[j], f);
             unpack<T, VB>(gv[j], gr);
-            if (gate) {   // the gradient that passes the ReLU is what is kept in registers
-                const VT av = *reinterpret_cast<const VT *>(gate + off);
-                float a[VE];
-                unpack<T, VB>(av, a);
+            if (relu) {   // the gradient that passes the ReLU is what is kept in registers
 #pragma unroll
-                for (int k = 0; k < VE; ++k) gr[k] = a[k] > 0.f ? gr[k] : 0.f;
+                for (int k = 0; k < VE; ++k) gr[k] = relu_passes<T>(bn_affine(f[k], mu, ga, gb)) ? gr[k] : 0.f;
                 gv[j] = pack<T, VB>(gr);
             }
 #pragma unroll
@@ -556,7 +572,7 @@ bn_bwd_fused_kernel(const T *__restrict__ x, const T *__restrict__ dy, const T *
     const float dg = block_sum_1024(s2, red) * is;
     if (tid == 0) { dbeta[c] = db; dgamma[c] = dg; }
     const float invM = 1.f / ((float)N * (float)HW);
-    const float k1 = gamma[c] * is, kb = db * invM, kg = dg * invM * is;
+    const float k1 = ga, kb = db * invM, kg = dg * invM * is;
 #pragma unroll
     for (int j = 0; j < NVMAX; ++j) {
         const int i = tid + j * 1024;
@@ -615,12 +631,12 @@ __global__ void bn_fwd_tiny_kernel(const T *__restrict__ x, T *__restrict__ y, c
     for (int n = 0; n < N; ++n)
         for (int i = 0; i < HW; ++i) {
             const size_t j = ((size_t)n * C + c) * HW + i;
-            st(y + j, act((ld<T>(x + j) - mu) * a + b, relu));
+            st(y + j, act(bn_affine(ld<T>(x + j), mu, a, b), relu));
         }
 }
 
 template <typename T>
-__global__ void bn_bwd_tiny_kernel(const T *__restrict__ x, const T *__restrict__ dy, const T *__restrict__ gate,
+__global__ void bn_bwd_tiny_kernel(const T *__restrict__ x, const T *__restrict__ dy, const float *__restrict__ beta,
                                    T *__restrict__ dx,
                                    const float *__restrict__ gamma, const float *__restrict__ mean,
                                    const float *__restrict__ invstd, float *__restrict__ dgamma,
@@ -630,23 +646,27 @@ __global__ void bn_bwd_tiny_kernel(const T *__restrict__ x, const T *__restrict_
     if (c >= C) return;
     const float invM = 1.f / ((float)N * (float)HW);
     const float mu = mean[c], is = invstd[c];
+    const bool relu = beta != nullptr;
+    const float ga = gamma[c] * is, gb = relu ? beta[c] : 0.f;
     float db = 0.f, dg = 0.f;
     for (int n = 0; n < N; ++n)
         for (int i = 0; i < HW; ++i) {
             const size_t j = ((size_t)n * C + c) * HW + i;
-            const float gr = (gate && !(ld<T>(gate + j) > 0.f)) ? 0.f : ld<T>(dy + j);
+            const float f = ld<T>(x + j);
+            const float gr = (relu && !relu_passes<T>(bn_affine(f, mu, ga, gb))) ? 0.f : ld<T>(dy + j);
             db += gr;
-            dg += gr * (ld<T>(x + j) - mu);
+            dg += gr * (f - mu);
         }
     dg *= is;
     dbeta[c] = db;
     dgamma[c] = dg;
-    const float k1 = gamma[c] * is, kb = db * invM, kg = dg * invM * is;
+    const float k1 = ga, kb = db * invM, kg = dg * invM * is;
     for (int n = 0; n < N; ++n)
         for (int i = 0; i < HW; ++i) {
             const size_t j = ((size_t)n * C + c) * HW + i;
-            const float gr = (gate && !(ld<T>(gate + j) > 0.f)) ? 0.f : ld<T>(dy + j);
-            st(dx + j, k1 * (gr - kb - (ld<T>(x + j) - mu) * kg));
+            const float f = ld<T>(x + j);
+            const float gr = (relu && !relu_passes<T>(bn_affine(f, mu, ga, gb))) ? 0.f : ld<T>(dy + j);
+            st(dx + j, k1 * (gr - kb - (f - mu) * kg));
         }
 }
 
@@ -906,7 +926,7 @@ hipError_t launch_bn_fwd(const void *x, const float *gamma, const float *beta, v
     });
 }
 
-hipError_t launch_bn_bwd(const void *x, const void *dy, const void *gate, const float *gamma, const float *mean,
+hipError_t launch_bn_bwd(const void *x, const void *dy, const float *relu_beta, const float *gamma, const float *mean,
                          const float *invstd, void *dx, float *dgamma, float *dbeta, int N, int C, int HW,
                          int bf16, hipStream_t s)
 {
@@ -915,20 +935,19 @@ hipError_t launch_bn_bwd(const void *x, const void *dy, const void *gate, const 
         return by_dtype(bf16, [&](auto *tag) {
             typedef typename std::remove_pointer<decltype(tag)>::type T;
             hipLaunchKernelGGL(bn_bwd_tiny_kernel<T>, dim3((C + 63) / 64), dim3(64), 0, s, (const T *)x,
-                               (const T *)dy, (const T *)gate, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);
+                               (const T *)dy, relu_beta, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);
         });
     {
         int vb = bf16 ? bn_fused_vb<bf16_t>(x, dy, dx, N, HW) : bn_fused_vb<float>(x, dy, dx, N, HW);
-        if (vb && gate && reinterpret_cast<uintptr_t>(gate) % vb != 0) vb = 0;
         if (vb)
             return by_dtype(bf16, [&](auto *tag) {
                 typedef typename std::remove_pointer<decltype(tag)>::type T;
                 if (vb == 16)
                     hipLaunchKernelGGL((bn_bwd_fused_kernel<T, 16, BN_FUSED_NV>), dim3(C), dim3(1024), 0, s, (const T *)x,
-                                       (const T *)dy, (const T *)gate, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);
+                                       (const T *)dy, relu_beta, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);
                 else
                     hipLaunchKernelGGL((bn_bwd_fused_kernel<T, 8, BN_FUSED_NV>), dim3(C), dim3(1024), 0, s, (const T *)x,
-                                       (const T *)dy, (const T *)gate, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);
+                                       (const T *)dy, relu_beta, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);
             });
     }
     const Slices sl = make_slices(N, C, HW, (size_t)N * C * HW * esz);
@@ -936,11 +955,11 @@ hipError_t launch_bn_bwd(const void *x, const void *dy, const void *gate, const 
     return by_dtype(bf16, [&](auto *tag) {
         typedef typename std::remove_pointer<decltype(tag)>::type T;
         dim3 grid(C, sl.nslice), block(256);
-        hipLaunchKernelGGL(bn_bwd_reduce_kernel<T>, grid, block, 0, s, (const T *)x, (const T *)dy, (const T *)gate,
-                           mean, part, N, C, HW, sl);
+        hipLaunchKernelGGL(bn_bwd_reduce_kernel<T>, grid, block, 0, s, (const T *)x, (const T *)dy, gamma, relu_beta,
+                           mean, invstd, part, N, C, HW, sl);
         hipLaunchKernelGGL(bn_bwd_final_kernel, dim3(C), dim3(64), 0, s, part, invstd, dgamma, dbeta,
                            sl.nslice);
-        hipLaunchKernelGGL(bn_bwd_apply_kernel<T>, grid, block, 0, s, (const T *)x, (const T *)dy, (const T *)gate,
+        hipLaunchKernelGGL(bn_bwd_apply_kernel<T>, grid, block, 0, s, (const T *)x, (const T *)dy, relu_beta,
                            (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW, sl);
     });
 }

@@ -501,20 +501,19 @@ sn_status sn_bn_relu_fwd(const void *x, const float *gamma, const float *beta, v
     return bn_fwd_common(x, gamma, beta, y, save_mean, save_invstd, N, C, H, W, eps, dtype, 1, stream);
 }
 
-static sn_status bn_bwd_common(const void *x, const void *dy, const void *gate, const float *gamma,
+static sn_status bn_bwd_common(const void *x, const void *dy, const float *relu_beta, const float *gamma,
                                const float *save_mean, const float *save_invstd, void *dx, float *dgamma,
                                float *dbeta, int N, int C, int H, int W, sn_dtype dtype, sn_stream stream)
 {
     sn_status s = check_cheap(N, C, H, W, dtype);
     if (s != SN_OK) return s;
-    if (!x || !dy || !gamma || !save_mean || !save_invstd || !dx || !dgamma || !dbeta || dx == x || dx == dy ||
-        dx == gate)
+    if (!x || !dy || !gamma || !save_mean || !save_invstd || !dx || !dgamma || !dbeta || dx == x || dx == dy)
         return SN_ERR_BAD_ARG;
     if (!aligned(x, 16) || !aligned(dy, 16) || !aligned(dx, 16) || !aligned(gamma, 4) || !aligned(save_mean, 4) ||
-        !aligned(save_invstd, 4) || !aligned(dgamma, 4) || !aligned(dbeta, 4) || (gate && !aligned(gate, 16)))
+        !aligned(save_invstd, 4) || !aligned(dgamma, 4) || !aligned(dbeta, 4) || (relu_beta && !aligned(relu_beta, 4)))
         return SN_ERR_BAD_ARG;
     if (C > 65535 * 32) return SN_ERR_UNSUPPORTED;
-    return launch_status(launch_bn_bwd(x, dy, gate, gamma, save_mean, save_invstd, dx, dgamma, dbeta, N, C, H * W,
+    return launch_status(launch_bn_bwd(x, dy, relu_beta, gamma, save_mean, save_invstd, dx, dgamma, dbeta, N, C, H * W,
                                        dtype == SN_BF16, static_cast<hipStream_t>(stream)));
 }
 
@@ -525,12 +524,12 @@ sn_status sn_bn_bwd(const void *x, const void *dy, const float *gamma, const flo
     return bn_bwd_common(x, dy, nullptr, gamma, save_mean, save_invstd, dx, dgamma, dbeta, N, C, H, W, dtype, stream);
 }
 
-sn_status sn_bn_relu_bwd(const void *x, const void *y, const void *dy, const float *gamma, const float *save_mean,
-                         const float *save_invstd, void *dx, float *dgamma, float *dbeta, int N, int C, int H,
-                         int W, sn_dtype dtype, sn_stream stream)
+sn_status sn_bn_relu_bwd(const void *x, const void *dy, const float *gamma, const float *beta,
+                         const float *save_mean, const float *save_invstd, void *dx, float *dgamma, float *dbeta,
+                         int N, int C, int H, int W, sn_dtype dtype, sn_stream stream)
 {
-    if (!y) return SN_ERR_BAD_ARG;
-    return bn_bwd_common(x, dy, y, gamma, save_mean, save_invstd, dx, dgamma, dbeta, N, C, H, W, dtype, stream);
+    if (!beta) return SN_ERR_BAD_ARG;
+    return bn_bwd_common(x, dy, beta, gamma, save_mean, save_invstd, dx, dgamma, dbeta, N, C, H, W, dtype, stream);
 }
 
 static sn_status check_pool(int N, int C, int H, int W, int kh, int kw, int sh, int sw, int ph, int pw, int dtype,

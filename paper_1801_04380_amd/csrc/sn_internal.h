@@ -87,8 +87,9 @@ hipError_t launch_relu_bwd(const void *x, const void *dy, void *dx, size_t n, in
 // relu != 0: the ReLU that follows BN is applied in the same pass (y = max(BN(x), 0)).
 hipError_t launch_bn_fwd(const void *x, const float *gamma, const float *beta, void *y, float *mean,
                          float *invstd, int N, int C, int HW, float eps, int bf16, int relu, hipStream_t st);
-// gate != nullptr: dy is first passed through the ReLU backward gate (kept where gate > 0).
-hipError_t launch_bn_bwd(const void *x, const void *dy, const void *gate, const float *gamma, const float *mean,
+// relu_beta != nullptr: the layer was BN + ReLU with this beta; dy is first passed through the
+// ReLU backward gate, which is re-derived from x (the forward pass's own expression) and not read.
+hipError_t launch_bn_bwd(const void *x, const void *dy, const float *relu_beta, const float *gamma, const float *mean,
                          const float *invstd, void *dx, float *dgamma, float *dbeta, int N, int C,
                          int HW, int bf16, hipStream_t st);
 hipError_t launch_maxpool_fwd(const void *x, void *y, int32_t *idx, int NC, int H, int W, int P, int Q,

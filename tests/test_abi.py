@@ -66,9 +66,9 @@ def test_bad_arguments_are_refused_before_any_launch():
     assert lib.sn_bn_fwd(one, one, one, one, one, one, 1, 1, 1, 1, 1e-5, 0, None) == 1   # y aliases x
     assert lib.sn_bn_relu_fwd(one, one, one, one, one, one, 1, 1, 1, 1, 1e-5, 0, None) == 1   # y aliases x
     two = ctypes.c_void_p(512)
-    # the pair's backward needs the gate tensor; dx must alias none of its inputs
-    assert lib.sn_bn_relu_bwd(one, None, two, one, one, one, ctypes.c_void_p(768), one, one, 1, 1, 1, 1, 0, None) == 1
-    assert lib.sn_bn_relu_bwd(one, two, ctypes.c_void_p(768), one, one, one, two, one, one, 1, 1, 1, 1, 0, None) == 1
+    # the pair's backward needs beta to re-derive the ReLU gate; dx must alias none of its inputs
+    assert lib.sn_bn_relu_bwd(one, two, one, None, one, one, ctypes.c_void_p(768), one, one, 1, 1, 1, 1, 0, None) == 1
+    assert lib.sn_bn_relu_bwd(one, two, one, one, one, one, two, one, one, 1, 1, 1, 1, 0, None) == 1
     assert lib.sn_maxpool_fwd(one, one, one, 1, 1, 4, 4, 2, 2, 2, 2, 2, 0, 0, None) == 1  # pad >= window
 
 

@@ -104,7 +104,7 @@ def test_bn(shape, dtype):
     sn.sn_bn_bwd(xd, g, gd, mean, invstd, dx_ref, dg_ref, db_ref)
     dx_f = torch.full_like(xd, float("nan"))
     dg_f, db_f = torch.empty(C, device="cuda"), torch.empty(C, device="cuda")
-    sn.sn_bn_relu_bwd(xd, a, dyd, gd, mean, invstd, dx_f, dg_f, db_f)
+    sn.sn_bn_relu_bwd(xd, dyd, gd, bd, mean, invstd, dx_f, dg_f, db_f)
     torch.cuda.synchronize()
     assert torch.equal(dx_f, dx_ref) and torch.equal(dg_f, dg_ref) and torch.equal(db_f, db_ref)
     go = oracle.relu_bwd(f64(a), f64(dy))
@@ -124,6 +124,35 @@ def test_bn(shape, dtype):
         # (exactly 0 for M = 1), so the error is measured against the size of those terms
         terms = f64(gamma).reshape(1, C, 1, 1) * f64(invstd).reshape(1, C, 1, 1) * f64(dy)
         assert np.linalg.norm(f64(dx) - dxo) <= tol * np.linalg.norm(terms)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("N,H", [(4, 16), (40, 64)], ids=["one_pass", "two_pass"])
+def test_bn_relu_bwd_gate_edges(N, H, dtype):
+    """The pair's backward re-derives the ReLU gate from x.  Where the BN output is 0, negative,
+    or so small that its stored value rounds to 0, it must decide as a read of the stored output does."""
+    C, W = 6, H
+    x = wl.activation((N, C, H, W), dtype, 77).cuda()
+    x[:, 1] = 0.25                                    # a constant channel: BN output exactly beta
+    dy = wl.activation((N, C, H, W), dtype, 78).cuda()
+    # channel 0: outputs around the smallest bf16 subnormal (2^-133); 1: exactly 0; 2: all negative;
+    # 3: tiny negative gamma; 4, 5: ordinary
+    gamma = torch.tensor([2.0 ** -133, 1.0, 1e-3, -(2.0 ** -134), 1.0, -0.7], device="cuda")
+    beta = torch.tensor([0.0, 0.0, -1.0, 2.0 ** -135, 0.1, 0.2], device="cuda")
+    mean, invstd = torch.empty(C, device="cuda"), torch.empty(C, device="cuda")
+    a = torch.empty_like(x)
+    sn.sn_bn_relu_fwd(x, gamma, beta, a, mean, invstd, 1e-5)
+    g = torch.empty_like(dy)
+    sn.sn_relu_bwd(a, dy, g)
+    dx_ref, dx_f = torch.empty_like(x), torch.empty_like(x)
+    dg_ref, db_ref = torch.empty(C, device="cuda"), torch.empty(C, device="cuda")
+    dg_f, db_f = torch.empty(C, device="cuda"), torch.empty(C, device="cuda")
+    sn.sn_bn_bwd(x, g, gamma, mean, invstd, dx_ref, dg_ref, db_ref)
+    sn.sn_bn_relu_bwd(x, dy, gamma, beta, mean, invstd, dx_f, dg_f, db_f)
+    torch.cuda.synchronize()
+    assert torch.equal(db_f, db_ref) and torch.equal(dg_f, dg_ref) and torch.equal(dx_f, dx_ref)
+    assert float(db_ref[1]) == 0.0 and float(db_ref[2]) == 0.0     # nothing passes where the output is <= 0
+    assert float(db_ref[4]) != 0.0
 
 
 POOL_CASES = [((2, 16, 16, 16), (2, 2), (2, 2), (0, 0)), ((2, 8, 55, 55), (3, 3), (2, 2), (0, 0)),
