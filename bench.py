@@ -6,7 +6,8 @@ network-shaped workload (default: the VGG-16-shaped configuration, N = 32, bf16
 in / fp32 accumulate): for every conv layer, CONV forward, BN forward, ReLU
 forward and max-pool forward (the layers recomputation replays; BN and the ReLU
 after it are one call, sn_bn_relu_fwd, and so are their backward passes,
-sn_bn_relu_bwd, unless --no-fuse), then their backward
+sn_bn_relu_bwd, and where a 2x2 pool follows, BN + ReLU + pool are one call each
+way, sn_bn_relu_pool2_fwd / _bwd, unless --no-fuse), then their backward
 passes, CONV backward-data and CONV backward-filter, each CONV planned under the
 given workspace budget.  Inputs are resident in HBM before the timed
 region; autotuning happens before it too.
@@ -126,7 +127,13 @@ def build_ops(cfg_no, budget, autotune, fuse):
             dgamma, dbeta = torch.empty(K, device=dev), torch.empty(K, device=dev)
             g_bn = torch.empty_like(y)
         a = torch.empty_like(y)
-        if cfg["bn"] and fuse:
+        # BN + ReLU + 2x2 pool as one call each way where the pool's shape allows: the full-resolution
+        # activation and its gradient are then never written
+        pool_pair = (cfg["bn"] and fuse and layer.pool == ((2, 2), (2, 2)) and P % 2 == 0 and Q % 2 == 0
+                     and Q % (8 // b) == 0)
+        if pool_pair:
+            pass
+        elif cfg["bn"] and fuse:
             # BN and the ReLU after it in one pass: 1 read + 1 write of E elements is all the pair needs
             cheap_f.append(Op("bn_relu_fwd", layer.name,
                               lambda y=y, ga=gamma, be=beta, o=a, m=mean, i=invstd: sn.sn_bn_relu_fwd(y, ga, be, o, m, i),
@@ -146,6 +153,15 @@ def build_ops(cfg_no, budget, autotune, fuse):
             idx = torch.empty((N, K, PP, QQ), dtype=torch.int32, device=dev)
             g_pool = wl.activation((N, K, PP, QQ), dtype, wl.layer_seed(cfg_no, li) + 9).to(dev)
             Eo = pooled.numel()
+        if pool_pair:
+            cheap_f.append(Op("bn_relu_pool_fwd", layer.name,
+                              lambda y=y, ga=gamma, be=beta, o=pooled, ix=idx, m=mean, i=invstd:
+                              sn.sn_bn_relu_pool2_fwd(y, ga, be, o, ix, m, i), nbytes=E * b + Eo * (b + 4)))
+            cheap_b.append(Op("bn_relu_pool_bwd", layer.name,
+                              lambda y=y, g=g_pool, ix=idx, ga=gamma, be=beta, m=mean, i=invstd, o=dy, dg=dgamma, db=dbeta:
+                              sn.sn_bn_relu_pool2_bwd(y, g, ix, ga, be, m, i, o, dg, db),
+                              nbytes=Eo * (b + 4) + 2 * E * b))
+        elif layer.pool:
             cheap_f.append(Op("maxpool_fwd", layer.name,
                               lambda s=a, o=pooled, i=idx, k=kernel, st=stride: sn.sn_maxpool_fwd(s, o, i, k, st),
                               nbytes=E * b + Eo * (b + 4)))
@@ -154,7 +170,9 @@ def build_ops(cfg_no, budget, autotune, fuse):
                               nbytes=Eo * (b + 4) + E * b))
         else:
             g_a.copy_(dy)
-        if cfg["bn"] and fuse:
+        if pool_pair:
+            pass
+        elif cfg["bn"] and fuse:
             # ReLU backward and BN backward in one call: reads x and the gradient, writes dx (the
             # ReLU gate is re-derived from x)
             cheap_b.append(Op("bn_relu_bwd", layer.name,

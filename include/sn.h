@@ -192,6 +192,28 @@ sn_status sn_bn_relu_bwd(const void *x, const void *dy, const float *gamma, cons
                          void *dx, float *dgamma, float *dbeta,
                          int N, int C, int H, int W, sn_dtype dtype, sn_stream stream);
 
+/* BN + ReLU + 2x2 / stride-2 max-pool without padding in one call: the whole run of cheap layers
+ * that follows the last CONV of a VGG-style block, which recomputation replays together
+ * (Sec. 3.4).  save_mean / save_invstd as sn_bn_fwd; pooled [N][C][H/2][W/2] of `dtype` and idx
+ * (int32, same shape) are bit-identical to sn_maxpool_fwd applied to sn_bn_relu_fwd's output,
+ * which is not written: nothing after this call needs it (sn_bn_relu_pool2_bwd takes x, the next
+ * CONV takes pooled).  H and W must be even and W a multiple of 4 elements (bf16) or 2 (fp32),
+ * else SN_ERR_UNSUPPORTED: make the separate calls then.  idx doubles as scratch for the partial
+ * statistics; x, pooled and idx must not alias. */
+sn_status sn_bn_relu_pool2_fwd(const void *x, const float *gamma, const float *beta, void *pooled, int32_t *idx,
+                               float *save_mean, float *save_invstd,
+                               int N, int C, int H, int W, float eps, sn_dtype dtype, sn_stream stream);
+
+/* Backward of sn_bn_relu_pool2_fwd: sn_bn_relu_bwd applied to the gradient sn_maxpool_bwd would
+ * give for (dpooled, idx) -- dpooled of a window goes to the window's winner, 0 elsewhere --
+ * formed on the fly, never stored; results bit-identical to the two calls.  Same shape limits;
+ * dx [N][C][H][W] must alias none of x, dpooled, idx. */
+sn_status sn_bn_relu_pool2_bwd(const void *x, const void *dpooled, const int32_t *idx,
+                               const float *gamma, const float *beta,
+                               const float *save_mean, const float *save_invstd,
+                               void *dx, float *dgamma, float *dbeta,
+                               int N, int C, int H, int W, sn_dtype dtype, sn_stream stream);
+
 /* POOL (max) forward, the paper's example of a cheap-to-recompute layer
  * (Sec. 3.4).  Window kh x kw, stride, padding (pad < window; padded positions
  * never win).  Of equal maxima the first in row-major window order wins.

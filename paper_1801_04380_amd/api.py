@@ -15,7 +15,7 @@ __all__ = [
     "SnError", "conv_shape", "sn_out_dim", "sn_conv_workspace_query", "sn_conv_plan",
     "sn_planner_record", "sn_planner_clear", "sn_conv_autotune",
     "sn_conv2d_fwd", "sn_conv2d_bwd_data", "sn_conv2d_bwd_filter",
-    "sn_relu_fwd", "sn_relu_bwd", "sn_bn_fwd", "sn_bn_relu_fwd", "sn_bn_bwd", "sn_bn_relu_bwd", "sn_maxpool_fwd", "sn_maxpool_bwd",
+    "sn_relu_fwd", "sn_relu_bwd", "sn_bn_fwd", "sn_bn_relu_fwd", "sn_bn_bwd", "sn_bn_relu_bwd", "sn_bn_relu_pool2_fwd", "sn_bn_relu_pool2_bwd", "sn_maxpool_fwd", "sn_maxpool_bwd",
 ]
 
 SN_F32, SN_BF16 = 0, 1
@@ -153,6 +153,20 @@ def sn_bn_relu_bwd(x, dy, gamma, beta, save_mean, save_invstd, dx, dgamma, dbeta
     _check("sn_bn_relu_bwd", load().sn_bn_relu_bwd(_ptr(x), _ptr(dy), _ptr(gamma), _ptr(beta), _ptr(save_mean),
                                                    _ptr(save_invstd), _ptr(dx), _ptr(dgamma), _ptr(dbeta), N, C, H,
                                                    W, _dtype_code(x), _stream()))
+
+
+def sn_bn_relu_pool2_fwd(x, gamma, beta, pooled, idx, save_mean, save_invstd, eps=1e-5):
+    N, C, H, W = x.shape
+    _check("sn_bn_relu_pool2_fwd", load().sn_bn_relu_pool2_fwd(
+        _ptr(x), _ptr(gamma), _ptr(beta), _ptr(pooled), _ptr(idx), _ptr(save_mean), _ptr(save_invstd), N, C, H, W,
+        eps, _dtype_code(x), _stream()))
+
+
+def sn_bn_relu_pool2_bwd(x, dpooled, idx, gamma, beta, save_mean, save_invstd, dx, dgamma, dbeta):
+    N, C, H, W = x.shape
+    _check("sn_bn_relu_pool2_bwd", load().sn_bn_relu_pool2_bwd(
+        _ptr(x), _ptr(dpooled), _ptr(idx), _ptr(gamma), _ptr(beta), _ptr(save_mean), _ptr(save_invstd), _ptr(dx),
+        _ptr(dgamma), _ptr(dbeta), N, C, H, W, _dtype_code(x), _stream()))
 
 
 def sn_maxpool_fwd(x, y, idx, kernel, stride, pad=(0, 0)):

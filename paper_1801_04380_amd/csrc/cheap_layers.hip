@@ -173,6 +173,95 @@ __device__ inline float wave_sum(float v)
     return v;
 }
 
+// Raw vectors of VB bytes of T, unpacked to / packed from floats.
+template <int VB> struct RawVec;
+template <> struct RawVec<16> { typedef uint4 type; };
+template <> struct RawVec<8> { typedef uint2 type; };
+template <> struct RawVec<4> { typedef uint32_t type; };
+
+template <typename T, int VB> __device__ inline void unpack(const typename RawVec<VB>::type &v, float (&f)[VB / sizeof(T)])
+{
+    const uint32_t *w = reinterpret_cast<const uint32_t *>(&v);
+    if (sizeof(T) == 2) {
+#pragma unroll
+        for (int i = 0; i < VB / 4; ++i) {
+            f[2 * i] = __uint_as_float(w[i] << 16);
+            f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < VB / 4; ++i) f[i] = __uint_as_float(w[i]);
+    }
+}
+
+template <typename T, int VB> __device__ inline typename RawVec<VB>::type pack(const float (&f)[VB / sizeof(T)])
+{
+    typename RawVec<VB>::type v;
+    uint32_t *w = reinterpret_cast<uint32_t *>(&v);
+    if (sizeof(T) == 2) {
+#pragma unroll
+        for (int i = 0; i < VB / 4; ++i)
+            w[i] = (uint32_t)f32_to_bf16(f[2 * i]) | ((uint32_t)f32_to_bf16(f[2 * i + 1]) << 16);
+    } else {
+#pragma unroll
+        for (int i = 0; i < VB / 4; ++i) w[i] = __float_as_uint(f[i]);
+    }
+    return v;
+}
+
+// Where a backward pass takes the gradient dy from: the tensor itself, or -- when a 2x2 / stride-2
+// max-pool (no padding) follows the layer -- the pooled gradient g [N*C][H/2][W/2] and the winners'
+// positions idx, from which each element's gradient is formed on the fly exactly as the pool
+// backward would have stored it: g of its window if the element is the window's winner, else 0.
+template <typename T> struct GradSrc {
+    const T *dy;            // the gradient itself, or nullptr
+    const T *g;             // pooled gradient
+    const int32_t *idx;     // position h*W + v of each window's winner inside its input plane
+    int W, Q, HW, PQ;
+};
+
+// Gradient of element e of plane pl.
+template <typename T> __device__ inline float grad_one(const GradSrc<T> &gs, size_t pl, int e)
+{
+    if (gs.dy) return ld<T>(gs.dy + pl * gs.HW + e);
+    const int h = e / gs.W, w = e - h * gs.W;
+    const size_t wi = pl * gs.PQ + (size_t)(h >> 1) * gs.Q + (w >> 1);
+    return gs.idx[wi] == e ? ld<T>(gs.g + wi) : 0.f;
+}
+
+// Gradients of the VB / sizeof(T) elements from element e (a multiple of that count within the
+// plane's 16-byte grid, hence even).  Where a vector cannot cross a row (W a multiple of the
+// vector length) its windows' entries are one aligned vector of g and one of idx.
+template <typename T, int VB>
+__device__ inline void grad_vec(const GradSrc<T> &gs, size_t pl, int e, float (&gr)[VB / sizeof(T)])
+{
+    constexpr int VE = VB / sizeof(T);
+    if (gs.dy) {
+        unpack<T, VB>(*reinterpret_cast<const typename RawVec<VB>::type *>(gs.dy + pl * gs.HW + e), gr);
+        return;
+    }
+    if (gs.W % VE == 0) {
+        const int h = e / gs.W, w = e - h * gs.W;
+        const size_t wi = pl * gs.PQ + (size_t)(h >> 1) * gs.Q + (w >> 1);
+        float gw[VE / 2];
+        unpack<T, VB / 2>(*reinterpret_cast<const typename RawVec<VB / 2>::type *>(gs.g + wi), gw);
+        const typename RawVec<2 * VE>::type iv = *reinterpret_cast<const typename RawVec<2 * VE>::type *>(gs.idx + wi);
+        const int32_t *iw = reinterpret_cast<const int32_t *>(&iv);
+#pragma unroll
+        for (int k = 0; k < VE; ++k) gr[k] = iw[k >> 1] == e + k ? gw[k >> 1] : 0.f;
+    } else {
+#pragma unroll
+        for (int k = 0; k < VE; k += 2) {
+            const int ee = e + k, h = ee / gs.W, w = ee - h * gs.W;
+            const size_t wi = pl * gs.PQ + (size_t)(h >> 1) * gs.Q + (w >> 1);
+            const int win = gs.idx[wi];
+            const float g = ld<T>(gs.g + wi);
+            gr[k] = win == ee ? g : 0.f;
+            gr[k + 1] = win == ee + 1 ? g : 0.f;
+        }
+    }
+}
+
 // The activation that may follow BN in the same pass: ReLU as in relu_fwd_kernel (0 unless v > 0).
 __device__ inline float act(float v, int relu) { return (!relu || v > 0.f) ? v : 0.f; }
 
@@ -300,7 +389,7 @@ bn_apply_kernel(const T *__restrict__ x, T *__restrict__ y, const float *__restr
 // Backward pass 1: per (channel, slice) partial sums of dy and dy*(x - mean).
 template <typename T>
 __global__ void __launch_bounds__(256)
-bn_bwd_reduce_kernel(const T *__restrict__ x, const T *__restrict__ dy, const float *__restrict__ gamma,
+bn_bwd_reduce_kernel(const T *__restrict__ x, const GradSrc<T> gs, const float *__restrict__ gamma,
                      const float *__restrict__ beta, const float *__restrict__ mean,
                      const float *__restrict__ invstd, float *__restrict__ part, int N, int C, int HW, Slices sl)
 {
@@ -315,13 +404,14 @@ bn_bwd_reduce_kernel(const T *__restrict__ x, const T *__restrict__ dy, const fl
         const int n = seg / sl.nseg_plane, k = seg - n * sl.nseg_plane;
         const int e0 = k * SEG, len = min(SEG, HW - e0);
         const size_t base = ((size_t)n * C + c) * HW + e0;
-        const T *p = x + base, *gp = dy + base;
+        const T *p = x + base;
+        const size_t pl = (size_t)n * C + c;
         walk_segment<T>(
             p, len, lane,
             [&](int off) {
                 float f[V], gr[V];
                 Vec<T>::load(p + off, f);
-                Vec<T>::load(gp + off, gr);
+                grad_vec<T, 16>(gs, pl, e0 + off, gr);
                 if (relu) {
 #pragma unroll
                     for (int i = 0; i < V; ++i) gr[i] = relu_passes<T>(bn_affine(f[i], mu, ga, gb)) ? gr[i] : 0.f;
@@ -334,7 +424,7 @@ bn_bwd_reduce_kernel(const T *__restrict__ x, const T *__restrict__ dy, const fl
             },
             [&](int off) {
                 const float f = ld<T>(p + off);
-                float gr = ld<T>(gp + off);
+                float gr = grad_one<T>(gs, pl, e0 + off);
                 if (relu && !relu_passes<T>(bn_affine(f, mu, ga, gb))) gr = 0.f;
                 s1 += gr;
                 s2 += gr * (f - mu);
@@ -376,7 +466,7 @@ bn_bwd_final_kernel(const float *__restrict__ part, const float *__restrict__ in
 // Backward pass 3: dx = gamma*invstd * (dy - dbeta/M - xhat*dgamma/M).
 template <typename T>
 __global__ void __launch_bounds__(256)
-bn_bwd_apply_kernel(const T *__restrict__ x, const T *__restrict__ dy, const float *__restrict__ beta,
+bn_bwd_apply_kernel(const T *__restrict__ x, const GradSrc<T> gs, const float *__restrict__ beta,
                     T *__restrict__ dx, const float *__restrict__ gamma, const float *__restrict__ mean,
                     const float *__restrict__ invstd, const float *__restrict__ dgamma,
                     const float *__restrict__ dbeta, int N, int C, int HW, Slices sl)
@@ -395,14 +485,15 @@ bn_bwd_apply_kernel(const T *__restrict__ x, const T *__restrict__ dy, const flo
         const int n = seg / sl.nseg_plane, k = seg - n * sl.nseg_plane;
         const int e0 = k * SEG, len = min(SEG, HW - e0);
         const size_t base = ((size_t)n * C + c) * HW + e0;
-        const T *p = x + base, *gp = dy + base;
+        const T *p = x + base;
+        const size_t pl = (size_t)n * C + c;
         T *o = dx + base;
         walk_segment<T>(
             p, len, lane,
             [&](int off) {
                 float f[V], gr[V];
                 Vec<T>::load(p + off, f);
-                Vec<T>::load(gp + off, gr);
+                grad_vec<T, 16>(gs, pl, e0 + off, gr);
                 if (relu) {
 #pragma unroll
                     for (int i = 0; i < V; ++i) gr[i] = relu_passes<T>(bn_affine(f[i], mu, k1, gb)) ? gr[i] : 0.f;
@@ -413,7 +504,7 @@ bn_bwd_apply_kernel(const T *__restrict__ x, const T *__restrict__ dy, const flo
             },
             [&](int off) {
                 const float f = ld<T>(p + off);
-                float gr = ld<T>(gp + off);
+                float gr = grad_one<T>(gs, pl, e0 + off);
                 if (relu && !relu_passes<T>(bn_affine(f, mu, k1, gb))) gr = 0.f;
                 st(o + off, k1 * (gr - kb - (f - mu) * kg));
             });
@@ -426,38 +517,64 @@ bn_bwd_apply_kernel(const T *__restrict__ x, const T *__restrict__ dy, const flo
 // (and dy) are read once and y (dx) written once.  The statistics are two-pass sums over
 // the registers, reduced in a fixed order (wavefront butterflies, then the 16 wavefront
 // sums in index order), so they are the same from run to run.
-template <int VB> struct RawVec;
-template <> struct RawVec<16> { typedef uint4 type; };
-template <> struct RawVec<8> { typedef uint2 type; };
-
-template <typename T, int VB> __device__ inline void unpack(const typename RawVec<VB>::type &v, float (&f)[VB / sizeof(T)])
+// BN + ReLU + 2x2 / stride-2 max-pool (no padding) of one unit: VB bytes of input row 2p and the
+// same columns of row 2p + 1 give VB / (2 sizeof(T)) windows.  The activations are rounded to
+// the storage type before they are compared, so values, winners and ties (first maximum in
+// row-major window order) are those of the pool run on the stored BN + ReLU output.
+template <typename T, int VB>
+__device__ inline void bn_relu_pool2_unit(const T *__restrict__ x, T *__restrict__ pooled, int32_t *__restrict__ idx,
+                                          int u, int c, int C, int H, int W, float mu, float a, float b)
 {
-    const uint32_t *w = reinterpret_cast<const uint32_t *>(&v);
-    if (sizeof(T) == 2) {
+    constexpr int VE = VB / sizeof(T);
+    typedef typename RawVec<VB>::type VT;
+    const int vpr = W / VE, P = H >> 1, Q = W >> 1, upp = P * vpr;
+    const int n = u / upp, r = u - n * upp, p = r / vpr, qv = r - p * vpr;
+    const size_t pl = (size_t)n * C + c;
+    const T *r0 = x + (pl * H + 2 * p) * W + qv * VE;
+    float fa[VE], fb[VE];
+    unpack<T, VB>(*reinterpret_cast<const VT *>(r0), fa);
+    unpack<T, VB>(*reinterpret_cast<const VT *>(r0 + W), fb);
 #pragma unroll
-        for (int i = 0; i < VB / 4; ++i) {
-            f[2 * i] = __uint_as_float(w[i] << 16);
-            f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
-        }
-    } else {
-#pragma unroll
-        for (int i = 0; i < VB / 4; ++i) f[i] = __uint_as_float(w[i]);
+    for (int k = 0; k < VE; ++k) {
+        fa[k] = act(bn_affine(fa[k], mu, a, b), 1);
+        fb[k] = act(bn_affine(fb[k], mu, a, b), 1);
     }
+    unpack<T, VB>(pack<T, VB>(fa), fa);   // the values as stored
+    unpack<T, VB>(pack<T, VB>(fb), fb);
+    const int base = 2 * p * W + qv * VE;
+    float out[VE / 2];
+    typename RawVec<2 * VE>::type oi;
+    int32_t *oiw = reinterpret_cast<int32_t *>(&oi);
+#pragma unroll
+    for (int j = 0; j < VE / 2; ++j) {
+        float bv = fa[2 * j];
+        int best = base + 2 * j;
+        if (fa[2 * j + 1] > bv) { bv = fa[2 * j + 1]; best = base + 2 * j + 1; }
+        if (fb[2 * j] > bv) { bv = fb[2 * j]; best = base + W + 2 * j; }
+        if (fb[2 * j + 1] > bv) { bv = fb[2 * j + 1]; best = base + W + 2 * j + 1; }
+        out[j] = bv;
+        oiw[j] = best;
+    }
+    const size_t o = (pl * P + p) * Q + qv * (VE / 2);
+    *reinterpret_cast<typename RawVec<VB / 2>::type *>(pooled + o) = pack<T, VB / 2>(out);   // exact: stored values
+    *reinterpret_cast<typename RawVec<2 * VE>::type *>(idx + o) = oi;
 }
 
-template <typename T, int VB> __device__ inline typename RawVec<VB>::type pack(const float (&f)[VB / sizeof(T)])
+// Pass 3 of the forward pass when the pool follows: one thread per unit, back to front as in
+// bn_apply_kernel; the full-resolution activation is never written.
+template <typename T, int VB>
+__global__ void __launch_bounds__(256)
+bn_relu_pool2_apply_kernel(const T *__restrict__ x, T *__restrict__ pooled, int32_t *__restrict__ idx,
+                           const float *__restrict__ gamma, const float *__restrict__ beta,
+                           const float *__restrict__ mean, const float *__restrict__ invstd, int C, int H, int W,
+                           int units)
 {
-    typename RawVec<VB>::type v;
-    uint32_t *w = reinterpret_cast<uint32_t *>(&v);
-    if (sizeof(T) == 2) {
-#pragma unroll
-        for (int i = 0; i < VB / 4; ++i)
-            w[i] = (uint32_t)f32_to_bf16(f[2 * i]) | ((uint32_t)f32_to_bf16(f[2 * i + 1]) << 16);
-    } else {
-#pragma unroll
-        for (int i = 0; i < VB / 4; ++i) w[i] = __float_as_uint(f[i]);
-    }
-    return v;
+    const int c = gridDim.x - 1 - blockIdx.x;
+    const float mu = mean[c], a = gamma[c] * invstd[c], b = beta[c];
+    const int u0 = (gridDim.y - 1 - blockIdx.y) * 256 + threadIdx.x, step = gridDim.y * 256;
+    if (u0 >= units) return;
+    for (int u = u0 + (units - 1 - u0) / step * step; u >= u0; u -= step)
+        bn_relu_pool2_unit<T, VB>(x, pooled, idx, u, c, C, H, W, mu, a, b);
 }
 
 // Sum over the 1024 threads of a workgroup, the same value in every thread.
@@ -473,11 +590,17 @@ __device__ inline float block_sum_1024(float v, float *red)
     return s;
 }
 
-template <typename T, int VB, int NVMAX>
+// PVB != 0: BN + ReLU + 2x2 max-pool.  The statistics are taken exactly as without the pool (same
+// element-to-thread mapping, same order); the last phase then reads the channel a second time in
+// units of PVB bytes of a row pair -- the workgroup has just streamed it, so it comes from the
+// caches -- and writes the pooled values and indices only (y is not touched; H, W as the pool
+// sees them).
+template <typename T, int VB, int NVMAX, int PVB>
 __global__ void __launch_bounds__(1024)
 bn_fwd_fused_kernel(const T *__restrict__ x, T *__restrict__ y, const float *__restrict__ gamma,
                     const float *__restrict__ beta, float *__restrict__ mean, float *__restrict__ invstd,
-                    int N, int C, int HW, float eps, int relu)
+                    int N, int C, int HW, float eps, int relu, T *__restrict__ pooled, int32_t *__restrict__ idx,
+                    int H, int W)
 {
     constexpr int VE = VB / sizeof(T);
     typedef typename RawVec<VB>::type VT;
@@ -514,6 +637,12 @@ bn_fwd_fused_kernel(const T *__restrict__ x, T *__restrict__ y, const float *__r
     const float is = 1.f / sqrtf(var + eps);
     if (tid == 0) { mean[c] = mu; invstd[c] = is; }
     const float a = gamma[c] * is, b = beta[c];
+    if (PVB != 0) {
+        constexpr int PB = PVB ? PVB : 16;
+        const int units = N * (H >> 1) * (W / (PB / (int)sizeof(T)));
+        for (int u = tid; u < units; u += 1024) bn_relu_pool2_unit<T, PB>(x, pooled, idx, u, c, C, H, W, mu, a, b);
+        return;
+    }
 #pragma unroll
     for (int j = 0; j < NVMAX; ++j) {
         const int i = tid + j * 1024;
@@ -530,7 +659,7 @@ bn_fwd_fused_kernel(const T *__restrict__ x, T *__restrict__ y, const float *__r
 
 template <typename T, int VB, int NVMAX>
 __global__ void __launch_bounds__(1024)
-bn_bwd_fused_kernel(const T *__restrict__ x, const T *__restrict__ dy, const float *__restrict__ beta,
+bn_bwd_fused_kernel(const T *__restrict__ x, const GradSrc<T> gs, const float *__restrict__ beta,
                     T *__restrict__ dx, const float *__restrict__ gamma, const float *__restrict__ mean,
                     const float *__restrict__ invstd, float *__restrict__ dgamma, float *__restrict__ dbeta,
                     int N, int C, int HW)
@@ -552,15 +681,19 @@ bn_bwd_fused_kernel(const T *__restrict__ x, const T *__restrict__ dy, const flo
             const int n = i / vpp, e = i - n * vpp;
             const size_t off = ((size_t)n * C + c) * HW + (size_t)e * VE;
             xv[j] = *reinterpret_cast<const VT *>(x + off);
-            gv[j] = *reinterpret_cast<const VT *>(dy + off);
             float f[VE], gr[VE];
             unpack<T, VB>(xv[j], f);
-            unpack<T, VB>(gv[j], gr);
+            if (gs.dy) {
+                gv[j] = *reinterpret_cast<const VT *>(gs.dy + off);
+                unpack<T, VB>(gv[j], gr);
+            } else {
+                grad_vec<T, VB>(gs, (size_t)n * C + c, e * VE, gr);
+            }
             if (relu) {   // the gradient that passes the ReLU is what is kept in registers
 #pragma unroll
                 for (int k = 0; k < VE; ++k) gr[k] = relu_passes<T>(bn_affine(f[k], mu, ga, gb)) ? gr[k] : 0.f;
-                gv[j] = pack<T, VB>(gr);
             }
+            if (relu || !gs.dy) gv[j] = pack<T, VB>(gr);
 #pragma unroll
             for (int k = 0; k < VE; ++k) {
                 s1 += gr[k];
@@ -905,11 +1038,13 @@ hipError_t launch_bn_fwd(const void *x, const float *gamma, const float *beta, v
             return by_dtype(bf16, [&](auto *tag) {
                 typedef typename std::remove_pointer<decltype(tag)>::type T;
                 if (vb == 16)
-                    hipLaunchKernelGGL((bn_fwd_fused_kernel<T, 16, BN_FUSED_NV>), dim3(C), dim3(1024), 0, s, (const T *)x,
-                                       (T *)y, gamma, beta, mean, invstd, N, C, HW, eps, relu);
+                    hipLaunchKernelGGL((bn_fwd_fused_kernel<T, 16, BN_FUSED_NV, 0>), dim3(C), dim3(1024), 0, s, (const T *)x,
+                                       (T *)y, gamma, beta, mean, invstd, N, C, HW, eps, relu, (T *)nullptr,
+                                       (int32_t *)nullptr, 0, 0);
                 else
-                    hipLaunchKernelGGL((bn_fwd_fused_kernel<T, 8, BN_FUSED_NV>), dim3(C), dim3(1024), 0, s, (const T *)x,
-                                       (T *)y, gamma, beta, mean, invstd, N, C, HW, eps, relu);
+                    hipLaunchKernelGGL((bn_fwd_fused_kernel<T, 8, BN_FUSED_NV, 0>), dim3(C), dim3(1024), 0, s, (const T *)x,
+                                       (T *)y, gamma, beta, mean, invstd, N, C, HW, eps, relu, (T *)nullptr,
+                                       (int32_t *)nullptr, 0, 0);
             });
     }
     // y is dead until pass 3, so it holds the per-slice partial sums meanwhile
@@ -926,11 +1061,63 @@ hipError_t launch_bn_fwd(const void *x, const float *gamma, const float *beta, v
     });
 }
 
-hipError_t launch_bn_bwd(const void *x, const void *dy, const float *relu_beta, const float *gamma, const float *mean,
-                         const float *invstd, void *dx, float *dgamma, float *dbeta, int N, int C, int HW,
-                         int bf16, hipStream_t s)
+int bn_relu_pool2_vb(int W, int bf16)
+{
+    const int esz = bf16 ? 2 : 4;
+    return W % (16 / esz) == 0 ? 16 : W % (8 / esz) == 0 ? 8 : 0;
+}
+
+hipError_t launch_bn_relu_pool2_fwd(const void *x, const float *gamma, const float *beta, void *pooled, int32_t *idx,
+                                    float *mean, float *invstd, int N, int C, int H, int W, float eps, int bf16,
+                                    hipStream_t s)
 {
     const size_t esz = bf16 ? 2 : 4;
+    const int HW = H * W, pvb = bn_relu_pool2_vb(W, bf16);
+    if (pvb == 0 || (H & 1)) return hipErrorInvalidValue;
+    // the statistics come from the very kernels launch_bn_fwd picks for this shape
+    const int vb = bf16 ? bn_fused_vb<bf16_t>(x, nullptr, nullptr, N, HW) : bn_fused_vb<float>(x, nullptr, nullptr, N, HW);
+    if (vb != 0 && vb != 16) return hipErrorInvalidValue;
+    if (vb)
+        return by_dtype(bf16, [&](auto *tag) {
+            typedef typename std::remove_pointer<decltype(tag)>::type T;
+#define SN_POOL_FUSED(VB_, PVB_)                                                                                  \
+    hipLaunchKernelGGL((bn_fwd_fused_kernel<T, VB_, BN_FUSED_NV, PVB_>), dim3(C), dim3(1024), 0, s, (const T *)x, \
+                       (T *)nullptr, gamma, beta, mean, invstd, N, C, HW, eps, 1, (T *)pooled, idx, H, W)
+            // H even and W a multiple of half a 16-byte vector make H*W a multiple of the whole one
+            if (pvb == 16) SN_POOL_FUSED(16, 16);
+            else SN_POOL_FUSED(16, 8);
+#undef SN_POOL_FUSED
+        });
+    // idx is dead until the last pass, so it holds the per-slice partial sums meanwhile (launch_bn_fwd
+    // keeps them in y; the slices are the same)
+    const Slices sl = make_slices(N, C, HW, (size_t)N * C * HW * esz);
+    if ((size_t)C * sl.nslice * 2 * sizeof(float) > (size_t)N * C * (HW / 4) * sizeof(int32_t)) return hipErrorInvalidValue;
+    float *part = reinterpret_cast<float *>(idx);
+    const int units = N * (H / 2) * (W / (pvb / (int)esz));
+    long long want = (4096 + C - 1) / C, most = (units + 255) / 256;
+    if (want > most) want = most;
+    if (want > 65535) want = 65535;
+    return by_dtype(bf16, [&](auto *tag) {
+        typedef typename std::remove_pointer<decltype(tag)>::type T;
+        dim3 grid(C, sl.nslice), block(256), pgrid(C, (unsigned)want);
+        hipLaunchKernelGGL(bn_stats_kernel<T>, grid, block, 0, s, (const T *)x, part, N, C, HW, sl);
+        hipLaunchKernelGGL(bn_stats_final_kernel<T>, dim3(C), dim3(64), 0, s, (const T *)x, part, mean, invstd,
+                           N, HW, sl.nslice, eps);
+        if (pvb == 16)
+            hipLaunchKernelGGL((bn_relu_pool2_apply_kernel<T, 16>), pgrid, block, 0, s, (const T *)x, (T *)pooled, idx,
+                               gamma, beta, mean, invstd, C, H, W, units);
+        else
+            hipLaunchKernelGGL((bn_relu_pool2_apply_kernel<T, 8>), pgrid, block, 0, s, (const T *)x, (T *)pooled, idx,
+                               gamma, beta, mean, invstd, C, H, W, units);
+    });
+}
+
+hipError_t launch_bn_bwd(const void *x, const void *dy, const float *relu_beta, const float *gamma, const float *mean,
+                         const float *invstd, void *dx, float *dgamma, float *dbeta, int N, int C, int HW,
+                         int bf16, hipStream_t s, const void *pool_g, const int32_t *pool_idx, int pool_W)
+{
+    const size_t esz = bf16 ? 2 : 4;
+    if (!dy && (!pool_g || !pool_idx || pool_W < 2 || (pool_W & 1) || HW % (2 * pool_W) != 0)) return hipErrorInvalidValue;
     if ((size_t)N * HW * esz < 2 * sizeof(float))
         return by_dtype(bf16, [&](auto *tag) {
             typedef typename std::remove_pointer<decltype(tag)>::type T;
@@ -942,12 +1129,13 @@ hipError_t launch_bn_bwd(const void *x, const void *dy, const float *relu_beta, 
         if (vb)
             return by_dtype(bf16, [&](auto *tag) {
                 typedef typename std::remove_pointer<decltype(tag)>::type T;
+                const GradSrc<T> gs{(const T *)dy, (const T *)pool_g, pool_idx, pool_W, pool_W / 2, HW, HW / 4};
                 if (vb == 16)
                     hipLaunchKernelGGL((bn_bwd_fused_kernel<T, 16, BN_FUSED_NV>), dim3(C), dim3(1024), 0, s, (const T *)x,
-                                       (const T *)dy, relu_beta, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);
+                                       gs, relu_beta, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);
                 else
                     hipLaunchKernelGGL((bn_bwd_fused_kernel<T, 8, BN_FUSED_NV>), dim3(C), dim3(1024), 0, s, (const T *)x,
-                                       (const T *)dy, relu_beta, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);
+                                       gs, relu_beta, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);
             });
     }
     const Slices sl = make_slices(N, C, HW, (size_t)N * C * HW * esz);
@@ -955,11 +1143,12 @@ hipError_t launch_bn_bwd(const void *x, const void *dy, const float *relu_beta, 
     return by_dtype(bf16, [&](auto *tag) {
         typedef typename std::remove_pointer<decltype(tag)>::type T;
         dim3 grid(C, sl.nslice), block(256);
-        hipLaunchKernelGGL(bn_bwd_reduce_kernel<T>, grid, block, 0, s, (const T *)x, (const T *)dy, gamma, relu_beta,
+        const GradSrc<T> gs{(const T *)dy, (const T *)pool_g, pool_idx, pool_W, pool_W / 2, HW, HW / 4};
+        hipLaunchKernelGGL(bn_bwd_reduce_kernel<T>, grid, block, 0, s, (const T *)x, gs, gamma, relu_beta,
                            mean, invstd, part, N, C, HW, sl);
         hipLaunchKernelGGL(bn_bwd_final_kernel, dim3(C), dim3(64), 0, s, part, invstd, dgamma, dbeta,
                            sl.nslice);
-        hipLaunchKernelGGL(bn_bwd_apply_kernel<T>, grid, block, 0, s, (const T *)x, (const T *)dy, relu_beta,
+        hipLaunchKernelGGL(bn_bwd_apply_kernel<T>, grid, block, 0, s, (const T *)x, gs, relu_beta,
                            (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW, sl);
     });
 }

@@ -501,6 +501,50 @@ sn_status sn_bn_relu_fwd(const void *x, const float *gamma, const float *beta, v
     return bn_fwd_common(x, gamma, beta, y, save_mean, save_invstd, N, C, H, W, eps, dtype, 1, stream);
 }
 
+// The shapes the BN + ReLU + 2x2 pool calls take.
+static sn_status check_pool2_pair(int N, int C, int H, int W, int dtype)
+{
+    sn_status s = check_cheap(N, C, H, W, dtype);
+    if (s != SN_OK) return s;
+    if ((H & 1) || (W & 1) || bn_relu_pool2_vb(W, dtype == SN_BF16) == 0) return SN_ERR_UNSUPPORTED;
+    if (C > 65535 * 32) return SN_ERR_UNSUPPORTED;
+    return SN_OK;
+}
+
+sn_status sn_bn_relu_pool2_fwd(const void *x, const float *gamma, const float *beta, void *pooled, int32_t *idx,
+                               float *save_mean, float *save_invstd, int N, int C, int H, int W, float eps,
+                               sn_dtype dtype, sn_stream stream)
+{
+    sn_status s = check_pool2_pair(N, C, H, W, dtype);
+    if (s != SN_OK) return s;
+    if (!x || !gamma || !beta || !pooled || !idx || !save_mean || !save_invstd || x == pooled ||
+        x == static_cast<const void *>(idx) || pooled == static_cast<void *>(idx))
+        return SN_ERR_BAD_ARG;
+    if (!aligned(x, 16) || !aligned(pooled, 16) || !aligned(idx, 16) || !aligned(gamma, 4) || !aligned(beta, 4) ||
+        !aligned(save_mean, 4) || !aligned(save_invstd, 4) || !(eps >= 0.f))
+        return SN_ERR_BAD_ARG;
+    return launch_status(launch_bn_relu_pool2_fwd(x, gamma, beta, pooled, idx, save_mean, save_invstd, N, C, H, W, eps,
+                                                  dtype == SN_BF16, static_cast<hipStream_t>(stream)));
+}
+
+sn_status sn_bn_relu_pool2_bwd(const void *x, const void *dpooled, const int32_t *idx, const float *gamma,
+                               const float *beta, const float *save_mean, const float *save_invstd, void *dx,
+                               float *dgamma, float *dbeta, int N, int C, int H, int W, sn_dtype dtype,
+                               sn_stream stream)
+{
+    sn_status s = check_pool2_pair(N, C, H, W, dtype);
+    if (s != SN_OK) return s;
+    if (!x || !dpooled || !idx || !gamma || !beta || !save_mean || !save_invstd || !dx || !dgamma || !dbeta ||
+        dx == x || dx == dpooled || dx == static_cast<const void *>(idx))
+        return SN_ERR_BAD_ARG;
+    if (!aligned(x, 16) || !aligned(dpooled, 16) || !aligned(idx, 16) || !aligned(dx, 16) || !aligned(gamma, 4) ||
+        !aligned(beta, 4) || !aligned(save_mean, 4) || !aligned(save_invstd, 4) || !aligned(dgamma, 4) ||
+        !aligned(dbeta, 4))
+        return SN_ERR_BAD_ARG;
+    return launch_status(launch_bn_bwd(x, nullptr, beta, gamma, save_mean, save_invstd, dx, dgamma, dbeta, N, C, H * W,
+                                       dtype == SN_BF16, static_cast<hipStream_t>(stream), dpooled, idx, W));
+}
+
 static sn_status bn_bwd_common(const void *x, const void *dy, const float *relu_beta, const float *gamma,
                                const float *save_mean, const float *save_invstd, void *dx, float *dgamma,
                                float *dbeta, int N, int C, int H, int W, sn_dtype dtype, sn_stream stream)

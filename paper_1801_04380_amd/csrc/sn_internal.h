@@ -91,7 +91,17 @@ hipError_t launch_bn_fwd(const void *x, const float *gamma, const float *beta, v
 // ReLU backward gate, which is re-derived from x (the forward pass's own expression) and not read.
 hipError_t launch_bn_bwd(const void *x, const void *dy, const float *relu_beta, const float *gamma, const float *mean,
                          const float *invstd, void *dx, float *dgamma, float *dbeta, int N, int C,
-                         int HW, int bf16, hipStream_t st);
+                         int HW, int bf16, hipStream_t st, const void *pool_g = nullptr,
+                         const int32_t *pool_idx = nullptr, int pool_W = 0);
+// BN + ReLU + 2x2 / stride-2 max-pool without padding, H and W even: the statistics of launch_bn_fwd,
+// then pooled values and winner indices as launch_maxpool_fwd gives them on the BN + ReLU output,
+// which is not written.  idx doubles as scratch.  bn_relu_pool2_vb: bytes per access along a row,
+// 0 if W does not allow any.  Its backward is launch_bn_bwd with dy == nullptr and the pooled
+// gradient, the indices and W in the pool_* arguments (relu_beta set).
+int bn_relu_pool2_vb(int W, int bf16);
+hipError_t launch_bn_relu_pool2_fwd(const void *x, const float *gamma, const float *beta, void *pooled, int32_t *idx,
+                                    float *mean, float *invstd, int N, int C, int H, int W, float eps, int bf16,
+                                    hipStream_t st);
 hipError_t launch_maxpool_fwd(const void *x, void *y, int32_t *idx, int NC, int H, int W, int P, int Q,
                               int kh, int kw, int sh, int sw, int ph, int pw, int bf16, hipStream_t st);
 hipError_t launch_maxpool_bwd(const void *dy, const int32_t *idx, void *dx, int NC, int H, int W, int P,

@@ -70,6 +70,14 @@ def test_bad_arguments_are_refused_before_any_launch():
     assert lib.sn_bn_relu_bwd(one, two, one, None, one, one, ctypes.c_void_p(768), one, one, 1, 1, 1, 1, 0, None) == 1
     assert lib.sn_bn_relu_bwd(one, two, one, one, one, one, two, one, one, 1, 1, 1, 1, 0, None) == 1
     assert lib.sn_maxpool_fwd(one, one, one, 1, 1, 4, 4, 2, 2, 2, 2, 2, 0, 0, None) == 1  # pad >= window
+    # BN + ReLU + 2x2 pool: odd sizes and rows too short for a vector access are for the separate calls
+    three = ctypes.c_void_p(768)
+    assert lib.sn_bn_relu_pool2_fwd(one, one, one, two, three, one, one, 1, 1, 5, 8, 1e-5, 1, None) == 2
+    assert lib.sn_bn_relu_pool2_fwd(one, one, one, two, three, one, one, 1, 1, 14, 14, 1e-5, 1, None) == 2
+    assert lib.sn_bn_relu_pool2_fwd(one, one, one, two, two, one, one, 1, 1, 4, 8, 1e-5, 1, None) == 1   # pooled aliases idx
+    assert lib.sn_bn_relu_pool2_fwd(one, one, one, two, None, one, one, 1, 1, 4, 8, 1e-5, 1, None) == 1
+    assert lib.sn_bn_relu_pool2_bwd(one, two, three, one, one, one, one, one, one, one, 1, 1, 4, 8, 1, None) == 1  # dx aliases x
+    assert lib.sn_bn_relu_pool2_bwd(one, two, three, one, one, one, one, ctypes.c_void_p(1024), one, one, 1, 1, 4, 6, 1, None) == 2
 
 
 def test_workspace_query():

@@ -155,6 +155,80 @@ def test_bn_relu_bwd_gate_edges(N, H, dtype):
     assert float(db_ref[4]) != 0.0
 
 
+# one-pass statistics with 16- and 8-byte row accesses, the three-kernel path with both, a single
+# window per plane, rows of one access, a wide plane
+POOL2_PAIR_SHAPES = [(4, 16, 16, 16), (2, 5, 4, 12), (40, 4, 64, 64), (40, 3, 56, 60), (3, 7, 2, 4),
+                     (2, 3, 6, 8), (32, 6, 56, 56), (2, 2, 2, 304), (36, 2, 56, 56)]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", POOL2_PAIR_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_bn_relu_pool2(shape, dtype):
+    """BN + ReLU + 2x2 pool in one call, forward and backward: bit-identical to the separate calls
+    (themselves checked against the oracle above), and the chain against the oracle's."""
+    N, C, H, W = shape
+    seed = N * 1000 + C * 10 + H
+    x = wl.activation(shape, "f32", seed, scale=1.0)
+    x = (x * torch.linspace(0.5, 3.0, C).view(1, C, 1, 1) + torch.linspace(-2.0, 5.0, C).view(1, C, 1, 1))
+    x = (torch.round(x * 8.0) / 8.0).to(DT[dtype])          # coarse values: equal maxima inside windows
+    gamma, beta = wl.bn_params(C, seed)
+    dp = wl.activation((N, C, H // 2, W // 2), dtype, seed + 1)
+    xd, gd, bd, dpd = x.cuda(), gamma.cuda(), beta.cuda(), dp.cuda()
+    new = lambda *s, dt=torch.float32: torch.empty(*s, dtype=dt, device="cuda")
+
+    # the separate calls
+    a, mean, invstd = torch.empty_like(xd), new(C), new(C)
+    sn.sn_bn_relu_fwd(xd, gd, bd, a, mean, invstd)
+    pooled_ref = torch.empty_like(dpd)
+    idx_ref = new(N, C, H // 2, W // 2, dt=torch.int32)
+    sn.sn_maxpool_fwd(a, pooled_ref, idx_ref, (2, 2), (2, 2))
+    g = torch.empty_like(xd)
+    sn.sn_maxpool_bwd(dpd, idx_ref, g, (2, 2), (2, 2))
+    dx_ref, dg_ref, db_ref = torch.empty_like(xd), new(C), new(C)
+    sn.sn_bn_relu_bwd(xd, g, gd, bd, mean, invstd, dx_ref, dg_ref, db_ref)
+
+    # the single calls
+    pooled = torch.full_like(dpd, float("nan"))
+    idx = torch.full((N, C, H // 2, W // 2), -7, dtype=torch.int32, device="cuda")
+    mean2, invstd2 = new(C), new(C)
+    sn.sn_bn_relu_pool2_fwd(xd, gd, bd, pooled, idx, mean2, invstd2)
+    dx, dg, db = torch.full_like(xd, float("nan")), new(C), new(C)
+    sn.sn_bn_relu_pool2_bwd(xd, dpd, idx, gd, bd, mean2, invstd2, dx, dg, db)
+    torch.cuda.synchronize()
+    assert torch.equal(mean2, mean) and torch.equal(invstd2, invstd)
+    assert torch.equal(idx, idx_ref) and torch.equal(pooled, pooled_ref)
+    assert torch.equal(db, db_ref) and torch.equal(dg, dg_ref) and torch.equal(dx, dx_ref)
+
+    # the chain against the oracle: pooling and routing by the GPU's (checked) indices are exact on
+    # the stored activations, the BN arithmetic is within the storage type's tolerance
+    tol = TOL[dtype]
+    yo, _, _ = oracle.bn_fwd(f64(x), f64(gamma), f64(beta), 1e-5)
+    ao = oracle.relu_fwd(yo)
+    po, _ = oracle.maxpool_fwd(ao, (2, 2), (2, 2))
+    assert rel_l2(f64(pooled), po) <= tol
+    a_st, io = oracle.maxpool_fwd(f64(a), (2, 2), (2, 2))
+    assert np.array_equal(idx.cpu().numpy(), io) and np.array_equal(f64(pooled), a_st)
+    go = oracle.relu_bwd(f64(a), oracle.maxpool_bwd(f64(dp), io, shape))
+    dxo, dgo, dbo = oracle.bn_bwd(f64(x), go, f64(gamma), f64(mean), f64(invstd))
+    assert rel_l2(f64(dg), dgo) <= 1e-5 and rel_l2(f64(db), dbo) <= 1e-5
+    assert rel_l2(f64(dx), dxo) <= tol
+
+
+def test_bn_relu_pool2_unsupported():
+    """Shapes the single call does not take are refused, not mishandled."""
+    x = torch.zeros(2, 2, 14, 14, dtype=torch.bfloat16, device="cuda")     # rows of 14 bf16: no 8-byte access
+    one = torch.zeros(2, device="cuda")
+    pooled = torch.zeros(2, 2, 7, 7, dtype=torch.bfloat16, device="cuda")
+    idx = torch.zeros(2, 2, 7, 7, dtype=torch.int32, device="cuda")
+    with pytest.raises(sn.SnError) as e:
+        sn.sn_bn_relu_pool2_fwd(x, one, one, pooled, idx, one.clone(), one.clone())
+    assert e.value.status == 2   # SN_ERR_UNSUPPORTED
+    x = torch.zeros(2, 2, 5, 8, dtype=torch.bfloat16, device="cuda")       # odd height
+    with pytest.raises(sn.SnError) as e:
+        sn.sn_bn_relu_pool2_fwd(x, one, one, pooled, idx, one.clone(), one.clone())
+    assert e.value.status == 2   # SN_ERR_UNSUPPORTED
+
+
 POOL_CASES = [((2, 16, 16, 16), (2, 2), (2, 2), (0, 0)), ((2, 8, 55, 55), (3, 3), (2, 2), (0, 0)),
               ((3, 5, 13, 13), (3, 3), (2, 2), (0, 0)), ((2, 6, 35, 35), (3, 3), (2, 2), (0, 0)),
               ((2, 4, 17, 17), (3, 3), (2, 2), (0, 0)), ((1, 3, 9, 12), (3, 3), (2, 2), (1, 1)),
