@@ -74,13 +74,37 @@ struct TileProblem {
     int xt_upc;              // units of the load size a parked channel has room for (64, 128 or 256)
     uint32_t in_bytes, w_bytes;   // sizes of the input tensor and of the packed filter
     int nptiles, nktiles, pt_per_xcd;   // pixel tiles, channel tiles, pixel tiles per XCD (the grid is 8 * pt_per_xcd * nktiles)
+    // Filters too large for an XCD's L2: kmajor = min(nktiles, 8) XCDs take different channel
+    // tiles (kk = nktiles / 8 of them each, at least 1) and pt_per_xcd counts the pixel tiles of
+    // one of the 8 / kmajor groups of XCDs; the grid is 8 * kk * pt_per_xcd.  0: the mapping above.
+    int kmajor, kk;
 };
+
+// Which tile a workgroup computes; false if none (the grid is rounded up).  Workgroup L runs on
+// XCD L % 8 (round-robin dispatch), and every XCD has an L2 of its own.  By default each XCD
+// gets a contiguous range of pixel tiles, and the channel tiles of one pixel tile, which read
+// the same patch, follow each other on the same XCD.  Where the filter would not stay in one L2
+// (kmajor), an XCD keeps to its channel tile(s) instead, so that its share of the filter stays
+// there, and walks through the pixel tiles of its group.
+__device__ inline bool tile_of(const TileProblem &p, int *ktile, int *ptile)
+{
+    const int xcd = blockIdx.x & 7, jx = blockIdx.x >> 3;
+    if (p.kmajor) {
+        *ktile = xcd % p.kmajor + 8 * (jx % p.kk);
+        *ptile = (xcd / p.kmajor) * p.pt_per_xcd + jx / p.kk;
+        return jx / p.kk < p.pt_per_xcd && *ptile < p.nptiles;
+    }
+    *ktile = jx % p.nktiles;
+    *ptile = xcd * p.pt_per_xcd + jx / p.nktiles;
+    return *ptile < p.nptiles;
+}
 
 struct Plan {
     TileProblem p;
     int KT, NF;
     bool wide;
     int dw;                  // conv_tile2.h only: bytes per load item (16 or 4)
+    int ks;                  // conv_tile2.h only: sets of waves that split a tile's chunks (1 or 2)
     size_t lds;
     dim3 grid;
 };
@@ -198,12 +222,9 @@ conv_tile_kernel(const bf16_t *__restrict__ in, const bf16_t *__restrict__ w, vo
     const int wk = (KT == 128) ? (wave >> 1) : 0;
     const int wp = (KT == 128) ? (wave & 1) : wave;
 
-    // ---- which tile.  Workgroup L runs on XCD L % 8 (round-robin dispatch), and every XCD has an
-    // L2 of its own: each XCD gets a contiguous range of pixel tiles, and the channel tiles of
-    // one pixel tile, which read the same patch, follow each other on the same XCD.
-    const int xcd_j = blockIdx.x >> 3;
-    const int ktile = xcd_j % p.nktiles, ptile = (blockIdx.x & 7) * p.pt_per_xcd + xcd_j / p.nktiles;
-    if (ptile >= p.nptiles) return;   // uniform for the workgroup, before any barrier
+    // ---- which tile
+    int ktile, ptile;
+    if (!tile_of(p, &ktile, &ptile)) return;   // uniform for the workgroup, before any barrier
     // ---- tile geometry
     const int rowtile = ptile / p.ncoltiles, coltile = ptile - rowtile * p.ncoltiles;
     const int k0 = ktile * KT;

@@ -103,7 +103,18 @@ bool plan_for(const TileProblem &base, int R, int S, int NF, Plan *pl, bool pref
     p.nptiles = (int)(nrowtiles * p.ncoltiles);
     p.nktiles = (p.Kout + KT - 1) / KT;
     p.pt_per_xcd = (p.nptiles + 7) / 8;
-    const long long nwg = 8LL * p.pt_per_xcd * p.nktiles;
+    long long nwg = 8LL * p.pt_per_xcd * p.nktiles;
+    p.kmajor = 0;
+    p.kk = 1;
+    // a packed filter of more than half an XCD's L2 (4 MB), and a channel tile count that spreads evenly
+    const size_t filter_bytes = (size_t)p.nchunks * R * S * p.Mpad * 16 * sizeof(bf16_t);
+    if (filter_bytes > ((size_t)2 << 20) && p.nktiles >= 2 && (p.nktiles < 8 ? 8 % p.nktiles == 0 : p.nktiles % 8 == 0)) {
+        p.kmajor = p.nktiles < 8 ? p.nktiles : 8;
+        p.kk = p.nktiles < 8 ? 1 : p.nktiles / 8;
+        const int groups = 8 / p.kmajor;
+        p.pt_per_xcd = (p.nptiles + groups - 1) / groups;
+        nwg = 8LL * p.kk * p.pt_per_xcd;
+    }
     if (nwg > 0x7fffffffLL) return false;
     pl->p = p;
     pl->grid = dim3((unsigned)nwg, 1, 1);
@@ -161,11 +172,25 @@ bool make_plan2(const TileProblem &base, int R, int S, Plan *pl)
     if (in_bytes > 0x80000000ull || w_bytes >= 0xfffffff0ull) return false;
     p.in_bytes = (uint32_t)in_bytes;
     p.w_bytes = (uint32_t)w_bytes;
-    size_t lds = (size_t)2 * (p.xslots * 2 + V2_TRASH) * 16 + (size_t)2 * p.pk_bytes;
+    const size_t set_bytes = (size_t)2 * (p.xslots * 2 + V2_TRASH) * 16 + (size_t)2 * p.pk_bytes;
+    size_t lds = set_bytes;
     if (lds < (size_t)4 * 32 * EPI_PITCH) lds = (size_t)4 * 32 * EPI_PITCH;
     if (lds > (size_t)LDS_LIMIT) return false;
     pl->lds = lds;
     pl->dw = dw;
+    pl->ks = 1;
+    // Tiles that leave compute units without a workgroup (small images): two sets of waves per
+    // workgroup split the tile's chunks.  LDS: both sets' buffers, the 8 waves' epilogue staging,
+    // and half of a set's accumulators for the sum of the two.
+    if (pl->NF == 2 && !pl->wide && p.nchunks % 2 == 0 && p.nchunks >= 4 && (long long)p.nptiles * p.nktiles <= 256) {
+        size_t lds2 = 2 * set_bytes;
+        if (lds2 < (size_t)8 * 32 * EPI_PITCH) lds2 = (size_t)8 * 32 * EPI_PITCH;
+        if (lds2 < (size_t)4 * pl->NF * 16 * 64 * sizeof(float)) lds2 = (size_t)4 * pl->NF * 16 * 64 * sizeof(float);
+        if (lds2 <= (size_t)LDS_LIMIT) {
+            pl->ks = 2;
+            pl->lds = lds2;
+        }
+    }
     return true;
 }
 

@@ -26,6 +26,11 @@
 //  * Parked buffers and patch buffers are double buffered over chunks: while chunk
 //    c is multiplied, chunk c+1 is transposed and chunk c+2 is in flight.  One
 //    barrier per chunk.
+//  * KS = 2 (small images, where the tiles do not even give every compute unit a
+//    workgroup): a workgroup has two sets of four waves, each with buffers of its own,
+//    which run the same pipeline over the even and the odd chunks of the same tile
+//    and add their accumulators through LDS before the epilogue -- twice the waves
+//    per compute unit to hide latencies behind, without a second pass over memory.
 #include "conv_tile.h"
 
 namespace sn {
@@ -46,7 +51,7 @@ __device__ inline s16x4 lds_read_tr16(const char *p)
 
 // The body of the kernel; the four LDS regions are distinct, which the qualifiers tell the
 // compiler (loads into a parked buffer then do not hold up the reads of a patch buffer).
-template <int R, int S, int NF, bool WIDE, int DW>
+template <int R, int S, int NF, bool WIDE, int DW, int KS>
 __device__ __forceinline__ void conv_tile2_body(const bf16_t *__restrict__ in, const bf16_t *__restrict__ w,
                                                 void *__restrict__ out, const TileProblem &p,
                                                 uint4 *__restrict__ xs0, uint4 *__restrict__ xs1,
@@ -60,17 +65,17 @@ __device__ __forceinline__ void conv_tile2_body(const bf16_t *__restrict__ in, c
     constexpr int XG = DW == 16 ? 4 : 16;   // most load rounds per chunk: 16 / (channels per round)
     constexpr int XTR = WIDE ? (2 * WROWS * (WIDE_LWP / 16) + 15) / 16 : V2_XTR_MAX_NARROW;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // tid, wave: within the set of four waves; set s of KS takes the chunks s, s + KS, ...
+    const int tid = threadIdx.x & 255, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int set = KS > 1 ? __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 8) : 0;
+    const int nch = p.nchunks / KS;   // chunks per set (the host gives KS > 1 only chunk counts it divides)
     const int l32 = lane & 31, g = lane >> 5;
     const int wk = wave >> 1, wp = wave & 1;
     const int XS = p.xslots * 2 + V2_TRASH;
 
-    // ---- which tile.  Workgroup L runs on XCD L % 8 (round-robin dispatch), and every XCD has an
-    // L2 of its own: each XCD gets a contiguous range of pixel tiles, and the channel tiles of
-    // one pixel tile, which read the same patch, follow each other on the same XCD.
-    const int xcd = blockIdx.x & 7, jx = blockIdx.x >> 3;
-    const int ktile = jx % p.nktiles, ptile = xcd * p.pt_per_xcd + jx / p.nktiles;
-    if (ptile >= p.nptiles) return;   // uniform for the workgroup, before any barrier
+    // ---- which tile
+    int ktile, ptile;
+    if (!tile_of(p, &ktile, &ptile)) return;   // uniform for the workgroup, before any barrier
     // ---- tile geometry (as in conv_tile.h)
     const int rowtile = ptile / p.ncoltiles, coltile = ptile - rowtile * p.ncoltiles;
     const int k0 = ktile * KT;
@@ -128,7 +133,7 @@ __device__ __forceinline__ void conv_tile2_body(const bf16_t *__restrict__ in, c
     const int wave_dst = ((wave * 64) / upc) * chstride + ((wave * 64) % upc) * DW;
     const int round_dst = gch * chstride;
     auto dma_issue = [&](int chunk, char *__restrict__ pk) {
-        const int c0 = chunk * 16;
+        const int c0 = (chunk * KS + set) * 16;
         const bool full = c0 + 16 <= p.Cin;
 #pragma unroll
         for (int rd = 0; rd < XG; ++rd) {
@@ -199,7 +204,7 @@ __device__ __forceinline__ void conv_tile2_body(const bf16_t *__restrict__ in, c
 
     // ---- filter operands: lane (l32, g) of wave row wk takes, for tap tl and channel tile i,
     // the 16-byte item ((stage * TRES + tl) * Mpad + k0 + wk*64 + i*32 + l32) * 2 + (g ^ swz(l32)).
-    const int nstage = p.nchunks * NSUB;
+    const int nstage = nch * NSUB;   // stages of this set; its stage t is stage t + (t / NSUB * (KS - 1) + set) * NSUB of the tile
     const __amdgpu_buffer_rsrc_t w_rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(w), 0, p.w_bytes, 0x00020000);
     const uint32_t wlane = (uint32_t)(((k0 + wk * 64 + l32) * 2 + (g ^ swz(l32))) * 16);
     const uint32_t wtap = (uint32_t)p.Mpad * 32u;   // bytes per tap
@@ -209,7 +214,8 @@ __device__ __forceinline__ void conv_tile2_body(const bf16_t *__restrict__ in, c
     static_assert((2 * NSUB) % AD == 0, "a trip of the main loop must use every set equally often");
     u32x4 areg[AD][TRES * 2];
     auto load_a = [&](int stage, u32x4(&dst)[TRES * 2]) {
-        const uint32_t sbase = (uint32_t)min(stage, nstage - 1) * (uint32_t)TRES * wtap;
+        const int t = min(stage, nstage - 1);
+        const uint32_t sbase = (uint32_t)(KS > 1 ? t + (t / NSUB * (KS - 1) + set) * NSUB : t) * (uint32_t)TRES * wtap;
 #pragma unroll
         for (int tl = 0; tl < TRES; ++tl)
 #pragma unroll
@@ -297,7 +303,7 @@ __device__ __forceinline__ void conv_tile2_body(const bf16_t *__restrict__ in, c
 #pragma unroll
     for (int i = 0; i < AD - 1; ++i) load_a(i, areg[i]);
     dma_issue(0, pk0);
-    dma_issue(min(1, p.nchunks - 1), pk1);
+    dma_issue(min(1, nch - 1), pk1);
     __syncthreads();   // zero fill done, both parked patches have landed
     x_transpose(pk0, xs0);
     __syncthreads();
@@ -316,7 +322,7 @@ __device__ __forceinline__ void conv_tile2_body(const bf16_t *__restrict__ in, c
             for (int f = 0; f < (WIDE ? 1 : NF); ++f) asm volatile("" : "+v"(pixbase[f]));
         }
         load_a(chunk * NSUB + sg + AD - 1, areg[(par + AD - 1) % AD]);   // past the end: the last stage again
-        if (!tail && sg == 0) dma_issue(min(chunk + 2, p.nchunks - 1), pcur);
+        if (!tail && sg == 0) dma_issue(min(chunk + 2, nch - 1), pcur);
         __builtin_amdgcn_sched_barrier(0);   // the loads are issued a whole stage before their use
         if (!tail && sg == NSUB - 1) x_transpose(pnext, xnext);
         compute(xcur, areg[par], sgc);
@@ -333,14 +339,14 @@ __device__ __forceinline__ void conv_tile2_body(const bf16_t *__restrict__ in, c
         }
     };
     int chunk0 = 0;
-    for (; chunk0 + 1 < p.nchunks; chunk0 += 2) {
+    for (; chunk0 + 1 < nch; chunk0 += 2) {
         static_for<2 * NSUB>([&](auto idx) {
             constexpr int c = decltype(idx)::value / NSUB, sg = decltype(idx)::value % NSUB;
             stage(std::integral_constant<int, c>{}, std::integral_constant<int, sg>{},
                   std::integral_constant<int, decltype(idx)::value % AD>{}, std::false_type{}, chunk0 + c);
         });
     }
-    if (p.nchunks & 1) {
+    if (nch & 1) {
         static_for<NSUB>([&](auto idx) {
             stage(std::integral_constant<int, 0>{}, idx, std::integral_constant<int, decltype(idx)::value % AD>{},
                   std::true_type{}, chunk0);
@@ -359,9 +365,34 @@ __device__ __forceinline__ void conv_tile2_body(const bf16_t *__restrict__ in, c
     };
     __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): no load into LDS is still on its way
     __syncthreads();
+    if constexpr (KS > 1) {
+        // the second set's sums reach the first through LDS, half of the accumulators at a time
+        static_assert(KS == 2, "two sets");
+        float *const red = reinterpret_cast<float *>(smem) + wave * NF * 16 * 64 + lane;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            if (set == 1) {
+#pragma unroll
+                for (int f = 0; f < NF; ++f)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) red[(f * 16 + v) * 64] = acc[i][f][v];
+            }
+            __syncthreads();
+            if (set == 0) {
+#pragma unroll
+                for (int f = 0; f < NF; ++f)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[i][f][v] += red[(f * 16 + v) * 64];
+            }
+            __syncthreads();
+        }
+    }
+    // The second set walks through the epilogue as well (it has the same barriers to meet) but
+    // owns no output channel: its channel numbers are past the last.
+    const int kst = set == 0 ? k0 : (1 << 29);
     if (p.out_bf16) {
         constexpr int EP = EPI_PITCH;
-        char *const stage = reinterpret_cast<char *>(smem) + wave * 32 * EP;
+        char *const stage = reinterpret_cast<char *>(smem) + (set * 4 + wave) * 32 * EP;
         constexpr int OCT = NF * 4, KPR = 64 / OCT;
         const int oct = lane % OCT, krow = lane / OCT;
         const int i0 = wp * NF * 32 + oct * 8;
@@ -388,7 +419,7 @@ __device__ __forceinline__ void conv_tile2_body(const bf16_t *__restrict__ in, c
             __syncthreads();
 #pragma unroll
             for (int rd = 0; rd < 32 / KPR; ++rd) {
-                const int kl = rd * KPR + krow, k = k0 + wk * 64 + i * 32 + kl;
+                const int kl = rd * KPR + krow, k = kst + wk * 64 + i * 32 + kl;
                 const uint4 v = *reinterpret_cast<const uint4 *>(stage + kl * EP + oct * 16);
                 if (k >= p.Kout) continue;
                 if (contig) {
@@ -414,27 +445,30 @@ __device__ __forceinline__ void conv_tile2_body(const bf16_t *__restrict__ in, c
                     if (off < 0) continue;
 #pragma unroll
                     for (int i = 0; i < 2; ++i) {
-                        const int k = k0 + wk * 64 + i * 32 + l32;
+                        const int k = kst + wk * 64 + i * 32 + l32;
                         if (k < p.Kout) o32[(size_t)k * PQ + off] = acc[i][f][4 * j + e];
                     }
                 }
     }
 }
 
-template <int R, int S, int NF, bool WIDE, int DW>
-__global__ void __launch_bounds__(256, 2)
+template <int R, int S, int NF, bool WIDE, int DW, int KS>
+__global__ void __launch_bounds__(256 * KS, 2)
 conv_tile2_kernel(const bf16_t *__restrict__ in, const bf16_t *__restrict__ w, void *__restrict__ out, TileProblem p)
 {
     extern __shared__ __attribute__((aligned(16))) uint4 smem[];
     const int XS = p.xslots * 2 + V2_TRASH;
-    char *const pk = reinterpret_cast<char *>(smem + 2 * XS);
-    conv_tile2_body<R, S, NF, WIDE, DW>(in, w, out, p, smem, smem + XS, pk, pk + p.pk_bytes, smem);
+    // each set of waves has its two patch buffers and two parked buffers
+    const int set = KS > 1 ? __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 8) : 0;
+    uint4 *const xs = smem + set * (2 * XS + 2 * (p.pk_bytes / 16));
+    char *const pk = reinterpret_cast<char *>(xs + 2 * XS);
+    conv_tile2_body<R, S, NF, WIDE, DW, KS>(in, w, out, p, xs, xs + XS, pk, pk + p.pk_bytes, smem);
 }
 
-template <int R, int S, int NF, bool WIDE, int DW>
+template <int R, int S, int NF, bool WIDE, int DW, int KS = 1>
 hipError_t launch2_one(const bf16_t *in, const bf16_t *w, void *out, const Plan &pl, hipStream_t st)
 {
-    auto kern = conv_tile2_kernel<R, S, NF, WIDE, DW>;
+    auto kern = conv_tile2_kernel<R, S, NF, WIDE, DW, KS>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -442,7 +476,7 @@ hipError_t launch2_one(const bf16_t *in, const bf16_t *w, void *out, const Plan 
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, pl.grid, dim3(256), pl.lds, st, in, w, out, pl.p);
+    hipLaunchKernelGGL(kern, pl.grid, dim3(256 * KS), pl.lds, st, in, w, out, pl.p);
     return hipGetLastError();
 }
 

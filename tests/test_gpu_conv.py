@@ -53,6 +53,12 @@ CASES = [
     (L("w28_k96", 32, 28, 28, 96, 3, 3, (1, 1), (1, 1)), 32),         # backward-filter with two wave sets per tile
     (L("c96_bwd", 96, 16, 16, 48, 3, 3, (1, 1), (1, 1)), 3),          # backward-data into 96 channels
     (L("c130_pad2", 130, 10, 12, 130, 3, 3, (1, 1), (2, 2)), 2),
+    # few tiles of small images: two sets of waves share a tile's chunks (an even chunk count):
+    # 4 chunks; 6 (an odd count per set); 8 with a partial last chunk, 8-wide rows (16-byte items)
+    (L("w14_split", 64, 14, 14, 128, 3, 3, (1, 1), (1, 1)), 4),
+    (L("w14_split_c96", 96, 14, 14, 160, 3, 3, (1, 1), (1, 1)), 5),
+    (L("w8_split_c120", 120, 8, 8, 128, 3, 3, (1, 1), (1, 1)), 6),
+    (L("w14_split_bwd", 128, 14, 14, 64, 3, 3, (1, 1), (1, 1)), 3),   # backward-data from 64 channels into 128
 ]
 IDS = [c[0].name for c in CASES]
 
