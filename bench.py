@@ -4,10 +4,13 @@
 One step = one pass of the whole hot path over one batch of a synthetic,
 network-shaped workload (default: the VGG-16-shaped configuration, N = 32, bf16
 in / fp32 accumulate): for every conv layer, CONV forward, BN forward, ReLU
-forward and max-pool forward (the layers recomputation replays; BN and the ReLU
-after it are one call, sn_bn_relu_fwd, and so are their backward passes,
-sn_bn_relu_bwd, and where a 2x2 pool follows, BN + ReLU + pool are one call each
-way, sn_bn_relu_pool2_fwd / _bwd, unless --no-fuse), then their backward
+forward and max-pool forward (the layers recomputation replays; unless --no-fuse
+BN and the ReLU after it are one call, sn_bn_relu_fwd, and so are their backward
+passes, sn_bn_relu_bwd; where a 2x2 pool follows, BN + ReLU + pool are one call
+each way, sn_bn_relu_pool2_fwd / _bwd; and where a channel is too large for BN's
+one-pass kernel the CONV leaves the batch statistics of its output,
+sn_conv2d_fwd_bn_stats, and BN is one pass from them, sn_bn_apply /
+sn_bn_relu_pool2_apply), then their backward
 passes, CONV backward-data and CONV backward-filter, each CONV planned under the
 given workspace budget.  Inputs are resident in HBM before the timed
 region; autotuning happens before it too.
@@ -115,8 +118,6 @@ def build_ops(cfg_no, budget, autotune, fuse):
             plans[(layer.name, d)] = (sn.ALGO_NAMES[algo], used, ms)
         names = {0: "conv_fwd", 1: "conv_bwd_data", 2: "conv_bwd_filter"}
         byts = {0: (ex + ew) * b + ey * b, 1: (ey + ew) * b + ex * b, 2: (ex + ey) * b + ew * 4}
-        for _ in range(layer.mult):
-            fwd_ops.append(Op(names[0], layer.name, conv_call(0, xd, wd, y), algo_flops, byts[0], nominal))
         cheap_f, cheap_b = [], []
         act_in = y
         E = y.numel()
@@ -124,6 +125,19 @@ def build_ops(cfg_no, budget, autotune, fuse):
             gamma, beta = (t.to(dev) for t in wl.bn_params(K, wl.layer_seed(cfg_no, li)))
             ybn = torch.empty_like(y)
             mean, invstd = torch.empty(K, device=dev), torch.empty(K, device=dev)
+        # Where a channel of the output is too large for the one-pass BN kernel (which holds it in
+        # registers), the CONV leaves the batch statistics of its output and the BN is one pass from
+        # them; elsewhere taking them in the CONV costs more than BN's own single pass saves.
+        conv_stats = cfg["bn"] and fuse and N * P * Q * b > 13 * 1024 * 16
+        if conv_stats:
+            scratch = torch.empty(max(sn.sn_conv_bn_stats_scratch_bytes(shape), 256), dtype=torch.uint8, device=dev)
+            fwd_call = (lambda xd=xd, wd=wd, y=y, shape=shape, m=mean, i=invstd, sc=scratch:
+                        sn.sn_conv2d_fwd_bn_stats(xd, wd, y, shape, m, i, sc, sn.SN_ALGO_AUTO, wsbox[0]))
+        else:
+            fwd_call = conv_call(0, xd, wd, y)
+        for _ in range(layer.mult):
+            fwd_ops.append(Op(names[0], layer.name, fwd_call, algo_flops, byts[0], nominal))
+        if cfg["bn"]:
             dgamma, dbeta = torch.empty(K, device=dev), torch.empty(K, device=dev)
             g_bn = torch.empty_like(y)
         a = torch.empty_like(y)
@@ -134,9 +148,12 @@ def build_ops(cfg_no, budget, autotune, fuse):
         if pool_pair:
             pass
         elif cfg["bn"] and fuse:
-            # BN and the ReLU after it in one pass: 1 read + 1 write of E elements is all the pair needs
+            # BN and the ReLU after it in one pass over the tensor, from the statistics the CONV left:
+            # 1 read + 1 write of E elements is all the pair needs
             cheap_f.append(Op("bn_relu_fwd", layer.name,
-                              lambda y=y, ga=gamma, be=beta, o=a, m=mean, i=invstd: sn.sn_bn_relu_fwd(y, ga, be, o, m, i),
+                              (lambda y=y, ga=gamma, be=beta, o=a, m=mean, i=invstd: sn.sn_bn_apply(y, ga, be, m, i, o, relu=True))
+                              if conv_stats else
+                              (lambda y=y, ga=gamma, be=beta, o=a, m=mean, i=invstd: sn.sn_bn_relu_fwd(y, ga, be, o, m, i)),
                               nbytes=2 * E * b))
         else:
             if cfg["bn"]:
@@ -155,8 +172,10 @@ def build_ops(cfg_no, budget, autotune, fuse):
             Eo = pooled.numel()
         if pool_pair:
             cheap_f.append(Op("bn_relu_pool_fwd", layer.name,
-                              lambda y=y, ga=gamma, be=beta, o=pooled, ix=idx, m=mean, i=invstd:
-                              sn.sn_bn_relu_pool2_fwd(y, ga, be, o, ix, m, i), nbytes=E * b + Eo * (b + 4)))
+                              (lambda y=y, ga=gamma, be=beta, o=pooled, ix=idx, m=mean, i=invstd:
+                               sn.sn_bn_relu_pool2_apply(y, ga, be, m, i, o, ix)) if conv_stats else
+                              (lambda y=y, ga=gamma, be=beta, o=pooled, ix=idx, m=mean, i=invstd:
+                               sn.sn_bn_relu_pool2_fwd(y, ga, be, o, ix, m, i)), nbytes=E * b + Eo * (b + 4)))
             cheap_b.append(Op("bn_relu_pool_bwd", layer.name,
                               lambda y=y, g=g_pool, ix=idx, ga=gamma, be=beta, m=mean, i=invstd, o=dy, dg=dgamma, db=dbeta:
                               sn.sn_bn_relu_pool2_bwd(y, g, ix, ga, be, m, i, o, dg, db),
@@ -302,7 +321,7 @@ def main():
     # alone, handed a smaller slice of the same workspace; the planner falls back by itself
     per_budget = {}
     full_ws = wsbox[0]
-    for bb in sorted(set(cfg["budgets"]) | {budget}):
+    for bb in sorted({x for x in cfg["budgets"] if x is not None} | {budget}):   # None = no limit: the default budget stands for it
         if bb > budget or args.no_budget_sweep:
             continue
         wsbox[0] = None if bb == 0 else full_ws[:bb]

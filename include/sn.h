@@ -129,6 +129,23 @@ sn_status sn_conv_autotune(sn_conv_dir dir, const void *a, const void *b, void *
 sn_status sn_conv2d_fwd(const void *x, const void *w, void *y, const sn_conv_shape *shape,
                         sn_conv_algo algo, void *workspace, size_t workspace_bytes, sn_stream stream);
 
+/* CONV forward that also takes, for the BN layer that follows it, the batch statistics of its own
+ * output (Sec. 3.4: CONV -> BN -> ReLU is the chain the runtime schedules as a unit): y exactly
+ * as sn_conv2d_fwd writes it for the same algo and workspace, and
+ *   save_mean[k] = mean over (n,p,q) of y[n,k,p,q], save_invstd[k] = 1/sqrt(biased var + eps),
+ * of the values as stored (after rounding to out_dtype), i.e. what sn_bn_fwd(y) would save, up to
+ * the order of the sums.  Where a tile kernel runs the CONV (stride 1, bf16 inputs) the
+ * statistics come out of its accumulators -- per tile and channel a count, a mean and a sum of
+ * squared deviations, combined pairwise in fp64 in a fixed order -- and y is not read again;
+ * elsewhere a pass over y follows the CONV.  sn_bn_apply / sn_bn_relu_pool2_apply then finish the
+ * BN in one pass.  scratch: device memory of at least sn_conv_bn_stats_scratch_bytes(shape)
+ * bytes, 16-byte aligned, contents undefined afterwards (SN_ERR_WORKSPACE_TOO_SMALL if smaller). */
+size_t sn_conv_bn_stats_scratch_bytes(const sn_conv_shape *shape);
+sn_status sn_conv2d_fwd_bn_stats(const void *x, const void *w, void *y, const sn_conv_shape *shape,
+                                 sn_conv_algo algo, void *workspace, size_t workspace_bytes,
+                                 float *save_mean, float *save_invstd, float eps,
+                                 void *scratch, size_t scratch_bytes, sn_stream stream);
+
 /* CONV backward-data: dx[n,c,h,v] = sum over (k,p,q,r,s) with p*sh+r-ph = h and
  * q*sw+s-pw = v of dy[n,k,p,q] * w[k,c,r,s].  dy, w of in_dtype; dx of out_dtype. */
 sn_status sn_conv2d_bwd_data(const void *dy, const void *w, void *dx, const sn_conv_shape *shape,
@@ -169,6 +186,14 @@ sn_status sn_bn_relu_fwd(const void *x, const float *gamma, const float *beta, v
                          float *save_mean, float *save_invstd,
                          int N, int C, int H, int W, float eps, sn_dtype dtype, sn_stream stream);
 
+/* BN forward (optionally with the ReLU, relu != 0) from statistics the caller already has --
+ * sn_conv2d_fwd_bn_stats leaves them, or an earlier sn_bn_fwd on the same x: the normalisation
+ * pass alone, one read of x and one write of y, with the arithmetic of sn_bn_fwd /
+ * sn_bn_relu_fwd (bit-identical y for the same mean and invstd).  y may alias x. */
+sn_status sn_bn_apply(const void *x, const float *gamma, const float *beta,
+                      const float *mean, const float *invstd, void *y,
+                      int N, int C, int H, int W, int relu, sn_dtype dtype, sn_stream stream);
+
 /* BN backward from the saved statistics, xhat = (x-mean)*invstd:
  *   dbeta = sum(dy), dgamma = sum(dy*xhat),
  *   dx = gamma*invstd/M * (M*dy - dbeta - xhat*dgamma).
@@ -203,6 +228,12 @@ sn_status sn_bn_relu_bwd(const void *x, const void *dy, const float *gamma, cons
 sn_status sn_bn_relu_pool2_fwd(const void *x, const float *gamma, const float *beta, void *pooled, int32_t *idx,
                                float *save_mean, float *save_invstd,
                                int N, int C, int H, int W, float eps, sn_dtype dtype, sn_stream stream);
+
+/* sn_bn_relu_pool2_fwd from statistics the caller already has (as sn_bn_apply): pooled and idx
+ * bit-identical to sn_bn_relu_pool2_fwd's for the same mean and invstd.  Same shape limits. */
+sn_status sn_bn_relu_pool2_apply(const void *x, const float *gamma, const float *beta,
+                                 const float *mean, const float *invstd, void *pooled, int32_t *idx,
+                                 int N, int C, int H, int W, sn_dtype dtype, sn_stream stream);
 
 /* Backward of sn_bn_relu_pool2_fwd: sn_bn_relu_bwd applied to the gradient sn_maxpool_bwd would
  * give for (dpooled, idx) -- dpooled of a window goes to the window's winner, 0 elsewhere --

@@ -28,12 +28,16 @@ SIGNATURES = {
     "sn_planner_clear": (None, []),
     "sn_conv_autotune": (_i, [_i, _vp, _vp, _vp, _shape_p, _vp, _sz, _i, _vp]),
     "sn_conv2d_fwd": (_i, _conv_args),
+    "sn_conv_bn_stats_scratch_bytes": (_sz, [_shape_p]),
+    "sn_conv2d_fwd_bn_stats": (_i, _conv_args[:-1] + [_vp, _vp, ctypes.c_float, _vp, _sz, _vp]),
     "sn_conv2d_bwd_data": (_i, _conv_args),
     "sn_conv2d_bwd_filter": (_i, _conv_args),
     "sn_relu_fwd": (_i, [_vp, _vp, _sz, _i, _vp]),
     "sn_relu_bwd": (_i, [_vp, _vp, _vp, _sz, _i, _vp]),
     "sn_bn_fwd": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, ctypes.c_float, _i, _vp]),
     "sn_bn_relu_fwd": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, ctypes.c_float, _i, _vp]),
+    "sn_bn_apply": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp]),
+    "sn_bn_relu_pool2_apply": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp]),
     "sn_bn_bwd": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp]),
     "sn_bn_relu_bwd": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp]),  # x, dy, gamma, beta, ...
     "sn_bn_relu_pool2_fwd": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, ctypes.c_float, _i, _vp]),

@@ -15,6 +15,7 @@ __all__ = [
     "SnError", "conv_shape", "sn_out_dim", "sn_conv_workspace_query", "sn_conv_plan",
     "sn_planner_record", "sn_planner_clear", "sn_conv_autotune",
     "sn_conv2d_fwd", "sn_conv2d_bwd_data", "sn_conv2d_bwd_filter",
+    "sn_conv_bn_stats_scratch_bytes", "sn_conv2d_fwd_bn_stats", "sn_bn_apply", "sn_bn_relu_pool2_apply",
     "sn_relu_fwd", "sn_relu_bwd", "sn_bn_fwd", "sn_bn_relu_fwd", "sn_bn_bwd", "sn_bn_relu_bwd", "sn_bn_relu_pool2_fwd", "sn_bn_relu_pool2_bwd", "sn_maxpool_fwd", "sn_maxpool_bwd",
 ]
 
@@ -109,6 +110,18 @@ def sn_conv2d_fwd(x, w, y, shape, algo=SN_ALGO_AUTO, workspace=None):
                                                  _stream()))
 
 
+def sn_conv_bn_stats_scratch_bytes(shape):
+    return int(load().sn_conv_bn_stats_scratch_bytes(ctypes.byref(shape)))
+
+
+def sn_conv2d_fwd_bn_stats(x, w, y, shape, save_mean, save_invstd, scratch, algo=SN_ALGO_AUTO, workspace=None,
+                           eps=1e-5):
+    wp, wb = _ws(workspace)
+    _check("sn_conv2d_fwd_bn_stats", load().sn_conv2d_fwd_bn_stats(
+        _ptr(x), _ptr(w), _ptr(y), ctypes.byref(shape), algo, wp, wb, _ptr(save_mean), _ptr(save_invstd), eps,
+        _ptr(scratch), scratch.numel() * scratch.element_size(), _stream()))
+
+
 def sn_conv2d_bwd_data(dy, w, dx, shape, algo=SN_ALGO_AUTO, workspace=None):
     wp, wb = _ws(workspace)
     _check("sn_conv2d_bwd_data", load().sn_conv2d_bwd_data(_ptr(dy), _ptr(w), _ptr(dx), ctypes.byref(shape), algo,
@@ -139,6 +152,19 @@ def sn_bn_relu_fwd(x, gamma, beta, y, save_mean, save_invstd, eps=1e-5):
     N, C, H, W = x.shape
     _check("sn_bn_relu_fwd", load().sn_bn_relu_fwd(_ptr(x), _ptr(gamma), _ptr(beta), _ptr(y), _ptr(save_mean),
                                                    _ptr(save_invstd), N, C, H, W, eps, _dtype_code(x), _stream()))
+
+
+def sn_bn_apply(x, gamma, beta, mean, invstd, y, relu=False):
+    N, C, H, W = x.shape
+    _check("sn_bn_apply", load().sn_bn_apply(_ptr(x), _ptr(gamma), _ptr(beta), _ptr(mean), _ptr(invstd), _ptr(y),
+                                             N, C, H, W, int(relu), _dtype_code(x), _stream()))
+
+
+def sn_bn_relu_pool2_apply(x, gamma, beta, mean, invstd, pooled, idx):
+    N, C, H, W = x.shape
+    _check("sn_bn_relu_pool2_apply", load().sn_bn_relu_pool2_apply(
+        _ptr(x), _ptr(gamma), _ptr(beta), _ptr(mean), _ptr(invstd), _ptr(pooled), _ptr(idx), N, C, H, W,
+        _dtype_code(x), _stream()))
 
 
 def sn_bn_bwd(x, dy, gamma, save_mean, save_invstd, dx, dgamma, dbeta):

@@ -353,6 +353,56 @@ bn_stats_final_kernel(const T *__restrict__ x, const float *__restrict__ part, f
     }
 }
 
+// Statistics from the partial results the CONV kernels leave per (channel, pixel tile): count,
+// mean, and sum of squared deviations from that mean.  Two such triples combine exactly
+// (pairwise update).  One workgroup of 1024 threads per channel: a thread folds the tiles
+// t, t + 1024, ... in order, the threads of a wave combine in a butterfly, and thread 0 folds
+// the sixteen waves' results, all in fp64 and always in the same order.
+struct Moments { double n, mu, m2; };
+
+__device__ inline void moments_fold(Moments &a, double nb, double mb, double m2b)
+{
+    if (!(nb > 0.0)) return;
+    const double nt = a.n + nb, d = mb - a.mu, r = nb / nt;
+    a.mu += d * r;
+    a.m2 += m2b + d * d * (a.n * r);
+    a.n = nt;
+}
+
+__global__ void __launch_bounds__(1024)
+bn_finalize_tiles_kernel(const float *__restrict__ part, int ntiles, float *__restrict__ mean,
+                         float *__restrict__ invstd, float eps)
+{
+    const int c = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    Moments a = {0.0, 0.0, 0.0};
+    for (int t = tid; t < ntiles; t += 1024) {
+        const float *e = part + ((size_t)c * ntiles + t) * 3;
+        moments_fold(a, (double)e[0], (double)e[1], (double)e[2]);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const Moments b = {__shfl_xor(a.n, o, WAVE), __shfl_xor(a.mu, o, WAVE), __shfl_xor(a.m2, o, WAVE)};
+        // both partners arrive at the same bits: the higher lane's triple is folded into the lower's
+        if (lane & o) {
+            const Moments own = a;
+            a = b;
+            moments_fold(a, own.n, own.mu, own.m2);
+        } else {
+            moments_fold(a, b.n, b.mu, b.m2);
+        }
+    }
+    __shared__ double red[16][3];
+    if (lane == 0) { red[wave][0] = a.n; red[wave][1] = a.mu; red[wave][2] = a.m2; }
+    __syncthreads();
+    if (tid == 0) {
+        for (int w = 1; w < 16; ++w) moments_fold(a, red[w][0], red[w][1], red[w][2]);
+        double var = a.n > 0.0 ? a.m2 / a.n : 0.0;
+        if (var < 0.0) var = 0.0;
+        mean[c] = (float)a.mu;
+        invstd[c] = (float)(1.0 / sqrt(var + (double)eps));
+    }
+}
+
 // Pass 3 (forward): y = gamma*invstd*(x - mean) + beta.
 template <typename T>
 __global__ void __launch_bounds__(256)
@@ -1061,10 +1111,68 @@ hipError_t launch_bn_fwd(const void *x, const float *gamma, const float *beta, v
     });
 }
 
+hipError_t launch_bn_finalize_tiles(const float *part, int C, int ntiles, float *mean, float *invstd, float eps,
+                                    hipStream_t s)
+{
+    hipLaunchKernelGGL(bn_finalize_tiles_kernel, dim3(C), dim3(1024), 0, s, part, ntiles, mean, invstd, eps);
+    return hipGetLastError();
+}
+
+size_t bn_stats_scratch_bytes(int N, int C, int HW)
+{
+    const Slices sl = make_slices(N, C, HW, ~(size_t)0);
+    return (size_t)C * sl.nslice * 2 * sizeof(float);
+}
+
+hipError_t launch_bn_stats(const void *x, float *scratch, float *mean, float *invstd, int N, int C, int HW, float eps,
+                           int bf16, hipStream_t s)
+{
+    const Slices sl = make_slices(N, C, HW, ~(size_t)0);
+    return by_dtype(bf16, [&](auto *tag) {
+        typedef typename std::remove_pointer<decltype(tag)>::type T;
+        hipLaunchKernelGGL(bn_stats_kernel<T>, dim3(C, sl.nslice), dim3(256), 0, s, (const T *)x, scratch, N, C, HW, sl);
+        hipLaunchKernelGGL(bn_stats_final_kernel<T>, dim3(C), dim3(64), 0, s, (const T *)x, scratch, mean, invstd,
+                           N, HW, sl.nslice, eps);
+    });
+}
+
+hipError_t launch_bn_apply(const void *x, const float *gamma, const float *beta, const float *mean,
+                           const float *invstd, void *y, int N, int C, int HW, int bf16, int relu, hipStream_t s)
+{
+    const Slices sl = make_slices(N, C, HW, ~(size_t)0);
+    return by_dtype(bf16, [&](auto *tag) {
+        typedef typename std::remove_pointer<decltype(tag)>::type T;
+        hipLaunchKernelGGL(bn_apply_kernel<T>, dim3(C, sl.nslice), dim3(256), 0, s, (const T *)x, (T *)y, gamma, beta,
+                           mean, invstd, N, C, HW, sl, relu);
+    });
+}
+
 int bn_relu_pool2_vb(int W, int bf16)
 {
     const int esz = bf16 ? 2 : 4;
     return W % (16 / esz) == 0 ? 16 : W % (8 / esz) == 0 ? 8 : 0;
+}
+
+hipError_t launch_bn_relu_pool2_apply(const void *x, const float *gamma, const float *beta, const float *mean,
+                                      const float *invstd, void *pooled, int32_t *idx, int N, int C, int H, int W,
+                                      int bf16, hipStream_t s)
+{
+    const int esz = bf16 ? 2 : 4, pvb = bn_relu_pool2_vb(W, bf16);
+    if (pvb == 0 || (H & 1)) return hipErrorInvalidValue;
+    const int units = N * (H / 2) * (W / (pvb / esz));
+    long long want = (4096 + C - 1) / C, most = (units + 255) / 256;
+    if (want > most) want = most;
+    if (want > 65535) want = 65535;
+    return by_dtype(bf16, [&](auto *tag) {
+        typedef typename std::remove_pointer<decltype(tag)>::type T;
+        dim3 block(256), pgrid(C, (unsigned)want);
+        if (pvb == 16)
+            hipLaunchKernelGGL((bn_relu_pool2_apply_kernel<T, 16>), pgrid, block, 0, s, (const T *)x, (T *)pooled, idx,
+                               gamma, beta, mean, invstd, C, H, W, units);
+        else
+            hipLaunchKernelGGL((bn_relu_pool2_apply_kernel<T, 8>), pgrid, block, 0, s, (const T *)x, (T *)pooled, idx,
+                               gamma, beta, mean, invstd, C, H, W, units);
+    });
 }
 
 hipError_t launch_bn_relu_pool2_fwd(const void *x, const float *gamma, const float *beta, void *pooled, int32_t *idx,
@@ -1093,23 +1201,15 @@ hipError_t launch_bn_relu_pool2_fwd(const void *x, const float *gamma, const flo
     const Slices sl = make_slices(N, C, HW, (size_t)N * C * HW * esz);
     if ((size_t)C * sl.nslice * 2 * sizeof(float) > (size_t)N * C * (HW / 4) * sizeof(int32_t)) return hipErrorInvalidValue;
     float *part = reinterpret_cast<float *>(idx);
-    const int units = N * (H / 2) * (W / (pvb / (int)esz));
-    long long want = (4096 + C - 1) / C, most = (units + 255) / 256;
-    if (want > most) want = most;
-    if (want > 65535) want = 65535;
-    return by_dtype(bf16, [&](auto *tag) {
+    hipError_t e = by_dtype(bf16, [&](auto *tag) {
         typedef typename std::remove_pointer<decltype(tag)>::type T;
-        dim3 grid(C, sl.nslice), block(256), pgrid(C, (unsigned)want);
+        dim3 grid(C, sl.nslice), block(256);
         hipLaunchKernelGGL(bn_stats_kernel<T>, grid, block, 0, s, (const T *)x, part, N, C, HW, sl);
         hipLaunchKernelGGL(bn_stats_final_kernel<T>, dim3(C), dim3(64), 0, s, (const T *)x, part, mean, invstd,
                            N, HW, sl.nslice, eps);
-        if (pvb == 16)
-            hipLaunchKernelGGL((bn_relu_pool2_apply_kernel<T, 16>), pgrid, block, 0, s, (const T *)x, (T *)pooled, idx,
-                               gamma, beta, mean, invstd, C, H, W, units);
-        else
-            hipLaunchKernelGGL((bn_relu_pool2_apply_kernel<T, 8>), pgrid, block, 0, s, (const T *)x, (T *)pooled, idx,
-                               gamma, beta, mean, invstd, C, H, W, units);
     });
+    if (e != hipSuccess) return e;
+    return launch_bn_relu_pool2_apply(x, gamma, beta, mean, invstd, pooled, idx, N, C, H, W, bf16, s);
 }
 
 hipError_t launch_bn_bwd(const void *x, const void *dy, const float *relu_beta, const float *gamma, const float *mean,

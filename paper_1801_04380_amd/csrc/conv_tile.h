@@ -78,6 +78,10 @@ struct TileProblem {
     // tiles (kk = nktiles / 8 of them each, at least 1) and pt_per_xcd counts the pixel tiles of
     // one of the 8 / kmajor groups of XCDs; the grid is 8 * kk * pt_per_xcd.  0: the mapping above.
     int kmajor, kk;
+    // Forward only, may be null: where the tiles leave, for the BN that follows the CONV, the count,
+    // mean and sum of squared deviations of their output values per channel:
+    // stats[(k * nptiles + ptile) * 3 + {0, 1, 2}].
+    float *stats;
 };
 
 // Which tile a workgroup computes; false if none (the grid is rounded up).  Workgroup L runs on
@@ -164,6 +168,129 @@ __device__ inline uint32_t pack2_bf16(float a, float b)
 
 // Never written: the source of every load that must bring zeros.
 __device__ __attribute__((aligned(16))) uint32_t zero_page[4];
+
+// Per-channel statistics of a tile's outputs, taken from the accumulators before they are stored
+// (as the stored values: rounded to bf16 where the output is bf16), for the batch normalisation
+// that follows: the count n of the tile's real output pixels, their mean, and the sum M2 of squared
+// deviations from that mean.  A lane makes one pass over its registers with sums of d and d^2,
+// d = value - the lane's first value (a shift next to the data keeps the variance free of
+// cancellation), turns them into (n, mean, M2), and such triples combine exactly (pairwise
+// formula): lane with lane + 32, then the NWP waves that hold the pixels of one channel through
+// LDS, always in the same order.  acc[i][f][v]: channel kbase + 32 i + lane % 32, pixel
+// (wp * NF + f) * 32 + 8 (v / 4) + 4 (lane / 32) + v % 4 of the tile; `slot` numbers the groups
+// of NWP waves; red: 3 * 64 * NWP * nslots floats of LDS that nothing else uses until the function
+// returns (it ends with a barrier).  Every wave of the workgroup must call it.
+struct TileMoments { float n, mean, m2; };
+
+__device__ inline TileMoments moments_join(const TileMoments &a, const TileMoments &b)
+{
+    const float nt = a.n + b.n;
+    if (!(nt > 0.f)) return a;
+    const float d = b.mean - a.mean, r = b.n / nt;
+    TileMoments o;
+    o.n = nt;
+    o.mean = a.mean + d * r;
+    o.m2 = a.m2 + b.m2 + d * d * a.n * r;
+    return o;
+}
+
+template <int NF, int NWP>
+__device__ inline void tile_bn_partials(const f32x16 (&acc)[2][NF], int TW, int rows_ok, int cols_ok, int wp, int slot,
+                                        int l32, int g, int kbase, int Kout, bool round_bf16,
+                                        float *__restrict__ stats, int nptiles, int ptile, float *red)
+{
+    // Which of the lane's pixels are real outputs, without the divisions of the store offsets.  A
+    // tile is either 32 columns wide (32-pixel group F = wp * NF + f is row F of a column tile
+    // with cols_ok real columns) or spans whole image rows, where the real pixels are the first
+    // rows_ok * TW; rows_ok = min(TH, rows left).  Either way the lane's pixel v of group f,
+    // 8 (v / 4) + v % 4 + 4 (lane / 32) into the group, is real iff 8 (v / 4) + v % 4 < lim[f].
+    int lim[NF];
+    float n = 0.f;
+#pragma unroll
+    for (int f = 0; f < NF; ++f) {
+        const int F = wp * NF + f;
+        int L = TW == 32 ? (F < rows_ok ? cols_ok - 4 * g : 0) : rows_ok * TW - F * 32 - 4 * g;
+        L = min(max(L, 0), 32);
+        lim[f] = L;
+        n += (float)(4 * (L >> 3) + min(L & 7, 4));
+    }
+    // Sums of d and d^2 over the lane's real pixels, d = stored value - shift.  Four variants of
+    // one loop (rounded to bf16 or not, every pixel real or not), chosen by conditions that are
+    // the same for the whole wave, so that the loop itself has no selects it does not need; the
+    // bf16 rounding converts two values per instruction.
+    float s1[2] = {0.f, 0.f}, s2[2] = {0.f, 0.f}, shift[2];
+    const bool full = __all(n == (float)(NF * 16)) != 0;   // every pixel of every lane of the wave is real
+    auto sums = [&](auto rb, auto all) {
+        constexpr bool RB = decltype(rb)::value, ALL = decltype(all)::value;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            shift[i] = RB ? __uint_as_float(pack2_bf16(acc[i][0][0], 0.f) << 16) : acc[i][0][0];   // any value next to the data will do
+#pragma unroll
+            for (int f = 0; f < NF; ++f)
+#pragma unroll
+                for (int v = 0; v < 16; v += 2) {
+                    float x0 = acc[i][f][v], x1 = acc[i][f][v + 1];
+                    if (RB) {
+                        const uint32_t u = pack2_bf16(x0, x1);
+                        x0 = __uint_as_float(u << 16);
+                        x1 = __uint_as_float(u & 0xffff0000u);
+                    }
+                    float d0 = x0 - shift[i], d1 = x1 - shift[i];
+                    if (!ALL) {
+                        d0 = (8 * (v / 4) + v % 4 < lim[f]) ? d0 : 0.f;
+                        d1 = (8 * ((v + 1) / 4) + (v + 1) % 4 < lim[f]) ? d1 : 0.f;
+                    }
+                    s1[i] += d0;
+                    s2[i] = __builtin_fmaf(d0, d0, s2[i]);
+                    s1[i] += d1;
+                    s2[i] = __builtin_fmaf(d1, d1, s2[i]);
+                }
+        }
+    };
+    if (round_bf16) {
+        if (full) sums(std::true_type{}, std::true_type{});
+        else sums(std::true_type{}, std::false_type{});
+    } else {
+        if (full) sums(std::false_type{}, std::true_type{});
+        else sums(std::false_type{}, std::false_type{});
+    }
+    __syncthreads();   // red is free
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        TileMoments m;
+        m.n = n;
+        m.mean = n > 0.f ? shift[i] + s1[i] / n : 0.f;
+        m.m2 = n > 0.f ? fmaxf(s2[i] - s1[i] * s1[i] / n, 0.f) : 0.f;
+        TileMoments o;
+        o.n = __shfl_xor(m.n, 32);
+        o.mean = __shfl_xor(m.mean, 32);
+        o.m2 = __shfl_xor(m.m2, 32);
+        if (g == 0) {
+            m = moments_join(m, o);
+            float *e = red + (((slot * 2 + i) * 32 + l32) * NWP + wp) * 3;
+            e[0] = m.n; e[1] = m.mean; e[2] = m.m2;
+        }
+    }
+    __syncthreads();
+    if (g == 0 && wp == 0) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const float *e = red + ((slot * 2 + i) * 32 + l32) * NWP * 3;
+            TileMoments m = {e[0], e[1], e[2]};
+#pragma unroll
+            for (int w = 1; w < NWP; ++w) {
+                const TileMoments o = {e[3 * w], e[3 * w + 1], e[3 * w + 2]};
+                m = moments_join(m, o);
+            }
+            const int k = kbase + i * 32 + l32;
+            if (k < Kout) {
+                float *o = stats + ((size_t)k * nptiles + ptile) * 3;
+                o[0] = m.n; o[1] = m.mean; o[2] = m.m2;
+            }
+        }
+    }
+    __syncthreads();   // red may be written again
+}
 
 // Eight consecutive bf16 as one 16-byte load, whatever the alignment.
 struct __attribute__((packed, aligned(2))) V128u { u32x4 v; };
@@ -691,6 +818,9 @@ conv_tile_kernel(const bf16_t *__restrict__ in, const bf16_t *__restrict__ w, vo
         const int n = o / p.Pout, pp = o - n * p.Pout;
         return (n * p.Kout * p.Pout + pp) * p.Qout + q0 + cl;
     };
+    if (p.stats)
+        tile_bn_partials<NF, KT == 128 ? 2 : 4>(acc, p.TW, min(p.TH, NP - o0), p.Qout - q0, wp, wk, l32, g, k0 + wk * 64, p.Kout, p.out_bf16 != 0, p.stats,
+                                                p.nptiles, ptile, reinterpret_cast<float *>(smem));
     if (p.out_bf16) {
         // bf16: through LDS, 32 channels x NF*32 pixels per wave and pass, so that a lane
         // writes 8 consecutive pixels of one channel with one 16-byte store

@@ -213,6 +213,7 @@ bool problem_of(const ConvGeom &g, bool bwd_data, TileProblem *p)
         p->w_sm = T; p->w_sr = g.C * T; p->tflip = 1;
     }
     p->out_bf16 = g.out_bf16;
+    p->stats = nullptr;
     return true;
 }
 
@@ -240,14 +241,26 @@ size_t tile_conv_packed_bytes(const ConvGeom &g, bool bwd_data)
     return align_up((size_t)pl.p.nchunks * g.R * g.S * pl.p.Mpad * 16 * sizeof(bf16_t), 256);
 }
 
+// Pixel tiles of the plan launch_tile_conv would use (forward); 0 if the kernels do not apply.
+int tile_conv_stats_tiles(const ConvGeom &g, bool staged, bool in_aligned16)
+{
+    TileProblem p;
+    Plan pl, pl2;
+    if (!tile_conv_supported(g, false) || !problem_of(g, false, &p) || !make_plan(p, g.R, g.S, staged, &pl)) return 0;
+    if (staged && in_aligned16 && make_plan2(p, g.R, g.S, &pl2)) return pl2.p.nptiles;
+    return pl.p.nptiles;
+}
+
 hipError_t launch_tile_conv(const void *in, const void *w, void *out, const ConvGeom &g, bool bwd_data,
-                            void *packed, hipStream_t st)
+                            void *packed, hipStream_t st, float *stats)
 {
     TileProblem p;
     Plan pl;
     if (!tile_conv_supported(g, bwd_data) || !problem_of(g, bwd_data, &p) ||
         !make_plan(p, g.R, g.S, packed != nullptr, &pl))
         return hipErrorInvalidValue;
+    if (stats && bwd_data) return hipErrorInvalidValue;
+    pl.p.stats = stats;
     const bf16_t *wsrc = static_cast<const bf16_t *>(w);
     if (packed) {
         const size_t items = (size_t)pl.p.nchunks * g.R * g.S * pl.p.Mpad * 2;
@@ -261,8 +274,10 @@ hipError_t launch_tile_conv(const void *in, const void *w, void *out, const Conv
     const bf16_t *src = static_cast<const bf16_t *>(in);
     const bool staged = packed != nullptr;
     Plan pl2;
-    if (staged && reinterpret_cast<uintptr_t>(in) % 16 == 0 && make_plan2(p, g.R, g.S, &pl2))
+    if (staged && reinterpret_cast<uintptr_t>(in) % 16 == 0 && make_plan2(p, g.R, g.S, &pl2)) {
+        pl2.p.stats = stats;
         return launch_tile2_3x3(src, wsrc, out, pl2, st);
+    }
     if (g.R == 1 && g.S == 1) return launch_tile_1x1(src, wsrc, out, pl, staged, st);
     if (g.R == 3 && g.S == 3) return launch_tile_3x3(src, wsrc, out, pl, staged, st);
     return launch_tile_other(g.R, g.S, src, wsrc, out, pl, staged, st);

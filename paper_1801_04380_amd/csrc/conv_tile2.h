@@ -390,6 +390,9 @@ __device__ __forceinline__ void conv_tile2_body(const bf16_t *__restrict__ in, c
     // The second set walks through the epilogue as well (it has the same barriers to meet) but
     // owns no output channel: its channel numbers are past the last.
     const int kst = set == 0 ? k0 : (1 << 29);
+    if (p.stats)
+        tile_bn_partials<NF, 2>(acc, p.TW, min(p.TH, NP - o0), p.Qout - q0, wp, wk, l32, g, kst + wk * 64, p.Kout, p.out_bf16 != 0, p.stats, p.nptiles,
+                                ptile, reinterpret_cast<float *>(smem) + set * 1024);
     if (p.out_bf16) {
         constexpr int EP = EPI_PITCH;
         char *const stage = reinterpret_cast<char *>(smem) + (set * 4 + wave) * 32 * EP;

@@ -399,6 +399,57 @@ sn_status sn_conv2d_fwd(const void *x, const void *w, void *y, const sn_conv_sha
     return conv_call(SN_CONV_FWD, x, w, y, shape, algo, workspace, workspace_bytes, stream);
 }
 
+// Scratch of sn_conv2d_fwd_bn_stats: the per-tile triples of whichever tile kernel runs, or the
+// partial sums of a pass over y where none does.
+static size_t conv_bn_stats_need(const ConvGeom &g)
+{
+    size_t need = bn_stats_scratch_bytes(g.N, g.K, g.P * g.Q);
+    for (int v = 0; v < 4; ++v) {
+        const size_t t = (size_t)tile_conv_stats_tiles(g, (v & 1) != 0, (v & 2) != 0);
+        need = std::max(need, t * g.K * 3 * sizeof(float));
+    }
+    return align_up(need, 256);
+}
+
+size_t sn_conv_bn_stats_scratch_bytes(const sn_conv_shape *shape)
+{
+    ConvGeom g;
+    if (make_geom(shape, &g) != SN_OK) return 0;
+    return conv_bn_stats_need(g);
+}
+
+sn_status sn_conv2d_fwd_bn_stats(const void *x, const void *w, void *y, const sn_conv_shape *shape, sn_conv_algo algo,
+                                 void *workspace, size_t workspace_bytes, float *save_mean, float *save_invstd,
+                                 float eps, void *scratch, size_t scratch_bytes, sn_stream stream)
+{
+    ConvGeom g;
+    sn_status s = make_geom(shape, &g);
+    if (s != SN_OK) return s;
+    if (!x || !w || !y || !aligned(x, 16) || !aligned(w, 16) || !aligned(y, 16)) return SN_ERR_BAD_ARG;
+    if (!save_mean || !save_invstd || !scratch || !aligned(save_mean, 4) || !aligned(save_invstd, 4) ||
+        !aligned(scratch, 16) || !(eps >= 0.f))
+        return SN_ERR_BAD_ARG;
+    if (algo < SN_ALGO_AUTO || algo >= SN_ALGO_COUNT) return SN_ERR_BAD_ARG;
+    s = check_ws(workspace, workspace_bytes);
+    if (s != SN_OK) return s;
+    if (scratch_bytes < conv_bn_stats_need(g)) return SN_ERR_WORKSPACE_TOO_SMALL;
+    s = resolve(shape, g, SN_CONV_FWD, &algo, workspace_bytes);
+    if (s != SN_OK) return s;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float *part = static_cast<float *>(scratch);
+    const bool staged = algo == SN_ALGO_STAGED;
+    if (staged || (algo == SN_ALGO_DIRECT && tile_conv_supported(g, false))) {
+        // the tile kernels take the statistics from their accumulators: y is not read again
+        const int tiles = tile_conv_stats_tiles(g, staged, true);
+        if (tiles <= 0) return SN_ERR_UNSUPPORTED;
+        if (launch_tile_conv(x, w, y, g, false, staged ? workspace : nullptr, st, part) != hipSuccess) return SN_ERR_LAUNCH;
+        return launch_status(launch_bn_finalize_tiles(part, g.K, tiles, save_mean, save_invstd, eps, st));
+    }
+    s = run_fwd(x, w, y, g, algo, workspace, workspace_bytes, st);
+    if (s != SN_OK) return s;
+    return launch_status(launch_bn_stats(y, part, save_mean, save_invstd, g.N, g.K, g.P * g.Q, eps, g.out_bf16, st));
+}
+
 sn_status sn_conv2d_bwd_data(const void *dy, const void *w, void *dx, const sn_conv_shape *shape,
                              sn_conv_algo algo, void *workspace, size_t workspace_bytes, sn_stream stream)
 {
@@ -501,6 +552,20 @@ sn_status sn_bn_relu_fwd(const void *x, const float *gamma, const float *beta, v
     return bn_fwd_common(x, gamma, beta, y, save_mean, save_invstd, N, C, H, W, eps, dtype, 1, stream);
 }
 
+sn_status sn_bn_apply(const void *x, const float *gamma, const float *beta, const float *mean, const float *invstd,
+                      void *y, int N, int C, int H, int W, int relu, sn_dtype dtype, sn_stream stream)
+{
+    sn_status s = check_cheap(N, C, H, W, dtype);
+    if (s != SN_OK) return s;
+    if (!x || !gamma || !beta || !mean || !invstd || !y) return SN_ERR_BAD_ARG;
+    if (!aligned(x, 16) || !aligned(y, 16) || !aligned(gamma, 4) || !aligned(beta, 4) || !aligned(mean, 4) ||
+        !aligned(invstd, 4))
+        return SN_ERR_BAD_ARG;
+    if (C > 65535 * 32) return SN_ERR_UNSUPPORTED;
+    return launch_status(launch_bn_apply(x, gamma, beta, mean, invstd, y, N, C, H * W, dtype == SN_BF16, relu != 0,
+                                         static_cast<hipStream_t>(stream)));
+}
+
 // The shapes the BN + ReLU + 2x2 pool calls take.
 static sn_status check_pool2_pair(int N, int C, int H, int W, int dtype)
 {
@@ -525,6 +590,22 @@ sn_status sn_bn_relu_pool2_fwd(const void *x, const float *gamma, const float *b
         return SN_ERR_BAD_ARG;
     return launch_status(launch_bn_relu_pool2_fwd(x, gamma, beta, pooled, idx, save_mean, save_invstd, N, C, H, W, eps,
                                                   dtype == SN_BF16, static_cast<hipStream_t>(stream)));
+}
+
+sn_status sn_bn_relu_pool2_apply(const void *x, const float *gamma, const float *beta, const float *mean,
+                                 const float *invstd, void *pooled, int32_t *idx, int N, int C, int H, int W,
+                                 sn_dtype dtype, sn_stream stream)
+{
+    sn_status s = check_pool2_pair(N, C, H, W, dtype);
+    if (s != SN_OK) return s;
+    if (!x || !gamma || !beta || !pooled || !idx || !mean || !invstd || x == pooled ||
+        x == static_cast<const void *>(idx) || pooled == static_cast<void *>(idx))
+        return SN_ERR_BAD_ARG;
+    if (!aligned(x, 16) || !aligned(pooled, 16) || !aligned(idx, 16) || !aligned(gamma, 4) || !aligned(beta, 4) ||
+        !aligned(mean, 4) || !aligned(invstd, 4))
+        return SN_ERR_BAD_ARG;
+    return launch_status(launch_bn_relu_pool2_apply(x, gamma, beta, mean, invstd, pooled, idx, N, C, H, W,
+                                                    dtype == SN_BF16, static_cast<hipStream_t>(stream)));
 }
 
 sn_status sn_bn_relu_pool2_bwd(const void *x, const void *dpooled, const int32_t *idx, const float *gamma,

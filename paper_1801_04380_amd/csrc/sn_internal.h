@@ -53,8 +53,12 @@ int generic_bwd_filter_splits(const ConvGeom &g);
 // nullptr to gather the filter from the KCRS tensor inside the kernel.
 bool tile_conv_supported(const ConvGeom &g, bool bwd_data);
 size_t tile_conv_packed_bytes(const ConvGeom &g, bool bwd_data);
+// stats (forward only, may be null): room for tile_conv_stats_tiles(...) * K * 3 floats, where every
+// pixel tile leaves (count, mean, sum of squared deviations) of its outputs per channel, for
+// launch_bn_finalize_tiles.
 hipError_t launch_tile_conv(const void *in, const void *w, void *out, const ConvGeom &g, bool bwd_data,
-                            void *packed, hipStream_t st);
+                            void *packed, hipStream_t st, float *stats = nullptr);
+int tile_conv_stats_tiles(const ConvGeom &g, bool staged, bool in_aligned16);
 
 // Stride-1 bf16 backward-filter fast path.  partial == nullptr: the slices of the
 // (n,p,q) sum combine with atomics into a zero-filled dw; otherwise slice z writes
@@ -99,6 +103,19 @@ hipError_t launch_bn_bwd(const void *x, const void *dy, const float *relu_beta, 
 // 0 if W does not allow any.  Its backward is launch_bn_bwd with dy == nullptr and the pooled
 // gradient, the indices and W in the pool_* arguments (relu_beta set).
 int bn_relu_pool2_vb(int W, int bf16);
+// The last pass of the two calls above alone, from statistics the caller has.
+hipError_t launch_bn_apply(const void *x, const float *gamma, const float *beta, const float *mean,
+                           const float *invstd, void *y, int N, int C, int HW, int bf16, int relu, hipStream_t st);
+hipError_t launch_bn_relu_pool2_apply(const void *x, const float *gamma, const float *beta, const float *mean,
+                                      const float *invstd, void *pooled, int32_t *idx, int N, int C, int H, int W,
+                                      int bf16, hipStream_t st);
+// Statistics alone: from the per-tile triples of launch_tile_conv (part: C * ntiles * 3 floats), or by
+// a pass over x with bn_stats_scratch_bytes of scratch.
+hipError_t launch_bn_finalize_tiles(const float *part, int C, int ntiles, float *mean, float *invstd, float eps,
+                                    hipStream_t st);
+size_t bn_stats_scratch_bytes(int N, int C, int HW);
+hipError_t launch_bn_stats(const void *x, float *scratch, float *mean, float *invstd, int N, int C, int HW, float eps,
+                           int bf16, hipStream_t st);
 hipError_t launch_bn_relu_pool2_fwd(const void *x, const float *gamma, const float *beta, void *pooled, int32_t *idx,
                                     float *mean, float *invstd, int N, int C, int H, int W, float eps, int bf16,
                                     hipStream_t st);

@@ -70,6 +70,20 @@ def test_bad_arguments_are_refused_before_any_launch():
     assert lib.sn_bn_relu_bwd(one, two, one, None, one, one, ctypes.c_void_p(768), one, one, 1, 1, 1, 1, 0, None) == 1
     assert lib.sn_bn_relu_bwd(one, two, one, one, one, one, two, one, one, 1, 1, 1, 1, 0, None) == 1
     assert lib.sn_maxpool_fwd(one, one, one, 1, 1, 4, 4, 2, 2, 2, 2, 2, 0, 0, None) == 1  # pad >= window
+    # CONV forward with the statistics for BN: needs its scratch, large enough
+    s3 = sn.conv_shape(2, 16, 16, 16, 16, 3, 3, (1, 1), (1, 1))
+    need = lib.sn_conv_bn_stats_scratch_bytes(ctypes.byref(s3))
+    assert need >= 256 and need % 256 == 0
+    assert lib.sn_conv_bn_stats_scratch_bytes(ctypes.byref(sn.conv_shape(0, 16, 16, 16, 16, 3, 3))) == 0
+    assert lib.sn_conv2d_fwd_bn_stats(one, one, one, ctypes.byref(s3), 0, None, 0, one, one, 1e-5, None, 0, None) == 1
+    assert lib.sn_conv2d_fwd_bn_stats(one, one, one, ctypes.byref(s3), 0, None, 0, one, one, 1e-5, one, need - 1, None) == 3
+    assert lib.sn_conv2d_fwd_bn_stats(one, one, one, ctypes.byref(s3), 0, None, 0, one, None, 1e-5, one, need, None) == 1
+    assert lib.sn_conv2d_fwd_bn_stats(one, one, one, ctypes.byref(s3), 0, None, 0, one, one, -1.0, one, need, None) == 1
+    # BN from given statistics
+    assert lib.sn_bn_apply(one, one, one, one, None, two, 1, 1, 1, 1, 0, 0, None) == 1
+    assert lib.sn_bn_apply(one, one, one, one, one, two, 1, 1, 0, 1, 0, 0, None) == 1
+    assert lib.sn_bn_relu_pool2_apply(one, one, one, one, one, two, ctypes.c_void_p(768), 1, 1, 5, 8, 1, None) == 2
+    assert lib.sn_bn_relu_pool2_apply(one, one, one, one, one, two, two, 1, 1, 4, 8, 1, None) == 1
     # BN + ReLU + 2x2 pool: odd sizes and rows too short for a vector access are for the separate calls
     three = ctypes.c_void_p(768)
     assert lib.sn_bn_relu_pool2_fwd(one, one, one, two, three, one, one, 1, 1, 5, 8, 1e-5, 1, None) == 2
