@@ -113,7 +113,7 @@ def build_ops(cfg_no, budget, autotune, fuse):
         if autotune:
             t0 = time.time()
             for d, (a, bb, out) in {0: (xd, wd, y), 1: (dy, wd, dx), 2: (xd, dy, dw)}.items():
-                sn.sn_conv_autotune(d, a, bb, out, shape, ws, iters=2)
+                sn.sn_conv_autotune(d, a, bb, out, shape, ws, iters=5)
             torch.cuda.synchronize()
             tune_ms += (time.time() - t0) * 1e3
         for d in (0, 1, 2):
