@@ -175,3 +175,21 @@ def maxpool_bwd(dy, idx, x_shape):
     dx = np.empty(tuple(x_shape), dtype=np.float64)
     _load().sn_oracle_maxpool_bwd(_d(dy), idx.ctypes.data_as(_I), _d(dx), N, C, H, W, P, Q)
     return dx
+
+
+def lrn_fwd(x, size=5, alpha=1e-4, beta=0.75, k=2.0):
+    x = _f64(x)
+    N, C, H, W = x.shape
+    y = np.empty_like(x)
+    _load().sn_oracle_lrn_fwd(_d(x), _d(y), N, C, H, W, int(size), ctypes.c_double(alpha), ctypes.c_double(beta),
+                              ctypes.c_double(k))
+    return y
+
+
+def lrn_bwd(x, dy, size=5, alpha=1e-4, beta=0.75, k=2.0):
+    x, dy = _f64(x), _f64(dy)
+    N, C, H, W = x.shape
+    dx = np.empty_like(x)
+    _load().sn_oracle_lrn_bwd(_d(x), _d(dy), _d(dx), N, C, H, W, int(size), ctypes.c_double(alpha),
+                              ctypes.c_double(beta), ctypes.c_double(k))
+    return dx

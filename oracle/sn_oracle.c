@@ -265,3 +265,57 @@ void sn_oracle_maxpool_bwd(const double *dy, const int32_t *idx, double *dx,
         for (int i = 0; i < P * Q; ++i)
             dx[(size_t)nc * H * W + idx[(size_t)nc * P * Q + i]] += dy[(size_t)nc * P * Q + i];
 }
+
+/* LRN across channels (the LRN1 / LRN2 layers of the paper's AlexNet example, Sec. 4; the paper
+ * prints no formula, this is the normalisation of the AlexNet publication with the window's
+ * alpha divided by the window size, as the cuDNN call the paper's runtime makes does):
+ *   s[n,c,h,w] = k + (alpha / size) * sum_{j = c - size/2 .. c + size/2, 0 <= j < C} x[n,j,h,w]^2,
+ *   y = x * s^(-beta).
+ * size is odd; channels outside [0, C) contribute nothing. */
+static double lrn_scale(const double *x, int C, int HW, size_t base, int c, int size, double alpha, double k)
+{
+    const int half = size / 2;
+    double acc = 0.0;
+    for (int j = c - half; j <= c + half; ++j) {
+        if (j < 0 || j >= C) continue;
+        const double v = x[base + (size_t)j * HW];
+        acc += v * v;
+    }
+    return k + alpha / size * acc;
+}
+
+void sn_oracle_lrn_fwd(const double *x, double *y, int N, int C, int H, int W,
+                       int size, double alpha, double beta, double k)
+{
+    const int HW = H * W;
+    for (int n = 0; n < N; ++n)
+        for (int i = 0; i < HW; ++i) {
+            const size_t base = (size_t)n * C * HW + i;
+            for (int c = 0; c < C; ++c)
+                y[base + (size_t)c * HW] = x[base + (size_t)c * HW] * pow(lrn_scale(x, C, HW, base, c, size, alpha, k), -beta);
+        }
+}
+
+/* LRN backward, the derivative of the above: y_j depends on x_c for every j whose window holds c,
+ *   dx_c = dy_c * s_c^(-beta)
+ *          - (2 * alpha * beta / size) * x_c * sum_{j: |j - c| <= size/2, 0 <= j < C} dy_j * x_j * s_j^(-beta-1). */
+void sn_oracle_lrn_bwd(const double *x, const double *dy, double *dx, int N, int C, int H, int W,
+                       int size, double alpha, double beta, double k)
+{
+    const int HW = H * W, half = size / 2;
+    for (int n = 0; n < N; ++n)
+        for (int i = 0; i < HW; ++i) {
+            const size_t base = (size_t)n * C * HW + i;
+            for (int c = 0; c < C; ++c) {
+                const size_t e = base + (size_t)c * HW;
+                double acc = 0.0;
+                for (int j = c - half; j <= c + half; ++j) {
+                    if (j < 0 || j >= C) continue;
+                    const size_t ej = base + (size_t)j * HW;
+                    acc += dy[ej] * x[ej] * pow(lrn_scale(x, C, HW, base, j, size, alpha, k), -beta - 1.0);
+                }
+                dx[e] = dy[e] * pow(lrn_scale(x, C, HW, base, c, size, alpha, k), -beta)
+                        - 2.0 * alpha * beta / size * x[e] * acc;
+            }
+        }
+}

@@ -191,3 +191,52 @@ def test_pool_finite_differences_away_from_ties():
             e[0, 0, i, j] = 1e-3
             fd = (loss(x + e) - loss(x - e)) / 2e-3
             assert abs(fd - dx[0, 0, i, j]) < 1e-9
+
+
+# ----------------------------------------------------------------- LRN
+def test_lrn_hand_example():
+    # one pixel, three channels 1, 2, 3; size 3, alpha 3 (so alpha / size = 1), beta 1, k 1:
+    # s = 1 + (1 + 4), 1 + (1 + 4 + 9), 1 + (4 + 9) = 6, 15, 14
+    x = np.array([1.0, 2.0, 3.0]).reshape(1, 3, 1, 1)
+    y = oracle.lrn_fwd(x, size=3, alpha=3.0, beta=1.0, k=1.0).ravel()
+    assert np.allclose(y, [1 / 6, 2 / 15, 3 / 14], rtol=1e-15, atol=0)
+    # dy = (1, 0, 0): dx_0 = 1/6 - 2*1*1*(1*1/36) = 1/6 - 1/18, dx_1 = -2*2*(1/36), dx_2 = 0 (channel 0's window ends at 1)
+    dx = oracle.lrn_bwd(x, np.array([1.0, 0.0, 0.0]).reshape(1, 3, 1, 1), size=3, alpha=3.0, beta=1.0, k=1.0).ravel()
+    assert np.allclose(dx, [1 / 6 - 1 / 18, -4 / 36, 0.0], rtol=1e-14, atol=1e-16)
+
+
+def test_lrn_special_cases():
+    x = RNG.standard_normal((2, 7, 3, 4))
+    dy = RNG.standard_normal(x.shape)
+    # a window of one channel: elementwise
+    y = oracle.lrn_fwd(x, size=1, alpha=0.3, beta=0.75, k=2.0)
+    assert np.allclose(y, x / (2.0 + 0.3 * x * x) ** 0.75, rtol=1e-14)
+    # alpha = 0: a constant factor both ways
+    assert np.allclose(oracle.lrn_fwd(x, 5, 0.0, 0.75, 2.0), x * 2.0 ** -0.75, rtol=1e-15)
+    assert np.allclose(oracle.lrn_bwd(x, dy, 5, 0.0, 0.75, 2.0), dy * 2.0 ** -0.75, rtol=1e-15)
+    # all channels equal to v: the window of channel c holds min(c, h) + min(C-1-c, h) + 1 channels
+    C, size, v = 9, 5, 1.5
+    xc = np.full((1, C, 2, 2), v)
+    cnt = np.array([min(c, 2) + min(C - 1 - c, 2) + 1 for c in range(C)], dtype=np.float64)
+    want = v / (1.0 + 0.5 / size * cnt * v * v) ** 0.75
+    assert np.allclose(oracle.lrn_fwd(xc, size, 0.5, 0.75, 1.0)[0, :, 1, 1], want, rtol=1e-14)
+
+
+def test_lrn_matches_torch_and_finite_differences():
+    x = RNG.standard_normal((2, 11, 3, 5)) * 2.0
+    dy = RNG.standard_normal(x.shape)
+    for size, alpha, beta, k in ((5, 1e-1, 0.75, 2.0), (3, 0.7, 0.5, 1.0), (7, 2.0, 1.25, 0.5)):
+        xt = torch.tensor(x, dtype=torch.float64, requires_grad=True)
+        yt = torch.nn.functional.local_response_norm(xt, size, alpha=alpha, beta=beta, k=k)
+        yt.backward(torch.tensor(dy))
+        assert np.allclose(oracle.lrn_fwd(x, size, alpha, beta, k), yt.detach().numpy(), rtol=1e-12, atol=1e-14)
+        dx = oracle.lrn_bwd(x, dy, size, alpha, beta, k)
+        assert np.allclose(dx, xt.grad.numpy(), rtol=1e-11, atol=1e-13)
+        # central differences of sum(dy * y) in a few coordinates
+        f = lambda z: float((dy * oracle.lrn_fwd(z, size, alpha, beta, k)).sum())
+        for idx in [(0, 0, 0, 0), (1, 5, 2, 3), (0, 10, 1, 4), (1, 1, 0, 2)]:
+            h = 1e-6
+            xp, xm = x.copy(), x.copy()
+            xp[idx] += h
+            xm[idx] -= h
+            assert abs((f(xp) - f(xm)) / (2 * h) - dx[idx]) <= 1e-7 * max(1.0, abs(dx[idx]))
