@@ -166,6 +166,13 @@ def build_ops(cfg_no, budget, autotune, fuse):
                 act_in = ybn
             cheap_f.append(Op("relu_fwd", layer.name, lambda s=act_in, o=a: sn.sn_relu_fwd(s, o), nbytes=2 * E * b))
         g_a = torch.empty_like(y)
+        pool_src, pool_grad = a, g_a
+        if layer.lrn and not pool_pair:
+            # LRN between the ReLU and the pool; its backward needs its input and the gradient only
+            a_l, g_l = torch.empty_like(y), torch.empty_like(y)
+            cheap_f.append(Op("lrn_fwd", layer.name, lambda s=a, o=a_l, p=layer.lrn: sn.sn_lrn_fwd(s, o, *p),
+                              nbytes=2 * E * b))
+            pool_src, pool_grad = a_l, g_l
         if layer.pool:
             kernel, stride = layer.pool
             PP, QQ = sn.sn_out_dim(P, 0, kernel[0], stride[0]), sn.sn_out_dim(Q, 0, kernel[1], stride[1])
@@ -185,13 +192,16 @@ def build_ops(cfg_no, budget, autotune, fuse):
                               nbytes=Eo * (b + 4) + 2 * E * b))
         elif layer.pool:
             cheap_f.append(Op("maxpool_fwd", layer.name,
-                              lambda s=a, o=pooled, i=idx, k=kernel, st=stride: sn.sn_maxpool_fwd(s, o, i, k, st),
+                              lambda s=pool_src, o=pooled, i=idx, k=kernel, st=stride: sn.sn_maxpool_fwd(s, o, i, k, st),
                               nbytes=E * b + Eo * (b + 4)))
             cheap_b.append(Op("maxpool_bwd", layer.name,
-                              lambda g=g_pool, i=idx, o=g_a, k=kernel, st=stride: sn.sn_maxpool_bwd(g, i, o, k, st),
+                              lambda g=g_pool, i=idx, o=pool_grad, k=kernel, st=stride: sn.sn_maxpool_bwd(g, i, o, k, st),
                               nbytes=Eo * (b + 4) + E * b))
         else:
-            g_a.copy_(dy)
+            pool_grad.copy_(dy)
+        if layer.lrn and not pool_pair:
+            cheap_b.append(Op("lrn_bwd", layer.name,
+                              lambda s=a, g=g_l, o=g_a, p=layer.lrn: sn.sn_lrn_bwd(s, g, o, *p), nbytes=3 * E * b))
         if pool_pair:
             pass
         elif cfg["bn"] and fuse:

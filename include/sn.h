@@ -245,6 +245,24 @@ sn_status sn_bn_relu_pool2_bwd(const void *x, const void *dpooled, const int32_t
                                void *dx, float *dgamma, float *dbeta,
                                int N, int C, int H, int W, sn_dtype dtype, sn_stream stream);
 
+/* LRN across channels, one of the cheap layers that recomputation replays (Sec. 3.4) and the
+ * LRN1 / LRN2 layers of the AlexNet example (Sec. 4).  The paper prints no formula; this is the
+ * AlexNet normalisation with alpha divided by the window size (the convention of the library call
+ * the paper's runtime makes):
+ *   s[n,c,h,w] = k + (alpha / size) * sum over j in [c - size/2, c + size/2], 0 <= j < C, of x[n,j,h,w]^2,
+ *   y = x * s^(-beta).
+ * size odd, at most 9 (SN_ERR_UNSUPPORTED beyond); alpha >= 0, k > 0.  x, y of `dtype`
+ * [N][C][H][W], arithmetic in fp32.  y must not alias x. */
+sn_status sn_lrn_fwd(const void *x, void *y, int N, int C, int H, int W,
+                     int size, float alpha, float beta, float k, sn_dtype dtype, sn_stream stream);
+
+/* LRN backward from x and dy alone (s is recomputed, y is not needed):
+ *   dx_c = dy_c * s_c^(-beta) - (2 * alpha * beta / size) * x_c * sum over j with |j - c| <= size/2
+ *          of dy_j * x_j * s_j^(-beta-1).
+ * dx must alias neither x nor dy. */
+sn_status sn_lrn_bwd(const void *x, const void *dy, void *dx, int N, int C, int H, int W,
+                     int size, float alpha, float beta, float k, sn_dtype dtype, sn_stream stream);
+
 /* POOL (max) forward, the paper's example of a cheap-to-recompute layer
  * (Sec. 3.4).  Window kh x kw, stride, padding (pad < window; padded positions
  * never win).  Of equal maxima the first in row-major window order wins.

@@ -42,6 +42,8 @@ SIGNATURES = {
     "sn_bn_relu_bwd": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp]),  # x, dy, gamma, beta, ...
     "sn_bn_relu_pool2_fwd": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, ctypes.c_float, _i, _vp]),
     "sn_bn_relu_pool2_bwd": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp]),
+    "sn_lrn_fwd": (_i, [_vp, _vp, _i, _i, _i, _i, _i, ctypes.c_float, ctypes.c_float, ctypes.c_float, _i, _vp]),
+    "sn_lrn_bwd": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, ctypes.c_float, ctypes.c_float, ctypes.c_float, _i, _vp]),
     "sn_maxpool_fwd": (_i, [_vp, _vp, _vp] + [_i] * 10 + [_i, _vp]),
     "sn_maxpool_bwd": (_i, [_vp, _vp, _vp] + [_i] * 10 + [_i, _vp]),
 }

@@ -16,7 +16,7 @@ __all__ = [
     "sn_planner_record", "sn_planner_clear", "sn_conv_autotune",
     "sn_conv2d_fwd", "sn_conv2d_bwd_data", "sn_conv2d_bwd_filter",
     "sn_conv_bn_stats_scratch_bytes", "sn_conv2d_fwd_bn_stats", "sn_bn_apply", "sn_bn_relu_pool2_apply",
-    "sn_relu_fwd", "sn_relu_bwd", "sn_bn_fwd", "sn_bn_relu_fwd", "sn_bn_bwd", "sn_bn_relu_bwd", "sn_bn_relu_pool2_fwd", "sn_bn_relu_pool2_bwd", "sn_maxpool_fwd", "sn_maxpool_bwd",
+    "sn_relu_fwd", "sn_relu_bwd", "sn_bn_fwd", "sn_bn_relu_fwd", "sn_bn_bwd", "sn_bn_relu_bwd", "sn_bn_relu_pool2_fwd", "sn_bn_relu_pool2_bwd", "sn_lrn_fwd", "sn_lrn_bwd", "sn_maxpool_fwd", "sn_maxpool_bwd",
 ]
 
 SN_F32, SN_BF16 = 0, 1
@@ -193,6 +193,18 @@ def sn_bn_relu_pool2_bwd(x, dpooled, idx, gamma, beta, save_mean, save_invstd, d
     _check("sn_bn_relu_pool2_bwd", load().sn_bn_relu_pool2_bwd(
         _ptr(x), _ptr(dpooled), _ptr(idx), _ptr(gamma), _ptr(beta), _ptr(save_mean), _ptr(save_invstd), _ptr(dx),
         _ptr(dgamma), _ptr(dbeta), N, C, H, W, _dtype_code(x), _stream()))
+
+
+def sn_lrn_fwd(x, y, size=5, alpha=1e-4, beta=0.75, k=2.0):
+    N, C, H, W = x.shape
+    _check("sn_lrn_fwd", load().sn_lrn_fwd(_ptr(x), _ptr(y), N, C, H, W, size, alpha, beta, k, _dtype_code(x),
+                                           _stream()))
+
+
+def sn_lrn_bwd(x, dy, dx, size=5, alpha=1e-4, beta=0.75, k=2.0):
+    N, C, H, W = x.shape
+    _check("sn_lrn_bwd", load().sn_lrn_bwd(_ptr(x), _ptr(dy), _ptr(dx), N, C, H, W, size, alpha, beta, k,
+                                           _dtype_code(x), _stream()))
 
 
 def sn_maxpool_fwd(x, y, idx, kernel, stride, pad=(0, 0)):

@@ -1025,6 +1025,131 @@ maxpool2_bwd_kernel(const T *__restrict__ dy, const int32_t *__restrict__ idx, T
     }
 }
 
+// ------------------------------------------------------------------ LRN
+// LRN across channels (definition in sn.h).  A thread owns VEC neighbouring positions of one
+// image and walks the channels, which are H*W elements apart, so a wave reads one contiguous run
+// per channel; the window of the last 2 HALF + 1 channels lives in registers (a shift per step),
+// so x is read once.  s^(-beta) = exp2(-beta log2 s) on the transcendental unit (s >= k > 0).
+// Backward needs, for channel c, the terms r_j = dy_j x_j s_j^(-beta-1) of the channels around
+// it, each of which needs the window around j: the loop runs HALF channels ahead for s_j and
+// another HALF ahead for x, with r, s^(-beta) and dy of the channels in between in registers;
+// x and dy are read once, the forward output is not needed.  The channel loops are unrolled so
+// that the loads of several channels are in flight at once: nothing else hides their latency.
+template <typename T, int VEC> struct LrnIo {
+    static constexpr int VB = VEC * (int)sizeof(T);
+    __device__ static void load(const T *p, float (&f)[VEC])
+    {
+        if constexpr (VEC == 1) f[0] = ld<T>(p);
+        else unpack<T, VB>(*reinterpret_cast<const typename RawVec<VB>::type *>(p), f);
+    }
+    __device__ static void store(T *p, const float (&f)[VEC])
+    {
+        if constexpr (VEC == 1) st(p, f[0]);
+        else *reinterpret_cast<typename RawVec<VB>::type *>(p) = pack<T, VB>(f);
+    }
+};
+
+__device__ inline float pow_neg(float s, float beta) { return __builtin_amdgcn_exp2f(-beta * __builtin_amdgcn_logf(s)); }
+
+template <typename T, int VEC, int HALF>
+__global__ void __launch_bounds__(256)
+lrn_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, int C, int HW, int vpp, size_t total, float a_n,
+               float beta, float k)
+{
+    constexpr int SIZE = 2 * HALF + 1;
+    const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= total) return;
+    const size_t n = t / vpp, off = n * (size_t)C * HW + (t - n * vpp) * VEC;
+    float xr[SIZE][VEC];   // after channel m has been pushed: xr[i] = channel m - (SIZE - 1) + i, zeros outside [0, C)
+#pragma unroll
+    for (int i = 0; i < SIZE; ++i)
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) xr[i][v] = 0.f;
+#pragma unroll 8
+    for (int m = 0; m < C + HALF; ++m) {
+#pragma unroll
+        for (int i = 0; i + 1 < SIZE; ++i)
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) xr[i][v] = xr[i + 1][v];
+        if (m < C) {
+            LrnIo<T, VEC>::load(x + off + (size_t)m * HW, xr[SIZE - 1]);
+        } else {
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) xr[SIZE - 1][v] = 0.f;
+        }
+        const int c = m - HALF;
+        if (c < 0) continue;
+        float out[VEC];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            float sum = 0.f;
+#pragma unroll
+            for (int i = 0; i < SIZE; ++i) sum = __builtin_fmaf(xr[i][v], xr[i][v], sum);
+            out[v] = xr[HALF][v] * pow_neg(__builtin_fmaf(a_n, sum, k), beta);
+        }
+        LrnIo<T, VEC>::store(y + off + (size_t)c * HW, out);
+    }
+}
+
+template <typename T, int VEC, int HALF>
+__global__ void __launch_bounds__(256)
+lrn_bwd_kernel(const T *__restrict__ x, const T *__restrict__ dy, T *__restrict__ dx, int C, int HW, int vpp,
+               size_t total, float a_n, float beta, float k)
+{
+    constexpr int SIZE = 2 * HALF + 1, H1 = HALF + 1;
+    const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= total) return;
+    const size_t n = t / vpp, off = n * (size_t)C * HW + (t - n * vpp) * VEC;
+    const float coef = 2.f * a_n * beta;
+    float xr[SIZE][VEC], rr[SIZE][VEC];   // x of channels m - 2 HALF .. m; r of channels j - 2 HALF .. j (j = m - HALF)
+    float pr[H1][VEC], gr[H1][VEC];       // s^(-beta) and dy of channels j - HALF .. j
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) {
+#pragma unroll
+        for (int i = 0; i < SIZE; ++i) xr[i][v] = rr[i][v] = 0.f;
+#pragma unroll
+        for (int i = 0; i < H1; ++i) pr[i][v] = gr[i][v] = 0.f;
+    }
+#pragma unroll 8
+    for (int m = 0; m < C + 2 * HALF; ++m) {
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+#pragma unroll
+            for (int i = 0; i + 1 < SIZE; ++i) { xr[i][v] = xr[i + 1][v]; rr[i][v] = rr[i + 1][v]; }
+#pragma unroll
+            for (int i = 0; i + 1 < H1; ++i) { pr[i][v] = pr[i + 1][v]; gr[i][v] = gr[i + 1][v]; }
+            xr[SIZE - 1][v] = 0.f;
+            rr[SIZE - 1][v] = pr[H1 - 1][v] = gr[H1 - 1][v] = 0.f;
+        }
+        if (m < C) LrnIo<T, VEC>::load(x + off + (size_t)m * HW, xr[SIZE - 1]);
+        const int j = m - HALF;   // the channel whose window is complete: x_j = xr[HALF]
+        if (j < 0) continue;
+        if (j < C) {
+            LrnIo<T, VEC>::load(dy + off + (size_t)j * HW, gr[H1 - 1]);
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+                float sum = 0.f;
+#pragma unroll
+                for (int i = 0; i < SIZE; ++i) sum = __builtin_fmaf(xr[i][v], xr[i][v], sum);
+                const float s = __builtin_fmaf(a_n, sum, k), p = pow_neg(s, beta);
+                pr[H1 - 1][v] = p;
+                rr[SIZE - 1][v] = gr[H1 - 1][v] * xr[HALF][v] * (p / s);
+            }
+        }
+        const int c = j - HALF;   // every r of its window is known: x_c = xr[0], dy_c = gr[0], s_c^(-beta) = pr[0]
+        if (c < 0) continue;
+        float out[VEC];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            float acc = 0.f;
+#pragma unroll
+            for (int i = 0; i < SIZE; ++i) acc += rr[i][v];
+            out[v] = gr[0][v] * pr[0][v] - coef * xr[0][v] * acc;
+        }
+        LrnIo<T, VEC>::store(dx + off + (size_t)c * HW, out);
+    }
+}
+
 template <typename F> hipError_t by_dtype(int bf16, F f)
 {
     if (bf16) f((bf16_t *)nullptr);
@@ -1251,6 +1376,41 @@ hipError_t launch_bn_bwd(const void *x, const void *dy, const float *relu_beta, 
         hipLaunchKernelGGL(bn_bwd_apply_kernel<T>, grid, block, 0, s, (const T *)x, gs, relu_beta,
                            (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW, sl);
     });
+}
+
+template <typename T, int VEC>
+hipError_t lrn_launch(bool bwd, const void *x, const void *dy, void *out, int N, int C, int HW, int half, float a_n,
+                      float beta, float k, hipStream_t s)
+{
+    const int vpp = HW / VEC;
+    const size_t total = (size_t)N * vpp;
+    const dim3 grid((unsigned)((total + 255) / 256)), block(256);
+#define SN_LRN(H_)                                                                                                  \
+    case H_:                                                                                                        \
+        if (bwd) hipLaunchKernelGGL((lrn_bwd_kernel<T, VEC, H_>), grid, block, 0, s, (const T *)x, (const T *)dy,  \
+                                    (T *)out, C, HW, vpp, total, a_n, beta, k);                                    \
+        else hipLaunchKernelGGL((lrn_fwd_kernel<T, VEC, H_>), grid, block, 0, s, (const T *)x, (T *)out, C, HW,    \
+                                vpp, total, a_n, beta, k);                                                          \
+        break;
+    switch (half) {
+        SN_LRN(0) SN_LRN(1) SN_LRN(2) SN_LRN(3) SN_LRN(4)
+    default: return hipErrorInvalidValue;
+    }
+#undef SN_LRN
+    return hipGetLastError();
+}
+
+// size: odd, at most 9.  dy == nullptr: forward (out = y); else backward (out = dx).
+hipError_t launch_lrn(const void *x, const void *dy, void *out, int N, int C, int HW, int size, float alpha,
+                      float beta, float k, int bf16, hipStream_t s)
+{
+    if (size < 1 || size > 9 || !(size & 1)) return hipErrorInvalidValue;
+    const bool bwd = dy != nullptr, vec = HW % 4 == 0;
+    const float a_n = alpha / (float)size;
+    if (bf16) return vec ? lrn_launch<bf16_t, 4>(bwd, x, dy, out, N, C, HW, size / 2, a_n, beta, k, s)
+                         : lrn_launch<bf16_t, 1>(bwd, x, dy, out, N, C, HW, size / 2, a_n, beta, k, s);
+    return vec ? lrn_launch<float, 4>(bwd, x, dy, out, N, C, HW, size / 2, a_n, beta, k, s)
+               : lrn_launch<float, 1>(bwd, x, dy, out, N, C, HW, size / 2, a_n, beta, k, s);
 }
 
 hipError_t launch_maxpool_fwd(const void *x, void *y, int32_t *idx, int NC, int H, int W, int P, int Q, int kh,

@@ -657,6 +657,32 @@ sn_status sn_bn_relu_bwd(const void *x, const void *dy, const float *gamma, cons
     return bn_bwd_common(x, dy, beta, gamma, save_mean, save_invstd, dx, dgamma, dbeta, N, C, H, W, dtype, stream);
 }
 
+static sn_status lrn_common(const void *x, const void *dy, void *out, int N, int C, int H, int W, int size,
+                            float alpha, float beta, float k, sn_dtype dtype, sn_stream stream, bool bwd)
+{
+    sn_status s = check_cheap(N, C, H, W, dtype);
+    if (s != SN_OK) return s;
+    if (!x || !out || (bwd && !dy) || out == x || (bwd && out == dy)) return SN_ERR_BAD_ARG;
+    if (!aligned(x, 16) || !aligned(out, 16) || (bwd && !aligned(dy, 16))) return SN_ERR_BAD_ARG;
+    if (size < 1 || !(size & 1) || !(alpha >= 0.f) || !(k > 0.f) || !(beta == beta)) return SN_ERR_BAD_ARG;
+    if (size > 9) return SN_ERR_UNSUPPORTED;
+    if ((long long)N * H * W / 256 > 0x7fffffffLL) return SN_ERR_UNSUPPORTED;
+    return launch_status(launch_lrn(x, bwd ? dy : nullptr, out, N, C, H * W, size, alpha, beta, k, dtype == SN_BF16,
+                                    static_cast<hipStream_t>(stream)));
+}
+
+sn_status sn_lrn_fwd(const void *x, void *y, int N, int C, int H, int W, int size, float alpha, float beta, float k,
+                     sn_dtype dtype, sn_stream stream)
+{
+    return lrn_common(x, nullptr, y, N, C, H, W, size, alpha, beta, k, dtype, stream, false);
+}
+
+sn_status sn_lrn_bwd(const void *x, const void *dy, void *dx, int N, int C, int H, int W, int size, float alpha,
+                     float beta, float k, sn_dtype dtype, sn_stream stream)
+{
+    return lrn_common(x, dy, dx, N, C, H, W, size, alpha, beta, k, dtype, stream, true);
+}
+
 static sn_status check_pool(int N, int C, int H, int W, int kh, int kw, int sh, int sw, int ph, int pw, int dtype,
                             int *P, int *Q)
 {

@@ -13,12 +13,13 @@ import torch
 # One convolution layer.  relu_in: its input comes after a ReLU (so it is drawn
 # as max(N(0,1), 0)); pool: (kernel, stride) of the max-pool that follows, or
 # None; mult: how many times the shape occurs in the network; first: the image
-# layer (its backward-data is reported apart).
-Layer = namedtuple("Layer", "name C H W K R S stride pad relu_in pool mult first")
+# layer (its backward-data is reported apart); lrn: (size, alpha, beta, k) of the LRN
+# between the ReLU and the pool, or None.
+Layer = namedtuple("Layer", "name C H W K R S stride pad relu_in pool mult first lrn")
 
 
-def _L(name, C, H, W, K, R, S, stride=(1, 1), pad=(0, 0), relu_in=True, pool=None, mult=1, first=False):
-    return Layer(name, C, H, W, K, R, S, stride, pad, relu_in, pool, mult, first)
+def _L(name, C, H, W, K, R, S, stride=(1, 1), pad=(0, 0), relu_in=True, pool=None, mult=1, first=False, lrn=None):
+    return Layer(name, C, H, W, K, R, S, stride, pad, relu_in, pool, mult, first, lrn)
 
 
 def out_hw(layer):
@@ -41,8 +42,10 @@ def _vgg16():
 
 def _alexnet():
     return [
-        _L("conv1", 3, 227, 227, 96, 11, 11, (4, 4), (0, 0), relu_in=False, pool=((3, 3), (2, 2)), first=True),
-        _L("conv2", 96, 27, 27, 256, 5, 5, (1, 1), (2, 2), pool=((3, 3), (2, 2))),
+        # CONV -> ReLU -> LRN -> POOL, as in the paper's AlexNet example (Sec. 4); AlexNet's LRN constants
+        _L("conv1", 3, 227, 227, 96, 11, 11, (4, 4), (0, 0), relu_in=False, pool=((3, 3), (2, 2)), first=True,
+           lrn=(5, 1e-4, 0.75, 2.0)),
+        _L("conv2", 96, 27, 27, 256, 5, 5, (1, 1), (2, 2), pool=((3, 3), (2, 2)), lrn=(5, 1e-4, 0.75, 2.0)),
         _L("conv3", 256, 13, 13, 384, 3, 3, (1, 1), (1, 1)),
         _L("conv4", 384, 13, 13, 384, 3, 3, (1, 1), (1, 1)),
         _L("conv5", 384, 13, 13, 256, 3, 3, (1, 1), (1, 1), pool=((3, 3), (2, 2))),

@@ -1,4 +1,4 @@
-"""GPU parity of the cheap layers (ReLU, BN, max-pool) against the fp64 oracle.
+"""GPU parity of the cheap layers (ReLU, BN, LRN, max-pool) against the fp64 oracle.
 
 Bars: pool indices bit-exact; values relative L2 <= 1e-5 (fp32 storage) or
 <= 5e-3 (bf16 storage, oracle fed the bf16-rounded inputs).  ReLU and pool
@@ -227,6 +227,30 @@ def test_bn_relu_pool2_unsupported():
     with pytest.raises(sn.SnError) as e:
         sn.sn_bn_relu_pool2_fwd(x, one, one, pooled, idx, one.clone(), one.clone())
     assert e.value.status == 2   # SN_ERR_UNSUPPORTED
+
+
+LRN_SHAPES = [(2, 16, 8, 8), (2, 96, 27, 27), (1, 3, 5, 7), (3, 2, 4, 4), (2, 1, 3, 3), (2, 256, 13, 13),
+              (4, 40, 16, 20)]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("params", [(5, 1e-4, 0.75, 2.0), (3, 1.0, 0.5, 1.0), (9, 2.0, 1.25, 0.5), (1, 0.3, 0.75, 2.0),
+                                    (7, 0.0, 0.75, 2.0)], ids=lambda p: "n%d_a%g" % (p[0], p[1]))
+@pytest.mark.parametrize("shape", LRN_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_lrn(shape, params, dtype):
+    size, alpha, beta, k = params
+    seed = shape[1] * 100 + shape[2] + size
+    x = wl.activation(shape, dtype, seed, scale=2.0)
+    dy = wl.activation(shape, dtype, seed + 1)
+    xd, dyd = x.cuda(), dy.cuda()
+    y = torch.full_like(xd, float("nan"))
+    dx = torch.full_like(xd, float("nan"))
+    sn.sn_lrn_fwd(xd, y, size, alpha, beta, k)
+    sn.sn_lrn_bwd(xd, dyd, dx, size, alpha, beta, k)
+    torch.cuda.synchronize()
+    tol = TOL[dtype]
+    assert rel_l2(f64(y), oracle.lrn_fwd(f64(x), size, alpha, beta, k)) <= tol
+    assert rel_l2(f64(dx), oracle.lrn_bwd(f64(x), f64(dy), size, alpha, beta, k)) <= tol
 
 
 POOL_CASES = [((2, 16, 16, 16), (2, 2), (2, 2), (0, 0)), ((2, 8, 55, 55), (3, 3), (2, 2), (0, 0)),
