@@ -897,27 +897,31 @@ maxpool_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, int32_t *__restri
     idx[o] = best;
 }
 
-template <typename T>
+// One thread per input element; a workgroup stays inside one plane (bpp workgroups per plane), so
+// the plane number is a scalar.  K > 0: a K x K window with stride 2 (3x3 / stride 2 is the
+// overlapping pool of the AlexNet- and Inception-style workloads), whose window bounds need no
+// division; K == 0: the window and stride of the arguments.
+template <typename T, int K>
 __global__ void __launch_bounds__(256)
-maxpool_bwd_kernel(const T *__restrict__ dy, const int32_t *__restrict__ idx, T *__restrict__ dx, size_t total,
+maxpool_bwd_kernel(const T *__restrict__ dy, const int32_t *__restrict__ idx, T *__restrict__ dx, unsigned bpp,
                    int H, int W, int P, int Q, int kh, int kw, int sh, int sw, int ph, int pw)
 {
-    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (e >= total) return;
-    const int HW = H * W;
-    const size_t nc = e / HW;
-    const int hw = (int)(e - nc * HW), h = hw / W, v = hw - h * W;
+    const unsigned nc = blockIdx.x / bpp;
+    const int hw = (int)((blockIdx.x - nc * bpp) * 256 + threadIdx.x), HW = H * W;
+    if (hw >= HW) return;
+    const int h = hw / W, v = hw - h * W;
+    if (K > 0) { kh = kw = K; sh = sw = 2; }
     // windows p with p*sh - ph <= h < p*sh - ph + kh
     const int pnum = h + ph - kh + 1, qnum = v + pw - kw + 1;
     const int p0 = pnum > 0 ? (pnum + sh - 1) / sh : 0, p1 = min((h + ph) / sh, P - 1);
     const int q0 = qnum > 0 ? (qnum + sw - 1) / sw : 0, q1 = min((v + pw) / sw, Q - 1);
-    const T *gp = dy + nc * (size_t)P * Q;
-    const int32_t *ip = idx + nc * (size_t)P * Q;
+    const T *gp = dy + (size_t)nc * P * Q;
+    const int32_t *ip = idx + (size_t)nc * P * Q;
     float acc = 0.f;
     for (int p = p0; p <= p1; ++p)
         for (int q = q0; q <= q1; ++q)
             if (ip[p * Q + q] == hw) acc += ld<T>(gp + p * Q + q);
-    st(dx + e, acc);
+    st(dx + (size_t)nc * HW + hw, acc);
 }
 
 // 2x2 windows, stride 2, no padding (the pool of the VGG-style workloads): windows do not
@@ -1449,11 +1453,17 @@ hipError_t launch_maxpool_bwd(const void *dy, const int32_t *idx, void *dx, int 
                                idx, (T *)dx, rows, H, W, P, Q, lg);
         });
     }
+    const unsigned bpp = (unsigned)(((long long)H * W + 255) / 256);
+    if ((unsigned long long)bpp * (unsigned)NC > 0x7fffffffULL) return hipErrorInvalidValue;
     return by_dtype(bf16, [&](auto *tag) {
         typedef typename std::remove_pointer<decltype(tag)>::type T;
-        dim3 grid((unsigned)((total + 255) / 256)), block(256);
-        hipLaunchKernelGGL(maxpool_bwd_kernel<T>, grid, block, 0, s, (const T *)dy, idx, (T *)dx, total, H, W, P,
-                           Q, kh, kw, sh, sw, ph, pw);
+        dim3 grid(bpp * (unsigned)NC), block(256);
+        if (kh == 3 && kw == 3 && sh == 2 && sw == 2)
+            hipLaunchKernelGGL((maxpool_bwd_kernel<T, 3>), grid, block, 0, s, (const T *)dy, idx, (T *)dx, bpp, H, W, P,
+                               Q, kh, kw, sh, sw, ph, pw);
+        else
+            hipLaunchKernelGGL((maxpool_bwd_kernel<T, 0>), grid, block, 0, s, (const T *)dy, idx, (T *)dx, bpp, H, W, P,
+                               Q, kh, kw, sh, sw, ph, pw);
     });
 }
 
