@@ -114,3 +114,81 @@ def test_cheap_layers_full_size():
     gp = wl.activation((32, 64, 112, 112), "bf16", seed=79)
     sn.sn_maxpool_bwd(gp.cuda(), idx, out, (2, 2), (2, 2))
     assert np.array_equal(f64(out), oracle.maxpool_bwd(f64(gp), pio, shape))
+
+
+def test_fused_cheap_layers_full_size():
+    """The one-call forms the benchmark step uses, on the largest activation of the VGG-shaped
+    configuration: bit-identical to the separate calls (which the test above holds against the oracle)."""
+    shape = (32, 64, 224, 224)
+    N, C, H, W = shape
+    xd = wl.activation(shape, "bf16", seed=77).cuda()
+    gamma, beta = (t.cuda() for t in wl.bn_params(C, 5))
+    new = lambda: torch.empty(C, device="cuda")
+    # separate calls
+    a, mean, invstd = torch.empty_like(xd), new(), new()
+    sn.sn_bn_relu_fwd(xd, gamma, beta, a, mean, invstd)
+    pooled_ref = torch.empty((N, C, H // 2, W // 2), dtype=torch.bfloat16, device="cuda")
+    idx_ref = torch.empty((N, C, H // 2, W // 2), dtype=torch.int32, device="cuda")
+    sn.sn_maxpool_fwd(a, pooled_ref, idx_ref, (2, 2), (2, 2))
+    gp = wl.activation((N, C, H // 2, W // 2), "bf16", seed=79).cuda()
+    g = torch.empty_like(xd)
+    sn.sn_maxpool_bwd(gp, idx_ref, g, (2, 2), (2, 2))
+    gr = torch.empty_like(xd)
+    sn.sn_relu_bwd(a, g, gr)
+    dx_ref, dg_ref, db_ref = torch.empty_like(xd), new(), new()
+    sn.sn_bn_bwd(xd, gr, gamma, mean, invstd, dx_ref, dg_ref, db_ref)
+    del g, gr
+    # BN + ReLU backward from x alone
+    g2 = torch.empty_like(xd)
+    sn.sn_maxpool_bwd(gp, idx_ref, g2, (2, 2), (2, 2))
+    dx, dg, db = torch.empty_like(xd), new(), new()
+    sn.sn_bn_relu_bwd(xd, g2, gamma, beta, mean, invstd, dx, dg, db)
+    torch.cuda.synchronize()
+    assert torch.equal(dx, dx_ref) and torch.equal(dg, dg_ref) and torch.equal(db, db_ref)
+    del g2
+    # BN + ReLU + pool, forward and backward, and the forward from given statistics
+    pooled, idx = torch.empty_like(pooled_ref), torch.empty_like(idx_ref)
+    m2, i2 = new(), new()
+    sn.sn_bn_relu_pool2_fwd(xd, gamma, beta, pooled, idx, m2, i2)
+    dx.fill_(float("nan"))
+    sn.sn_bn_relu_pool2_bwd(xd, gp, idx, gamma, beta, m2, i2, dx, dg, db)
+    torch.cuda.synchronize()
+    assert torch.equal(m2, mean) and torch.equal(i2, invstd)
+    assert torch.equal(pooled, pooled_ref) and torch.equal(idx, idx_ref)
+    assert torch.equal(dx, dx_ref) and torch.equal(dg, dg_ref) and torch.equal(db, db_ref)
+    pooled.fill_(float("nan"))
+    idx.fill_(-1)
+    sn.sn_bn_relu_pool2_apply(xd, gamma, beta, mean, invstd, pooled, idx)
+    a2 = torch.empty_like(xd)
+    sn.sn_bn_apply(xd, gamma, beta, mean, invstd, a2, relu=True)
+    torch.cuda.synchronize()
+    assert torch.equal(pooled, pooled_ref) and torch.equal(idx, idx_ref) and torch.equal(a2, a)
+
+
+@pytest.mark.parametrize("name", ["conv1_1", "conv1_2", "conv2_2", "conv4_1", "conv5_2"])
+def test_conv_fwd_bn_stats_full_size(name):
+    """CONV forward with the BN statistics of its output at the benchmark's sizes and plan: y as the
+    plain call writes it, statistics within 1e-5 of the oracle's on sampled channels of the stored y."""
+    cfg = wl.CONFIGS[3]
+    N, dtype = cfg["N"], cfg["dtype"]
+    li, layer = [(i, l) for i, l in enumerate(cfg["layers"]) if l.name == name][0]
+    x, w, _ = wl.conv_inputs(layer, N, dtype, wl.layer_seed(3, li))
+    P, Q = wl.out_hw(layer)
+    shape = shape_of(layer, N, dtype, dtype)
+    budget = max(b for b in cfg["budgets"] if b is not None)
+    ws = torch.empty(budget, dtype=torch.uint8, device="cuda")
+    xd, wd = x.cuda(), w.cuda()
+    y_ref = torch.empty((N, layer.K, P, Q), dtype=torch.bfloat16, device="cuda")
+    sn.sn_conv_autotune(sn.SN_CONV_FWD, xd, wd, y_ref, shape, ws, iters=1)
+    sn.sn_conv2d_fwd(xd, wd, y_ref, shape, sn.SN_ALGO_AUTO, ws)
+    y = torch.full_like(y_ref, float("nan"))
+    mean, invstd = torch.empty(layer.K, device="cuda"), torch.empty(layer.K, device="cuda")
+    scratch = torch.empty(sn.sn_conv_bn_stats_scratch_bytes(shape), dtype=torch.uint8, device="cuda")
+    sn.sn_conv2d_fwd_bn_stats(xd, wd, y, shape, mean, invstd, scratch, sn.SN_ALGO_AUTO, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y_ref)
+    ks = sorted({0, 1, layer.K // 2, layer.K - 1})
+    ys = f64(y[:, ks])
+    _, mo, io = oracle.bn_fwd(ys, np.ones(len(ks)), np.zeros(len(ks)), 1e-5)
+    assert rel_l2(f64(mean[ks]), mo) <= 1e-5 or np.linalg.norm(f64(mean[ks]) - mo) <= 1e-6
+    assert rel_l2(f64(invstd[ks]), io) <= 1e-5
