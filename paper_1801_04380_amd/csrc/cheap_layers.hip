@@ -178,9 +178,14 @@ template <int VB> struct RawVec;
 template <> struct RawVec<16> { typedef uint4 type; };
 template <> struct RawVec<8> { typedef uint2 type; };
 template <> struct RawVec<4> { typedef uint32_t type; };
+template <> struct RawVec<2> { typedef unsigned short type; };   // one bf16
 
 template <typename T, int VB> __device__ inline void unpack(const typename RawVec<VB>::type &v, float (&f)[VB / sizeof(T)])
 {
+    if constexpr (VB == 2) {
+        f[0] = __uint_as_float((uint32_t)v << 16);
+        return;
+    }
     const uint32_t *w = reinterpret_cast<const uint32_t *>(&v);
     if (sizeof(T) == 2) {
 #pragma unroll
@@ -196,6 +201,7 @@ template <typename T, int VB> __device__ inline void unpack(const typename RawVe
 
 template <typename T, int VB> __device__ inline typename RawVec<VB>::type pack(const float (&f)[VB / sizeof(T)])
 {
+    if constexpr (VB == 2) return f32_to_bf16(f[0]);
     typename RawVec<VB>::type v;
     uint32_t *w = reinterpret_cast<uint32_t *>(&v);
     if (sizeof(T) == 2) {
@@ -240,7 +246,9 @@ __device__ inline void grad_vec(const GradSrc<T> &gs, size_t pl, int e, float (&
         unpack<T, VB>(*reinterpret_cast<const typename RawVec<VB>::type *>(gs.dy + pl * gs.HW + e), gr);
         return;
     }
-    if (gs.W % VE == 0) {
+    if constexpr (VE == 1) {   // single elements: planes of odd size, which no 2x2 pool follows
+        gr[0] = grad_one<T>(gs, pl, e);
+    } else if (gs.W % VE == 0) {
         const int h = e / gs.W, w = e - h * gs.W;
         const size_t wi = pl * gs.PQ + (size_t)(h >> 1) * gs.Q + (w >> 1);
         float gw[VE / 2];
@@ -773,6 +781,7 @@ bn_bwd_fused_kernel(const T *__restrict__ x, const GradSrc<T> gs, const float *_
 }
 
 constexpr int BN_FUSED_NV = 13;   // vectors a thread can hold (13 * 1024 * 8 bf16 = 106496 elements per channel)
+constexpr int BN_FUSED_NV1 = 32;  // single elements a thread can hold: planes of odd size (7x7, 17x17) have no wider access
 
 // Vector size in bytes for the one-pass kernels, 0 if they do not apply.
 template <typename T> int bn_fused_vb(const void *a, const void *b, const void *c3, int N, int HW)
@@ -784,6 +793,7 @@ template <typename T> int bn_fused_vb(const void *a, const void *b, const void *
         const long long nvec = (long long)N * (HW / ve);
         if (nvec <= 1024LL * BN_FUSED_NV) return vb;
     }
+    if ((HW & 1) && bits % sizeof(T) == 0 && (long long)N * HW <= 1024LL * BN_FUSED_NV1) return (int)sizeof(T);
     return 0;
 }
 
@@ -1220,6 +1230,10 @@ hipError_t launch_bn_fwd(const void *x, const float *gamma, const float *beta, v
                     hipLaunchKernelGGL((bn_fwd_fused_kernel<T, 16, BN_FUSED_NV, 0>), dim3(C), dim3(1024), 0, s, (const T *)x,
                                        (T *)y, gamma, beta, mean, invstd, N, C, HW, eps, relu, (T *)nullptr,
                                        (int32_t *)nullptr, 0, 0);
+                else if (vb == (int)sizeof(T))
+                    hipLaunchKernelGGL((bn_fwd_fused_kernel<T, sizeof(T), BN_FUSED_NV1, 0>), dim3(C), dim3(1024), 0, s,
+                                       (const T *)x, (T *)y, gamma, beta, mean, invstd, N, C, HW, eps, relu, (T *)nullptr,
+                                       (int32_t *)nullptr, 0, 0);
                 else
                     hipLaunchKernelGGL((bn_fwd_fused_kernel<T, 8, BN_FUSED_NV, 0>), dim3(C), dim3(1024), 0, s, (const T *)x,
                                        (T *)y, gamma, beta, mean, invstd, N, C, HW, eps, relu, (T *)nullptr,
@@ -1362,6 +1376,9 @@ hipError_t launch_bn_bwd(const void *x, const void *dy, const float *relu_beta, 
                 if (vb == 16)
                     hipLaunchKernelGGL((bn_bwd_fused_kernel<T, 16, BN_FUSED_NV>), dim3(C), dim3(1024), 0, s, (const T *)x,
                                        gs, relu_beta, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);
+                else if (vb == (int)sizeof(T))
+                    hipLaunchKernelGGL((bn_bwd_fused_kernel<T, sizeof(T), BN_FUSED_NV1>), dim3(C), dim3(1024), 0, s,
+                                       (const T *)x, gs, relu_beta, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);
                 else
                     hipLaunchKernelGGL((bn_bwd_fused_kernel<T, 8, BN_FUSED_NV>), dim3(C), dim3(1024), 0, s, (const T *)x,
                                        gs, relu_beta, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);
