@@ -59,6 +59,10 @@ CASES = [
     (L("w14_split_c96", 96, 14, 14, 160, 3, 3, (1, 1), (1, 1)), 5),
     (L("w8_split_c120", 120, 8, 8, 128, 3, 3, (1, 1), (1, 1)), 6),
     (L("w14_split_bwd", 128, 14, 14, 64, 3, 3, (1, 1), (1, 1)), 3),   # backward-data from 64 channels into 128
+    # filters of more than 2 MB: the XCDs keep to their channel tiles (8 tiles: one each; 16: two each; 4: pairs of XCDs)
+    (L("1x1_k1024", 1040, 7, 7, 1024, 1, 1), 2),
+    (L("1x1_k2048", 528, 7, 7, 2048, 1, 1), 2),
+    (L("3x3_k512", 272, 6, 8, 512, 3, 3, (1, 1), (1, 1)), 2),
 ]
 IDS = [c[0].name for c in CASES]
 
