@@ -189,7 +189,7 @@ sn_status sn_bn_relu_fwd(const void *x, const float *gamma, const float *beta, v
 /* BN forward (optionally with the ReLU, relu != 0) from statistics the caller already has --
  * sn_conv2d_fwd_bn_stats leaves them, or an earlier sn_bn_fwd on the same x: the normalisation
  * pass alone, one read of x and one write of y, with the arithmetic of sn_bn_fwd /
- * sn_bn_relu_fwd (bit-identical y for the same mean and invstd).  y may alias x. */
+ * sn_bn_relu_fwd (bit-identical y for the same mean and invstd).  y must not alias x. */
 sn_status sn_bn_apply(const void *x, const float *gamma, const float *beta,
                       const float *mean, const float *invstd, void *y,
                       int N, int C, int H, int W, int relu, sn_dtype dtype, sn_stream stream);

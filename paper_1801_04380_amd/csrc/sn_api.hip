@@ -557,7 +557,7 @@ sn_status sn_bn_apply(const void *x, const float *gamma, const float *beta, cons
 {
     sn_status s = check_cheap(N, C, H, W, dtype);
     if (s != SN_OK) return s;
-    if (!x || !gamma || !beta || !mean || !invstd || !y) return SN_ERR_BAD_ARG;
+    if (!x || !gamma || !beta || !mean || !invstd || !y || x == y) return SN_ERR_BAD_ARG;
     if (!aligned(x, 16) || !aligned(y, 16) || !aligned(gamma, 4) || !aligned(beta, 4) || !aligned(mean, 4) ||
         !aligned(invstd, 4))
         return SN_ERR_BAD_ARG;

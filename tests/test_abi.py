@@ -82,6 +82,7 @@ def test_bad_arguments_are_refused_before_any_launch():
     # BN from given statistics
     assert lib.sn_bn_apply(one, one, one, one, None, two, 1, 1, 1, 1, 0, 0, None) == 1
     assert lib.sn_bn_apply(one, one, one, one, one, two, 1, 1, 0, 1, 0, 0, None) == 1
+    assert lib.sn_bn_apply(one, one, one, one, one, one, 1, 1, 1, 1, 0, 0, None) == 1    # y aliases x
     assert lib.sn_bn_relu_pool2_apply(one, one, one, one, one, two, ctypes.c_void_p(768), 1, 1, 5, 8, 1, None) == 2
     assert lib.sn_bn_relu_pool2_apply(one, one, one, one, one, two, two, 1, 1, 4, 8, 1, None) == 1
     # LRN: odd window of at most 9 channels, k > 0, no aliasing
