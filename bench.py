@@ -60,6 +60,9 @@ def parse():
     ap.add_argument("--no-budget-sweep", action="store_true", help="skip the conv timing at the smaller budgets")
     ap.add_argument("--no-fuse", action="store_true", help="BN and ReLU as separate calls, forward and backward")
     ap.add_argument("--detail", default=None, help="write the per-layer table to this JSON file")
+    ap.add_argument("--table", default=None,
+                    help="instead of the step: time every layer x direction x algorithm of the workload, and the "
+                         "cheap layers on every conv output, and write the table to this text file")
     return ap.parse_args()
 
 
@@ -230,6 +233,128 @@ def build_ops(cfg_no, budget, autotune, fuse):
     return cfg, fwd_ops + bwd_ops, plans, tune_ms, wsbox
 
 
+def layer_table(cfg_no, budget, path):
+    """Per layer x direction x algorithm (at its least and its preferred workspace, the latter capped
+    by the budget): median and minimum of 20 launches after 5 warm-up launches, each between a pair
+    of events.  Cheap layers: every call on every conv output, rotating through three sets of
+    buffers so that the working set of consecutive launches exceeds the 256 MB last-level cache."""
+    import torch
+
+    import paper_1801_04380_amd as sn
+    from paper_1801_04380_amd import workloads as wl
+
+    cfg = wl.CONFIGS[cfg_no]
+    N, dtype, dev = cfg["N"], cfg["dtype"], torch.device("cuda:0")
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    code = sn.SN_BF16 if dtype == "bf16" else sn.SN_F32
+    b = 2 if dtype == "bf16" else 4
+    peak = PEAK["bf16_mfma_tflops"] if dtype == "bf16" else PEAK["f32_mfma_tflops"]
+    ws = torch.empty(max(budget, 256), dtype=torch.uint8, device=dev)
+
+    def timed(fns):
+        """fns: the same call on rotating buffer sets; -> (median, min) ms over 20 launches."""
+        for i in range(5):
+            fns[i % len(fns)]()
+        ev = []
+        for i in range(20):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fns[i % len(fns)]()
+            e1.record()
+            ev.append((e0, e1))
+        torch.cuda.synchronize()
+        t = sorted(a.elapsed_time(c) for a, c in ev)
+        return (t[9] + t[10]) / 2, t[0]
+
+    out = ["%s, N = %d, %s, workspace budget %d MiB; times in us (median / min of 20 launches); TFLOP/s and %% of the"
+           % (cfg["name"], N, dtype, budget >> 20),
+           "dense MFMA peak (%.0f TFLOP/s) from algorithmic FLOPs and the median; GB/s and %% of 8 TB/s from the" % peak,
+           "compulsory bytes of the call and the median.", "",
+           "%-10s %-10s %-12s %10s %9s %9s %8s %6s" % ("layer", "direction", "algorithm", "ws MiB", "median", "min", "TFLOP/s", "peak")]
+    names = {0: "forward", 1: "bwd-data", 2: "bwd-filter"}
+    cheap = []
+    for li, layer in enumerate(cfg["layers"]):
+        x, w, dy = wl.conv_inputs(layer, N, dtype, wl.layer_seed(cfg_no, li))
+        xd, wd, dyd = x.to(dev), w.to(dev), dy.to(dev)
+        K = layer.K
+        P, Q = wl.out_hw(layer)
+        shape = sn.conv_shape(N, layer.C, layer.H, layer.W, K, layer.R, layer.S, layer.stride, layer.pad, code, code)
+        y, dx = torch.empty((N, K, P, Q), dtype=tdt, device=dev), torch.empty_like(xd)
+        dw = torch.empty(tuple(w.shape), dtype=torch.float32, device=dev)
+        flops = wl.conv_flops(layer, N)[1]
+        for d, (fn, a, bb, o) in {0: (sn.sn_conv2d_fwd, xd, wd, y), 1: (sn.sn_conv2d_bwd_data, dyd, wd, dx),
+                                  2: (sn.sn_conv2d_bwd_filter, xd, dyd, dw)}.items():
+            if d == 1 and layer.first:
+                continue
+            for algo in (sn.SN_ALGO_DIRECT, sn.SN_ALGO_STAGED, sn.SN_ALGO_IM2COL_GEMM):
+                try:
+                    mn, pf = sn.sn_conv_workspace_query(shape, d, algo)
+                except sn.SnError:
+                    continue
+                for used in sorted({mn, min(pf, budget)}):
+                    if used < mn or used > budget:
+                        continue
+                    wsv = ws[:used] if used else None
+                    med, lo = timed([lambda: fn(a, bb, o, shape, algo, wsv)])
+                    tf = flops / (med * 1e-3) / 1e12
+                    out.append("%-10s %-10s %-12s %10.1f %9.1f %9.1f %8.1f %5.1f%%"
+                               % (layer.name, names[d], sn.ALGO_NAMES[algo], used / 2 ** 20, med * 1e3, lo * 1e3, tf,
+                                  100 * tf / peak))
+        cheap.append((layer, (N, K, P, Q)))
+        del xd, wd, dyd, y, dx, dw
+    out += ["", "%-10s %-22s %12s %9s %9s %8s %6s" % ("layer", "call", "MB moved", "median", "min", "GB/s", "of HBM")]
+    seen = set()
+    for layer, shp in cheap:
+        if (shp, layer.pool, layer.lrn) in seen:
+            continue
+        seen.add((shp, layer.pool, layer.lrn))
+        E = shp[0] * shp[1] * shp[2] * shp[3]
+        sets = max(1, min(3, int(600e6 // (3 * E * b)) or 1)) if 3 * E * b < 600e6 else 3
+        bufs = [[wl.activation(shp, dtype, 40 + i).to(dev) for i in range(2)] + [torch.empty(shp, dtype=tdt, device=dev) for _ in range(2)]
+                for _ in range(sets)]
+        gamma, beta = (t.to(dev) for t in wl.bn_params(shp[1], 1))
+        stat = [torch.empty(shp[1], device=dev) for _ in range(4)]
+        calls = [("relu_fwd", 2, lambda s: sn.sn_relu_fwd(s[0], s[2])),
+                 ("relu_bwd", 3, lambda s: sn.sn_relu_bwd(s[0], s[1], s[2]))]
+        if cfg["bn"]:
+            calls += [("bn_fwd", 2, lambda s: sn.sn_bn_fwd(s[0], gamma, beta, s[2], stat[0], stat[1])),
+                      ("bn_relu_fwd", 2, lambda s: sn.sn_bn_relu_fwd(s[0], gamma, beta, s[2], stat[0], stat[1])),
+                      ("bn_apply (+relu)", 2, lambda s: sn.sn_bn_apply(s[0], gamma, beta, stat[0], stat[1], s[2], relu=True)),
+                      ("bn_bwd", 3, lambda s: sn.sn_bn_bwd(s[0], s[1], gamma, stat[0], stat[1], s[2], stat[2], stat[3])),
+                      ("bn_relu_bwd", 3, lambda s: sn.sn_bn_relu_bwd(s[0], s[1], gamma, beta, stat[0], stat[1], s[2], stat[2], stat[3]))]
+        if layer.lrn:
+            calls += [("lrn_fwd", 2, lambda s: sn.sn_lrn_fwd(s[0], s[2], *layer.lrn)),
+                      ("lrn_bwd", 3, lambda s: sn.sn_lrn_bwd(s[0], s[1], s[2], *layer.lrn))]
+        for cname, passes, f in calls:
+            med, lo = timed([(lambda s=s_: f(s)) for s_ in bufs])
+            mb = passes * E * b
+            out.append("%-10s %-22s %12.1f %9.1f %9.1f %8.0f %5.1f%%" % (layer.name, cname, mb / 1e6, med * 1e3, lo * 1e3,
+                                                                        mb / (med * 1e-3) / 1e9, 100 * mb / (med * 1e-3) / 1e9 / PEAK["hbm_gbs"]))
+        if layer.pool:
+            kernel, stride = layer.pool
+            PP, QQ = sn.sn_out_dim(shp[2], 0, kernel[0], stride[0]), sn.sn_out_dim(shp[3], 0, kernel[1], stride[1])
+            pooled = [torch.empty((shp[0], shp[1], PP, QQ), dtype=tdt, device=dev) for _ in range(sets)]
+            idx = [torch.empty((shp[0], shp[1], PP, QQ), dtype=torch.int32, device=dev) for _ in range(sets)]
+            gp = wl.activation((shp[0], shp[1], PP, QQ), dtype, 50).to(dev)
+            Eo = pooled[0].numel()
+            pc = [("maxpool_fwd", E * b + Eo * (b + 4), lambda i: sn.sn_maxpool_fwd(bufs[i][0], pooled[i], idx[i], kernel, stride)),
+                  ("maxpool_bwd", Eo * (b + 4) + E * b, lambda i: sn.sn_maxpool_bwd(gp, idx[i], bufs[i][2], kernel, stride))]
+            if cfg["bn"] and kernel == (2, 2) and stride == (2, 2) and shp[2] % 2 == 0 and shp[3] % (8 // b) == 0:
+                pc += [("bn_relu_pool2_fwd", E * b + Eo * (b + 4),
+                        lambda i: sn.sn_bn_relu_pool2_fwd(bufs[i][0], gamma, beta, pooled[i], idx[i], stat[0], stat[1])),
+                       ("bn_relu_pool2_bwd", Eo * (b + 4) + 2 * E * b,
+                        lambda i: sn.sn_bn_relu_pool2_bwd(bufs[i][0], gp, idx[i], gamma, beta, stat[0], stat[1], bufs[i][2],
+                                                          stat[2], stat[3]))]
+            for cname, mb, f in pc:
+                med, lo = timed([(lambda i=i_: f(i)) for i_ in range(sets)])
+                out.append("%-10s %-22s %12.1f %9.1f %9.1f %8.0f %5.1f%%" % (layer.name, cname, mb / 1e6, med * 1e3, lo * 1e3,
+                                                                            mb / (med * 1e-3) / 1e9, 100 * mb / (med * 1e-3) / 1e9 / PEAK["hbm_gbs"]))
+        del bufs
+    with open(path, "w") as f:
+        f.write("\n".join(out) + "\n")
+    print("\n".join(out))
+
+
 def cpu_baseline(cfg_no):
     """The fp64 oracle, as it stands, on a bounded sample: the most expensive layer of the
     workload at a reduced batch (conv cost is linear in N), all three directions."""
@@ -275,6 +400,9 @@ def main():
         budget = int(args.budget_mib * (1 << 20))
     else:
         budget = max(budgets) if budgets else 64 << 20
+    if args.table:
+        layer_table(args.workload, budget, args.table)
+        return
     cfg, ops, plans, tune_ms, wsbox = build_ops(args.workload, budget, not args.no_autotune, not args.no_fuse)
     stream = torch.cuda.current_stream()
 

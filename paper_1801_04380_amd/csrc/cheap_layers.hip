@@ -781,6 +781,7 @@ bn_bwd_fused_kernel(const T *__restrict__ x, const GradSrc<T> gs, const float *_
 }
 
 constexpr int BN_FUSED_NV = 13;   // vectors a thread can hold (13 * 1024 * 8 bf16 = 106496 elements per channel)
+constexpr int BN_FUSED_NVS = 4;   // the same kernels built for short channels: fewer registers, two workgroups per compute unit
 constexpr int BN_FUSED_NV1 = 32;  // single elements a thread can hold: planes of odd size (7x7, 17x17) have no wider access
 
 // Vector size in bytes for the one-pass kernels, 0 if they do not apply.
@@ -1226,7 +1227,18 @@ hipError_t launch_bn_fwd(const void *x, const float *gamma, const float *beta, v
         if (vb)
             return by_dtype(bf16, [&](auto *tag) {
                 typedef typename std::remove_pointer<decltype(tag)>::type T;
-                if (vb == 16)
+                // a channel of at most 4 vectors per thread goes to the build with 4 registers' worth of them
+                // (the sums run over the same elements in the same order either way)
+                const bool few = vb >= 8 && (long long)N * (HW / (vb / (int)sizeof(T))) <= 1024LL * BN_FUSED_NVS;
+                if (vb == 16 && few)
+                    hipLaunchKernelGGL((bn_fwd_fused_kernel<T, 16, BN_FUSED_NVS, 0>), dim3(C), dim3(1024), 0, s, (const T *)x,
+                                       (T *)y, gamma, beta, mean, invstd, N, C, HW, eps, relu, (T *)nullptr,
+                                       (int32_t *)nullptr, 0, 0);
+                else if (vb == 8 && few)
+                    hipLaunchKernelGGL((bn_fwd_fused_kernel<T, 8, BN_FUSED_NVS, 0>), dim3(C), dim3(1024), 0, s, (const T *)x,
+                                       (T *)y, gamma, beta, mean, invstd, N, C, HW, eps, relu, (T *)nullptr,
+                                       (int32_t *)nullptr, 0, 0);
+                else if (vb == 16)
                     hipLaunchKernelGGL((bn_fwd_fused_kernel<T, 16, BN_FUSED_NV, 0>), dim3(C), dim3(1024), 0, s, (const T *)x,
                                        (T *)y, gamma, beta, mean, invstd, N, C, HW, eps, relu, (T *)nullptr,
                                        (int32_t *)nullptr, 0, 0);
@@ -1331,12 +1343,15 @@ hipError_t launch_bn_relu_pool2_fwd(const void *x, const float *gamma, const flo
     if (vb)
         return by_dtype(bf16, [&](auto *tag) {
             typedef typename std::remove_pointer<decltype(tag)>::type T;
-#define SN_POOL_FUSED(VB_, PVB_)                                                                                  \
-    hipLaunchKernelGGL((bn_fwd_fused_kernel<T, VB_, BN_FUSED_NV, PVB_>), dim3(C), dim3(1024), 0, s, (const T *)x, \
+#define SN_POOL_FUSED(VB_, NV_, PVB_)                                                                       \
+    hipLaunchKernelGGL((bn_fwd_fused_kernel<T, VB_, NV_, PVB_>), dim3(C), dim3(1024), 0, s, (const T *)x,         \
                        (T *)nullptr, gamma, beta, mean, invstd, N, C, HW, eps, 1, (T *)pooled, idx, H, W)
             // H even and W a multiple of half a 16-byte vector make H*W a multiple of the whole one
-            if (pvb == 16) SN_POOL_FUSED(16, 16);
-            else SN_POOL_FUSED(16, 8);
+            const bool few = (long long)N * (HW / (16 / (int)sizeof(T))) <= 1024LL * BN_FUSED_NVS;
+            if (pvb == 16 && few) SN_POOL_FUSED(16, BN_FUSED_NVS, 16);
+            else if (pvb == 16) SN_POOL_FUSED(16, BN_FUSED_NV, 16);
+            else if (few) SN_POOL_FUSED(16, BN_FUSED_NVS, 8);
+            else SN_POOL_FUSED(16, BN_FUSED_NV, 8);
 #undef SN_POOL_FUSED
         });
     // idx is dead until the last pass, so it holds the per-slice partial sums meanwhile (launch_bn_fwd
@@ -1373,7 +1388,14 @@ hipError_t launch_bn_bwd(const void *x, const void *dy, const float *relu_beta, 
             return by_dtype(bf16, [&](auto *tag) {
                 typedef typename std::remove_pointer<decltype(tag)>::type T;
                 const GradSrc<T> gs{(const T *)dy, (const T *)pool_g, pool_idx, pool_W, pool_W / 2, HW, HW / 4};
-                if (vb == 16)
+                const bool few = vb >= 8 && (long long)N * (HW / (vb / (int)sizeof(T))) <= 1024LL * BN_FUSED_NVS;
+                if (vb == 16 && few)
+                    hipLaunchKernelGGL((bn_bwd_fused_kernel<T, 16, BN_FUSED_NVS>), dim3(C), dim3(1024), 0, s, (const T *)x,
+                                       gs, relu_beta, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);
+                else if (vb == 8 && few)
+                    hipLaunchKernelGGL((bn_bwd_fused_kernel<T, 8, BN_FUSED_NVS>), dim3(C), dim3(1024), 0, s, (const T *)x,
+                                       gs, relu_beta, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);
+                else if (vb == 16)
                     hipLaunchKernelGGL((bn_bwd_fused_kernel<T, 16, BN_FUSED_NV>), dim3(C), dim3(1024), 0, s, (const T *)x,
                                        gs, relu_beta, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);
                 else if (vb == (int)sizeof(T))
