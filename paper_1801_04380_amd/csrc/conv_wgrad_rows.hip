@@ -282,7 +282,11 @@ wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
     };
     constexpr int NCGW = NCG / TP;       // column groups per wave
     constexpr int NSTEP = NCGW * XROWS;  // (column group, x row) steps of a chunk, per wave
-    constexpr int LAG = 4;               // an item is written to LDS this many items after its load
+    // An item is written to LDS LAG items after its load.  With one wave per SIMD nothing else
+    // covers the latency of the loads: they are all issued in the first half of the chunk and
+    // written after its last MFMA.
+    constexpr bool LONE = TM * TP == 1;
+    constexpr int LAG = LONE ? NITEMS : 4;
     auto compute = [&](int buf) {
         const bf16_t *ys = smem + buf * BUF + ylane, *xs = smem + buf * BUF + YS + xlane;
         auto load_raw = [&](Raw &r, int cg, int xr) {
@@ -335,7 +339,8 @@ wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
                 __builtin_amdgcn_sched_barrier(0);
                 // this step's share of the next chunk's staging
                 const int st = cgi * XROWS + xr;
-                const int lo = st * NITEMS / NSTEP, hi = (st + 1) * NITEMS / NSTEP;
+                const int lo = min(NITEMS, st * NITEMS * (LONE ? 2 : 1) / NSTEP);
+                const int hi = min(NITEMS, (st + 1) * NITEMS * (LONE ? 2 : 1) / NSTEP);
 #pragma unroll
                 for (int i = 0; i < NITEMS; ++i)
                     if (i >= lo && i < hi) item_load(i);
