@@ -138,18 +138,24 @@ bool make_plan(const TileProblem &base, int R, int S, bool staged, Plan *pl, boo
 }
 
 // The tiling for the second-generation kernel (conv_tile2.h), or false where it does not apply:
-// 3x3 filters, more than 64 output channels, an even image width (a multiple of 8 for the
-// WIDE tiling), an input tensor of at most 2 GiB.
+// 3x3 filters, an even image width (a multiple of 8 for the WIDE tiling), an input tensor of at
+// most 2 GiB; with at most 64 output channels only the WIDE tiling and 96 input channels or more.
 bool make_plan2(const TileProblem &base, int R, int S, Plan *pl)
 {
-    if (!(R == 3 && S == 3) || base.Kout <= 64 || base.Win % 2 != 0) return false;
-    // a width that rules out the WIDE tiling here (not a multiple of 8): whole rows where they fill the tile as well
-    if (!make_plan(base, R, S, true, pl, base.Win % 8 != 0) || pl->KT != 128 || (pl->NF != 4 && pl->NF != 2))
+    if (!(R == 3 && S == 3) || base.Win % 2 != 0) return false;
+    if (base.Kout <= 64) {
+        // one 64-channel tile: four waves along the pixels, 2 x 32 pixels each, on 8 x 32 patches.  With few
+        // input channels (measured: 64) the first-generation kernel's 512-pixel tiles are faster: the loop
+        // is too short to pay for this kernel's longer prologue, and the tiles are half the size.
+        if (base.Win % 8 != 0 || base.Cin < 96 || !plan_for(base, R, S, 2, pl) || pl->KT != 64 || !pl->wide) return false;
+    } else if (!make_plan(base, R, S, true, pl, base.Win % 8 != 0) || pl->KT != 128 || (pl->NF != 4 && pl->NF != 2)) {
+        // (a width that rules out the WIDE tiling here, not a multiple of 8: whole rows where they fill the tile as well)
         return false;
+    }
     TileProblem &p = pl->p;
     const int dw = p.Win % 8 == 0 ? 16 : 4;
     if (pl->wide && dw != 16) return false;
-    const int pixt = 2 * pl->NF * 32;
+    const int pixt = (pl->KT == 128 ? 2 : 4) * pl->NF * 32;
     if (pl->wide) {
         p.xt_rows = pixt / 32 + R - 1;
         p.xt_cols = WIDE_LWP;

@@ -26,6 +26,9 @@
 //  * Parked buffers and patch buffers are double buffered over chunks: while chunk
 //    c is multiplied, chunk c+1 is transposed and chunk c+2 is in flight.  One
 //    barrier per chunk.
+//  * WPN = 4 (at most 64 output channels): the four waves of the workgroup all take the 64
+//    channels and a quarter of the tile's pixels each (NF 32-pixel groups per wave), instead
+//    of two halves of 128 channels x two halves of the pixels.
 //  * KS = 2 (small images, where the tiles do not even give every compute unit a
 //    workgroup): a workgroup has two sets of four waves, each with buffers of its own,
 //    which run the same pipeline over the even and the odd chunks of the same tile
@@ -51,15 +54,16 @@ __device__ inline s16x4 lds_read_tr16(const char *p)
 
 // The body of the kernel; the four LDS regions are distinct, which the qualifiers tell the
 // compiler (loads into a parked buffer then do not hold up the reads of a patch buffer).
-template <int R, int S, int NF, bool WIDE, int DW, int KS>
+template <int R, int S, int NF, bool WIDE, int DW, int KS, int WPN>
 __device__ __forceinline__ void conv_tile2_body(const bf16_t *__restrict__ in, const bf16_t *__restrict__ w,
                                                 void *__restrict__ out, const TileProblem &p,
                                                 uint4 *__restrict__ xs0, uint4 *__restrict__ xs1,
                                                 char *__restrict__ pk0, char *__restrict__ pk1, uint4 *smem)
 {
-    constexpr int KT = 128;
+    constexpr int KT = WPN == 2 ? 128 : 64;
+    static_assert(WPN == 2 || (WPN == 4 && KS == 1), "wave layouts");
     constexpr int SG = sg_of(R, S), TRES = R * SG, NSUB = S / SG;
-    constexpr int PIXT = 2 * NF * 32;
+    constexpr int PIXT = WPN * NF * 32;
     constexpr int NB = WIDE ? NF + R - 1 : NF;
     constexpr int WROWS = PIXT / 32 + R - 1;   // WIDE: patch rows
     constexpr int XG = DW == 16 ? 4 : 16;   // most load rounds per chunk: 16 / (channels per round)
@@ -70,7 +74,7 @@ __device__ __forceinline__ void conv_tile2_body(const bf16_t *__restrict__ in, c
     const int set = KS > 1 ? __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 8) : 0;
     const int nch = p.nchunks / KS;   // chunks per set (the host gives KS > 1 only chunk counts it divides)
     const int l32 = lane & 31, g = lane >> 5;
-    const int wk = wave >> 1, wp = wave & 1;
+    const int wk = WPN == 2 ? wave >> 1 : 0, wp = WPN == 2 ? wave & 1 : wave;
     const int XS = p.xslots * 2 + V2_TRASH;
 
     // ---- which tile
@@ -166,7 +170,8 @@ __device__ __forceinline__ void conv_tile2_body(const bf16_t *__restrict__ in, c
             if (prow < lrows) {
                 src = (uint32_t)((xo * 8 + (j >> 2)) * chstride + (prow * pitch + cg * 16 + (j & 3) * 4) * 2);
                 const int pcol = cg * 16 + j;
-                const int lcol = WIDE ? pcol - 7 : pcol + p.padw;
+                // WIDE: the parked patch starts 8 columns left of the tile, the patch buffer padw columns left of it
+                const int lcol = WIDE ? pcol - 8 + p.padw : pcol + p.padw;
                 const bool ok = WIDE ? (lcol >= 0 && lcol < p.LW) : pcol < p.Win;
                 if (ok) {
                     const int slot = prow * LWp + lcol;
@@ -391,7 +396,7 @@ __device__ __forceinline__ void conv_tile2_body(const bf16_t *__restrict__ in, c
     // owns no output channel: its channel numbers are past the last.
     const int kst = set == 0 ? k0 : (1 << 29);
     if (p.stats)
-        tile_bn_partials<NF, 2>(acc, p.TW, min(p.TH, NP - o0), p.Qout - q0, wp, wk, l32, g, kst + wk * 64, p.Kout, p.out_bf16 != 0, p.stats, p.nptiles,
+        tile_bn_partials<NF, WPN>(acc, p.TW, min(p.TH, NP - o0), p.Qout - q0, wp, wk, l32, g, kst + wk * 64, p.Kout, p.out_bf16 != 0, p.stats, p.nptiles,
                                 ptile, reinterpret_cast<float *>(smem) + set * 1024);
     if (p.out_bf16) {
         constexpr int EP = EPI_PITCH;
@@ -455,7 +460,7 @@ __device__ __forceinline__ void conv_tile2_body(const bf16_t *__restrict__ in, c
     }
 }
 
-template <int R, int S, int NF, bool WIDE, int DW, int KS>
+template <int R, int S, int NF, bool WIDE, int DW, int KS, int WPN>
 __global__ void __launch_bounds__(256 * KS, 2)
 conv_tile2_kernel(const bf16_t *__restrict__ in, const bf16_t *__restrict__ w, void *__restrict__ out, TileProblem p)
 {
@@ -465,13 +470,13 @@ conv_tile2_kernel(const bf16_t *__restrict__ in, const bf16_t *__restrict__ w, v
     const int set = KS > 1 ? __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 8) : 0;
     uint4 *const xs = smem + set * (2 * XS + 2 * (p.pk_bytes / 16));
     char *const pk = reinterpret_cast<char *>(xs + 2 * XS);
-    conv_tile2_body<R, S, NF, WIDE, DW, KS>(in, w, out, p, xs, xs + XS, pk, pk + p.pk_bytes, smem);
+    conv_tile2_body<R, S, NF, WIDE, DW, KS, WPN>(in, w, out, p, xs, xs + XS, pk, pk + p.pk_bytes, smem);
 }
 
-template <int R, int S, int NF, bool WIDE, int DW, int KS = 1>
+template <int R, int S, int NF, bool WIDE, int DW, int KS = 1, int WPN = 2>
 hipError_t launch2_one(const bf16_t *in, const bf16_t *w, void *out, const Plan &pl, hipStream_t st)
 {
-    auto kern = conv_tile2_kernel<R, S, NF, WIDE, DW, KS>;
+    auto kern = conv_tile2_kernel<R, S, NF, WIDE, DW, KS, WPN>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),

@@ -59,6 +59,14 @@ CASES = [
     (L("w14_split_c96", 96, 14, 14, 160, 3, 3, (1, 1), (1, 1)), 5),
     (L("w8_split_c120", 120, 8, 8, 128, 3, 3, (1, 1), (1, 1)), 6),
     (L("w14_split_bwd", 128, 14, 14, 64, 3, 3, (1, 1), (1, 1)), 3),   # backward-data from 64 channels into 128
+    # at most 64 output channels on 32-column patches: four waves along the pixels (forward: K, backward-data: C)
+    (L("k64_w64", 96, 16, 64, 64, 3, 3, (1, 1), (1, 1)), 2),
+    (L("k48_w72", 104, 12, 72, 48, 3, 3, (1, 1), (1, 1)), 3),
+    (L("k64_w112_pad0", 128, 20, 112, 64, 3, 3, (1, 1), (0, 0)), 1),
+    (L("c40_bwd_w72", 40, 12, 72, 112, 3, 3, (1, 1), (1, 1)), 2),      # backward-data: 112 channels into 40
+    # 32-column patches with no padding, and with more than the filter needs
+    (L("wide_pad0", 32, 20, 112, 96, 3, 3, (1, 1), (0, 0)), 1),
+    (L("wide_pad2", 32, 12, 72, 96, 3, 3, (1, 1), (2, 2)), 2),
     # filters of more than 2 MB: the XCDs keep to their channel tiles (8 tiles: one each; 16: two each; 4: pairs of XCDs)
     (L("1x1_k1024", 1040, 7, 7, 1024, 1, 1), 2),
     (L("1x1_k2048", 528, 7, 7, 2048, 1, 1), 2),

@@ -26,6 +26,7 @@ CASES = [
     (L("w28", 64, 28, 28, 128, 3, 3, (1, 1), (1, 1)), 3),
     (L("w14_split", 64, 14, 14, 128, 3, 3, (1, 1), (1, 1)), 4),
     (L("k64", 48, 20, 36, 64, 3, 3, (1, 1), (1, 1)), 3),
+    (L("k48_w72", 104, 12, 72, 48, 3, 3, (1, 1), (1, 1)), 3),
     (L("first3", 3, 40, 40, 64, 3, 3, (1, 1), (1, 1), relu_in=False), 2),
     (L("ragged3x3", 19, 37, 29, 70, 3, 3, (1, 1), (1, 1)), 3),
     (L("1x1", 96, 14, 14, 160, 1, 1), 3),
