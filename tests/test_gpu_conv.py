@@ -174,3 +174,53 @@ def test_autotune_records_and_plan_follows():
     assert algo0 == sn.SN_ALGO_DIRECT and used0 == 0 and ms0 >= ms
     assert rel_l2(f64(y), want[sn.SN_CONV_FWD]) <= TOL["bf16"]
     sn.sn_planner_clear()
+
+
+def _random_cases(n, seed):
+    """Seeded 3x3 / 1x1 stride-1 layers over the ranges where the tile kernels switch tilings: widths on both
+    sides of the multiples of 8, 32-column patches and whole rows, paddings 0..2, channel counts on both sides
+    of 64 and 128, a ragged last chunk of channels."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        R = int(rng.choice([3, 3, 3, 1]))
+        W = int(rng.choice([6, 8, 10, 14, 16, 24, 28, 30, 32, 40, 56, 64, 66, 72, 80, 112]))
+        H = int(rng.integers(3, 20))
+        C = int(rng.choice([3, 8, 20, 32, 48, 64, 72, 96, 104, 128, 136, 200]))
+        K = int(rng.choice([16, 40, 64, 72, 96, 128, 136, 192, 260]))
+        pad = int(rng.integers(0, 3)) if R == 3 else 0
+        N = int(rng.integers(1, 4))
+        if H + 2 * pad < R or W + 2 * pad < R:
+            continue
+        cases.append((L("rnd%d" % i, C, H, W, K, R, R, (1, 1), (pad, pad)), N))
+    return cases
+
+
+RANDOM_CASES = _random_cases(36, 2024) + _random_cases(36, 7)
+
+
+@pytest.mark.parametrize("case", range(len(RANDOM_CASES)),
+                         ids=["%d_c%d_%dx%d_k%d_r%d_p%d_n%d" % (i, c[0].C, c[0].H, c[0].W, c[0].K, c[0].R, c[0].pad[0], c[1])
+                              for i, c in enumerate(RANDOM_CASES)])
+def test_conv_random_geometries(case):
+    """bf16, every direction and algorithm at its preferred workspace, against the oracle."""
+    layer, N = RANDOM_CASES[case]
+    x, w, dy = wl.conv_inputs(layer, N, "bf16", seed=500 + case)
+    xo, wo, dyo = f64(x), f64(w), f64(dy)
+    want = {sn.SN_CONV_FWD: lambda: oracle.conv2d_fwd(xo, wo, layer.stride, layer.pad),
+            sn.SN_CONV_BWD_DATA: lambda: oracle.conv2d_bwd_data(dyo, wo, xo.shape, layer.stride, layer.pad),
+            sn.SN_CONV_BWD_FILTER: lambda: oracle.conv2d_bwd_filter(xo, dyo, wo.shape, layer.stride, layer.pad)}
+    shape = shape_of(layer, N, "bf16", "bf16")
+    for direction in (sn.SN_CONV_FWD, sn.SN_CONV_BWD_DATA, sn.SN_CONV_BWD_FILTER):
+        ref = want[direction]()
+        a, b = {sn.SN_CONV_FWD: (x, w), sn.SN_CONV_BWD_DATA: (dy, w), sn.SN_CONV_BWD_FILTER: (x, dy)}[direction]
+        od = torch.float32 if direction == sn.SN_CONV_BWD_FILTER else torch.bfloat16
+        for algo in (sn.SN_ALGO_DIRECT, sn.SN_ALGO_STAGED, sn.SN_ALGO_IM2COL_GEMM):
+            try:
+                mn, pf = sn.sn_conv_workspace_query(shape, direction, algo)
+            except sn.SnError:
+                continue
+            print("case", layer, "N", N, "dir", direction, "algo", sn.ALGO_NAMES[algo], "ws", pf, flush=True)
+            got = run_conv(direction, a, b, ref.shape, od, shape, algo, pf)
+            err = rel_l2(f64(got), ref)
+            assert err <= TOL["bf16"], (layer, N, direction, sn.ALGO_NAMES[algo], err)
