@@ -72,6 +72,8 @@ struct TileProblem {
     // conv_tile2.h only: load rounds and transposition rounds per chunk, bytes of one parked buffer
     int xg_rounds, xtr_rounds, pk_bytes;
     int xt_upc;              // units of the load size a parked channel has room for (64, 128 or 256)
+    int xt_shift;            // NARROW, 16-byte loads of rows that start on odd multiples of 8 bytes: a parked row begins
+                             // at the 16-byte boundary at or below the image row, (h * Win) % 8 elements before it
     uint32_t in_bytes, w_bytes;   // sizes of the input tensor and of the packed filter
     int nptiles, nktiles, pt_per_xcd;   // pixel tiles, channel tiles, pixel tiles per XCD (the grid is 8 * pt_per_xcd * nktiles)
     // Filters too large for an XCD's L2: kmajor = min(nktiles, 8) XCDs take different channel

@@ -160,22 +160,32 @@ bool make_plan2(const TileProblem &base, int R, int S, Plan *pl)
         return false;
     }
     TileProblem &p = pl->p;
-    const int dw = p.Win % 8 == 0 ? 16 : 4;
+    int dw = p.Win % 8 == 0 ? 16 : 4;
     if (pl->wide && dw != 16) return false;
     const int pixt = (pl->KT == 128 ? 2 : 4) * pl->NF * 32;
     if (pl->wide) {
         p.xt_rows = pixt / 32 + R - 1;
         p.xt_cols = WIDE_LWP;
-    } else {
-        // xt_rows = the most patch rows of a tile (set by plan_for); a parked row holds the image row
-        p.xt_cols = dw == 16 ? p.Win : (p.Win + 3) / 4 * 4;
     }
-    const int units = p.xt_rows * (p.xt_cols * 2 / dw);   // units of dw bytes per parked channel
-    p.xt_upc = units <= 64 ? 64 : units <= 128 ? 128 : 256;
-    if (units > 256 || (dw == 16 && p.xt_upc != 64)) return false;
-    p.xg_rounds = 16 * p.xt_upc / 256;
-    p.xtr_rounds = (2 * p.xt_rows * ((p.xt_cols + 15) / 16) + 15) / 16;
-    if (!pl->wide && p.xtr_rounds > V2_XTR_MAX_NARROW) return false;
+    // xt_rows = the most patch rows of a tile (set by plan_for for whole rows); a parked row holds the image row.
+    // Units of dw bytes per parked channel, and what follows from them:
+    auto park = [&](int d, int cols, bool shift) {
+        const int units = p.xt_rows * (cols * 2 / d);
+        const int upc = units <= 64 ? 64 : units <= 128 ? 128 : 256;
+        if (units > 256 || (d == 16 && upc != 64)) return false;
+        const int xtr = (2 * p.xt_rows * ((cols + 15) / 16) + 15) / 16;
+        if (!pl->wide && xtr > V2_XTR_MAX_NARROW) return false;
+        dw = d; p.xt_cols = cols; p.xt_shift = shift ? 1 : 0; p.xt_upc = upc;
+        p.xg_rounds = 16 * upc / 256;
+        p.xtr_rounds = xtr;
+        return true;
+    };
+    // Whole rows of 8 * odd bytes (28 columns) whose channels start on 16-byte boundaries: 16-byte loads from the
+    // boundary at or below each row, if the longer parked rows fit; else 4-byte loads.
+    const bool can_shift = !pl->wide && dw == 4 && p.Win % 4 == 0 && (p.Hin * p.Win) % 8 == 0;
+    if (!(can_shift && park(16, (p.Win + 4 + 7) / 8 * 8, true)) &&
+        !park(dw, pl->wide ? WIDE_LWP : dw == 16 ? p.Win : (p.Win + 3) / 4 * 4, false))
+        return false;
     const int chstride = p.xt_upc * dw + V2_CH_PAD;
     p.pk_bytes = (16 * chstride + V2_PK_SLACK + 15) / 16 * 16;
     if (p.pk_bytes > 0xffff) return false;   // transposition offsets are 16 bits
@@ -227,6 +237,7 @@ bool problem_of(const ConvGeom &g, bool bwd_data, TileProblem *p)
     }
     p->out_bf16 = g.out_bf16;
     p->stats = nullptr;
+    p->xt_shift = 0;
     return true;
 }
 

@@ -128,8 +128,9 @@ __device__ __forceinline__ void conv_tile2_body(const bf16_t *__restrict__ in, c
         const int unit = e % upr, srow = e / upr;
         if (srow < lrows) {
             const int u = u0 + srow, n = WIDE ? img : u / p.Hp, h = u - n * p.Hp - p.padh;
-            const int col0 = (WIDE ? q0 - 8 : 0) + unit * (DW / 2);
-            if (n < p.N && (unsigned)h < (unsigned)p.Hin && col0 >= 0 && col0 < p.Win)
+            const int sh = (!WIDE && DW == 16 && p.xt_shift) ? (h * p.Win) & 7 : 0;   // the row starts sh elements into its first unit
+            const int col0 = (WIDE ? q0 - 8 : -sh) + unit * (DW / 2);
+            if (n < p.N && (unsigned)h < (unsigned)p.Hin && col0 > -(DW / 2) && col0 < p.Win)
                 xg_off = (uint32_t)(((n * p.Cin + xg_sub) * p.Hin + h) * p.Win + col0) * 2u;
         }
     }
@@ -168,7 +169,12 @@ __device__ __forceinline__ void conv_tile2_body(const bf16_t *__restrict__ in, c
             const int xo = unit & 1, t2 = unit >> 1, cg = t2 % ncg, prow = t2 / ncg;
             uint32_t src = 0, dst = trash;
             if (prow < lrows) {
-                src = (uint32_t)((xo * 8 + (j >> 2)) * chstride + (prow * pitch + cg * 16 + (j & 3) * 4) * 2);
+                int sh = 0;
+                if (!WIDE && DW == 16 && p.xt_shift) {
+                    const int u = u0 + prow, n = u / p.Hp, h = u - n * p.Hp - p.padh;
+                    sh = (h * p.Win) & 7;
+                }
+                src = (uint32_t)((xo * 8 + (j >> 2)) * chstride + (prow * pitch + sh + cg * 16 + (j & 3) * 4) * 2);
                 const int pcol = cg * 16 + j;
                 // WIDE: the parked patch starts 8 columns left of the tile, the patch buffer padw columns left of it
                 const int lcol = WIDE ? pcol - 8 + p.padw : pcol + p.padw;

@@ -67,6 +67,13 @@ CASES = [
     # 32-column patches with no padding, and with more than the filter needs
     (L("wide_pad0", 32, 20, 112, 96, 3, 3, (1, 1), (0, 0)), 1),
     (L("wide_pad2", 32, 12, 72, 96, 3, 3, (1, 1), (2, 2)), 2),
+    # whole rows of 8 * odd bytes (28, 12, 20 columns) with channels on 16-byte boundaries: 16-byte patch loads
+    # that start before the row; tiles that cross images; a plane that rules the form out (27 x 28)
+    (L("w28_shift", 40, 28, 28, 136, 3, 3, (1, 1), (1, 1)), 2),
+    (L("w28_shift_bwd", 136, 28, 28, 72, 3, 3, (1, 1), (1, 1)), 3),
+    (L("w12_shift", 48, 12, 12, 130, 3, 3, (1, 1), (1, 1)), 5),
+    (L("w20_shift_pad0", 32, 10, 20, 128, 3, 3, (1, 1), (0, 0)), 3),
+    (L("w28_h27", 32, 27, 28, 128, 3, 3, (1, 1), (1, 1)), 2),
     # filters of more than 2 MB: the XCDs keep to their channel tiles (8 tiles: one each; 16: two each; 4: pairs of XCDs)
     (L("1x1_k1024", 1040, 7, 7, 1024, 1, 1), 2),
     (L("1x1_k2048", 528, 7, 7, 2048, 1, 1), 2),
