@@ -57,6 +57,7 @@ struct RowsProblem {
     int nchunks, cps;           // total chunks, chunks per slice
     int ctiles, ktiles;
     int xcd_slices;             // > 0: one-dimensional grid, this many slices per XCD
+    int nslices;                // with xcd_slices > 0: slice z takes the chunks z, z + nslices, ...
 };
 
 struct __attribute__((packed, aligned(2))) U128u { u32x4 v; };
@@ -354,7 +355,13 @@ wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
         for (int i = NITEMS - LAG; i < NITEMS; ++i) item_store(i, buf ^ 1);
     };
 
-    const int cbeg = zslice * p.cps, cend = min(p.nchunks, cbeg + p.cps);
+    // The chunks of a slice.  With the XCD-aware grid the slices interleave: at any time the workgroups
+    // of an XCD work on neighbouring chunks -- the column tiles of the same image rows, whose 64-byte
+    // row segments share cache lines and DRAM pages, and the row chunks next to them, which share halo
+    // rows -- instead of 256 places far apart.  Otherwise a slice is a contiguous range.
+    const int cstep = p.xcd_slices > 0 ? p.nslices : 1;
+    const int cbeg = p.xcd_slices > 0 ? zslice : zslice * p.cps;
+    const int cend = p.xcd_slices > 0 ? p.nchunks : min(p.nchunks, cbeg + p.cps);
     __syncthreads();   // the zero fill is complete
     if (cbeg < cend) {
         set_chunk(cbeg);
@@ -365,9 +372,12 @@ wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
         for (int i = 0; i < NITEMS; ++i) item_store(i, 0);
     }
     __syncthreads();
-    for (int chunk = cbeg, buf = 0; chunk < cend; ++chunk, buf ^= 1) {
+    for (int chunk = cbeg, buf = 0; chunk < cend; chunk += cstep, buf ^= 1) {
         // every round stages a chunk; past the end it is the last chunk again
-        if (chunk + 1 < cend) next_chunk();
+        if (chunk + cstep < cend) {
+            if (cstep == 1) next_chunk();
+            else set_chunk(chunk + cstep);
+        }
         begin_chunk();
         compute(buf);
         __syncthreads();
@@ -492,6 +502,7 @@ bool make_rplan(const ConvGeom &g, RPlan *pl)
     slices = (p.nchunks + p.cps - 1) / p.cps;
     p.ktiles = ktiles;
     p.xcd_slices = 0;
+    p.nslices = (int)slices;
     pl->nslices = (int)slices;
     pl->grid = dim3(p.ctiles, ktiles, (unsigned)slices);
     if (slices % 8 == 0 && tiles * slices <= 0x7fffffffLL) {
