@@ -390,21 +390,24 @@ __global__ void reduce_partials_kernel(const float *__restrict__ partial, float 
     dw[i] = s;
 }
 
-// The same sum for n a multiple of 4, 16 bytes per load: a workgroup of 16 x 16 threads takes 64
-// consecutive elements; thread (tx, ty) adds slices ty, ty + 16, ... of its four elements in
-// ascending order, and the 16 sums are added in the order of ty.  The order is fixed, so the
-// result is the same from run to run.
+// The same sum for n a multiple of 4, 16 bytes per load: a workgroup of TX x TY threads (256 in all)
+// takes TX consecutive float4; thread (tx, ty) adds slices ty, ty + TY, ... of its element in
+// ascending order, and the TY sums are added in the order of ty.  The order is fixed, so the result
+// is the same from run to run.  Few slices: TY = 4, so that a thread still has several loads in
+// flight and a row of lanes reads 1 KB at a stretch; many slices: TY = 16.
+template <int TY>
 __global__ void __launch_bounds__(256)
 reduce_partials4_kernel(const float4 *__restrict__ partial, float4 *__restrict__ dw, size_t n4, int splits,
                         bool accumulate)
 {
-    __shared__ float4 part[16][16];
-    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
-    const size_t i = (size_t)blockIdx.x * 16 + tx;
+    constexpr int TX = 256 / TY;
+    __shared__ float4 part[TY][TX];
+    const int tx = threadIdx.x % TX, ty = threadIdx.x / TX;
+    const size_t i = (size_t)blockIdx.x * TX + tx;
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
     if (i < n4) {
 #pragma unroll 4
-        for (int z = ty; z < splits; z += 16) {
+        for (int z = ty; z < splits; z += TY) {
             const float4 v = partial[(size_t)z * n4 + i];
             s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
         }
@@ -413,7 +416,7 @@ reduce_partials4_kernel(const float4 *__restrict__ partial, float4 *__restrict__
     __syncthreads();
     if (ty == 0 && i < n4) {
         float4 t = accumulate ? dw[i] : make_float4(0.f, 0.f, 0.f, 0.f);
-        const int ny = splits < 16 ? splits : 16;
+        const int ny = splits < TY ? splits : TY;
         for (int y = 0; y < ny; ++y) {
             const float4 v = part[y][tx];
             t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w;
@@ -528,9 +531,14 @@ hipError_t launch_reduce_partials(const float *partial, float *dw, size_t n, int
 {
     if (n % 4 == 0 && reinterpret_cast<uintptr_t>(partial) % 16 == 0 && reinterpret_cast<uintptr_t>(dw) % 16 == 0) {
         const size_t n4 = n / 4;
-        hipLaunchKernelGGL(reduce_partials4_kernel, dim3((unsigned)((n4 + 15) / 16)), dim3(256), 0, st,
-                           reinterpret_cast<const float4 *>(partial), reinterpret_cast<float4 *>(dw), n4, splits,
-                           accumulate);
+        const float4 *p4 = reinterpret_cast<const float4 *>(partial);
+        float4 *d4 = reinterpret_cast<float4 *>(dw);
+        if (splits >= 64)
+            hipLaunchKernelGGL(reduce_partials4_kernel<16>, dim3((unsigned)((n4 + 15) / 16)), dim3(256), 0, st, p4, d4,
+                               n4, splits, accumulate);
+        else
+            hipLaunchKernelGGL(reduce_partials4_kernel<4>, dim3((unsigned)((n4 + 63) / 64)), dim3(256), 0, st, p4, d4,
+                               n4, splits, accumulate);
         return hipGetLastError();
     }
     dim3 grid((unsigned)((n + 255) / 256)), block(256);

@@ -72,8 +72,10 @@ struct TileProblem {
     // conv_tile2.h only: load rounds and transposition rounds per chunk, bytes of one parked buffer
     int xg_rounds, xtr_rounds, pk_bytes;
     int xt_upc;              // units of the load size a parked channel has room for (64, 128 or 256)
-    int xt_shift;            // NARROW, 16-byte loads of rows that start on odd multiples of 8 bytes: a parked row begins
-                             // at the 16-byte boundary at or below the image row, (h * Win) % 8 elements before it
+    int xt_shift;            // NARROW, 16-byte loads of rows that do not start on 16-byte boundaries: 0 = off, else the
+                             // number G (1 or 2) of consecutive image rows that make one parked row: G rows start on
+                             // multiples of 8 bytes, and the parked row begins at the 16-byte boundary at or below it
+    int xt_ncg;              // with xt_shift: 16-column groups per patch row in the transposition
     uint32_t in_bytes, w_bytes;   // sizes of the input tensor and of the packed filter
     int nptiles, nktiles, pt_per_xcd;   // pixel tiles, channel tiles, pixel tiles per XCD (the grid is 8 * pt_per_xcd * nktiles)
     // Filters too large for an XCD's L2: kmajor = min(nktiles, 8) XCDs take different channel

@@ -15,14 +15,15 @@ pack_filter_kernel(const bf16_t *__restrict__ w, uint4 *__restrict__ wp, int M, 
 {
     // Threads are numbered so that neighbours read neighbouring source elements: the tap runs
     // fastest, then (forward) the half and the row, or (backward-data) the row and the half.
-    size_t q = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (q >= items) return;
+    // (the filter has fewer than 2^31 elements, so there are fewer than 2^28 items: 32-bit arithmetic)
+    if ((size_t)blockIdx.x * 256 + threadIdx.x >= items) return;
+    uint32_t q = blockIdx.x * 256u + threadIdx.x;
     const int T = R * S, TRES = R * SG, NSUB = S / SG;
-    const int tap = (int)(q % T);
-    q /= T;
+    const int tap = (int)(q % (uint32_t)T);
+    q /= (uint32_t)T;
     int hs, m;
-    if (tflip) { m = (int)(q % Mpad); q /= Mpad; hs = (int)(q & 1); q >>= 1; }
-    else { hs = (int)(q & 1); q >>= 1; m = (int)(q % Mpad); q /= Mpad; }
+    if (tflip) { m = (int)(q % (uint32_t)Mpad); q /= (uint32_t)Mpad; hs = (int)(q & 1); q >>= 1; }
+    else { hs = (int)(q & 1); q >>= 1; m = (int)(q % (uint32_t)Mpad); q /= (uint32_t)Mpad; }
     const int chunk = (int)q;
     const int r = tap / S, s = tap - r * S, sg = s / SG, tl = r * SG + (s - sg * SG);
     const size_t it = ((((size_t)chunk * NSUB + sg) * TRES + tl) * Mpad + m) * 2 + hs;
@@ -167,24 +168,31 @@ bool make_plan2(const TileProblem &base, int R, int S, Plan *pl)
         p.xt_rows = pixt / 32 + R - 1;
         p.xt_cols = WIDE_LWP;
     }
-    // xt_rows = the most patch rows of a tile (set by plan_for for whole rows); a parked row holds the image row.
-    // Units of dw bytes per parked channel, and what follows from them:
-    auto park = [&](int d, int cols, bool shift) {
-        const int units = p.xt_rows * (cols * 2 / d);
+    // xt_rows = the most patch rows of a tile (set by plan_for for whole rows); a parked row holds `group` image rows
+    // (0: one, on its own 16- or 4-byte boundary).  Units of d bytes per parked channel, and what follows from them:
+    auto park = [&](int d, int cols, int group) {
+        const int prows = group > 1 ? (p.xt_rows + group - 1) / group + 1 : p.xt_rows;
+        const int units = prows * (cols * 2 / d);
         const int upc = units <= 64 ? 64 : units <= 128 ? 128 : 256;
         if (units > 256 || (d == 16 && upc != 64)) return false;
-        const int xtr = (2 * p.xt_rows * ((cols + 15) / 16) + 15) / 16;
+        const int ncg = group ? (p.Win + 2 + 15) / 16 : (cols + 15) / 16;
+        const int xtr = (2 * p.xt_rows * ncg + 15) / 16;
         if (!pl->wide && xtr > V2_XTR_MAX_NARROW) return false;
-        dw = d; p.xt_cols = cols; p.xt_shift = shift ? 1 : 0; p.xt_upc = upc;
+        dw = d; p.xt_cols = cols; p.xt_shift = group; p.xt_ncg = ncg; p.xt_upc = upc;
         p.xg_rounds = 16 * upc / 256;
         p.xtr_rounds = xtr;
         return true;
     };
-    // Whole rows of 8 * odd bytes (28 columns) whose channels start on 16-byte boundaries: 16-byte loads from the
-    // boundary at or below each row, if the longer parked rows fit; else 4-byte loads.
-    const bool can_shift = !pl->wide && dw == 4 && p.Win % 4 == 0 && (p.Hin * p.Win) % 8 == 0;
-    if (!(can_shift && park(16, (p.Win + 4 + 7) / 8 * 8, true)) &&
-        !park(dw, pl->wide ? WIDE_LWP : dw == 16 ? p.Win : (p.Win + 3) / 4 * 4, false))
+    // Whole rows that are not multiples of 16 bytes: 16-byte loads all the same where one row (28 columns) or two
+    // consecutive rows (14 columns) are a multiple of 8 bytes and every channel starts on one: a parked row then
+    // starts at the 16-byte boundary at or below its first image row.  If the longer parked rows do not fit: 4-byte loads.
+    const long long HW = (long long)p.Hin * p.Win;
+    const bool tight = !pl->wide && dw == 4;
+    const bool shift1 = tight && p.Win % 4 == 0 && HW % 8 == 0;
+    const bool shift2 = tight && !shift1 && p.Win % 2 == 0 && p.Hin % 2 == 0 && p.Hp % 2 == 0 && HW % 4 == 0 &&
+                        (p.Cin * HW) % 8 == 0;
+    if (!(shift1 && park(16, (p.Win + 4 + 7) / 8 * 8, 1)) && !(shift2 && park(16, (2 * p.Win + 4 + 7) / 8 * 8, 2)) &&
+        !park(dw, pl->wide ? WIDE_LWP : dw == 16 ? p.Win : (p.Win + 3) / 4 * 4, 0))
         return false;
     const int chstride = p.xt_upc * dw + V2_CH_PAD;
     p.pk_bytes = (16 * chstride + V2_PK_SLACK + 15) / 16 * 16;
@@ -238,6 +246,7 @@ bool problem_of(const ConvGeom &g, bool bwd_data, TileProblem *p)
     p->out_bf16 = g.out_bf16;
     p->stats = nullptr;
     p->xt_shift = 0;
+    p->xt_ncg = 0;
     return true;
 }
 

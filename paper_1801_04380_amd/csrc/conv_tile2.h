@@ -122,15 +122,21 @@ __device__ __forceinline__ void conv_tile2_body(const bf16_t *__restrict__ in, c
     constexpr uint32_t OUTSIDE = 0x80000000u;
     const __amdgpu_buffer_rsrc_t in_rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(in), 0, p.in_bytes, 0x00020000);
     const int xg_sub = tid / upc;     // the thread's channel within a round
+    // Shifted 16-byte loads (whole rows only): G image rows per parked row, groups aligned to even image rows.
+    const int G = (!WIDE && DW == 16) ? p.xt_shift : 0;
+    const int ubase = G > 1 ? u0 - ((u0 - p.padh) & (G - 1)) : u0;   // first patch row of the first group
+    const int nprk = G > 1 ? (u0 + lrows - 1 - ubase) / G + 1 : lrows;   // parked rows of this tile
     uint32_t xg_off = OUTSIDE;        // byte offset of the thread's unit in channel xg_sub of chunk 0
     {
         const int e = tid - xg_sub * upc;
         const int unit = e % upr, srow = e / upr;
-        if (srow < lrows) {
-            const int u = u0 + srow, n = WIDE ? img : u / p.Hp, h = u - n * p.Hp - p.padh;
-            const int sh = (!WIDE && DW == 16 && p.xt_shift) ? (h * p.Win) & 7 : 0;   // the row starts sh elements into its first unit
+        if (srow < nprk) {
+            // (G > 1: u is the first row of the group, an even image row or a padding row: n and h are then those of
+            // no image row, u < 0 included, and nothing is loaded)
+            const int u = G > 1 ? ubase + G * srow : u0 + srow, n = WIDE ? img : u / p.Hp, h = u - n * p.Hp - p.padh;
+            const int sh = G ? (xg_sub * HWin + h * p.Win) & 7 : 0;   // the row starts sh elements into its first unit
             const int col0 = (WIDE ? q0 - 8 : -sh) + unit * (DW / 2);
-            if (n < p.N && (unsigned)h < (unsigned)p.Hin && col0 > -(DW / 2) && col0 < p.Win)
+            if (n < p.N && (unsigned)h < (unsigned)p.Hin && col0 > -(DW / 2) && col0 < (G > 1 ? G : 1) * p.Win)
                 xg_off = (uint32_t)(((n * p.Cin + xg_sub) * p.Hin + h) * p.Win + col0) * 2u;
         }
     }
@@ -161,7 +167,7 @@ __device__ __forceinline__ void conv_tile2_body(const bf16_t *__restrict__ in, c
     uint32_t xs_sd[XTR];   // byte offset of the lane's first read | 16-byte LDS index of its pixel << 16
     {
         const int blk = tid >> 4, j = tid & 15;
-        const int ncg = (pitch + 15) >> 4;
+        const int ncg = G ? p.xt_ncg : (pitch + 15) >> 4;
         const uint32_t trash = (uint32_t)(p.xslots * 2 + lane);   // where a lane without a pixel writes
 #pragma unroll
         for (int rd = 0; rd < XTR; ++rd) {
@@ -169,16 +175,22 @@ __device__ __forceinline__ void conv_tile2_body(const bf16_t *__restrict__ in, c
             const int xo = unit & 1, t2 = unit >> 1, cg = t2 % ncg, prow = t2 / ncg;
             uint32_t src = 0, dst = trash;
             if (prow < lrows) {
-                int sh = 0;
-                if (!WIDE && DW == 16 && p.xt_shift) {
+                // where the patch row starts in its parked row, rounded down to the 8 bytes the transposing
+                // read needs; cadj: the columns that rounding puts before the row
+                int grow = prow, roff = 0, cadj = 0;
+                if (G) {
                     const int u = u0 + prow, n = u / p.Hp, h = u - n * p.Hp - p.padh;
-                    sh = (h * p.Win) & 7;
+                    const int jr = (u - ubase) & (G - 1);   // row within its group
+                    grow = (u - ubase) / G;
+                    roff = (((j >> 2) * HWin + (h - jr) * p.Win) & 7) + jr * p.Win;
+                    cadj = roff & 3;
+                    roff -= cadj;
                 }
-                src = (uint32_t)((xo * 8 + (j >> 2)) * chstride + (prow * pitch + sh + cg * 16 + (j & 3) * 4) * 2);
-                const int pcol = cg * 16 + j;
+                src = (uint32_t)((xo * 8 + (j >> 2)) * chstride + (grow * pitch + roff + cg * 16 + (j & 3) * 4) * 2);
+                const int pcol = cg * 16 + j - cadj;
                 // WIDE: the parked patch starts 8 columns left of the tile, the patch buffer padw columns left of it
                 const int lcol = WIDE ? pcol - 8 + p.padw : pcol + p.padw;
-                const bool ok = WIDE ? (lcol >= 0 && lcol < p.LW) : pcol < p.Win;
+                const bool ok = WIDE ? (lcol >= 0 && lcol < p.LW) : (pcol >= 0 && pcol < p.Win);
                 if (ok) {
                     const int slot = prow * LWp + lcol;
                     dst = (uint32_t)(slot * 2 + (xo ^ swz(slot)));

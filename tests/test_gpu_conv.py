@@ -74,6 +74,13 @@ CASES = [
     (L("w12_shift", 48, 12, 12, 130, 3, 3, (1, 1), (1, 1)), 5),
     (L("w20_shift_pad0", 32, 10, 20, 128, 3, 3, (1, 1), (0, 0)), 3),
     (L("w28_h27", 32, 27, 28, 128, 3, 3, (1, 1), (1, 1)), 2),
+    # rows of 4 * odd bytes (14, 6, 10, 22 columns): two rows to a 16-byte-loaded unit; odd channel counts rule it out
+    (L("w14_pairs", 48, 14, 14, 130, 3, 3, (1, 1), (1, 1)), 5),
+    (L("w14_pairs_bwd", 130, 14, 14, 72, 3, 3, (1, 1), (1, 1)), 3),
+    (L("w6_pairs", 32, 6, 6, 128, 3, 3, (1, 1), (1, 1)), 7),
+    (L("w10_pairs_pad0", 32, 10, 10, 128, 3, 3, (1, 1), (0, 0)), 3),
+    (L("w22_pairs", 24, 8, 22, 96, 3, 3, (1, 1), (1, 1)), 3),
+    (L("w14_c35", 35, 14, 14, 128, 3, 3, (1, 1), (1, 1)), 2),
     # filters of more than 2 MB: the XCDs keep to their channel tiles (8 tiles: one each; 16: two each; 4: pairs of XCDs)
     (L("1x1_k1024", 1040, 7, 7, 1024, 1, 1), 2),
     (L("1x1_k2048", 528, 7, 7, 2048, 1, 1), 2),
