@@ -1040,6 +1040,51 @@ maxpool2_bwd_kernel(const T *__restrict__ dy, const int32_t *__restrict__ idx, T
     }
 }
 
+// 3x3 windows, stride 2 (the overlapping pool of the AlexNet- and Inception-style workloads),
+// backward: a thread owns 8 neighbouring columns of one input row.  At most 2 window rows and
+// 5 window columns cover them; every window's index and gradient are read once per thread and
+// added, in ascending (p, q) order -- the order of the one-thread-per-element kernel -- to
+// the column the index names, and the row piece leaves in one store.
+template <typename T>
+__global__ void __launch_bounds__(256)
+maxpool3s2_bwd_kernel(const T *__restrict__ dy, const int32_t *__restrict__ idx, T *__restrict__ dx, unsigned rows,
+                      int H, int W, int P, int Q, int ph, int pw, int lg)
+{
+    const unsigned row = blockIdx.x * (256u >> lg) + (threadIdx.x >> lg);
+    const int g = threadIdx.x & ((1 << lg) - 1);
+    if (row >= rows || g * 8 >= W) return;
+    const unsigned nc = row / (unsigned)H;
+    const int h = (int)(row - nc * (unsigned)H), v0 = 8 * g;
+    const int ncol = min(8, W - v0);
+    // windows p with 2p - ph <= h <= 2p - ph + 2, windows q that reach one of the columns
+    const int p0 = max(0, (h + ph - 1) >> 1), p1 = min((h + ph) >> 1, P - 1);
+    const int q0 = max(0, (v0 + pw - 1) >> 1), q1 = min((v0 + ncol - 1 + pw) >> 1, Q - 1);
+    const T *gp = dy + (size_t)nc * P * Q;
+    const int32_t *ip = idx + (size_t)nc * P * Q;
+    const int first = h * W + v0;
+    float acc[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) acc[c] = 0.f;
+    for (int p = p0; p <= p1; ++p)
+        for (int q = q0; q <= q1; ++q) {
+            const int rel = ip[p * Q + q] - first;
+            const float d = ld<T>(gp + p * Q + q);
+#pragma unroll
+            for (int c = 0; c < 8; ++c) acc[c] += rel == c ? d : 0.f;
+        }
+    T *o = dx + (size_t)row * W + v0;
+    if (ncol == 8) {
+        Pack<T, 8> out;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) st(&out.e[c], acc[c]);
+        *reinterpret_cast<Pack<T, 8> *>(o) = out;
+    } else {
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+            if (c < ncol) st(o + c, acc[c]);
+    }
+}
+
 // ------------------------------------------------------------------ LRN
 // LRN across channels (definition in sn.h).  A thread owns VEC neighbouring positions of one
 // image and walks the channels, which are H*W elements apart, so a wave reads one contiguous run
@@ -1490,6 +1535,16 @@ hipError_t launch_maxpool_bwd(const void *dy, const int32_t *idx, void *dx, int 
             typedef typename std::remove_pointer<decltype(tag)>::type T;
             hipLaunchKernelGGL(maxpool2_bwd_kernel<T>, dim3((rows + rpb - 1) / rpb), dim3(256), 0, s, (const T *)dy,
                                idx, (T *)dx, rows, H, W, P, Q, lg);
+        });
+    }
+    if (kh == 3 && kw == 3 && sh == 2 && sw == 2 && ph >= 0 && ph <= 2 && pw >= 0 && pw <= 2 && P > 0 && Q > 0 &&
+        (long long)NC * H <= 0x7fffffffLL && log2_groups((W + 7) / 8) >= 0) {
+        const int lg = log2_groups((W + 7) / 8);
+        const unsigned rows = (unsigned)NC * H, rpb = 256u >> lg;
+        return by_dtype(bf16, [&](auto *tag) {
+            typedef typename std::remove_pointer<decltype(tag)>::type T;
+            hipLaunchKernelGGL(maxpool3s2_bwd_kernel<T>, dim3((rows + rpb - 1) / rpb), dim3(256), 0, s, (const T *)dy,
+                               idx, (T *)dx, rows, H, W, P, Q, ph, pw, lg);
         });
     }
     const unsigned bpp = (unsigned)(((long long)H * W + 255) / 256);

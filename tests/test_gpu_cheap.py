@@ -260,7 +260,10 @@ POOL_CASES = [((2, 16, 16, 16), (2, 2), (2, 2), (0, 0)), ((2, 8, 55, 55), (3, 3)
               ((2, 4, 224, 224), (2, 2), (2, 2), (0, 0)), ((2, 3, 15, 15), (2, 2), (2, 2), (0, 0)),
               ((1, 2, 8, 8), (3, 3), (1, 1), (1, 1)), ((3, 5, 14, 14), (2, 2), (2, 2), (0, 0)),
               ((1, 2, 2, 2), (2, 2), (2, 2), (0, 0)), ((2, 3, 33, 20), (2, 2), (2, 2), (0, 0)),
-              ((1, 2, 6, 300), (2, 2), (2, 2), (0, 0))]
+              ((1, 2, 6, 300), (2, 2), (2, 2), (0, 0)),
+              # 3x3 / stride 2 backward by row pieces of 8 columns: wide rows, padding, a column no window covers
+              ((1, 2, 10, 150), (3, 3), (2, 2), (0, 0)), ((2, 3, 12, 40), (3, 3), (2, 2), (1, 1)),
+              ((1, 2, 8, 8), (3, 3), (2, 2), (0, 0)), ((1, 2, 4, 3), (3, 3), (2, 2), (1, 1))]
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
