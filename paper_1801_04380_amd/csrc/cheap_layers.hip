@@ -881,7 +881,8 @@ Slices make_slices(int N, int C, int HW, size_t scratch_bytes)
 }
 
 // ------------------------------------------------------------------ max-pool
-template <typename T>
+// One thread per output.  IX: the type the output number is split in (32 bits where they do).
+template <typename T, typename IX>
 __global__ void __launch_bounds__(256)
 maxpool_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, int32_t *__restrict__ idx, size_t total,
                    int H, int W, int P, int Q, int kh, int kw, int sh, int sw, int ph, int pw)
@@ -889,7 +890,7 @@ maxpool_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, int32_t *__restri
     const size_t o = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (o >= total) return;
     const int PQ = P * Q;
-    const size_t nc = o / PQ;
+    const size_t nc = (size_t)((IX)o / (IX)PQ);
     const int pq = (int)(o - nc * PQ), p = pq / Q, q = pq - p * Q;
     const T *xp = x + nc * (size_t)H * W;
     const int h0 = p * sh - ph, v0 = q * sw - pw;
@@ -1518,8 +1519,12 @@ hipError_t launch_maxpool_fwd(const void *x, void *y, int32_t *idx, int NC, int 
     return by_dtype(bf16, [&](auto *tag) {
         typedef typename std::remove_pointer<decltype(tag)>::type T;
         dim3 grid((unsigned)((total + 255) / 256)), block(256);
-        hipLaunchKernelGGL(maxpool_fwd_kernel<T>, grid, block, 0, s, (const T *)x, (T *)y, idx, total, H, W, P,
-                           Q, kh, kw, sh, sw, ph, pw);
+        if (total <= 0xffffffffull)
+            hipLaunchKernelGGL((maxpool_fwd_kernel<T, uint32_t>), grid, block, 0, s, (const T *)x, (T *)y, idx, total, H,
+                               W, P, Q, kh, kw, sh, sw, ph, pw);
+        else
+            hipLaunchKernelGGL((maxpool_fwd_kernel<T, size_t>), grid, block, 0, s, (const T *)x, (T *)y, idx, total, H,
+                               W, P, Q, kh, kw, sh, sw, ph, pw);
     });
 }
 
