@@ -1115,8 +1115,9 @@ __device__ inline float pow_neg(float s, float beta) { return __builtin_amdgcn_e
 template <typename T, int VEC, int HALF>
 __global__ void __launch_bounds__(256)
 lrn_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, int C, int HW, int vpp, size_t total, float a_n,
-               float beta, float k)
+               float beta, float k, int cc)
 {
+    const int cb = blockIdx.y * cc, ce = min(C, cb + cc);   // this workgroup's channels
     constexpr int SIZE = 2 * HALF + 1;
     const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (t >= total) return;
@@ -1127,19 +1128,19 @@ lrn_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, int C, int HW, int vp
 #pragma unroll
         for (int v = 0; v < VEC; ++v) xr[i][v] = 0.f;
 #pragma unroll 8
-    for (int m = 0; m < C + HALF; ++m) {
+    for (int m = cb - HALF; m < ce + HALF; ++m) {
 #pragma unroll
         for (int i = 0; i + 1 < SIZE; ++i)
 #pragma unroll
             for (int v = 0; v < VEC; ++v) xr[i][v] = xr[i + 1][v];
-        if (m < C) {
+        if (m >= 0 && m < C) {
             LrnIo<T, VEC>::load(x + off + (size_t)m * HW, xr[SIZE - 1]);
         } else {
 #pragma unroll
             for (int v = 0; v < VEC; ++v) xr[SIZE - 1][v] = 0.f;
         }
         const int c = m - HALF;
-        if (c < 0) continue;
+        if (c < cb) continue;
         float out[VEC];
 #pragma unroll
         for (int v = 0; v < VEC; ++v) {
@@ -1155,8 +1156,9 @@ lrn_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, int C, int HW, int vp
 template <typename T, int VEC, int HALF>
 __global__ void __launch_bounds__(256)
 lrn_bwd_kernel(const T *__restrict__ x, const T *__restrict__ dy, T *__restrict__ dx, int C, int HW, int vpp,
-               size_t total, float a_n, float beta, float k)
+               size_t total, float a_n, float beta, float k, int cc)
 {
+    const int cb = blockIdx.y * cc, ce = min(C, cb + cc);   // this workgroup's channels
     constexpr int SIZE = 2 * HALF + 1, H1 = HALF + 1;
     const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (t >= total) return;
@@ -1172,7 +1174,7 @@ lrn_bwd_kernel(const T *__restrict__ x, const T *__restrict__ dy, T *__restrict_
         for (int i = 0; i < H1; ++i) pr[i][v] = gr[i][v] = 0.f;
     }
 #pragma unroll 8
-    for (int m = 0; m < C + 2 * HALF; ++m) {
+    for (int m = cb - 2 * HALF; m < ce + 2 * HALF; ++m) {
 #pragma unroll
         for (int v = 0; v < VEC; ++v) {
 #pragma unroll
@@ -1182,7 +1184,7 @@ lrn_bwd_kernel(const T *__restrict__ x, const T *__restrict__ dy, T *__restrict_
             xr[SIZE - 1][v] = 0.f;
             rr[SIZE - 1][v] = pr[H1 - 1][v] = gr[H1 - 1][v] = 0.f;
         }
-        if (m < C) LrnIo<T, VEC>::load(x + off + (size_t)m * HW, xr[SIZE - 1]);
+        if (m >= 0 && m < C) LrnIo<T, VEC>::load(x + off + (size_t)m * HW, xr[SIZE - 1]);
         const int j = m - HALF;   // the channel whose window is complete: x_j = xr[HALF]
         if (j < 0) continue;
         if (j < C) {
@@ -1198,7 +1200,7 @@ lrn_bwd_kernel(const T *__restrict__ x, const T *__restrict__ dy, T *__restrict_
             }
         }
         const int c = j - HALF;   // every r of its window is known: x_c = xr[0], dy_c = gr[0], s_c^(-beta) = pr[0]
-        if (c < 0) continue;
+        if (c < cb) continue;
         float out[VEC];
 #pragma unroll
         for (int v = 0; v < VEC; ++v) {
@@ -1473,13 +1475,20 @@ hipError_t lrn_launch(bool bwd, const void *x, const void *dy, void *out, int N,
 {
     const int vpp = HW / VEC;
     const size_t total = (size_t)N * vpp;
-    const dim3 grid((unsigned)((total + 255) / 256)), block(256);
+    // A thread walks its channels one after the other: with few positions the channels are split over
+    // blockIdx.y (each part re-reads the HALF or 2 HALF channels beside it) until there are enough threads.
+    // (measured on 128 x 256 x 27 x 27: 5 parts of 52 channels 3.1 TB/s forward, 1 part 0.9, 6 parts of 43 2.4)
+    long long parts = total >= 400000 ? 1 : (450000 + (long long)total - 1) / (long long)total;
+    if (parts > (C + 7) / 8) parts = (C + 7) / 8;
+    if (parts < 1) parts = 1;
+    const int cc = (int)((C + parts - 1) / parts + 3) / 4 * 4, ny = (C + cc - 1) / cc;
+    const dim3 grid((unsigned)((total + 255) / 256), (unsigned)ny), block(256);
 #define SN_LRN(H_)                                                                                                  \
     case H_:                                                                                                        \
         if (bwd) hipLaunchKernelGGL((lrn_bwd_kernel<T, VEC, H_>), grid, block, 0, s, (const T *)x, (const T *)dy,  \
-                                    (T *)out, C, HW, vpp, total, a_n, beta, k);                                    \
+                                    (T *)out, C, HW, vpp, total, a_n, beta, k, cc);                                \
         else hipLaunchKernelGGL((lrn_fwd_kernel<T, VEC, H_>), grid, block, 0, s, (const T *)x, (T *)out, C, HW,    \
-                                vpp, total, a_n, beta, k);                                                          \
+                                vpp, total, a_n, beta, k, cc);                                                      \
         break;
     switch (half) {
         SN_LRN(0) SN_LRN(1) SN_LRN(2) SN_LRN(3) SN_LRN(4)

@@ -230,7 +230,7 @@ def test_bn_relu_pool2_unsupported():
 
 
 LRN_SHAPES = [(2, 16, 8, 8), (2, 96, 27, 27), (1, 3, 5, 7), (3, 2, 4, 4), (2, 1, 3, 3), (2, 256, 13, 13),
-              (4, 40, 16, 20)]
+              (4, 40, 16, 20), (2, 6, 5, 6), (3, 4, 1, 1), (1, 7, 55, 55)]
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
