@@ -488,7 +488,7 @@ bool make_rplan(const ConvGeom &g, RPlan *pl)
     p.nchunks = (int)nch;
     // 64 k per workgroup of 256 threads; 128 k per 512 threads (two waves per SIMD, half the L1
     // traffic per MFMA, but twice the bytes the slices add into dw) where there is enough work
-    const int TM = (g.K >= 256 && (long long)g.N * g.P * g.Q >= 20000) ? 2 : 1, KTB = 2 * TM * 32;
+    const int TM = (g.K >= 128 && (long long)g.N * g.P * g.Q >= 20000) ? 2 : 1, KTB = 2 * TM * 32;
     p.ctiles = (g.C + CTB - 1) / CTB;
     const int ktiles = (g.K + KTB - 1) / KTB;
     if (ktiles > 65535) return false;
