@@ -231,9 +231,10 @@ __device__ __forceinline__ void conv_tile2_body(const bf16_t *__restrict__ in, c
     const __amdgpu_buffer_rsrc_t w_rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(w), 0, p.w_bytes, 0x00020000);
     const uint32_t wlane = (uint32_t)(((k0 + wk * 64 + l32) * 2 + (g ^ swz(l32))) * 16);
     const uint32_t wtap = (uint32_t)p.Mpad * 32u;   // bytes per tap
-    // Register sets of filter operands: a stage's set is loaded AD - 1 stages ahead.  Small tiles
-    // have short stages and few registers in accumulators: they look further ahead.
-    constexpr int AD = (NF >= 4) ? 2 : 2 * NSUB;
+    // Register sets of filter operands: a stage's set is loaded AD - 1 stages ahead.  (Looking five
+    // stages ahead on the small tiles, whose stages are short, measured 3-8 % slower than one: the 144
+    // registers of six sets cost more than the latency they cover.)
+    constexpr int AD = 2;
     static_assert((2 * NSUB) % AD == 0, "a trip of the main loop must use every set equally often");
     u32x4 areg[AD][TRES * 2];
     auto load_a = [&](int stage, u32x4(&dst)[TRES * 2]) {
