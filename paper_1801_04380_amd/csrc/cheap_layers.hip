@@ -1041,6 +1041,80 @@ maxpool2_bwd_kernel(const T *__restrict__ dy, const int32_t *__restrict__ idx, T
     }
 }
 
+// 3x3 windows, stride 2, forward: a thread owns 4 neighbouring windows of one output row, i.e.
+// 9 columns of 3 input rows, which it reads as one 8-element piece and one element per row where the
+// piece lies inside the image and the tensor (anything else: element by element).  The scan of a
+// window is the generic kernel's: row-major over the positions inside the image, a later element
+// wins only if strictly greater.
+template <typename T>
+__global__ void __launch_bounds__(256)
+maxpool3s2_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, int32_t *__restrict__ idx, unsigned rows, int H,
+                      int W, int P, int Q, int ph, int pw, int lg, const T *__restrict__ xend)
+{
+    const unsigned row = blockIdx.x * (256u >> lg) + (threadIdx.x >> lg);
+    const int g = threadIdx.x & ((1 << lg) - 1);
+    if (row >= rows || g * 4 >= Q) return;
+    const unsigned nc = row / (unsigned)P;
+    const int p = (int)(row - nc * (unsigned)P), q0 = 4 * g;
+    const int nout = min(4, Q - q0);
+    const int h0 = 2 * p - ph, v0 = 2 * q0 - pw;
+    const T *xp = x + (size_t)nc * H * W;
+    // the 3 x 9 elements; outside the image: never looked at
+    T e[3][9];
+    const bool inside = v0 >= 0 && v0 + 9 <= W;
+#pragma unroll
+    for (int r = 0; r < 3; ++r) {
+        const int h = h0 + r;
+        if ((unsigned)h >= (unsigned)H) {
+#pragma unroll
+            for (int c = 0; c < 9; ++c) e[r][c] = T(0);
+            continue;
+        }
+        const T *rp = xp + (size_t)h * W + v0;
+        if (inside && rp + 9 <= xend) {
+            const Pack<T, 8> v = *reinterpret_cast<const Pack<T, 8> *>(rp);
+#pragma unroll
+            for (int c = 0; c < 8; ++c) e[r][c] = v.e[c];
+            e[r][8] = rp[8];
+        } else {
+#pragma unroll
+            for (int c = 0; c < 9; ++c) e[r][c] = (unsigned)(v0 + c) < (unsigned)W ? rp[c] : T(0);
+        }
+    }
+    Pack<T, 4> out;
+    Pack<int32_t, 4> oi;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        bool have = false;
+        float bv = 0.f;
+        int best = 0;
+        T raw = T(0);
+#pragma unroll
+        for (int r = 0; r < 3; ++r)
+#pragma unroll
+            for (int c = 0; c < 3; ++c) {
+                const int h = h0 + r, v = v0 + 2 * j + c;
+                if ((unsigned)h >= (unsigned)H || (unsigned)v >= (unsigned)W) continue;
+                const T cand = e[r][2 * j + c];
+                const float f = ld<T>(&cand);
+                if (!have) { have = true; bv = f; best = h * W + v; raw = cand; }
+                else if (f > bv) { bv = f; best = h * W + v; raw = cand; }
+            }
+        out.e[j] = raw;
+        oi.e[j] = best;
+    }
+    T *yo = y + (size_t)row * Q + q0;
+    int32_t *io = idx + (size_t)row * Q + q0;
+    if (nout == 4) {
+        *reinterpret_cast<Pack<T, 4> *>(yo) = out;
+        *reinterpret_cast<Pack<int32_t, 4> *>(io) = oi;
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (j < nout) { yo[j] = out.e[j]; io[j] = oi.e[j]; }
+    }
+}
+
 // 3x3 windows, stride 2 (the overlapping pool of the AlexNet- and Inception-style workloads),
 // backward: a thread owns 8 neighbouring columns of one input row.  At most 2 window rows and
 // 5 window columns cover them; every window's index and gradient are read once per thread and
@@ -1523,6 +1597,16 @@ hipError_t launch_maxpool_fwd(const void *x, void *y, int32_t *idx, int NC, int 
             typedef typename std::remove_pointer<decltype(tag)>::type T;
             hipLaunchKernelGGL(maxpool2_fwd_kernel<T>, dim3((rows + rpb - 1) / rpb), dim3(256), 0, s, (const T *)x,
                                (T *)y, idx, rows, H, W, P, Q, lg, (const T *)x + (size_t)NC * H * W);
+        });
+    }
+    if (kh == 3 && kw == 3 && sh == 2 && sw == 2 && ph >= 0 && ph <= 2 && pw >= 0 && pw <= 2 &&
+        (long long)NC * P <= 0x7fffffffLL && (long long)H * W <= 0x7fffffffLL && log2_groups((Q + 3) / 4) >= 0) {
+        const int lg = log2_groups((Q + 3) / 4);
+        const unsigned rows = (unsigned)NC * P, rpb = 256u >> lg;
+        return by_dtype(bf16, [&](auto *tag) {
+            typedef typename std::remove_pointer<decltype(tag)>::type T;
+            hipLaunchKernelGGL(maxpool3s2_fwd_kernel<T>, dim3((rows + rpb - 1) / rpb), dim3(256), 0, s, (const T *)x,
+                               (T *)y, idx, rows, H, W, P, Q, ph, pw, lg, (const T *)x + (size_t)NC * H * W);
         });
     }
     return by_dtype(bf16, [&](auto *tag) {
