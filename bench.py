@@ -39,7 +39,7 @@ PEAK = {"bf16_mfma_tflops": 2500.0, "f32_mfma_tflops": 157.3, "hbm_gbs": 8000.0}
 # HBM bytes per launch of an op class, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this
 # command (profiles/bench_vgg16_n32_hbm_traffic.txt gives the runs, the calibration and the sums).
 # Only for the workload and budget the counters were collected on; anything else reports null.
-MEASURED_TRAFFIC = {("cfg3_vgg16_n32", 2 << 30, "conv_bwd_filter"): 248e6,
+MEASURED_TRAFFIC = {("cfg3_vgg16_n32", 2 << 30, "conv_bwd_filter"): 258e6,
                     # forward and backward-data run the same kernels: one figure for the 25 launches of both
                     ("cfg3_vgg16_n32", 2 << 30, "conv_fwd"): 146e6,
                     ("cfg3_vgg16_n32", 2 << 30, "conv_bwd_data"): 146e6}
