@@ -337,7 +337,6 @@ wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
                             acc[tm][fr * S + s] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                                 aw[pl % (RG + 1)][tm], b[s], acc[tm][fr * S + s], 0, 0, 0);
                 }
-                __builtin_amdgcn_sched_barrier(0);
                 // this step's share of the next chunk's staging
                 const int st = cgi * XROWS + xr;
                 const int lo = min(NITEMS, st * NITEMS * (LONE ? 2 : 1) / NSTEP);
@@ -348,6 +347,15 @@ wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
 #pragma unroll
                 for (int i = 0; i < NITEMS; ++i)
                     if (i + LAG >= lo && i + LAG < hi) item_store(i, buf ^ 1);
+                // The staging instructions go between the MFMAs (a few per MFMA) rather than after them:
+                // the wave has something to issue while its own MFMAs queue for the matrix pipe (measured 2-5 %).
+#pragma unroll
+                for (int q = 0; q < RG * S * WTM; ++q) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x006, 4, 0);   // four vector or scalar ALU instructions
+                    __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // one global load
+                    __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // one LDS store
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
