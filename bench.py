@@ -41,8 +41,8 @@ PEAK = {"bf16_mfma_tflops": 2500.0, "f32_mfma_tflops": 157.3, "hbm_gbs": 8000.0}
 # Only for the workload and budget the counters were collected on; anything else reports null.
 MEASURED_TRAFFIC = {("cfg3_vgg16_n32", 2 << 30, "conv_bwd_filter"): 258e6,
                     # forward and backward-data run the same kernels: one figure for the 25 launches of both
-                    ("cfg3_vgg16_n32", 2 << 30, "conv_fwd"): 146e6,
-                    ("cfg3_vgg16_n32", 2 << 30, "conv_bwd_data"): 146e6}
+                    ("cfg3_vgg16_n32", 2 << 30, "conv_fwd"): 149e6,
+                    ("cfg3_vgg16_n32", 2 << 30, "conv_bwd_data"): 149e6}
 KERNELS = {"conv_fwd": "conv_tile2_kernel / conv_tile_kernel (+ pack_filter_kernel)",
            "conv_bwd_data": "conv_tile2_kernel / conv_tile_kernel (+ pack_filter_kernel)",
            "conv_bwd_filter": "wgrad_rows_kernel + reduce_partials4_kernel (STAGED) or fill_zero_kernel (DIRECT)"}
