@@ -414,7 +414,7 @@ conv_wgrad_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
             // rr = ((wk*TM + tm)*2 + g)*4 + i  ->  k = k0 + (wk*TM + tm)*32 + 8*ps + 4*g + i
             const int k = k0 + (rr >> 3) * 32 + 8 * ps + (rr & 7);
             const int c = c0 + cl;
-            if (k < p.K && c < p.C) {
+            if (k < p.K && c < p.C && r0 * S + t < Tall) {
                 const size_t off = ((size_t)k * p.C + c) * Tall + r0 * S + t;
                 const float val = stage[rr * EP + j];
                 if (use_atomics) unsafeAtomicAdd(dst + off, val);
@@ -449,7 +449,8 @@ bool make_wplan(const ConvGeom &g, WPlan *pl)
     if (g.S == 1 && g.R == 1) { RG = 1; TM = 2; TC = 2; }
     else if (g.S == 3 && g.R == 3) RG = 3;
     else if (g.S == 1 && g.R == 7) RG = 7;
-    else if ((g.S == 5 && g.R == 5) || (g.S == 7 && g.R == 1)) RG = 1;
+    else if (g.S == 5 && g.R == 5) RG = 3;   // two groups of three filter rows; the sixth row is not written
+    else if (g.S == 7 && g.R == 1) RG = 1;
     else return false;
     const long long lim = 0x7fffffffLL;
     if ((long long)g.N * g.C * g.H * g.W + 64 > lim || (long long)g.N * g.K * g.P * g.Q + 64 > lim) return false;
@@ -479,7 +480,7 @@ bool make_wplan(const ConvGeom &g, WPlan *pl)
     const long long nch = (long long)g.N * p.rowchunks * p.ncoltiles;
     if (nch > lim) return false;
     p.nchunks = (int)nch;
-    const int nrg = g.R / RG;
+    const int nrg = (g.R + RG - 1) / RG;
     p.ctiles = (g.C + CTB - 1) / CTB;
     const int ktiles = (g.K + KTB - 1) / KTB;
     if (ktiles > 65535) return false;
@@ -559,7 +560,7 @@ hipError_t launch_tile_wgrad(const void *x, const void *dy, float *dw, const Con
     if (pl.S == 3) e = launch_cfg<3, 3, 1, 1>(xs, ds, out, atomics, pl, st);
     else if (pl.S == 1 && pl.RG == 1) e = launch_cfg<1, 1, 2, 2>(xs, ds, out, atomics, pl, st);
     else if (pl.S == 1) e = launch_cfg<1, 7, 1, 1>(xs, ds, out, atomics, pl, st);
-    else if (pl.S == 5) e = launch_cfg<5, 1, 1, 1>(xs, ds, out, atomics, pl, st);
+    else if (pl.S == 5) e = launch_cfg<5, 3, 1, 1>(xs, ds, out, atomics, pl, st);
     else e = launch_cfg<7, 1, 1, 1>(xs, ds, out, atomics, pl, st);
     if (e != hipSuccess) return e;
     if (partial) return launch_reduce_partials(partial, dw, nw, slices, false, st);
