@@ -119,6 +119,28 @@ def conv2d_bwd_filter_at(x, dy, w_shape, stride, pad, k, c, r, s):
     return float(_load().sn_oracle_conv2d_bwd_filter_at(_d(x), _d(dy), *map(ctypes.c_int, g + (k, c, r, s))))
 
 
+def _points(fn, a, b, g, coords):
+    coords = np.ascontiguousarray(coords, dtype=np.int32).reshape(-1, 4)
+    out = np.empty(coords.shape[0], dtype=np.float64)
+    fn(_d(a), _d(b), *map(ctypes.c_int, g), coords.ctypes.data_as(_I), ctypes.c_size_t(coords.shape[0]), _d(out))
+    return out
+
+
+def conv2d_fwd_points(x, w, stride, pad, coords):
+    """y at the listed (n, k, p, q); x, w float64 C-contiguous."""
+    return _points(_load().sn_oracle_conv2d_fwd_points, x, w, _geom(x.shape, w.shape, stride, pad), coords)
+
+
+def conv2d_bwd_data_points(dy, w, x_shape, stride, pad, coords):
+    """dx at the listed (n, c, h, v)."""
+    return _points(_load().sn_oracle_conv2d_bwd_data_points, dy, w, _geom(x_shape, w.shape, stride, pad), coords)
+
+
+def conv2d_bwd_filter_points(x, dy, w_shape, stride, pad, coords):
+    """dw at the listed (k, c, r, s)."""
+    return _points(_load().sn_oracle_conv2d_bwd_filter_points, x, dy, _geom(x.shape, w_shape, stride, pad), coords)
+
+
 def relu_fwd(x):
     x = _f64(x)
     y = np.empty_like(x)

@@ -153,6 +153,58 @@ double sn_oracle_conv2d_bwd_filter_at(const double *x, const double *dy,
     return acc;
 }
 
+/* Lists of output elements, for structured samples of tensors too large for the full loops:
+ * out[i] = the output element at coords[4*i .. 4*i+3], in the index order of the matching _at
+ * function.  Forward and backward-filter call the single-output definitions above.  For
+ * backward-data the filtered walk over every (k,p,q,r,s) costs K*P*Q*R*S per element, so the
+ * list version solves p*sh + r - ph = h for p (and likewise q) per tap instead of testing every
+ * p; it is pinned against the scatter form on strided and padded shapes by the CPU tests. */
+void sn_oracle_conv2d_fwd_points(const double *x, const double *w,
+                                 int N, int C, int H, int W, int K, int R, int S,
+                                 int sh, int sw, int ph, int pw,
+                                 const int32_t *coords, size_t npts, double *out)
+{
+#pragma omp parallel for schedule(dynamic, 64)
+    for (size_t i = 0; i < npts; ++i)
+        out[i] = sn_oracle_conv2d_fwd_at(x, w, N, C, H, W, K, R, S, sh, sw, ph, pw,
+                                         coords[4 * i], coords[4 * i + 1], coords[4 * i + 2], coords[4 * i + 3]);
+}
+
+void sn_oracle_conv2d_bwd_data_points(const double *dy, const double *w,
+                                      int N, int C, int H, int W, int K, int R, int S,
+                                      int sh, int sw, int ph, int pw,
+                                      const int32_t *coords, size_t npts, double *out)
+{
+    const int P = sn_oracle_out_dim(H, ph, R, sh), Q = sn_oracle_out_dim(W, pw, S, sw);
+#pragma omp parallel for schedule(dynamic, 64)
+    for (size_t i = 0; i < npts; ++i) {
+        const int n = coords[4 * i], c = coords[4 * i + 1], h = coords[4 * i + 2], v = coords[4 * i + 3];
+        double acc = 0.0;
+        for (int k = 0; k < K; ++k)
+            for (int r = 0; r < R; ++r) {
+                const int th = h + ph - r;           /* = p * sh for the p that reaches row h through tap row r */
+                if (th < 0 || th % sh != 0 || th / sh >= P) continue;
+                for (int s = 0; s < S; ++s) {
+                    const int tv = v + pw - s;
+                    if (tv < 0 || tv % sw != 0 || tv / sw >= Q) continue;
+                    acc += dy[IDX4(n, N, k, K, th / sh, P, tv / sw, Q)] * w[IDX4(k, K, c, C, r, R, s, S)];
+                }
+            }
+        out[i] = acc;
+    }
+}
+
+void sn_oracle_conv2d_bwd_filter_points(const double *x, const double *dy,
+                                        int N, int C, int H, int W, int K, int R, int S,
+                                        int sh, int sw, int ph, int pw,
+                                        const int32_t *coords, size_t npts, double *out)
+{
+#pragma omp parallel for schedule(dynamic, 1)
+    for (size_t i = 0; i < npts; ++i)
+        out[i] = sn_oracle_conv2d_bwd_filter_at(x, dy, N, C, H, W, K, R, S, sh, sw, ph, pw,
+                                                coords[4 * i], coords[4 * i + 1], coords[4 * i + 2], coords[4 * i + 3]);
+}
+
 /* ACT (ReLU): y = x if x > 0 else 0; the gradient passes where x > 0 (strictly). */
 void sn_oracle_relu_fwd(const double *x, double *y, size_t n)
 {

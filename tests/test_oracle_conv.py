@@ -194,6 +194,29 @@ def test_point_versions_match_full(shape):
         assert abs(oracle.conv2d_bwd_filter_at(x, dy, w.shape, stride, pad, k, c, rr, s) - dw[k, c, rr, s]) < 1e-11
 
 
+@pytest.mark.parametrize("shape", SHAPES)
+def test_point_list_versions_match_full(shape):
+    """Every output element through the list versions (backward-data solves for the output row and
+    column per tap instead of walking all of them) against the pinned full loops, on every shape of
+    the list: strides 1, 2 and 4, asymmetric and zero padding."""
+    N, C, H, W, K, R, S, stride, pad = shape
+    x, w = _rand(N, C, H, W), _rand(K, C, R, S)
+    y = oracle.conv2d_fwd(x, w, stride, pad)
+    dy = _rand(*y.shape)
+    dx = oracle.conv2d_bwd_data(dy, w, x.shape, stride, pad)
+    dw = oracle.conv2d_bwd_filter(x, dy, w.shape, stride, pad)
+
+    def every(shape4):
+        return np.stack(np.meshgrid(*[np.arange(d) for d in shape4], indexing="ij"), -1).reshape(-1, 4)
+
+    np.testing.assert_allclose(oracle.conv2d_fwd_points(x, w, stride, pad, every(y.shape)), y.ravel(),
+                               rtol=0, atol=1e-12)
+    np.testing.assert_allclose(oracle.conv2d_bwd_data_points(dy, w, x.shape, stride, pad, every(x.shape)),
+                               dx.ravel(), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(oracle.conv2d_bwd_filter_points(x, dy, w.shape, stride, pad, every(w.shape)),
+                               dw.ravel(), rtol=0, atol=1e-11)
+
+
 def test_paper_alexnet_tensor_sizes():
     path = os.path.join(os.path.dirname(__file__), "golden", "alexnet_conv_output_mib.txt")
     want = {}
