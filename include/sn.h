@@ -16,7 +16,8 @@
  *    aligned (workspace: 256-byte aligned).  Shape structs and the size_t /
  *    enum outputs of the query and planner calls are HOST memory.
  *  - The library never allocates, frees or keeps device memory and holds no
- *    pointer after a call returns.
+ *    pointer after a call returns.  (Its one buffer is the fixed-size array of
+ *    sn_conv2d_fwd_noalloc, part of the loaded code object.)
  *  - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
  *    default stream).  No call synchronises the device.  Outputs are valid once
  *    the stream reaches that point; workspace contents are undefined afterwards.
@@ -128,6 +129,23 @@ sn_status sn_conv_autotune(sn_conv_dir dir, const void *a, const void *b, void *
  * workspace may be NULL iff workspace_bytes == 0. */
 sn_status sn_conv2d_fwd(const void *x, const void *w, void *y, const sn_conv_shape *shape,
                         sn_conv_algo algo, void *workspace, size_t workspace_bytes, sn_stream stream);
+
+/* sn_conv2d_fwd for callers that cannot allocate or pass device memory beyond the tensors
+ * themselves: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * It is sn_conv2d_fwd with algo = SN_ALGO_STAGED (same kernels, bit-identical y) whose workspace,
+ * the re-laid-out filter, is a fixed array of SN_NOALLOC_SCRATCH_BYTES that the library's code
+ * object holds on every GPU it is loaded on until the process ends.  No hipMalloc / hipFree or
+ * other allocating call is made.  The first call on a device looks up the array's address there
+ * (make that call outside a graph capture).
+ *  - SN_ERR_UNSUPPORTED if STAGED has no kernel for the shape (see sn_conv_workspace_query);
+ *    SN_ERR_WORKSPACE_TOO_SMALL if its min_bytes exceed SN_NOALLOC_SCRATCH_BYTES (filters of
+ *    more than about 4 M elements); nothing is launched then.
+ *  - Every call on a GPU uses that GPU's one array: calls that overlap on a GPU (different
+ *    streams, or host threads without ordering) race on it; calls on one stream are safe.  The
+ *    array keeps the last call's packed filter; each call rewrites all of what it reads. */
+#define SN_NOALLOC_SCRATCH_BYTES (8u << 20)
+sn_status sn_conv2d_fwd_noalloc(const void *x, const void *w, void *y, const sn_conv_shape *shape,
+                                sn_stream stream);
 
 /* CONV forward that also takes, for the BN layer that follows it, the batch statistics of its own
  * output (Sec. 3.4: CONV -> BN -> ReLU is the chain the runtime schedules as a unit): y exactly

@@ -28,6 +28,7 @@ SIGNATURES = {
     "sn_planner_clear": (None, []),
     "sn_conv_autotune": (_i, [_i, _vp, _vp, _vp, _shape_p, _vp, _sz, _i, _vp]),
     "sn_conv2d_fwd": (_i, _conv_args),
+    "sn_conv2d_fwd_noalloc": (_i, [_vp, _vp, _vp, _shape_p, _vp]),
     "sn_conv_bn_stats_scratch_bytes": (_sz, [_shape_p]),
     "sn_conv2d_fwd_bn_stats": (_i, _conv_args[:-1] + [_vp, _vp, ctypes.c_float, _vp, _sz, _vp]),
     "sn_conv2d_bwd_data": (_i, _conv_args),

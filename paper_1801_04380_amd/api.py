@@ -14,7 +14,8 @@ __all__ = [
     "SN_ALGO_AUTO", "SN_ALGO_DIRECT", "SN_ALGO_IM2COL_GEMM", "SN_ALGO_STAGED", "ALGO_NAMES",
     "SnError", "conv_shape", "sn_out_dim", "sn_conv_workspace_query", "sn_conv_plan",
     "sn_planner_record", "sn_planner_clear", "sn_conv_autotune",
-    "sn_conv2d_fwd", "sn_conv2d_bwd_data", "sn_conv2d_bwd_filter",
+    "sn_conv2d_fwd", "sn_conv2d_bwd_data", "sn_conv2d_bwd_filter", "sn_conv2d_fwd_noalloc",
+    "SN_NOALLOC_SCRATCH_BYTES",
     "sn_conv_bn_stats_scratch_bytes", "sn_conv2d_fwd_bn_stats", "sn_bn_apply", "sn_bn_relu_pool2_apply",
     "sn_relu_fwd", "sn_relu_bwd", "sn_bn_fwd", "sn_bn_relu_fwd", "sn_bn_bwd", "sn_bn_relu_bwd", "sn_bn_relu_pool2_fwd", "sn_bn_relu_pool2_bwd", "sn_lrn_fwd", "sn_lrn_bwd", "sn_maxpool_fwd", "sn_maxpool_bwd",
 ]
@@ -108,6 +109,14 @@ def sn_conv2d_fwd(x, w, y, shape, algo=SN_ALGO_AUTO, workspace=None):
     wp, wb = _ws(workspace)
     _check("sn_conv2d_fwd", load().sn_conv2d_fwd(_ptr(x), _ptr(w), _ptr(y), ctypes.byref(shape), algo, wp, wb,
                                                  _stream()))
+
+
+SN_NOALLOC_SCRATCH_BYTES = 8 << 20
+
+
+def sn_conv2d_fwd_noalloc(x, w, y, shape):
+    _check("sn_conv2d_fwd_noalloc", load().sn_conv2d_fwd_noalloc(_ptr(x), _ptr(w), _ptr(y), ctypes.byref(shape),
+                                                                 _stream()))
 
 
 def sn_conv_bn_stats_scratch_bytes(shape):

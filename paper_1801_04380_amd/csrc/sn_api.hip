@@ -1,6 +1,7 @@
 // Host side of the C ABI: argument checks, the workspace queries, the planner of
 // Sec. 3.5 (fastest algorithm whose workspace fits the budget) and the dispatch
-// of each call to the HIP kernels.  No device memory is allocated here.
+// of each call to the HIP kernels.  No device memory is allocated here; the one
+// buffer the library owns is the fixed-size `scratch` array of sn_conv2d_fwd_noalloc.
 #include <algorithm>
 #include <cstring>
 #include <mutex>
@@ -308,6 +309,34 @@ sn_status run_bwd_filter(const void *x, const void *dy, void *dw, const ConvGeom
 
 }  // namespace
 
+// ---- the library's own workspace, for sn_conv2d_fwd_noalloc -----------------------------------
+// One array per GPU, resident from the moment the library's code is loaded on that GPU until the
+// process ends.  In host code `scratch` is only a handle for hipGetSymbolAddress: the array's
+// device address differs per GPU and is looked up once per device.
+static __device__ __align__(256) unsigned char scratch[SN_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[MAX_DEVICES];   // device address of `scratch` on GPU i, nullptr until first use
+
+sn_status scratch_of_current_device(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return SN_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return SN_ERR_LAUNCH;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return SN_OK;
+}
+
+}  // namespace
+
 extern "C" {
 
 int sn_version(void) { return 1; }
@@ -397,6 +426,24 @@ sn_status sn_conv2d_fwd(const void *x, const void *w, void *y, const sn_conv_sha
                         void *workspace, size_t workspace_bytes, sn_stream stream)
 {
     return conv_call(SN_CONV_FWD, x, w, y, shape, algo, workspace, workspace_bytes, stream);
+}
+
+sn_status sn_conv2d_fwd_noalloc(const void *x, const void *w, void *y, const sn_conv_shape *shape, sn_stream stream)
+{
+    ConvGeom g;
+    sn_status s = make_geom(shape, &g);
+    if (s != SN_OK) return s;
+    if (!x || !w || !y || !aligned(x, 16) || !aligned(w, 16) || !aligned(y, 16)) return SN_ERR_BAD_ARG;
+    size_t mn = 0, pf = 0;
+    s = query(g, SN_CONV_FWD, SN_ALGO_STAGED, &mn, &pf);
+    if (s != SN_OK) return s;
+    if (mn > (size_t)SN_NOALLOC_SCRATCH_BYTES) return SN_ERR_WORKSPACE_TOO_SMALL;
+    void *ws = nullptr;
+    s = scratch_of_current_device(&ws);
+    if (s != SN_OK) return s;
+    // the packing kernel rewrites every item of the packed filter, padding included: nothing of an
+    // earlier call's contents is read
+    return run_fwd(x, w, y, g, SN_ALGO_STAGED, ws, SN_NOALLOC_SCRATCH_BYTES, static_cast<hipStream_t>(stream));
 }
 
 // Scratch of sn_conv2d_fwd_bn_stats: the per-tile triples of whichever tile kernel runs, or the
