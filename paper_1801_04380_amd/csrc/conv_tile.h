@@ -46,8 +46,15 @@
 //
 // The filter slab comes either from a copy pre-packed into the caller's
 // workspace in exactly the LDS order, swizzle included (STAGED algorithm: a
-// stage is one contiguous run of 16-byte loads), or is gathered from the KCRS
-// tensor with 2-byte loads (DIRECT, no workspace).
+// stage is one contiguous run of 16-byte loads), or comes straight from the KCRS
+// tensor (DIRECT, no workspace).  There a thread owns one (row, 8-channel half) of
+// the slab and, where the filter has at most 9 taps and the reduction channels
+// come in whole chunks of 16, fetches its share of a whole chunk with 16-byte
+// loads -- forward: the 8 channels x T taps of its row are one contiguous run of
+// the KCRS tensor; backward-data (3x3): eight runs of T taps, one per channel,
+// contiguous across the lanes -- keeps it in registers and cuts each stage's
+// 16-byte LDS items out of them with byte permutes whose selectors are compile
+// time constants (WM = 1 / 2).  Other shapes gather element by element (WM = 0).
 #include <type_traits>
 #include <utility>
 
@@ -328,7 +335,15 @@ __device__ inline uint4 keep_first(uint4 v, int n)
     return v;
 }
 
-template <int R, int S, int KT, int NF, bool STAGED, bool WIDE>
+// The two 16-bit elements h0, h1 (halfword indices into wc) as one dword, h0 in the low half.
+template <int N> __device__ inline uint32_t pick2(const uint32_t (&wc)[N], int h0, int h1)
+{
+    const uint32_t sel = (uint32_t)((h0 & 1) * 2) | (uint32_t)((h0 & 1) * 2 + 1) << 8 |
+                         (uint32_t)(4 + (h1 & 1) * 2) << 16 | (uint32_t)(5 + (h1 & 1) * 2) << 24;
+    return __builtin_amdgcn_perm(wc[h1 >> 1], wc[h0 >> 1], sel);
+}
+
+template <int R, int S, int KT, int NF, bool STAGED, bool WIDE, int WM = 0>
 __global__ void __launch_bounds__(256, 2)
 conv_tile_kernel(const bf16_t *__restrict__ in, const bf16_t *__restrict__ w, void *__restrict__ out, TileProblem p)
 {
@@ -471,9 +486,9 @@ conv_tile_kernel(const bf16_t *__restrict__ in, const bf16_t *__restrict__ w, vo
     }
 
     // ---- per-thread constants of the DIRECT filter gather: thread item = (tap, row, half)
-    uint32_t wsrc[STAGED ? 1 : WITEMS];
-    int wdst[STAGED ? 1 : WITEMS];
-    if (!STAGED) {
+    uint32_t wsrc[(STAGED || WM) ? 1 : WITEMS];
+    int wdst[(STAGED || WM) ? 1 : WITEMS];
+    if (!STAGED && !WM) {
 #pragma unroll
         for (int it = 0; it < WITEMS; ++it) {
             const int e = min(it * 256 + tid, WSZ - 1);
@@ -520,7 +535,7 @@ conv_tile_kernel(const bf16_t *__restrict__ in, const bf16_t *__restrict__ w, vo
 
     uint32_t xraw[XT ? 1 : XR][8];
     u32x4 xg[XT ? XG : 1];
-    u16x8 wreg[STAGED ? 1 : WITEMS];
+    u16x8 wreg[(STAGED || WM) ? 1 : WITEMS];
 
     // Global loads of the patch of one chunk; nothing here looks at what a load returns.
     auto load_x = [&](int chunk) {
@@ -609,7 +624,8 @@ conv_tile_kernel(const bf16_t *__restrict__ in, const bf16_t *__restrict__ w, vo
 
     // Global loads of the filter slab of stage (chunk, sg).
     auto load_w = [&](int chunk, int sg) {
-        if (STAGED) {
+        if (WM) {
+        } else if (STAGED) {
             const uint4 *src = reinterpret_cast<const uint4 *>(w) +
                                ((size_t)(chunk * NSUB + sg) * TRES * p.Mpad + k0) * 2;
 #pragma unroll
@@ -643,7 +659,7 @@ conv_tile_kernel(const bf16_t *__restrict__ in, const bf16_t *__restrict__ w, vo
     };
     auto store_w = [&](uint4 *wb) {
 #pragma unroll
-        for (int it = 0; it < WITEMS; ++it) {
+        for (int it = 0; it < (WM ? 0 : WITEMS); ++it) {
             const int e = it * 256 + tid;
             if ((it + 1) * 256 <= WSZ || e < WSZ) {
                 uint4 v;
@@ -651,6 +667,53 @@ conv_tile_kernel(const bf16_t *__restrict__ in, const bf16_t *__restrict__ w, vo
                 wb[STAGED ? e : wdst[it]] = v;
             }
         }
+    };
+
+    // ---- DIRECT with the thread's share of a chunk's filter in registers (WM = 1 forward, 2 backward-data).
+    // Thread (row, half o) of the KT x 2 items of a slab; with KT = 64 the upper two waves have none.
+    constexpr int WCD = WM == 1 ? 4 * T : WM == 2 ? 40 : 1;   // dwords: 8 x T elements, or 8 runs of 10
+    constexpr int NPRE = (WM && NSUB > 2) ? (NSUB - 2) * TRES : 1;
+    uint32_t wc[WCD];
+    u32x4 wpre[NPRE];   // the slabs of stages 2 .. NSUB-1, cut out at the end of stage 0
+    const bool wc_on = KT * 2 >= 256 || tid < KT * 2;
+    const int wc_row = WM == 2 ? tid % KT : tid >> 1, wc_o = WM == 2 ? (tid / KT) & 1 : tid & 1;
+    const int wc_dst = wc_row * 2 + (wc_o ^ swz(wc_row));
+    auto load_wc = [&](int chunk) {
+        if (!WM || !wc_on) return;
+        const int m = min(k0 + wc_row, p.Kout - 1);
+        const bf16_t *src = w + (size_t)m * p.w_sm + (size_t)(chunk * 16 + wc_o * 8) * p.w_sr;
+        if (WM == 1) {   // w_sr = T: 8 channels x T taps in one run
+#pragma unroll
+            for (int j = 0; j < T; ++j) {
+                const u32x4 v = load8_any(src + 8 * j);
+                wc[4 * j] = v.x; wc[4 * j + 1] = v.y; wc[4 * j + 2] = v.z; wc[4 * j + 3] = v.w;
+            }
+        } else {         // w_sm = T = 9: one run of 9 taps per channel, 8 + 1 elements
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const bf16_t *run = src + (size_t)i * p.w_sr;
+                const u32x4 v = load8_any(run);
+                wc[5 * i] = v.x; wc[5 * i + 1] = v.y; wc[5 * i + 2] = v.z; wc[5 * i + 3] = v.w;
+                wc[5 * i + 4] = run[8];
+            }
+        }
+    };
+    // Item tl of the slab of stage sg: the thread's 8 channels at tap (tl / SG, sg * SG + tl % SG).
+    auto cut_wc = [&](int sg, int tl) -> u32x4 {
+        const int tap = (tl / SG) * S + sg * SG + tl % SG;
+        u32x4 v;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int h0 = WM == 1 ? (2 * j) * T + tap : (2 * j) * 10 + (T - 1 - tap);
+            const int h1 = WM == 1 ? (2 * j + 1) * T + tap : (2 * j + 1) * 10 + (T - 1 - tap);
+            v[j] = pick2(wc, h0, h1);
+        }
+        return v;
+    };
+    auto store_wc = [&](uint4 *wb, int sg) {   // cuts the slab of stage sg and writes it
+        if (!WM || !wc_on) return;
+#pragma unroll
+        for (int tl = 0; tl < TRES; ++tl) reinterpret_cast<u32x4 *>(wb)[tl * KT * 2 + wc_dst] = cut_wc(sg, tl);
     };
 
     // The MFMAs of one stage.
@@ -761,6 +824,72 @@ conv_tile_kernel(const bf16_t *__restrict__ in, const bf16_t *__restrict__ w, vo
                 }
             });
         }
+    } else if constexpr (WM != 0) {
+    // Filter share of a chunk in registers.  The slab of stage 1 is cut and written at the end of
+    // stage 0, those of the later stages are cut then too and wait in registers, so that the loads
+    // of the next chunk's share can go out at the start of stage 1 and have until the end of the
+    // chunk's last stage to arrive.  With one stage per chunk they go out at its start.
+    uint4 *const ws = smem + 2 * XS;
+    load_wc(0);
+    if (XT) {
+        x_issue(0);
+        x_park(0);
+        __syncthreads();   // the zero fill is complete, the patch is parked
+        x_transpose(xs);
+    } else {
+        load_x(0);
+        __syncthreads();   // the zero fill is complete
+        store_x(0, xs);
+    }
+    store_wc(ws, 0);
+    int wpar = 0;
+    for (int chunk = 0; chunk < p.nchunks; ++chunk) {
+        const int cnext = min(chunk + 1, p.nchunks - 1);
+        uint4 *const xcur = xs + (chunk & 1) * XS, *const xnext = xs + ((chunk + 1) & 1) * XS;
+        if (!WIDE) {
+#pragma unroll
+            for (int f = 0; f < (WIDE ? 1 : NF); ++f) asm volatile("" : "+v"(pixbase[f]));
+        }
+#pragma unroll
+        for (int sg = 0; sg < NSUB; ++sg) {
+            __syncthreads();
+            if (sg == (NSUB > 1 ? 1 : 0)) load_wc(cnext);
+            if (XT) {
+                if (sg == 0) x_issue(cnext);
+                if (sg == 2) x_transpose(xnext);
+            } else {
+                if (sg == 0) load_x(cnext);
+            }
+            __builtin_amdgcn_sched_barrier(0);   // the loads stay ahead of the MFMAs
+            compute(xcur, ws + wpar * WSZ, sg);
+            __builtin_amdgcn_sched_barrier(0);
+            wpar ^= 1;
+            if (NSUB == 1) {
+                store_wc(ws + wpar * WSZ, 0);
+            } else if (sg == 0) {
+                store_wc(ws + wpar * WSZ, 1);
+                if (wc_on) {
+#pragma unroll
+                    for (int s2 = 2; s2 < NSUB; ++s2)
+#pragma unroll
+                        for (int tl = 0; tl < TRES; ++tl) wpre[(s2 - 2) * TRES + tl] = cut_wc(s2, tl);
+                }
+            } else if (sg + 1 < NSUB) {
+                if (wc_on) {
+#pragma unroll
+                    for (int tl = 0; tl < TRES; ++tl)
+                        reinterpret_cast<u32x4 *>(ws + wpar * WSZ)[tl * KT * 2 + wc_dst] = wpre[(sg - 1) * TRES + tl];
+                }
+            } else {
+                store_wc(ws + wpar * WSZ, 0);
+            }
+            if (XT) {
+                if (sg == 1) x_park(cnext);
+            } else {
+                if (sg == NSUB - 1) store_x(cnext, xnext);
+            }
+        }
+    }
     } else {
     uint4 *const ws = smem + 2 * XS;
     load_w(0, 0);
@@ -892,24 +1021,44 @@ conv_tile_kernel(const bf16_t *__restrict__ in, const bf16_t *__restrict__ w, vo
 
 
 
-template <int R, int S, int KT, int NF, bool STAGED, bool WIDE>
+template <int R, int S, int KT, int NF, bool STAGED, bool WIDE, int WM = 0>
 hipError_t launch_one(const bf16_t *in, const bf16_t *w, void *out, const Plan &pl, hipStream_t st)
 {
-    auto kern = conv_tile_kernel<R, S, KT, NF, STAGED, WIDE>;
-    static bool attr_set = false;   // the limit of dynamic LDS is a property of the kernel, set once
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_LIMIT);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    auto kern = conv_tile_kernel<R, S, KT, NF, STAGED, WIDE, WM>;
+    // the limit of dynamic LDS is a property of the kernel, set once (thread-safe initialisation)
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS_LIMIT);
+    if (attr != hipSuccess) return attr;
     hipLaunchKernelGGL(kern, pl.grid, dim3(256), pl.lds, st, in, w, out, pl.p);
     return hipGetLastError();
+}
+
+// DIRECT with the filter share of a chunk in registers: 3x3 either direction, 1x1 forward; the
+// reduction channels must come in whole chunks.
+template <int R, int S, int NF, int WM>
+hipError_t launch_wm(const bf16_t *in, const bf16_t *w, void *out, const Plan &pl, hipStream_t st)
+{
+    const int sel = (pl.KT == 128 ? 2 : 0) | (pl.wide ? 1 : 0);
+    switch (sel) {
+    case 0: return launch_one<R, S, 64, NF, false, false, WM>(in, w, out, pl, st);
+    case 1: return launch_one<R, S, 64, NF, false, true, WM>(in, w, out, pl, st);
+    case 2: return launch_one<R, S, 128, NF, false, false, WM>(in, w, out, pl, st);
+    default: return launch_one<R, S, 128, NF, false, true, WM>(in, w, out, pl, st);
+    }
 }
 
 template <int R, int S, int NF>
 hipError_t launch_nf(const bf16_t *in, const bf16_t *w, void *out, const Plan &pl, bool staged, hipStream_t st)
 {
+    if (!staged && pl.p.Cin % 16 == 0) {
+        if constexpr (R == 3 && S == 3) {
+            if (pl.p.tflip) return launch_wm<R, S, NF, 2>(in, w, out, pl, st);
+            return launch_wm<R, S, NF, 1>(in, w, out, pl, st);
+        }
+        if constexpr (R == 1 && S == 1) {
+            if (!pl.p.tflip) return launch_wm<R, S, NF, 1>(in, w, out, pl, st);
+        }
+    }
     const int sel = (pl.KT == 128 ? 4 : 0) | (staged ? 2 : 0) | (pl.wide ? 1 : 0);
     switch (sel) {
     case 0: return launch_one<R, S, 64, NF, false, false>(in, w, out, pl, st);

@@ -22,6 +22,19 @@ def rel_l2(got, want):
     return num / den
 
 
+def elementwise_excess(got, want, tol, out_bf16=False):
+    """The bound on every single element that goes beside the relative L2 (a norm alone lets one wrong
+    element in 10^5 through): |got - want| <= 8 * tol * rms(want), plus half a bf16 unit of the element
+    where the result is stored as bf16.  Returns the worst excess over the bound (<= 0 passes)."""
+    got = np.asarray(got, dtype=np.float64).ravel()
+    want = np.asarray(want, dtype=np.float64).ravel()
+    if not np.isfinite(got).all():
+        return np.inf
+    rms = float(np.sqrt(np.mean(want * want))) if want.size else 0.0
+    bound = 8 * tol * rms + (2.0 ** -8 * np.abs(want) if out_bf16 else 0.0)
+    return float(np.max(np.abs(got - want) - bound)) if want.size else 0.0
+
+
 def f64(t):
     return t.detach().cpu().to(torch.float64).numpy()
 

@@ -12,7 +12,7 @@ import torch
 import oracle
 import paper_1801_04380_amd as sn
 from paper_1801_04380_amd import workloads as wl
-from _parity import CODE, DT, TOL, f64, rel_l2, run_conv, shape_of
+from _parity import CODE, DT, TOL, elementwise_excess, f64, rel_l2, run_conv, shape_of
 
 pytestmark = pytest.mark.gpu
 
@@ -141,6 +141,8 @@ def test_conv_matches_oracle(case, direction, dtype):
                            shape, algo, ws)
             err = rel_l2(f64(got), ref)
             assert err <= TOL[dtype], (layer.name, sn.ALGO_NAMES[algo], ws, err)
+            assert elementwise_excess(f64(got), ref, TOL[dtype], got.dtype == torch.bfloat16) <= 0, \
+                (layer.name, sn.ALGO_NAMES[algo], ws, "element")
             results.append(f64(got))
         # the budget changes speed, never the function: all variants agree with each other too
         for r in results[1:]:
@@ -155,6 +157,7 @@ def test_auto_uses_budget_and_matches():
         for budget in (0, 1 << 20, 64 << 20):
             got = run_conv(direction, a, b, want[direction].shape, torch.float32, shape, sn.SN_ALGO_AUTO, budget)
             assert rel_l2(f64(got), want[direction]) <= TOL["bf16"]
+            assert elementwise_excess(f64(got), want[direction], TOL["bf16"]) <= 0
 
 
 def test_named_algo_with_too_little_workspace_is_refused():
@@ -238,3 +241,5 @@ def test_conv_random_geometries(case):
             got = run_conv(direction, a, b, ref.shape, od, shape, algo, pf)
             err = rel_l2(f64(got), ref)
             assert err <= TOL["bf16"], (layer, N, direction, sn.ALGO_NAMES[algo], err)
+            assert elementwise_excess(f64(got), ref, TOL["bf16"], got.dtype == torch.bfloat16) <= 0, \
+                (layer, N, direction, sn.ALGO_NAMES[algo], "element")
