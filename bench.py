@@ -38,7 +38,10 @@ PEAK = {"bf16_mfma_tflops": 2500.0, "f32_mfma_tflops": 157.3, "hbm_gbs": 8000.0}
 
 # HBM bytes per launch of an op class, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this
 # command (profiles/bench_vgg16_n32_hbm_traffic.txt gives the runs, the calibration and the sums).
-# Only for the workload and budget the counters were collected on; anything else reports null.
+# Only for the workload and budget the counters were collected on, and only while the kernel sources
+# are the ones they were collected on (TRAFFIC_KERNEL_SET = kernel_set_id() at that time); anything
+# else reports null with a note.
+TRAFFIC_KERNEL_SET = "unset"
 MEASURED_TRAFFIC = {("cfg3_vgg16_n32", 2 << 30, "conv_bwd_filter"): 258e6,
                     # forward and backward-data run the same kernels: one figure for the 25 launches of both
                     ("cfg3_vgg16_n32", 2 << 30, "conv_fwd"): 149e6,
@@ -74,6 +77,28 @@ class Op:
         self.flops, self.nbytes, self.nominal = flops, nbytes, nominal
         self.ms = []
         self.ev = None
+
+
+def kernel_set_id():
+    """A short hash of the HIP sources: tells a stale counter figure from a current one."""
+    import hashlib
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_1801_04380_amd", "csrc")
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".hip", ".h", ".cpp")):
+            with open(os.path.join(d, name), "rb") as f:
+                h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()[:12]
+
+
+def measure_ceilings(buf):
+    """What the plainest kernels reach on this GPU (sn_measure_ceiling), beside the datasheet peaks."""
+    import paper_1801_04380_amd as sn
+    kinds = {"mfma_bf16_tflops": sn.SN_CEIL_MFMA_BF16, "mfma_f32_tflops": sn.SN_CEIL_MFMA_F32,
+             "hbm_copy_gbs": sn.SN_CEIL_COPY, "hbm_read_gbs": sn.SN_CEIL_READ, "hbm_write_gbs": sn.SN_CEIL_WRITE}
+    out = {k: sn.sn_measure_ceiling(v, buf, iters=5) for k, v in kinds.items()}
+    out["buffer_bytes"] = buf.numel()
+    return out
 
 
 def build_ops(cfg_no, budget, autotune, fuse):
@@ -509,6 +534,14 @@ def main():
         roof = {"bound": "hbm", "achieved": achieved, "peak": PEAK["hbm_gbs"], "unit": "GB/s",
                 "frac": achieved / PEAK["hbm_gbs"], "traffic": None}
     roof["traffic"] = MEASURED_TRAFFIC.get((cfg["name"], budget, dom))
+    if roof["traffic"] is not None and kernel_set_id() != TRAFFIC_KERNEL_SET:
+        roof["traffic"] = None
+        roof["traffic_note"] = "the kernel sources changed since the counters in profiles/ were taken"
+    # the device's own ceilings, on a buffer far beyond the memory-side cache
+    cbuf = full_ws if (full_ws is not None and full_ws.numel() >= (1 << 30)) else torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    ceilings = measure_ceilings(cbuf)
+    roof["peak_measured"] = (ceilings["mfma_bf16_tflops" if cfg["dtype"] == "bf16" else "mfma_f32_tflops"]
+                             if roof["bound"] == "mfma" else ceilings["hbm_copy_gbs"])
     roof.update({"kernel": dom, "hip_kernels": KERNELS.get(dom, dom), "launches_per_step": d["launches"] / args.steps,
                  "avg_launch_ms": avg_ms, "algorithmic_bytes_per_launch": d["nbytes"] / d["launches"]})
 
@@ -537,7 +570,7 @@ def main():
         "recompute_gbs": replay_gbs,
         "recompute_ms_per_step": sum(by_key[k]["ms"] for k in replay_keys) / BREAKDOWN_STEPS, "cheap_layers_gbs": cheap_bytes_step / (cheap_ms_step * 1e-3) / 1e9,
         "autotune_ms": tune_ms, "conv_per_budget": per_budget,
-        "roofline": roof, "breakdown": breakdown,
+        "roofline": roof, "ceilings": ceilings, "breakdown": breakdown,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.workload)

@@ -281,6 +281,19 @@ sn_status sn_lrn_fwd(const void *x, void *y, int N, int C, int H, int W,
 sn_status sn_lrn_bwd(const void *x, const void *dy, void *dx, int N, int C, int H, int W,
                      int size, float alpha, float beta, float k, sn_dtype dtype, sn_stream stream);
 
+/* Ceilings of the device for the roofline figures (the fractions the benchmark reports are quoted
+ * against the datasheet peaks; these are what this GPU reaches in the plainest possible kernel):
+ *  MFMA_BF16 / MFMA_F32  a register-resident loop of 32x32x16 bf16 / 32x32x2 fp32 MFMAs on every
+ *                        compute unit -> *value in TFLOP/s;
+ *  COPY / READ / WRITE   a streaming kernel, 16 bytes per lane, over buf (COPY: first half to
+ *                        second half, read + written bytes counted) -> *value in GB/s.  Give it a
+ *                        buffer well beyond the 256 MB memory-side cache.
+ * buf: device memory, 256-byte aligned, at least 2 MiB for the MFMA kinds; it is overwritten.
+ * The best of `iters` timed launches counts.  Synchronises the stream. */
+typedef enum { SN_CEIL_MFMA_BF16 = 0, SN_CEIL_MFMA_F32 = 1, SN_CEIL_COPY = 2, SN_CEIL_READ = 3, SN_CEIL_WRITE = 4 } sn_ceiling_kind;
+sn_status sn_measure_ceiling(sn_ceiling_kind kind, void *buf, size_t buf_bytes, int iters, sn_stream stream,
+                             double *value);
+
 /* POOL (max) forward, the paper's example of a cheap-to-recompute layer
  * (Sec. 3.4).  Window kh x kw, stride, padding (pad < window; padded positions
  * never win).  Of equal maxima the first in row-major window order wins.

@@ -18,6 +18,7 @@ __all__ = [
     "SN_NOALLOC_SCRATCH_BYTES",
     "sn_conv_bn_stats_scratch_bytes", "sn_conv2d_fwd_bn_stats", "sn_bn_apply", "sn_bn_relu_pool2_apply",
     "sn_relu_fwd", "sn_relu_bwd", "sn_bn_fwd", "sn_bn_relu_fwd", "sn_bn_bwd", "sn_bn_relu_bwd", "sn_bn_relu_pool2_fwd", "sn_bn_relu_pool2_bwd", "sn_lrn_fwd", "sn_lrn_bwd", "sn_maxpool_fwd", "sn_maxpool_bwd",
+    "sn_measure_ceiling", "SN_CEIL_MFMA_BF16", "SN_CEIL_MFMA_F32", "SN_CEIL_COPY", "SN_CEIL_READ", "SN_CEIL_WRITE",
 ]
 
 SN_F32, SN_BF16 = 0, 1
@@ -214,6 +215,17 @@ def sn_lrn_bwd(x, dy, dx, size=5, alpha=1e-4, beta=0.75, k=2.0):
     N, C, H, W = x.shape
     _check("sn_lrn_bwd", load().sn_lrn_bwd(_ptr(x), _ptr(dy), _ptr(dx), N, C, H, W, size, alpha, beta, k,
                                            _dtype_code(x), _stream()))
+
+
+SN_CEIL_MFMA_BF16, SN_CEIL_MFMA_F32, SN_CEIL_COPY, SN_CEIL_READ, SN_CEIL_WRITE = 0, 1, 2, 3, 4
+
+
+def sn_measure_ceiling(kind, buf, iters=5):
+    """-> TFLOP/s (MFMA kinds) or GB/s (streaming kinds) on the device buf lives on."""
+    val = ctypes.c_double()
+    _check("sn_measure_ceiling", load().sn_measure_ceiling(kind, _ptr(buf), buf.numel() * buf.element_size(), iters,
+                                                           _stream(), ctypes.byref(val)))
+    return val.value
 
 
 def sn_maxpool_fwd(x, y, idx, kernel, stride, pad=(0, 0)):

@@ -1,4 +1,4 @@
-"""Build the HIP library (gfx950 only) in-tree: csrc/*.hip -> libsn_hip.so.
+"""Build the HIP library (gfx950 only) in-tree: csrc/*.hip and the host-only csrc/*.cpp -> libsn_hip.so.
 
 hipcc cross-compiles without a GPU.  Objects go to _build/ (git-ignored); the
 shared library sits next to this file so it travels with the source tree.
@@ -24,7 +24,7 @@ FLAGS = [
 
 
 def sources():
-    return sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hip"))
+    return sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hip", ".cpp")))
 
 
 def _stale(target, deps):
@@ -37,7 +37,7 @@ def _stale(target, deps):
 def _compile(src, force):
     obj = os.path.join(OBJ, os.path.basename(src) + ".o")
     headers = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
-    headers.append(os.path.join(ROOT, "include", "sn.h"))
+    headers += [os.path.join(ROOT, "include", h) for h in ("sn.h", "sn_runtime.h")]
     if force or _stale(obj, [src] + headers):
         cmd = ["hipcc"] + FLAGS + ["-c", src, "-o", obj]
         r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
