@@ -351,10 +351,13 @@ __device__ __forceinline__ void conv_tile2_body(const bf16_t *__restrict__ in, c
         if (!tail && sg == NSUB - 1) x_transpose(pnext, xnext);
         compute(xcur, areg[par], sgc);
         if (!tail && sg == NSUB - 1) {
-            // End of a chunk: the next patch buffer has been written, and the parked patch after
-            // it, whose loads were issued a chunk ago, has to have landed; the loads issued since
-            // (KEEP of them, at least) stay in flight, which a fence would not allow.
-            constexpr int KEEP = (2 * NSUB - 1) * TRES * 2 + (DW == 16 ? 4 : 8);
+            // End of a chunk: the next patch buffer has been written, and the parked patch after it
+            // (chunk + 2, whose loads every wave issued in the first stage of this chunk) has to have
+            // landed for every wave before the barrier, because the next chunk's last stage transposes it
+            // and there is no other barrier in between.  The loads issued after it -- the filter
+            // operands of this chunk's later stages, KEEP of them -- stay in flight, which a fence would
+            // not allow.
+            constexpr int KEEP = (NSUB - 1) * TRES * 2;
             static_assert(KEEP < 64, "the counter has 6 bits");
             asm volatile("" ::: "memory");
             __builtin_amdgcn_s_waitcnt((KEEP & 15) | ((KEEP >> 4) << 14) | (7 << 4));   // vmcnt(KEEP) lgkmcnt(0)
@@ -496,13 +499,9 @@ template <int R, int S, int NF, bool WIDE, int DW, int KS = 1, int WPN = 2>
 hipError_t launch2_one(const bf16_t *in, const bf16_t *w, void *out, const Plan &pl, hipStream_t st)
 {
     auto kern = conv_tile2_kernel<R, S, NF, WIDE, DW, KS, WPN>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_LIMIT);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS_LIMIT);
+    if (attr != hipSuccess) return attr;
     hipLaunchKernelGGL(kern, pl.grid, dim3(256 * KS), pl.lds, st, in, w, out, pl.p);
     return hipGetLastError();
 }
