@@ -25,7 +25,9 @@
  *  - Layouts: activations NCHW, filters KCRS, both dense row-major.
  *    P = floor((H + 2*pad_h - R)/stride_h) + 1, Q likewise.  groups = 1,
  *    dilation = 1, no bias.  The filter is applied as cross-correlation.
- *  - Errors are return codes; on any error nothing has been launched.
+ *  - Errors are return codes.  With SN_ERR_BAD_ARG, SN_ERR_UNSUPPORTED and
+ *    SN_ERR_WORKSPACE_TOO_SMALL nothing has been launched; SN_ERR_LAUNCH may come after part
+ *    of a call's kernels has been enqueued (outputs and workspace are then undefined).
  *  - bf16 values are the upper 16 bits of an IEEE fp32, stored as uint16;
  *    fp32 results are rounded to bf16 to nearest, ties to even.
  */
@@ -61,7 +63,12 @@ typedef enum { SN_CONV_FWD = 0, SN_CONV_BWD_DATA = 1, SN_CONV_BWD_FILTER = 2 } s
  *               workspace: the filter packed tap-major for forward and
  *               backward-data; per-slice partial sums of dw (reduced in a fixed
  *               order, so the result is run-to-run identical) for
- *               backward-filter.
+ *               backward-filter.  On strided shapes (bf16; 1x1 filters without
+ *               padding, and filters whose taps reach at most one row / column
+ *               of the stride grid beyond the output's, e.g. 3x3 stride 2 pad 1)
+ *               also the phase planes of the input: x[i*stride + a] for each
+ *               residue a becomes a channel group, over which the convolution
+ *               has stride 1 and runs on the stride-1 kernels.
  *  AUTO         let the planner pick the fastest algorithm that fits. */
 typedef enum {
     SN_ALGO_AUTO = -1,
@@ -103,8 +110,9 @@ sn_status sn_conv_workspace_query(const sn_conv_shape *shape, sn_conv_dir dir, s
  * sn_planner_record / sn_conv_autotune (the paper benchmarks the feasible
  * algorithms at run time); a recorded time applies to budgets >= the workspace
  * it was measured with.  With no feasible record the choice falls back to a
- * built-in ranking.  Ties go to the smaller workspace.  DIRECT needs 0 bytes,
- * so a plan always exists.  bytes_used = the workspace the choice will use
+ * built-in ranking (STAGED, then DIRECT; for strided backward-data the explicit
+ * algorithm before DIRECT).  Among records within 3 % of the fastest the one with the
+ * smallest workspace wins (then the faster).  DIRECT needs 0 bytes, so a plan always exists.  bytes_used = the workspace the choice will use
  * (<= budget_bytes).  predicted_ms may be NULL; it receives the recorded time
  * or a negative value if the choice came from the built-in ranking. */
 sn_status sn_conv_plan(const sn_conv_shape *shape, sn_conv_dir dir, size_t budget_bytes,
@@ -117,7 +125,8 @@ void sn_planner_clear(void);
 
 /* Benchmark every algorithm that fits workspace_bytes on the caller's own
  * buffers (same arguments as the matching sn_conv2d_* call: a, b are its two
- * inputs, out its output) and record the times.  Synchronises the stream. */
+ * inputs, out its output) and record the times: per algorithm one untimed launch, then
+ * `iters` launches timed one by one, of which the median counts.  Synchronises the stream. */
 sn_status sn_conv_autotune(sn_conv_dir dir, const void *a, const void *b, void *out,
                            const sn_conv_shape *shape, void *workspace, size_t workspace_bytes,
                            int iters, sn_stream stream);

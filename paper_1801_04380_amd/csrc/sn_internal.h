@@ -85,6 +85,23 @@ hipError_t launch_im2col(const void *x, void *col, const ConvGeom &g, int n0, in
 // col2im: dx[n][c][h][v] = sum over taps of dcol[i][(c,r,s)][p][q]; dcol is fp32.
 hipError_t launch_col2im(const float *dcol, void *dx, const ConvGeom &g, int n0, int nimg, hipStream_t st);
 
+// Phase decomposition of a strided convolution (conv_phase.hip): which residues of the rows and
+// columns occur as phases, and the geometry of the phase planes.  row_phase[i] = residue of the
+// i-th row phase (na of them), row_index[a] = its number or -1; columns likewise (nb);
+// nphases = na * nb, phase number = row number * nb + column number.  The inner filter is
+// Ri x Si (1x1, or 3x3 with tap (d, e) at [d + center][e + center]); planes are Hs x Ws.
+struct PhaseMap {
+    int sh, sw, ph, pw;
+    int na, nb, nphases;
+    int row_phase[8], col_phase[8], row_index[8], col_index[8];
+    int Ri, Si, center;
+    int Hs, Ws;
+};
+hipError_t launch_phase_split(const void *x, void *xs, const PhaseMap &m, const ConvGeom &g, hipStream_t st);
+hipError_t launch_phase_filter(const void *w, void *wp, const PhaseMap &m, const ConvGeom &g, hipStream_t st);
+hipError_t launch_phase_merge(const void *dxs, void *dx, const PhaseMap &m, const ConvGeom &g, hipStream_t st);
+hipError_t launch_phase_dw(const float *dwp, float *dw, const PhaseMap &m, const ConvGeom &g, hipStream_t st);
+
 // Cheap layers.
 hipError_t launch_relu_fwd(const void *x, void *y, size_t n, int bf16, hipStream_t st);
 hipError_t launch_relu_bwd(const void *x, const void *dy, void *dx, size_t n, int bf16, hipStream_t st);

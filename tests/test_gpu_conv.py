@@ -85,6 +85,19 @@ CASES = [
     (L("1x1_k1024", 1040, 7, 7, 1024, 1, 1), 2),
     (L("1x1_k2048", 528, 7, 7, 2048, 1, 1), 2),
     (L("3x3_k512", 272, 6, 8, 512, 3, 3, (1, 1), (1, 1)), 2),
+    # strided shapes the STAGED algorithm runs as a stride-1 convolution over the phase planes of the input:
+    # 3x3 / stride 2 / pad 1 on even and odd images, 1x1 with strides 2 and 3 (odd image: the last row and column
+    # are read by no window), 5x5 / stride 2 / pad 2 (every tap of the 3x3 inner filter real), strides that differ
+    # per axis, many channels (several tiles and chunks), a 1x3 filter striding along its own axis
+    (L("s2_3x3_even", 48, 28, 28, 160, 3, 3, (2, 2), (1, 1)), 3),
+    (L("s2_3x3_odd", 24, 15, 17, 72, 3, 3, (2, 2), (1, 1)), 2),
+    (L("s2_3x3_c130", 130, 14, 14, 136, 3, 3, (2, 2), (1, 1)), 2),
+    (L("s2_1x1_odd", 40, 7, 7, 96, 1, 1, (2, 2)), 5),
+    (L("s3_1x1", 32, 20, 20, 48, 1, 1, (3, 3)), 2),
+    (L("s2_5x5", 16, 16, 16, 40, 5, 5, (2, 2), (2, 2)), 2),
+    (L("s21_3x3", 32, 16, 12, 64, 3, 3, (2, 1), (1, 1)), 2),
+    (L("s12_1x3", 32, 9, 20, 48, 1, 3, (1, 2), (0, 1)), 2),
+    (L("s2_1x1_big", 256, 56, 56, 128, 1, 1, (2, 2)), 2),
 ]
 IDS = [c[0].name for c in CASES]
 

@@ -57,11 +57,15 @@ def test_fastest_feasible_matches_brute_force():
                 feasible = [r for r in rows if r[2] <= budget]
                 algo, used, ms = sn.sn_conv_plan(shape, d, budget)
                 if feasible:
-                    best = min(feasible, key=lambda r: (r[3], r[2]))
+                    # the fastest; among the records within 3 % of it the smallest workspace, then the faster
+                    fastest = min(r[3] for r in feasible)
+                    near = [r for r in feasible if r[3] <= fastest * 1.03 + 1e-9]
+                    best = min(near, key=lambda r: (r[2], r[3]))
                     assert abs(ms - best[3]) < 1e-6 and used == best[2] and algo == best[1], (trial, d, budget)
+                    assert ms <= fastest * 1.03 + 1e-6
                     if last is not None:
-                        assert ms <= last + 1e-6      # a bigger budget never predicts a slower step
-                    last = ms
+                        assert fastest <= last + 1e-6   # a bigger budget never makes the fastest feasible step slower
+                    last = fastest
                 else:
                     assert ms is None and used <= budget
     sn.sn_planner_clear()

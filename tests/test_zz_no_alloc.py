@@ -56,8 +56,8 @@ def test_sizes_beyond_the_array_are_refused():
     w = torch.zeros((1024, 1024, 3, 3), dtype=torch.bfloat16, device="cuda")
     y = torch.full((1, 1024, 8, 8), 7.0, dtype=torch.bfloat16, device="cuda")
     assert _raw_call(x, w, y, shape) == 3
-    # a strided shape has no STAGED kernel
-    shape2 = sn.conv_shape(1, 16, 8, 8, 16, 3, 3, (2, 2), (1, 1), sn.SN_BF16, sn.SN_BF16)
+    # fp32 inputs have no STAGED kernel
+    shape2 = sn.conv_shape(1, 16, 8, 8, 16, 3, 3, (1, 1), (1, 1), sn.SN_F32, sn.SN_F32)
     assert _raw_call(x, w, y, shape2) == 2
     torch.cuda.synchronize()
     assert bool((y == 7.0).all())
