@@ -38,6 +38,59 @@ pack_filter_kernel(const bf16_t *__restrict__ w, uint4 *__restrict__ wp, int M, 
     wp[it] = make_uint4(d[0], d[1], d[2], d[3]);
 }
 
+// The same packing for whole chunks of 3x3 filters with 16-byte loads: one thread per (chunk, row m,
+// 8-channel half) fetches its 8 channels x 9 taps -- forward: one contiguous run of the KCRS tensor;
+// backward-data: eight runs of 9 taps -- and cuts the nine 16-byte items out of registers (the
+// cut the zero-workspace kernel makes per stage, see conv_tile.h).  RED must be a multiple of 16.
+template <bool TFLIP>
+__global__ void __launch_bounds__(256)
+pack_filter9_kernel(const bf16_t *__restrict__ w, uint4 *__restrict__ wp, int M, int w_sm, int w_sr, int Mpad, uint32_t nthreads)
+{
+    constexpr int T = 9, S = 3, TRES = 3, NSUB = 3;
+    uint32_t q = blockIdx.x * 256u + threadIdx.x;
+    if (q >= nthreads) return;
+    const int hs = (int)(q & 1);
+    q >>= 1;
+    const int m = (int)(q % (uint32_t)Mpad), chunk = (int)(q / (uint32_t)Mpad);
+    const int red0 = chunk * 16 + (hs ^ swz(m)) * 8;
+    constexpr int WCD = TFLIP ? 40 : 36;
+    uint32_t wc[WCD];
+    if (m < M) {
+        const bf16_t *src = w + (size_t)m * w_sm + (size_t)red0 * w_sr;
+        if (!TFLIP) {
+#pragma unroll
+            for (int j = 0; j < T; ++j) {
+                const u32x4 v = load8_any(src + 8 * j);
+                wc[4 * j] = v.x; wc[4 * j + 1] = v.y; wc[4 * j + 2] = v.z; wc[4 * j + 3] = v.w;
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const bf16_t *run = src + (size_t)i * w_sr;
+                const u32x4 v = load8_any(run);
+                wc[5 * i] = v.x; wc[5 * i + 1] = v.y; wc[5 * i + 2] = v.z; wc[5 * i + 3] = v.w;
+                wc[5 * i + 4] = run[8];
+            }
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < WCD; ++i) wc[i] = 0;
+    }
+#pragma unroll
+    for (int tap = 0; tap < T; ++tap) {
+        const int r = tap / S, s = tap - r * S;   // stage s, item r of the stage
+        uint32_t d[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int h0 = TFLIP ? (2 * j) * 10 + (T - 1 - tap) : (2 * j) * T + tap;
+            const int h1 = TFLIP ? (2 * j + 1) * 10 + (T - 1 - tap) : (2 * j + 1) * T + tap;
+            d[j] = pick2(wc, h0, h1);
+        }
+        const size_t it = ((((size_t)chunk * NSUB + s) * TRES + r) * Mpad + m) * 2 + hs;
+        wp[it] = make_uint4(d[0], d[1], d[2], d[3]);
+    }
+}
+
 // Tiling for one problem with NF 32-pixel tiles per wave; false if the patch would not fit in LDS.
 bool plan_for(const TileProblem &base, int R, int S, int NF, Plan *pl, bool prefer_narrow = false)
 {
@@ -297,6 +350,16 @@ hipError_t launch_tile_conv(const void *in, const void *w, void *out, const Conv
     const bf16_t *wsrc = static_cast<const bf16_t *>(w);
     if (packed) {
         const size_t items = (size_t)pl.p.nchunks * g.R * g.S * pl.p.Mpad * 2;
+        if (g.R == 3 && g.S == 3 && pl.p.Cin % 16 == 0) {
+            const uint32_t nthreads = (uint32_t)(items / 9);
+            const dim3 grid((nthreads + 255) / 256), block(256);
+            if (pl.p.tflip)
+                hipLaunchKernelGGL(pack_filter9_kernel<true>, grid, block, 0, st, wsrc, static_cast<uint4 *>(packed),
+                                   pl.p.Kout, pl.p.w_sm, pl.p.w_sr, pl.p.Mpad, nthreads);
+            else
+                hipLaunchKernelGGL(pack_filter9_kernel<false>, grid, block, 0, st, wsrc, static_cast<uint4 *>(packed),
+                                   pl.p.Kout, pl.p.w_sm, pl.p.w_sr, pl.p.Mpad, nthreads);
+        } else
         hipLaunchKernelGGL(pack_filter_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, st, wsrc,
                            static_cast<uint4 *>(packed), pl.p.Kout, pl.p.Cin, g.R, g.S, sg_of(g.R, g.S),
                            pl.p.w_sm, pl.p.w_sr, pl.p.tflip, pl.p.Mpad, items);

@@ -119,7 +119,10 @@ struct PhasePlan {
 
 int floor_div(int a, int b) { return (a >= 0 ? a : a - b + 1) / b; }
 
-bool phase_axis(int R, int stride, int pad, int in, int out, int *phases, int *index, int *count, int *dmin, int *dmax)
+// *extra: 1 if the planes need one row more than the output has (an offset +1 tap whose plane row
+// `out` lies inside the input: convolutions without padding), else 0.
+bool phase_axis(int R, int stride, int pad, int in, int out, int *phases, int *index, int *count, int *dmin, int *dmax,
+                int *extra)
 {
     if (stride > 8) return false;
     for (int a = 0; a < 8; ++a) index[a] = -1;
@@ -137,37 +140,40 @@ bool phase_axis(int R, int stride, int pad, int in, int out, int *phases, int *i
     for (int a = 0; a < stride; ++a)
         if (index[a] == 0) { index[a] = *count; phases[(*count)++] = a; }
     if (*dmin < -1 || *dmax > 1) return false;
-    // plane row `out` (offset +1 at the last output) is not stored: it must lie outside the input
+    *extra = 0;
     for (int a = 0; a < stride; ++a)
-        if (has_plus[a] && out * stride + a < in) return false;
+        if (has_plus[a] && out * stride + a < in) *extra = 1;
     return true;
 }
 
-bool phase_plan(const ConvGeom &g, PhasePlan *pp)
+bool phase_plan(const ConvGeom &g, sn_conv_dir dir, PhasePlan *pp)
 {
     if (!g.in_bf16 || (g.sh == 1 && g.sw == 1)) return false;
     if (g.R > 16 || g.S > 16) return false;
     PhaseMap &m = pp->m;
     m.sh = g.sh; m.sw = g.sw; m.ph = g.ph; m.pw = g.pw;
-    int dmin, dmax, emin, emax;
-    if (!phase_axis(g.R, g.sh, g.ph, g.H, g.P, m.row_phase, m.row_index, &m.na, &dmin, &dmax)) return false;
-    if (!phase_axis(g.S, g.sw, g.pw, g.W, g.Q, m.col_phase, m.col_index, &m.nb, &emin, &emax)) return false;
+    int dmin, dmax, emin, emax, xr, xc;
+    if (!phase_axis(g.R, g.sh, g.ph, g.H, g.P, m.row_phase, m.row_index, &m.na, &dmin, &dmax, &xr)) return false;
+    if (!phase_axis(g.S, g.sw, g.pw, g.W, g.Q, m.col_phase, m.col_index, &m.nb, &emin, &emax, &xc)) return false;
+    // planes larger than the output: the inner convolution is no longer a "same" one, which the
+    // backward-filter kernels are built for
+    if ((xr || xc) && dir == SN_CONV_BWD_FILTER) return false;
     m.nphases = m.na * m.nb;
     const bool one_tap = dmin == 0 && dmax == 0 && emin == 0 && emax == 0;
     m.Ri = m.Si = one_tap ? 1 : 3;
     m.center = one_tap ? 0 : 1;
-    m.Hs = g.P;
-    m.Ws = g.Q;
+    m.Hs = g.P + xr;
+    m.Ws = g.Q + xc;
     if ((long long)g.C * m.nphases > 0x7fffffffLL / 16) return false;
     ConvGeom &u = pp->inner;
     u = g;
     u.C = g.C * m.nphases;
-    u.H = g.P; u.W = g.Q;
+    u.H = m.Hs; u.W = m.Ws;
     u.R = m.Ri; u.S = m.Si;
     u.sh = u.sw = 1;
     u.ph = u.pw = m.center;
     pp->plain = m.nphases == 1 && g.R == 1 && g.S == 1;
-    if (!tile_conv_supported(u, false) || !tile_conv_supported(u, true) || !tile_wgrad_supported(u)) return false;
+    if (dir == SN_CONV_BWD_FILTER ? !tile_wgrad_supported(u) : !tile_conv_supported(u, dir == SN_CONV_BWD_DATA)) return false;
     pp->wprime_bytes = pp->plain ? 0 : align_up((size_t)g.K * u.C * u.R * u.S * 2, WS_ALIGN);
     pp->dwprime_bytes = pp->plain ? 0 : align_up((size_t)g.K * u.C * u.R * u.S * 4, WS_ALIGN);
     return true;
@@ -197,7 +203,7 @@ sn_status query(const ConvGeom &g, sn_conv_dir dir, sn_conv_algo algo, size_t *m
     }
     case SN_ALGO_STAGED: {
         PhasePlan pp;
-        if (phase_plan(g, &pp)) {
+        if (phase_plan(g, dir, &pp)) {
             *min_b = *pref_b = phase_bytes(pp, dir);
             return SN_OK;
         }
@@ -340,7 +346,7 @@ sn_status run_fwd(const void *x, const void *w, void *y, const ConvGeom &g, sn_c
 {
     if (algo == SN_ALGO_DIRECT) return launch_status(direct_fwd(x, w, y, g, st));
     PhasePlan pp;
-    if (algo == SN_ALGO_STAGED && phase_plan(g, &pp)) {
+    if (algo == SN_ALGO_STAGED && phase_plan(g, SN_CONV_FWD, &pp)) {
         // workspace: phase planes of x | transformed filter | packed filter of the inner convolution
         char *base = static_cast<char *>(ws);
         void *xs = base;
@@ -372,7 +378,7 @@ sn_status run_bwd_data(const void *dy, const void *w, void *dx, const ConvGeom &
 {
     if (algo == SN_ALGO_DIRECT) return launch_status(direct_bwd_data(dy, w, dx, g, st));
     PhasePlan pp;
-    if (algo == SN_ALGO_STAGED && phase_plan(g, &pp)) {
+    if (algo == SN_ALGO_STAGED && phase_plan(g, SN_CONV_BWD_DATA, &pp)) {
         // workspace: phase planes of dx | transformed filter | packed filter of the inner convolution
         char *base = static_cast<char *>(ws);
         void *dxs = base;
@@ -411,7 +417,7 @@ sn_status run_bwd_filter(const void *x, const void *dy, void *dw, const ConvGeom
         return launch_status(launch_generic_bwd_filter(x, dy, dwf, g, generic_bwd_filter_splits(g), nullptr, false, st));
     }
     PhasePlan pp;
-    if (algo == SN_ALGO_STAGED && phase_plan(g, &pp)) {
+    if (algo == SN_ALGO_STAGED && phase_plan(g, SN_CONV_BWD_FILTER, &pp)) {
         // workspace: phase planes of x | dw of the inner convolution | its partial sums
         char *base = static_cast<char *>(ws);
         void *xs = base;
