@@ -446,14 +446,20 @@ def main():
             else:
                 op.fn()
 
-    def collect():
+    def collect(robust=False):
         # an Op object appears once per occurrence in the step; shared objects (mult > 1) hold all their events
+        # robust: every launch of an op counts with the op's median time -- in the breakdown pass, where
+        # the host records two events per call and now and then falls behind the GPU, a pair of events
+        # then also spans the GPU's wait for the next call to arrive
         seen, table = set(), {}
         for op in ops:
             if id(op) in seen or not op.ev:
                 continue
             seen.add(id(op))
             times = [a.elapsed_time(bb) for a, bb in op.ev]
+            if robust:
+                med = sorted(times)[len(times) // 2]
+                times = [med] * len(times)
             k = table.setdefault(op.key, dict(ms=0.0, launches=0, flops=0.0, nbytes=0.0, nominal=0.0, layers={}))
             k["ms"] += sum(times)
             k["launches"] += len(times)
@@ -475,7 +481,7 @@ def main():
     for _ in range(BREAKDOWN_STEPS):
         step(None)
     torch.cuda.synchronize()
-    by_key = collect()
+    by_key = collect(robust=True)
     dom = max(by_key, key=lambda k: by_key[k]["ms"])
     # the timed region: exactly args.steps steps, events only around the launches of the dominant class
     torch.cuda.synchronize()
