@@ -73,7 +73,11 @@ class Pool:
             _lib().sn_pool_destroy(self._p)
             self._p = None
 
-    __del__ = close
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:      # interpreter shutdown: the library may be gone already
+            pass
 
     def alloc(self, nbytes):
         """-> (id, offset), or None if no empty node is large enough."""
@@ -107,7 +111,11 @@ class Net:
             _lib().sn_net_destroy(self._n)
             self._n = None
 
-    __del__ = close
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:      # interpreter shutdown: the library may be gone already
+            pass
 
     def add(self, kind, out_bytes, prev=()):
         arr = (ctypes.c_int * len(prev))(*prev)
