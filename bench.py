@@ -311,7 +311,7 @@ def layer_table(cfg_no, budget, path):
                                   2: (sn.sn_conv2d_bwd_filter, xd, dyd, dw)}.items():
             if d == 1 and layer.first:
                 continue
-            for algo in (sn.SN_ALGO_DIRECT, sn.SN_ALGO_STAGED, sn.SN_ALGO_IM2COL_GEMM):
+            for algo in (sn.SN_ALGO_DIRECT, sn.SN_ALGO_STAGED, sn.SN_ALGO_IM2COL_GEMM, sn.SN_ALGO_WINOGRAD):
                 try:
                     mn, pf = sn.sn_conv_workspace_query(shape, d, algo)
                 except sn.SnError:

@@ -69,13 +69,19 @@ typedef enum { SN_CONV_FWD = 0, SN_CONV_BWD_DATA = 1, SN_CONV_BWD_FILTER = 2 } s
  *               also the phase planes of the input: x[i*stride + a] for each
  *               residue a becomes a channel group, over which the convolution
  *               has stride 1 and runs on the stride-1 kernels.
+ *  WINOGRAD     F(2x2, 3x3) for the fp32 path (3x3 filters, stride 1, forward and
+ *               backward-data): the transformed filter, the transformed input
+ *               tiles and the 16 products per tile live in the workspace, for as
+ *               many images per pass as fit; 2.25 times fewer multiplications.
+ *               Sums in a different order than the direct form (fp32 rounding).
  *  AUTO         let the planner pick the fastest algorithm that fits. */
 typedef enum {
     SN_ALGO_AUTO = -1,
     SN_ALGO_DIRECT = 0,
     SN_ALGO_IM2COL_GEMM = 1,
     SN_ALGO_STAGED = 2,
-    SN_ALGO_COUNT = 3
+    SN_ALGO_WINOGRAD = 3,
+    SN_ALGO_COUNT = 4
 } sn_conv_algo;
 
 typedef struct {
@@ -110,8 +116,8 @@ sn_status sn_conv_workspace_query(const sn_conv_shape *shape, sn_conv_dir dir, s
  * sn_planner_record / sn_conv_autotune (the paper benchmarks the feasible
  * algorithms at run time); a recorded time applies to budgets >= the workspace
  * it was measured with.  With no feasible record the choice falls back to a
- * built-in ranking (STAGED, then DIRECT; for strided backward-data the explicit
- * algorithm before DIRECT).  Among records within 3 % of the fastest the one with the
+ * built-in ranking (WINOGRAD where it applies and at least 2048 tiles fit a pass, STAGED,
+ * then DIRECT; for strided backward-data the explicit algorithm before DIRECT).  Among records within 3 % of the fastest the one with the
  * smallest workspace wins (then the faster).  DIRECT needs 0 bytes, so a plan always exists.  bytes_used = the workspace the choice will use
  * (<= budget_bytes).  predicted_ms may be NULL; it receives the recorded time
  * or a negative value if the choice came from the built-in ranking. */

@@ -11,7 +11,7 @@ from ._lib import ConvShape, load
 
 __all__ = [
     "SN_F32", "SN_BF16", "SN_CONV_FWD", "SN_CONV_BWD_DATA", "SN_CONV_BWD_FILTER",
-    "SN_ALGO_AUTO", "SN_ALGO_DIRECT", "SN_ALGO_IM2COL_GEMM", "SN_ALGO_STAGED", "ALGO_NAMES",
+    "SN_ALGO_AUTO", "SN_ALGO_DIRECT", "SN_ALGO_IM2COL_GEMM", "SN_ALGO_STAGED", "SN_ALGO_WINOGRAD", "ALGO_NAMES",
     "SnError", "conv_shape", "sn_out_dim", "sn_conv_workspace_query", "sn_conv_plan",
     "sn_planner_record", "sn_planner_clear", "sn_conv_autotune",
     "sn_conv2d_fwd", "sn_conv2d_bwd_data", "sn_conv2d_bwd_filter", "sn_conv2d_fwd_noalloc",
@@ -23,9 +23,9 @@ __all__ = [
 
 SN_F32, SN_BF16 = 0, 1
 SN_CONV_FWD, SN_CONV_BWD_DATA, SN_CONV_BWD_FILTER = 0, 1, 2
-SN_ALGO_AUTO, SN_ALGO_DIRECT, SN_ALGO_IM2COL_GEMM, SN_ALGO_STAGED = -1, 0, 1, 2
+SN_ALGO_AUTO, SN_ALGO_DIRECT, SN_ALGO_IM2COL_GEMM, SN_ALGO_STAGED, SN_ALGO_WINOGRAD = -1, 0, 1, 2, 3
 ALGO_NAMES = {SN_ALGO_AUTO: "auto", SN_ALGO_DIRECT: "direct", SN_ALGO_IM2COL_GEMM: "im2col_gemm",
-              SN_ALGO_STAGED: "staged"}
+              SN_ALGO_STAGED: "staged", SN_ALGO_WINOGRAD: "winograd"}
 _STATUS = {1: "SN_ERR_BAD_ARG", 2: "SN_ERR_UNSUPPORTED", 3: "SN_ERR_WORKSPACE_TOO_SMALL", 4: "SN_ERR_LAUNCH"}
 
 

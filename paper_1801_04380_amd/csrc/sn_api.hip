@@ -201,6 +201,10 @@ sn_status query(const ConvGeom &g, sn_conv_dir dir, sn_conv_algo algo, size_t *m
         *pref_b = p.fixed + p.per_image * (size_t)g.N;
         return SN_OK;
     }
+    case SN_ALGO_WINOGRAD:
+        if (dir == SN_CONV_BWD_FILTER || !winograd_supported(g, dir == SN_CONV_BWD_DATA)) return SN_ERR_UNSUPPORTED;
+        winograd_bytes(g, dir == SN_CONV_BWD_DATA, min_b, pref_b);
+        return SN_OK;
     case SN_ALGO_STAGED: {
         PhasePlan pp;
         if (phase_plan(g, dir, &pp)) {
@@ -236,7 +240,7 @@ bool same_shape(const sn_conv_shape &a, const sn_conv_shape &b) { return std::me
 // tried first.  The workspace-staged implicit GEMM, then the direct one; the
 // explicit unfold pays a write and a read of a buffer R*S times the input, so it
 // is picked on measurement, or for strided backward-data (see plan).
-const sn_conv_algo kRanking[] = {SN_ALGO_STAGED, SN_ALGO_DIRECT, SN_ALGO_IM2COL_GEMM};
+const sn_conv_algo kRanking[] = {SN_ALGO_WINOGRAD, SN_ALGO_STAGED, SN_ALGO_DIRECT, SN_ALGO_IM2COL_GEMM};
 
 sn_status plan(const sn_conv_shape *shape, const ConvGeom &g, sn_conv_dir dir, size_t budget,
                sn_conv_algo *algo, size_t *bytes, float *ms_out)
@@ -285,6 +289,8 @@ sn_status plan(const sn_conv_shape *shape, const ConvGeom &g, sn_conv_dir dir, s
         }
         if (a == SN_ALGO_IM2COL_GEMM) continue;
         if (query(g, dir, a, &mn, &pf) != SN_OK || mn > budget) continue;
+        // Winograd pays four kernels per pass: a guess in its favour only where a pass has real work
+        if (a == SN_ALGO_WINOGRAD && pf > budget && winograd_pass_tiles(g, dir == SN_CONV_BWD_DATA, budget) < 2048) continue;
         *algo = a;
         *bytes = std::min(pf, budget);
         if (ms_out) *ms_out = -1.f;
@@ -345,6 +351,7 @@ sn_status run_fwd(const void *x, const void *w, void *y, const ConvGeom &g, sn_c
                   size_t ws_bytes, hipStream_t st)
 {
     if (algo == SN_ALGO_DIRECT) return launch_status(direct_fwd(x, w, y, g, st));
+    if (algo == SN_ALGO_WINOGRAD) return launch_status(launch_winograd(x, w, y, g, false, ws, ws_bytes, st));
     PhasePlan pp;
     if (algo == SN_ALGO_STAGED && phase_plan(g, SN_CONV_FWD, &pp)) {
         // workspace: phase planes of x | transformed filter | packed filter of the inner convolution
@@ -377,6 +384,7 @@ sn_status run_bwd_data(const void *dy, const void *w, void *dx, const ConvGeom &
                        size_t ws_bytes, hipStream_t st)
 {
     if (algo == SN_ALGO_DIRECT) return launch_status(direct_bwd_data(dy, w, dx, g, st));
+    if (algo == SN_ALGO_WINOGRAD) return launch_status(launch_winograd(dy, w, dx, g, true, ws, ws_bytes, st));
     PhasePlan pp;
     if (algo == SN_ALGO_STAGED && phase_plan(g, SN_CONV_BWD_DATA, &pp)) {
         // workspace: phase planes of dx | transformed filter | packed filter of the inner convolution

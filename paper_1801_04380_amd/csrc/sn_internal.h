@@ -102,6 +102,14 @@ hipError_t launch_phase_filter(const void *w, void *wp, const PhaseMap &m, const
 hipError_t launch_phase_merge(const void *dxs, void *dx, const PhaseMap &m, const ConvGeom &g, hipStream_t st);
 hipError_t launch_phase_dw(const float *dwp, float *dw, const PhaseMap &m, const ConvGeom &g, hipStream_t st);
 
+// Winograd F(2x2, 3x3), fp32, 3x3 stride-1 forward / backward-data (conv_winograd.hip).
+// winograd_pass_tiles: 2x2 output tiles one pass handles with ws_bytes of workspace (0: does not fit).
+bool winograd_supported(const ConvGeom &g, bool bwd_data);
+void winograd_bytes(const ConvGeom &g, bool bwd_data, size_t *min_b, size_t *pref_b);
+long long winograd_pass_tiles(const ConvGeom &g, bool bwd_data, size_t ws_bytes);
+hipError_t launch_winograd(const void *in, const void *w, void *out, const ConvGeom &g, bool bwd_data, void *ws,
+                           size_t ws_bytes, hipStream_t st);
+
 // Cheap layers.
 hipError_t launch_relu_fwd(const void *x, void *y, size_t n, int bf16, hipStream_t st);
 hipError_t launch_relu_bwd(const void *x, const void *dy, void *dx, size_t n, int bf16, hipStream_t st);

@@ -24,9 +24,17 @@ int main()
     size_t mn = 0, pf = 0;
     for (int dir = 0; dir < 3; ++dir)
         for (int algo = 0; algo < SN_ALGO_COUNT; ++algo) {
-            CHECK(sn_conv_workspace_query(&s, (sn_conv_dir)dir, (sn_conv_algo)algo, &mn, &pf) == SN_OK);
-            CHECK(mn <= pf);
+            const sn_status st = sn_conv_workspace_query(&s, (sn_conv_dir)dir, (sn_conv_algo)algo, &mn, &pf);
+            CHECK(st == (algo == SN_ALGO_WINOGRAD ? SN_ERR_UNSUPPORTED : SN_OK));   // Winograd is the fp32 path's
+            CHECK(st != SN_OK || mn <= pf);
         }
+    // the fp32 3x3 shape: Winograd for forward and backward-data, every pass size the workspace allows
+    sn_conv_shape f = shape_of(8, 64, 28, 28, 96, 3, 3, 1, 1, SN_F32);
+    for (int dir = 0; dir < 3; ++dir) {
+        const sn_status st = sn_conv_workspace_query(&f, (sn_conv_dir)dir, SN_ALGO_WINOGRAD, &mn, &pf);
+        CHECK(st == (dir == SN_CONV_BWD_FILTER ? SN_ERR_UNSUPPORTED : SN_OK));
+        CHECK(st != SN_OK || (mn > 0 && mn <= pf));
+    }
     CHECK(sn_conv_workspace_query(nullptr, SN_CONV_FWD, SN_ALGO_DIRECT, &mn, &pf) == SN_ERR_BAD_ARG);
     CHECK(sn_conv_workspace_query(&s, SN_CONV_FWD, SN_ALGO_AUTO, &mn, &pf) == SN_ERR_BAD_ARG);   // AUTO names no algorithm
     // strided shapes: the phase decomposition's bookkeeping, supported and refused forms

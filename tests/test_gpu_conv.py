@@ -122,7 +122,7 @@ def _inputs(i, dtype):
 def _algos(shape, direction):
     """(algo, workspace bytes) pairs to try: every algorithm at its least and its preferred workspace."""
     out = []
-    for algo in (sn.SN_ALGO_DIRECT, sn.SN_ALGO_IM2COL_GEMM, sn.SN_ALGO_STAGED):
+    for algo in (sn.SN_ALGO_DIRECT, sn.SN_ALGO_IM2COL_GEMM, sn.SN_ALGO_STAGED, sn.SN_ALGO_WINOGRAD):
         try:
             mn, pf = sn.sn_conv_workspace_query(shape, direction, algo)
         except sn.SnError:

@@ -152,7 +152,7 @@ def test_conv_full_size(cfg_no, li, layer):
             out_bf16 = out.dtype == torch.bfloat16
             sn.sn_conv_autotune(d, a, b, out, shape, ws, iters=1)
             runs = [(sn.SN_ALGO_AUTO, None)]
-            for algo in (sn.SN_ALGO_DIRECT, sn.SN_ALGO_IM2COL_GEMM, sn.SN_ALGO_STAGED):
+            for algo in (sn.SN_ALGO_DIRECT, sn.SN_ALGO_IM2COL_GEMM, sn.SN_ALGO_STAGED, sn.SN_ALGO_WINOGRAD):
                 try:
                     mn, pf = sn.sn_conv_workspace_query(shape, d, algo)
                 except sn.SnError:

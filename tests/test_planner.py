@@ -7,7 +7,7 @@ import random
 import paper_1801_04380_amd as sn
 
 DIRS = (sn.SN_CONV_FWD, sn.SN_CONV_BWD_DATA, sn.SN_CONV_BWD_FILTER)
-ALGOS = (sn.SN_ALGO_DIRECT, sn.SN_ALGO_IM2COL_GEMM, sn.SN_ALGO_STAGED)
+ALGOS = (sn.SN_ALGO_DIRECT, sn.SN_ALGO_IM2COL_GEMM, sn.SN_ALGO_STAGED, sn.SN_ALGO_WINOGRAD)
 
 
 def _needs(shape, d):
