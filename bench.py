@@ -94,7 +94,8 @@ def kernel_set_id():
 def measure_ceilings(buf):
     """What the plainest kernels reach on this GPU (sn_measure_ceiling), beside the datasheet peaks."""
     import paper_1801_04380_amd as sn
-    kinds = {"mfma_bf16_tflops": sn.SN_CEIL_MFMA_BF16, "mfma_f32_tflops": sn.SN_CEIL_MFMA_F32,
+    kinds = {"mfma_bf16_tflops": sn.SN_CEIL_MFMA_BF16, "mfma_bf16_fed_tflops": sn.SN_CEIL_MFMA_BF16_FED,
+             "mfma_f32_tflops": sn.SN_CEIL_MFMA_F32,
              "hbm_copy_gbs": sn.SN_CEIL_COPY, "hbm_read_gbs": sn.SN_CEIL_READ, "hbm_write_gbs": sn.SN_CEIL_WRITE}
     out = {k: sn.sn_measure_ceiling(v, buf, iters=5) for k, v in kinds.items()}
     out["buffer_bytes"] = buf.numel()

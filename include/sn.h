@@ -300,12 +300,20 @@ sn_status sn_lrn_bwd(const void *x, const void *dy, void *dx, int N, int C, int 
  * against the datasheet peaks; these are what this GPU reaches in the plainest possible kernel):
  *  MFMA_BF16 / MFMA_F32  a register-resident loop of 32x32x16 bf16 / 32x32x2 fp32 MFMAs on every
  *                        compute unit -> *value in TFLOP/s;
+ *  MFMA_BF16_FED         the bf16 loop with its operands arriving as the 3x3 tile kernels get them
+ *                        (a wave of 64 channels x 128 pixels; per 24 MFMAs six 1 KB filter items
+ *                        from a 2 MiB L2-resident buffer and six pixel operands from LDS; per 72
+ *                        MFMAs 32 bytes per thread from memory into LDS behind a barrier; two
+ *                        workgroups per compute unit), trivial addresses, nothing transposed or
+ *                        stored: what the operand streams alone leave of the peak -> TFLOP/s;
  *  COPY / READ / WRITE   a streaming kernel, 16 bytes per lane, over buf (COPY: first half to
  *                        second half, read + written bytes counted) -> *value in GB/s.  Give it a
  *                        buffer well beyond the 256 MB memory-side cache.
- * buf: device memory, 256-byte aligned, at least 2 MiB for the MFMA kinds; it is overwritten.
+ * buf: device memory, 256-byte aligned, at least 2 MiB for the MFMA kinds (4 MiB for MFMA_BF16_FED);
+ * it is overwritten.
  * The best of `iters` timed launches counts.  Synchronises the stream. */
-typedef enum { SN_CEIL_MFMA_BF16 = 0, SN_CEIL_MFMA_F32 = 1, SN_CEIL_COPY = 2, SN_CEIL_READ = 3, SN_CEIL_WRITE = 4 } sn_ceiling_kind;
+typedef enum { SN_CEIL_MFMA_BF16 = 0, SN_CEIL_MFMA_F32 = 1, SN_CEIL_COPY = 2, SN_CEIL_READ = 3, SN_CEIL_WRITE = 4,
+               SN_CEIL_MFMA_BF16_FED = 5 } sn_ceiling_kind;
 sn_status sn_measure_ceiling(sn_ceiling_kind kind, void *buf, size_t buf_bytes, int iters, sn_stream stream,
                              double *value);
 

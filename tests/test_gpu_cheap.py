@@ -49,7 +49,9 @@ def test_relu(n, dtype):
 BN_SHAPES = [(2, 3, 5, 7), (4, 16, 14, 14), (3, 8, 7, 7), (2, 5, 35, 35), (8, 64, 56, 56), (2, 4, 224, 224),
              (1, 1, 1, 1), (1, 3, 1, 1), (2, 2, 1, 1), (1, 2, 1, 3), (64, 32, 7, 7), (2, 130, 9, 9),
              # a channel that just fits the one-pass kernels' registers, one just past that, 8-byte vectors
-             (32, 6, 56, 56), (34, 3, 56, 56), (32, 8, 14, 14)]
+             (32, 6, 56, 56), (34, 3, 56, 56), (32, 8, 14, 14),
+             # long channels with many planes: whole slices and a ragged last one
+             (16, 64, 64, 64), (12, 130, 36, 40)]
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -158,7 +160,8 @@ def test_bn_relu_bwd_gate_edges(N, H, dtype):
 # one-pass statistics with 16- and 8-byte row accesses, the three-kernel path with both, a single
 # window per plane, rows of one access, a wide plane
 POOL2_PAIR_SHAPES = [(4, 16, 16, 16), (2, 5, 4, 12), (40, 4, 64, 64), (40, 3, 56, 60), (3, 7, 2, 4),
-                     (2, 3, 6, 8), (32, 6, 56, 56), (2, 2, 2, 304), (36, 2, 56, 56)]
+                     (2, 3, 6, 8), (32, 6, 56, 56), (2, 2, 2, 304), (36, 2, 56, 56),
+                     (16, 64, 64, 64), (12, 130, 36, 40)]
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -291,3 +294,20 @@ def test_maxpool(case, dtype):
         assert np.array_equal(f64(dx), dxo)                # no overlap: pure routing
     else:
         assert rel_l2(f64(dx), dxo) <= TOL[dtype]
+
+
+def test_measured_ceilings_are_sane():
+    """sn_measure_ceiling: every kind runs, stays below the datasheet peak it is quoted beside, and the
+    operand-fed MFMA loop does not beat the register-resident one; bad arguments are refused."""
+    buf = torch.empty(512 << 20, dtype=torch.uint8, device="cuda")
+    bf16 = sn.sn_measure_ceiling(sn.SN_CEIL_MFMA_BF16, buf, iters=2)
+    fed = sn.sn_measure_ceiling(sn.SN_CEIL_MFMA_BF16_FED, buf, iters=2)
+    f32 = sn.sn_measure_ceiling(sn.SN_CEIL_MFMA_F32, buf, iters=2)
+    assert 500.0 < bf16 <= 2600.0 and 10.0 < f32 <= 165.0
+    assert 300.0 < fed <= bf16 * 1.02
+    for kind in (sn.SN_CEIL_COPY, sn.SN_CEIL_READ, sn.SN_CEIL_WRITE):
+        assert 1000.0 < sn.sn_measure_ceiling(kind, buf, iters=2) <= 8000.0
+    with pytest.raises(sn.SnError):
+        sn.sn_measure_ceiling(6, buf)                                   # no such kind
+    with pytest.raises(sn.SnError):
+        sn.sn_measure_ceiling(sn.SN_CEIL_MFMA_BF16_FED, buf[: 2 << 20])    # needs the source and the sink
