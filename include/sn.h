@@ -68,7 +68,9 @@ typedef enum { SN_CONV_FWD = 0, SN_CONV_BWD_DATA = 1, SN_CONV_BWD_FILTER = 2 } s
  *               of the stride grid beyond the output's, e.g. 3x3 stride 2 pad 1)
  *               also the phase planes of the input: x[i*stride + a] for each
  *               residue a becomes a channel group, over which the convolution
- *               has stride 1 and runs on the stride-1 kernels.
+ *               has stride 1 and runs on the stride-1 kernels; forward and
+ *               backward-data take the planes of as many images per pass as the
+ *               workspace holds (min_bytes: one image).
  *  WINOGRAD     F(2x2, 3x3) for the fp32 path (3x3 filters, stride 1, forward and
  *               backward-data): the transformed filter, the transformed input
  *               tiles and the 16 products per tile live in the workspace, for as

@@ -114,6 +114,7 @@ struct PhasePlan {
     PhaseMap m;
     ConvGeom inner;
     bool plain;          // one phase and a 1x1 filter: w and dw need no transform
+    bool chunkable;      // every image of x, y, dy, dx starts on a 16-byte boundary: passes over parts of the batch
     size_t wprime_bytes, dwprime_bytes;   // 256-aligned parts of the workspace (0 if plain)
 };
 
@@ -173,19 +174,48 @@ bool phase_plan(const ConvGeom &g, sn_conv_dir dir, PhasePlan *pp)
     u.sh = u.sw = 1;
     u.ph = u.pw = m.center;
     pp->plain = m.nphases == 1 && g.R == 1 && g.S == 1;
+    pp->chunkable = ((long long)g.K * g.P * g.Q) % 8 == 0 && ((long long)g.C * g.H * g.W) % 8 == 0;
     if (dir == SN_CONV_BWD_FILTER ? !tile_wgrad_supported(u) : !tile_conv_supported(u, dir == SN_CONV_BWD_DATA)) return false;
     pp->wprime_bytes = pp->plain ? 0 : align_up((size_t)g.K * u.C * u.R * u.S * 2, WS_ALIGN);
     pp->dwprime_bytes = pp->plain ? 0 : align_up((size_t)g.K * u.C * u.R * u.S * 4, WS_ALIGN);
     return true;
 }
 
-size_t phase_bytes(const PhasePlan &pp, sn_conv_dir dir)
+// Workspace of the phase path.  Forward and backward-data: transformed filter | packed filter of the
+// inner convolution | the phase planes of as many images as a pass takes (`nimg`; the passes reuse
+// the same planes), so the path runs from one image's planes up.  Backward-filter: the planes of the
+// whole batch | dw of the inner convolution | its partial sums.
+size_t phase_fixed_bytes(const PhasePlan &pp, sn_conv_dir dir)
 {
-    const size_t planes = (size_t)pp.inner.N * pp.inner.C * pp.inner.H * pp.inner.W;
+    return pp.wprime_bytes + tile_conv_packed_bytes(pp.inner, dir == SN_CONV_BWD_DATA);
+}
+
+size_t phase_plane_bytes(const PhasePlan &pp, sn_conv_dir dir, int nimg)
+{
+    const size_t planes = (size_t)nimg * pp.inner.C * pp.inner.H * pp.inner.W;
+    return align_up(planes * (dir == SN_CONV_BWD_DATA && !pp.inner.out_bf16 ? 4 : 2), WS_ALIGN);
+}
+
+size_t phase_bytes(const PhasePlan &pp, sn_conv_dir dir, int nimg)
+{
     if (dir == SN_CONV_BWD_FILTER)
-        return align_up(planes * 2, WS_ALIGN) + pp.dwprime_bytes + staged_bwd_filter_bytes(pp.inner, nullptr);
-    const size_t pl = dir == SN_CONV_FWD ? align_up(planes * 2, WS_ALIGN) : align_up(planes * (pp.inner.out_bf16 ? 2 : 4), WS_ALIGN);
-    return pl + pp.wprime_bytes + tile_conv_packed_bytes(pp.inner, dir == SN_CONV_BWD_DATA);
+        return phase_plane_bytes(pp, dir, pp.inner.N) + pp.dwprime_bytes + staged_bwd_filter_bytes(pp.inner, nullptr);
+    return phase_fixed_bytes(pp, dir) + phase_plane_bytes(pp, dir, nimg);
+}
+
+// Images per pass of the phase path under this budget (forward, backward-data; at least 1: the
+// caller has checked the least workspace; the whole batch where the images do not start on
+// 16-byte boundaries, which the kernels' wide accesses assume of their tensors).
+int phase_chunk(const PhasePlan &pp, sn_conv_dir dir, size_t ws_bytes)
+{
+    if (!pp.chunkable) return pp.inner.N;
+    int lo = 1, hi = pp.inner.N;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) / 2;
+        if (phase_bytes(pp, dir, mid) <= ws_bytes) lo = mid;
+        else hi = mid - 1;
+    }
+    return lo;
 }
 
 sn_status query(const ConvGeom &g, sn_conv_dir dir, sn_conv_algo algo, size_t *min_b, size_t *pref_b)
@@ -208,7 +238,8 @@ sn_status query(const ConvGeom &g, sn_conv_dir dir, sn_conv_algo algo, size_t *m
     case SN_ALGO_STAGED: {
         PhasePlan pp;
         if (phase_plan(g, dir, &pp)) {
-            *min_b = *pref_b = phase_bytes(pp, dir);
+            *pref_b = phase_bytes(pp, dir, g.N);
+            *min_b = pp.chunkable ? phase_bytes(pp, dir, 1) : *pref_b;
             return SN_OK;
         }
         if (dir == SN_CONV_BWD_FILTER) {
@@ -291,6 +322,8 @@ sn_status plan(const sn_conv_shape *shape, const ConvGeom &g, sn_conv_dir dir, s
         if (query(g, dir, a, &mn, &pf) != SN_OK || mn > budget) continue;
         // Winograd pays four kernels per pass: a guess in its favour only where a pass has real work
         if (a == SN_ALGO_WINOGRAD && pf > budget && winograd_pass_tiles(g, dir == SN_CONV_BWD_DATA, budget) < 2048) continue;
+        // strided forward over phase planes gains little over the zero-workspace kernel: not in passes
+        if (a == SN_ALGO_STAGED && dir == SN_CONV_FWD && pf > budget && (g.sh > 1 || g.sw > 1)) continue;
         *algo = a;
         *bytes = std::min(pf, budget);
         if (ms_out) *ms_out = -1.f;
@@ -354,14 +387,19 @@ sn_status run_fwd(const void *x, const void *w, void *y, const ConvGeom &g, sn_c
     if (algo == SN_ALGO_WINOGRAD) return launch_status(launch_winograd(x, w, y, g, false, ws, ws_bytes, st));
     PhasePlan pp;
     if (algo == SN_ALGO_STAGED && phase_plan(g, SN_CONV_FWD, &pp)) {
-        // workspace: phase planes of x | transformed filter | packed filter of the inner convolution
         char *base = static_cast<char *>(ws);
-        void *xs = base;
-        char *wp = base + align_up((size_t)pp.inner.N * pp.inner.C * pp.inner.H * pp.inner.W * 2, WS_ALIGN);
-        void *packed = wp + pp.wprime_bytes;
-        if (launch_phase_split(x, xs, pp.m, g, st) != hipSuccess) return SN_ERR_LAUNCH;
+        void *wp = base, *packed = base + pp.wprime_bytes, *xs = base + phase_fixed_bytes(pp, SN_CONV_FWD);
         if (!pp.plain && launch_phase_filter(w, wp, pp.m, g, st) != hipSuccess) return SN_ERR_LAUNCH;
-        return launch_status(launch_tile_conv(xs, pp.plain ? w : wp, y, pp.inner, false, packed, st));
+        const int chunk = phase_chunk(pp, SN_CONV_FWD, ws_bytes);
+        for (int n0 = 0; n0 < g.N; n0 += chunk) {
+            ConvGeom go = g, gi = pp.inner;
+            go.N = gi.N = std::min(chunk, g.N - n0);
+            const char *xo = static_cast<const char *>(x) + (size_t)n0 * g.C * g.H * g.W * in_elem(g);
+            char *yo = static_cast<char *>(y) + (size_t)n0 * g.K * g.P * g.Q * out_elem(g);
+            if (launch_phase_split(xo, xs, pp.m, go, st) != hipSuccess) return SN_ERR_LAUNCH;
+            if (launch_tile_conv(xs, pp.plain ? w : wp, yo, gi, false, packed, st) != hipSuccess) return SN_ERR_LAUNCH;
+        }
+        return SN_OK;
     }
     if (algo == SN_ALGO_STAGED) return launch_status(launch_tile_conv(x, w, y, g, false, ws, st));
     if (algo == SN_ALGO_IM2COL_GEMM) {
@@ -387,14 +425,19 @@ sn_status run_bwd_data(const void *dy, const void *w, void *dx, const ConvGeom &
     if (algo == SN_ALGO_WINOGRAD) return launch_status(launch_winograd(dy, w, dx, g, true, ws, ws_bytes, st));
     PhasePlan pp;
     if (algo == SN_ALGO_STAGED && phase_plan(g, SN_CONV_BWD_DATA, &pp)) {
-        // workspace: phase planes of dx | transformed filter | packed filter of the inner convolution
         char *base = static_cast<char *>(ws);
-        void *dxs = base;
-        char *wp = base + align_up((size_t)pp.inner.N * pp.inner.C * pp.inner.H * pp.inner.W * (g.out_bf16 ? 2 : 4), WS_ALIGN);
-        void *packed = wp + pp.wprime_bytes;
+        void *wp = base, *packed = base + pp.wprime_bytes, *dxs = base + phase_fixed_bytes(pp, SN_CONV_BWD_DATA);
         if (!pp.plain && launch_phase_filter(w, wp, pp.m, g, st) != hipSuccess) return SN_ERR_LAUNCH;
-        if (launch_tile_conv(dy, pp.plain ? w : wp, dxs, pp.inner, true, packed, st) != hipSuccess) return SN_ERR_LAUNCH;
-        return launch_status(launch_phase_merge(dxs, dx, pp.m, g, st));
+        const int chunk = phase_chunk(pp, SN_CONV_BWD_DATA, ws_bytes);
+        for (int n0 = 0; n0 < g.N; n0 += chunk) {
+            ConvGeom go = g, gi = pp.inner;
+            go.N = gi.N = std::min(chunk, g.N - n0);
+            const char *dyo = static_cast<const char *>(dy) + (size_t)n0 * g.K * g.P * g.Q * in_elem(g);
+            char *dxo = static_cast<char *>(dx) + (size_t)n0 * g.C * g.H * g.W * out_elem(g);
+            if (launch_tile_conv(dyo, pp.plain ? w : wp, dxs, gi, true, packed, st) != hipSuccess) return SN_ERR_LAUNCH;
+            if (launch_phase_merge(dxs, dxo, pp.m, go, st) != hipSuccess) return SN_ERR_LAUNCH;
+        }
+        return SN_OK;
     }
     if (algo == SN_ALGO_STAGED) return launch_status(launch_tile_conv(dy, w, dx, g, true, ws, st));
     if (algo == SN_ALGO_IM2COL_GEMM) {
