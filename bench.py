@@ -41,13 +41,13 @@ PEAK = {"bf16_mfma_tflops": 2500.0, "f32_mfma_tflops": 157.3, "hbm_gbs": 8000.0}
 # Only for the workload and budget the counters were collected on, and only while the kernel sources
 # are the ones they were collected on (TRAFFIC_KERNEL_SET = kernel_set_id() at that time); anything
 # else reports null with a note.
-TRAFFIC_KERNEL_SET = "unset"
+TRAFFIC_KERNEL_SET = "7fbb2d4e7f02"
 MEASURED_TRAFFIC = {("cfg3_vgg16_n32", 2 << 30, "conv_bwd_filter"): 258e6,
                     # forward and backward-data run the same kernels: one figure for the 25 launches of both
-                    ("cfg3_vgg16_n32", 2 << 30, "conv_fwd"): 149e6,
-                    ("cfg3_vgg16_n32", 2 << 30, "conv_bwd_data"): 149e6}
-KERNELS = {"conv_fwd": "conv_tile2_kernel / conv_tile_kernel (+ pack_filter_kernel)",
-           "conv_bwd_data": "conv_tile2_kernel / conv_tile_kernel (+ pack_filter_kernel)",
+                    ("cfg3_vgg16_n32", 2 << 30, "conv_fwd"): 145e6,
+                    ("cfg3_vgg16_n32", 2 << 30, "conv_bwd_data"): 145e6}
+KERNELS = {"conv_fwd": "conv_tile2_kernel / conv_tile_kernel (+ pack_filter9_kernel)",
+           "conv_bwd_data": "conv_tile2_kernel / conv_tile_kernel (+ pack_filter9_kernel)",
            "conv_bwd_filter": "wgrad_rows_kernel + reduce_partials4_kernel (STAGED) or fill_zero_kernel (DIRECT)"}
 
 
@@ -60,6 +60,10 @@ def parse():
     ap.add_argument("--budget-mib", type=float, default=None, help="workspace budget; default: the largest listed")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-autotune", action="store_true")
+    ap.add_argument("--plan-file", default=None,
+                    help="JSON of the planner's choices: written after autotuning if absent, loaded instead of "
+                         "autotuning if present (a run under a counter-collecting profiler then launches the kernels "
+                         "the plain run launched; the profiler's cost per dispatch skews the autotuner's timings)")
     ap.add_argument("--no-budget-sweep", action="store_true", help="skip the conv timing at the smaller budgets")
     ap.add_argument("--no-fuse", action="store_true", help="BN and ReLU as separate calls, forward and backward")
     ap.add_argument("--detail", default=None, help="write the per-layer table to this JSON file")
@@ -102,7 +106,7 @@ def measure_ceilings(buf):
     return out
 
 
-def build_ops(cfg_no, budget, autotune, fuse):
+def build_ops(cfg_no, budget, autotune, fuse, plan_file=None):
     import torch
 
     import paper_1801_04380_amd as sn
@@ -118,6 +122,12 @@ def build_ops(cfg_no, budget, autotune, fuse):
     wsbox = [ws]   # the workspace the conv calls are handed; main() swaps in smaller budgets
     fwd_ops, bwd_ops, plans = [], [], {}
     tune_ms = 0.0
+    saved_plan = plan_out = None
+    if plan_file and os.path.exists(plan_file):
+        with open(plan_file) as f:
+            saved_plan = json.load(f)
+    elif plan_file and autotune:
+        plan_out = {}
     for li, layer in enumerate(cfg["layers"]):
         x, w, _ = wl.conv_inputs(layer, N, dtype, wl.layer_seed(cfg_no, li))
         P, Q = wl.out_hw(layer)
@@ -139,7 +149,11 @@ def build_ops(cfg_no, budget, autotune, fuse):
         # the gradient that reaches the conv comes from the cheap layers' backward below;
         # fill it once so the autotune runs on real values
         dy.copy_(wl.activation((N, K, P, Q), dtype, wl.layer_seed(cfg_no, li) + 7).to(dev))
-        if autotune:
+        if saved_plan is not None:
+            for d in (0, 1, 2):
+                for algo, used, ms in saved_plan.get("%s|%d" % (layer.name, d), []):
+                    sn.sn_planner_record(shape, d, algo, used, ms)
+        elif autotune:
             t0 = time.time()
             for d, (a, bb, out) in {0: (xd, wd, y), 1: (dy, wd, dx), 2: (xd, dy, dw)}.items():
                 sn.sn_conv_autotune(d, a, bb, out, shape, ws, iters=5)
@@ -148,6 +162,10 @@ def build_ops(cfg_no, budget, autotune, fuse):
         for d in (0, 1, 2):
             algo, used, ms = sn.sn_conv_plan(shape, d, budget)
             plans[(layer.name, d)] = (sn.ALGO_NAMES[algo], used, ms)
+            if plan_out is not None:
+                # the choice at every budget of the workload: enough to reproduce each of them
+                picks = {sn.sn_conv_plan(shape, d, bb_) for bb_ in sorted({budget} | {x_ if x_ is not None else budget for x_ in cfg["budgets"]})}
+                plan_out["%s|%d" % (layer.name, d)] = sorted([a_, u_, m_] for a_, u_, m_ in picks if m_ is not None)
         names = {0: "conv_fwd", 1: "conv_bwd_data", 2: "conv_bwd_filter"}
         byts = {0: (ex + ew) * b + ey * b, 1: (ey + ew) * b + ex * b, 2: (ex + ey) * b + ew * 4}
         cheap_f, cheap_b = [], []
@@ -256,6 +274,9 @@ def build_ops(cfg_no, budget, autotune, fuse):
                 layer_bwd.append(Op(names[1], layer.name, conv_call(1, dy, wd, dx), algo_flops, byts[1], nominal))
             layer_bwd.append(Op(names[2], layer.name, conv_call(2, xd, dy, dw), algo_flops, byts[2], nominal))
         bwd_ops = layer_bwd + bwd_ops  # backward visits the layers in reverse
+    if plan_out is not None:
+        with open(plan_file, "w") as f:
+            json.dump(plan_out, f, indent=0, sort_keys=True)
     return cfg, fwd_ops + bwd_ops, plans, tune_ms, wsbox
 
 
@@ -432,7 +453,7 @@ def main():
     if args.table:
         layer_table(args.workload, budget, args.table)
         return
-    cfg, ops, plans, tune_ms, wsbox = build_ops(args.workload, budget, not args.no_autotune, not args.no_fuse)
+    cfg, ops, plans, tune_ms, wsbox = build_ops(args.workload, budget, not args.no_autotune, not args.no_fuse, args.plan_file)
     stream = torch.cuda.current_stream()
 
     def step(timed_keys):

@@ -322,8 +322,14 @@ sn_status plan(const sn_conv_shape *shape, const ConvGeom &g, sn_conv_dir dir, s
         if (query(g, dir, a, &mn, &pf) != SN_OK || mn > budget) continue;
         // Winograd pays four kernels per pass: a guess in its favour only where a pass has real work
         if (a == SN_ALGO_WINOGRAD && pf > budget && winograd_pass_tiles(g, dir == SN_CONV_BWD_DATA, budget) < 2048) continue;
-        // strided forward over phase planes gains little over the zero-workspace kernel: not in passes
-        if (a == SN_ALGO_STAGED && dir == SN_CONV_FWD && pf > budget && (g.sh > 1 || g.sw > 1)) continue;
+        // The phase planes in passes: strided forward gains little over the zero-workspace kernel, so only
+        // with the whole batch; backward-data gains 2-4x, which more than eight passes' launches eat up.
+        if (a == SN_ALGO_STAGED && pf > budget && (g.sh > 1 || g.sw > 1) && dir != SN_CONV_BWD_FILTER) {
+            PhasePlan pp;
+            if (dir == SN_CONV_FWD || !phase_plan(g, dir, &pp)) continue;
+            const int chunk = phase_chunk(pp, dir, budget);
+            if ((g.N + chunk - 1) / chunk > 8) continue;
+        }
         *algo = a;
         *bytes = std::min(pf, budget);
         if (ms_out) *ms_out = -1.f;
