@@ -570,7 +570,9 @@ bn_bwd_apply_kernel(const T *__restrict__ x, const GradSrc<T> gs, const float *_
 }
 
 // ---- BN in one pass over HBM, for channels that fit in the registers of one workgroup.
-// A workgroup of 1024 threads takes one channel: thread t holds vectors t, t + 1024, ...
+// A workgroup of BT threads (1024, or 256 where that holds the channel: four times the workgroups per
+// compute unit, which is what the short channels of small planes need) takes one channel: thread t holds
+// vectors t, t + BT, ...
 // (16 or 8 bytes each) of the channel's N*HW elements from the load until the store, so x
 // (and dy) are read once and y (dx) written once.  The statistics are two-pass sums over
 // the registers, reduced in a fixed order (wavefront butterflies, then the 16 wavefront
@@ -635,8 +637,8 @@ bn_relu_pool2_apply_kernel(const T *__restrict__ x, T *__restrict__ pooled, int3
         bn_relu_pool2_unit<T, VB>(x, pooled, idx, u, c, C, H, W, mu, a, b);
 }
 
-// Sum over the 1024 threads of a workgroup, the same value in every thread.
-__device__ inline float block_sum_1024(float v, float *red)
+// Sum over the BT threads of a workgroup (whole waves), the same value in every thread.
+template <int BT> __device__ inline float block_sum(float v, float *red)
 {
     v = wave_sum(v);
     __syncthreads();   // red may still be read from the previous sum
@@ -644,7 +646,7 @@ __device__ inline float block_sum_1024(float v, float *red)
     __syncthreads();
     float s = 0.f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) s += red[i];
+    for (int i = 0; i < BT / 64; ++i) s += red[i];
     return s;
 }
 
@@ -653,8 +655,8 @@ __device__ inline float block_sum_1024(float v, float *red)
 // units of PVB bytes of a row pair -- the workgroup has just streamed it, so it comes from the
 // caches -- and writes the pooled values and indices only (y is not touched; H, W as the pool
 // sees them).
-template <typename T, int VB, int NVMAX, int PVB>
-__global__ void __launch_bounds__(1024)
+template <typename T, int VB, int NVMAX, int PVB, int BT>
+__global__ void __launch_bounds__(BT)
 bn_fwd_fused_kernel(const T *__restrict__ x, T *__restrict__ y, const float *__restrict__ gamma,
                     const float *__restrict__ beta, float *__restrict__ mean, float *__restrict__ invstd,
                     int N, int C, int HW, float eps, int relu, T *__restrict__ pooled, int32_t *__restrict__ idx,
@@ -669,7 +671,7 @@ bn_fwd_fused_kernel(const T *__restrict__ x, T *__restrict__ y, const float *__r
     float s = 0.f;
 #pragma unroll
     for (int j = 0; j < NVMAX; ++j) {
-        const int i = tid + j * 1024;
+        const int i = tid + j * BT;
         if (i < nvec) {
             const int n = i / vpp, e = i - n * vpp;
             v[j] = *reinterpret_cast<const VT *>(x + ((size_t)n * C + c) * HW + (size_t)e * VE);
@@ -680,30 +682,30 @@ bn_fwd_fused_kernel(const T *__restrict__ x, T *__restrict__ y, const float *__r
         }
     }
     const float M = (float)N * (float)HW;
-    const float mu = block_sum_1024(s, red) / M;
+    const float mu = block_sum<BT>(s, red) / M;
     float q = 0.f;
 #pragma unroll
     for (int j = 0; j < NVMAX; ++j) {
-        if (tid + j * 1024 < nvec) {
+        if (tid + j * BT < nvec) {
             float f[VE];
             unpack<T, VB>(v[j], f);
 #pragma unroll
             for (int k = 0; k < VE; ++k) q += (f[k] - mu) * (f[k] - mu);
         }
     }
-    const float var = block_sum_1024(q, red) / M;
+    const float var = block_sum<BT>(q, red) / M;
     const float is = 1.f / sqrtf(var + eps);
     if (tid == 0) { mean[c] = mu; invstd[c] = is; }
     const float a = gamma[c] * is, b = beta[c];
     if (PVB != 0) {
         constexpr int PB = PVB ? PVB : 16;
         const int units = N * (H >> 1) * (W / (PB / (int)sizeof(T)));
-        for (int u = tid; u < units; u += 1024) bn_relu_pool2_unit<T, PB>(x, pooled, idx, u, c, C, H, W, mu, a, b);
+        for (int u = tid; u < units; u += BT) bn_relu_pool2_unit<T, PB>(x, pooled, idx, u, c, C, H, W, mu, a, b);
         return;
     }
 #pragma unroll
     for (int j = 0; j < NVMAX; ++j) {
-        const int i = tid + j * 1024;
+        const int i = tid + j * BT;
         if (i < nvec) {
             const int n = i / vpp, e = i - n * vpp;
             float f[VE];
@@ -715,8 +717,8 @@ bn_fwd_fused_kernel(const T *__restrict__ x, T *__restrict__ y, const float *__r
     }
 }
 
-template <typename T, int VB, int NVMAX>
-__global__ void __launch_bounds__(1024)
+template <typename T, int VB, int NVMAX, int BT>
+__global__ void __launch_bounds__(BT)
 bn_bwd_fused_kernel(const T *__restrict__ x, const GradSrc<T> gs, const float *__restrict__ beta,
                     T *__restrict__ dx, const float *__restrict__ gamma, const float *__restrict__ mean,
                     const float *__restrict__ invstd, float *__restrict__ dgamma, float *__restrict__ dbeta,
@@ -734,7 +736,7 @@ bn_bwd_fused_kernel(const T *__restrict__ x, const GradSrc<T> gs, const float *_
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
     for (int j = 0; j < NVMAX; ++j) {
-        const int i = tid + j * 1024;
+        const int i = tid + j * BT;
         if (i < nvec) {
             const int n = i / vpp, e = i - n * vpp;
             const size_t off = ((size_t)n * C + c) * HW + (size_t)e * VE;
@@ -759,14 +761,14 @@ bn_bwd_fused_kernel(const T *__restrict__ x, const GradSrc<T> gs, const float *_
             }
         }
     }
-    const float db = block_sum_1024(s1, red);
-    const float dg = block_sum_1024(s2, red) * is;
+    const float db = block_sum<BT>(s1, red);
+    const float dg = block_sum<BT>(s2, red) * is;
     if (tid == 0) { dbeta[c] = db; dgamma[c] = dg; }
     const float invM = 1.f / ((float)N * (float)HW);
     const float k1 = ga, kb = db * invM, kg = dg * invM * is;
 #pragma unroll
     for (int j = 0; j < NVMAX; ++j) {
-        const int i = tid + j * 1024;
+        const int i = tid + j * BT;
         if (i < nvec) {
             const int n = i / vpp, e = i - n * vpp;
             const size_t off = ((size_t)n * C + c) * HW + (size_t)e * VE;
@@ -783,6 +785,9 @@ bn_bwd_fused_kernel(const T *__restrict__ x, const GradSrc<T> gs, const float *_
 constexpr int BN_FUSED_NV = 13;   // vectors a thread can hold (13 * 1024 * 8 bf16 = 106496 elements per channel)
 constexpr int BN_FUSED_NVS = 4;   // the same kernels built for short channels: fewer registers, two workgroups per compute unit
 constexpr int BN_FUSED_NV1 = 32;  // single elements a thread can hold: planes of odd size (7x7, 17x17) have no wider access
+
+// A channel of `count` vectors that 256 threads hold with nv vectors each: the 256-thread build.
+inline bool bn_fused_small(long long count, int nv) { return count <= 256LL * nv; }
 
 // Vector size in bytes for the one-pass kernels, 0 if they do not apply.
 template <typename T> int bn_fused_vb(const void *a, const void *b, const void *c3, int N, int HW)
@@ -1352,26 +1357,24 @@ hipError_t launch_bn_fwd(const void *x, const float *gamma, const float *beta, v
                 // a channel of at most 4 vectors per thread goes to the build with 4 registers' worth of them
                 // (the sums run over the same elements in the same order either way)
                 const bool few = vb >= 8 && (long long)N * (HW / (vb / (int)sizeof(T))) <= 1024LL * BN_FUSED_NVS;
-                if (vb == 16 && few)
-                    hipLaunchKernelGGL((bn_fwd_fused_kernel<T, 16, BN_FUSED_NVS, 0>), dim3(C), dim3(1024), 0, s, (const T *)x,
-                                       (T *)y, gamma, beta, mean, invstd, N, C, HW, eps, relu, (T *)nullptr,
-                                       (int32_t *)nullptr, 0, 0);
-                else if (vb == 8 && few)
-                    hipLaunchKernelGGL((bn_fwd_fused_kernel<T, 8, BN_FUSED_NVS, 0>), dim3(C), dim3(1024), 0, s, (const T *)x,
-                                       (T *)y, gamma, beta, mean, invstd, N, C, HW, eps, relu, (T *)nullptr,
-                                       (int32_t *)nullptr, 0, 0);
-                else if (vb == 16)
-                    hipLaunchKernelGGL((bn_fwd_fused_kernel<T, 16, BN_FUSED_NV, 0>), dim3(C), dim3(1024), 0, s, (const T *)x,
-                                       (T *)y, gamma, beta, mean, invstd, N, C, HW, eps, relu, (T *)nullptr,
-                                       (int32_t *)nullptr, 0, 0);
-                else if (vb == (int)sizeof(T))
-                    hipLaunchKernelGGL((bn_fwd_fused_kernel<T, sizeof(T), BN_FUSED_NV1, 0>), dim3(C), dim3(1024), 0, s,
-                                       (const T *)x, (T *)y, gamma, beta, mean, invstd, N, C, HW, eps, relu, (T *)nullptr,
-                                       (int32_t *)nullptr, 0, 0);
-                else
-                    hipLaunchKernelGGL((bn_fwd_fused_kernel<T, 8, BN_FUSED_NV, 0>), dim3(C), dim3(1024), 0, s, (const T *)x,
-                                       (T *)y, gamma, beta, mean, invstd, N, C, HW, eps, relu, (T *)nullptr,
-                                       (int32_t *)nullptr, 0, 0);
+                const long long cnt = (long long)N * (HW / (vb / (int)sizeof(T)));   // vectors per channel
+#define SN_BN_FWD(VB_, NV_)                                                                                          \
+    do {                                                                                                             \
+        if (bn_fused_small(cnt, NV_))                                                                                \
+            hipLaunchKernelGGL((bn_fwd_fused_kernel<T, VB_, NV_, 0, 256>), dim3(C), dim3(256), 0, s, (const T *)x,   \
+                               (T *)y, gamma, beta, mean, invstd, N, C, HW, eps, relu, (T *)nullptr,                 \
+                               (int32_t *)nullptr, 0, 0);                                                            \
+        else                                                                                                         \
+            hipLaunchKernelGGL((bn_fwd_fused_kernel<T, VB_, NV_, 0, 1024>), dim3(C), dim3(1024), 0, s, (const T *)x, \
+                               (T *)y, gamma, beta, mean, invstd, N, C, HW, eps, relu, (T *)nullptr,                 \
+                               (int32_t *)nullptr, 0, 0);                                                            \
+    } while (0)
+                if (vb == 16 && few) SN_BN_FWD(16, BN_FUSED_NVS);
+                else if (vb == 8 && few) SN_BN_FWD(8, BN_FUSED_NVS);
+                else if (vb == 16) SN_BN_FWD(16, BN_FUSED_NV);
+                else if (vb == (int)sizeof(T)) SN_BN_FWD(sizeof(T), BN_FUSED_NV1);
+                else SN_BN_FWD(8, BN_FUSED_NV);
+#undef SN_BN_FWD
             });
     }
     // y is dead until pass 3, so it holds the per-slice partial sums meanwhile
@@ -1465,9 +1468,17 @@ hipError_t launch_bn_relu_pool2_fwd(const void *x, const float *gamma, const flo
     if (vb)
         return by_dtype(bf16, [&](auto *tag) {
             typedef typename std::remove_pointer<decltype(tag)>::type T;
-#define SN_POOL_FUSED(VB_, NV_, PVB_)                                                                       \
-    hipLaunchKernelGGL((bn_fwd_fused_kernel<T, VB_, NV_, PVB_>), dim3(C), dim3(1024), 0, s, (const T *)x,         \
-                       (T *)nullptr, gamma, beta, mean, invstd, N, C, HW, eps, 1, (T *)pooled, idx, H, W)
+#define SN_POOL_FUSED(VB_, NV_, PVB_)                                                                                \
+    do {                                                                                                             \
+        if (bn_fused_small((long long)N * (HW / (VB_ / (int)sizeof(T))), NV_))                                       \
+            hipLaunchKernelGGL((bn_fwd_fused_kernel<T, VB_, NV_, PVB_, 256>), dim3(C), dim3(256), 0, s,             \
+                               (const T *)x, (T *)nullptr, gamma, beta, mean, invstd, N, C, HW, eps, 1, (T *)pooled, \
+                               idx, H, W);                                                                           \
+        else                                                                                                         \
+            hipLaunchKernelGGL((bn_fwd_fused_kernel<T, VB_, NV_, PVB_, 1024>), dim3(C), dim3(1024), 0, s,           \
+                               (const T *)x, (T *)nullptr, gamma, beta, mean, invstd, N, C, HW, eps, 1, (T *)pooled, \
+                               idx, H, W);                                                                           \
+    } while (0)
             // H even and W a multiple of half a 16-byte vector make H*W a multiple of the whole one
             const bool few = (long long)N * (HW / (16 / (int)sizeof(T))) <= 1024LL * BN_FUSED_NVS;
             if (pvb == 16 && few) SN_POOL_FUSED(16, BN_FUSED_NVS, 16);
@@ -1511,21 +1522,22 @@ hipError_t launch_bn_bwd(const void *x, const void *dy, const float *relu_beta, 
                 typedef typename std::remove_pointer<decltype(tag)>::type T;
                 const GradSrc<T> gs{(const T *)dy, (const T *)pool_g, pool_idx, pool_W, pool_W / 2, HW, HW / 4};
                 const bool few = vb >= 8 && (long long)N * (HW / (vb / (int)sizeof(T))) <= 1024LL * BN_FUSED_NVS;
-                if (vb == 16 && few)
-                    hipLaunchKernelGGL((bn_bwd_fused_kernel<T, 16, BN_FUSED_NVS>), dim3(C), dim3(1024), 0, s, (const T *)x,
-                                       gs, relu_beta, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);
-                else if (vb == 8 && few)
-                    hipLaunchKernelGGL((bn_bwd_fused_kernel<T, 8, BN_FUSED_NVS>), dim3(C), dim3(1024), 0, s, (const T *)x,
-                                       gs, relu_beta, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);
-                else if (vb == 16)
-                    hipLaunchKernelGGL((bn_bwd_fused_kernel<T, 16, BN_FUSED_NV>), dim3(C), dim3(1024), 0, s, (const T *)x,
-                                       gs, relu_beta, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);
-                else if (vb == (int)sizeof(T))
-                    hipLaunchKernelGGL((bn_bwd_fused_kernel<T, sizeof(T), BN_FUSED_NV1>), dim3(C), dim3(1024), 0, s,
-                                       (const T *)x, gs, relu_beta, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);
-                else
-                    hipLaunchKernelGGL((bn_bwd_fused_kernel<T, 8, BN_FUSED_NV>), dim3(C), dim3(1024), 0, s, (const T *)x,
-                                       gs, relu_beta, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);
+                const long long cnt = (long long)N * (HW / (vb / (int)sizeof(T)));   // vectors per channel
+#define SN_BN_BWD(VB_, NV_)                                                                                           \
+    do {                                                                                                              \
+        if (bn_fused_small(cnt, NV_))                                                                                 \
+            hipLaunchKernelGGL((bn_bwd_fused_kernel<T, VB_, NV_, 256>), dim3(C), dim3(256), 0, s, (const T *)x, gs,   \
+                               relu_beta, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);                     \
+        else                                                                                                          \
+            hipLaunchKernelGGL((bn_bwd_fused_kernel<T, VB_, NV_, 1024>), dim3(C), dim3(1024), 0, s, (const T *)x, gs, \
+                               relu_beta, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);                     \
+    } while (0)
+                if (vb == 16 && few) SN_BN_BWD(16, BN_FUSED_NVS);
+                else if (vb == 8 && few) SN_BN_BWD(8, BN_FUSED_NVS);
+                else if (vb == 16) SN_BN_BWD(16, BN_FUSED_NV);
+                else if (vb == (int)sizeof(T)) SN_BN_BWD(sizeof(T), BN_FUSED_NV1);
+                else SN_BN_BWD(8, BN_FUSED_NV);
+#undef SN_BN_BWD
             });
     }
     const Slices sl = make_slices(N, C, HW, (size_t)N * C * HW * esz);
