@@ -41,7 +41,7 @@ PEAK = {"bf16_mfma_tflops": 2500.0, "f32_mfma_tflops": 157.3, "hbm_gbs": 8000.0}
 # Only for the workload and budget the counters were collected on, and only while the kernel sources
 # are the ones they were collected on (TRAFFIC_KERNEL_SET = kernel_set_id() at that time); anything
 # else reports null with a note.
-TRAFFIC_KERNEL_SET = "7fbb2d4e7f02"
+TRAFFIC_KERNEL_SET = "9e9e99e92a93"
 MEASURED_TRAFFIC = {("cfg3_vgg16_n32", 2 << 30, "conv_bwd_filter"): 258e6,
                     # forward and backward-data run the same kernels: one figure for the 25 launches of both
                     ("cfg3_vgg16_n32", 2 << 30, "conv_fwd"): 145e6,
@@ -66,6 +66,8 @@ def parse():
                          "the plain run launched; the profiler's cost per dispatch skews the autotuner's timings)")
     ap.add_argument("--no-budget-sweep", action="store_true", help="skip the conv timing at the smaller budgets")
     ap.add_argument("--no-fuse", action="store_true", help="BN and ReLU as separate calls, forward and backward")
+    ap.add_argument("--table-dtype", default=None, choices=["bf16", "f32"], help="--table only: run the workload's layers in this type")
+    ap.add_argument("--table-batch", type=int, default=None, help="--table only: batch size instead of the workload's")
     ap.add_argument("--detail", default=None, help="write the per-layer table to this JSON file")
     ap.add_argument("--table", default=None,
                     help="instead of the step: time every layer x direction x algorithm of the workload, and the "
@@ -84,12 +86,13 @@ class Op:
 
 
 def kernel_set_id():
-    """A short hash of the HIP sources: tells a stale counter figure from a current one."""
+    """A short hash of the sources of the kernels the traffic figures are about (the stride-1 tile and
+    backward-filter kernels): tells a stale counter figure from a current one."""
     import hashlib
     h = hashlib.sha256()
     d = os.path.join(ROOT, "paper_1801_04380_amd", "csrc")
     for name in sorted(os.listdir(d)):
-        if name.endswith((".hip", ".h", ".cpp")):
+        if name.startswith(("conv_tile", "conv_wgrad")) and name.endswith((".hip", ".h")):
             with open(os.path.join(d, name), "rb") as f:
                 h.update(name.encode() + b"\0" + f.read())
     return h.hexdigest()[:12]
@@ -280,7 +283,7 @@ def build_ops(cfg_no, budget, autotune, fuse, plan_file=None):
     return cfg, fwd_ops + bwd_ops, plans, tune_ms, wsbox
 
 
-def layer_table(cfg_no, budget, path):
+def layer_table(cfg_no, budget, path, dtype_override=None, batch_override=None):
     """Per layer x direction x algorithm (at its least and its preferred workspace, the latter capped
     by the budget): median and minimum of 20 launches after 5 warm-up launches, each between a pair
     of events.  Cheap layers: every call on every conv output, rotating through three sets of
@@ -291,7 +294,7 @@ def layer_table(cfg_no, budget, path):
     from paper_1801_04380_amd import workloads as wl
 
     cfg = wl.CONFIGS[cfg_no]
-    N, dtype, dev = cfg["N"], cfg["dtype"], torch.device("cuda:0")
+    N, dtype, dev = batch_override or cfg["N"], dtype_override or cfg["dtype"], torch.device("cuda:0")
     tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
     code = sn.SN_BF16 if dtype == "bf16" else sn.SN_F32
     b = 2 if dtype == "bf16" else 4
@@ -316,8 +319,11 @@ def layer_table(cfg_no, budget, path):
     out = ["%s, N = %d, %s, workspace budget %d MiB; times in us (median / min of 20 launches); TFLOP/s and %% of the"
            % (cfg["name"], N, dtype, budget >> 20),
            "dense MFMA peak (%.0f TFLOP/s) from algorithmic FLOPs and the median; GB/s and %% of 8 TB/s from the" % peak,
-           "compulsory bytes of the call and the median.", "",
-           "%-10s %-10s %-12s %10s %9s %9s %8s %6s" % ("layer", "direction", "algorithm", "ws MiB", "median", "min", "TFLOP/s", "peak")]
+           "compulsory bytes of the call and the median.  F/B: algorithmic FLOPs per compulsory byte; roof: what bounds the",
+           "call at that intensity (mfma above %.0f F/B, else hbm at 8 TB/s x F/B) and the share of that roof reached."
+           % (peak * 1e12 / (PEAK["hbm_gbs"] * 1e9)), "",
+           "%-10s %-10s %-12s %10s %9s %9s %8s %6s %7s %5s %7s" % ("layer", "direction", "algorithm", "ws MiB", "median", "min",
+                                                                  "TFLOP/s", "peak", "F/B", "roof", "of roof")]
     names = {0: "forward", 1: "bwd-data", 2: "bwd-filter"}
     cheap = []
     for li, layer in enumerate(cfg["layers"]):
@@ -329,6 +335,8 @@ def layer_table(cfg_no, budget, path):
         y, dx = torch.empty((N, K, P, Q), dtype=tdt, device=dev), torch.empty_like(xd)
         dw = torch.empty(tuple(w.shape), dtype=torch.float32, device=dev)
         flops = wl.conv_flops(layer, N)[1]
+        ex, ew, ey = xd.numel(), wd.numel(), y.numel()
+        cbytes = {0: (ex + ew) * b + ey * b, 1: (ey + ew) * b + ex * b, 2: (ex + ey) * b + ew * 4}
         for d, (fn, a, bb, o) in {0: (sn.sn_conv2d_fwd, xd, wd, y), 1: (sn.sn_conv2d_bwd_data, dyd, wd, dx),
                                   2: (sn.sn_conv2d_bwd_filter, xd, dyd, dw)}.items():
             if d == 1 and layer.first:
@@ -344,9 +352,12 @@ def layer_table(cfg_no, budget, path):
                     wsv = ws[:used] if used else None
                     med, lo = timed([lambda: fn(a, bb, o, shape, algo, wsv)])
                     tf = flops / (med * 1e-3) / 1e12
-                    out.append("%-10s %-10s %-12s %10.1f %9.1f %9.1f %8.1f %5.1f%%"
+                    ai = flops / cbytes[d]
+                    hbm_roof = ai * PEAK["hbm_gbs"] * 1e9 / 1e12
+                    roof = min(peak, hbm_roof)
+                    out.append("%-10s %-10s %-12s %10.1f %9.1f %9.1f %8.1f %5.1f%% %7.0f %5s %6.1f%%"
                                % (layer.name, names[d], sn.ALGO_NAMES[algo], used / 2 ** 20, med * 1e3, lo * 1e3, tf,
-                                  100 * tf / peak))
+                                  100 * tf / peak, ai, "mfma" if peak <= hbm_roof else "hbm", 100 * tf / roof))
         cheap.append((layer, (N, K, P, Q)))
         del xd, wd, dyd, y, dx, dw
     out += ["", "%-10s %-22s %12s %9s %9s %8s %6s" % ("layer", "call", "MB moved", "median", "min", "GB/s", "of HBM")]
@@ -451,7 +462,7 @@ def main():
     else:
         budget = max(budgets) if budgets else 64 << 20
     if args.table:
-        layer_table(args.workload, budget, args.table)
+        layer_table(args.workload, budget, args.table, args.table_dtype, args.table_batch)
         return
     cfg, ops, plans, tune_ms, wsbox = build_ops(args.workload, budget, not args.no_autotune, not args.no_fuse, args.plan_file)
     stream = torch.cuda.current_stream()

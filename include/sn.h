@@ -118,7 +118,7 @@ sn_status sn_conv_workspace_query(const sn_conv_shape *shape, sn_conv_dir dir, s
  * sn_planner_record / sn_conv_autotune (the paper benchmarks the feasible
  * algorithms at run time); a recorded time applies to budgets >= the workspace
  * it was measured with.  With no feasible record the choice falls back to a
- * built-in ranking (WINOGRAD where it applies and at least 2048 tiles fit a pass, STAGED,
+ * built-in ranking (WINOGRAD where it applies, C * K >= 8192 and at least 2048 tiles fit a pass, STAGED,
  * then DIRECT; for strided backward-data the explicit algorithm before DIRECT).  Among records within 3 % of the fastest the one with the
  * smallest workspace wins (then the faster).  DIRECT needs 0 bytes, so a plan always exists.  bytes_used = the workspace the choice will use
  * (<= budget_bytes).  predicted_ms may be NULL; it receives the recorded time

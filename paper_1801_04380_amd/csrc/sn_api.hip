@@ -320,8 +320,11 @@ sn_status plan(const sn_conv_shape *shape, const ConvGeom &g, sn_conv_dir dir, s
         }
         if (a == SN_ALGO_IM2COL_GEMM) continue;
         if (query(g, dir, a, &mn, &pf) != SN_OK || mn > budget) continue;
-        // Winograd pays four kernels per pass: a guess in its favour only where a pass has real work
-        if (a == SN_ALGO_WINOGRAD && pf > budget && winograd_pass_tiles(g, dir == SN_CONV_BWD_DATA, budget) < 2048) continue;
+        // Winograd pays four kernels per pass and streams 16 transformed values per 4 inputs: a guess in its
+        // favour only where a pass has real work and the products outweigh the transforms (measured: 64 x 128
+        // channels gain, 64 x 64 lose)
+        if (a == SN_ALGO_WINOGRAD && ((pf > budget && winograd_pass_tiles(g, dir == SN_CONV_BWD_DATA, budget) < 2048) ||
+                                      (long long)g.C * g.K < 8192)) continue;
         // The phase planes in passes: strided forward gains little over the zero-workspace kernel, so only
         // with the whole batch; backward-data gains 2-4x, which more than eight passes' launches eat up.
         if (a == SN_ALGO_STAGED && pf > budget && (g.sh > 1 || g.sw > 1) && dir != SN_CONV_BWD_FILTER) {
