@@ -65,7 +65,8 @@ typedef enum { SN_CONV_FWD = 0, SN_CONV_BWD_DATA = 1, SN_CONV_BWD_FILTER = 2 } s
  *               order, so the result is run-to-run identical) for
  *               backward-filter.  On strided shapes (bf16; 1x1 filters without
  *               padding, and filters whose taps reach at most one row / column
- *               of the stride grid beyond the output's, e.g. 3x3 stride 2 pad 1)
+ *               of the stride grid beyond the output's, e.g. 3x3 stride 2 pad 1, or
+ *               at most two on one side without padding, e.g. 11x11 stride 4)
  *               also the phase planes of the input: x[i*stride + a] for each
  *               residue a becomes a channel group, over which the convolution
  *               has stride 1 and runs on the stride-1 kernels; forward and

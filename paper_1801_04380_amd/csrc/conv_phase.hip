@@ -6,7 +6,9 @@
 // input, x_a[i] = x[i*sh + a] (columns likewise with e, b).  Over the phase planes as channels the
 // convolution has stride 1 and a filter whose taps are the (d, e) that occur; the layers here have
 // d, e in {-1, 0, 1}, i.e. a 3x3 filter with "same" padding on planes of the output's size (or 1x1
-// for 1x1 filters), which the stride-1 MFMA kernels run.  Taps that do not occur are zeros in the
+// for 1x1 filters), or in {0, 1, 2} (filters up to three strides long without padding, e.g. 11x11 /
+// stride 4), a 3x3 filter without padding on planes two rows / columns larger, which the stride-1
+// MFMA kernels run.  Taps that do not occur are zeros in the
 // transformed filter.  This file holds the copies around that inner convolution:
 //   phase_split   x  -> xs[n][phase*C + c][i][j]           (forward, backward-filter)
 //   phase_filter  w  -> w'[k][phase*C + c][d+1][e+1]       (forward, backward-data)
@@ -118,7 +120,7 @@ phase_filter_kernel(const bf16_t *__restrict__ w, bf16_t *__restrict__ wp, Phase
     const int k = (int)(t / ((long long)C * m.nphases));
     const int phase = cp / C, c = cp - phase * C;
     const int a = m.row_phase[phase / m.nb], b = m.col_phase[phase % m.nb];
-    const int dd = tap / m.Si - m.center, ee = tap % m.Si - m.center;
+    const int dd = tap / m.Si - m.center_r, ee = tap % m.Si - m.center_c;
     const int r = dd * m.sh + a + m.ph, s = ee * m.sw + b + m.pw;   // the tap with r - ph = d*sh + a
     bf16_t v = 0;
     if (r >= 0 && r < R && s >= 0 && s < S) v = w[(((long long)k * C + c) * R + r) * S + s];
@@ -195,7 +197,7 @@ phase_merge_kernel(const T *__restrict__ dxs, T *__restrict__ dx, PhaseMap m, in
         if (v0 + e < W) dst[e] = vals[e];
 }
 
-// dw[k][c][r][s] = dw'[k][phase*C + c][d+center][e+center]: one thread per element of dw.
+// dw[k][c][r][s] = dw'[k][phase*C + c][d + center_r][e + center_c]: one thread per element of dw.
 __global__ void __launch_bounds__(256)
 phase_dw_kernel(const float *__restrict__ dwp, float *__restrict__ dw, PhaseMap m, int K, int C, int R, int S,
                 long long total)
@@ -212,7 +214,7 @@ phase_dw_kernel(const float *__restrict__ dwp, float *__restrict__ dw, PhaseMap 
     const int d = (u >= 0 ? u : u - m.sh + 1) / m.sh, a = u - d * m.sh;
     const int e = (z >= 0 ? z : z - m.sw + 1) / m.sw, b = z - e * m.sw;
     const int phase = m.row_index[a] * m.nb + m.col_index[b];
-    dw[it] = dwp[((((long long)k * m.nphases + phase) * C + c) * m.Ri + (d + m.center)) * m.Si + (e + m.center)];
+    dw[it] = dwp[((((long long)k * m.nphases + phase) * C + c) * m.Ri + (d + m.center_r)) * m.Si + (e + m.center_c)];
 }
 
 unsigned blocks_for(long long items) { return (unsigned)((items + 255) / 256); }

@@ -120,8 +120,10 @@ struct PhasePlan {
 
 int floor_div(int a, int b) { return (a >= 0 ? a : a - b + 1) / b; }
 
-// *extra: 1 if the planes need one row more than the output has (an offset +1 tap whose plane row
-// `out` lies inside the input: convolutions without padding), else 0.
+// The taps of one axis as plane offsets d (r - pad = d * stride + a): which residues a occur, the range
+// of d, and how many plane rows beyond the output's hold input that a tap with d > 0 reads (*extra:
+// convolutions without padding; the rest of such rows lies outside the image and reads as zero).
+// Supported: d within -1 .. 1, or within 0 .. 2.
 bool phase_axis(int R, int stride, int pad, int in, int out, int *phases, int *index, int *count, int *dmin, int *dmax,
                 int *extra)
 {
@@ -130,20 +132,21 @@ bool phase_axis(int R, int stride, int pad, int in, int out, int *phases, int *i
     *count = 0;
     *dmin = 1 << 20;
     *dmax = -(1 << 20);
-    bool has_plus[8] = {false, false, false, false, false, false, false, false};
+    int top[8] = {0, 0, 0, 0, 0, 0, 0, 0};   // largest d of each residue
     for (int r = 0; r < R; ++r) {
         const int u = r - pad, d = floor_div(u, stride), a = u - d * stride;
         if (index[a] < 0) index[a] = 0;
         *dmin = std::min(*dmin, d);
         *dmax = std::max(*dmax, d);
-        if (d == 1) has_plus[a] = true;
+        top[a] = std::max(top[a], d);
     }
     for (int a = 0; a < stride; ++a)
         if (index[a] == 0) { index[a] = *count; phases[(*count)++] = a; }
-    if (*dmin < -1 || *dmax > 1) return false;
+    if (*dmin < -1 || *dmax > 2 || *dmax - *dmin > 2) return false;
     *extra = 0;
     for (int a = 0; a < stride; ++a)
-        if (has_plus[a] && out * stride + a < in) *extra = 1;
+        for (int d = 1; d <= top[a]; ++d)
+            if ((out - 1 + d) * stride + a < in) *extra = std::max(*extra, d);
     return true;
 }
 
@@ -158,11 +161,14 @@ bool phase_plan(const ConvGeom &g, sn_conv_dir dir, PhasePlan *pp)
     if (!phase_axis(g.S, g.sw, g.pw, g.W, g.Q, m.col_phase, m.col_index, &m.nb, &emin, &emax, &xc)) return false;
     // planes larger than the output: the inner convolution is no longer a "same" one, which the
     // backward-filter kernels are built for
-    if ((xr || xc) && dir == SN_CONV_BWD_FILTER) return false;
+    if ((xr || xc || dmax > 1 || emax > 1) && dir == SN_CONV_BWD_FILTER) return false;
     m.nphases = m.na * m.nb;
     const bool one_tap = dmin == 0 && dmax == 0 && emin == 0 && emax == 0;
     m.Ri = m.Si = one_tap ? 1 : 3;
-    m.center = one_tap ? 0 : 1;
+    // offsets -1 .. 1: "same" padding; 0 .. 2: no padding (an axis with the one offset 0 goes either way)
+    m.center_r = one_tap ? 0 : (dmax > 1 ? 0 : 1);
+    m.center_c = one_tap ? 0 : (emax > 1 ? 0 : 1);
+    if ((dmax > 1 && dmin < 0) || (emax > 1 && emin < 0)) return false;
     m.Hs = g.P + xr;
     m.Ws = g.Q + xc;
     if ((long long)g.C * m.nphases > 0x7fffffffLL / 16) return false;
@@ -172,7 +178,8 @@ bool phase_plan(const ConvGeom &g, sn_conv_dir dir, PhasePlan *pp)
     u.H = m.Hs; u.W = m.Ws;
     u.R = m.Ri; u.S = m.Si;
     u.sh = u.sw = 1;
-    u.ph = u.pw = m.center;
+    u.ph = m.center_r;
+    u.pw = m.center_c;
     pp->plain = m.nphases == 1 && g.R == 1 && g.S == 1;
     pp->chunkable = ((long long)g.K * g.P * g.Q) % 8 == 0 && ((long long)g.C * g.H * g.W) % 8 == 0;
     if (dir == SN_CONV_BWD_FILTER ? !tile_wgrad_supported(u) : !tile_conv_supported(u, dir == SN_CONV_BWD_DATA)) return false;

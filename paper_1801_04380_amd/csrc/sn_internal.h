@@ -89,12 +89,13 @@ hipError_t launch_col2im(const float *dcol, void *dx, const ConvGeom &g, int n0,
 // columns occur as phases, and the geometry of the phase planes.  row_phase[i] = residue of the
 // i-th row phase (na of them), row_index[a] = its number or -1; columns likewise (nb);
 // nphases = na * nb, phase number = row number * nb + column number.  The inner filter is
-// Ri x Si (1x1, or 3x3 with tap (d, e) at [d + center][e + center]); planes are Hs x Ws.
+// Ri x Si (1x1, or 3x3 with tap (d, e) at [d + center_r][e + center_c], the inner padding being the
+// centres: 1 where the offsets are within -1 .. 1, 0 where they are 0 .. 2); planes are Hs x Ws.
 struct PhaseMap {
     int sh, sw, ph, pw;
     int na, nb, nphases;
     int row_phase[8], col_phase[8], row_index[8], col_index[8];
-    int Ri, Si, center;
+    int Ri, Si, center_r, center_c;
     int Hs, Ws;
 };
 hipError_t launch_phase_split(const void *x, void *xs, const PhaseMap &m, const ConvGeom &g, hipStream_t st);
