@@ -100,7 +100,8 @@ ConvGeom gemm_geom_1x1(const ConvGeom &g, int nimg)
 // STAGED backward-filter: fp32 partial dw per slice of the (n,p,q) sum.
 size_t staged_bwd_filter_bytes(const ConvGeom &g, int *splits_out)
 {
-    int splits = tile_wgrad_supported(g) ? tile_wgrad_slices(g) : generic_bwd_filter_splits(g);
+    int splits = smallc_supported(g) ? smallc_wgrad_slices(g)
+               : tile_wgrad_supported(g) ? tile_wgrad_slices(g) : generic_bwd_filter_splits(g);
     if (splits_out) *splits_out = splits;
     return align_up((size_t)splits * g.K * g.C * g.R * g.S * sizeof(float), WS_ALIGN);
 }
@@ -244,6 +245,10 @@ sn_status query(const ConvGeom &g, sn_conv_dir dir, sn_conv_algo algo, size_t *m
         return SN_OK;
     case SN_ALGO_STAGED: {
         PhasePlan pp;
+        if (dir == SN_CONV_BWD_FILTER && smallc_supported(g)) {
+            *min_b = *pref_b = staged_bwd_filter_bytes(g, nullptr);
+            return SN_OK;
+        }
         if (phase_plan(g, dir, &pp)) {
             *pref_b = phase_bytes(pp, dir, g.N);
             *min_b = pp.chunkable ? phase_bytes(pp, dir, 1) : *pref_b;
@@ -317,6 +322,14 @@ sn_status plan(const sn_conv_shape *shape, const ConvGeom &g, sn_conv_dir dir, s
     // input pixel although only 1 in stride_h * stride_w meets an output; the explicit algorithm does
     // not, and is the better guess where it fits.
     const bool explicit_first = dir == SN_CONV_BWD_DATA && (g.sh > 1 || g.sw > 1);
+    // Few input channels: the zero-workspace kernel is the memory-bound one (forward); backward-filter
+    // runs it under either name, STAGED with a fixed summation order.
+    if (dir == SN_CONV_FWD && smallc_supported(g)) {
+        *algo = SN_ALGO_DIRECT;
+        *bytes = 0;
+        if (ms_out) *ms_out = -1.f;
+        return SN_OK;
+    }
     for (sn_conv_algo a : kRanking) {
         size_t mn = 0, pf = 0;
         if (a == SN_ALGO_DIRECT && explicit_first && query(g, dir, SN_ALGO_IM2COL_GEMM, &mn, &pf) == SN_OK && mn <= budget) {
@@ -386,6 +399,7 @@ size_t out_elem(const ConvGeom &g) { return g.out_bf16 ? 2 : 4; }
 // the general kernel otherwise.
 hipError_t direct_fwd(const void *x, const void *w, void *y, const ConvGeom &g, hipStream_t st)
 {
+    if (smallc_supported(g)) return launch_smallc_fwd(x, w, y, g, st, nullptr);
     if (tile_conv_supported(g, false)) return launch_tile_conv(x, w, y, g, false, nullptr, st);
     return launch_generic_fwd(x, w, y, g, st);
 }
@@ -479,6 +493,8 @@ sn_status run_bwd_filter(const void *x, const void *dy, void *dw, const ConvGeom
 {
     float *dwf = static_cast<float *>(dw);
     const bool tile = tile_wgrad_supported(g);
+    if (smallc_supported(g) && (algo == SN_ALGO_DIRECT || algo == SN_ALGO_STAGED))
+        return launch_status(launch_smallc_wgrad(x, dy, dwf, g, algo == SN_ALGO_STAGED ? static_cast<float *>(ws) : nullptr, st));
     if (algo == SN_ALGO_DIRECT) {
         if (tile) return launch_status(launch_tile_wgrad(x, dy, dwf, g, nullptr, st));
         return launch_status(launch_generic_bwd_filter(x, dy, dwf, g, generic_bwd_filter_splits(g), nullptr, false, st));
@@ -667,6 +683,7 @@ sn_status sn_conv2d_fwd_noalloc(const void *x, const void *w, void *y, const sn_
 static size_t conv_bn_stats_need(const ConvGeom &g)
 {
     size_t need = bn_stats_scratch_bytes(g.N, g.K, g.P * g.Q);
+    need = std::max(need, (size_t)smallc_fwd_stats_tiles(g) * g.K * 3 * sizeof(float));
     for (int v = 0; v < 4; ++v) {
         const size_t t = (size_t)tile_conv_stats_tiles(g, (v & 1) != 0, (v & 2) != 0);
         need = std::max(need, t * g.K * 3 * sizeof(float));
@@ -701,6 +718,11 @@ sn_status sn_conv2d_fwd_bn_stats(const void *x, const void *w, void *y, const sn
     hipStream_t st = static_cast<hipStream_t>(stream);
     float *part = static_cast<float *>(scratch);
     const bool staged = algo == SN_ALGO_STAGED;
+    if (algo == SN_ALGO_DIRECT && smallc_supported(g)) {
+        // the few-channel kernel leaves one triple per wave and channel
+        if (launch_smallc_fwd(x, w, y, g, st, part) != hipSuccess) return SN_ERR_LAUNCH;
+        return launch_status(launch_bn_finalize_tiles(part, g.K, smallc_fwd_stats_tiles(g), save_mean, save_invstd, eps, st));
+    }
     if (tile_conv_supported(g, false) && (staged || algo == SN_ALGO_DIRECT)) {
         // the tile kernels take the statistics from their accumulators: y is not read again
         const int tiles = tile_conv_stats_tiles(g, staged, true);

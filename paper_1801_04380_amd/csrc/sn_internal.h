@@ -74,6 +74,17 @@ int rows_wgrad_slices(const ConvGeom &g);
 hipError_t launch_rows_wgrad(const void *x, const void *dy, float *dw, const ConvGeom &g, float *partial,
                              hipStream_t st);
 
+// Few input channels (C*R*S <= 32, bf16 operands, any stride and padding; conv_smallc.hip): forward
+// without workspace, optionally leaving smallc_fwd_stats_tiles(g) * K (count, mean, M2) triples in
+// `stats` for launch_bn_finalize_tiles; backward-filter with the contract of launch_rows_wgrad
+// (smallc_wgrad_slices slices).
+bool smallc_supported(const ConvGeom &g);
+int smallc_fwd_stats_tiles(const ConvGeom &g);
+hipError_t launch_smallc_fwd(const void *x, const void *w, void *y, const ConvGeom &g, hipStream_t st, float *stats);
+int smallc_wgrad_slices(const ConvGeom &g);
+hipError_t launch_smallc_wgrad(const void *x, const void *dy, float *dw, const ConvGeom &g, float *partial,
+                               hipStream_t st);
+
 hipError_t launch_fill_zero(float *p, size_t n, hipStream_t st);
 // dw[i] = (accumulate ? dw[i] : 0) + sum_z partial[z][i], z ascending.
 hipError_t launch_reduce_partials(const float *partial, float *dw, size_t n, int splits, bool accumulate,

@@ -98,6 +98,16 @@ CASES = [
     (L("s21_3x3", 32, 16, 12, 64, 3, 3, (2, 1), (1, 1)), 2),
     (L("s12_1x3", 32, 9, 20, 48, 1, 3, (1, 2), (0, 1)), 2),
     (L("s2_1x1_big", 256, 56, 56, 128, 1, 1, (2, 2)), 2),
+    # few input channels (C*R*S <= 32: one MFMA operand holds the whole reduction): rows longer than one
+    # 64-pixel unit with a ragged end, more than 64 output channels, stride 2 without padding on an odd
+    # image, one channel under a 5x5 filter, two channels under a 4x4 filter with a large padding, a
+    # 1x1 filter over 32 channels on rows shorter than a unit, strides that differ per axis
+    (L("few_c3_w150", 3, 9, 150, 70, 3, 3, (1, 1), (1, 1), relu_in=False), 2),
+    (L("few_c3_s2_valid", 3, 37, 41, 32, 3, 3, (2, 2), (0, 0), relu_in=False), 3),
+    (L("few_c1_5x5", 1, 20, 75, 130, 5, 5, (1, 1), (2, 2), relu_in=False), 2),
+    (L("few_c2_4x4_pad3", 2, 11, 13, 24, 4, 4, (1, 1), (3, 3), relu_in=False), 2),
+    (L("few_c32_1x1", 32, 7, 9, 40, 1, 1), 5),
+    (L("few_c3_s12", 3, 12, 90, 64, 3, 3, (1, 2), (1, 0), relu_in=False), 2),
 ]
 IDS = [c[0].name for c in CASES]
 

@@ -28,6 +28,8 @@ CASES = [
     (L("k64", 48, 20, 36, 64, 3, 3, (1, 1), (1, 1)), 3),
     (L("k48_w72", 104, 12, 72, 48, 3, 3, (1, 1), (1, 1)), 3),
     (L("first3", 3, 40, 40, 64, 3, 3, (1, 1), (1, 1), relu_in=False), 2),
+    (L("few_c3_w150", 3, 9, 150, 70, 3, 3, (1, 1), (1, 1), relu_in=False), 2),
+    (L("few_c3_s2_valid", 3, 37, 41, 32, 3, 3, (2, 2), (0, 0), relu_in=False), 3),
     (L("ragged3x3", 19, 37, 29, 70, 3, 3, (1, 1), (1, 1)), 3),
     (L("1x1", 96, 14, 14, 160, 1, 1), 3),
     (L("5x5", 24, 27, 27, 32, 5, 5, (1, 1), (2, 2)), 2),
