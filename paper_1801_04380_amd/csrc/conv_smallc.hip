@@ -39,6 +39,7 @@ constexpr int KT = 64;           // output channels per pass (blockIdx.y)
 constexpr int UPX = 64;          // pixels per unit
 constexpr int RED = 32;          // the padded reduction length
 constexpr int STG_PITCH = 144;   // bytes per channel row of the staged block: 64 px, and 16 so that rows spread over the banks
+constexpr int STG_ROWS = 32;     // channel rows of the staged block (forward stores 32 channels at a time)
 constexpr int WAVES = 4;
 
 struct SmallProblem {
@@ -96,10 +97,9 @@ __device__ inline Moments3 join(const Moments3 &a, const Moments3 &b)   // exact
 struct UnitWalk {
     const SmallProblem &p;
     int lane;
-    char *patch;
     int n, pr, cb;    // the unit being staged (uniform)
 
-    __device__ UnitWalk(const SmallProblem &pp, int lane_, char *patch_) : p(pp), lane(lane_), patch(patch_) { n = pr = cb = 0; }
+    __device__ UnitWalk(const SmallProblem &pp, int lane_) : p(pp), lane(lane_) { n = pr = cb = 0; }
     __device__ void set_unit(int u)
     {
         const int per_img = p.P * p.ncb;
@@ -116,7 +116,7 @@ struct UnitWalk {
         if (cb >= p.ncb) { cb -= p.ncb; ++pr; }
         if (pr >= p.P) { pr -= p.P; ++n; }
     }
-    __device__ void patch_fetch(const __amdgpu_buffer_rsrc_t &xr) const
+    __device__ void patch_fetch(const __amdgpu_buffer_rsrc_t &xr, char *__restrict__ patch) const
     {
         constexpr uint32_t OUTSIDE = 0x80000000u;
         const int h0 = pr * p.sh - p.ph, w0 = cb * UPX * p.sw - p.pw - p.shiftc;
@@ -146,17 +146,20 @@ struct UnitWalk {
 __device__ inline uint32_t lds_u16(const char *p) { return *reinterpret_cast<const bf16_t *>(p); }
 
 // ---- forward ---------------------------------------------------------------------------------
-template <bool OUT_BF16, bool STATS>
-__global__ void __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(3, 3)))
-smallc_fwd_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w, void *__restrict__ y, SmallProblem p)
+// pb0, pb1: the wave's two patch buffers (the patch of unit u + 1 lands while unit u is stored); stage: its
+// staging block.  The three are distinct, which the qualifiers tell the compiler: a read of one then does
+// not wait for a load into another.  Q8: the row length is a multiple of 8 pixels, so the 8-pixel pieces a
+// lane stores are inside a row or outside it as a whole and the stores of a unit are always the same eight
+// instructions (predicated per lane), which lets the wave leave them in flight while it goes on.
+template <bool OUT_BF16, bool STATS, bool Q8>
+__device__ __forceinline__ void smallc_fwd_body(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w, void *__restrict__ y,
+                                                const SmallProblem &p, char *__restrict__ pb0, char *__restrict__ pb1,
+                                                char *__restrict__ stage, int wave)
 {
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
     const int l32 = lane & 31, g = lane >> 5;
     const int k0 = blockIdx.y * KT;
-    char *const mine = smem + wave * (p.patch_bytes + KT * STG_PITCH);
-    char *const stage = mine + p.patch_bytes;
-    UnitWalk uw(p, lane, mine);
+    UnitWalk uw(p, lane);
     const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(x), 0, p.x_bytes, 0x00020000);
 
     // the filter operand: channel k0 + 32 i + l32, entries 16 b + 8 g .. + 7 (zeros past the last entry or channel)
@@ -177,9 +180,9 @@ smallc_fwd_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w, vo
             __builtin_memcpy(&wreg[i][b], d, 16);
         }
     // where the lane's pixel (l32 of the first 32; the second 32 are 32 sw columns on) finds its
-    // reduction entries 16 b + 8 g + e in the patch; past the last entry any tap will do: the filter
+    // reduction entries 16 b + 8 g + e in a patch; past the last entry any tap will do: the filter
     // operand is zero there
-    const char *ga[2][8];
+    int ga[2][8];
 #pragma unroll
     for (int b = 0; b < 2; ++b)
 #pragma unroll
@@ -190,7 +193,7 @@ smallc_fwd_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w, vo
                 const int c = j / p.RS, rem = j - c * p.RS, r = rem / p.S, s = rem - r * p.S;
                 off = (c * p.R + r) * p.ppitch + s;
             }
-            ga[b][e] = mine + (off + p.shiftc + l32 * p.sw) * 2;
+            ga[b][e] = (off + p.shiftc + l32 * p.sw) * 2;
         }
     const int fstep = 32 * p.sw * 2;
     // the lane's share of the staged block on its way out: channel rows it * 8 + lane / 8, octet lane % 8
@@ -203,14 +206,15 @@ smallc_fwd_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w, vo
     const int gw = blockIdx.x * WAVES + wave;   // this wave's number among those of the channel pass
     float cnt = 0.f, s1[2] = {0.f, 0.f}, s2[2] = {0.f, 0.f}, shift[2] = {0.f, 0.f};
     const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    // The patch is not fetched ahead: x is small and stays in L2, and the other waves of the compute
-    // unit (three per SIMD) cover the wait.
-    if (gw < p.nunits) uw.set_unit(gw);
-    for (int u = gw; u < p.nunits; u += p.nwaves, uw.advance()) {
+
+    auto unit = [&](const char *__restrict__ pcur, char *__restrict__ pnext, bool more) {
         const int n = uw.n, pr = uw.pr, q0 = uw.cb * UPX;
-        uw.patch_fetch(xr);
-        __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): the patch has landed (and the last unit's stores are done)
+        // The loads that fill this unit's patch were sent before the last unit's stores; the compiler does not
+        // count loads into LDS by itself, so wait here for everything this wave has sent.
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0)
         __builtin_amdgcn_wave_barrier();
+        asm volatile("" ::: "memory");
         f32x16 acc[2][2];   // [pixel group f][channel tile i]
 #pragma unroll
         for (int f = 0; f < 2; ++f) {
@@ -219,7 +223,7 @@ smallc_fwd_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w, vo
                 uint32_t d[4];
 #pragma unroll
                 for (int e = 0; e < 8; e += 2)
-                    d[e >> 1] = lds_u16(ga[b][e] + f * fstep) | (lds_u16(ga[b][e + 1] + f * fstep) << 16);
+                    d[e >> 1] = lds_u16(pcur + ga[b][e] + f * fstep) | (lds_u16(pcur + ga[b][e + 1] + f * fstep) << 16);
                 bf16x8 a;
                 __builtin_memcpy(&a, d, 16);
 #pragma unroll
@@ -227,14 +231,21 @@ smallc_fwd_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w, vo
                     acc[f][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, wreg[i][b], b == 0 ? zero : acc[f][i], 0, 0, 0);
             }
         }
+        // the next unit's patch is on its way while this one is rounded, staged and stored
+        if (more) {
+            uw.advance();
+            uw.patch_fetch(xr, pnext);
+        }
         // acc[f][i][v]: channel k0 + 32 i + l32, pixel q0 + 32 f + 8 (v / 4) + 4 g + v % 4.  One pass over the
         // accumulators, four pixels at a time: rounded (bf16 output), into the statistics, into the staged
-        // block (bf16) or to memory (fp32).
+        // block (bf16), from where a lane stores 8 consecutive pixels of a channel, or to memory (fp32).
         const bool whole = q0 + UPX <= p.Q && k0 + KT <= p.K;   // no pixel and no channel of the block is past the end
         const bool first = cnt == 0.f;
         float add = 0.f;
+        // rows of the block: 128 bytes of one channel each; a lane moves 16 of them
+        char *const ub = reinterpret_cast<char *>(y) + (uint32_t)(((n * p.K + k0) * p.P + pr) * p.Q + q0) * 2u;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < 2; ++i) {   // 32 channels at a time through the staging block
             const int k = k0 + 32 * i + l32;
             if (STATS && first) shift[i] = OUT_BF16 ? __uint_as_float(pack2(acc[0][i][0], 0.f) << 16) : acc[0][i][0];
 #pragma unroll
@@ -247,7 +258,7 @@ smallc_fwd_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w, vo
                         uint2 pk;
                         pk.x = pack2(v[0], v[1]);
                         pk.y = pack2(v[2], v[3]);
-                        *reinterpret_cast<uint2 *>(swrite + 32 * i * STG_PITCH + (32 * f + 8 * jv) * 2) = pk;
+                        *reinterpret_cast<uint2 *>(swrite + (32 * f + 8 * jv) * 2) = pk;
                         if (STATS) {
                             v[0] = __uint_as_float(pk.x << 16);
                             v[1] = __uint_as_float(pk.x & 0xffff0000u);
@@ -280,36 +291,49 @@ smallc_fwd_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w, vo
                         }
                     }
                 }
-        }
-        cnt += whole ? 32.f : add;
-        if (OUT_BF16) {
-            __builtin_amdgcn_wave_barrier();
-            // rows of the block: 128 bytes of one channel each; a lane moves 16 of them
-            char *const ub = reinterpret_cast<char *>(y) + (uint32_t)(((n * p.K + k0) * p.P + pr) * p.Q + q0) * 2u;
-            if (whole) {
-#pragma unroll
-                for (int it = 0; it < 8; ++it) {
-                    const u32x4 v = *reinterpret_cast<const u32x4 *>(sread + it * 8 * STG_PITCH);
-                    store8_any(ub + (size_t)(it * 8) * PQ2 + lane_y, v);
-                }
-            } else {
+            if (OUT_BF16) {
+                __builtin_amdgcn_wave_barrier();
                 const int q = q0 + oct * 8;
+                if (whole) {
 #pragma unroll
-                for (int it = 0; it < 8; ++it) {
-                    const u32x4 v = *reinterpret_cast<const u32x4 *>(sread + it * 8 * STG_PITCH);
-                    if (k0 + it * 8 + krow0 >= p.K || q >= p.Q) continue;
-                    bf16_t *dst = reinterpret_cast<bf16_t *>(ub + (size_t)(it * 8) * PQ2 + lane_y);
-                    if (q + 8 <= p.Q) {
-                        store8_any(dst, v);
-                    } else {
+                    for (int it = 0; it < 4; ++it) {
+                        const u32x4 v = *reinterpret_cast<const u32x4 *>(sread + it * 8 * STG_PITCH);
+                        store8_any(ub + (size_t)(32 * i + it * 8) * PQ2 + lane_y, v);
+                    }
+                } else {
 #pragma unroll
-                        for (int e = 0; e < 8; ++e)
-                            if (q + e < p.Q) dst[e] = (bf16_t)(v[e >> 1] >> (16 * (e & 1)));
+                    for (int it = 0; it < 4; ++it) {
+                        const u32x4 v = *reinterpret_cast<const u32x4 *>(sread + it * 8 * STG_PITCH);
+                        char *const dst = ub + (size_t)(32 * i + it * 8) * PQ2 + lane_y;
+                        const bool kok = k0 + 32 * i + it * 8 + krow0 < p.K;
+                        if (Q8) {
+                            if (kok && q < p.Q) store8_any(dst, v);
+                        } else if (kok && q < p.Q) {
+                            if (q + 8 <= p.Q) {
+                                store8_any(dst, v);
+                            } else {
+                                bf16_t *const d16 = reinterpret_cast<bf16_t *>(dst);
+#pragma unroll
+                                for (int e = 0; e < 8; ++e)
+                                    if (q + e < p.Q) d16[e] = (bf16_t)(v[e >> 1] >> (16 * (e & 1)));
+                            }
+                        }
                     }
                 }
+                __builtin_amdgcn_wave_barrier();
             }
-            __builtin_amdgcn_wave_barrier();
         }
+        cnt += whole ? 32.f : add;
+    };
+
+    if (gw < p.nunits) {
+        uw.set_unit(gw);
+        uw.patch_fetch(xr, pb0);
+    }
+    // two units per trip, so that which buffer is read and which is loaded is fixed in the code
+    for (int u = gw; u < p.nunits; u += 2 * p.nwaves) {
+        unit(pb0, pb1, u + p.nwaves < p.nunits);
+        if (u + p.nwaves < p.nunits) unit(pb1, pb0, u + 2 * p.nwaves < p.nunits);
     }
     if (STATS) {
 #pragma unroll
@@ -332,24 +356,36 @@ smallc_fwd_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w, vo
     }
 }
 
+template <bool OUT_BF16, bool STATS, bool Q8>
+__global__ void __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(4, 4)))
+smallc_fwd_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w, void *__restrict__ y, SmallProblem p)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    char *const mine = smem + wave * (2 * p.patch_bytes + STG_ROWS * STG_PITCH);
+    smallc_fwd_body<OUT_BF16, STATS, Q8>(x, w, y, p, mine, mine + p.patch_bytes, mine + 2 * p.patch_bytes, wave);
+}
+
 // ---- backward-filter ----------------------------------------------------------------------------
 // out: partial sums, slice blockIdx.x at out + blockIdx.x * K * CRS (use_atomics == 0), or dw itself,
 // zero-filled, which every workgroup adds into (use_atomics != 0).
-__global__ void __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(3, 3)))
-smallc_wgrad_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, float *__restrict__ out, int use_atomics,
-                    SmallProblem p)
+// The dy operand needs no staging: in NCHW a lane's 8 pixels of one channel are 16 contiguous bytes,
+// loaded straight into the register the MFMA reads (a wave's load touches 32 channel planes, 32
+// bytes of each; the four steps of a unit use up the 128-byte lines).  Unit u + 1 is loaded while unit
+// u is multiplied.
+template <bool Q8>
+__device__ __forceinline__ void smallc_wgrad_body(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy,
+                                                  float *__restrict__ out, int use_atomics, const SmallProblem &p,
+                                                  char *__restrict__ pb0, char *__restrict__ pb1, float *__restrict__ red, int wave)
 {
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
     const int l32 = lane & 31, g = lane >> 5;
     const int k0 = blockIdx.y * KT;
-    char *const mine = smem + wave * (p.patch_bytes + KT * STG_PITCH);
-    char *const stage = mine + p.patch_bytes;
-    UnitWalk uw(p, lane, mine);
+    UnitWalk uw(p, lane);
     const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(x), 0, p.x_bytes, 0x00020000);
     // the lane's reduction entry as an operand column: entry l32, pixels 8 g .. 8 g + 7 of a 16-pixel step
     // (entries past the last read any tap: their columns of the result are never written)
-    const char *xa[8];
+    int xa[8];
     {
         int off = 0;
         if (l32 < p.CRS) {
@@ -357,43 +393,40 @@ smallc_wgrad_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy,
             off = (c * p.R + r) * p.ppitch + s;
         }
 #pragma unroll
-        for (int e = 0; e < 8; ++e) xa[e] = mine + (off + p.shiftc + (8 * g + e) * p.sw) * 2;
+        for (int e = 0; e < 8; ++e) xa[e] = (off + p.shiftc + (8 * g + e) * p.sw) * 2;
     }
     const int ststep = 16 * p.sw * 2;
-
-    // dy block of a unit: channel rows it * 8 + lane / 8, the octet lane % 8 of the 64 pixels
-    const int oct = lane & 7, krow0 = lane >> 3;
+    // dy operand of channel tile i, step st: channel k0 + 32 i + l32, pixels q0 + 16 st + 8 g .. + 7
     const uint32_t PQ2 = (uint32_t)(p.P * p.Q) * 2u;
-    const uint32_t lane_y = (uint32_t)krow0 * PQ2 + (uint32_t)oct * 16u;
+    const uint32_t lane_y = (uint32_t)l32 * PQ2 + (uint32_t)g * 16u;
+    const bool kok[2] = {k0 + l32 < p.K, k0 + 32 + l32 < p.K};
     auto dy_load = [&](u32x4 (&reg)[8]) {
         const int q0 = uw.cb * UPX;
         const char *const ub = reinterpret_cast<const char *>(dy) + (uint32_t)(((uw.n * p.K + k0) * p.P + uw.pr) * p.Q + q0) * 2u;
-        if (q0 + UPX <= p.Q && k0 + KT <= p.K) {
 #pragma unroll
-            for (int it = 0; it < 8; ++it) reg[it] = load8_any(ub + (size_t)(it * 8) * PQ2 + lane_y);
-        } else {
-            const int q = q0 + oct * 8;
+        for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int it = 0; it < 8; ++it) {
+            for (int st = 0; st < 4; ++st) {
+                const int q = q0 + 16 * st + 8 * g;
+                const char *const src = ub + (size_t)(32 * i) * PQ2 + 32 * st + lane_y;
                 u32x4 v = {0, 0, 0, 0};
-                if (k0 + it * 8 + krow0 < p.K && q < p.Q) {
-                    const bf16_t *src = reinterpret_cast<const bf16_t *>(ub + (size_t)(it * 8) * PQ2 + lane_y);
+                if (Q8) {
+                    if (kok[i] && q < p.Q) v = load8_any(src);
+                } else if (kok[i] && q < p.Q) {
                     if (q + 8 <= p.Q) {
                         v = load8_any(src);
                     } else {
+                        const bf16_t *const s16 = reinterpret_cast<const bf16_t *>(src);
                         uint32_t d[4] = {0, 0, 0, 0};
 #pragma unroll
                         for (int e = 0; e < 8; ++e)
-                            if (q + e < p.Q) d[e >> 1] |= (uint32_t)src[e] << (16 * (e & 1));
+                            if (q + e < p.Q) d[e >> 1] |= (uint32_t)s16[e] << (16 * (e & 1));
                         v = u32x4{d[0], d[1], d[2], d[3]};
                     }
                 }
-                reg[it] = v;
+                reg[i * 4 + st] = v;
             }
-        }
     };
-    char *const swrite = stage + krow0 * STG_PITCH + oct * 16;
-    const char *const sread = stage + l32 * STG_PITCH + 16 * g;
 
     f32x16 acc[2];   // [channel tile i]: rows k, columns = reduction entries
 #pragma unroll
@@ -402,43 +435,50 @@ smallc_wgrad_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy,
         for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
 
     const int gw = blockIdx.x * WAVES + wave;
-    u32x4 yreg[8];
-    if (gw < p.nunits) {
-        uw.set_unit(gw);
-        dy_load(yreg);
-    }
-    for (int u = gw; u < p.nunits; u += p.nwaves) {
-        uw.patch_fetch(xr);
-#pragma unroll
-        for (int it = 0; it < 8; ++it) *reinterpret_cast<u32x4 *>(swrite + it * 8 * STG_PITCH) = yreg[it];
-        if (u + p.nwaves < p.nunits) {
-            uw.advance();
-            dy_load(yreg);   // the next unit's dy flies while this unit waits for its patch and during its MFMAs
-        }
-        // The reads of the patch below wait for the loads that write it (the compiler counts loads into
-        // LDS as it counts loads into registers) and leave the dy loads issued after them in flight.
+    u32x4 yreg[2][8];
+    // unit u: its patch is in pcur, its dy in ycur, both sent a unit ago
+    auto unit = [&](const char *__restrict__ pcur, char *__restrict__ pnext, const u32x4 (&ycur)[8], u32x4 (&ynext)[8], bool more) {
+        // Wait for them (everything this wave has in flight; the compiler does not count loads into LDS by
+        // itself), then send the next unit's before the MFMAs: a wave always has a unit on its way.
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0)
         __builtin_amdgcn_wave_barrier();
+        asm volatile("" ::: "memory");
+        if (more) {
+            uw.advance();
+            uw.patch_fetch(xr, pnext);
+            dy_load(ynext);
+        }
 #pragma unroll
         for (int st = 0; st < 4; ++st) {   // 16 pixels per step
             uint32_t d[4];
 #pragma unroll
             for (int e = 0; e < 8; e += 2)
-                d[e >> 1] = lds_u16(xa[e] + st * ststep) | (lds_u16(xa[e + 1] + st * ststep) << 16);
+                d[e >> 1] = lds_u16(pcur + xa[e] + st * ststep) | (lds_u16(pcur + xa[e + 1] + st * ststep) << 16);
             bf16x8 b;
             __builtin_memcpy(&b, d, 16);
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                const bf16x8 a = *reinterpret_cast<const bf16x8 *>(sread + 32 * i * STG_PITCH + 32 * st);
+                bf16x8 a;
+                __builtin_memcpy(&a, &ycur[i * 4 + st], 16);
                 acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
             }
         }
-        __builtin_amdgcn_wave_barrier();
+    };
+    if (gw < p.nunits) {
+        uw.set_unit(gw);
+        uw.patch_fetch(xr, pb0);
+        dy_load(yreg[0]);
+    }
+    // two units per trip, so that which registers and which buffer a unit uses is fixed in the code
+    for (int u = gw; u < p.nunits; u += 2 * p.nwaves) {
+        unit(pb0, pb1, yreg[0], yreg[1], u + p.nwaves < p.nunits);
+        if (u + p.nwaves < p.nunits) unit(pb1, pb0, yreg[1], yreg[0], u + 2 * p.nwaves < p.nunits);
     }
 
     // The workgroup's four waves add up through LDS (fixed order), then the slice is written.
     // acc[i][v]: column (entry) l32, row k0 + 32 i + 8 (v / 4) + 4 g + v % 4.
-    __syncthreads();
-    float *const red = reinterpret_cast<float *>(smem);   // [wave][k 64][33]
+    __syncthreads();   // every wave is done with its patches: red takes their place
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -458,9 +498,21 @@ smallc_wgrad_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy,
     }
 }
 
-int workgroups_per_cu(size_t lds) { return (int)std::min<size_t>(4, (160 * 1024) / lds); }
+template <bool Q8>
+__global__ void __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(4, 4)))
+smallc_wgrad_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, float *__restrict__ out, int use_atomics,
+                    SmallProblem p)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    char *const mine = smem + wave * 2 * p.patch_bytes;
+    smallc_wgrad_body<Q8>(x, dy, out, use_atomics, p, mine, mine + p.patch_bytes, reinterpret_cast<float *>(smem), wave);
+}
 
-bool make_problem(const ConvGeom &g, SmallProblem *p, dim3 *grid, size_t *lds)
+// resident workgroups per compute unit: the kernels are built for four waves per SIMD
+int workgroups_per_cu(size_t lds, bool) { return (int)std::min<size_t>(4, (160 * 1024) / lds); }
+
+bool make_problem(const ConvGeom &g, bool wgrad, SmallProblem *p, dim3 *grid, size_t *lds)
 {
     if (!g.in_bf16) return false;
     const long long crs = (long long)g.C * g.R * g.S;
@@ -489,13 +541,14 @@ bool make_problem(const ConvGeom &g, SmallProblem *p, dim3 *grid, size_t *lds)
     p->out_bf16 = g.out_bf16;
     p->x_bytes = (int)((long long)g.N * g.C * g.H * g.W * 2);
     p->stats = nullptr;
-    const size_t per_wave = (size_t)p->patch_bytes + KT * STG_PITCH;
-    *lds = std::max(per_wave * WAVES, (size_t)WAVES * KT * 33 * sizeof(float));
+    // per wave: two patch buffers, and forward's staging block; backward-filter's final sums reuse the space
+    const size_t per_wave = 2 * (size_t)p->patch_bytes + (wgrad ? 0 : STG_ROWS * STG_PITCH);
+    *lds = wgrad ? std::max(per_wave * WAVES, (size_t)WAVES * KT * 33 * sizeof(float)) : per_wave * WAVES;
     if (*lds > 160 * 1024) return false;
     const int ktiles = (g.K + KT - 1) / KT;
     if (ktiles > 65535) return false;
     const long long want = (nunits + WAVES - 1) / WAVES;
-    const long long cap = 256LL * workgroups_per_cu(*lds);
+    const long long cap = 256LL * workgroups_per_cu(*lds, wgrad);
     const int gx = (int)std::max(1LL, std::min(want, cap));
     p->nwaves = gx * WAVES;
     const int per_img = g.P * p->ncb;
@@ -519,7 +572,7 @@ bool smallc_supported(const ConvGeom &g)
     SmallProblem p;
     dim3 grid;
     size_t lds;
-    return make_problem(g, &p, &grid, &lds);
+    return make_problem(g, false, &p, &grid, &lds) && make_problem(g, true, &p, &grid, &lds);
 }
 
 int smallc_fwd_stats_tiles(const ConvGeom &g)
@@ -527,7 +580,7 @@ int smallc_fwd_stats_tiles(const ConvGeom &g)
     SmallProblem p;
     dim3 grid;
     size_t lds;
-    return make_problem(g, &p, &grid, &lds) ? p.nwaves : 0;
+    return make_problem(g, false, &p, &grid, &lds) ? p.nwaves : 0;
 }
 
 hipError_t launch_smallc_fwd(const void *x, const void *w, void *y, const ConvGeom &g, hipStream_t st, float *stats)
@@ -535,7 +588,7 @@ hipError_t launch_smallc_fwd(const void *x, const void *w, void *y, const ConvGe
     SmallProblem p;
     dim3 grid;
     size_t lds;
-    if (!make_problem(g, &p, &grid, &lds)) return hipErrorInvalidValue;
+    if (!make_problem(g, false, &p, &grid, &lds)) return hipErrorInvalidValue;
     p.stats = stats;
     const bf16_t *xs = static_cast<const bf16_t *>(x), *wsrc = static_cast<const bf16_t *>(w);
     auto go = [&](auto kern) -> hipError_t {
@@ -544,8 +597,12 @@ hipError_t launch_smallc_fwd(const void *x, const void *w, void *y, const ConvGe
         hipLaunchKernelGGL(kern, grid, dim3(WAVES * 64), lds, st, xs, wsrc, y, p);
         return hipGetLastError();
     };
-    if (g.out_bf16) return stats ? go(smallc_fwd_kernel<true, true>) : go(smallc_fwd_kernel<true, false>);
-    return stats ? go(smallc_fwd_kernel<false, true>) : go(smallc_fwd_kernel<false, false>);
+    const bool q8 = g.Q % 8 == 0;
+    if (g.out_bf16) {
+        if (q8) return stats ? go(smallc_fwd_kernel<true, true, true>) : go(smallc_fwd_kernel<true, false, true>);
+        return stats ? go(smallc_fwd_kernel<true, true, false>) : go(smallc_fwd_kernel<true, false, false>);
+    }
+    return stats ? go(smallc_fwd_kernel<false, true, false>) : go(smallc_fwd_kernel<false, false, false>);
 }
 
 int smallc_wgrad_slices(const ConvGeom &g)
@@ -553,7 +610,7 @@ int smallc_wgrad_slices(const ConvGeom &g)
     SmallProblem p;
     dim3 grid;
     size_t lds;
-    return make_problem(g, &p, &grid, &lds) ? (int)grid.x : 0;
+    return make_problem(g, true, &p, &grid, &lds) ? (int)grid.x : 0;
 }
 
 // partial == nullptr: the workgroups add into a zero-filled dw with atomics; otherwise workgroup z
@@ -563,7 +620,7 @@ hipError_t launch_smallc_wgrad(const void *x, const void *dy, float *dw, const C
     SmallProblem p;
     dim3 grid;
     size_t lds;
-    if (!make_problem(g, &p, &grid, &lds)) return hipErrorInvalidValue;
+    if (!make_problem(g, true, &p, &grid, &lds)) return hipErrorInvalidValue;
     const size_t nw = (size_t)g.K * p.CRS;
     const bool direct_store = !partial && grid.x == 1;
     if (!partial && !direct_store) {
@@ -579,7 +636,7 @@ hipError_t launch_smallc_wgrad(const void *x, const void *dy, float *dw, const C
         hipLaunchKernelGGL(kern, grid, dim3(WAVES * 64), lds, st, xs, ds, out, atomics, p);
         return hipSuccess;
     };
-    hipError_t e0 = go(smallc_wgrad_kernel);
+    hipError_t e0 = g.Q % 8 == 0 ? go(smallc_wgrad_kernel<true>) : go(smallc_wgrad_kernel<false>);
     if (e0 != hipSuccess) return e0;
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
