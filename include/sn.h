@@ -56,6 +56,11 @@ typedef enum { SN_CONV_FWD = 0, SN_CONV_BWD_DATA = 1, SN_CONV_BWD_FILTER = 2 } s
 /* The algorithm menu the planner chooses from (Sec. 3.5: several algorithms,
  * some of which need workspace to reach their speed).
  *  DIRECT       implicit GEMM straight from the NCHW/KCRS tensors; 0 bytes.
+ *               Inputs with very few channels (bf16, C * R * S <= 32, W even: a
+ *               network's first layer) run a kernel of their own here that
+ *               holds the whole reduction in one MFMA operand and is bound by
+ *               writing y (forward) or reading dy (backward-filter, also under
+ *               STAGED, where its workgroups' partial sums are reduced in a fixed order).
  *  IM2COL_GEMM  explicit: unfold patches into a column buffer in the workspace
  *               (as many images per pass as fit), then a GEMM over it; the
  *               backward-data form folds the column gradient back (col2im).
@@ -120,7 +125,7 @@ sn_status sn_conv_workspace_query(const sn_conv_shape *shape, sn_conv_dir dir, s
  * algorithms at run time); a recorded time applies to budgets >= the workspace
  * it was measured with.  With no feasible record the choice falls back to a
  * built-in ranking (WINOGRAD where it applies, C * K >= 8192 and at least 2048 tiles fit a pass, STAGED,
- * then DIRECT; for strided backward-data the explicit algorithm before DIRECT).  Among records within 3 % of the fastest the one with the
+ * then DIRECT; for strided backward-data the explicit algorithm before DIRECT; DIRECT first for forward on few-channel inputs).  Among records within 3 % of the fastest the one with the
  * smallest workspace wins (then the faster).  DIRECT needs 0 bytes, so a plan always exists.  bytes_used = the workspace the choice will use
  * (<= budget_bytes).  predicted_ms may be NULL; it receives the recorded time
  * or a negative value if the choice came from the built-in ranking. */
