@@ -98,6 +98,11 @@ CASES = [
     (L("s21_3x3", 32, 16, 12, 64, 3, 3, (2, 1), (1, 1)), 2),
     (L("s12_1x3", 32, 9, 20, 48, 1, 3, (1, 2), (0, 1)), 2),
     (L("s2_1x1_big", 256, 56, 56, 128, 1, 1, (2, 2)), 2),
+    # at most 64 channels in and out on 32-column patches (4 chunks; 2 chunks with a ragged channel tile; a ragged
+    # last chunk and more padding than the filter needs)
+    (L("rf_c64_k64", 64, 20, 40, 64, 3, 3, (1, 1), (1, 1)), 3),
+    (L("rf_c32_k40_pad0", 32, 12, 72, 40, 3, 3, (1, 1), (0, 0)), 2),
+    (L("rf_c50_k64_pad2", 50, 17, 48, 64, 3, 3, (1, 1), (2, 2)), 2),
     # few input channels (C*R*S <= 32: one MFMA operand holds the whole reduction): rows longer than one
     # 64-pixel unit with a ragged end, more than 64 output channels, stride 2 without padding on an odd
     # image, one channel under a 5x5 filter, two channels under a 4x4 filter with a large padding, a

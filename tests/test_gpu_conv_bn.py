@@ -27,6 +27,8 @@ CASES = [
     (L("w14_split", 64, 14, 14, 128, 3, 3, (1, 1), (1, 1)), 4),
     (L("k64", 48, 20, 36, 64, 3, 3, (1, 1), (1, 1)), 3),
     (L("k48_w72", 104, 12, 72, 48, 3, 3, (1, 1), (1, 1)), 3),
+    (L("rf_c64_k64", 64, 20, 40, 64, 3, 3, (1, 1), (1, 1)), 3),
+    (L("rf_c32_k40_pad0", 32, 12, 72, 40, 3, 3, (1, 1), (0, 0)), 2),
     (L("first3", 3, 40, 40, 64, 3, 3, (1, 1), (1, 1), relu_in=False), 2),
     (L("few_c3_w150", 3, 9, 150, 70, 3, 3, (1, 1), (1, 1), relu_in=False), 2),
     (L("few_c3_s2_valid", 3, 37, 41, 32, 3, 3, (2, 2), (0, 0), relu_in=False), 3),
