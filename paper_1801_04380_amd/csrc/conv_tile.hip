@@ -305,7 +305,7 @@ bool problem_of(const ConvGeom &g, bool bwd_data, TileProblem *p)
 
 bool filter_supported(int R, int S)
 {
-    return (R == 1 && S == 1) || (R == 3 && S == 3) || (R == 5 && S == 5) || (R == 1 && S == 7) ||
+    return (R == 1 && S == 1) || (R == 2 && S == 2) || (R == 3 && S == 3) || (R == 5 && S == 5) || (R == 1 && S == 7) ||
            (R == 7 && S == 1);
 }
 

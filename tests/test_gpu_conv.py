@@ -98,6 +98,11 @@ CASES = [
     (L("s21_3x3", 32, 16, 12, 64, 3, 3, (2, 1), (1, 1)), 2),
     (L("s12_1x3", 32, 9, 20, 48, 1, 3, (1, 2), (0, 1)), 2),
     (L("s2_1x1_big", 256, 56, 56, 128, 1, 1, (2, 2)), 2),
+    # 3x3 / stride 2 as a 2x2 inner convolution over the four phases (forward, backward-data): without padding on
+    # an odd image (planes one row / column larger than the output), many channels; and a plain 2x2 filter
+    (L("s2_3x3_valid_odd", 48, 35, 35, 72, 3, 3, (2, 2), (0, 0)), 3),
+    (L("s2_3x3_valid_c136", 136, 17, 17, 96, 3, 3, (2, 2), (0, 0)), 2),
+    (L("2x2_pad1", 24, 13, 18, 40, 2, 2, (1, 1), (1, 1)), 2),
     # at most 64 channels in and out on 32-column patches (4 chunks; 2 chunks with a ragged channel tile; a ragged
     # last chunk and more padding than the filter needs)
     (L("rf_c64_k64", 64, 20, 40, 64, 3, 3, (1, 1), (1, 1)), 3),
