@@ -74,7 +74,8 @@ typedef enum { SN_CONV_FWD = 0, SN_CONV_BWD_DATA = 1, SN_CONV_BWD_FILTER = 2 } s
  *               at most two on one side without padding, e.g. 11x11 stride 4)
  *               also the phase planes of the input: x[i*stride + a] for each
  *               residue a becomes a channel group, over which the convolution
- *               has stride 1 and runs on the stride-1 kernels; forward and
+ *               has stride 1 and runs on the stride-1 kernels (inner filter
+ *               1x1, 2x2 or 3x3 by the span of the tap offsets); forward and
  *               backward-data take the planes of as many images per pass as the
  *               workspace holds (min_bytes: one image).
  *  WINOGRAD     F(2x2, 3x3) for the fp32 path (3x3 filters, stride 1, forward and
