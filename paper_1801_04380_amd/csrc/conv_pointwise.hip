@@ -1,0 +1,389 @@
+// 1x1 / stride-1 / unpadded CONV forward and backward-data on gfx950, bf16 operands
+// (Sec. 3.5 of the paper: needs no workspace at all, so it serves DIRECT and STAGED alike;
+// definitions in sn.h).
+//
+// Without taps the layer is a matrix product per image,
+//     Y[n][m][px] = sum_r A[m][r] * X[n][r][px],
+// forward with A = w[K][C] (m = k, r = c), backward-data with A = w transposed (m = c, r = k).
+// At 50-200 FLOP per byte these layers sit under the HBM roof, and on small images they are a few
+// microseconds of work: what counts is that every byte is asked for once, early, by many waves.
+//
+//  * NCHW has the pixels of a channel contiguous, the MFMA wants 8 reduction channels of one pixel
+//    per lane.  No transposition is needed for that: a lane loads its pixel (pair) from 8 channel
+//    rows with 8 loads whose addresses differ by a uniform row pitch -- a per-lane constant offset
+//    plus a scalar offset -- and packs halves of the 8 registers into the operand.  With an even
+//    plane size a lane takes two neighbouring pixels per load (4 bytes); the even pixels form one
+//    32-column operand, the odd ones a second, and the epilogue finds both pixels of the pair in the
+//    same lane again and stores them with one 4-byte store.  Odd plane sizes use 2-byte accesses.
+//    The pixel index runs over the whole batch (n * HW + px), so a tile may span images and only
+//    the last tile of the tensor is ragged.
+//  * A is the operand all waves of a workgroup share: 64 reduction channels of it at a time are
+//    staged in LDS (double buffered, one barrier per stage).  Forward reads its operands from there
+//    with 16-byte reads; backward-data parks the rows of w as they are and reads them through the
+//    transposing LDS read (ds_read_b64_tr_b16).
+//  * X loads run three 16-channel steps ahead of the MFMAs, in registers (four rotating sets).
+//  * SPLIT (few pixels, long reductions: 7x7 and 14x14 images under 1024 or 2048 channels): the four
+//    waves of a workgroup share 64 pixels and each takes every fourth pair of 16-channel steps;
+//    their accumulators are added through LDS in a fixed order.  Four times the waves per pixel,
+//    each with a quarter of the serial chain of loads and MFMAs.
+//  * Workgroups are numbered so that the output-channel tiles of one pixel tile run on the same
+//    XCD one after the other: X comes from HBM once and from that XCD's L2 afterwards.
+#include "sn_internal.h"
+
+namespace sn {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+constexpr uint32_t OUTSIDE = 0x80000000u;   // an offset past any tensor this kernel accepts: loads bring zeros, stores are dropped
+constexpr int RG = 64;                      // reduction channels per LDS stage of A (SPLIT: 128, 32 per wave)
+
+struct PwProblem {
+    int M, Rd, HW;
+    uint32_t npx;            // N * HW
+    int mtiles, ptiles;
+    int out_bf16;
+    uint32_t x_bytes, a_bytes, y_bytes;
+    int niter;               // main-loop trips: four 16-channel steps per wave each
+};
+
+__device__ inline uint32_t pack2(float a, float b)   // two fp32 -> two bf16, round to nearest even, a in the low half
+{
+    f32x2 f = {a, b};
+    bf16x2 h = __builtin_convertvector(f, bf16x2);
+    uint32_t r;
+    __builtin_memcpy(&r, &h, 4);
+    return r;
+}
+
+// MS: 32-row blocks of output channels per workgroup; NW: waves per workgroup, 64 pixels each, or
+// with SPLIT a share of the reduction each; AT: A[m][r] = w[r][m] (backward-data); PAIR: plane size
+// even, a lane owns two neighbouring pixels.
+template <int MS, int NW, bool SPLIT, bool AT, bool PAIR>
+__global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
+pointwise_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ a, void *__restrict__ y, PwProblem p)
+{
+    static_assert(!SPLIT || (NW == 4 && MS == 2), "the split form: four waves, 64 output channels");
+    constexpr int MT = 32 * MS, NT = 64 * NW;
+    constexpr int RGS = SPLIT ? 2 * RG : RG;                 // reduction channels per stage
+    constexpr int SPG = SPLIT ? 2 : 4;                       // 16-channel steps per wave and stage
+    constexpr int GPI = 4 / SPG;                             // stages per main-loop trip
+    constexpr int APITCH = AT ? 2 * MT + 64 : 2 * RGS + 16;  // bytes per LDS row (AT: a reduction channel, else an output channel)
+    constexpr int AROWS = AT ? RGS : MT;
+    constexpr int ABUF = AROWS * APITCH;
+    constexpr int IPR = AT ? MT / 8 : RGS / 8;               // 16-byte items per row
+    constexpr int AIT = AROWS * IPR / NT;                    // items per thread and stage
+    constexpr int NX = PAIR ? 8 : 16;                        // registers of one X set
+    static_assert(AROWS * IPR % NT == 0, "stage does not divide over the threads");
+    static_assert(!SPLIT || 2 * ABUF >= 4 * 32 * 64 * 4, "the accumulators of one 32-row block of four waves fit the A buffers");
+    __shared__ __attribute__((aligned(16))) char lds[2 * ABUF];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, g = lane >> 5;
+
+    // ---- which tile: the workgroups of an XCD (every eighth) walk the channel tiles of one pixel tile first
+    const int id = blockIdx.x, xcd = id & 7, slot = id >> 3;
+    const int ptile = (slot / p.mtiles) * 8 + xcd, mtile = slot % p.mtiles;
+    if (ptile >= p.ptiles) return;
+    const int m0 = mtile * MT;
+    const uint32_t px0 = SPLIT ? (uint32_t)ptile * 64 : (uint32_t)ptile * (64 * NW) + wave * 64;
+
+    const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(x), 0, p.x_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t ar = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(a), 0, p.a_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t yr = __builtin_amdgcn_make_buffer_rsrc(y, 0, p.y_bytes, 0x00020000);
+
+    // ---- per-lane constants: where the lane's pixel (pair) sits in X and in Y, channel 8g / 4g of its image
+    constexpr int NCOL = PAIR ? 1 : 2;
+    const uint32_t esz = p.out_bf16 ? 2 : 4;
+    uint32_t xlane[NCOL], ylane[NCOL];
+#pragma unroll
+    for (int e = 0; e < NCOL; ++e) {
+        const uint32_t j = PAIR ? px0 + 2 * l32 : px0 + 32 * e + l32;
+        const uint32_t n = j / (uint32_t)p.HW, pp = j - n * p.HW;
+        const bool ok = j < p.npx;
+        xlane[e] = ok ? ((n * p.Rd + 8 * g) * p.HW + pp) * 2 : OUTSIDE;
+        ylane[e] = ok ? ((n * p.M + 4 * g) * p.HW + pp) * esz : OUTSIDE;
+    }
+    const uint32_t xrow = (uint32_t)p.HW * 2;   // bytes between reduction channels of X
+
+    // ---- per-thread constants of the A stage
+    uint32_t asrc[AIT], adst[AIT];
+    int alim[AIT];   // the item is inside A while group * RG < alim
+#pragma unroll
+    for (int k = 0; k < AIT; ++k) {
+        const int it = tid + NT * k, row = it / IPR, col = it - row * IPR;
+        if (AT) {   // row = reduction channel of the group, col = 8 output channels
+            const bool ok = m0 + col * 8 < p.M;
+            asrc[k] = ok ? (uint32_t)(row * p.M + m0 + col * 8) * 2 : OUTSIDE;
+            alim[k] = p.Rd - row;
+        } else {    // row = output channel of the tile, col = 8 reduction channels
+            const bool ok = m0 + row < p.M;
+            asrc[k] = ok ? (uint32_t)((m0 + row) * p.Rd + col * 8) * 2 : OUTSIDE;
+            alim[k] = p.Rd - col * 8;
+        }
+        adst[k] = row * APITCH + col * 16;
+    }
+    const uint32_t agroup = AT ? (uint32_t)RGS * p.M * 2 : RGS * 2;   // bytes from a stage to the next
+
+    u32x4 areg[AIT];
+    auto a_issue = [&](int grp) {
+#pragma unroll
+        for (int k = 0; k < AIT; ++k)
+            areg[k] = __builtin_amdgcn_raw_buffer_load_b128(ar, grp * RGS < alim[k] ? asrc[k] : OUTSIDE, grp * agroup, 0);
+    };
+    auto a_store = [&](int buf) {
+#pragma unroll
+        for (int k = 0; k < AIT; ++k) *reinterpret_cast<u32x4 *>(lds + buf * ABUF + adst[k]) = areg[k];
+    };
+
+    uint32_t xraw[4][NX];
+    // the q-th step of this wave is 16-channel step q, or with SPLIT step 2 * wave + q % 2 of stage q / 2
+    auto x_issue = [&](int q, uint32_t (&dst)[NX]) {
+        const int c = SPLIT ? (q >> 1) * 8 + 2 * wave + (q & 1) : q;
+        const bool rows_ok = c * 16 + 8 * g < p.Rd;     // Rd is a multiple of 8: a lane's 8 rows are in or out together
+        const uint32_t sb = (uint32_t)c * 16 * xrow;
+#pragma unroll
+        for (int e = 0; e < NCOL; ++e) {
+            const uint32_t v = rows_ok ? xlane[e] : OUTSIDE;
+#pragma unroll
+            for (int jj = 0; jj < 8; ++jj) {
+                if (PAIR) dst[jj] = __builtin_amdgcn_raw_buffer_load_b32(xr, v, sb + jj * xrow, 0);
+                else dst[e * 8 + jj] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(xr, v, sb + jj * xrow, 0);
+            }
+        }
+    };
+
+    // ---- per-lane constants of the A operand reads (SPLIT: the wave's two steps of the stage)
+    uint32_t aread;
+    if (AT) {
+        const int i16 = lane & 15, half = (lane >> 4) & 1;
+        aread = (8 * g + (i16 >> 2)) * APITCH + (16 * half + 4 * (i16 & 3)) * 2;
+        if (SPLIT) aread += wave * SPG * 16 * APITCH;
+    } else {
+        aread = l32 * APITCH + 8 * g * 2;
+        if (SPLIT) aread += wave * SPG * 32;
+    }
+
+    f32x16 acc[MS][2];
+#pragma unroll
+    for (int i = 0; i < MS; ++i)
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][e][v] = 0.f;
+
+    // ---- prologue: group 0 of A into LDS, three steps of X on their way
+    a_issue(0);
+    x_issue(0, xraw[0]);
+    x_issue(1, xraw[1]);
+    x_issue(2, xraw[2]);
+    a_store(0);
+    __syncthreads();
+
+    for (int it = 0; it < p.niter; ++it) {
+#pragma unroll
+        for (int h = 0; h < GPI; ++h) {
+            const int grp = it * GPI + h;
+            a_issue(grp + 1);   // past the last stage: zeros
+            __builtin_amdgcn_sched_barrier(0);
+            const char *ab = lds + (grp & 1) * ABUF;
+#pragma unroll
+            for (int s = 0; s < SPG; ++s) {
+                const int qs = h * SPG + s;   // 0 .. 3: the register set
+                x_issue(it * 4 + qs + 3, xraw[(qs + 3) & 3]);
+                __builtin_amdgcn_sched_barrier(0);   // the loads go out here, three steps ahead, not where the scheduler likes them
+                const uint32_t(&xs)[NX] = xraw[qs];
+                bf16x8 b[2];
+                {
+                    u32x4 d0, d1;
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        if (PAIR) {   // low halves: the even pixel, high halves: the odd one
+                            d0[t] = __builtin_amdgcn_perm(xs[2 * t + 1], xs[2 * t], 0x05040100u);
+                            d1[t] = __builtin_amdgcn_perm(xs[2 * t + 1], xs[2 * t], 0x07060302u);
+                        } else {
+                            d0[t] = xs[2 * t] | xs[2 * t + 1] << 16;
+                            d1[t] = xs[8 + 2 * t] | xs[8 + 2 * t + 1] << 16;
+                        }
+                    }
+                    __builtin_memcpy(&b[0], &d0, 16);
+                    __builtin_memcpy(&b[1], &d1, 16);
+                }
+                bf16x8 aop[MS];
+#pragma unroll
+                for (int i = 0; i < MS; ++i) {
+                    if (AT) {
+                        const char *q = ab + aread + s * 16 * APITCH + i * 64;
+                        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)q);
+                        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(q + 4 * APITCH));
+                        u32x2 l2, h2;
+                        __builtin_memcpy(&l2, &lo, 8);
+                        __builtin_memcpy(&h2, &hi, 8);
+                        u32x4 d = {l2[0], l2[1], h2[0], h2[1]};
+                        __builtin_memcpy(&aop[i], &d, 16);
+                    } else {
+                        u32x4 d = *reinterpret_cast<const u32x4 *>(ab + aread + i * 32 * APITCH + s * 32);
+                        __builtin_memcpy(&aop[i], &d, 16);
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < MS; ++i)
+#pragma unroll
+                    for (int e = 0; e < 2; ++e)
+                        acc[i][e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[i], b[e], acc[i][e], 0, 0, 0);
+            }
+            a_store((grp + 1) & 1);
+            __syncthreads();
+        }
+    }
+
+    // ---- epilogue: register v of a lane is output channel 8*(v/4) + 4*g + v%4 of its 32-row block
+    const uint32_t yrow = (uint32_t)p.HW * esz;
+    // row mu + 4*g + vv of the output for the lane's pixel pair (v0: even pixel or column group 0)
+    auto store_row = [&](int mu, int vv, float v0, float v1) {
+        const uint32_t sb = (uint32_t)(mu + vv) * yrow;
+        if (PAIR) {
+            if (p.out_bf16) {
+                __builtin_amdgcn_raw_buffer_store_b32(pack2(v0, v1), yr, ylane[0], sb, 0);
+            } else {
+                u32x2 d = {__float_as_uint(v0), __float_as_uint(v1)};
+                __builtin_amdgcn_raw_buffer_store_b64(d, yr, ylane[0], sb, 0);
+            }
+        } else {
+            const float vals[2] = {v0, v1};
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                if (p.out_bf16) __builtin_amdgcn_raw_buffer_store_b16((uint16_t)pack2(vals[e], 0.f), yr, ylane[PAIR ? 0 : e], sb, 0);
+                else __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(vals[e]), yr, ylane[PAIR ? 0 : e], sb, 0);
+            }
+        }
+    };
+    if (SPLIT) {
+        // the four waves hold partial sums of the same 64 x 64 block: per 32-row block, every wave parks its
+        // 32 registers in LDS ([wave][e][v][lane]) and wave w then adds up and stores rows 8*w .. 8*w+7
+        float *red = reinterpret_cast<float *>(lds);
+#pragma unroll
+        for (int i = 0; i < MS; ++i) {
+            // the main loop ended with a barrier: nobody reads the A buffers any more
+#pragma unroll
+            for (int e = 0; e < 2; ++e)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) red[((wave * 2 + e) * 16 + v) * 64 + lane] = acc[i][e][v];
+            __syncthreads();
+            const int mu = m0 + 32 * i + 8 * wave;
+            if (mu < p.M) {
+#pragma unroll
+                for (int vv = 0; vv < 4; ++vv) {
+                    float sum[2];
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) {
+                        sum[e] = red[((0 * 2 + e) * 16 + 4 * wave + vv) * 64 + lane];
+#pragma unroll
+                        for (int w2 = 1; w2 < 4; ++w2) sum[e] += red[((w2 * 2 + e) * 16 + 4 * wave + vv) * 64 + lane];
+                    }
+                    store_row(mu, vv, sum[0], sum[1]);
+                }
+            }
+            __syncthreads();
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < MS; ++i) {
+#pragma unroll
+            for (int vb = 0; vb < 4; ++vb) {
+                const int mu = m0 + 32 * i + 8 * vb;   // M is a multiple of 8: the 8 rows of a block are in or out together
+                if (mu < p.M) {
+#pragma unroll
+                    for (int vv = 0; vv < 4; ++vv) store_row(mu, vv, acc[i][0][4 * vb + vv], acc[i][1][4 * vb + vv]);
+                }
+            }
+        }
+    }
+}
+
+struct PwPlan {
+    PwProblem p;
+    int MS, NW;
+    bool split, at, pair;
+    unsigned grid;
+};
+
+bool make_plan(const ConvGeom &g, bool bwd_data, PwPlan *pl)
+{
+    if (!g.in_bf16 || g.R != 1 || g.S != 1 || g.sh != 1 || g.sw != 1 || g.ph != 0 || g.pw != 0) return false;
+    if (g.P != g.H || g.Q != g.W) return false;
+    if (g.C % 8 != 0 || g.K % 8 != 0) return false;
+    const long long HW = (long long)g.H * g.W, npx = HW * g.N;
+    const long long M = bwd_data ? g.C : g.K, Rd = bwd_data ? g.K : g.C;
+    const long long lim = 0x7fffffffLL - (1 << 20);
+    if (npx * Rd * 2 > lim || npx * M * (g.out_bf16 ? 2 : 4) > lim || (long long)g.K * g.C * 2 > lim) return false;
+    if (16 * HW * 2 * 4 > lim) return false;   // the scalar offset of a 16-channel step stays small next to the tensor
+    PwProblem &p = pl->p;
+    p.M = (int)M; p.Rd = (int)Rd; p.HW = (int)HW; p.npx = (uint32_t)npx;
+    p.out_bf16 = g.out_bf16;
+    p.x_bytes = (uint32_t)(npx * Rd * 2);
+    p.y_bytes = (uint32_t)(npx * M * (g.out_bf16 ? 2 : 4));
+    p.a_bytes = (uint32_t)((long long)g.K * g.C * 2);
+    pl->at = bwd_data;
+    pl->pair = HW % 2 == 0;
+    // 128 output channels x 256 pixels per workgroup where that still gives every compute unit a
+    // workgroup; else smaller tiles: more workgroups, and more passes over X and A, which these
+    // small problems take from L2; long reductions over few pixels are split over the waves
+    auto tiles = [&](int ms, int px) { return ((M + 32 * ms - 1) / (32 * ms)) * ((npx + px - 1) / px); };
+    pl->split = false;
+    if (M > 64 && tiles(4, 256) >= 256) { pl->MS = 4; pl->NW = 4; }
+    else if (tiles(2, 256) >= 256) { pl->MS = 2; pl->NW = 4; }
+    else if (Rd >= 256 && tiles(2, 64) < 640) { pl->MS = 2; pl->NW = 4; pl->split = true; }   // measured: 7x7 and 8x8 images gain, 14x14 ones do not
+    else { pl->MS = 2; pl->NW = 1; }
+    const int px = pl->split ? 64 : 64 * pl->NW;
+    p.mtiles = (int)((M + 32 * pl->MS - 1) / (32 * pl->MS));
+    p.ptiles = (int)((npx + px - 1) / px);
+    const long long per_trip = pl->split ? 4 * RG : RG;   // reduction channels a workgroup consumes per main-loop trip
+    p.niter = (int)((Rd + per_trip - 1) / per_trip);
+    const long long grid = 8LL * p.mtiles * ((p.ptiles + 7) / 8);
+    if (grid > 0x7fffffffLL) return false;
+    pl->grid = (unsigned)grid;
+    return true;
+}
+
+template <int MS, int NW, bool SPLIT>
+hipError_t launch_shape(const bf16_t *x, const bf16_t *a, void *y, const PwPlan &pl, hipStream_t st)
+{
+    const dim3 grid(pl.grid), block(64 * NW);
+    if (pl.at) {
+        if (pl.pair) hipLaunchKernelGGL((pointwise_kernel<MS, NW, SPLIT, true, true>), grid, block, 0, st, x, a, y, pl.p);
+        else hipLaunchKernelGGL((pointwise_kernel<MS, NW, SPLIT, true, false>), grid, block, 0, st, x, a, y, pl.p);
+    } else {
+        if (pl.pair) hipLaunchKernelGGL((pointwise_kernel<MS, NW, SPLIT, false, true>), grid, block, 0, st, x, a, y, pl.p);
+        else hipLaunchKernelGGL((pointwise_kernel<MS, NW, SPLIT, false, false>), grid, block, 0, st, x, a, y, pl.p);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool pointwise_supported(const ConvGeom &g, bool bwd_data)
+{
+    PwPlan pl;
+    return make_plan(g, bwd_data, &pl);
+}
+
+hipError_t launch_pointwise(const void *in, const void *w, void *out, const ConvGeom &g, bool bwd_data, hipStream_t st)
+{
+    PwPlan pl;
+    if (!make_plan(g, bwd_data, &pl)) return hipErrorInvalidValue;
+    const bf16_t *x = static_cast<const bf16_t *>(in), *a = static_cast<const bf16_t *>(w);
+    if (pl.split) return launch_shape<2, 4, true>(x, a, out, pl, st);
+    if (pl.MS == 4) return launch_shape<4, 4, false>(x, a, out, pl, st);
+    if (pl.NW == 4) return launch_shape<2, 4, false>(x, a, out, pl, st);
+    return launch_shape<2, 1, false>(x, a, out, pl, st);
+}
+
+}  // namespace sn

@@ -346,6 +346,7 @@ hipError_t launch_tile_conv(const void *in, const void *w, void *out, const Conv
         !make_plan(p, g.R, g.S, packed != nullptr, &pl))
         return hipErrorInvalidValue;
     if (stats && bwd_data) return hipErrorInvalidValue;
+    if (!stats && pointwise_supported(g, bwd_data)) return launch_pointwise(in, w, out, g, bwd_data, st);
     pl.p.stats = stats;
     const bf16_t *wsrc = static_cast<const bf16_t *>(w);
     if (packed) {

@@ -85,6 +85,12 @@ int smallc_wgrad_slices(const ConvGeom &g);
 hipError_t launch_smallc_wgrad(const void *x, const void *dy, float *dw, const ConvGeom &g, float *partial,
                                hipStream_t st);
 
+// 1x1 / stride-1 / unpadded layers with bf16 operands and channel counts that are multiples of 8
+// (conv_pointwise.hip): forward or backward-data without workspace; launch_tile_conv prefers it
+// when no statistics are asked for.
+bool pointwise_supported(const ConvGeom &g, bool bwd_data);
+hipError_t launch_pointwise(const void *in, const void *w, void *out, const ConvGeom &g, bool bwd_data, hipStream_t st);
+
 hipError_t launch_fill_zero(float *p, size_t n, hipStream_t st);
 // dw[i] = (accumulate ? dw[i] : 0) + sum_z partial[z][i], z ascending.
 hipError_t launch_reduce_partials(const float *partial, float *dw, size_t n, int splits, bool accumulate,

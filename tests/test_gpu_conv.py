@@ -118,6 +118,13 @@ CASES = [
     (L("few_c2_4x4_pad3", 2, 11, 13, 24, 4, 4, (1, 1), (3, 3), relu_in=False), 2),
     (L("few_c32_1x1", 32, 7, 9, 40, 1, 1), 5),
     (L("few_c3_s12", 3, 12, 90, 64, 3, 3, (1, 2), (1, 0), relu_in=False), 2),
+    # 1x1 / stride 1 with channel counts that are multiples of 8 (the matrix-product kernel): enough pixels
+    # for the largest tile with a ragged channel tile and a reduction that ends in half a 16-channel step,
+    # forward and backward-data swapped, an odd plane size (2-byte accesses, tiles spanning images)
+    (L("pw_c72_k136", 72, 82, 82, 136, 1, 1), 5),
+    (L("pw_c136_k72", 136, 82, 82, 72, 1, 1), 5),
+    (L("pw_odd_c80_k200", 80, 81, 83, 200, 1, 1), 5),
+    (L("pw_c264_k64", 264, 12, 10, 64, 1, 1), 7),
 ]
 IDS = [c[0].name for c in CASES]
 
