@@ -28,6 +28,7 @@
 //    each with a quarter of the serial chain of loads and MFMAs.
 //  * Workgroups are numbered so that the output-channel tiles of one pixel tile run on the same
 //    XCD one after the other: X comes from HBM once and from that XCD's L2 afterwards.
+#include <algorithm>
 #include "sn_internal.h"
 
 namespace sn {
@@ -181,9 +182,13 @@ pointwise_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ a, voi
 
     // ---- prologue: group 0 of A into LDS, three steps of X on their way
     a_issue(0);
+    __builtin_amdgcn_sched_barrier(0);   // in this order: the loop's waits count on it
     x_issue(0, xraw[0]);
+    __builtin_amdgcn_sched_barrier(0);
     x_issue(1, xraw[1]);
+    __builtin_amdgcn_sched_barrier(0);
     x_issue(2, xraw[2]);
+    __builtin_amdgcn_sched_barrier(0);
     a_store(0);
     __syncthreads();
 
@@ -367,6 +372,172 @@ hipError_t launch_shape(const bf16_t *x, const bf16_t *a, void *y, const PwPlan 
     return hipGetLastError();
 }
 
+// ---- backward-filter of the same layers on small images ------------------------------------------
+// dw[k][c] = sum over n and px of dy[n][k][px] * x[n][c][px]: the reduction runs along the pixels, which
+// both operands have contiguous, so a lane's 8 reduction entries are one 16-byte load (at any 2-byte
+// alignment) straight into the MFMA layout -- no LDS in the main loop.  A workgroup owns 64 k x 64 c; its
+// four waves take a quarter of the workgroup's images each (all 64 x 64, 2 x 2 MFMA tiles) and add their
+// accumulators through LDS in wave order at the end; gridDim.y slices split the batch further where
+// the tiles alone do not fill the chip.  An image is ceil(HW / 16) steps; in the last one the lanes
+// whose 8 pixels would pass the end of the plane read the last 8 pixels of the plane instead and
+// mask the ones an earlier step already had, on both operands, so nothing outside a row is ever
+// multiplied and nothing outside the tensors is read.
+struct PwWgradProblem {
+    int K, C, HW, N;
+    int ctiles;
+    int steps;     // 16-pixel steps per image
+    int ipw;       // images per wave
+    int atomics;
+};
+
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+pointwise_wgrad_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, float *__restrict__ out, PwWgradProblem p)
+{
+    __shared__ __attribute__((aligned(16))) float red[4 * 32 * 64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, g = lane >> 5;
+    const int kt = blockIdx.x / p.ctiles, ct = blockIdx.x - kt * p.ctiles, z = blockIdx.y;
+    const int k0 = kt * 64, c0 = ct * 64;
+
+    // rows past the last channel read the last channel instead: their products land in rows / columns that are not stored
+    uint32_t rowd[2], rowx[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        rowd[i] = (uint32_t)min(k0 + 32 * i + l32, p.K - 1) * p.HW * 2;
+        rowx[i] = (uint32_t)min(c0 + 32 * i + l32, p.C - 1) * p.HW * 2;
+    }
+    const int lastcol = 16 * (p.steps - 1) + 8 * g, cnt = min(max(p.HW - lastcol, 0), 8);
+    const uint32_t tailcolb = (uint32_t)(cnt < 8 ? p.HW - 8 : lastcol) * 2;
+    uint32_t tailmask[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+        tailmask[t] = (2 * t >= 8 - cnt ? 0xffffu : 0u) | (2 * t + 1 >= 8 - cnt ? 0xffff0000u : 0u);
+
+    // the wave's images: first .. first + nimg - 1
+    const int first = (z * 4 + wave) * p.ipw;
+    const int nimg = min(max(p.N - first, 0), p.ipw);
+    const int nq = nimg * p.steps;
+    const int nlast = min(first + max(nimg, 1) - 1, p.N - 1);
+    const uint32_t dimg = (uint32_t)p.K * p.HW * 2, ximg = (uint32_t)p.C * p.HW * 2;   // bytes per image
+    const __amdgpu_buffer_rsrc_t dr = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(dy), 0, (uint32_t)p.N * dimg, 0x00020000);
+    const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(x), 0, (uint32_t)p.N * ximg, 0x00020000);
+
+    u32x4 dreg[4][2], xreg[4][2];
+    int n_iss = first, s_iss = 0;
+    auto issue = [&](u32x4 (&dd)[2], u32x4 (&xd)[2]) {
+        const uint32_t n = (uint32_t)min(n_iss, nlast);
+        const uint32_t colb = s_iss == p.steps - 1 ? tailcolb : (uint32_t)(16 * s_iss + 8 * g) * 2;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            dd[i] = __builtin_amdgcn_raw_buffer_load_b128(dr, rowd[i] + colb, n * dimg, 0);
+            xd[i] = __builtin_amdgcn_raw_buffer_load_b128(xr, rowx[i] + colb, n * ximg, 0);
+        }
+        if (++s_iss == p.steps) { s_iss = 0; ++n_iss; }
+    };
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    issue(dreg[0], xreg[0]);
+    __builtin_amdgcn_sched_barrier(0);   // in this order: the first wait of the loop is for set 0 alone
+    issue(dreg[1], xreg[1]);
+    __builtin_amdgcn_sched_barrier(0);
+    issue(dreg[2], xreg[2]);
+    __builtin_amdgcn_sched_barrier(0);
+    int s_con = 0;
+    for (int q0 = 0; q0 < nq; q0 += 4) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            issue(dreg[(u + 3) & 3], xreg[(u + 3) & 3]);
+            __builtin_amdgcn_sched_barrier(0);
+            const bool live = q0 + u < nq, last = s_con == p.steps - 1;
+            if (++s_con == p.steps) s_con = 0;
+            bf16x8 a[2], b[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                u32x4 dm, xm;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const uint32_t m = live ? (last ? tailmask[t] : 0xffffffffu) : 0u;
+                    dm[t] = dreg[u][i][t] & m;
+                    xm[t] = xreg[u][i][t] & m;
+                }
+                __builtin_memcpy(&a[i], &dm, 16);
+                __builtin_memcpy(&b[i], &xm, 16);
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+    }
+
+    // ---- the four waves' sums, block of 32 k at a time: [wave][j][v][lane] in LDS, wave w adds up rows 8w .. 8w+7
+    float *dst = out + (p.atomics ? 0 : (size_t)z * p.K * p.C);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) red[((wave * 2 + j) * 16 + v) * 64 + lane] = acc[i][j][v];
+        __syncthreads();
+#pragma unroll
+        for (int vv = 0; vv < 4; ++vv) {
+            const int k = k0 + 32 * i + 8 * wave + 4 * g + vv;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                float sum = red[((0 * 2 + j) * 16 + 4 * wave + vv) * 64 + lane];
+#pragma unroll
+                for (int w2 = 1; w2 < 4; ++w2) sum += red[((w2 * 2 + j) * 16 + 4 * wave + vv) * 64 + lane];
+                const int c = c0 + 32 * j + l32;
+                if (k < p.K && c < p.C) {
+                    if (p.atomics) unsafeAtomicAdd(dst + (size_t)k * p.C + c, sum);
+                    else dst[(size_t)k * p.C + c] = sum;
+                }
+            }
+        }
+    }
+}
+
+struct PwWgradPlan {
+    PwWgradProblem p;
+    dim3 grid;
+    int slices;
+};
+
+bool make_wgrad_plan(const ConvGeom &g, PwWgradPlan *pl)
+{
+    if (!g.in_bf16 || g.R != 1 || g.S != 1 || g.sh != 1 || g.sw != 1 || g.ph != 0 || g.pw != 0) return false;
+    if (g.P != g.H || g.Q != g.W) return false;
+    const long long HW = (long long)g.H * g.W;
+    // the smallest planes only (7x7, 8x8): a load brings 32 bytes of each of 32 rows, which costs the memory
+    // pipeline about as much as 32 separate lines; from 14x14 on the row-stationary kernel's tiles, loaded as
+    // whole lines and re-laid out in LDS, are as fast (measured: 47 against 44 us on 1024 -> 256 channels)
+    if (HW < 8 || HW > 64) return false;
+    if ((long long)std::max(g.K, g.C) * HW * 2 * g.N > 0x7fffffffLL) return false;
+    PwWgradProblem &p = pl->p;
+    p.K = g.K; p.C = g.C; p.HW = (int)HW; p.N = g.N;
+    p.ctiles = (g.C + 63) / 64;
+    const long long tiles = (long long)((g.K + 63) / 64) * p.ctiles;
+    if (tiles > 0x7fffffffLL) return false;
+    p.steps = (int)((HW + 15) / 16);
+    long long slices = (256 + tiles - 1) / tiles;
+    slices = std::max(1LL, std::min(slices, (long long)g.N / 4));
+    p.ipw = (int)((g.N + 4 * slices - 1) / (4 * slices));
+    slices = (g.N + 4LL * p.ipw - 1) / (4LL * p.ipw);
+    if (slices > 65535) return false;
+    pl->slices = (int)slices;
+    pl->grid = dim3((unsigned)tiles, (unsigned)slices);
+    return true;
+}
+
 }  // namespace
 
 bool pointwise_supported(const ConvGeom &g, bool bwd_data)
@@ -384,6 +555,41 @@ hipError_t launch_pointwise(const void *in, const void *w, void *out, const Conv
     if (pl.MS == 4) return launch_shape<4, 4, false>(x, a, out, pl, st);
     if (pl.NW == 4) return launch_shape<2, 4, false>(x, a, out, pl, st);
     return launch_shape<2, 1, false>(x, a, out, pl, st);
+}
+
+bool pointwise_wgrad_supported(const ConvGeom &g)
+{
+    PwWgradPlan pl;
+    return make_wgrad_plan(g, &pl);
+}
+
+int pointwise_wgrad_slices(const ConvGeom &g)
+{
+    PwWgradPlan pl;
+    return make_wgrad_plan(g, &pl) ? pl.slices : 0;
+}
+
+// partial == nullptr: slices add into dw with atomics (dw is zero-filled first; one slice stores);
+// otherwise slice z writes partial[z][K*C] and a reduction in slice order follows.
+hipError_t launch_pointwise_wgrad(const void *x, const void *dy, float *dw, const ConvGeom &g, float *partial,
+                                  hipStream_t st)
+{
+    PwWgradPlan pl;
+    if (!make_wgrad_plan(g, &pl)) return hipErrorInvalidValue;
+    const size_t nw = (size_t)g.K * g.C;
+    const bool direct_store = pl.slices == 1;
+    pl.p.atomics = (!partial && !direct_store) ? 1 : 0;
+    if (pl.p.atomics) {
+        hipError_t e = launch_fill_zero(dw, nw, st);
+        if (e != hipSuccess) return e;
+    }
+    float *out = (partial && !direct_store) ? partial : dw;
+    hipLaunchKernelGGL(pointwise_wgrad_kernel, pl.grid, dim3(256), 0, st, static_cast<const bf16_t *>(x),
+                       static_cast<const bf16_t *>(dy), out, pl.p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (partial && !direct_store) return launch_reduce_partials(partial, dw, nw, pl.slices, false, st);
+    return hipSuccess;
 }
 
 }  // namespace sn

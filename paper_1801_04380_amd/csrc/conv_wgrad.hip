@@ -528,11 +528,12 @@ hipError_t launch_cfg(const bf16_t *x, const bf16_t *dy, float *out, int atomics
 bool tile_wgrad_supported(const ConvGeom &g)
 {
     WPlan pl;
-    return rows_wgrad_supported(g) || make_wplan(g, &pl);
+    return pointwise_wgrad_supported(g) || rows_wgrad_supported(g) || make_wplan(g, &pl);
 }
 
 int tile_wgrad_slices(const ConvGeom &g)
 {
+    if (pointwise_wgrad_supported(g)) return pointwise_wgrad_slices(g);
     if (rows_wgrad_supported(g)) return rows_wgrad_slices(g);
     WPlan pl;
     return make_wplan(g, &pl) ? (int)pl.grid.z : 0;
@@ -543,6 +544,7 @@ int tile_wgrad_slices(const ConvGeom &g)
 hipError_t launch_tile_wgrad(const void *x, const void *dy, float *dw, const ConvGeom &g, float *partial,
                              hipStream_t st)
 {
+    if (pointwise_wgrad_supported(g)) return launch_pointwise_wgrad(x, dy, dw, g, partial, st);
     if (rows_wgrad_supported(g)) return launch_rows_wgrad(x, dy, dw, g, partial, st);
     WPlan pl;
     if (!make_wplan(g, &pl)) return hipErrorInvalidValue;

@@ -91,6 +91,13 @@ hipError_t launch_smallc_wgrad(const void *x, const void *dy, float *dw, const C
 bool pointwise_supported(const ConvGeom &g, bool bwd_data);
 hipError_t launch_pointwise(const void *in, const void *w, void *out, const ConvGeom &g, bool bwd_data, hipStream_t st);
 
+// Backward-filter of the same layers on the smallest planes (8 to 64 pixels), any channel counts;
+// contract of launch_rows_wgrad (pointwise_wgrad_slices slices).  launch_tile_wgrad prefers it.
+bool pointwise_wgrad_supported(const ConvGeom &g);
+int pointwise_wgrad_slices(const ConvGeom &g);
+hipError_t launch_pointwise_wgrad(const void *x, const void *dy, float *dw, const ConvGeom &g, float *partial,
+                                  hipStream_t st);
+
 hipError_t launch_fill_zero(float *p, size_t n, hipStream_t st);
 // dw[i] = (accumulate ? dw[i] : 0) + sum_z partial[z][i], z ascending.
 hipError_t launch_reduce_partials(const float *partial, float *dw, size_t n, int splits, bool accumulate,

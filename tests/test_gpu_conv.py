@@ -125,6 +125,11 @@ CASES = [
     (L("pw_c136_k72", 136, 82, 82, 72, 1, 1), 5),
     (L("pw_odd_c80_k200", 80, 81, 83, 200, 1, 1), 5),
     (L("pw_c264_k64", 264, 12, 10, 64, 1, 1), 7),
+    # backward-filter of 1x1 layers on small planes: several slices of the batch with a ragged last wave,
+    # planes shorter than one 16-pixel step, a plane of exactly 8 pixels
+    (L("pw_slices_6x5", 72, 6, 5, 40, 1, 1), 19),
+    (L("pw_tiny_3x3", 16, 3, 3, 24, 1, 1), 5),
+    (L("pw_2x4", 24, 2, 4, 72, 1, 1), 9),
 ]
 IDS = [c[0].name for c in CASES]
 
