@@ -61,6 +61,9 @@ typedef enum { SN_CONV_FWD = 0, SN_CONV_BWD_DATA = 1, SN_CONV_BWD_FILTER = 2 } s
  *               holds the whole reduction in one MFMA operand and is bound by
  *               writing y (forward) or reading dy (backward-filter, also under
  *               STAGED, where its workgroups' partial sums are reduced in a fixed order).
+ *               1x1 / stride-1 / unpadded layers (bf16, C and K multiples of 8) run
+ *               forward and backward-data as a matrix product per image that
+ *               needs no re-laid-out operand, under DIRECT and STAGED alike.
  *  IM2COL_GEMM  explicit: unfold patches into a column buffer in the workspace
  *               (as many images per pass as fit), then a GEMM over it; the
  *               backward-data form folds the column gradient back (col2im).
