@@ -538,6 +538,182 @@ bool make_wgrad_plan(const ConvGeom &g, PwWgradPlan *pl)
     return true;
 }
 
+// ---- backward-filter of 1x1 layers on planes whose size is a multiple of 4 (14x14, 28x28) ----------
+// Same product as above, but the operands reach the MFMAs through LDS: a workgroup owns 128 k x 128 c and
+// walks its images in stages of 64 pixels; the 256 rows (128 of dy, 128 of x) of a stage are fetched as
+// 8-byte items, 16 consecutive lanes per row (whole 128-byte runs, which 4-pixel-aligned rows allow),
+// parked [row][64 px] and read back as 16-byte operands.  Items past the end of a plane are fetched
+// from an out-of-range offset and arrive as zeros, so a plane's ragged last stage needs no masks.
+// Four waves, 2 x 2, 64 x 64 each; two stages ahead of the one being multiplied are under way, one in
+// registers on its way from memory, one going from registers into the next of three LDS buffers (one
+// barrier per stage); slices of the batch split the sum, the tiles of a slice on one XCD.
+struct PwWgradLdsProblem {
+    int K, C, HW, N;
+    int ctiles, tiles, slices;
+    int spi;       // 64-pixel stages per image
+    int steps;     // 16-pixel steps per image
+    int ipw;       // images per workgroup
+    int atomics;
+    uint32_t d_bytes, x_bytes;
+};
+
+constexpr int WL_PITCH = 144, WL_BUF = 256 * WL_PITCH, WL_NBUF = 3;
+
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+pointwise_wgrad_lds_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, float *__restrict__ out,
+                           PwWgradLdsProblem p)
+{
+    extern __shared__ __attribute__((aligned(16))) char wl_lds[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, g = lane >> 5, wk = wave >> 1, wc = wave & 1;
+    // workgroups go round the XCDs: all tiles of a slice (they read the same images) on one XCD
+    const int xcd = blockIdx.x & 7, rest = blockIdx.x >> 3;
+    const int tile = rest % p.tiles, z = (rest / p.tiles) * 8 + xcd;
+    if (z >= p.slices) return;
+    const int kt = tile / p.ctiles, ct = tile - kt * p.ctiles;
+    const int k0 = kt * 128, c0 = ct * 128;
+    const __amdgpu_buffer_rsrc_t dr = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(dy), 0, p.d_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(x), 0, p.x_bytes, 0x00020000);
+
+    // item j of the thread: row (tid >> 4) + 16 * j of the stage (0 .. 127 dy, 128 .. 255 x), pixels 4 * (tid & 15) .. + 3
+    const int col8 = tid & 15, row0 = tid >> 4;
+    uint32_t src[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+        const int row = row0 + 16 * (j & 7);
+        const int ch = (j < 8 ? k0 : c0) + row;
+        src[j] = ch < (j < 8 ? p.K : p.C) ? (uint32_t)ch * p.HW * 2 + col8 * 8 : OUTSIDE;
+    }
+    const uint32_t dst = row0 * WL_PITCH + col8 * 8;   // + 16 * j rows
+    const uint32_t dimg = (uint32_t)p.K * p.HW * 2, ximg = (uint32_t)p.C * p.HW * 2;
+
+    const int first = z * p.ipw, nimg = min(max(p.N - first, 0), p.ipw);
+    const int nq = nimg * p.spi;
+
+    u32x2 reg[2][16];
+    int n_iss = first, js_iss = 0;
+    auto issue = [&](u32x2 (&rd)[16]) {   // the stage (n_iss, js_iss); past the last stage: zeros
+        const bool live = n_iss < first + nimg;
+        const uint32_t off = live && 64 * js_iss + 4 * col8 < p.HW ? 0u : OUTSIDE;
+        const uint32_t n = (uint32_t)min(n_iss, p.N - 1);
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+            rd[j] = j < 8 ? __builtin_amdgcn_raw_buffer_load_b64(dr, src[j] | off, n * dimg + js_iss * 128, 0)
+                          : __builtin_amdgcn_raw_buffer_load_b64(xr, src[j] | off, n * ximg + js_iss * 128, 0);
+        if (++js_iss == p.spi) { js_iss = 0; ++n_iss; }
+    };
+    auto park = [&](int buf, const u32x2 (&rd)[16]) {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) *reinterpret_cast<u32x2 *>(wl_lds + buf * WL_BUF + dst + j * 16 * WL_PITCH) = rd[j];
+    };
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    // stage q is multiplied out of LDS buffer q % 3 while stage q + 1 goes from registers into the next buffer
+    // and stage q + 2 is on its way from memory
+    issue(reg[0]);
+    __builtin_amdgcn_sched_barrier(0);
+    issue(reg[1]);
+    __builtin_amdgcn_sched_barrier(0);
+    park(0, reg[0]);
+    __syncthreads();
+    const uint32_t aoff = (wk * 64 + l32) * WL_PITCH + 16 * g, boff = (128 + wc * 64 + l32) * WL_PITCH + 16 * g;
+    int js = 0, cur = 0;
+    for (int q0 = 0; q0 < nq; q0 += 2) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            // registers h hold stage q + 2 from here on; registers 1 - h hold stage q + 1
+            issue(reg[h]);
+            __builtin_amdgcn_sched_barrier(0);
+            const char *b = wl_lds + cur * WL_BUF;
+            const int nxt = cur == 2 ? 0 : cur + 1;
+            const int nst = min(4, p.steps - 4 * js);
+            if (++js == p.spi) js = 0;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                if (s < nst) {
+                    bf16x8 a[2], bb[2];
+#pragma unroll
+                    for (int i = 0; i < 2; ++i) {
+                        u32x4 da = *reinterpret_cast<const u32x4 *>(b + aoff + i * 32 * WL_PITCH + s * 32);
+                        u32x4 db = *reinterpret_cast<const u32x4 *>(b + boff + i * 32 * WL_PITCH + s * 32);
+                        __builtin_memcpy(&a[i], &da, 16);
+                        __builtin_memcpy(&bb[i], &db, 16);
+                    }
+#pragma unroll
+                    for (int i = 0; i < 2; ++i)
+#pragma unroll
+                        for (int j = 0; j < 2; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bb[j], acc[i][j], 0, 0, 0);
+                }
+            }
+            park(nxt, reg[1 - h]);
+            __syncthreads();
+            cur = nxt;
+        }
+    }
+
+    float *o = out + (p.atomics ? 0 : (size_t)z * p.K * p.C);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int k = k0 + wk * 64 + 32 * i + 8 * (v >> 2) + 4 * g + (v & 3);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int c = c0 + wc * 64 + 32 * j + l32;
+                if (k < p.K && c < p.C) {
+                    if (p.atomics) unsafeAtomicAdd(o + (size_t)k * p.C + c, acc[i][j][v]);
+                    else o[(size_t)k * p.C + c] = acc[i][j][v];
+                }
+            }
+        }
+}
+
+struct PwWgradLdsPlan {
+    PwWgradLdsProblem p;
+    dim3 grid;
+    int slices;
+};
+
+bool make_wgrad_lds_plan(const ConvGeom &g, PwWgradLdsPlan *pl)
+{
+    if (!g.in_bf16 || g.R != 1 || g.S != 1 || g.sh != 1 || g.sw != 1 || g.ph != 0 || g.pw != 0) return false;
+    if (g.P != g.H || g.Q != g.W) return false;
+    const long long HW = (long long)g.H * g.W;
+    // rows of the plane on 8-byte boundaries; short rows (where the row-stationary kernel's 8 x 16 chunks are mostly padding)
+    if (HW % 4 != 0 || g.W > 16) return false;
+    const long long lim = 0x7fffffffLL - (1 << 20);
+    if ((long long)g.K * HW * 2 * g.N > lim || (long long)g.C * HW * 2 * g.N > lim) return false;
+    PwWgradLdsProblem &p = pl->p;
+    p.K = g.K; p.C = g.C; p.HW = (int)HW; p.N = g.N;
+    p.ctiles = (g.C + 127) / 128;
+    const long long tiles = (long long)((g.K + 127) / 128) * p.ctiles;
+    if (tiles > 0x7fffffffLL) return false;
+    p.spi = (int)((HW + 63) / 64);
+    p.steps = (int)((HW + 15) / 16);
+    long long slices = (256 + tiles - 1) / tiles;
+    slices = std::max(1LL, std::min(slices, (long long)g.N));
+    p.ipw = (int)((g.N + slices - 1) / slices);
+    slices = (g.N + p.ipw - 1) / p.ipw;
+    if (slices > 65535) return false;
+    p.d_bytes = (uint32_t)((long long)g.K * HW * 2 * g.N);
+    p.x_bytes = (uint32_t)((long long)g.C * HW * 2 * g.N);
+    pl->slices = (int)slices;
+    p.tiles = (int)tiles;
+    p.slices = (int)slices;
+    const long long grid = 8 * tiles * ((slices + 7) / 8);
+    if (grid > 0x7fffffffLL) return false;
+    pl->grid = dim3((unsigned)grid);
+    return true;
+}
+
 }  // namespace
 
 bool pointwise_supported(const ConvGeom &g, bool bwd_data)
@@ -560,13 +736,16 @@ hipError_t launch_pointwise(const void *in, const void *w, void *out, const Conv
 bool pointwise_wgrad_supported(const ConvGeom &g)
 {
     PwWgradPlan pl;
-    return make_wgrad_plan(g, &pl);
+    PwWgradLdsPlan pl2;
+    return make_wgrad_plan(g, &pl) || make_wgrad_lds_plan(g, &pl2);
 }
 
 int pointwise_wgrad_slices(const ConvGeom &g)
 {
     PwWgradPlan pl;
-    return make_wgrad_plan(g, &pl) ? pl.slices : 0;
+    PwWgradLdsPlan pl2;
+    if (make_wgrad_plan(g, &pl)) return pl.slices;
+    return make_wgrad_lds_plan(g, &pl2) ? pl2.slices : 0;
 }
 
 // partial == nullptr: slices add into dw with atomics (dw is zero-filled first; one slice stores);
@@ -575,20 +754,33 @@ hipError_t launch_pointwise_wgrad(const void *x, const void *dy, float *dw, cons
                                   hipStream_t st)
 {
     PwWgradPlan pl;
-    if (!make_wgrad_plan(g, &pl)) return hipErrorInvalidValue;
+    PwWgradLdsPlan pl2;
+    const bool small = make_wgrad_plan(g, &pl);
+    if (!small && !make_wgrad_lds_plan(g, &pl2)) return hipErrorInvalidValue;
+    const int slices = small ? pl.slices : pl2.slices;
     const size_t nw = (size_t)g.K * g.C;
-    const bool direct_store = pl.slices == 1;
-    pl.p.atomics = (!partial && !direct_store) ? 1 : 0;
-    if (pl.p.atomics) {
+    const bool direct_store = slices == 1;
+    const int atomics = (!partial && !direct_store) ? 1 : 0;
+    if (atomics) {
         hipError_t e = launch_fill_zero(dw, nw, st);
         if (e != hipSuccess) return e;
     }
     float *out = (partial && !direct_store) ? partial : dw;
-    hipLaunchKernelGGL(pointwise_wgrad_kernel, pl.grid, dim3(256), 0, st, static_cast<const bf16_t *>(x),
-                       static_cast<const bf16_t *>(dy), out, pl.p);
+    const bf16_t *xs = static_cast<const bf16_t *>(x), *ds = static_cast<const bf16_t *>(dy);
+    if (small) {
+        pl.p.atomics = atomics;
+        hipLaunchKernelGGL(pointwise_wgrad_kernel, pl.grid, dim3(256), 0, st, xs, ds, out, pl.p);
+    } else {
+        // dynamic LDS beyond 64 KB has to be enabled once per kernel
+        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(pointwise_wgrad_lds_kernel),
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, WL_NBUF * WL_BUF);
+        if (attr != hipSuccess) return attr;
+        pl2.p.atomics = atomics;
+        hipLaunchKernelGGL(pointwise_wgrad_lds_kernel, pl2.grid, dim3(256), WL_NBUF * WL_BUF, st, xs, ds, out, pl2.p);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (partial && !direct_store) return launch_reduce_partials(partial, dw, nw, pl.slices, false, st);
+    if (partial && !direct_store) return launch_reduce_partials(partial, dw, nw, slices, false, st);
     return hipSuccess;
 }
 

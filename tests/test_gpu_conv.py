@@ -130,6 +130,9 @@ CASES = [
     (L("pw_slices_6x5", 72, 6, 5, 40, 1, 1), 19),
     (L("pw_tiny_3x3", 16, 3, 3, 24, 1, 1), 5),
     (L("pw_2x4", 24, 2, 4, 72, 1, 1), 9),
+    # ... and on planes of a multiple of 4 pixels (operands through LDS): two images per workgroup with a
+    # ragged last slice, ragged channel tiles, a last stage of one 16-pixel step
+    (L("pw_lds_10x8", 264, 10, 8, 520, 1, 1), 41),
 ]
 IDS = [c[0].name for c in CASES]
 
