@@ -179,7 +179,11 @@ bool plan_for(const TileProblem &base, int R, int S, int NF, Plan *pl, bool pref
 // kernels) that leaves compute units without work and a smaller one does not.
 bool make_plan(const TileProblem &base, int R, int S, bool staged, Plan *pl, bool prefer_narrow = false)
 {
-    if (!plan_for(base, R, S, 4, pl, prefer_narrow)) return false;
+    if (!plan_for(base, R, S, 4, pl, prefer_narrow)) {
+        // 5x5 with at most 64 output channels: the patch of the 512-pixel tile does not fit LDS, a smaller one does
+        if (!(R == 5 && S == 5)) return false;
+        return plan_for(base, R, S, 2, pl, prefer_narrow) || plan_for(base, R, S, 1, pl, prefer_narrow);
+    }
     const bool multi = (R == 3 && S == 3) || (R == 1 && S == 1);
     if (!multi) return true;
     // 3x3 with at most 64 output channels and the packed filter: 256-pixel tiles (twice the workgroups per

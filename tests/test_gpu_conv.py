@@ -133,6 +133,8 @@ CASES = [
     # ... and on planes of a multiple of 4 pixels (operands through LDS): two images per workgroup with a
     # ragged last slice, ragged channel tiles, a last stage of one 16-pixel step
     (L("pw_lds_10x8", 264, 10, 8, 520, 1, 1), 41),
+    # 5x5 with at most 64 channels out (forward) and in (backward-data) on a 35-wide image: the smaller pixel tile
+    (L("5x5_c48_k64_w35", 48, 35, 35, 64, 5, 5, (1, 1), (2, 2)), 3),
 ]
 IDS = [c[0].name for c in CASES]
 
