@@ -545,8 +545,12 @@ hipError_t launch_tile_wgrad(const void *x, const void *dy, float *dw, const Con
                              hipStream_t st)
 {
     if (pointwise_wgrad_supported(g)) return launch_pointwise_wgrad(x, dy, dw, g, partial, st);
-    if (rows_wgrad_supported(g)) return launch_rows_wgrad(x, dy, dw, g, partial, st);
     WPlan pl;
+    // 5x5 on the row-stationary kernel is five launches, a filter row each: with partial sums and one reduction
+    // that is twice as fast as this file's kernel (measured 344 against 680 us on 96 -> 256 channels, 27x27),
+    // with five rounds of atomics it is slower (758 against 700 us)
+    const bool rows5 = g.R == 5 && !partial && make_wplan(g, &pl);
+    if (rows_wgrad_supported(g) && !rows5) return launch_rows_wgrad(x, dy, dw, g, partial, st);
     if (!make_wplan(g, &pl)) return hipErrorInvalidValue;
     const size_t nw = (size_t)g.K * g.C * g.R * g.S;
     const int slices = (int)pl.grid.z;

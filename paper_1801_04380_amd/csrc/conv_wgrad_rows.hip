@@ -58,6 +58,7 @@ struct RowsProblem {
     int ctiles, ktiles;
     int xcd_slices;             // > 0: one-dimensional grid, this many slices per XCD
     int nslices;                // with xcd_slices > 0: slice z takes the chunks z, z + nslices, ...
+    int Tfull, toff;            // taps of the whole filter; the first tap this launch computes (a launch may take some filter rows only)
 };
 
 struct __attribute__((packed, aligned(2))) U128u { u32x4 v; };
@@ -90,7 +91,7 @@ template <int d> __device__ inline bf16x8 shifted(const uint32_t (&D)[8])
     return r;
 }
 
-// S: filter width (1 or 3), RG: filter rows (= R), TM: the workgroup owns 2*TM*32 k, TH x TWP: chunk,
+// S: filter width (1, 3 or 5), RG: filter rows of this launch (R, or 1 of the 5 rows of a 5x5 filter), TM: the workgroup owns 2*TM*32 k, TH x TWP: chunk,
 // WIDE: 32-column tiles of an image whose width is a multiple of 8 (otherwise the chunk spans the
 // whole width, which may be ragged), TP: 2 = two sets of waves share the k x c tile and split the
 // chunk's 16-column groups between them (their accumulators are added in the epilogue): a second
@@ -293,9 +294,12 @@ wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
         auto load_raw = [&](Raw &r, int cg, int xr) {
             const bf16_t *src = xs + xr * LWX + cg * 16;
             r.m = *reinterpret_cast<const u32x4 *>(src);
-            if (S > 1) {
+            if (S == 3) {
                 r.lo = src[-1];
                 r.hi = src[8];
+            } else if (S == 5) {   // two elements on either side, as dwords
+                r.lo = *reinterpret_cast<const uint32_t *>(src - 2);
+                r.hi = *reinterpret_cast<const uint32_t *>(src + 8);
             }
         };
         auto load_a = [&](bf16x8 (&a)[WTM], int cg, int row) {
@@ -323,6 +327,14 @@ wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
                     b[0] = shifted<-1>(D);
                     b[1] = shifted<0>(D);
                     b[S - 1] = shifted<1>(D);
+                } else if (S == 5) {
+                    // elements -2 .. 9 of the row
+                    const uint32_t D[8] = {0, r.lo, r.m.x, r.m.y, r.m.z, r.m.w, r.hi, 0};
+                    b[0] = shifted<-2>(D);
+                    b[1] = shifted<-1>(D);
+                    b[2] = shifted<0>(D);
+                    b[S > 3 ? 3 : 0] = shifted<1>(D);
+                    b[S - 1] = shifted<2>(D);
                 } else {
                     __builtin_memcpy(&b[0], &r.m, 16);
                 }
@@ -397,7 +409,7 @@ wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
     // consecutive addresses of dw[k][c][r][s].
     constexpr int ROWS = KTB / 4, ROWLEN = CTB * T, EP = ROWLEN + 1;
     float *stage = reinterpret_cast<float *>(smem);
-    float *dst = out + (use_atomics ? (size_t)0 : (size_t)zslice * p.K * p.C * T);
+    float *dst = out + (use_atomics ? (size_t)0 : (size_t)zslice * p.K * p.C * p.Tfull);
 #pragma unroll
     for (int ps = 0; ps < 4; ++ps) {
 #pragma unroll
@@ -424,7 +436,7 @@ wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
             }
             __syncthreads();
         }
-        if (!use_atomics && p.C % CTB == 0 && (reinterpret_cast<uintptr_t>(dst) & 15) == 0) {
+        if (!use_atomics && p.Tfull == T && p.C % CTB == 0 && (reinterpret_cast<uintptr_t>(dst) & 15) == 0) {
             // whole rows of 64 c x T taps are contiguous and 16-byte aligned in dw: float4 stores
             constexpr int R4 = ROWLEN / 4;
             for (int e = tid; e < ROWS * R4; e += NT) {
@@ -443,7 +455,7 @@ wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
                 const int k = k0 + (rr >> 3) * 32 + 8 * ps + (rr & 7);
                 const int c = c0 + j / T;
                 if (k < p.K && c < p.C) {
-                    const size_t off = (size_t)k * p.C * T + (size_t)c0 * T + j;
+                    const size_t off = ((size_t)k * p.C + c) * p.Tfull + p.toff + (j - (j / T) * T);
                     const float val = stage[rr * EP + j];
                     if (use_atomics) unsafeAtomicAdd(dst + off, val);
                     else dst[off] = val;
@@ -474,7 +486,7 @@ constexpr size_t rows_smem()
 bool make_rplan(const ConvGeom &g, RPlan *pl)
 {
     if (!g.in_bf16 || g.sh != 1 || g.sw != 1) return false;
-    if (!((g.R == 3 && g.S == 3) || (g.R == 1 && g.S == 1))) return false;
+    if (!((g.R == 3 && g.S == 3) || (g.R == 1 && g.S == 1) || (g.R == 5 && g.S == 5))) return false;
     if (g.pw != (g.S - 1) / 2 || g.Q != g.W) return false;   // the column shift is built for "same" padding
     if (g.ph > g.R - 1 + 64) return false;
     const long long lim = 0x7fffffffLL;
@@ -482,6 +494,7 @@ bool make_rplan(const ConvGeom &g, RPlan *pl)
     if ((long long)g.N * g.C * g.H * g.W < 8 || (long long)g.N * g.K * g.P * g.Q < 8) return false;   // 16-byte loads
     RowsProblem p;
     p.N = g.N; p.C = g.C; p.H = g.H; p.W = g.W; p.K = g.K; p.P = g.P; p.Q = g.Q; p.R = g.R; p.ph = g.ph;
+    p.Tfull = g.R * g.S; p.toff = 0;
     bool wide;
     int TWP, TH;
     if (g.Q <= 16) { TWP = 16; TH = 8; wide = false; }
@@ -583,7 +596,17 @@ hipError_t launch_rows_wgrad(const void *x, const void *dy, float *dw, const Con
     const int atomics = (!partial && !direct_store) ? 1 : 0;
     const bf16_t *xs = static_cast<const bf16_t *>(x), *ds = static_cast<const bf16_t *>(dy);
     hipError_t e;
-    if (pl.S == 3) e = pl.TM == 2 ? launch_tm<3, 3, 2>(xs, ds, out, atomics, pl, st) : launch_tm<3, 3, 1>(xs, ds, out, atomics, pl, st);
+    if (pl.S == 5) {
+        // a filter row per launch (5 accumulator tiles; 25 would not fit the registers): row r0 of the filter meets
+        // input row p + r0 - ph, which is the one-row problem with its padding moved by r0
+        e = hipSuccess;
+        for (int r0 = 0; r0 < 5 && e == hipSuccess; ++r0) {
+            RPlan one = pl;
+            one.p.ph = g.ph - r0;
+            one.p.toff = r0 * 5;
+            e = pl.TM == 2 ? launch_tm<5, 1, 2>(xs, ds, out, atomics, one, st) : launch_tm<5, 1, 1>(xs, ds, out, atomics, one, st);
+        }
+    } else if (pl.S == 3) e = pl.TM == 2 ? launch_tm<3, 3, 2>(xs, ds, out, atomics, pl, st) : launch_tm<3, 3, 1>(xs, ds, out, atomics, pl, st);
     else e = pl.TM == 2 ? launch_tm<1, 1, 2>(xs, ds, out, atomics, pl, st) : launch_tm<1, 1, 1>(xs, ds, out, atomics, pl, st);
     if (e != hipSuccess) return e;
     if (partial) return launch_reduce_partials(partial, dw, nw, slices, false, st);

@@ -135,6 +135,9 @@ CASES = [
     (L("pw_lds_10x8", 264, 10, 8, 520, 1, 1), 41),
     # 5x5 with at most 64 channels out (forward) and in (backward-data) on a 35-wide image: the smaller pixel tile
     (L("5x5_c48_k64_w35", 48, 35, 35, 64, 5, 5, (1, 1), (2, 2)), 3),
+    # 5x5 backward-filter, a filter row per launch: 32-column tiles of a wide image, a narrow image, 136 output channels
+    (L("5x5_w40", 16, 12, 40, 40, 5, 5, (1, 1), (2, 2)), 2),
+    (L("5x5_w12_k136", 20, 9, 12, 136, 5, 5, (1, 1), (2, 2)), 5),
 ]
 IDS = [c[0].name for c in CASES]
 
