@@ -638,6 +638,25 @@ bn_relu_pool2_apply_kernel(const T *__restrict__ x, T *__restrict__ pooled, int3
 }
 
 // Sum over the BT threads of a workgroup (whole waves), the same value in every thread.
+// A vector at any element alignment (the hardware takes unaligned 16-byte accesses; the type tells the compiler).
+template <typename VT, typename T> __device__ inline VT load_any(const T *p)
+{
+    typedef uint32_t u32v __attribute__((ext_vector_type(sizeof(VT) / 4)));
+    struct __attribute__((packed, aligned(2))) U { u32v v; };
+    const u32v r = reinterpret_cast<const U *>(p)->v;
+    VT o;
+    __builtin_memcpy(&o, &r, sizeof(VT));
+    return o;
+}
+template <typename VT, typename T> __device__ inline void store_any(T *p, const VT &v)
+{
+    typedef uint32_t u32v __attribute__((ext_vector_type(sizeof(VT) / 4)));
+    struct __attribute__((packed, aligned(2))) U { u32v v; };
+    u32v r;
+    __builtin_memcpy(&r, &v, sizeof(VT));
+    reinterpret_cast<U *>(p)->v = r;
+}
+
 template <int BT> __device__ inline float block_sum(float v, float *red)
 {
     v = wave_sum(v);
@@ -655,7 +674,10 @@ template <int BT> __device__ inline float block_sum(float v, float *red)
 // units of PVB bytes of a row pair -- the workgroup has just streamed it, so it comes from the
 // caches -- and writes the pooled values and indices only (y is not touched; H, W as the pool
 // sees them).
-template <typename T, int VB, int NVMAX, int PVB, int BT>
+// RAG: planes whose size is not a multiple of the vector (7x7, 17x17, 35x35; at least one vector long): a plane
+// is ceil(HW / VE) vectors at any alignment, the last one moved back so that it ends with the plane; the elements
+// it shares with the one before count once in the sums and are written twice with the same value.
+template <typename T, int VB, int NVMAX, int PVB, int BT, bool RAG = false>
 __global__ void __launch_bounds__(BT)
 bn_fwd_fused_kernel(const T *__restrict__ x, T *__restrict__ y, const float *__restrict__ gamma,
                     const float *__restrict__ beta, float *__restrict__ mean, float *__restrict__ invstd,
@@ -666,7 +688,7 @@ bn_fwd_fused_kernel(const T *__restrict__ x, T *__restrict__ y, const float *__r
     typedef typename RawVec<VB>::type VT;
     __shared__ float red[16];
     const int c = blockIdx.x, tid = threadIdx.x;
-    const int vpp = HW / VE, nvec = N * vpp;
+    const int vpp = RAG ? (HW + VE - 1) / VE : HW / VE, nvec = N * vpp;
     VT v[NVMAX];
     float s = 0.f;
 #pragma unroll
@@ -674,11 +696,14 @@ bn_fwd_fused_kernel(const T *__restrict__ x, T *__restrict__ y, const float *__r
         const int i = tid + j * BT;
         if (i < nvec) {
             const int n = i / vpp, e = i - n * vpp;
-            v[j] = *reinterpret_cast<const VT *>(x + ((size_t)n * C + c) * HW + (size_t)e * VE);
+            const int eo = RAG ? min(e * VE, HW - VE) : e * VE, kf = e * VE - eo;   // kf: elements the vector before had
+            const T *src = x + ((size_t)n * C + c) * HW + (size_t)eo;
+            if constexpr (RAG) v[j] = load_any<VT>(src);
+            else v[j] = *reinterpret_cast<const VT *>(src);
             float f[VE];
             unpack<T, VB>(v[j], f);
 #pragma unroll
-            for (int k = 0; k < VE; ++k) s += f[k];
+            for (int k = 0; k < VE; ++k) s += (!RAG || k >= kf) ? f[k] : 0.f;
         }
     }
     const float M = (float)N * (float)HW;
@@ -686,11 +711,13 @@ bn_fwd_fused_kernel(const T *__restrict__ x, T *__restrict__ y, const float *__r
     float q = 0.f;
 #pragma unroll
     for (int j = 0; j < NVMAX; ++j) {
-        if (tid + j * BT < nvec) {
+        const int i = tid + j * BT;
+        if (i < nvec) {
+            const int e = i % vpp, kf = RAG ? e * VE - min(e * VE, HW - VE) : 0;
             float f[VE];
             unpack<T, VB>(v[j], f);
 #pragma unroll
-            for (int k = 0; k < VE; ++k) q += (f[k] - mu) * (f[k] - mu);
+            for (int k = 0; k < VE; ++k) q += (!RAG || k >= kf) ? (f[k] - mu) * (f[k] - mu) : 0.f;
         }
     }
     const float var = block_sum<BT>(q, red) / M;
@@ -708,16 +735,19 @@ bn_fwd_fused_kernel(const T *__restrict__ x, T *__restrict__ y, const float *__r
         const int i = tid + j * BT;
         if (i < nvec) {
             const int n = i / vpp, e = i - n * vpp;
+            const int eo = RAG ? min(e * VE, HW - VE) : e * VE;
             float f[VE];
             unpack<T, VB>(v[j], f);
 #pragma unroll
             for (int k = 0; k < VE; ++k) f[k] = act(bn_affine(f[k], mu, a, b), relu);
-            *reinterpret_cast<VT *>(y + ((size_t)n * C + c) * HW + (size_t)e * VE) = pack<T, VB>(f);
+            T *dst = y + ((size_t)n * C + c) * HW + (size_t)eo;
+            if constexpr (RAG) store_any<VT>(dst, pack<T, VB>(f));
+            else *reinterpret_cast<VT *>(dst) = pack<T, VB>(f);
         }
     }
 }
 
-template <typename T, int VB, int NVMAX, int BT>
+template <typename T, int VB, int NVMAX, int BT, bool RAG = false>
 __global__ void __launch_bounds__(BT)
 bn_bwd_fused_kernel(const T *__restrict__ x, const GradSrc<T> gs, const float *__restrict__ beta,
                     T *__restrict__ dx, const float *__restrict__ gamma, const float *__restrict__ mean,
@@ -728,7 +758,7 @@ bn_bwd_fused_kernel(const T *__restrict__ x, const GradSrc<T> gs, const float *_
     typedef typename RawVec<VB>::type VT;
     __shared__ float red[16];
     const int c = blockIdx.x, tid = threadIdx.x;
-    const int vpp = HW / VE, nvec = N * vpp;
+    const int vpp = RAG ? (HW + VE - 1) / VE : HW / VE, nvec = N * vpp;
     const float mu = mean[c], is = invstd[c];
     const bool relu = beta != nullptr;
     const float ga = gamma[c] * is, gb = relu ? beta[c] : 0.f;
@@ -739,12 +769,15 @@ bn_bwd_fused_kernel(const T *__restrict__ x, const GradSrc<T> gs, const float *_
         const int i = tid + j * BT;
         if (i < nvec) {
             const int n = i / vpp, e = i - n * vpp;
-            const size_t off = ((size_t)n * C + c) * HW + (size_t)e * VE;
-            xv[j] = *reinterpret_cast<const VT *>(x + off);
+            const int eo = RAG ? min(e * VE, HW - VE) : e * VE, kf = e * VE - eo;   // kf: elements the vector before had
+            const size_t off = ((size_t)n * C + c) * HW + (size_t)eo;
+            if constexpr (RAG) xv[j] = load_any<VT>(x + off);
+            else xv[j] = *reinterpret_cast<const VT *>(x + off);
             float f[VE], gr[VE];
             unpack<T, VB>(xv[j], f);
             if (gs.dy) {
-                gv[j] = *reinterpret_cast<const VT *>(gs.dy + off);
+                if constexpr (RAG) gv[j] = load_any<VT>(gs.dy + off);
+                else gv[j] = *reinterpret_cast<const VT *>(gs.dy + off);
                 unpack<T, VB>(gv[j], gr);
             } else {
                 grad_vec<T, VB>(gs, (size_t)n * C + c, e * VE, gr);
@@ -756,6 +789,7 @@ bn_bwd_fused_kernel(const T *__restrict__ x, const GradSrc<T> gs, const float *_
             if (relu || !gs.dy) gv[j] = pack<T, VB>(gr);
 #pragma unroll
             for (int k = 0; k < VE; ++k) {
+                if (RAG && k < kf) continue;
                 s1 += gr[k];
                 s2 += gr[k] * (f[k] - mu);
             }
@@ -771,13 +805,15 @@ bn_bwd_fused_kernel(const T *__restrict__ x, const GradSrc<T> gs, const float *_
         const int i = tid + j * BT;
         if (i < nvec) {
             const int n = i / vpp, e = i - n * vpp;
-            const size_t off = ((size_t)n * C + c) * HW + (size_t)e * VE;
+            const int eo = RAG ? min(e * VE, HW - VE) : e * VE;
+            const size_t off = ((size_t)n * C + c) * HW + (size_t)eo;
             float f[VE], gr[VE];
             unpack<T, VB>(xv[j], f);
             unpack<T, VB>(gv[j], gr);
 #pragma unroll
             for (int k = 0; k < VE; ++k) f[k] = k1 * (gr[k] - kb - (f[k] - mu) * kg);
-            *reinterpret_cast<VT *>(dx + off) = pack<T, VB>(f);
+            if constexpr (RAG) store_any<VT>(dx + off, pack<T, VB>(f));
+            else *reinterpret_cast<VT *>(dx + off) = pack<T, VB>(f);
         }
     }
 }
@@ -790,7 +826,7 @@ constexpr int BN_FUSED_NV1 = 32;  // single elements a thread can hold: planes o
 inline bool bn_fused_small(long long count, int nv) { return count <= 256LL * nv; }
 
 // Vector size in bytes for the one-pass kernels, 0 if they do not apply.
-template <typename T> int bn_fused_vb(const void *a, const void *b, const void *c3, int N, int HW)
+template <typename T> int bn_fused_vb(const void *a, const void *b, const void *c3, int N, int HW, bool ragged_ok = true)
 {
     const uintptr_t bits = reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b) | reinterpret_cast<uintptr_t>(c3);
     for (int vb = 16; vb >= 8; vb /= 2) {
@@ -799,6 +835,11 @@ template <typename T> int bn_fused_vb(const void *a, const void *b, const void *
         const long long nvec = (long long)N * (HW / ve);
         if (nvec <= 1024LL * BN_FUSED_NV) return vb;
     }
+    // planes that are no whole number of 8-byte vectors: 16-byte vectors at any alignment, the last one of a plane
+    // moved back (bf16, a given gradient tensor; reported as -16)
+    if (ragged_ok && sizeof(T) == 2 && HW % 4 != 0 && HW >= 8 && bits % sizeof(T) == 0 &&
+        (long long)N * ((HW + 7) / 8) <= 1024LL * BN_FUSED_NVS)   // longer channels: the two-pass kernels are faster (35x35: 2.9 against 2.6 TB/s)
+        return -16;
     if ((HW & 1) && bits % sizeof(T) == 0 && (long long)N * HW <= 1024LL * BN_FUSED_NV1) return (int)sizeof(T);
     return 0;
 }
@@ -1356,8 +1397,20 @@ hipError_t launch_bn_fwd(const void *x, const float *gamma, const float *beta, v
                 typedef typename std::remove_pointer<decltype(tag)>::type T;
                 // a channel of at most 4 vectors per thread goes to the build with 4 registers' worth of them
                 // (the sums run over the same elements in the same order either way)
-                const bool few = vb >= 8 && (long long)N * (HW / (vb / (int)sizeof(T))) <= 1024LL * BN_FUSED_NVS;
-                const long long cnt = (long long)N * (HW / (vb / (int)sizeof(T)));   // vectors per channel
+                const long long cnt = vb < 0 ? (long long)N * ((HW + 7) / 8)
+                                             : (long long)N * (HW / (vb / (int)sizeof(T)));   // vectors per channel
+                const bool few = (vb >= 8 || vb < 0) && cnt <= 1024LL * BN_FUSED_NVS;
+                if (vb < 0) {
+                    if (bn_fused_small(cnt, BN_FUSED_NVS))
+                        hipLaunchKernelGGL((bn_fwd_fused_kernel<T, 16, BN_FUSED_NVS, 0, 256, true>), dim3(C), dim3(256), 0, s,
+                                           (const T *)x, (T *)y, gamma, beta, mean, invstd, N, C, HW, eps, relu,
+                                           (T *)nullptr, (int32_t *)nullptr, 0, 0);
+                    else
+                        hipLaunchKernelGGL((bn_fwd_fused_kernel<T, 16, BN_FUSED_NVS, 0, 1024, true>), dim3(C), dim3(1024), 0, s,
+                                           (const T *)x, (T *)y, gamma, beta, mean, invstd, N, C, HW, eps, relu,
+                                           (T *)nullptr, (int32_t *)nullptr, 0, 0);
+                    return;
+                }
 #define SN_BN_FWD(VB_, NV_)                                                                                          \
     do {                                                                                                             \
         if (bn_fused_small(cnt, NV_))                                                                                \
@@ -1463,7 +1516,7 @@ hipError_t launch_bn_relu_pool2_fwd(const void *x, const float *gamma, const flo
     const int HW = H * W, pvb = bn_relu_pool2_vb(W, bf16);
     if (pvb == 0 || (H & 1)) return hipErrorInvalidValue;
     // the statistics come from the very kernels launch_bn_fwd picks for this shape
-    const int vb = bf16 ? bn_fused_vb<bf16_t>(x, nullptr, nullptr, N, HW) : bn_fused_vb<float>(x, nullptr, nullptr, N, HW);
+    const int vb = bf16 ? bn_fused_vb<bf16_t>(x, nullptr, nullptr, N, HW, false) : bn_fused_vb<float>(x, nullptr, nullptr, N, HW, false);
     if (vb != 0 && vb != 16) return hipErrorInvalidValue;
     if (vb)
         return by_dtype(bf16, [&](auto *tag) {
@@ -1516,13 +1569,23 @@ hipError_t launch_bn_bwd(const void *x, const void *dy, const float *relu_beta, 
                                (const T *)dy, relu_beta, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);
         });
     {
-        int vb = bf16 ? bn_fused_vb<bf16_t>(x, dy, dx, N, HW) : bn_fused_vb<float>(x, dy, dx, N, HW);
+        int vb = bf16 ? bn_fused_vb<bf16_t>(x, dy, dx, N, HW, dy != nullptr) : bn_fused_vb<float>(x, dy, dx, N, HW, false);
         if (vb)
             return by_dtype(bf16, [&](auto *tag) {
                 typedef typename std::remove_pointer<decltype(tag)>::type T;
                 const GradSrc<T> gs{(const T *)dy, (const T *)pool_g, pool_idx, pool_W, pool_W / 2, HW, HW / 4};
-                const bool few = vb >= 8 && (long long)N * (HW / (vb / (int)sizeof(T))) <= 1024LL * BN_FUSED_NVS;
-                const long long cnt = (long long)N * (HW / (vb / (int)sizeof(T)));   // vectors per channel
+                const long long cnt = vb < 0 ? (long long)N * ((HW + 7) / 8)
+                                             : (long long)N * (HW / (vb / (int)sizeof(T)));   // vectors per channel
+                const bool few = (vb >= 8 || vb < 0) && cnt <= 1024LL * BN_FUSED_NVS;
+                if (vb < 0) {
+                    if (bn_fused_small(cnt, BN_FUSED_NVS))
+                        hipLaunchKernelGGL((bn_bwd_fused_kernel<T, 16, BN_FUSED_NVS, 256, true>), dim3(C), dim3(256), 0, s,
+                                           (const T *)x, gs, relu_beta, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);
+                    else
+                        hipLaunchKernelGGL((bn_bwd_fused_kernel<T, 16, BN_FUSED_NVS, 1024, true>), dim3(C), dim3(1024), 0, s,
+                                           (const T *)x, gs, relu_beta, (T *)dx, gamma, mean, invstd, dgamma, dbeta, N, C, HW);
+                    return;
+                }
 #define SN_BN_BWD(VB_, NV_)                                                                                           \
     do {                                                                                                              \
         if (bn_fused_small(cnt, NV_))                                                                                 \

@@ -51,7 +51,10 @@ BN_SHAPES = [(2, 3, 5, 7), (4, 16, 14, 14), (3, 8, 7, 7), (2, 5, 35, 35), (8, 64
              # a channel that just fits the one-pass kernels' registers, one just past that, 8-byte vectors
              (32, 6, 56, 56), (34, 3, 56, 56), (32, 8, 14, 14),
              # long channels with many planes: whole slices and a ragged last one
-             (16, 64, 64, 64), (12, 130, 36, 40)]
+             (16, 64, 64, 64), (12, 130, 36, 40),
+             # planes that are no whole number of 8-byte vectors (16-byte vectors at any alignment, the last one of
+             # a plane moved back): 30 and 9 pixels, channels for the 256- and the 1024-thread build, the longest that takes this path and one past it
+             (3, 4, 5, 6), (5, 3, 3, 3), (64, 4, 17, 17), (26, 8, 35, 35), (27, 2, 35, 35)]
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
