@@ -91,7 +91,7 @@ template <int d> __device__ inline bf16x8 shifted(const uint32_t (&D)[8])
     return r;
 }
 
-// S: filter width (1, 3 or 5), RG: filter rows of this launch (R, or 1 of the 5 rows of a 5x5 filter), TM: the workgroup owns 2*TM*32 k, TH x TWP: chunk,
+// S: filter width (1, 3, 5 or 7), RG: filter rows of this launch (R, or 1 of the 5 rows of a 5x5 filter), TM: the workgroup owns 2*TM*32 k, TH x TWP: chunk,
 // WIDE: 32-column tiles of an image whose width is a multiple of 8 (otherwise the chunk spans the
 // whole width, which may be ragged), TP: 2 = two sets of waves share the k x c tile and split the
 // chunk's 16-column groups between them (their accumulators are added in the epilogue): a second
@@ -280,7 +280,7 @@ wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
     const int xlane = (wc * 32 + l32) * CP + APR + 8 * g;
     struct Raw {
         u32x4 m;
-        uint32_t lo, hi;
+        uint32_t lo, hi, lo2, hi2;   // the elements beside the octet (S = 7: lo2 and hi2 are the outer pairs)
     };
     constexpr int NCGW = NCG / TP;       // column groups per wave
     constexpr int NSTEP = NCGW * XROWS;  // (column group, x row) steps of a chunk, per wave
@@ -300,6 +300,9 @@ wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
             } else if (S == 5) {   // two elements on either side, as dwords
                 r.lo = *reinterpret_cast<const uint32_t *>(src - 2);
                 r.hi = *reinterpret_cast<const uint32_t *>(src + 8);
+            } else if (S == 7) {   // four on either side (three are used)
+                const uint2 lo = *reinterpret_cast<const uint2 *>(src - 4), hi = *reinterpret_cast<const uint2 *>(src + 8);
+                r.lo2 = lo.x; r.lo = lo.y; r.hi = hi.x; r.hi2 = hi.y;
             }
         };
         auto load_a = [&](bf16x8 (&a)[WTM], int cg, int row) {
@@ -335,6 +338,16 @@ wgrad_rows_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, f
                     b[2] = shifted<0>(D);
                     b[S > 3 ? 3 : 0] = shifted<1>(D);
                     b[S - 1] = shifted<2>(D);
+                } else if (S == 7) {
+                    // elements -4 .. 11 of the row
+                    const uint32_t D[8] = {r.lo2, r.lo, r.m.x, r.m.y, r.m.z, r.m.w, r.hi, r.hi2};
+                    b[0] = shifted<-3>(D);
+                    b[S > 1 ? 1 : 0] = shifted<-2>(D);
+                    b[S > 2 ? 2 : 0] = shifted<-1>(D);
+                    b[S > 3 ? 3 : 0] = shifted<0>(D);
+                    b[S > 4 ? 4 : 0] = shifted<1>(D);
+                    b[S > 5 ? 5 : 0] = shifted<2>(D);
+                    b[S - 1] = shifted<3>(D);
                 } else {
                     __builtin_memcpy(&b[0], &r.m, 16);
                 }
@@ -486,7 +499,9 @@ constexpr size_t rows_smem()
 bool make_rplan(const ConvGeom &g, RPlan *pl)
 {
     if (!g.in_bf16 || g.sh != 1 || g.sw != 1) return false;
-    if (!((g.R == 3 && g.S == 3) || (g.R == 1 && g.S == 1) || (g.R == 5 && g.S == 5))) return false;
+    if (!((g.R == 3 && g.S == 3) || (g.R == 1 && g.S == 1) || (g.R == 5 && g.S == 5) || (g.R == 7 && g.S == 1) ||
+          (g.R == 1 && g.S == 7)))
+        return false;
     if (g.pw != (g.S - 1) / 2 || g.Q != g.W) return false;   // the column shift is built for "same" padding
     if (g.ph > g.R - 1 + 64) return false;
     const long long lim = 0x7fffffffLL;
@@ -500,7 +515,7 @@ bool make_rplan(const ConvGeom &g, RPlan *pl)
     if (g.Q <= 16) { TWP = 16; TH = 8; wide = false; }
     else if (g.Q <= 32) { TWP = 32; TH = 4; wide = false; }
     else if (g.Q % 8 == 0) { TWP = 32; TH = 4; wide = true; }
-    else if (g.Q <= 64) { TWP = 64; TH = 2; wide = false; }
+    else if (g.Q <= 64 && g.R < 7) { TWP = 64; TH = 2; wide = false; }
     else return false;
     p.ncoltiles = wide ? (g.Q + TWP - 1) / TWP : 1;
     p.rowchunks = (g.P + TH - 1) / TH;
@@ -555,7 +570,11 @@ template <int S, int RG, int TM>
 hipError_t launch_tm(const bf16_t *x, const bf16_t *dy, float *out, int atomics, const RPlan &pl, hipStream_t st)
 {
     if (pl.TWP == 16) return launch_shape<S, RG, TM, 8, 16, false>(x, dy, out, atomics, pl, st);
-    if (pl.TWP == 64) return launch_shape<S, RG, TM, 2, 64, false>(x, dy, out, atomics, pl, st);
+    if (pl.TWP == 64) {
+        // seven filter rows of 64-column chunks do not fit LDS (make_rplan does not plan them)
+        if constexpr (rows_smem<S, RG, TM, 2, 64>() <= 160 * 1024) return launch_shape<S, RG, TM, 2, 64, false>(x, dy, out, atomics, pl, st);
+        else return hipErrorInvalidValue;
+    }
     if (TM == 1 && pl.TP == 2) {
         if (pl.wide) return launch_shape<S, RG, 1, 4, 32, true, 2>(x, dy, out, atomics, pl, st);
         return launch_shape<S, RG, 1, 4, 32, false, 2>(x, dy, out, atomics, pl, st);
@@ -596,7 +615,11 @@ hipError_t launch_rows_wgrad(const void *x, const void *dy, float *dw, const Con
     const int atomics = (!partial && !direct_store) ? 1 : 0;
     const bf16_t *xs = static_cast<const bf16_t *>(x), *ds = static_cast<const bf16_t *>(dy);
     hipError_t e;
-    if (pl.S == 5) {
+    if (g.R == 7 && g.S == 1) {
+        e = pl.TM == 2 ? launch_tm<1, 7, 2>(xs, ds, out, atomics, pl, st) : launch_tm<1, 7, 1>(xs, ds, out, atomics, pl, st);
+    } else if (g.R == 1 && g.S == 7) {
+        e = pl.TM == 2 ? launch_tm<7, 1, 2>(xs, ds, out, atomics, pl, st) : launch_tm<7, 1, 1>(xs, ds, out, atomics, pl, st);
+    } else if (pl.S == 5) {
         // a filter row per launch (5 accumulator tiles; 25 would not fit the registers): row r0 of the filter meets
         // input row p + r0 - ph, which is the one-row problem with its padding moved by r0
         e = hipSuccess;

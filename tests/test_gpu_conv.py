@@ -138,6 +138,11 @@ CASES = [
     # 5x5 backward-filter, a filter row per launch: 32-column tiles of a wide image, a narrow image, 136 output channels
     (L("5x5_w40", 16, 12, 40, 40, 5, 5, (1, 1), (2, 2)), 2),
     (L("5x5_w12_k136", 20, 9, 12, 136, 5, 5, (1, 1), (2, 2)), 5),
+    # 1x7 and 7x1 backward-filter on the row-stationary kernel: 32-column tiles of a wide image, 136 output channels
+    (L("1x7_w40", 24, 10, 40, 40, 1, 7, (1, 1), (0, 3)), 2),
+    (L("7x1_w40", 24, 10, 40, 40, 7, 1, (1, 1), (3, 0)), 2),
+    (L("1x7_w12_k136", 20, 9, 12, 136, 1, 7, (1, 1), (0, 3)), 5),
+    (L("7x1_w12_k136", 20, 9, 12, 136, 7, 1, (1, 1), (3, 0)), 5),
 ]
 IDS = [c[0].name for c in CASES]
 
