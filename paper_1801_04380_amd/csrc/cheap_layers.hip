@@ -1216,23 +1216,38 @@ maxpool3s2_bwd_kernel(const T *__restrict__ dy, const int32_t *__restrict__ idx,
 // another HALF ahead for x, with r, s^(-beta) and dy of the channels in between in registers;
 // x and dy are read once, the forward output is not needed.  The channel loops are unrolled so
 // that the loads of several channels are in flight at once: nothing else hides their latency.
-template <typename T, int VEC> struct LrnIo {
+// RAG: planes that are no whole number of vectors (55x55, 27x27): a plane is ceil(HW / VEC) vectors at the
+// element's own alignment, the last one moved back so that it ends with the plane; the positions it shares
+// with the vector before are computed and written twice, with the same values.
+template <typename T, int VEC, bool RAG = false> struct LrnIo {
     static constexpr int VB = VEC * (int)sizeof(T);
+    typedef typename RawVec<VB>::type VT;
+    struct __attribute__((packed, aligned(sizeof(T)))) Loose { uint32_t w[VB / 4 > 0 ? VB / 4 : 1]; };
     __device__ static void load(const T *p, float (&f)[VEC])
     {
         if constexpr (VEC == 1) f[0] = ld<T>(p);
-        else unpack<T, VB>(*reinterpret_cast<const typename RawVec<VB>::type *>(p), f);
+        else if constexpr (RAG) {
+            const Loose l = *reinterpret_cast<const Loose *>(p);
+            VT v;
+            __builtin_memcpy(&v, &l, VB);
+            unpack<T, VB>(v, f);
+        } else unpack<T, VB>(*reinterpret_cast<const VT *>(p), f);
     }
     __device__ static void store(T *p, const float (&f)[VEC])
     {
         if constexpr (VEC == 1) st(p, f[0]);
-        else *reinterpret_cast<typename RawVec<VB>::type *>(p) = pack<T, VB>(f);
+        else if constexpr (RAG) {
+            const VT v = pack<T, VB>(f);
+            Loose l;
+            __builtin_memcpy(&l, &v, VB);
+            *reinterpret_cast<Loose *>(p) = l;
+        } else *reinterpret_cast<VT *>(p) = pack<T, VB>(f);
     }
 };
 
 __device__ inline float pow_neg(float s, float beta) { return __builtin_amdgcn_exp2f(-beta * __builtin_amdgcn_logf(s)); }
 
-template <typename T, int VEC, int HALF>
+template <typename T, int VEC, int HALF, bool RAG = false>
 __global__ void __launch_bounds__(256)
 lrn_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, int C, int HW, int vpp, size_t total, float a_n,
                float beta, float k, int cc)
@@ -1241,7 +1256,8 @@ lrn_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, int C, int HW, int vp
     constexpr int SIZE = 2 * HALF + 1;
     const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (t >= total) return;
-    const size_t n = t / vpp, off = n * (size_t)C * HW + (t - n * vpp) * VEC;
+    const size_t n = t / vpp;
+    const size_t off = n * (size_t)C * HW + (RAG ? min((int)(t - n * vpp) * VEC, HW - VEC) : (int)(t - n * vpp) * VEC);
     float xr[SIZE][VEC];   // after channel m has been pushed: xr[i] = channel m - (SIZE - 1) + i, zeros outside [0, C)
 #pragma unroll
     for (int i = 0; i < SIZE; ++i)
@@ -1254,7 +1270,7 @@ lrn_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, int C, int HW, int vp
 #pragma unroll
             for (int v = 0; v < VEC; ++v) xr[i][v] = xr[i + 1][v];
         if (m >= 0 && m < C) {
-            LrnIo<T, VEC>::load(x + off + (size_t)m * HW, xr[SIZE - 1]);
+            LrnIo<T, VEC, RAG>::load(x + off + (size_t)m * HW, xr[SIZE - 1]);
         } else {
 #pragma unroll
             for (int v = 0; v < VEC; ++v) xr[SIZE - 1][v] = 0.f;
@@ -1269,11 +1285,11 @@ lrn_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, int C, int HW, int vp
             for (int i = 0; i < SIZE; ++i) sum = __builtin_fmaf(xr[i][v], xr[i][v], sum);
             out[v] = xr[HALF][v] * pow_neg(__builtin_fmaf(a_n, sum, k), beta);
         }
-        LrnIo<T, VEC>::store(y + off + (size_t)c * HW, out);
+        LrnIo<T, VEC, RAG>::store(y + off + (size_t)c * HW, out);
     }
 }
 
-template <typename T, int VEC, int HALF>
+template <typename T, int VEC, int HALF, bool RAG = false>
 __global__ void __launch_bounds__(256)
 lrn_bwd_kernel(const T *__restrict__ x, const T *__restrict__ dy, T *__restrict__ dx, int C, int HW, int vpp,
                size_t total, float a_n, float beta, float k, int cc)
@@ -1282,7 +1298,8 @@ lrn_bwd_kernel(const T *__restrict__ x, const T *__restrict__ dy, T *__restrict_
     constexpr int SIZE = 2 * HALF + 1, H1 = HALF + 1;
     const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (t >= total) return;
-    const size_t n = t / vpp, off = n * (size_t)C * HW + (t - n * vpp) * VEC;
+    const size_t n = t / vpp;
+    const size_t off = n * (size_t)C * HW + (RAG ? min((int)(t - n * vpp) * VEC, HW - VEC) : (int)(t - n * vpp) * VEC);
     const float coef = 2.f * a_n * beta;
     float xr[SIZE][VEC], rr[SIZE][VEC];   // x of channels m - 2 HALF .. m; r of channels j - 2 HALF .. j (j = m - HALF)
     float pr[H1][VEC], gr[H1][VEC];       // s^(-beta) and dy of channels j - HALF .. j
@@ -1304,11 +1321,11 @@ lrn_bwd_kernel(const T *__restrict__ x, const T *__restrict__ dy, T *__restrict_
             xr[SIZE - 1][v] = 0.f;
             rr[SIZE - 1][v] = pr[H1 - 1][v] = gr[H1 - 1][v] = 0.f;
         }
-        if (m >= 0 && m < C) LrnIo<T, VEC>::load(x + off + (size_t)m * HW, xr[SIZE - 1]);
+        if (m >= 0 && m < C) LrnIo<T, VEC, RAG>::load(x + off + (size_t)m * HW, xr[SIZE - 1]);
         const int j = m - HALF;   // the channel whose window is complete: x_j = xr[HALF]
         if (j < 0) continue;
         if (j < C) {
-            LrnIo<T, VEC>::load(dy + off + (size_t)j * HW, gr[H1 - 1]);
+            LrnIo<T, VEC, RAG>::load(dy + off + (size_t)j * HW, gr[H1 - 1]);
 #pragma unroll
             for (int v = 0; v < VEC; ++v) {
                 float sum = 0.f;
@@ -1329,7 +1346,7 @@ lrn_bwd_kernel(const T *__restrict__ x, const T *__restrict__ dy, T *__restrict_
             for (int i = 0; i < SIZE; ++i) acc += rr[i][v];
             out[v] = gr[0][v] * pr[0][v] - coef * xr[0][v] * acc;
         }
-        LrnIo<T, VEC>::store(dx + off + (size_t)c * HW, out);
+        LrnIo<T, VEC, RAG>::store(dx + off + (size_t)c * HW, out);
     }
 }
 
@@ -1618,11 +1635,11 @@ hipError_t launch_bn_bwd(const void *x, const void *dy, const float *relu_beta, 
     });
 }
 
-template <typename T, int VEC>
+template <typename T, int VEC, bool RAG = false>
 hipError_t lrn_launch(bool bwd, const void *x, const void *dy, void *out, int N, int C, int HW, int half, float a_n,
                       float beta, float k, hipStream_t s)
 {
-    const int vpp = HW / VEC;
+    const int vpp = RAG ? (HW + VEC - 1) / VEC : HW / VEC;
     const size_t total = (size_t)N * vpp;
     // A thread walks its channels one after the other: with few positions the channels are split over
     // blockIdx.y (each part re-reads the HALF or 2 HALF channels beside it) until there are enough threads.
@@ -1634,9 +1651,9 @@ hipError_t lrn_launch(bool bwd, const void *x, const void *dy, void *out, int N,
     const dim3 grid((unsigned)((total + 255) / 256), (unsigned)ny), block(256);
 #define SN_LRN(H_)                                                                                                  \
     case H_:                                                                                                        \
-        if (bwd) hipLaunchKernelGGL((lrn_bwd_kernel<T, VEC, H_>), grid, block, 0, s, (const T *)x, (const T *)dy,  \
+        if (bwd) hipLaunchKernelGGL((lrn_bwd_kernel<T, VEC, H_, RAG>), grid, block, 0, s, (const T *)x, (const T *)dy,  \
                                     (T *)out, C, HW, vpp, total, a_n, beta, k, cc);                                \
-        else hipLaunchKernelGGL((lrn_fwd_kernel<T, VEC, H_>), grid, block, 0, s, (const T *)x, (T *)out, C, HW,    \
+        else hipLaunchKernelGGL((lrn_fwd_kernel<T, VEC, H_, RAG>), grid, block, 0, s, (const T *)x, (T *)out, C, HW,    \
                                 vpp, total, a_n, beta, k, cc);                                                      \
         break;
     switch (half) {
@@ -1652,11 +1669,13 @@ hipError_t launch_lrn(const void *x, const void *dy, void *out, int N, int C, in
                       float beta, float k, int bf16, hipStream_t s)
 {
     if (size < 1 || size > 9 || !(size & 1)) return hipErrorInvalidValue;
-    const bool bwd = dy != nullptr, vec = HW % 4 == 0;
+    const bool bwd = dy != nullptr, vec = HW % 4 == 0, rag = !vec && HW >= 4;
     const float a_n = alpha / (float)size;
     if (bf16) return vec ? lrn_launch<bf16_t, 4>(bwd, x, dy, out, N, C, HW, size / 2, a_n, beta, k, s)
+                   : rag ? lrn_launch<bf16_t, 4, true>(bwd, x, dy, out, N, C, HW, size / 2, a_n, beta, k, s)
                          : lrn_launch<bf16_t, 1>(bwd, x, dy, out, N, C, HW, size / 2, a_n, beta, k, s);
     return vec ? lrn_launch<float, 4>(bwd, x, dy, out, N, C, HW, size / 2, a_n, beta, k, s)
+         : rag ? lrn_launch<float, 4, true>(bwd, x, dy, out, N, C, HW, size / 2, a_n, beta, k, s)
                : lrn_launch<float, 1>(bwd, x, dy, out, N, C, HW, size / 2, a_n, beta, k, s);
 }
 
