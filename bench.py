@@ -10,7 +10,8 @@ passes, sn_bn_relu_bwd; where a 2x2 pool follows, BN + ReLU + pool are one call
 each way, sn_bn_relu_pool2_fwd / _bwd; and where a channel is too large for BN's
 one-pass kernel the CONV leaves the batch statistics of its output,
 sn_conv2d_fwd_bn_stats, and BN is one pass from them, sn_bn_apply /
-sn_bn_relu_pool2_apply), then their backward
+sn_bn_relu_pool2_apply; without BN, a ReLU and the LRN after it are one call each
+way, sn_relu_lrn_fwd / _bwd), then their backward
 passes, CONV backward-data and CONV backward-filter, each CONV planned under the
 given workspace budget.  Inputs are resident in HBM before the timed
 region; autotuning happens before it too.
@@ -214,14 +215,22 @@ def build_ops(cfg_no, budget, autotune, fuse, plan_file=None):
                                   lambda y=y, ga=gamma, be=beta, o=ybn, m=mean, i=invstd: sn.sn_bn_fwd(y, ga, be, o, m, i),
                                   nbytes=2 * E * b))
                 act_in = ybn
-            cheap_f.append(Op("relu_fwd", layer.name, lambda s=act_in, o=a: sn.sn_relu_fwd(s, o), nbytes=2 * E * b))
+            # ReLU and the LRN after it in one pass each way (no BN in between): the ReLU output is never written
+            relu_lrn = bool(fuse and layer.lrn and not cfg["bn"])
+            if not relu_lrn:
+                cheap_f.append(Op("relu_fwd", layer.name, lambda s=act_in, o=a: sn.sn_relu_fwd(s, o), nbytes=2 * E * b))
         g_a = torch.empty_like(y)
         pool_src, pool_grad = a, g_a
+        relu_lrn = bool(fuse and layer.lrn and not cfg["bn"] and not pool_pair)
         if layer.lrn and not pool_pair:
             # LRN between the ReLU and the pool; its backward needs its input and the gradient only
             a_l, g_l = torch.empty_like(y), torch.empty_like(y)
-            cheap_f.append(Op("lrn_fwd", layer.name, lambda s=a, o=a_l, p=layer.lrn: sn.sn_lrn_fwd(s, o, *p),
-                              nbytes=2 * E * b))
+            if relu_lrn:
+                cheap_f.append(Op("relu_lrn_fwd", layer.name, lambda s=y, o=a_l, p=layer.lrn: sn.sn_relu_lrn_fwd(s, o, *p),
+                                  nbytes=2 * E * b))
+            else:
+                cheap_f.append(Op("lrn_fwd", layer.name, lambda s=a, o=a_l, p=layer.lrn: sn.sn_lrn_fwd(s, o, *p),
+                                  nbytes=2 * E * b))
             pool_src, pool_grad = a_l, g_l
         if layer.pool:
             kernel, stride = layer.pool
@@ -249,7 +258,10 @@ def build_ops(cfg_no, budget, autotune, fuse, plan_file=None):
                               nbytes=Eo * (b + 4) + E * b))
         else:
             pool_grad.copy_(dy)
-        if layer.lrn and not pool_pair:
+        if relu_lrn:
+            cheap_b.append(Op("relu_lrn_bwd", layer.name,
+                              lambda s=y, g=g_l, o=dy, p=layer.lrn: sn.sn_relu_lrn_bwd(s, g, o, *p), nbytes=3 * E * b))
+        elif layer.lrn and not pool_pair:
             cheap_b.append(Op("lrn_bwd", layer.name,
                               lambda s=a, g=g_l, o=g_a, p=layer.lrn: sn.sn_lrn_bwd(s, g, o, *p), nbytes=3 * E * b))
         if pool_pair:
@@ -260,6 +272,8 @@ def build_ops(cfg_no, budget, autotune, fuse, plan_file=None):
             cheap_b.append(Op("bn_relu_bwd", layer.name,
                               lambda y=y, g=g_a, ga=gamma, be=beta, m=mean, i=invstd, o=dy, dg=dgamma, db=dbeta:
                               sn.sn_bn_relu_bwd(y, g, ga, be, m, i, o, dg, db), nbytes=3 * E * b))
+        elif relu_lrn:
+            pass
         else:
             relu_grad_out = g_bn if cfg["bn"] else dy
             cheap_b.append(Op("relu_bwd", layer.name, lambda s=a, g=g_a, o=relu_grad_out: sn.sn_relu_bwd(s, g, o),

@@ -308,6 +308,17 @@ sn_status sn_lrn_fwd(const void *x, void *y, int N, int C, int H, int W,
 sn_status sn_lrn_bwd(const void *x, const void *dy, void *dx, int N, int C, int H, int W,
                      int size, float alpha, float beta, float k, sn_dtype dtype, sn_stream stream);
 
+/* ReLU and the LRN after it in one pass (the AlexNet-style chain CONV -> ReLU -> LRN; Sec. 3.4: one tensor
+ * less to keep or to replay, the ReLU output is never written):
+ *   forward   y = LRN(max(x, 0)) with the LRN of sn_lrn_fwd;
+ *   backward  dx = (x > 0) ? g : 0 with g = the dx of sn_lrn_bwd on (max(x, 0), dy),
+ * i.e. exactly what sn_relu_fwd + sn_lrn_fwd and sn_lrn_bwd + sn_relu_bwd give, from x (the CONV output) alone.
+ * Arguments, layouts and errors as for sn_lrn_fwd / sn_lrn_bwd. */
+sn_status sn_relu_lrn_fwd(const void *x, void *y, int N, int C, int H, int W,
+                          int size, float alpha, float beta, float k, sn_dtype dtype, sn_stream stream);
+sn_status sn_relu_lrn_bwd(const void *x, const void *dy, void *dx, int N, int C, int H, int W,
+                          int size, float alpha, float beta, float k, sn_dtype dtype, sn_stream stream);
+
 /* Ceilings of the device for the roofline figures (the fractions the benchmark reports are quoted
  * against the datasheet peaks; these are what this GPU reaches in the plainest possible kernel):
  *  MFMA_BF16 / MFMA_F32  a register-resident loop of 32x32x16 bf16 / 32x32x2 fp32 MFMAs on every

@@ -45,6 +45,8 @@ SIGNATURES = {
     "sn_bn_relu_pool2_bwd": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp]),
     "sn_lrn_fwd": (_i, [_vp, _vp, _i, _i, _i, _i, _i, ctypes.c_float, ctypes.c_float, ctypes.c_float, _i, _vp]),
     "sn_lrn_bwd": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, ctypes.c_float, ctypes.c_float, ctypes.c_float, _i, _vp]),
+    "sn_relu_lrn_fwd": (_i, [_vp, _vp, _i, _i, _i, _i, _i, ctypes.c_float, ctypes.c_float, ctypes.c_float, _i, _vp]),
+    "sn_relu_lrn_bwd": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, ctypes.c_float, ctypes.c_float, ctypes.c_float, _i, _vp]),
     "sn_measure_ceiling": (_i, [_i, _vp, _sz, _i, _vp, ctypes.POINTER(ctypes.c_double)]),
     "sn_maxpool_fwd": (_i, [_vp, _vp, _vp] + [_i] * 10 + [_i, _vp]),
     "sn_maxpool_bwd": (_i, [_vp, _vp, _vp] + [_i] * 10 + [_i, _vp]),

@@ -17,7 +17,7 @@ __all__ = [
     "sn_conv2d_fwd", "sn_conv2d_bwd_data", "sn_conv2d_bwd_filter", "sn_conv2d_fwd_noalloc",
     "SN_NOALLOC_SCRATCH_BYTES",
     "sn_conv_bn_stats_scratch_bytes", "sn_conv2d_fwd_bn_stats", "sn_bn_apply", "sn_bn_relu_pool2_apply",
-    "sn_relu_fwd", "sn_relu_bwd", "sn_bn_fwd", "sn_bn_relu_fwd", "sn_bn_bwd", "sn_bn_relu_bwd", "sn_bn_relu_pool2_fwd", "sn_bn_relu_pool2_bwd", "sn_lrn_fwd", "sn_lrn_bwd", "sn_maxpool_fwd", "sn_maxpool_bwd",
+    "sn_relu_fwd", "sn_relu_bwd", "sn_bn_fwd", "sn_bn_relu_fwd", "sn_bn_bwd", "sn_bn_relu_bwd", "sn_bn_relu_pool2_fwd", "sn_bn_relu_pool2_bwd", "sn_lrn_fwd", "sn_lrn_bwd", "sn_relu_lrn_fwd", "sn_relu_lrn_bwd", "sn_maxpool_fwd", "sn_maxpool_bwd",
     "sn_measure_ceiling", "SN_CEIL_MFMA_BF16", "SN_CEIL_MFMA_F32", "SN_CEIL_COPY", "SN_CEIL_READ", "SN_CEIL_WRITE", "SN_CEIL_MFMA_BF16_FED",
 ]
 
@@ -215,6 +215,18 @@ def sn_lrn_bwd(x, dy, dx, size=5, alpha=1e-4, beta=0.75, k=2.0):
     N, C, H, W = x.shape
     _check("sn_lrn_bwd", load().sn_lrn_bwd(_ptr(x), _ptr(dy), _ptr(dx), N, C, H, W, size, alpha, beta, k,
                                            _dtype_code(x), _stream()))
+
+
+def sn_relu_lrn_fwd(x, y, size=5, alpha=1e-4, beta=0.75, k=2.0):
+    N, C, H, W = x.shape
+    _check("sn_relu_lrn_fwd", load().sn_relu_lrn_fwd(_ptr(x), _ptr(y), N, C, H, W, size, alpha, beta, k,
+                                                     _dtype_code(x), _stream()))
+
+
+def sn_relu_lrn_bwd(x, dy, dx, size=5, alpha=1e-4, beta=0.75, k=2.0):
+    N, C, H, W = x.shape
+    _check("sn_relu_lrn_bwd", load().sn_relu_lrn_bwd(_ptr(x), _ptr(dy), _ptr(dx), N, C, H, W, size, alpha, beta, k,
+                                                     _dtype_code(x), _stream()))
 
 
 SN_CEIL_MFMA_BF16, SN_CEIL_MFMA_F32, SN_CEIL_COPY, SN_CEIL_READ, SN_CEIL_WRITE, SN_CEIL_MFMA_BF16_FED = 0, 1, 2, 3, 4, 5

@@ -1247,7 +1247,7 @@ template <typename T, int VEC, bool RAG = false> struct LrnIo {
 
 __device__ inline float pow_neg(float s, float beta) { return __builtin_amdgcn_exp2f(-beta * __builtin_amdgcn_logf(s)); }
 
-template <typename T, int VEC, int HALF, bool RAG = false>
+template <typename T, int VEC, int HALF, bool RAG = false, bool RELU = false>
 __global__ void __launch_bounds__(256)
 lrn_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, int C, int HW, int vpp, size_t total, float a_n,
                float beta, float k, int cc)
@@ -1271,6 +1271,10 @@ lrn_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, int C, int HW, int vp
             for (int v = 0; v < VEC; ++v) xr[i][v] = xr[i + 1][v];
         if (m >= 0 && m < C) {
             LrnIo<T, VEC, RAG>::load(x + off + (size_t)m * HW, xr[SIZE - 1]);
+            if (RELU) {   // the layer's input is the ReLU of x, which is never stored
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) xr[SIZE - 1][v] = act(xr[SIZE - 1][v], 1);
+            }
         } else {
 #pragma unroll
             for (int v = 0; v < VEC; ++v) xr[SIZE - 1][v] = 0.f;
@@ -1289,7 +1293,7 @@ lrn_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, int C, int HW, int vp
     }
 }
 
-template <typename T, int VEC, int HALF, bool RAG = false>
+template <typename T, int VEC, int HALF, bool RAG = false, bool RELU = false>
 __global__ void __launch_bounds__(256)
 lrn_bwd_kernel(const T *__restrict__ x, const T *__restrict__ dy, T *__restrict__ dx, int C, int HW, int vpp,
                size_t total, float a_n, float beta, float k, int cc)
@@ -1321,7 +1325,13 @@ lrn_bwd_kernel(const T *__restrict__ x, const T *__restrict__ dy, T *__restrict_
             xr[SIZE - 1][v] = 0.f;
             rr[SIZE - 1][v] = pr[H1 - 1][v] = gr[H1 - 1][v] = 0.f;
         }
-        if (m >= 0 && m < C) LrnIo<T, VEC, RAG>::load(x + off + (size_t)m * HW, xr[SIZE - 1]);
+        if (m >= 0 && m < C) {
+            LrnIo<T, VEC, RAG>::load(x + off + (size_t)m * HW, xr[SIZE - 1]);
+            if (RELU) {   // LRN saw max(x, 0): negative and zero x both count as 0, and their dx is 0 below
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) xr[SIZE - 1][v] = act(xr[SIZE - 1][v], 1);
+            }
+        }
         const int j = m - HALF;   // the channel whose window is complete: x_j = xr[HALF]
         if (j < 0) continue;
         if (j < C) {
@@ -1345,6 +1355,7 @@ lrn_bwd_kernel(const T *__restrict__ x, const T *__restrict__ dy, T *__restrict_
 #pragma unroll
             for (int i = 0; i < SIZE; ++i) acc += rr[i][v];
             out[v] = gr[0][v] * pr[0][v] - coef * xr[0][v] * acc;
+            if (RELU && !(xr[0][v] > 0.f)) out[v] = 0.f;   // the ReLU's gate: x > 0 (xr holds max(x, 0))
         }
         LrnIo<T, VEC, RAG>::store(dx + off + (size_t)c * HW, out);
     }
@@ -1635,7 +1646,7 @@ hipError_t launch_bn_bwd(const void *x, const void *dy, const float *relu_beta, 
     });
 }
 
-template <typename T, int VEC, bool RAG = false>
+template <typename T, int VEC, bool RAG = false, bool RELU = false>
 hipError_t lrn_launch(bool bwd, const void *x, const void *dy, void *out, int N, int C, int HW, int half, float a_n,
                       float beta, float k, hipStream_t s)
 {
@@ -1651,9 +1662,9 @@ hipError_t lrn_launch(bool bwd, const void *x, const void *dy, void *out, int N,
     const dim3 grid((unsigned)((total + 255) / 256), (unsigned)ny), block(256);
 #define SN_LRN(H_)                                                                                                  \
     case H_:                                                                                                        \
-        if (bwd) hipLaunchKernelGGL((lrn_bwd_kernel<T, VEC, H_, RAG>), grid, block, 0, s, (const T *)x, (const T *)dy,  \
+        if (bwd) hipLaunchKernelGGL((lrn_bwd_kernel<T, VEC, H_, RAG, RELU>), grid, block, 0, s, (const T *)x, (const T *)dy,  \
                                     (T *)out, C, HW, vpp, total, a_n, beta, k, cc);                                \
-        else hipLaunchKernelGGL((lrn_fwd_kernel<T, VEC, H_, RAG>), grid, block, 0, s, (const T *)x, (T *)out, C, HW,    \
+        else hipLaunchKernelGGL((lrn_fwd_kernel<T, VEC, H_, RAG, RELU>), grid, block, 0, s, (const T *)x, (T *)out, C, HW,    \
                                 vpp, total, a_n, beta, k, cc);                                                      \
         break;
     switch (half) {
@@ -1665,18 +1676,27 @@ hipError_t lrn_launch(bool bwd, const void *x, const void *dy, void *out, int N,
 }
 
 // size: odd, at most 9.  dy == nullptr: forward (out = y); else backward (out = dx).
-hipError_t launch_lrn(const void *x, const void *dy, void *out, int N, int C, int HW, int size, float alpha,
-                      float beta, float k, int bf16, hipStream_t s)
+// relu != 0: the layer's input is max(x, 0) (forward), and dx is also gated by x > 0 (backward).
+template <bool RELU>
+static hipError_t lrn_dispatch(const void *x, const void *dy, void *out, int N, int C, int HW, int size, float alpha,
+                               float beta, float k, int bf16, hipStream_t s)
 {
-    if (size < 1 || size > 9 || !(size & 1)) return hipErrorInvalidValue;
     const bool bwd = dy != nullptr, vec = HW % 4 == 0, rag = !vec && HW >= 4;
     const float a_n = alpha / (float)size;
-    if (bf16) return vec ? lrn_launch<bf16_t, 4>(bwd, x, dy, out, N, C, HW, size / 2, a_n, beta, k, s)
-                   : rag ? lrn_launch<bf16_t, 4, true>(bwd, x, dy, out, N, C, HW, size / 2, a_n, beta, k, s)
-                         : lrn_launch<bf16_t, 1>(bwd, x, dy, out, N, C, HW, size / 2, a_n, beta, k, s);
-    return vec ? lrn_launch<float, 4>(bwd, x, dy, out, N, C, HW, size / 2, a_n, beta, k, s)
-         : rag ? lrn_launch<float, 4, true>(bwd, x, dy, out, N, C, HW, size / 2, a_n, beta, k, s)
-               : lrn_launch<float, 1>(bwd, x, dy, out, N, C, HW, size / 2, a_n, beta, k, s);
+    if (bf16) return vec ? lrn_launch<bf16_t, 4, false, RELU>(bwd, x, dy, out, N, C, HW, size / 2, a_n, beta, k, s)
+                   : rag ? lrn_launch<bf16_t, 4, true, RELU>(bwd, x, dy, out, N, C, HW, size / 2, a_n, beta, k, s)
+                         : lrn_launch<bf16_t, 1, false, RELU>(bwd, x, dy, out, N, C, HW, size / 2, a_n, beta, k, s);
+    return vec ? lrn_launch<float, 4, false, RELU>(bwd, x, dy, out, N, C, HW, size / 2, a_n, beta, k, s)
+         : rag ? lrn_launch<float, 4, true, RELU>(bwd, x, dy, out, N, C, HW, size / 2, a_n, beta, k, s)
+               : lrn_launch<float, 1, false, RELU>(bwd, x, dy, out, N, C, HW, size / 2, a_n, beta, k, s);
+}
+
+hipError_t launch_lrn(const void *x, const void *dy, void *out, int N, int C, int HW, int size, float alpha,
+                      float beta, float k, int bf16, hipStream_t s, int relu)
+{
+    if (size < 1 || size > 9 || !(size & 1)) return hipErrorInvalidValue;
+    return relu ? lrn_dispatch<true>(x, dy, out, N, C, HW, size, alpha, beta, k, bf16, s)
+                : lrn_dispatch<false>(x, dy, out, N, C, HW, size, alpha, beta, k, bf16, s);
 }
 
 hipError_t launch_maxpool_fwd(const void *x, void *y, int32_t *idx, int NC, int H, int W, int P, int Q, int kh,

@@ -960,7 +960,7 @@ sn_status sn_bn_relu_bwd(const void *x, const void *dy, const float *gamma, cons
 }
 
 static sn_status lrn_common(const void *x, const void *dy, void *out, int N, int C, int H, int W, int size,
-                            float alpha, float beta, float k, sn_dtype dtype, sn_stream stream, bool bwd)
+                            float alpha, float beta, float k, sn_dtype dtype, sn_stream stream, bool bwd, int relu = 0)
 {
     sn_status s = check_cheap(N, C, H, W, dtype);
     if (s != SN_OK) return s;
@@ -970,7 +970,7 @@ static sn_status lrn_common(const void *x, const void *dy, void *out, int N, int
     if (size > 9) return SN_ERR_UNSUPPORTED;
     if ((long long)N * H * W / 256 > 0x7fffffffLL) return SN_ERR_UNSUPPORTED;
     return launch_status(launch_lrn(x, bwd ? dy : nullptr, out, N, C, H * W, size, alpha, beta, k, dtype == SN_BF16,
-                                    static_cast<hipStream_t>(stream)));
+                                    static_cast<hipStream_t>(stream), relu));
 }
 
 sn_status sn_lrn_fwd(const void *x, void *y, int N, int C, int H, int W, int size, float alpha, float beta, float k,
@@ -983,6 +983,18 @@ sn_status sn_lrn_bwd(const void *x, const void *dy, void *dx, int N, int C, int 
                      float beta, float k, sn_dtype dtype, sn_stream stream)
 {
     return lrn_common(x, dy, dx, N, C, H, W, size, alpha, beta, k, dtype, stream, true);
+}
+
+sn_status sn_relu_lrn_fwd(const void *x, void *y, int N, int C, int H, int W, int size, float alpha, float beta,
+                          float k, sn_dtype dtype, sn_stream stream)
+{
+    return lrn_common(x, nullptr, y, N, C, H, W, size, alpha, beta, k, dtype, stream, false, 1);
+}
+
+sn_status sn_relu_lrn_bwd(const void *x, const void *dy, void *dx, int N, int C, int H, int W, int size, float alpha,
+                          float beta, float k, sn_dtype dtype, sn_stream stream)
+{
+    return lrn_common(x, dy, dx, N, C, H, W, size, alpha, beta, k, dtype, stream, true, 1);
 }
 
 static sn_status check_pool(int N, int C, int H, int W, int kh, int kw, int sh, int sw, int ph, int pw, int dtype,

@@ -170,8 +170,9 @@ hipError_t launch_bn_relu_pool2_fwd(const void *x, const float *gamma, const flo
                                     float *mean, float *invstd, int N, int C, int H, int W, float eps, int bf16,
                                     hipStream_t st);
 // LRN across channels, size odd and at most 9; dy == nullptr: forward into out, else backward into out.
+// relu != 0: the ReLU before the LRN in the same pass (forward: LRN of max(x, 0); backward: dx through both).
 hipError_t launch_lrn(const void *x, const void *dy, void *out, int N, int C, int HW, int size, float alpha,
-                      float beta, float k, int bf16, hipStream_t st);
+                      float beta, float k, int bf16, hipStream_t st, int relu = 0);
 hipError_t launch_maxpool_fwd(const void *x, void *y, int32_t *idx, int NC, int H, int W, int P, int Q,
                               int kh, int kw, int sh, int sw, int ph, int pw, int bf16, hipStream_t st);
 hipError_t launch_maxpool_bwd(const void *dy, const int32_t *idx, void *dx, int NC, int H, int W, int P,

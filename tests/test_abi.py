@@ -92,6 +92,9 @@ def test_bad_arguments_are_refused_before_any_launch():
     assert lib.sn_lrn_fwd(one, one, 1, 4, 2, 2, 5, 1e-4, 0.75, 2.0, 0, None) == 1
     assert lib.sn_lrn_bwd(one, two, two, 1, 4, 2, 2, 5, 1e-4, 0.75, 2.0, 0, None) == 1
     assert lib.sn_lrn_bwd(one, None, two, 1, 4, 2, 2, 5, 1e-4, 0.75, 2.0, 0, None) == 1
+    assert lib.sn_relu_lrn_fwd(one, one, 1, 4, 2, 2, 5, 1e-4, 0.75, 2.0, 0, None) == 1
+    assert lib.sn_relu_lrn_fwd(one, two, 1, 4, 2, 2, 11, 1e-4, 0.75, 2.0, 0, None) == 2
+    assert lib.sn_relu_lrn_bwd(one, two, two, 1, 4, 2, 2, 5, 1e-4, 0.75, 2.0, 0, None) == 1
     # BN + ReLU + 2x2 pool: odd sizes and rows too short for a vector access are for the separate calls
     three = ctypes.c_void_p(768)
     assert lib.sn_bn_relu_pool2_fwd(one, one, one, two, three, one, one, 1, 1, 5, 8, 1e-5, 1, None) == 2

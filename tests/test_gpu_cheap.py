@@ -259,6 +259,34 @@ def test_lrn(shape, params, dtype):
     assert rel_l2(f64(dx), oracle.lrn_bwd(f64(x), f64(dy), size, alpha, beta, k)) <= tol
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("params", [(5, 1e-4, 0.75, 2.0), (3, 1.0, 0.5, 1.0), (9, 2.0, 1.25, 0.5)],
+                         ids=lambda p: "n%d_a%g" % (p[0], p[1]))
+@pytest.mark.parametrize("shape", LRN_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_relu_lrn_one_pass(shape, params, dtype):
+    """ReLU + LRN in one call each way: the oracle's ReLU and LRN composed, and bit for bit the two separate calls."""
+    size, alpha, beta, k = params
+    seed = shape[1] * 100 + shape[2] + size + 7
+    x = wl.activation(shape, dtype, seed, scale=2.0)
+    dy = wl.activation(shape, dtype, seed + 1)
+    xd, dyd = x.cuda(), dy.cuda()
+    y = torch.full_like(xd, float("nan"))
+    dx = torch.full_like(xd, float("nan"))
+    sn.sn_relu_lrn_fwd(xd, y, size, alpha, beta, k)
+    sn.sn_relu_lrn_bwd(xd, dyd, dx, size, alpha, beta, k)
+    a, y2, g, dx2 = (torch.full_like(xd, float("nan")) for _ in range(4))
+    sn.sn_relu_fwd(xd, a)
+    sn.sn_lrn_fwd(a, y2, size, alpha, beta, k)
+    sn.sn_lrn_bwd(a, dyd, g, size, alpha, beta, k)
+    sn.sn_relu_bwd(xd, g, dx2)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2) and torch.equal(dx, dx2)
+    tol = TOL[dtype]
+    ao = oracle.relu_fwd(f64(x))
+    assert rel_l2(f64(y), oracle.lrn_fwd(ao, size, alpha, beta, k)) <= tol
+    assert rel_l2(f64(dx), oracle.relu_bwd(f64(x), oracle.lrn_bwd(ao, f64(dy), size, alpha, beta, k))) <= tol
+
+
 POOL_CASES = [((2, 16, 16, 16), (2, 2), (2, 2), (0, 0)), ((2, 8, 55, 55), (3, 3), (2, 2), (0, 0)),
               ((3, 5, 13, 13), (3, 3), (2, 2), (0, 0)), ((2, 6, 35, 35), (3, 3), (2, 2), (0, 0)),
               ((2, 4, 17, 17), (3, 3), (2, 2), (0, 0)), ((1, 3, 9, 12), (3, 3), (2, 2), (1, 1)),
