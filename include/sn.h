@@ -78,7 +78,12 @@ typedef enum { SN_CONV_FWD = 0, SN_CONV_BWD_DATA = 1, SN_CONV_BWD_FILTER = 2 } s
  *               also the phase planes of the input: x[i*stride + a] for each
  *               residue a becomes a channel group, over which the convolution
  *               has stride 1 and runs on the stride-1 kernels (inner filter
- *               1x1, 2x2 or 3x3 by the span of the tap offsets); forward and
+ *               1x1, 2x2 or 3x3 by the span of the tap offsets).  Forward with C a
+ *               multiple of 16 and K of 8 needs the planes only as its preferred
+ *               workspace for 1x1 filters with 512 output channels or more: below
+ *               that, and for every other filter, it gathers the input pixel by
+ *               pixel under each tap and stages only the filter with the channel
+ *               innermost (min_bytes = K*C*R*S*2).  Otherwise forward and
  *               backward-data take the planes of as many images per pass as the
  *               workspace holds (min_bytes: one image).
  *  WINOGRAD     F(2x2, 3x3) for the fp32 path (3x3 filters, stride 1, forward and

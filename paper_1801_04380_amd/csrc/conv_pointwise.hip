@@ -53,6 +53,10 @@ struct PwProblem {
     int out_bf16;
     uint32_t x_bytes, a_bytes, y_bytes;
     int niter;               // main-loop trips: four 16-channel steps per wave each
+    // CONV (forward of any filter, stride and padding as a matrix product over (tap, channel)): HW is the output
+    // plane P * Q, Rd = R * S * C, and the input is [N][C][Hin][Win]
+    int C, Hin, Win, Q, R, S, sh, sw, ph, pw;
+    int spt;                 // 16-channel steps per tap: C / 16
 };
 
 __device__ inline uint32_t pack2(float a, float b)   // two fp32 -> two bf16, round to nearest even, a in the low half
@@ -67,11 +71,17 @@ __device__ inline uint32_t pack2(float a, float b)   // two fp32 -> two bf16, ro
 // MS: 32-row blocks of output channels per workgroup; NW: waves per workgroup, 64 pixels each, or
 // with SPLIT a share of the reduction each; AT: A[m][r] = w[r][m] (backward-data); PAIR: plane size
 // even, a lane owns two neighbouring pixels.
-template <int MS, int NW, bool SPLIT, bool AT, bool PAIR>
+// CONV: forward of a filter with taps, strides and padding by the same means.  The reduction runs over
+// (tap, channel) with the channel innermost, A is the filter re-laid out [k][tap][c] (in the caller's
+// workspace), and a lane's 8 loads of a step are the 8 channels of ITS input pixel under the step's tap:
+// the per-lane offset is that of the window's first pixel plus the tap's (uniform) offset, or out of
+// range where the tap falls into the padding.  No phase planes, no unfolded copy.
+template <int MS, int NW, bool SPLIT, bool AT, bool PAIR, bool CONV = false>
 __global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 pointwise_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ a, void *__restrict__ y, PwProblem p)
 {
     static_assert(!SPLIT || (NW == 4 && MS == 2), "the split form: four waves, 64 output channels");
+    static_assert(!CONV || (!SPLIT && !AT && !PAIR), "the general forward form: single pixels, whole reduction per wave");
     constexpr int MT = 32 * MS, NT = 64 * NW;
     constexpr int RGS = SPLIT ? 2 * RG : RG;                 // reduction channels per stage
     constexpr int SPG = SPLIT ? 2 : 4;                       // 16-channel steps per wave and stage
@@ -104,15 +114,27 @@ pointwise_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ a, voi
     constexpr int NCOL = PAIR ? 1 : 2;
     const uint32_t esz = p.out_bf16 ? 2 : 4;
     uint32_t xlane[NCOL], ylane[NCOL];
+    int ih0[NCOL], iw0[NCOL];   // CONV: the input row and column under the window's first tap
+    bool okj[NCOL];
 #pragma unroll
     for (int e = 0; e < NCOL; ++e) {
         const uint32_t j = PAIR ? px0 + 2 * l32 : px0 + 32 * e + l32;
         const uint32_t n = j / (uint32_t)p.HW, pp = j - n * p.HW;
         const bool ok = j < p.npx;
-        xlane[e] = ok ? ((n * p.Rd + 8 * g) * p.HW + pp) * 2 : OUTSIDE;
+        okj[e] = ok;
+        if (CONV) {
+            const int po = (int)pp / p.Q, qo = (int)pp - po * p.Q;
+            ih0[e] = po * p.sh - p.ph;
+            iw0[e] = qo * p.sw - p.pw;
+            // (wraps where the window starts in the padding; the taps inside the image add up to a proper offset)
+            xlane[e] = (uint32_t)((((int)n * p.C + 8 * g) * p.Hin + ih0[e]) * p.Win + iw0[e]) * 2u;
+        } else {
+            ih0[e] = iw0[e] = 0;
+            xlane[e] = ok ? ((n * p.Rd + 8 * g) * p.HW + pp) * 2 : OUTSIDE;
+        }
         ylane[e] = ok ? ((n * p.M + 4 * g) * p.HW + pp) * esz : OUTSIDE;
     }
-    const uint32_t xrow = (uint32_t)p.HW * 2;   // bytes between reduction channels of X
+    const uint32_t xrow = CONV ? (uint32_t)p.Hin * p.Win * 2 : (uint32_t)p.HW * 2;   // bytes between channels of X
 
     // ---- per-thread constants of the A stage
     uint32_t asrc[AIT], adst[AIT];
@@ -146,18 +168,32 @@ pointwise_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ a, voi
 
     uint32_t xraw[4][NX];
     // the q-th step of this wave is 16-channel step q, or with SPLIT step 2 * wave + q % 2 of stage q / 2
+    int tap_r = 0, tap_s = 0, tap_c = 0;   // CONV: the tap and the 16-channel step within it of the next x_issue (called in step order)
+    const int conv_steps = CONV ? p.R * p.S * p.spt : 0;
     auto x_issue = [&](int q, uint32_t (&dst)[NX]) {
         const int c = SPLIT ? (q >> 1) * 8 + 2 * wave + (q & 1) : q;
         const bool rows_ok = c * 16 + 8 * g < p.Rd;     // Rd is a multiple of 8: a lane's 8 rows are in or out together
-        const uint32_t sb = (uint32_t)c * 16 * xrow;
+        const uint32_t sb = CONV ? (uint32_t)tap_c * 16 * xrow : (uint32_t)c * 16 * xrow;
+        const uint32_t tapoff = CONV ? (uint32_t)((tap_r * p.Win + tap_s) * 2) : 0u;
 #pragma unroll
         for (int e = 0; e < NCOL; ++e) {
-            const uint32_t v = rows_ok ? xlane[e] : OUTSIDE;
+            uint32_t v;
+            if (CONV) {
+                const bool in = okj[e] && q < conv_steps && (unsigned)(ih0[e] + tap_r) < (unsigned)p.Hin &&
+                                (unsigned)(iw0[e] + tap_s) < (unsigned)p.Win;
+                v = in ? xlane[e] + tapoff : OUTSIDE;
+            } else {
+                v = rows_ok ? xlane[e] : OUTSIDE;
+            }
 #pragma unroll
             for (int jj = 0; jj < 8; ++jj) {
                 if (PAIR) dst[jj] = __builtin_amdgcn_raw_buffer_load_b32(xr, v, sb + jj * xrow, 0);
                 else dst[e * 8 + jj] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(xr, v, sb + jj * xrow, 0);
             }
+        }
+        if (CONV && ++tap_c == p.spt) {
+            tap_c = 0;
+            if (++tap_s == p.S) { tap_s = 0; ++tap_r; }
         }
     };
 
@@ -370,6 +406,52 @@ hipError_t launch_shape(const bf16_t *x, const bf16_t *a, void *y, const PwPlan 
         else hipLaunchKernelGGL((pointwise_kernel<MS, NW, SPLIT, false, false>), grid, block, 0, st, x, a, y, pl.p);
     }
     return hipGetLastError();
+}
+
+// ---- forward of any filter by the CONV form of the kernel above ----------------------------------
+// wp[k][tap][c] = w[k][c][tap]: the filter with the channel innermost, so that a row of A is contiguous.
+__global__ void __launch_bounds__(256)
+pack_tap_major_kernel(const bf16_t *__restrict__ w, bf16_t *__restrict__ wp, int C, int T, size_t total)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;   // index into wp
+    if (i >= total) return;
+    const size_t kt = i / C;
+    const int c = (int)(i - kt * C), t = (int)(kt % T);
+    const size_t k = kt / T;
+    wp[i] = w[(k * C + c) * T + t];
+}
+
+bool make_conv_plan(const ConvGeom &g, PwPlan *pl)
+{
+    if (!g.in_bf16 || g.C % 16 != 0 || g.K % 8 != 0) return false;
+    if (g.R * g.S > 121) return false;
+    const long long PQ = (long long)g.P * g.Q, npx = PQ * g.N, Rd = (long long)g.C * g.R * g.S, M = g.K;
+    const long long lim = 0x7fffffffLL - (1 << 20);
+    const long long xb = (long long)g.N * g.C * g.H * g.W * 2;
+    if (xb > lim || npx * M * (g.out_bf16 ? 2 : 4) > lim || M * Rd * 2 > lim) return false;
+    if (16LL * g.H * g.W * 2 * 4 > lim) return false;
+    PwProblem &p = pl->p;
+    p.M = (int)M; p.Rd = (int)Rd; p.HW = (int)PQ; p.npx = (uint32_t)npx;
+    p.out_bf16 = g.out_bf16;
+    p.x_bytes = (uint32_t)xb;
+    p.y_bytes = (uint32_t)(npx * M * (g.out_bf16 ? 2 : 4));
+    p.a_bytes = (uint32_t)(M * Rd * 2);
+    p.C = g.C; p.Hin = g.H; p.Win = g.W; p.Q = g.Q; p.R = g.R; p.S = g.S;
+    p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw;
+    p.spt = g.C / 16;
+    pl->at = false; pl->pair = false; pl->split = false;
+    auto tiles = [&](int ms, int px) { return ((M + 32 * ms - 1) / (32 * ms)) * ((npx + px - 1) / px); };
+    if (M > 64 && tiles(4, 256) >= 256) { pl->MS = 4; pl->NW = 4; }
+    else if (tiles(2, 256) >= 256) { pl->MS = 2; pl->NW = 4; }
+    else { pl->MS = 2; pl->NW = 1; }
+    const int px = 64 * pl->NW;
+    p.mtiles = (int)((M + 32 * pl->MS - 1) / (32 * pl->MS));
+    p.ptiles = (int)((npx + px - 1) / px);
+    p.niter = (int)((Rd + RG - 1) / RG);
+    const long long grid = 8LL * p.mtiles * ((p.ptiles + 7) / 8);
+    if (grid > 0x7fffffffLL) return false;
+    pl->grid = (unsigned)grid;
+    return true;
 }
 
 // ---- backward-filter of the same layers on small images ------------------------------------------
@@ -731,6 +813,34 @@ hipError_t launch_pointwise(const void *in, const void *w, void *out, const Conv
     if (pl.MS == 4) return launch_shape<4, 4, false>(x, a, out, pl, st);
     if (pl.NW == 4) return launch_shape<2, 4, false>(x, a, out, pl, st);
     return launch_shape<2, 1, false>(x, a, out, pl, st);
+}
+
+bool gather_conv_supported(const ConvGeom &g)
+{
+    PwPlan pl;
+    return make_conv_plan(g, &pl);
+}
+
+size_t gather_conv_packed_bytes(const ConvGeom &g)
+{
+    return align_up((size_t)g.K * g.C * g.R * g.S * sizeof(bf16_t), 256);
+}
+
+hipError_t launch_gather_conv_fwd(const void *x, const void *w, void *y, const ConvGeom &g, void *packed, hipStream_t st)
+{
+    PwPlan pl;
+    if (!make_conv_plan(g, &pl) || !packed) return hipErrorInvalidValue;
+    const size_t total = (size_t)g.K * g.C * g.R * g.S;
+    hipLaunchKernelGGL(pack_tap_major_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                       static_cast<const bf16_t *>(w), static_cast<bf16_t *>(packed), g.C, g.R * g.S, total);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const bf16_t *xs = static_cast<const bf16_t *>(x), *a = static_cast<const bf16_t *>(packed);
+    const dim3 grid(pl.grid);
+    if (pl.MS == 4) hipLaunchKernelGGL((pointwise_kernel<4, 4, false, false, false, true>), grid, dim3(256), 0, st, xs, a, y, pl.p);
+    else if (pl.NW == 4) hipLaunchKernelGGL((pointwise_kernel<2, 4, false, false, false, true>), grid, dim3(256), 0, st, xs, a, y, pl.p);
+    else hipLaunchKernelGGL((pointwise_kernel<2, 1, false, false, false, true>), grid, dim3(64), 0, st, xs, a, y, pl.p);
+    return hipGetLastError();
 }
 
 bool pointwise_wgrad_supported(const ConvGeom &g)

@@ -237,6 +237,19 @@ int phase_chunk(const PhasePlan &pp, sn_conv_dir dir, size_t ws_bytes)
     return lo;
 }
 
+// STAGED forward by the pixel-gathering matrix product (conv_pointwise.hip), whose only workspace is the filter
+// with the channel innermost: strided shapes, and stride-1 shapes the tile kernels do not take.
+bool gather_fwd(const ConvGeom &g)
+{
+    return gather_conv_supported(g) && (g.sh > 1 || g.sw > 1 || !tile_conv_supported(g, false));
+}
+
+// Where the phase planes of the whole batch fit, 1x1 strided layers with many output channels are faster
+// on them (one pass to take every other pixel, then pixel pairs per load and no re-gathering per channel
+// tile; measured 256 -> 512 on 56x56: 54 against 66 us, 1024 -> 2048 on 14x14: 63 against 90 us); everything
+// else, and every budget below that, takes the gathering kernel.
+bool phase_fwd_when_it_fits(const ConvGeom &g) { return g.R == 1 && g.S == 1 && g.K >= 512; }
+
 sn_status query(const ConvGeom &g, sn_conv_dir dir, sn_conv_algo algo, size_t *min_b, size_t *pref_b)
 {
     switch (algo) {
@@ -258,6 +271,14 @@ sn_status query(const ConvGeom &g, sn_conv_dir dir, sn_conv_algo algo, size_t *m
         PhasePlan pp;
         if (dir == SN_CONV_BWD_FILTER && smallc_supported(g)) {
             *min_b = *pref_b = staged_bwd_filter_bytes(g, nullptr);
+            return SN_OK;
+        }
+        if (dir == SN_CONV_FWD && gather_fwd(g)) {
+            *min_b = *pref_b = gather_conv_packed_bytes(g);
+            if (phase_fwd_when_it_fits(g) && phase_plan(g, dir, &pp)) {
+                *pref_b = phase_bytes(pp, dir, g.N);
+                *min_b = std::min(*min_b, pp.chunkable ? phase_bytes(pp, dir, 1) : *pref_b);
+            }
             return SN_OK;
         }
         if (phase_plan(g, dir, &pp)) {
@@ -357,12 +378,17 @@ sn_status plan(const sn_conv_shape *shape, const ConvGeom &g, sn_conv_dir dir, s
         if (a == SN_ALGO_WINOGRAD && ((pf > budget && winograd_pass_tiles(g, dir == SN_CONV_BWD_DATA, budget) < 2048) ||
                                       (long long)g.C * g.K < 8192)) continue;
         // The phase planes in passes: strided forward gains little over the zero-workspace kernel, so only
-        // with the whole batch; backward-data gains 2-4x, which more than eight passes' launches eat up.
+        // with the whole batch (below that STAGED forward is the gathering kernel, which needs the re-laid-out
+        // filter alone); backward-data gains 2-4x, which more than eight passes' launches eat up.
         if (a == SN_ALGO_STAGED && pf > budget && (g.sh > 1 || g.sw > 1) && dir != SN_CONV_BWD_FILTER) {
             PhasePlan pp;
-            if (dir == SN_CONV_FWD || !phase_plan(g, dir, &pp)) continue;
-            const int chunk = phase_chunk(pp, dir, budget);
-            if ((g.N + chunk - 1) / chunk > 8) continue;
+            if (dir == SN_CONV_FWD) {
+                if (!(gather_fwd(g) && budget >= gather_conv_packed_bytes(g))) continue;
+            } else {
+                if (!phase_plan(g, dir, &pp)) continue;
+                const int chunk = phase_chunk(pp, dir, budget);
+                if ((g.N + chunk - 1) / chunk > 8) continue;
+            }
         }
         *algo = a;
         *bytes = std::min(pf, budget);
@@ -427,6 +453,11 @@ sn_status run_fwd(const void *x, const void *w, void *y, const ConvGeom &g, sn_c
     if (algo == SN_ALGO_DIRECT) return launch_status(direct_fwd(x, w, y, g, st));
     if (algo == SN_ALGO_WINOGRAD) return launch_status(launch_winograd(x, w, y, g, false, ws, ws_bytes, st));
     PhasePlan pp;
+    if (algo == SN_ALGO_STAGED && gather_fwd(g)) {
+        const bool planes = phase_fwd_when_it_fits(g) && phase_plan(g, SN_CONV_FWD, &pp);
+        const bool whole = planes && ws_bytes >= phase_bytes(pp, SN_CONV_FWD, g.N);
+        if (!whole && ws_bytes >= gather_conv_packed_bytes(g)) return launch_status(launch_gather_conv_fwd(x, w, y, g, ws, st));
+    }
     if (algo == SN_ALGO_STAGED && phase_plan(g, SN_CONV_FWD, &pp)) {
         char *base = static_cast<char *>(ws);
         void *wp = base, *packed = base + pp.wprime_bytes, *xs = base + phase_fixed_bytes(pp, SN_CONV_FWD);

@@ -91,6 +91,13 @@ hipError_t launch_smallc_wgrad(const void *x, const void *dy, float *dw, const C
 bool pointwise_supported(const ConvGeom &g, bool bwd_data);
 hipError_t launch_pointwise(const void *in, const void *w, void *out, const ConvGeom &g, bool bwd_data, hipStream_t st);
 
+// Forward of any filter, stride and padding (bf16, C a multiple of 16, K of 8) as a matrix product over
+// (tap, channel) whose input operand is gathered pixel by pixel straight from x (conv_pointwise.hip);
+// `packed`: gather_conv_packed_bytes for the filter re-laid out [k][tap][c], written by the call.
+bool gather_conv_supported(const ConvGeom &g);
+size_t gather_conv_packed_bytes(const ConvGeom &g);
+hipError_t launch_gather_conv_fwd(const void *x, const void *w, void *y, const ConvGeom &g, void *packed, hipStream_t st);
+
 // Backward-filter of the same layers on the smallest planes (8 to 64 pixels), any channel counts;
 // contract of launch_rows_wgrad (pointwise_wgrad_slices slices).  launch_tile_wgrad prefers it.
 bool pointwise_wgrad_supported(const ConvGeom &g);

@@ -143,6 +143,15 @@ CASES = [
     (L("7x1_w40", 24, 10, 40, 40, 7, 1, (1, 1), (3, 0)), 2),
     (L("1x7_w12_k136", 20, 9, 12, 136, 1, 7, (1, 1), (0, 3)), 5),
     (L("7x1_w12_k136", 20, 9, 12, 136, 7, 1, (1, 1), (3, 0)), 5),
+    # forward as a matrix product over (tap, channel) with the input gathered pixel by pixel (channels a multiple of
+    # 16): each tile size with ragged channel tiles, strides that differ per axis under a 5x5 filter with padding, a
+    # 4x4 stride-1 filter no tile kernel takes, a 1x1 / stride-2 layer that goes to the phase planes when they fit
+    (L("g_s2_3x3_k136_big", 16, 130, 130, 136, 3, 3, (2, 2), (1, 1)), 8),
+    (L("g_s2_3x3_k72_big", 16, 130, 130, 72, 3, 3, (2, 2), (1, 1)), 8),
+    (L("g_s2_3x3_c32_k136", 32, 40, 40, 136, 3, 3, (2, 2), (1, 1)), 6),
+    (L("g_5x5_s32", 32, 23, 31, 40, 5, 5, (3, 2), (2, 1)), 3),
+    (L("g_4x4_s1", 16, 12, 14, 24, 4, 4, (1, 1), (1, 1)), 3),
+    (L("g_1x1_s2_k512", 32, 14, 14, 512, 1, 1, (2, 2)), 4),
 ]
 IDS = [c[0].name for c in CASES]
 
