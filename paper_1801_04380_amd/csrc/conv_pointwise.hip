@@ -57,6 +57,9 @@ struct PwProblem {
     // plane P * Q, Rd = R * S * C, and the input is [N][C][Hin][Win]
     int C, Hin, Win, Q, R, S, sh, sw, ph, pw;
     int spt;                 // 16-channel steps per tap: C / 16
+    // backward-data of a 1x1 / stride-2 layer: pixel (p, q) of the HW = P * Q plane goes to (2p, 2q) of the
+    // Hd x Wd plane of dx, and the other three pixels of its 2 x 2 cell are written as zeros
+    int scat, Hd, Wd, Qd;
 };
 
 __device__ inline uint32_t pack2(float a, float b)   // two fp32 -> two bf16, round to nearest even, a in the low half
@@ -133,6 +136,10 @@ pointwise_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ a, voi
             xlane[e] = ok ? ((n * p.Rd + 8 * g) * p.HW + pp) * 2 : OUTSIDE;
         }
         ylane[e] = ok ? ((n * p.M + 4 * g) * p.HW + pp) * esz : OUTSIDE;
+        if (!CONV && p.scat && ok) {
+            const uint32_t po = pp / (uint32_t)p.Qd, qo = pp - po * p.Qd;
+            ylane[e] = (((n * p.M + 4 * g) * p.Hd + 2 * po) * p.Wd + 2 * qo) * esz;
+        }
     }
     const uint32_t xrow = CONV ? (uint32_t)p.Hin * p.Win * 2 : (uint32_t)p.HW * 2;   // bytes between channels of X
 
@@ -286,10 +293,38 @@ pointwise_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ a, voi
     }
 
     // ---- epilogue: register v of a lane is output channel 8*(v/4) + 4*g + v%4 of its 32-row block
-    const uint32_t yrow = (uint32_t)p.HW * esz;
+    const uint32_t yrow = (!CONV && p.scat) ? (uint32_t)p.Hd * p.Wd * esz : (uint32_t)p.HW * esz;
     // row mu + 4*g + vv of the output for the lane's pixel pair (v0: even pixel or column group 0)
     auto store_row = [&](int mu, int vv, float v0, float v1) {
         const uint32_t sb = (uint32_t)(mu + vv) * yrow;
+        if (!CONV && p.scat) {   // every pixel with a zero to its right, and a row of zeros below
+            const uint32_t below = (uint32_t)p.Wd * esz;
+            if (PAIR) {
+                if (p.out_bf16) {
+                    const u32x2 d = {pack2(v0, 0.f), pack2(v1, 0.f)}, z = {0u, 0u};
+                    __builtin_amdgcn_raw_buffer_store_b64(d, yr, ylane[0], sb, 0);
+                    __builtin_amdgcn_raw_buffer_store_b64(z, yr, ylane[0], sb + below, 0);
+                } else {
+                    const u32x4 d = {__float_as_uint(v0), 0u, __float_as_uint(v1), 0u}, z = {0u, 0u, 0u, 0u};
+                    __builtin_amdgcn_raw_buffer_store_b128(d, yr, ylane[0], sb, 0);
+                    __builtin_amdgcn_raw_buffer_store_b128(z, yr, ylane[0], sb + below, 0);
+                }
+            } else {
+                const float vals[2] = {v0, v1};
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    if (p.out_bf16) {
+                        __builtin_amdgcn_raw_buffer_store_b32(pack2(vals[e], 0.f), yr, ylane[PAIR ? 0 : e], sb, 0);
+                        __builtin_amdgcn_raw_buffer_store_b32(0u, yr, ylane[PAIR ? 0 : e], sb + below, 0);
+                    } else {
+                        const u32x2 d = {__float_as_uint(vals[e]), 0u}, z = {0u, 0u};
+                        __builtin_amdgcn_raw_buffer_store_b64(d, yr, ylane[PAIR ? 0 : e], sb, 0);
+                        __builtin_amdgcn_raw_buffer_store_b64(z, yr, ylane[PAIR ? 0 : e], sb + below, 0);
+                    }
+                }
+            }
+            return;
+        }
         if (PAIR) {
             if (p.out_bf16) {
                 __builtin_amdgcn_raw_buffer_store_b32(pack2(v0, v1), yr, ylane[0], sb, 0);
@@ -358,10 +393,12 @@ struct PwPlan {
 
 bool make_plan(const ConvGeom &g, bool bwd_data, PwPlan *pl)
 {
-    if (!g.in_bf16 || g.R != 1 || g.S != 1 || g.sh != 1 || g.sw != 1 || g.ph != 0 || g.pw != 0) return false;
-    if (g.P != g.H || g.Q != g.W) return false;
+    if (!g.in_bf16 || g.R != 1 || g.S != 1 || g.ph != 0 || g.pw != 0) return false;
+    // stride 1; or backward-data of stride 2 on planes of even size (whole 2 x 2 cells)
+    const bool scat = bwd_data && g.sh == 2 && g.sw == 2 && g.H % 2 == 0 && g.W % 2 == 0 && g.P == g.H / 2 && g.Q == g.W / 2;
+    if (!scat && (g.sh != 1 || g.sw != 1 || g.P != g.H || g.Q != g.W)) return false;
     if (g.C % 8 != 0 || g.K % 8 != 0) return false;
-    const long long HW = (long long)g.H * g.W, npx = HW * g.N;
+    const long long HW = (long long)g.P * g.Q, npx = HW * g.N;
     const long long M = bwd_data ? g.C : g.K, Rd = bwd_data ? g.K : g.C;
     const long long lim = 0x7fffffffLL - (1 << 20);
     if (npx * Rd * 2 > lim || npx * M * (g.out_bf16 ? 2 : 4) > lim || (long long)g.K * g.C * 2 > lim) return false;
@@ -371,6 +408,12 @@ bool make_plan(const ConvGeom &g, bool bwd_data, PwPlan *pl)
     p.out_bf16 = g.out_bf16;
     p.x_bytes = (uint32_t)(npx * Rd * 2);
     p.y_bytes = (uint32_t)(npx * M * (g.out_bf16 ? 2 : 4));
+    p.scat = scat; p.Hd = g.H; p.Wd = g.W; p.Qd = g.Q;
+    if (scat) {
+        const long long yb = (long long)g.N * g.C * g.H * g.W * (g.out_bf16 ? 2 : 4);
+        if (yb > lim) return false;
+        p.y_bytes = (uint32_t)yb;
+    }
     p.a_bytes = (uint32_t)((long long)g.K * g.C * 2);
     pl->at = bwd_data;
     pl->pair = HW % 2 == 0;
@@ -439,6 +482,7 @@ bool make_conv_plan(const ConvGeom &g, PwPlan *pl)
     p.C = g.C; p.Hin = g.H; p.Win = g.W; p.Q = g.Q; p.R = g.R; p.S = g.S;
     p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw;
     p.spt = g.C / 16;
+    p.scat = 0; p.Hd = p.Wd = p.Qd = 0;
     pl->at = false; pl->pair = false; pl->split = false;
     auto tiles = [&](int ms, int px) { return ((M + 32 * ms - 1) / (32 * ms)) * ((npx + px - 1) / px); };
     if (M > 64 && tiles(4, 256) >= 256) { pl->MS = 4; pl->NW = 4; }

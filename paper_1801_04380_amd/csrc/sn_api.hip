@@ -244,6 +244,10 @@ bool gather_fwd(const ConvGeom &g)
     return gather_conv_supported(g) && (g.sh > 1 || g.sw > 1 || !tile_conv_supported(g, false));
 }
 
+// 1x1 / stride-2 backward-data on planes of even size: the 1x1 kernel writes every result with the zeros of its
+// 2 x 2 cell (no workspace, under either name).
+bool scatter_bwd_data(const ConvGeom &g) { return (g.sh > 1 || g.sw > 1) && pointwise_supported(g, true); }
+
 // Where the phase planes of the whole batch fit, 1x1 strided layers with many output channels are faster
 // on them (one pass to take every other pixel, then pixel pairs per load and no re-gathering per channel
 // tile; measured 256 -> 512 on 56x56: 54 against 66 us, 1024 -> 2048 on 14x14: 63 against 90 us); everything
@@ -271,6 +275,10 @@ sn_status query(const ConvGeom &g, sn_conv_dir dir, sn_conv_algo algo, size_t *m
         PhasePlan pp;
         if (dir == SN_CONV_BWD_FILTER && smallc_supported(g)) {
             *min_b = *pref_b = staged_bwd_filter_bytes(g, nullptr);
+            return SN_OK;
+        }
+        if (dir == SN_CONV_BWD_DATA && scatter_bwd_data(g)) {
+            *min_b = *pref_b = 0;
             return SN_OK;
         }
         if (dir == SN_CONV_FWD && gather_fwd(g)) {
@@ -372,6 +380,7 @@ sn_status plan(const sn_conv_shape *shape, const ConvGeom &g, sn_conv_dir dir, s
         }
         if (a == SN_ALGO_IM2COL_GEMM) continue;
         if (query(g, dir, a, &mn, &pf) != SN_OK || mn > budget) continue;
+        if (a == SN_ALGO_STAGED && pf == 0) continue;   // nothing to stage: the same kernel runs as DIRECT
         // Winograd pays four kernels per pass and streams 16 transformed values per 4 inputs: a guess in its
         // favour only where a pass has real work and the products outweigh the transforms (measured: 64 x 128
         // channels gain, 64 x 64 lose)
@@ -443,6 +452,7 @@ hipError_t direct_fwd(const void *x, const void *w, void *y, const ConvGeom &g, 
 
 hipError_t direct_bwd_data(const void *dy, const void *w, void *dx, const ConvGeom &g, hipStream_t st)
 {
+    if (scatter_bwd_data(g)) return launch_pointwise(dy, w, dx, g, true, st);
     if (tile_conv_supported(g, true)) return launch_tile_conv(dy, w, dx, g, true, nullptr, st);
     return launch_generic_bwd_data(dy, w, dx, g, st);
 }
@@ -495,6 +505,7 @@ sn_status run_bwd_data(const void *dy, const void *w, void *dx, const ConvGeom &
 {
     if (algo == SN_ALGO_DIRECT) return launch_status(direct_bwd_data(dy, w, dx, g, st));
     if (algo == SN_ALGO_WINOGRAD) return launch_status(launch_winograd(dy, w, dx, g, true, ws, ws_bytes, st));
+    if (algo == SN_ALGO_STAGED && scatter_bwd_data(g)) return launch_status(launch_pointwise(dy, w, dx, g, true, st));
     PhasePlan pp;
     if (algo == SN_ALGO_STAGED && phase_plan(g, SN_CONV_BWD_DATA, &pp)) {
         char *base = static_cast<char *>(ws);

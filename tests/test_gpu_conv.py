@@ -152,6 +152,8 @@ CASES = [
     (L("g_5x5_s32", 32, 23, 31, 40, 5, 5, (3, 2), (2, 1)), 3),
     (L("g_4x4_s1", 16, 12, 14, 24, 4, 4, (1, 1), (1, 1)), 3),
     (L("g_1x1_s2_k512", 32, 14, 14, 512, 1, 1, (2, 2)), 4),
+    # 1x1 / stride-2 backward-data written with the zeros of its 2x2 cells: an odd output width (single pixels per lane)
+    (L("sc_1x1_s2_q5", 24, 10, 10, 40, 1, 1, (2, 2)), 3),
 ]
 IDS = [c[0].name for c in CASES]
 
