@@ -63,7 +63,14 @@ typedef enum { SN_CONV_FWD = 0, SN_CONV_BWD_DATA = 1, SN_CONV_BWD_FILTER = 2 } s
  *               STAGED, where its workgroups' partial sums are reduced in a fixed order).
  *               1x1 / stride-1 / unpadded layers (bf16, C and K multiples of 8) run
  *               forward and backward-data as a matrix product per image that
- *               needs no re-laid-out operand, under DIRECT and STAGED alike.
+ *               needs no re-laid-out operand, under DIRECT and STAGED alike;
+ *               so does backward-data of 1x1 / stride-2 layers on planes of even
+ *               size, whose kernel writes each 2x2 cell of dx (one value, three
+ *               zeros) itself: sn_conv_workspace_query reports STAGED there with
+ *               0 bytes and sn_conv_plan names DIRECT.  Every other strided
+ *               backward-data works by residue classes of the input pixels
+ *               (h mod stride_h, w mod stride_w): a class shares its taps, so only
+ *               the taps that meet an output pixel are multiplied.
  *  IM2COL_GEMM  explicit: unfold patches into a column buffer in the workspace
  *               (as many images per pass as fit), then a GEMM over it; the
  *               backward-data form folds the column gradient back (col2im).
@@ -134,7 +141,7 @@ sn_status sn_conv_workspace_query(const sn_conv_shape *shape, sn_conv_dir dir, s
  * algorithms at run time); a recorded time applies to budgets >= the workspace
  * it was measured with.  With no feasible record the choice falls back to a
  * built-in ranking (WINOGRAD where it applies, C * K >= 8192 and at least 2048 tiles fit a pass, STAGED,
- * then DIRECT; for strided backward-data the explicit algorithm before DIRECT; DIRECT first for forward on few-channel inputs).  Among records within 3 % of the fastest the one with the
+ * then DIRECT; DIRECT first for forward on few-channel inputs).  Among records within 3 % of the fastest the one with the
  * smallest workspace wins (then the faster).  DIRECT needs 0 bytes, so a plan always exists.  bytes_used = the workspace the choice will use
  * (<= budget_bytes).  predicted_ms may be NULL; it receives the recorded time
  * or a negative value if the choice came from the built-in ranking. */

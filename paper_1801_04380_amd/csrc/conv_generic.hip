@@ -380,6 +380,150 @@ igemm_generic_kernel(const T *__restrict__ Asrc, const T *__restrict__ Bsrc, voi
     }
 }
 
+// Backward-data of a strided convolution, one residue class of input pixels per blockIdx.z.
+// Input pixel (h, v) receives tap (r, s) only where sh divides h + ph - r and sw divides
+// v + pw - s, so the pixels with h = a (mod sh), v = b (mod sw) all use the same taps:
+// r = r0 + sh*t, s = s0 + sw*u with r0 = (a + ph) mod sh, s0 = (b + pw) mod sw, and pixel
+// (a + sh*i, b + sw*j) reads dy at (i + (a + ph)/sh - t, j + (b + pw)/sw - u).  A tile's 128
+// columns are pixels (n, i, j) of one class, so the reduction runs over that class's taps only
+// (R*S / (sh*sw) of them on average instead of R*S with the rest multiplying zeros), a tap at a
+// time over the output channels (padded to whole steps: a step never straddles two taps), and
+// neighbouring lanes read neighbouring dy elements.  A class without taps (filter shorter than
+// the stride) stores zeros.
+template <typename T, int BM>
+__global__ void __launch_bounds__(NTHREADS)
+igemm_bwd_data_classes_kernel(const T *__restrict__ w, const T *__restrict__ dy, void *__restrict__ dx,
+                              ConvGeom g, int Kpad)
+{
+    constexpr int BK = TileCfg<T>::BK, PITCH = TileCfg<T>::PITCH;
+    constexpr int A_KSEGS = NTHREADS / BM, A_E = BK / A_KSEGS;
+    constexpr int B_KSEGS = NTHREADS / BN, B_E = BK / B_KSEGS;
+    constexpr int TM = 2, TN = (BM == 128) ? 2 : 1;
+
+    __shared__ __attribute__((aligned(16))) T As[BM * PITCH];
+    __shared__ __attribute__((aligned(16))) T Bs[BN * PITCH];
+
+    const int ca = blockIdx.z / g.sw, cb = blockIdx.z - ca * g.sw;
+    const int Ha = ca < g.H ? (g.H - ca + g.sh - 1) / g.sh : 0;
+    const int Wb = cb < g.W ? (g.W - cb + g.sw - 1) / g.sw : 0;
+    const int ncols = g.N * Ha * Wb;
+    const int col0 = blockIdx.x * BN;
+    if (col0 >= ncols) return;  // the grid is sized for the largest class
+    const int r0 = (ca + g.ph) % g.sh, s0 = (cb + g.pw) % g.sw;
+    const int pa = (ca + g.ph) / g.sh, qb = (cb + g.pw) / g.sw;
+    const int nt = r0 < g.R ? (g.R - r0 + g.sh - 1) / g.sh : 0;
+    const int nu = s0 < g.S ? (g.S - s0 + g.sw - 1) / g.sw : 0;
+    const int kend = nt * nu * Kpad;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int m0 = blockIdx.y * BM;
+    const int a_row = tid % BM, a_kseg = tid / BM, b_row = tid % BN, b_kseg = tid / BN;
+    const int RS = g.R * g.S, PQ = g.P * g.Q;
+
+    // this thread's column of B: pixel (n, i, j) of the class
+    const bool bvalid = col0 + b_row < ncols;
+    int bp, bq;
+    long long bbase;
+    {
+        const int j = bvalid ? col0 + b_row : 0;
+        const int n = j / (Ha * Wb), ij = j - n * (Ha * Wb), i = ij / Wb;
+        bp = i + pa;
+        bq = ij - i * Wb + qb;
+        bbase = (long long)n * g.K * PQ;
+    }
+    const bool avalid = m0 + a_row < g.C;
+    const long long abase = (long long)(avalid ? m0 + a_row : 0) * RS;
+
+    T ra[A_E], rb[B_E];
+    auto fetch = [&](int k0) {
+        const int tap = k0 / Kpad, kb = k0 - tap * Kpad;
+        const int t = tap / nu, u = tap - t * nu;
+        const int rs = (r0 + g.sh * t) * g.S + s0 + g.sw * u;
+        const int p = bp - t, q = bq - u;
+        const bool in = bvalid && (unsigned)p < (unsigned)g.P && (unsigned)q < (unsigned)g.Q;
+        const T *bsrc = dy + bbase + (long long)(in ? p * g.Q + q : 0);
+#pragma unroll
+        for (int e = 0; e < B_E; ++e) {
+            const int k = kb + b_kseg * B_E + e;
+            rb[e] = (in && k < g.K) ? bsrc[(long long)k * PQ] : zero_of<T>();
+        }
+        const T *asrc = w + abase + rs;
+#pragma unroll
+        for (int e = 0; e < A_E; ++e) {
+            const int k = kb + a_kseg * A_E + e;
+            ra[e] = (avalid && k < g.K) ? asrc[(long long)k * g.C * RS] : zero_of<T>();
+        }
+    };
+    auto stage = [&]() {
+        store_row<T, A_E>(As, a_row, a_kseg, ra);
+        store_row<T, B_E>(Bs, b_row, b_kseg, rb);
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int arow = (BM == 128) ? (wave >> 1) * 64 : 0;
+    const int brow = (BM == 128) ? (wave & 1) * 64 : wave * 32;
+
+    if (kend > 0) {
+        fetch(0);
+        stage();
+        __syncthreads();
+        for (int k0 = 0; k0 < kend; k0 += BK) {
+            const bool more = k0 + BK < kend;
+            if (more) fetch(k0 + BK);
+            mma_tile<TM, TN>(As, Bs, arow, brow, lane, acc);
+            __syncthreads();
+            if (more) {
+                stage();
+                __syncthreads();
+            }
+        }
+    }
+
+    const int r = lane & 31, hi = lane >> 5;
+    const long long HW = (long long)g.H * g.W;
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+        const int col = col0 + brow + tn * 32 + r;
+        if (col >= ncols) continue;
+        const int n = col / (Ha * Wb), ij = col - n * (Ha * Wb), i = ij / Wb, j = ij - i * Wb;
+        const long long cbase = (long long)n * g.C * HW + (long long)(ca + g.sh * i) * g.W + cb + g.sw * j;
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = m0 + arow + tm * 32 + 8 * (v >> 2) + 4 * hi + (v & 3);
+                if (row >= g.C) continue;
+                const long long off = cbase + row * HW;
+                const float val = acc[tm][tn][v];
+                if (g.out_bf16) reinterpret_cast<bf16_t *>(dx)[off] = f32_to_bf16(val);
+                else reinterpret_cast<float *>(dx)[off] = val;
+            }
+    }
+}
+
+template <typename T>
+hipError_t launch_bwd_data_classes(const void *dy, const void *w, void *dx, const ConvGeom &g, hipStream_t st)
+{
+    constexpr int BK = TileCfg<T>::BK;
+    const int Kpad = (g.K + BK - 1) / BK * BK;
+    const long long cols = (long long)g.N * ((g.H + g.sh - 1) / g.sh) * ((g.W + g.sw - 1) / g.sw);
+    const unsigned gx = (unsigned)((cols + BN - 1) / BN), gz = (unsigned)(g.sh * g.sw);
+    if (g.C <= 64)
+        hipLaunchKernelGGL((igemm_bwd_data_classes_kernel<T, 64>), dim3(gx, (g.C + 63) / 64, gz), dim3(NTHREADS), 0, st,
+                           (const T *)w, (const T *)dy, dx, g, Kpad);
+    else
+        hipLaunchKernelGGL((igemm_bwd_data_classes_kernel<T, 128>), dim3(gx, (g.C + 127) / 128, gz), dim3(NTHREADS), 0,
+                           st, (const T *)w, (const T *)dy, dx, g, Kpad);
+    return hipGetLastError();
+}
+
 __global__ void reduce_partials_kernel(const float *__restrict__ partial, float *__restrict__ dw, size_t n,
                                        int splits, bool accumulate)
 {
@@ -472,6 +616,10 @@ hipError_t launch_generic_fwd(const void *x, const void *w, void *y, const ConvG
 
 hipError_t launch_generic_bwd_data(const void *dy, const void *w, void *dx, const ConvGeom &g, hipStream_t st)
 {
+    if (g.sh > 1 || g.sw > 1) {
+        if (g.in_bf16) return launch_bwd_data_classes<bf16_t>(dy, w, dx, g, st);
+        return launch_bwd_data_classes<float>(dy, w, dx, g, st);
+    }
     GemmDims d;
     d.M = g.C;
     d.Ncols = g.N * g.H * g.W;

@@ -322,7 +322,7 @@ bool same_shape(const sn_conv_shape &a, const sn_conv_shape &b) { return std::me
 // Built-in ranking used when nothing has been measured for the shape: lower is
 // tried first.  The workspace-staged implicit GEMM, then the direct one; the
 // explicit unfold pays a write and a read of a buffer R*S times the input, so it
-// is picked on measurement, or for strided backward-data (see plan).
+// is picked on measurement only.
 const sn_conv_algo kRanking[] = {SN_ALGO_WINOGRAD, SN_ALGO_STAGED, SN_ALGO_DIRECT, SN_ALGO_IM2COL_GEMM};
 
 sn_status plan(const sn_conv_shape *shape, const ConvGeom &g, sn_conv_dir dir, size_t budget,
@@ -358,10 +358,6 @@ sn_status plan(const sn_conv_shape *shape, const ConvGeom &g, sn_conv_dir dir, s
         if (ms_out) *ms_out = best.ms;
         return SN_OK;
     }
-    // Strided backward-data without a tile kernel: the zero-workspace kernel visits every tap of every
-    // input pixel although only 1 in stride_h * stride_w meets an output; the explicit algorithm does
-    // not, and is the better guess where it fits.
-    const bool explicit_first = dir == SN_CONV_BWD_DATA && (g.sh > 1 || g.sw > 1);
     // Few input channels: the zero-workspace kernel is the memory-bound one (forward); backward-filter
     // runs it under either name, STAGED with a fixed summation order.
     if (dir == SN_CONV_FWD && smallc_supported(g)) {
@@ -372,12 +368,6 @@ sn_status plan(const sn_conv_shape *shape, const ConvGeom &g, sn_conv_dir dir, s
     }
     for (sn_conv_algo a : kRanking) {
         size_t mn = 0, pf = 0;
-        if (a == SN_ALGO_DIRECT && explicit_first && query(g, dir, SN_ALGO_IM2COL_GEMM, &mn, &pf) == SN_OK && mn <= budget) {
-            *algo = SN_ALGO_IM2COL_GEMM;
-            *bytes = std::min(pf, budget);
-            if (ms_out) *ms_out = -1.f;
-            return SN_OK;
-        }
         if (a == SN_ALGO_IM2COL_GEMM) continue;
         if (query(g, dir, a, &mn, &pf) != SN_OK || mn > budget) continue;
         if (a == SN_ALGO_STAGED && pf == 0) continue;   // nothing to stage: the same kernel runs as DIRECT
@@ -388,7 +378,8 @@ sn_status plan(const sn_conv_shape *shape, const ConvGeom &g, sn_conv_dir dir, s
                                       (long long)g.C * g.K < 8192)) continue;
         // The phase planes in passes: strided forward gains little over the zero-workspace kernel, so only
         // with the whole batch (below that STAGED forward is the gathering kernel, which needs the re-laid-out
-        // filter alone); backward-data gains 2-4x, which more than eight passes' launches eat up.
+        // filter alone); backward-data gains a quarter over the zero-workspace kernel, which works by residue
+        // classes of the input pixels, and more than two passes' launches eat that up.
         if (a == SN_ALGO_STAGED && pf > budget && (g.sh > 1 || g.sw > 1) && dir != SN_CONV_BWD_FILTER) {
             PhasePlan pp;
             if (dir == SN_CONV_FWD) {
@@ -396,7 +387,7 @@ sn_status plan(const sn_conv_shape *shape, const ConvGeom &g, sn_conv_dir dir, s
             } else {
                 if (!phase_plan(g, dir, &pp)) continue;
                 const int chunk = phase_chunk(pp, dir, budget);
-                if ((g.N + chunk - 1) / chunk > 8) continue;
+                if ((g.N + chunk - 1) / chunk > 2) continue;
             }
         }
         *algo = a;

@@ -154,6 +154,12 @@ CASES = [
     (L("g_1x1_s2_k512", 32, 14, 14, 512, 1, 1, (2, 2)), 4),
     # 1x1 / stride-2 backward-data written with the zeros of its 2x2 cells: an odd output width (single pixels per lane)
     (L("sc_1x1_s2_q5", 24, 10, 10, 40, 1, 1, (2, 2)), 3),
+    # zero-workspace strided backward-data by residue classes of the input pixels: two ragged tiles of input channels,
+    # output channels short of a whole step, a stride larger than one side of the filter (classes without taps store
+    # zeros), an image shorter than the stride along one axis
+    (L("cls_5x4_s32_c136", 136, 19, 22, 40, 5, 4, (3, 2), (2, 1)), 3),
+    (L("cls_2x5_s43", 24, 21, 17, 24, 2, 5, (4, 3), (1, 2)), 2),
+    (L("cls_short_image", 16, 2, 37, 16, 1, 3, (3, 2), (0, 1)), 2),
 ]
 IDS = [c[0].name for c in CASES]
 

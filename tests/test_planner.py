@@ -95,17 +95,17 @@ def test_record_rejects_infeasible_measurements():
 def test_cold_start_on_strided_shapes_counts_the_passes():
     """Without measurements the phase planes are guessed only where they pay (Sec. 3.5 leaves the
     ranking to measurement; this is the stand-in before any exists): backward-data in at most
-    eight passes, forward only with the whole batch; the explicit algorithm before the
-    zero-workspace kernel for strided backward-data otherwise."""
+    two passes, forward only with the whole batch; the zero-workspace kernel otherwise (never the
+    explicit algorithm, which is picked on measurement only)."""
     sn.sn_planner_clear()
     shape = sn.conv_shape(64, 128, 56, 56, 128, 3, 3, (2, 2), (1, 1), sn.SN_BF16, sn.SN_BF16)
     mn, pf = sn.sn_conv_workspace_query(shape, sn.SN_CONV_BWD_DATA, sn.SN_ALGO_STAGED)
     assert mn < pf                                     # one image's planes up to the whole batch
     per_image = (pf - mn) // 63
     assert sn.sn_conv_plan(shape, sn.SN_CONV_BWD_DATA, pf)[0] == sn.SN_ALGO_STAGED
-    assert sn.sn_conv_plan(shape, sn.SN_CONV_BWD_DATA, mn + 8 * per_image)[0] == sn.SN_ALGO_STAGED      # 9 images: 8 passes
-    algo, used, _ = sn.sn_conv_plan(shape, sn.SN_CONV_BWD_DATA, mn + 6 * per_image)                    # 7 images: 10 passes
-    assert algo == sn.SN_ALGO_IM2COL_GEMM and used <= mn + 6 * per_image
+    assert sn.sn_conv_plan(shape, sn.SN_CONV_BWD_DATA, mn + 31 * per_image)[0] == sn.SN_ALGO_STAGED     # 32 images: 2 passes
+    algo, used, _ = sn.sn_conv_plan(shape, sn.SN_CONV_BWD_DATA, mn + 30 * per_image)                   # 31 images: 3 passes
+    assert algo == sn.SN_ALGO_DIRECT and used == 0
     assert sn.sn_conv_plan(shape, sn.SN_CONV_BWD_DATA, 4096)[0] == sn.SN_ALGO_DIRECT
     fmn, fpf = sn.sn_conv_workspace_query(shape, sn.SN_CONV_FWD, sn.SN_ALGO_STAGED)
     assert sn.sn_conv_plan(shape, sn.SN_CONV_FWD, fpf)[0] == sn.SN_ALGO_STAGED
