@@ -90,7 +90,8 @@ typedef enum { SN_CONV_FWD = 0, SN_CONV_BWD_DATA = 1, SN_CONV_BWD_FILTER = 2 } s
  *               workspace for 1x1 filters with 512 output channels or more: below
  *               that, and for every other filter, it gathers the input pixel by
  *               pixel under each tap and stages only the filter with the channel
- *               innermost (min_bytes = K*C*R*S*2).  Otherwise forward and
+ *               innermost (min_bytes = K*C*R*S*2; 0 for 1x1 filters, which are that
+ *               form already, so DIRECT runs the same kernel).  Otherwise forward and
  *               backward-data take the planes of as many images per pass as the
  *               workspace holds (min_bytes: one image).
  *  WINOGRAD     F(2x2, 3x3) for the fp32 path (3x3 filters, stride 1, forward and

@@ -867,19 +867,24 @@ bool gather_conv_supported(const ConvGeom &g)
 
 size_t gather_conv_packed_bytes(const ConvGeom &g)
 {
+    if (g.R == 1 && g.S == 1) return 0;   // KC11 is already [k][tap][c]
     return align_up((size_t)g.K * g.C * g.R * g.S * sizeof(bf16_t), 256);
 }
 
 hipError_t launch_gather_conv_fwd(const void *x, const void *w, void *y, const ConvGeom &g, void *packed, hipStream_t st)
 {
     PwPlan pl;
-    if (!make_conv_plan(g, &pl) || !packed) return hipErrorInvalidValue;
-    const size_t total = (size_t)g.K * g.C * g.R * g.S;
-    hipLaunchKernelGGL(pack_tap_major_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                       static_cast<const bf16_t *>(w), static_cast<bf16_t *>(packed), g.C, g.R * g.S, total);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    const bf16_t *xs = static_cast<const bf16_t *>(x), *a = static_cast<const bf16_t *>(packed);
+    // a 1x1 filter is its own tap-major form: nothing to re-lay out, no workspace
+    const bool as_is = g.R == 1 && g.S == 1;
+    if (!make_conv_plan(g, &pl) || (!packed && !as_is)) return hipErrorInvalidValue;
+    if (!as_is) {
+        const size_t total = (size_t)g.K * g.C * g.R * g.S;
+        hipLaunchKernelGGL(pack_tap_major_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                           static_cast<const bf16_t *>(w), static_cast<bf16_t *>(packed), g.C, g.R * g.S, total);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    const bf16_t *xs = static_cast<const bf16_t *>(x), *a = static_cast<const bf16_t *>(as_is ? w : packed);
     const dim3 grid(pl.grid);
     if (pl.MS == 4) hipLaunchKernelGGL((pointwise_kernel<4, 4, false, false, false, true>), grid, dim3(256), 0, st, xs, a, y, pl.p);
     else if (pl.NW == 4) hipLaunchKernelGGL((pointwise_kernel<2, 4, false, false, false, true>), grid, dim3(256), 0, st, xs, a, y, pl.p);

@@ -438,6 +438,7 @@ hipError_t direct_fwd(const void *x, const void *w, void *y, const ConvGeom &g, 
 {
     if (smallc_supported(g)) return launch_smallc_fwd(x, w, y, g, st, nullptr);
     if (tile_conv_supported(g, false)) return launch_tile_conv(x, w, y, g, false, nullptr, st);
+    if (g.R == 1 && g.S == 1 && gather_fwd(g)) return launch_gather_conv_fwd(x, w, y, g, nullptr, st);
     return launch_generic_fwd(x, w, y, g, st);
 }
 
