@@ -664,7 +664,7 @@ bool make_wgrad_plan(const ConvGeom &g, PwWgradPlan *pl)
     return true;
 }
 
-// ---- backward-filter of 1x1 layers on planes whose size is a multiple of 4 (14x14, 28x28) ----------
+// ---- backward-filter of 1x1 layers through LDS (14x14; planes of odd sizes: 17x17, 35x35) ----------
 // Same product as above, but the operands reach the MFMAs through LDS: a workgroup owns 128 k x 128 c and
 // walks its images in stages of 64 pixels; the 256 rows (128 of dy, 128 of x) of a stage are fetched as
 // 8-byte items, 16 consecutive lanes per row (whole 128-byte runs, which 4-pixel-aligned rows allow),
@@ -680,6 +680,7 @@ struct PwWgradLdsProblem {
     int steps;     // 16-pixel steps per image
     int ipw;       // images per workgroup
     int atomics;
+    int ragged;    // HW is not a multiple of 4
     uint32_t d_bytes, x_bytes;
 };
 
@@ -716,19 +717,40 @@ pointwise_wgrad_lds_kernel(const bf16_t *__restrict__ x, const bf16_t *__restric
     const int first = z * p.ipw, nimg = min(max(p.N - first, 0), p.ipw);
     const int nq = nimg * p.spi;
 
+    // Planes that are no whole number of 4-pixel items: the item over a plane's end is fetched `back` pixels
+    // earlier, so that it ends with the plane (nothing past a plane, or past the tensor, is read), and moved
+    // down by as many pixels before it reaches LDS, which leaves zeros behind the plane's last pixel.  Only the
+    // last stage of an image has such an item; stages are parked in the order they were issued.
+    const int tail = p.HW - 64 * (p.spi - 1) - 4 * col8;   // pixels this thread's item has left in a last stage
+    const int back = p.ragged && tail > 0 && tail < 4 ? 4 - tail : 0;
     u32x2 reg[2][16];
     int n_iss = first, js_iss = 0;
     auto issue = [&](u32x2 (&rd)[16]) {   // the stage (n_iss, js_iss); past the last stage: zeros
         const bool live = n_iss < first + nimg;
         const uint32_t off = live && 64 * js_iss + 4 * col8 < p.HW ? 0u : OUTSIDE;
+        // the stage's offset within the plane, less the pixels a last item starts early by (never negative:
+        // such an item is not the first of its plane)
+        const uint32_t adv = js_iss * 128 - (js_iss == p.spi - 1 ? 2u * back : 0u);
         const uint32_t n = (uint32_t)min(n_iss, p.N - 1);
 #pragma unroll
-        for (int j = 0; j < 16; ++j)
-            rd[j] = j < 8 ? __builtin_amdgcn_raw_buffer_load_b64(dr, src[j] | off, n * dimg + js_iss * 128, 0)
-                          : __builtin_amdgcn_raw_buffer_load_b64(xr, src[j] | off, n * ximg + js_iss * 128, 0);
+        for (int j = 0; j < 16; ++j) {
+            const uint32_t v = (src[j] + adv) | (src[j] & OUTSIDE) | off;
+            rd[j] = j < 8 ? __builtin_amdgcn_raw_buffer_load_b64(dr, v, n * dimg, 0)
+                          : __builtin_amdgcn_raw_buffer_load_b64(xr, v, n * ximg, 0);
+        }
         if (++js_iss == p.spi) { js_iss = 0; ++n_iss; }
     };
-    auto park = [&](int buf, const u32x2 (&rd)[16]) {
+    int js_park = 0;
+    auto park = [&](int buf, u32x2 (&rd)[16]) {
+        if (p.ragged && js_park == p.spi - 1 && back) {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const uint64_t v = (((uint64_t)rd[j].y << 32) | rd[j].x) >> (16 * back);
+                rd[j].x = (uint32_t)v;
+                rd[j].y = (uint32_t)(v >> 32);
+            }
+        }
+        if (++js_park == p.spi) js_park = 0;
 #pragma unroll
         for (int j = 0; j < 16; ++j) *reinterpret_cast<u32x2 *>(wl_lds + buf * WL_BUF + dst + j * 16 * WL_PITCH) = rd[j];
     };
@@ -813,12 +835,14 @@ bool make_wgrad_lds_plan(const ConvGeom &g, PwWgradLdsPlan *pl)
     if (!g.in_bf16 || g.R != 1 || g.S != 1 || g.sh != 1 || g.sw != 1 || g.ph != 0 || g.pw != 0) return false;
     if (g.P != g.H || g.Q != g.W) return false;
     const long long HW = (long long)g.H * g.W;
-    // rows of the plane on 8-byte boundaries; short rows (where the row-stationary kernel's 8 x 16 chunks are mostly padding)
-    if (HW % 4 != 0 || g.W > 16) return false;
+    // short rows (where the row-stationary kernel's 8 x 16 chunks are mostly padding) and planes of an odd size
+    // (whose rows that kernel cannot fetch in aligned pieces)
+    if ((HW % 4 == 0 && g.W > 16) || HW < 8) return false;
     const long long lim = 0x7fffffffLL - (1 << 20);
     if ((long long)g.K * HW * 2 * g.N > lim || (long long)g.C * HW * 2 * g.N > lim) return false;
     PwWgradLdsProblem &p = pl->p;
     p.K = g.K; p.C = g.C; p.HW = (int)HW; p.N = g.N;
+    p.ragged = HW % 4 != 0;
     p.ctiles = (g.C + 127) / 128;
     const long long tiles = (long long)((g.K + 127) / 128) * p.ctiles;
     if (tiles > 0x7fffffffLL) return false;

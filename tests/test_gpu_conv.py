@@ -154,6 +154,12 @@ CASES = [
     (L("g_1x1_s2_k512", 32, 14, 14, 512, 1, 1, (2, 2)), 4),
     # 1x1 / stride-2 backward-data written with the zeros of its 2x2 cells: an odd output width (single pixels per lane)
     (L("sc_1x1_s2_q5", 24, 10, 10, 40, 1, 1, (2, 2)), 3),
+    # 1x1 backward-filter through LDS on planes that are no whole number of 4-pixel items (1, 2 and 3 pixels over):
+    # the item over a plane's end starts early and is moved down; ragged channel tiles, several slices
+    (L("pw_lds_9x9", 72, 9, 9, 136, 1, 1), 5),
+    (L("pw_lds_6x11", 136, 6, 11, 40, 1, 1), 3),
+    (L("pw_lds_5x19", 40, 5, 19, 72, 1, 1), 9),
+    (L("pw_lds_13x5", 24, 13, 5, 24, 1, 1), 2),
     # zero-workspace strided backward-data by residue classes of the input pixels: two ragged tiles of input channels,
     # output channels short of a whole step, a stride larger than one side of the filter (classes without taps store
     # zeros), an image shorter than the stride along one axis
