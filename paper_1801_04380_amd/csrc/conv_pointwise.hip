@@ -864,6 +864,221 @@ bool make_wgrad_lds_plan(const ConvGeom &g, PwWgradLdsPlan *pl)
     return true;
 }
 
+// ---- backward-filter of 1x1 layers with a stride or padding: the same product, x gathered ----
+// dw[k][c] = sum over (n, p, q) of dy[n][k][p][q] * x[n][c][p*sh - ph][q*sw - pw].  A workgroup owns 128 k x 128 c
+// and walks its images in stages of 64 output pixels: dy arrives as in the kernel above (8-byte items of the flat
+// plane, the item over its end fetched early and shifted down); x is gathered element by element, a wavefront
+// taking 64 consecutive output pixels of one channel per load (addresses sw elements apart within an output row;
+// pixels in the padding or past the plane read as zeros from an out-of-range offset) and parking them as 2-byte
+// items.  The gathers use a quarter of every cache line they touch (stride 2), and every tile of output channels
+// repeats them, which bounds the kernel; a tap at a time it also ran larger filters, and lost to the fallback
+// kernel on each (3x3 / stride 2: 185 - 380 against 164 - 182 us), so it is built for 1x1 filters only.
+struct GwProblem {
+    int K, C, N;
+    int PQ, Q;          // the plane of dy
+    int H, W;           // the plane of x
+    int sh, sw, ph, pw;
+    int d64, m64;       // 64 / Q, 64 % Q: how a stage moves a pixel's (row, column)
+    int ctiles, units, slices;   // units = tiles of 128 k x 128 c
+    int spi, steps, ipw, atomics, ragged;
+    uint32_t d_bytes, x_bytes;
+};
+
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+gather_wgrad_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, float *__restrict__ out, GwProblem p)
+{
+    extern __shared__ __attribute__((aligned(16))) char wl_lds[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, g = lane >> 5, wk = wave >> 1, wc = wave & 1;
+    const int xcd = blockIdx.x & 7, rest = blockIdx.x >> 3;
+    const int unit = rest % p.units, z = (rest / p.units) * 8 + xcd;
+    if (z >= p.slices) return;
+    const int kt = unit / p.ctiles, ct = unit - kt * p.ctiles;
+    const int k0 = kt * 128, c0 = ct * 128;
+    const __amdgpu_buffer_rsrc_t dr = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(dy), 0, p.d_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(x), 0, p.x_bytes, 0x00020000);
+
+    // dy: item j of the thread is row (tid >> 4) + 16 * j of the stage, pixels 4 * (tid & 15) .. + 3
+    const int col8 = tid & 15, row0 = tid >> 4;
+    uint32_t src[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int ch = k0 + row0 + 16 * j;
+        src[j] = ch < p.K ? (uint32_t)ch * p.PQ * 2 + col8 * 8 : OUTSIDE;
+    }
+    const uint32_t dst_a = row0 * WL_PITCH + col8 * 8;   // + 16 * j rows
+    // x: the thread's pixel of the stage is its lane; its wavefront takes channels c0 + wave + 4 * j
+    const uint32_t xplane = (uint32_t)p.H * p.W * 2;
+    const uint32_t xbase = (uint32_t)(c0 + wave) * xplane;
+    const int jlim = c0 + wave < p.C ? (p.C - c0 - wave + 3) / 4 : 0;   // channels of the wavefront inside the tensor
+    const uint32_t dst_b = (128 + wave) * WL_PITCH + lane * 2;           // + 4 * j rows
+    const uint32_t dimg = (uint32_t)p.K * p.PQ * 2, ximg = (uint32_t)p.C * xplane;
+
+    const int first = z * p.ipw, nimg = min(max(p.N - first, 0), p.ipw);
+    const int nq = nimg * p.spi;
+
+    const int tail = p.PQ - 64 * (p.spi - 1) - 4 * col8;   // pixels this thread's dy item has left in a last stage
+    const int back = p.ragged && tail > 0 && tail < 4 ? 4 - tail : 0;
+    const int pp0 = lane / p.Q, qq0 = lane - pp0 * p.Q;    // the thread's output pixel in stage 0
+    u32x2 ra[2][8];
+    uint32_t rb[2][32];
+    int n_iss = first, js_iss = 0, pp = pp0, qq = qq0;
+    auto issue = [&](u32x2 (&rd)[8], uint32_t (&rx)[32]) {   // the stage (n_iss, js_iss); past the last stage: zeros
+        const bool live = n_iss < first + nimg;
+        const uint32_t off = live && 64 * js_iss + 4 * col8 < p.PQ ? 0u : OUTSIDE;
+        const uint32_t adv = js_iss * 128 - (js_iss == p.spi - 1 ? 2u * back : 0u);
+        const uint32_t n = (uint32_t)min(n_iss, p.N - 1);
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            rd[j] = __builtin_amdgcn_raw_buffer_load_b64(dr, (src[j] + adv) | (src[j] & OUTSIDE) | off, n * dimg, 0);
+        const int hh = pp * p.sh - p.ph, ww = qq * p.sw - p.pw;
+        const bool in = live && 64 * js_iss + lane < p.PQ && (unsigned)hh < (unsigned)p.H && (unsigned)ww < (unsigned)p.W;
+        const uint32_t voff = in ? xbase + (uint32_t)(hh * p.W + ww) * 2 : OUTSIDE;
+#pragma unroll
+        for (int j = 0; j < 32; ++j)
+            rx[j] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(xr, j < jlim ? voff : OUTSIDE, n * ximg + j * 4 * xplane, 0);
+        if (++js_iss == p.spi) {
+            js_iss = 0; ++n_iss; pp = pp0; qq = qq0;
+        } else {
+            pp += p.d64; qq += p.m64;
+            if (qq >= p.Q) { qq -= p.Q; ++pp; }
+        }
+    };
+    int js_park = 0;
+    auto park = [&](int buf, u32x2 (&rd)[8], const uint32_t (&rx)[32]) {
+        if (p.ragged && js_park == p.spi - 1 && back) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const uint64_t v = (((uint64_t)rd[j].y << 32) | rd[j].x) >> (16 * back);
+                rd[j].x = (uint32_t)v;
+                rd[j].y = (uint32_t)(v >> 32);
+            }
+        }
+        if (++js_park == p.spi) js_park = 0;
+        char *b = wl_lds + buf * WL_BUF;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) *reinterpret_cast<u32x2 *>(b + dst_a + j * 16 * WL_PITCH) = rd[j];
+#pragma unroll
+        for (int j = 0; j < 32; ++j) *reinterpret_cast<uint16_t *>(b + dst_b + j * 4 * WL_PITCH) = (uint16_t)rx[j];
+    };
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    // as in the kernel above: stage q is multiplied out of LDS buffer q % 3 while stage q + 1 goes from registers
+    // into the next buffer and stage q + 2 is on its way from memory
+    issue(ra[0], rb[0]);
+    __builtin_amdgcn_sched_barrier(0);
+    issue(ra[1], rb[1]);
+    __builtin_amdgcn_sched_barrier(0);
+    park(0, ra[0], rb[0]);
+    __syncthreads();
+    const uint32_t aoff = (wk * 64 + l32) * WL_PITCH + 16 * g, boff = (128 + wc * 64 + l32) * WL_PITCH + 16 * g;
+    int js = 0, cur = 0;
+    for (int q0 = 0; q0 < nq; q0 += 2) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            issue(ra[h], rb[h]);
+            __builtin_amdgcn_sched_barrier(0);
+            const char *b = wl_lds + cur * WL_BUF;
+            const int nxt = cur == 2 ? 0 : cur + 1;
+            const int nst = min(4, p.steps - 4 * js);
+            if (++js == p.spi) js = 0;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                if (s < nst) {
+                    bf16x8 a[2], bb[2];
+#pragma unroll
+                    for (int i = 0; i < 2; ++i) {
+                        u32x4 da = *reinterpret_cast<const u32x4 *>(b + aoff + i * 32 * WL_PITCH + s * 32);
+                        u32x4 db = *reinterpret_cast<const u32x4 *>(b + boff + i * 32 * WL_PITCH + s * 32);
+                        __builtin_memcpy(&a[i], &da, 16);
+                        __builtin_memcpy(&bb[i], &db, 16);
+                    }
+#pragma unroll
+                    for (int i = 0; i < 2; ++i)
+#pragma unroll
+                        for (int j = 0; j < 2; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bb[j], acc[i][j], 0, 0, 0);
+                }
+            }
+            park(nxt, ra[1 - h], rb[1 - h]);
+            __syncthreads();
+            cur = nxt;
+        }
+    }
+
+    float *o = out + (p.atomics ? 0 : (size_t)z * p.K * p.C);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int k = k0 + wk * 64 + 32 * i + 8 * (v >> 2) + 4 * g + (v & 3);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int c = c0 + wc * 64 + 32 * j + l32;
+                if (k < p.K && c < p.C) {
+                    float *e = o + (size_t)k * p.C + c;
+                    if (p.atomics) unsafeAtomicAdd(e, acc[i][j][v]);
+                    else *e = acc[i][j][v];
+                }
+            }
+        }
+}
+
+struct GwPlan {
+    GwProblem p;
+    dim3 grid;
+};
+
+bool make_gather_wgrad_plan(const ConvGeom &g, GwPlan *pl)
+{
+    if (!g.in_bf16 || g.R != 1 || g.S != 1) return false;
+    const long long PQ = (long long)g.P * g.Q, HW = (long long)g.H * g.W;
+    if (PQ < 8) return false;   // the early-fetched last item of a plane is not its first
+    // every tile of output channels gathers x again: beyond eight of them the fallback kernel is faster
+    // (measured on 1024 -> 2048 channels, 14x14 -> 7x7: 296 against 160 us)
+    if (g.K > 1024) return false;
+    const long long lim = 0x7fffffffLL - (1 << 20);
+    if ((long long)g.K * PQ * 2 * g.N > lim || (long long)g.C * HW * 2 * g.N > lim) return false;
+    GwProblem &p = pl->p;
+    p.K = g.K; p.C = g.C; p.N = g.N;
+    p.PQ = (int)PQ; p.Q = g.Q; p.H = g.H; p.W = g.W;
+    p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw;
+    p.d64 = 64 / g.Q; p.m64 = 64 % g.Q;
+    p.ragged = PQ % 4 != 0;
+    p.ctiles = (g.C + 127) / 128;
+    const long long units = (long long)((g.K + 127) / 128) * p.ctiles;
+    if (units > (1 << 24)) return false;
+    p.units = (int)units;
+    p.spi = (int)((PQ + 63) / 64);
+    p.steps = (int)((PQ + 15) / 16);
+    // One workgroup fits a compute unit (three stage buffers of LDS): the slices of the batch are chosen for the
+    // fewest rounds of 256 workgroups times images per workgroup; among equals the fewest slices (partial sums).
+    // A workgroup's epilogue (its 128 x 128 sums, and their share of the reduction that follows) is priced at 16 stages.
+    long long best = 0, best_cost = -1;
+    for (long long sl = 1; sl <= g.N; ++sl) {
+        const long long ipw = (g.N + sl - 1) / sl;
+        if ((g.N + ipw - 1) / ipw != sl) continue;   // the same images per workgroup in fewer slices
+        const long long cost = ((units * sl + 255) / 256) * (ipw * p.spi + 16);
+        if (best_cost < 0 || cost < best_cost) { best = sl; best_cost = cost; }
+    }
+    p.slices = (int)best;
+    p.ipw = (int)((g.N + best - 1) / best);
+    if (p.slices > 65535) return false;
+    p.d_bytes = (uint32_t)((long long)g.K * PQ * 2 * g.N);
+    p.x_bytes = (uint32_t)((long long)g.C * HW * 2 * g.N);
+    const long long grid = 8 * units * ((best + 7) / 8);
+    if (grid > 0x7fffffffLL) return false;
+    pl->grid = dim3((unsigned)grid);
+    return true;
+}
+
 }  // namespace
 
 bool pointwise_supported(const ConvGeom &g, bool bwd_data)
@@ -964,6 +1179,43 @@ hipError_t launch_pointwise_wgrad(const void *x, const void *dy, float *dw, cons
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (partial && !direct_store) return launch_reduce_partials(partial, dw, nw, slices, false, st);
+    return hipSuccess;
+}
+
+bool gather_wgrad_supported(const ConvGeom &g)
+{
+    GwPlan pl;
+    return make_gather_wgrad_plan(g, &pl);
+}
+
+int gather_wgrad_slices(const ConvGeom &g)
+{
+    GwPlan pl;
+    return make_gather_wgrad_plan(g, &pl) ? pl.p.slices : 0;
+}
+
+// partial == nullptr: slices add into dw with atomics (dw is zero-filled first; one slice stores);
+// otherwise slice z writes partial[z][K*C] and a reduction in slice order follows.
+hipError_t launch_gather_wgrad(const void *x, const void *dy, float *dw, const ConvGeom &g, float *partial, hipStream_t st)
+{
+    GwPlan pl;
+    if (!make_gather_wgrad_plan(g, &pl)) return hipErrorInvalidValue;
+    const size_t nw = (size_t)g.K * g.C;
+    const bool direct_store = pl.p.slices == 1;
+    pl.p.atomics = (!partial && !direct_store) ? 1 : 0;
+    if (pl.p.atomics) {
+        hipError_t e = launch_fill_zero(dw, nw, st);
+        if (e != hipSuccess) return e;
+    }
+    float *out = (partial && !direct_store) ? partial : dw;
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(gather_wgrad_kernel),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, WL_NBUF * WL_BUF);
+    if (attr != hipSuccess) return attr;
+    hipLaunchKernelGGL(gather_wgrad_kernel, pl.grid, dim3(256), WL_NBUF * WL_BUF, st, static_cast<const bf16_t *>(x),
+                       static_cast<const bf16_t *>(dy), out, pl.p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (partial && !direct_store) return launch_reduce_partials(partial, dw, nw, pl.p.slices, false, st);
     return hipSuccess;
 }
 

@@ -101,7 +101,8 @@ ConvGeom gemm_geom_1x1(const ConvGeom &g, int nimg)
 size_t staged_bwd_filter_bytes(const ConvGeom &g, int *splits_out)
 {
     int splits = smallc_supported(g) ? smallc_wgrad_slices(g)
-               : tile_wgrad_supported(g) ? tile_wgrad_slices(g) : generic_bwd_filter_splits(g);
+               : tile_wgrad_supported(g) ? tile_wgrad_slices(g)
+               : gather_wgrad_supported(g) ? gather_wgrad_slices(g) : generic_bwd_filter_splits(g);
     if (splits_out) *splits_out = splits;
     return align_up((size_t)splits * g.K * g.C * g.R * g.S * sizeof(float), WS_ALIGN);
 }
@@ -155,6 +156,9 @@ bool phase_plan(const ConvGeom &g, sn_conv_dir dir, PhasePlan *pp)
 {
     if (!g.in_bf16 || (g.sh == 1 && g.sw == 1)) return false;
     if (g.R > 16 || g.S > 16) return false;
+    // padding at least as large as the filter (the first output row or column sees padding only: every tap has
+    // a negative plane offset) is not built here; such shapes run the other kernels
+    if (g.ph >= g.R || g.pw >= g.S) return false;
     PhaseMap &m = pp->m;
     m.sh = g.sh; m.sw = g.sw; m.ph = g.ph; m.pw = g.pw;
     int dmin, dmax, emin, emax, xr, xc;
@@ -542,6 +546,7 @@ sn_status run_bwd_filter(const void *x, const void *dy, void *dw, const ConvGeom
         return launch_status(launch_smallc_wgrad(x, dy, dwf, g, algo == SN_ALGO_STAGED ? static_cast<float *>(ws) : nullptr, st));
     if (algo == SN_ALGO_DIRECT) {
         if (tile) return launch_status(launch_tile_wgrad(x, dy, dwf, g, nullptr, st));
+        if (gather_wgrad_supported(g)) return launch_status(launch_gather_wgrad(x, dy, dwf, g, nullptr, st));
         return launch_status(launch_generic_bwd_filter(x, dy, dwf, g, generic_bwd_filter_splits(g), nullptr, false, st));
     }
     PhasePlan pp;
@@ -559,6 +564,7 @@ sn_status run_bwd_filter(const void *x, const void *dy, void *dw, const ConvGeom
     }
     if (algo == SN_ALGO_STAGED) {
         if (tile) return launch_status(launch_tile_wgrad(x, dy, dwf, g, static_cast<float *>(ws), st));
+        if (gather_wgrad_supported(g)) return launch_status(launch_gather_wgrad(x, dy, dwf, g, static_cast<float *>(ws), st));
         int splits;
         staged_bwd_filter_bytes(g, &splits);
         return launch_status(launch_generic_bwd_filter(x, dy, dwf, g, splits, static_cast<float *>(ws), false, st));

@@ -104,6 +104,11 @@ bool pointwise_wgrad_supported(const ConvGeom &g);
 int pointwise_wgrad_slices(const ConvGeom &g);
 hipError_t launch_pointwise_wgrad(const void *x, const void *dy, float *dw, const ConvGeom &g, float *partial,
                                   hipStream_t st);
+// Backward-filter of 1x1 layers with a stride or padding (up to 1024 output channels), x gathered under each
+// output pixel (conv_pointwise.hip): runs where neither the stride-1 kernels nor the few-channel kernel apply.
+bool gather_wgrad_supported(const ConvGeom &g);
+int gather_wgrad_slices(const ConvGeom &g);
+hipError_t launch_gather_wgrad(const void *x, const void *dy, float *dw, const ConvGeom &g, float *partial, hipStream_t st);
 
 hipError_t launch_fill_zero(float *p, size_t n, hipStream_t st);
 // dw[i] = (accumulate ? dw[i] : 0) + sum_z partial[z][i], z ascending.

@@ -160,6 +160,10 @@ CASES = [
     (L("pw_lds_6x11", 136, 6, 11, 40, 1, 1), 3),
     (L("pw_lds_5x19", 40, 5, 19, 72, 1, 1), 9),
     (L("pw_lds_13x5", 24, 13, 5, 24, 1, 1), 2),
+    # 1x1 backward-filter with x gathered under each output pixel (zero workspace): padding that puts the first row
+    # and column of outputs on zeros, an output plane of 30 pixels (2 over a 4-pixel item), strides that differ
+    (L("gw_1x1_s2_pad1", 136, 9, 11, 72, 1, 1, (2, 2), (1, 1)), 5),
+    (L("gw_1x1_s13", 40, 6, 31, 136, 1, 1, (1, 3)), 3),
     # zero-workspace strided backward-data by residue classes of the input pixels: two ragged tiles of input channels,
     # output channels short of a whole step, a stride larger than one side of the filter (classes without taps store
     # zeros), an image shorter than the stride along one axis
