@@ -199,6 +199,11 @@ bool make_plan(const TileProblem &base, int R, int S, bool staged, Plan *pl, boo
         Plan alt;
         if (plan_for(base, R, S, 2, &alt, prefer_narrow)) *pl = alt;
     }
+    // still under half of them (7x7 images): halve again
+    if (pl->NF == 2 && (long long)pl->p.nptiles * pl->p.nktiles < 128) {
+        Plan alt;
+        if (plan_for(base, R, S, 1, &alt, prefer_narrow)) *pl = alt;
+    }
     return true;
 }
 

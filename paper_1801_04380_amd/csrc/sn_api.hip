@@ -327,7 +327,7 @@ bool same_shape(const sn_conv_shape &a, const sn_conv_shape &b) { return std::me
 // tried first.  The workspace-staged implicit GEMM, then the direct one; the
 // explicit unfold pays a write and a read of a buffer R*S times the input, so it
 // is picked on measurement only.
-const sn_conv_algo kRanking[] = {SN_ALGO_WINOGRAD, SN_ALGO_STAGED, SN_ALGO_DIRECT, SN_ALGO_IM2COL_GEMM};
+const sn_conv_algo kRanking[] = {SN_ALGO_WINOGRAD, SN_ALGO_STAGED, SN_ALGO_DIRECT};
 
 sn_status plan(const sn_conv_shape *shape, const ConvGeom &g, sn_conv_dir dir, size_t budget,
                sn_conv_algo *algo, size_t *bytes, float *ms_out)
@@ -372,7 +372,6 @@ sn_status plan(const sn_conv_shape *shape, const ConvGeom &g, sn_conv_dir dir, s
     }
     for (sn_conv_algo a : kRanking) {
         size_t mn = 0, pf = 0;
-        if (a == SN_ALGO_IM2COL_GEMM) continue;
         if (query(g, dir, a, &mn, &pf) != SN_OK || mn > budget) continue;
         if (a == SN_ALGO_STAGED && pf == 0) continue;   // nothing to stage: the same kernel runs as DIRECT
         // Winograd pays four kernels per pass and streams 16 transformed values per 4 inputs: a guess in its
