@@ -167,6 +167,10 @@ bool phase_plan(const ConvGeom &g, sn_conv_dir dir, PhasePlan *pp)
     // planes larger than the output: the inner convolution is no longer a "same" one, which the
     // backward-filter kernels are built for
     if ((xr || xc || dmax > 1 || emax > 1) && dir == SN_CONV_BWD_FILTER) return false;
+    // backward-filter of larger filters on small planes: the 3x3 inner filter multiplies four times the taps, on
+    // planes the row-stationary kernel fills badly; the fallback kernel is faster there (measured 3x3 / stride 2,
+    // 28 -> 14: 129 against 146 us, 14 -> 7: 152 against 218 us; level at 56 -> 28)
+    if (dir == SN_CONV_BWD_FILTER && g.R * g.S > 1 && g.P * g.Q <= 196) return false;
     m.nphases = m.na * m.nb;
     const bool one_tap = dmin == 0 && dmax == 0 && emin == 0 && emax == 0;
     // Offsets that span two values on either axis (3x3 / stride 2: -1 .. 0 with padding 1, 0 .. 1 without) fit a
