@@ -557,9 +557,9 @@ igemm_bwd_filter_kernel(const T *__restrict__ dy, const T *__restrict__ x, float
     const int seg = tid % SEGS, r0 = tid / SEGS;
     const int PQ = g.P * g.Q, RS = g.R * g.S;
 
-    // the thread's B columns: channel plane and tap offsets
-    long long bplane[B_IT];
-    int bdr[B_IT], bds[B_IT];
+    // the thread's B columns: tap offsets, and the element of the image the tap reads under output pixel (0, 0)
+    // (an image has fewer than 2^31 elements; the batch may have more)
+    int bconst[B_IT], bdr[B_IT], bds[B_IT];
     bool bok[B_IT];
 #pragma unroll
     for (int i = 0; i < B_IT; ++i) {
@@ -567,16 +567,32 @@ igemm_bwd_filter_kernel(const T *__restrict__ dy, const T *__restrict__ x, float
         bok[i] = j < d.Ncols;
         const int jj = bok[i] ? j : 0;
         const int c = jj / RS, rs = jj - c * RS, r = rs / g.S;
-        bplane[i] = (long long)c * g.H * g.W;
         bdr[i] = r - g.ph;
         bds[i] = rs - r * g.S - g.pw;
+        bconst[i] = (c * g.H + bdr[i]) * g.W + bds[i];
+    }
+    const long long xplane_img = (long long)g.C * g.H * g.W;
+    // the thread's first pixel of the step about to be fetched, kept from step to step (a step is BK pixels on)
+    const int step_q = BK % g.Q, step_p = BK / g.Q;
+    int fn, fp, fq;
+    {
+        const int kk = min(kbeg + seg * VEC, d.Kred - 1);
+        fn = kk / PQ;
+        const int pq = kk - fn * PQ;
+        fp = pq / g.Q;
+        fq = pq - fp * g.Q;
     }
 
     u32x4v ra[A_IT], rb[B_IT];
     auto fetch = [&](int k0) {
         const int kk = k0 + seg * VEC;
-        const int kc = min(kk, d.Kred - 1);
-        int n = kc / PQ, pq = kc - n * PQ;
+        int n = fn, p = fp, q = fq;
+        const int pq = p * g.Q + q;
+        // the same thread's pixel one step on (past the slice's end nothing is loaded)
+        fq += step_q;
+        fp += step_p;
+        if (fq >= g.Q) { fq -= g.Q; ++fp; }
+        while (fp >= g.P) { fp -= g.P; ++fn; }
         // A: dy[n][m][pq .. pq + VEC - 1]
         const bool whole = kk + VEC <= kend && pq + VEC <= PQ;
 #pragma unroll
@@ -596,18 +612,17 @@ igemm_bwd_filter_kernel(const T *__restrict__ dy, const T *__restrict__ x, float
             ra[i] = pack.u;
         }
         // B: x under each of the VEC pixels
-        int p = pq / g.Q, q = pq - p * g.Q;
         union { T t[VEC]; u32x4v u; } pb[B_IT];
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
             const bool live = kk + e < kend;
-            const long long img = (long long)n * g.C * g.H * g.W;
-            const int hb = p * g.sh, wb = q * g.sw;
+            const T *img = x + n * xplane_img;
+            const int hb = p * g.sh, wb = q * g.sw, po = hb * g.W + wb;
 #pragma unroll
             for (int i = 0; i < B_IT; ++i) {
-                const int h = hb + bdr[i], w = wb + bds[i];
-                const bool in = live && bok[i] && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W;
-                pb[i].t[e] = in ? x[img + bplane[i] + (long long)h * g.W + w] : zero_of<T>();
+                const bool in = live && bok[i] && (unsigned)(hb + bdr[i]) < (unsigned)g.H &&
+                                (unsigned)(wb + bds[i]) < (unsigned)g.W;
+                pb[i].t[e] = in ? img[bconst[i] + po] : zero_of<T>();
             }
             if (++q == g.Q) { q = 0; if (++p == g.P) { p = 0; ++n; } }
         }
