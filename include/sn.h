@@ -78,7 +78,9 @@ typedef enum { SN_CONV_FWD = 0, SN_CONV_BWD_DATA = 1, SN_CONV_BWD_FILTER = 2 } s
  *               workspace: the filter packed tap-major for forward and
  *               backward-data; per-slice partial sums of dw (reduced in a fixed
  *               order, so the result is run-to-run identical) for
- *               backward-filter.  On strided shapes (bf16; 1x1 filters without
+ *               backward-filter (3x3, 1x1, 5x5, 1x7 and 7x1 "same" layers take from a
+ *               quarter of the slices they want, min_bytes, up to all of them,
+ *               preferred_bytes: fewer slices are fewer, longer workgroups).  On strided shapes (bf16; 1x1 filters without
  *               padding, and filters whose taps reach at most one row / column
  *               of the stride grid beyond the output's, e.g. 3x3 stride 2 pad 1, or
  *               at most two on one side without padding, e.g. 11x11 stride 4)

@@ -531,10 +531,13 @@ bool tile_wgrad_supported(const ConvGeom &g)
     return pointwise_wgrad_supported(g) || rows_wgrad_supported(g) || make_wplan(g, &pl);
 }
 
-int tile_wgrad_slices(const ConvGeom &g)
+// The kernel that takes the shape with partial sums is the row-stationary one, whose slice count can be capped.
+bool tile_wgrad_cappable(const ConvGeom &g) { return !pointwise_wgrad_supported(g) && rows_wgrad_supported(g); }
+
+int tile_wgrad_slices(const ConvGeom &g, int cap)
 {
     if (pointwise_wgrad_supported(g)) return pointwise_wgrad_slices(g);
-    if (rows_wgrad_supported(g)) return rows_wgrad_slices(g);
+    if (rows_wgrad_supported(g)) return rows_wgrad_slices(g, cap);
     WPlan pl;
     return make_wplan(g, &pl) ? (int)pl.grid.z : 0;
 }
@@ -542,7 +545,7 @@ int tile_wgrad_slices(const ConvGeom &g)
 // partial == nullptr: slices add into dw with atomics (dw is zero-filled first);
 // otherwise slice z writes partial[z][K*C*R*S] and a reduction in slice order follows.
 hipError_t launch_tile_wgrad(const void *x, const void *dy, float *dw, const ConvGeom &g, float *partial,
-                             hipStream_t st)
+                             hipStream_t st, int cap)
 {
     if (pointwise_wgrad_supported(g)) return launch_pointwise_wgrad(x, dy, dw, g, partial, st);
     WPlan pl;
@@ -550,7 +553,7 @@ hipError_t launch_tile_wgrad(const void *x, const void *dy, float *dw, const Con
     // that is twice as fast as this file's kernel (measured 344 against 680 us on 96 -> 256 channels, 27x27),
     // with five rounds of atomics it is slower (758 against 700 us)
     const bool rows5 = g.R == 5 && !partial && make_wplan(g, &pl);
-    if (rows_wgrad_supported(g) && !rows5) return launch_rows_wgrad(x, dy, dw, g, partial, st);
+    if (rows_wgrad_supported(g) && !rows5) return launch_rows_wgrad(x, dy, dw, g, partial, st, partial ? cap : 0);
     if (!make_wplan(g, &pl)) return hipErrorInvalidValue;
     const size_t nw = (size_t)g.K * g.C * g.R * g.S;
     const int slices = (int)pl.grid.z;

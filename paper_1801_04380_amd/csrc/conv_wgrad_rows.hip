@@ -496,7 +496,8 @@ constexpr size_t rows_smem()
     return stage > epi ? stage : epi;
 }
 
-bool make_rplan(const ConvGeom &g, RPlan *pl)
+// cap > 0: at most that many slices (the caller's workspace holds no more partial sums)
+bool make_rplan(const ConvGeom &g, RPlan *pl, int cap = 0)
 {
     if (!g.in_bf16 || g.sh != 1 || g.sw != 1) return false;
     if (!((g.R == 3 && g.S == 3) || (g.R == 1 && g.S == 1) || (g.R == 5 && g.S == 5) || (g.R == 7 && g.S == 1) ||
@@ -533,6 +534,7 @@ bool make_rplan(const ConvGeom &g, RPlan *pl)
     long long slices = (256 + tiles - 1) / tiles;
     if (slices > p.nchunks) slices = p.nchunks;
     if (slices > 65535) slices = 65535;
+    if (cap > 0 && slices > cap) slices = cap;
     if (slices < 1) slices = 1;
     p.cps = (int)((p.nchunks + slices - 1) / slices);
     slices = (p.nchunks + p.cps - 1) / p.cps;
@@ -591,19 +593,19 @@ bool rows_wgrad_supported(const ConvGeom &g)
     return make_rplan(g, &pl);
 }
 
-int rows_wgrad_slices(const ConvGeom &g)
+int rows_wgrad_slices(const ConvGeom &g, int cap)
 {
     RPlan pl;
-    return make_rplan(g, &pl) ? pl.nslices : 0;
+    return make_rplan(g, &pl, cap) ? pl.nslices : 0;
 }
 
 // partial == nullptr: slices add into dw with atomics (dw is zero-filled first);
 // otherwise slice z writes partial[z][K*C*R*S] and a reduction in slice order follows.
 hipError_t launch_rows_wgrad(const void *x, const void *dy, float *dw, const ConvGeom &g, float *partial,
-                             hipStream_t st)
+                             hipStream_t st, int cap)
 {
     RPlan pl;
-    if (!make_rplan(g, &pl)) return hipErrorInvalidValue;
+    if (!make_rplan(g, &pl, cap)) return hipErrorInvalidValue;
     const size_t nw = (size_t)g.K * g.C * g.R * g.S;
     const int slices = pl.nslices;
     const bool direct_store = !partial && slices == 1;

@@ -107,6 +107,28 @@ size_t staged_bwd_filter_bytes(const ConvGeom &g, int *splits_out)
     return align_up((size_t)splits * g.K * g.C * g.R * g.S * sizeof(float), WS_ALIGN);
 }
 
+// The row-stationary kernel also runs with fewer slices than fill the chip (fewer, longer workgroups): a
+// quarter of them is the least STAGED backward-filter takes, so its workspace is a range (Sec. 3.5: more
+// workspace, more speed).  Whether the shape has that range, and its least workspace.
+bool staged_bwd_filter_ranged(const ConvGeom &g)
+{
+    return !smallc_supported(g) && tile_wgrad_supported(g) && tile_wgrad_cappable(g);
+}
+
+size_t staged_bwd_filter_min_bytes(const ConvGeom &g)
+{
+    const int full = tile_wgrad_slices(g), least = tile_wgrad_slices(g, (full + 3) / 4);
+    return align_up((size_t)least * g.K * g.C * g.R * g.S * sizeof(float), WS_ALIGN);
+}
+
+// Slices the row-stationary kernel may use with ws_bytes of workspace (0: all it wants).
+int staged_bwd_filter_cap(const ConvGeom &g, size_t ws_bytes)
+{
+    if (!staged_bwd_filter_ranged(g) || ws_bytes >= staged_bwd_filter_bytes(g, nullptr)) return 0;
+    const size_t per = (size_t)g.K * g.C * g.R * g.S * sizeof(float);
+    return (int)std::max<size_t>(1, ws_bytes / per);
+}
+
 // ---- STAGED on strided shapes: phase decomposition (conv_phase.hip) -----------------------------
 // The strided convolution becomes a stride-1 convolution over the phase planes of the input: 1x1
 // filters (no padding) keep a 1x1 filter over the one phase they touch; other filters whose taps
@@ -304,6 +326,7 @@ sn_status query(const ConvGeom &g, sn_conv_dir dir, sn_conv_algo algo, size_t *m
         }
         if (dir == SN_CONV_BWD_FILTER) {
             *min_b = *pref_b = staged_bwd_filter_bytes(g, nullptr);
+            if (staged_bwd_filter_ranged(g)) *min_b = staged_bwd_filter_min_bytes(g);
             return SN_OK;
         }
         if (!tile_conv_supported(g, dir == SN_CONV_BWD_DATA)) return SN_ERR_UNSUPPORTED;
@@ -397,6 +420,9 @@ sn_status plan(const sn_conv_shape *shape, const ConvGeom &g, sn_conv_dir dir, s
                 if ((g.N + chunk - 1) / chunk > 2) continue;
             }
         }
+        // backward-filter with fewer partial sums than it wants: a guess in its favour down to half of them
+        // (below that the zero-workspace form's atomics are the better guess)
+        if (a == SN_ALGO_STAGED && dir == SN_CONV_BWD_FILTER && pf > budget && budget < mn + (pf - mn) / 3) continue;
         *algo = a;
         *bytes = std::min(pf, budget);
         if (ms_out) *ms_out = -1.f;
@@ -566,7 +592,7 @@ sn_status run_bwd_filter(const void *x, const void *dy, void *dw, const ConvGeom
         return launch_status(launch_phase_dw(inner_dw, dwf, pp.m, g, st));
     }
     if (algo == SN_ALGO_STAGED) {
-        if (tile) return launch_status(launch_tile_wgrad(x, dy, dwf, g, static_cast<float *>(ws), st));
+        if (tile) return launch_status(launch_tile_wgrad(x, dy, dwf, g, static_cast<float *>(ws), st, staged_bwd_filter_cap(g, ws_bytes)));
         if (gather_wgrad_supported(g)) return launch_status(launch_gather_wgrad(x, dy, dwf, g, static_cast<float *>(ws), st));
         int splits;
         staged_bwd_filter_bytes(g, &splits);

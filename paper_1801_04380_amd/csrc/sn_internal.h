@@ -63,16 +63,19 @@ int tile_conv_stats_tiles(const ConvGeom &g, bool staged, bool in_aligned16);
 // Stride-1 bf16 backward-filter fast path.  partial == nullptr: the slices of the
 // (n,p,q) sum combine with atomics into a zero-filled dw; otherwise slice z writes
 // partial[z][K*C*R*S] (tile_wgrad_slices of them) and a fixed-order reduction follows.
+// cap > 0 (with partial): at most that many slices, where the kernel that takes the shape can work with
+// fewer (tile_wgrad_cappable: the row-stationary one) -- a workspace that holds fewer partial sums.
 bool tile_wgrad_supported(const ConvGeom &g);
-int tile_wgrad_slices(const ConvGeom &g);
+bool tile_wgrad_cappable(const ConvGeom &g);
+int tile_wgrad_slices(const ConvGeom &g, int cap = 0);
 hipError_t launch_tile_wgrad(const void *x, const void *dy, float *dw, const ConvGeom &g, float *partial,
-                             hipStream_t st);
+                             hipStream_t st, int cap = 0);
 
 // The row-stationary variant for 3x3 / 1x1 filters (same contract); launch_tile_wgrad prefers it.
 bool rows_wgrad_supported(const ConvGeom &g);
-int rows_wgrad_slices(const ConvGeom &g);
+int rows_wgrad_slices(const ConvGeom &g, int cap = 0);
 hipError_t launch_rows_wgrad(const void *x, const void *dy, float *dw, const ConvGeom &g, float *partial,
-                             hipStream_t st);
+                             hipStream_t st, int cap = 0);
 
 // Few input channels (C*R*S <= 32, bf16 operands, any stride and padding; conv_smallc.hip): forward
 // without workspace, optionally leaving smallc_fwd_stats_tiles(g) * K (count, mean, M2) triples in

@@ -110,3 +110,21 @@ def test_cold_start_on_strided_shapes_counts_the_passes():
     fmn, fpf = sn.sn_conv_workspace_query(shape, sn.SN_CONV_FWD, sn.SN_ALGO_STAGED)
     assert sn.sn_conv_plan(shape, sn.SN_CONV_FWD, fpf)[0] == sn.SN_ALGO_STAGED
     assert sn.sn_conv_plan(shape, sn.SN_CONV_FWD, fpf - 256)[0] == sn.SN_ALGO_DIRECT
+
+
+def test_backward_filter_workspace_is_a_range():
+    """STAGED backward-filter on the row-stationary kernel runs with a quarter of its slices upward
+    (Sec. 3.5: the more workspace, the faster); without measurements the planner guesses it down to
+    half of them and the zero-workspace form below that."""
+    sn.sn_planner_clear()
+    shape = sn.conv_shape(64, 96, 35, 35, 96, 3, 3, (1, 1), (1, 1), sn.SN_BF16, sn.SN_BF16)
+    mn, pf = sn.sn_conv_workspace_query(shape, sn.SN_CONV_BWD_FILTER, sn.SN_ALGO_STAGED)
+    per = 96 * 96 * 9 * 4
+    assert 0 < mn < pf and pf % per < 256 and mn <= pf // 4 + per + 256
+    algo, used, _ = sn.sn_conv_plan(shape, sn.SN_CONV_BWD_FILTER, pf)
+    assert algo == sn.SN_ALGO_STAGED and used == pf
+    half = mn + (pf - mn) // 3
+    algo, used, _ = sn.sn_conv_plan(shape, sn.SN_CONV_BWD_FILTER, half + per)
+    assert algo == sn.SN_ALGO_STAGED and used == half + per
+    assert sn.sn_conv_plan(shape, sn.SN_CONV_BWD_FILTER, half - per)[0] == sn.SN_ALGO_DIRECT
+    assert sn.sn_conv_plan(shape, sn.SN_CONV_BWD_FILTER, mn - 256)[0] == sn.SN_ALGO_DIRECT
